@@ -1,0 +1,279 @@
+"""Seeded synthetic inputs for the Lightplane Renderer path.
+
+This module serves BOTH the CPU oracle and the HIP library with identical host
+buffers.  It holds camera geometry, random-number draws and the table of
+workloads; it holds none of the method's arithmetic (no sampling of grids, no
+MLP, no compositing), so neither side can inherit a mistake from it.
+
+Every array is a C-contiguous numpy array; floats are float32, the precision of
+the library's inputs.  The layouts follow the hybrid representation of the
+paper (Section 3.2): a voxel grid is `[B][NX][NY][NZ][C]`, a triplane is three
+tensors `[B][NX][NY][C]`, `[B][NY][NZ][C]`, `[B][NZ][NX][C]` (channels
+innermost), and MLP layer `l` is a matrix `[out][in]` plus a bias `[out]`.
+"""
+from __future__ import annotations
+
+import dataclasses
+import math
+from typing import List, Optional, Tuple
+
+import numpy as np
+
+VOXEL = 0
+TRIPLANE = 1
+
+
+@dataclasses.dataclass(frozen=True)
+class Workload:
+    """One synthetic workload: the shapes of a benchmark configuration."""
+    name: str
+    kind: int                 # VOXEL or TRIPLANE
+    n_scenes: int             # B
+    channels: int             # C (the paper's K)
+    res: Tuple[int, int, int]  # NX, NY, NZ
+    grid_std: float
+    mlp_dims: Tuple[int, ...]  # C, hidden..., 4
+    image: int                # square image side
+    n_cameras: int            # views per scene
+    samples: int              # S (the paper's R)
+    near: float = 1.0
+    far: float = 4.0
+    aabb: float = 2.75        # grid spans [-aabb, aabb]^3
+    cfg_id: int = 0
+
+    @property
+    def rays(self) -> int:
+        return self.n_scenes * self.n_cameras * self.image * self.image
+
+    @property
+    def ray_samples(self) -> int:
+        return self.rays * self.samples
+
+    @property
+    def corners(self) -> int:
+        return 8 if self.kind == VOXEL else 12
+
+    @property
+    def gather_bytes_per_sample(self) -> int:
+        """Algorithmic bytes one sample reads from the grid (corners x C x 4)."""
+        return self.corners * self.channels * 4
+
+    @property
+    def mlp_flop_per_sample(self) -> int:
+        d = self.mlp_dims
+        return 2 * sum(d[i] * d[i + 1] for i in range(len(d) - 1))
+
+
+# The five benchmark configurations (tiny, single scene, voxel, batched, large).
+WORKLOADS = {
+    "tiny": Workload("tiny", TRIPLANE, 1, 16, (32, 32, 32), 0.1, (16, 32, 4),
+                     32, 1, 64, cfg_id=1),
+    "single_scene": Workload("single_scene", TRIPLANE, 1, 32, (128, 128, 128), 0.1,
+                             (32, 64, 64, 4), 128, 1, 128, cfg_id=2),
+    "voxel": Workload("voxel", VOXEL, 1, 32, (64, 64, 64), 0.1, (32, 64, 4),
+                      256, 4, 256, cfg_id=3),
+    "batched": Workload("batched", TRIPLANE, 8, 32, (256, 256, 256), 0.1,
+                        (32, 64, 64, 4), 256, 4, 192, cfg_id=4),
+    "large": Workload("large", VOXEL, 1, 16, (256, 256, 256), 0.05,
+                      (16, 64, 64, 4), 800, 1, 512, cfg_id=5),
+}
+WORKLOAD_ORDER = ["tiny", "single_scene", "voxel", "batched", "large"]
+
+
+def _seed(cfg_id: int, what: int, extra: int = 0) -> int:
+    # what: 0 grid, 1 weights, 2 target, 3 upstream alpha/depth grads
+    return 1000 * cfg_id + what + 10 * extra
+
+
+def camera_pose(azimuth_deg: float, elevation_deg: float, radius: float):
+    """Camera-to-world rotation (columns right, up, back) and position of a
+    camera on a sphere, looking at the origin with +y up."""
+    az = math.radians(azimuth_deg)
+    el = math.radians(elevation_deg)
+    pos = np.array([radius * math.cos(el) * math.sin(az),
+                    radius * math.sin(el),
+                    radius * math.cos(el) * math.cos(az)], dtype=np.float64)
+    back = pos / np.linalg.norm(pos)          # camera looks along -back
+    up0 = np.array([0.0, 1.0, 0.0])
+    right = np.cross(up0, back)
+    right /= np.linalg.norm(right)
+    up = np.cross(back, right)
+    rot = np.stack([right, up, back], axis=1)  # world = rot @ cam
+    return rot, pos
+
+
+def pinhole_rays(width: int, rot: np.ndarray, pos: np.ndarray, fov_deg: float = 60.0):
+    """Unit ray directions through pixel centres of a square pinhole image.
+    Returns (origins [W*W,3], dirs [W*W,3]) float32, row-major over (v, u)."""
+    f = (width / 2.0) / math.tan(math.radians(fov_deg) / 2.0)
+    u = (np.arange(width, dtype=np.float64) + 0.5 - width / 2.0) / f
+    uu, vv = np.meshgrid(u, u, indexing="xy")
+    cam = np.stack([uu, -vv, -np.ones_like(uu)], axis=-1).reshape(-1, 3)
+    cam /= np.linalg.norm(cam, axis=1, keepdims=True)
+    world = cam @ rot.T
+    # normalise once more in float32 so that |d| = 1 to float32 rounding
+    world = world.astype(np.float32)
+    world /= np.linalg.norm(world.astype(np.float64), axis=1, keepdims=True).astype(np.float32)
+    origins = np.broadcast_to(pos.astype(np.float32), world.shape).copy()
+    return origins, np.ascontiguousarray(world)
+
+
+def cameras_for(w: Workload):
+    if w.n_cameras == 1:
+        return [camera_pose(0.0, 0.0, 2.5)]
+    return [camera_pose(45.0 + 90.0 * k, 20.0, 2.5) for k in range(w.n_cameras)]
+
+
+@dataclasses.dataclass
+class Inputs:
+    """Host buffers for one call of the Renderer."""
+    kind: int
+    n_scenes: int
+    channels: int
+    res: Tuple[int, int, int]
+    grid: List[np.ndarray]            # 1 (voxel) or 3 (triplane) float32 arrays
+    aabb_min: Tuple[float, float, float]
+    aabb_max: Tuple[float, float, float]
+    mlp_dims: Tuple[int, ...]
+    weights: List[np.ndarray]         # [out][in] float32 per layer
+    biases: List[np.ndarray]          # [out] float32 per layer
+    origins: np.ndarray               # [M][3] float32
+    dirs: np.ndarray                  # [M][3] float32, unit length
+    near: np.ndarray                  # [M] float32
+    far: np.ndarray                   # [M] float32
+    scene: Optional[np.ndarray]       # [M] int32 or None when n_scenes == 1
+    samples: int
+    bg: Tuple[float, float, float]
+    target: Optional[np.ndarray] = None  # [M][3] float32 (for the MSE loss)
+
+    @property
+    def n_rays(self) -> int:
+        return int(self.origins.shape[0])
+
+    def subset(self, idx: np.ndarray) -> "Inputs":
+        """The same scene with only rays `idx` (rays are independent units)."""
+        idx = np.asarray(idx)
+        return dataclasses.replace(
+            self,
+            origins=np.ascontiguousarray(self.origins[idx]),
+            dirs=np.ascontiguousarray(self.dirs[idx]),
+            near=np.ascontiguousarray(self.near[idx]),
+            far=np.ascontiguousarray(self.far[idx]),
+            scene=None if self.scene is None else np.ascontiguousarray(self.scene[idx]),
+            target=None if self.target is None else np.ascontiguousarray(self.target[idx]),
+        )
+
+
+def grid_shapes(kind: int, n_scenes: int, res, channels: int):
+    nx, ny, nz = res
+    if kind == VOXEL:
+        return [(n_scenes, nx, ny, nz, channels)]
+    return [(n_scenes, nx, ny, channels), (n_scenes, ny, nz, channels),
+            (n_scenes, nz, nx, channels)]
+
+
+def make_grid(kind, n_scenes, res, channels, std, seed) -> List[np.ndarray]:
+    out = []
+    shapes = grid_shapes(kind, n_scenes, res, channels)
+    per_scene = [np.empty(s, dtype=np.float32) for s in shapes]
+    for b in range(n_scenes):
+        rng = np.random.default_rng(seed + 10 * b)
+        for p, s in enumerate(shapes):
+            blk = rng.standard_normal(s[1:], dtype=np.float32)
+            blk *= np.float32(std)
+            per_scene[p][b] = blk
+    out.extend(per_scene)
+    return out
+
+
+def make_mlp(dims, seed, bias_std: float = 0.0):
+    """He-normal weights N(0, sqrt(2/fan_in)); zero biases unless bias_std > 0."""
+    rng = np.random.default_rng(seed)
+    ws, bs = [], []
+    for l in range(len(dims) - 1):
+        fan_in, fan_out = dims[l], dims[l + 1]
+        w = rng.standard_normal((fan_out, fan_in)).astype(np.float32)
+        w *= np.float32(math.sqrt(2.0 / fan_in))
+        b = (rng.standard_normal(fan_out) * bias_std).astype(np.float32)
+        ws.append(np.ascontiguousarray(w))
+        bs.append(np.ascontiguousarray(b))
+    return ws, bs
+
+
+def make_rays(w: Workload):
+    """Rays of every camera of every scene, scene-major then camera then pixel."""
+    per_cam = [pinhole_rays(w.image, rot, pos) for rot, pos in cameras_for(w)]
+    o1 = np.concatenate([o for o, _ in per_cam], axis=0)
+    d1 = np.concatenate([d for _, d in per_cam], axis=0)
+    origins = np.tile(o1, (w.n_scenes, 1))
+    dirs = np.tile(d1, (w.n_scenes, 1))
+    m = origins.shape[0]
+    near = np.full(m, w.near, dtype=np.float32)
+    far = np.full(m, w.far, dtype=np.float32)
+    scene = None
+    if w.n_scenes > 1:
+        scene = np.repeat(np.arange(w.n_scenes, dtype=np.int32), o1.shape[0])
+    return (np.ascontiguousarray(origins), np.ascontiguousarray(dirs), near, far, scene)
+
+
+def make_inputs(name: str, aabb: Optional[float] = None, with_grid: bool = True) -> Inputs:
+    """All host buffers of workload `name` (see WORKLOADS)."""
+    w = WORKLOADS[name]
+    a = w.aabb if aabb is None else aabb
+    grid = (make_grid(w.kind, w.n_scenes, w.res, w.channels, w.grid_std, _seed(w.cfg_id, 0))
+            if with_grid else [])
+    ws, bs = make_mlp(w.mlp_dims, _seed(w.cfg_id, 1))
+    origins, dirs, near, far, scene = make_rays(w)
+    rng = np.random.default_rng(_seed(w.cfg_id, 2))
+    target = rng.random((origins.shape[0], 3), dtype=np.float32)
+    return Inputs(kind=w.kind, n_scenes=w.n_scenes, channels=w.channels, res=w.res, grid=grid,
+                  aabb_min=(-a, -a, -a), aabb_max=(a, a, a), mlp_dims=w.mlp_dims,
+                  weights=ws, biases=bs, origins=origins, dirs=dirs, near=near, far=far,
+                  scene=scene, samples=w.samples, bg=(1.0, 1.0, 1.0), target=target)
+
+
+def strided_ray_subset(n_rays: int, n_keep: int, offset: int = 0) -> np.ndarray:
+    """Deterministic subset: every (n_rays // n_keep)-th ray, starting at offset."""
+    n_keep = min(n_keep, n_rays)
+    stride = max(1, n_rays // n_keep)
+    return (np.arange(n_keep, dtype=np.int64) * stride + offset) % n_rays
+
+
+def make_small(kind: int, *, n_scenes=1, channels=4, res=(5, 4, 6), mlp_dims=(4, 8, 4),
+               n_rays=6, samples=7, seed=0, grid_std=0.5, bias_std=0.3,
+               aabb_min=(-1.0, -1.0, -1.0), aabb_max=(1.0, 1.0, 1.0),
+               near=(0.3, 0.9), far=(2.2, 3.7), origin_radius=2.0,
+               bg=(0.9, 0.5, 0.2)) -> Inputs:
+    """A small random problem for pins and edge cases: rays from random points on a
+    sphere towards random points near the origin, per-ray near/far, non-cubic grid,
+    non-zero biases, coloured background."""
+    rng = np.random.default_rng(seed)
+    grid = make_grid(kind, n_scenes, res, channels, grid_std, seed + 1)
+    ws, bs = make_mlp(mlp_dims, seed + 2, bias_std=bias_std)
+    p = rng.standard_normal((n_rays, 3))
+    p /= np.linalg.norm(p, axis=1, keepdims=True)
+    origins = (origin_radius * p).astype(np.float32)
+    look = rng.uniform(-0.6, 0.6, size=(n_rays, 3))
+    d = look - origins
+    d /= np.linalg.norm(d, axis=1, keepdims=True)
+    d = d.astype(np.float32)
+    d /= np.linalg.norm(d.astype(np.float64), axis=1, keepdims=True).astype(np.float32)
+    nr = rng.uniform(near[0], near[1], size=n_rays).astype(np.float32)
+    fr = rng.uniform(far[0], far[1], size=n_rays).astype(np.float32)
+    scene = None
+    if n_scenes > 1:
+        scene = rng.integers(0, n_scenes, size=n_rays).astype(np.int32)
+    target = rng.random((n_rays, 3), dtype=np.float32)
+    return Inputs(kind=kind, n_scenes=n_scenes, channels=channels, res=tuple(res), grid=grid,
+                  aabb_min=tuple(aabb_min), aabb_max=tuple(aabb_max), mlp_dims=tuple(mlp_dims),
+                  weights=ws, biases=bs, origins=np.ascontiguousarray(origins),
+                  dirs=np.ascontiguousarray(d), near=nr, far=fr, scene=scene, samples=samples,
+                  bg=tuple(bg), target=target)
+
+
+def upstream_grads(n_rays: int, seed: int):
+    """Random upstream gradients for alpha and depth (the MSE loss only feeds rgb)."""
+    rng = np.random.default_rng(seed)
+    p_alpha = (rng.standard_normal(n_rays) / n_rays).astype(np.float32)
+    p_depth = (rng.standard_normal(n_rays) / n_rays).astype(np.float32)
+    return p_alpha, p_depth

@@ -1,0 +1,180 @@
+"""Python face of the CPU oracle (`lp_oracle.c`).  TEST INFRASTRUCTURE ONLY.
+
+Only `tests/`, `__graft_entry__.smoke()` and the `cpu_baseline` leg of `bench.py`
+may import this package.  It compiles `lp_oracle.c` with gcc (fp64, OpenMP over
+rays) into `oracle/liblp_oracle.so` and calls it through ctypes.  Inputs are the
+float32 host buffers of `lp_inputs.Inputs`, widened exactly to float64; every
+result is float64.  Nothing here touches the HIP library.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import List, Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "lp_oracle.c")
+_LIB = os.path.join(_HERE, "liblp_oracle.so")
+_MAX_LAYERS = 8
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle (gcc -O2 -fopenmp).  Returns the library path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + f".tmp{os.getpid()}"
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11",
+                               "-Wall", "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+class _Grid(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("B", C.c_int32), ("C", C.c_int32),
+                ("NX", C.c_int32), ("NY", C.c_int32), ("NZ", C.c_int32),
+                ("data", C.c_void_p * 3),
+                ("aabb_min", C.c_double * 3), ("aabb_max", C.c_double * 3)]
+
+
+class _Mlp(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("dims", C.c_int32 * (_MAX_LAYERS + 1)),
+                ("W", C.c_void_p * _MAX_LAYERS), ("b", C.c_void_p * _MAX_LAYERS)]
+
+
+class _Rays(C.Structure):
+    _fields_ = [("M", C.c_int64), ("S", C.c_int32),
+                ("origins", C.c_void_p), ("dirs", C.c_void_p),
+                ("near", C.c_void_p), ("far", C.c_void_p), ("scene", C.c_void_p)]
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        _lib.lpo_render_fwd.restype = C.c_int
+        _lib.lpo_render_bwd.restype = C.c_int
+        _lib.lpo_ray_trace.restype = C.c_int
+        _lib.lpo_num_threads.restype = C.c_int
+    return _lib
+
+
+def num_threads() -> int:
+    return int(_load().lpo_num_threads())
+
+
+def _f64(a) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a), dtype=np.float64)
+
+
+class Problem:
+    """Float64 copies of one `lp_inputs.Inputs` plus the C structs that point at them."""
+
+    def __init__(self, inp):
+        self.inp = inp
+        self.grid = [_f64(g) for g in inp.grid]
+        self.W = [_f64(w) for w in inp.weights]
+        self.b = [_f64(b) for b in inp.biases]
+        self.origins = _f64(inp.origins)
+        self.dirs = _f64(inp.dirs)
+        self.near = _f64(inp.near)
+        self.far = _f64(inp.far)
+        self.scene = None if inp.scene is None else np.ascontiguousarray(inp.scene, dtype=np.int32)
+        # the library takes bg as float32; widen that value exactly
+        self.bg = (C.c_double * 3)(*[float(np.float32(v)) for v in inp.bg])
+
+        g = _Grid()
+        g.kind, g.B, g.C = inp.kind, inp.n_scenes, inp.channels
+        g.NX, g.NY, g.NZ = inp.res
+        for p, arr in enumerate(self.grid):
+            g.data[p] = arr.ctypes.data
+        for a in range(3):
+            g.aabb_min[a] = float(inp.aabb_min[a])
+            g.aabb_max[a] = float(inp.aabb_max[a])
+        self.c_grid = g
+
+        m = _Mlp()
+        m.n_layers = len(self.W)
+        for i, d in enumerate(inp.mlp_dims):
+            m.dims[i] = int(d)
+        for l in range(len(self.W)):
+            assert self.W[l].shape == (inp.mlp_dims[l + 1], inp.mlp_dims[l])
+            m.W[l] = self.W[l].ctypes.data
+            m.b[l] = self.b[l].ctypes.data
+        self.c_mlp = m
+
+        r = _Rays()
+        r.M, r.S = self.origins.shape[0], int(inp.samples)
+        r.origins, r.dirs = self.origins.ctypes.data, self.dirs.ctypes.data
+        r.near, r.far = self.near.ctypes.data, self.far.ctypes.data
+        r.scene = None if self.scene is None else self.scene.ctypes.data
+        self.c_rays = r
+
+    @property
+    def n_rays(self) -> int:
+        return int(self.origins.shape[0])
+
+
+def render_fwd(inp):
+    """rgb [M][3], alpha [M], depth [M] (float64) by Eq. (1) of the paper."""
+    p = inp if isinstance(inp, Problem) else Problem(inp)
+    m = p.n_rays
+    rgb = np.zeros((m, 3)); alpha = np.zeros(m); depth = np.zeros(m)
+    rc = _load().lpo_render_fwd(C.byref(p.c_grid), C.byref(p.c_mlp), C.byref(p.c_rays), p.bg,
+                                C.c_void_p(rgb.ctypes.data), C.c_void_p(alpha.ctypes.data),
+                                C.c_void_p(depth.ctypes.data))
+    if rc != 0:
+        raise RuntimeError(f"lpo_render_fwd failed with status {rc}")
+    return rgb, alpha, depth
+
+
+def render_bwd(inp, p_rgb, p_alpha=None, p_depth=None):
+    """Gradients of sum_i (p_rgb.rgb + p_alpha alpha + p_depth depth) w.r.t. the grid
+    tensors, weights and biases.  Returns (d_grid list, dW list, db list), float64."""
+    p = inp if isinstance(inp, Problem) else Problem(inp)
+    p_rgb = _f64(p_rgb)
+    assert p_rgb.shape == (p.n_rays, 3)
+    pa = None if p_alpha is None else _f64(p_alpha)
+    pd = None if p_depth is None else _f64(p_depth)
+    d_grid = [np.zeros_like(g) for g in p.grid]
+    dW = [np.zeros_like(w) for w in p.W]
+    db = [np.zeros_like(b) for b in p.b]
+    dg_arr = (C.c_void_p * 3)(*[d_grid[i].ctypes.data if i < len(d_grid) else None for i in range(3)])
+    dW_arr = (C.c_void_p * _MAX_LAYERS)(*[w.ctypes.data for w in dW])
+    db_arr = (C.c_void_p * _MAX_LAYERS)(*[b.ctypes.data for b in db])
+    rc = _load().lpo_render_bwd(C.byref(p.c_grid), C.byref(p.c_mlp), C.byref(p.c_rays), p.bg,
+                                C.c_void_p(p_rgb.ctypes.data),
+                                None if pa is None else C.c_void_p(pa.ctypes.data),
+                                None if pd is None else C.c_void_p(pd.ctypes.data),
+                                dg_arr, dW_arr, db_arr)
+    if rc != 0:
+        raise RuntimeError(f"lpo_render_bwd failed with status {rc}")
+    return d_grid, dW, db
+
+
+def ray_trace(inp, ray: int, p_rgb=None, p_alpha: float = 0.0, p_depth: float = 0.0):
+    """Per-sample quantities of one ray (dict of float64 arrays): t, x, feat, sigma, col,
+    T (S+1 entries, T[0] = 1), w; plus dsigma, dcol when p_rgb (3 floats) is given."""
+    p = inp if isinstance(inp, Problem) else Problem(inp)
+    s, c = int(p.c_rays.S), int(p.c_grid.C)
+    out = dict(t=np.zeros(s), x=np.zeros((s, 3)), feat=np.zeros((s, c)), sigma=np.zeros(s),
+               col=np.zeros((s, 3)), T=np.zeros(s + 1), w=np.zeros(s))
+    ptr = lambda a: C.c_void_p(a.ctypes.data)
+    pr = None
+    dsig = dcol = None
+    if p_rgb is not None:
+        pr = _f64(p_rgb).reshape(3)
+        dsig, dcol = np.zeros(s), np.zeros((s, 3))
+        out["dsigma"], out["dcol"] = dsig, dcol
+    rc = _load().lpo_ray_trace(C.byref(p.c_grid), C.byref(p.c_mlp), C.byref(p.c_rays), p.bg,
+                               C.c_int64(ray), None if pr is None else ptr(pr),
+                               C.c_double(p_alpha), C.c_double(p_depth),
+                               ptr(out["t"]), ptr(out["x"]), ptr(out["feat"]), ptr(out["sigma"]),
+                               ptr(out["col"]), ptr(out["T"]), ptr(out["w"]),
+                               None if dsig is None else ptr(dsig),
+                               None if dcol is None else ptr(dcol))
+    if rc != 0:
+        raise RuntimeError(f"lpo_ray_trace failed with status {rc}")
+    return out

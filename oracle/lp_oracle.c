@@ -1,0 +1,485 @@
+/*
+ * lp_oracle.c — CPU oracle for the Lightplane Renderer.  TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, fp64 implementation of what the Renderer computes: the "naive"
+ * renderer the paper contrasts itself with (Section 3.1), which materialises every
+ * per-sample quantity of a ray, composites with the emission-absorption sum of
+ * Eq. (1) (Section 3.3), and differentiates that stored computation by ordinary
+ * reverse-mode, operation by operation.  The paper's Renderer is exact (it changes
+ * what is stored, not what is computed), so this definition is its oracle.
+ *
+ * Only tests, the smoke check and the benchmark's cpu_baseline leg may call this
+ * file.  It shares no code with the HIP library and includes none of its headers.
+ *
+ * Conventions fixed where the paper is silent (each is one reading, listed in the
+ * design notes of the repository):
+ *   - T_0 = 1 and T_j = T_{j-1} exp(-sigma_j Delta); Eq. (1)'s inner sum is read as
+ *     running over n = 1..j.
+ *   - S samples at the midpoints of S equal bins of [near, far]; Delta = (far-near)/S.
+ *   - world -> grid: index 0 is at aabb_min, index N-1 at aabb_max; positions outside
+ *     the box are clamped to it (border).
+ *   - axis x <-> first spatial dim, y <-> second, z <-> third; channels innermost
+ *     (Section 3.2: voxel HxWxDxK; planes at (x,y), (y,z), (z,x), summed).
+ *   - one MLP C -> ... -> 4: ReLU hidden layers, linear last layer; output 0 through
+ *     softplus is the density, outputs 1..3 through the logistic sigmoid are the colour.
+ *   - depth = sum_j w_j t_j (a rendered feature like any other); rgb gets + T_S * bg.
+ *
+ * All arithmetic is double.  Parallel over rays only (OpenMP); grid gradients are
+ * added with atomic updates, weight gradients in per-thread buffers summed at the end.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define LPO_VOXEL 0
+#define LPO_TRIPLANE 1
+#define LPO_MAX_LAYERS 8
+
+typedef struct {
+    int32_t kind, B, C, NX, NY, NZ;
+    const double* data[3];
+    double aabb_min[3], aabb_max[3];
+} lpo_grid;
+
+typedef struct {
+    int32_t n_layers;
+    int32_t dims[LPO_MAX_LAYERS + 1];
+    const double* W[LPO_MAX_LAYERS]; /* [dims[l+1]][dims[l]] */
+    const double* b[LPO_MAX_LAYERS]; /* [dims[l+1]] */
+} lpo_mlp;
+
+typedef struct {
+    int64_t M;
+    int32_t S;
+    const double* origins; /* [M][3] */
+    const double* dirs;    /* [M][3] unit */
+    const double* near;    /* [M] */
+    const double* far;     /* [M] */
+    const int32_t* scene;  /* [M] or NULL */
+} lpo_rays;
+
+/* ---- Section 3.2: the hashing scheme h (bi/tri-linear interpolation) ---------- */
+
+/* continuous index along one axis -> cell index i in [0, N-2] and fraction f in [0,1] */
+static void axis_cell(double x, double lo, double hi, int N, int* i, double* f)
+{
+    double u = (x - lo) / (hi - lo) * (double)(N - 1);
+    if (u < 0.0) u = 0.0;
+    if (u > (double)(N - 1)) u = (double)(N - 1);
+    int c = (int)floor(u);
+    if (c > N - 2) c = N - 2;
+    *i = c;
+    *f = u - (double)c;
+}
+
+/* bilinear read of a [NA][NB][C] plane at cell (ia, ib), fractions (fa, fb); adds into feat */
+static void plane_gather(const double* P, int NB, int C, int ia, int ib, double fa, double fb,
+                         double* feat)
+{
+    for (int da = 0; da < 2; ++da)
+        for (int db = 0; db < 2; ++db) {
+            double w = (da ? fa : 1.0 - fa) * (db ? fb : 1.0 - fb);
+            const double* v = P + ((int64_t)(ia + da) * NB + (ib + db)) * C;
+            for (int k = 0; k < C; ++k) feat[k] += w * v[k];
+        }
+}
+
+static void plane_scatter(double* P, int NB, int C, int ia, int ib, double fa, double fb,
+                          const double* dfeat)
+{
+    for (int da = 0; da < 2; ++da)
+        for (int db = 0; db < 2; ++db) {
+            double w = (da ? fa : 1.0 - fa) * (db ? fb : 1.0 - fb);
+            double* v = P + ((int64_t)(ia + da) * NB + (ib + db)) * C;
+            for (int k = 0; k < C; ++k) {
+                double add = w * dfeat[k];
+#pragma omp atomic
+                v[k] += add;
+            }
+        }
+}
+
+/* h(x): feature of world point x in scene b */
+static void grid_gather(const lpo_grid* g, int b, const double x[3], double* feat)
+{
+    int i[3];
+    double f[3];
+    const int N[3] = {g->NX, g->NY, g->NZ};
+    for (int a = 0; a < 3; ++a) axis_cell(x[a], g->aabb_min[a], g->aabb_max[a], N[a], &i[a], &f[a]);
+    const int C = g->C;
+    for (int k = 0; k < C; ++k) feat[k] = 0.0;
+    if (g->kind == LPO_VOXEL) {
+        const double* V = g->data[0] + (int64_t)b * g->NX * g->NY * g->NZ * C;
+        for (int dx = 0; dx < 2; ++dx)
+            for (int dy = 0; dy < 2; ++dy)
+                for (int dz = 0; dz < 2; ++dz) {
+                    double w = (dx ? f[0] : 1.0 - f[0]) * (dy ? f[1] : 1.0 - f[1]) *
+                               (dz ? f[2] : 1.0 - f[2]);
+                    const double* v =
+                        V + (((int64_t)(i[0] + dx) * g->NY + (i[1] + dy)) * g->NZ + (i[2] + dz)) * C;
+                    for (int k = 0; k < C; ++k) feat[k] += w * v[k];
+                }
+    } else {
+        /* planes sampled at (x,y), (y,z), (z,x) and summed */
+        plane_gather(g->data[0] + (int64_t)b * g->NX * g->NY * C, g->NY, C, i[0], i[1], f[0], f[1], feat);
+        plane_gather(g->data[1] + (int64_t)b * g->NY * g->NZ * C, g->NZ, C, i[1], i[2], f[1], f[2], feat);
+        plane_gather(g->data[2] + (int64_t)b * g->NZ * g->NX * C, g->NX, C, i[2], i[0], f[2], f[0], feat);
+    }
+}
+
+/* transpose of grid_gather: d_grid[corner] += weight * dfeat, same corners and weights */
+static void grid_scatter(const lpo_grid* g, double* const d_grid[3], int b, const double x[3],
+                         const double* dfeat)
+{
+    int i[3];
+    double f[3];
+    const int N[3] = {g->NX, g->NY, g->NZ};
+    for (int a = 0; a < 3; ++a) axis_cell(x[a], g->aabb_min[a], g->aabb_max[a], N[a], &i[a], &f[a]);
+    const int C = g->C;
+    if (g->kind == LPO_VOXEL) {
+        double* V = d_grid[0] + (int64_t)b * g->NX * g->NY * g->NZ * C;
+        for (int dx = 0; dx < 2; ++dx)
+            for (int dy = 0; dy < 2; ++dy)
+                for (int dz = 0; dz < 2; ++dz) {
+                    double w = (dx ? f[0] : 1.0 - f[0]) * (dy ? f[1] : 1.0 - f[1]) *
+                               (dz ? f[2] : 1.0 - f[2]);
+                    double* v =
+                        V + (((int64_t)(i[0] + dx) * g->NY + (i[1] + dy)) * g->NZ + (i[2] + dz)) * C;
+                    for (int k = 0; k < C; ++k) {
+                        double add = w * dfeat[k];
+#pragma omp atomic
+                        v[k] += add;
+                    }
+                }
+    } else {
+        plane_scatter(d_grid[0] + (int64_t)b * g->NX * g->NY * C, g->NY, C, i[0], i[1], f[0], f[1], dfeat);
+        plane_scatter(d_grid[1] + (int64_t)b * g->NY * g->NZ * C, g->NZ, C, i[1], i[2], f[1], f[2], dfeat);
+        plane_scatter(d_grid[2] + (int64_t)b * g->NZ * g->NX * C, g->NX, C, i[2], i[0], f[2], f[0], dfeat);
+    }
+}
+
+/* ---- Section 3.2: the tiny MLP g ------------------------------------------------ */
+
+static int mlp_act_total(const lpo_mlp* m)
+{
+    int n = 0;
+    for (int l = 0; l <= m->n_layers; ++l) n += m->dims[l];
+    return n;
+}
+
+/* act holds the input (dims[0]) followed by every layer's post-activation output;
+   pre holds every layer's pre-activation (offset as act minus dims[0]). */
+static void mlp_forward(const lpo_mlp* m, double* act, double* pre)
+{
+    int off_in = 0, off_out = m->dims[0];
+    for (int l = 0; l < m->n_layers; ++l) {
+        const int nin = m->dims[l], nout = m->dims[l + 1];
+        const double* W = m->W[l];
+        const double* bb = m->b[l];
+        for (int o = 0; o < nout; ++o) {
+            double z = bb[o];
+            for (int k = 0; k < nin; ++k) z += W[(int64_t)o * nin + k] * act[off_in + k];
+            pre[off_out - m->dims[0] + o] = z;
+            act[off_out + o] = (l + 1 < m->n_layers) ? (z > 0.0 ? z : 0.0) : z;
+        }
+        off_in = off_out;
+        off_out += nout;
+    }
+}
+
+static double softplus(double z) { return (z > 0.0 ? z : 0.0) + log1p(exp(-fabs(z))); }
+static double logistic(double z) { return 1.0 / (1.0 + exp(-z)); }
+
+/* ---- per-ray record of the stored forward computation ------------------------- */
+
+typedef struct {
+    int S, nact, C;
+    double delta;
+    double* t;     /* [S]   distance of sample j along the ray            */
+    double* x;     /* [S][3] world position                               */
+    double* act;   /* [S][nact] feature + every layer's output            */
+    double* pre;   /* [S][nact - C] pre-activations                       */
+    double* sigma; /* [S]                                                  */
+    double* col;   /* [S][3]                                               */
+    double* e;     /* [S]   exp(-sigma_j Delta)                           */
+    double* T;     /* [S+1] T[0] = 1                                       */
+    double* w;     /* [S]   T[j-1] - T[j]                                  */
+} ray_tape;
+
+static int tape_alloc(ray_tape* r, int S, int nact, int C)
+{
+    memset(r, 0, sizeof(*r));
+    r->S = S; r->nact = nact; r->C = C;
+    r->t = (double*)malloc(sizeof(double) * S);
+    r->x = (double*)malloc(sizeof(double) * S * 3);
+    r->act = (double*)malloc(sizeof(double) * (size_t)S * nact);
+    r->pre = (double*)malloc(sizeof(double) * (size_t)S * (nact - C));
+    r->sigma = (double*)malloc(sizeof(double) * S);
+    r->col = (double*)malloc(sizeof(double) * S * 3);
+    r->e = (double*)malloc(sizeof(double) * S);
+    r->T = (double*)malloc(sizeof(double) * (S + 1));
+    r->w = (double*)malloc(sizeof(double) * S);
+    return r->t && r->x && r->act && r->pre && r->sigma && r->col && r->e && r->T && r->w;
+}
+
+static void tape_free(ray_tape* r)
+{
+    free(r->t); free(r->x); free(r->act); free(r->pre); free(r->sigma);
+    free(r->col); free(r->e); free(r->T); free(r->w);
+}
+
+/* Forward of one ray, everything stored (Section 3.1's naive renderer; Eq. (1)). */
+static void ray_forward(const lpo_grid* g, const lpo_mlp* m, const lpo_rays* rays, int64_t i,
+                        const double bg[3], ray_tape* r, double rgb[3], double* alpha, double* depth)
+{
+    const int S = r->S, nact = r->nact, C = r->C;
+    const double* o = rays->origins + 3 * i;
+    const double* d = rays->dirs + 3 * i;
+    const double nr = rays->near[i], fr = rays->far[i];
+    const int b = rays->scene ? rays->scene[i] : 0;
+    const int nl = m->n_layers;
+    const int out_off = nact - m->dims[nl]; /* offset of the last layer's output in act */
+    r->delta = (fr - nr) / (double)S;
+    r->T[0] = 1.0;
+    rgb[0] = rgb[1] = rgb[2] = 0.0;
+    *depth = 0.0;
+    for (int j = 0; j < S; ++j) {
+        const double t = nr + ((double)j + 0.5) * r->delta;
+        r->t[j] = t;
+        for (int a = 0; a < 3; ++a) r->x[3 * j + a] = o[a] + t * d[a];
+        double* act = r->act + (size_t)j * nact;
+        grid_gather(g, b, r->x + 3 * j, act);
+        mlp_forward(m, act, r->pre + (size_t)j * (nact - C));
+        const double* out = act + out_off;
+        r->sigma[j] = softplus(out[0]);
+        for (int c = 0; c < 3; ++c) r->col[3 * j + c] = logistic(out[1 + c]);
+        r->e[j] = exp(-r->sigma[j] * r->delta);
+        r->T[j + 1] = r->T[j] * r->e[j];
+        r->w[j] = r->T[j] - r->T[j + 1];
+        for (int c = 0; c < 3; ++c) rgb[c] += r->w[j] * r->col[3 * j + c];
+        *depth += r->w[j] * t;
+    }
+    for (int c = 0; c < 3; ++c) rgb[c] += r->T[S] * bg[c];
+    *alpha = 1.0 - r->T[S];
+}
+
+static int check_args(const lpo_grid* g, const lpo_mlp* m, const lpo_rays* rays)
+{
+    if (!g || !m || !rays) return 1;
+    if (g->B < 1 || g->C < 1 || g->NX < 2 || g->NY < 2 || g->NZ < 2) return 1;
+    if (m->n_layers < 1 || m->n_layers > LPO_MAX_LAYERS) return 1;
+    if (m->dims[0] != g->C || m->dims[m->n_layers] != 4) return 1;
+    if (rays->M < 0 || rays->S < 1) return 1;
+    return 0;
+}
+
+int lpo_render_fwd(const lpo_grid* g, const lpo_mlp* m, const lpo_rays* rays, const double bg[3],
+                   double* rgb, double* alpha, double* depth)
+{
+    if (check_args(g, m, rays)) return 1;
+    const int nact = mlp_act_total(m);
+    int fail = 0;
+#pragma omp parallel
+    {
+        ray_tape r;
+        if (!tape_alloc(&r, rays->S, nact, g->C)) {
+#pragma omp atomic write
+            fail = 1;
+        }
+#pragma omp barrier
+        if (!fail) {
+#pragma omp for schedule(dynamic, 16)
+            for (int64_t i = 0; i < rays->M; ++i)
+                ray_forward(g, m, rays, i, bg, &r, rgb + 3 * i, alpha + i, depth + i);
+        }
+        tape_free(&r);
+    }
+    return fail ? 2 : 0;
+}
+
+/* Reverse-mode over one ray's stored forward.  The forward operations, in order:
+     e_j = exp(-sigma_j Delta); T_j = T_{j-1} e_j; w_j = T_{j-1} - T_j;
+     rgb = sum_j w_j c_j + T_S bg; alpha = 1 - T_S; depth = sum_j w_j t_j.
+   Each is reversed individually; nothing is simplified algebraically.
+   dsig_out (optional) receives dL/dsigma_j, dcol_out (optional) dL/dc_j. */
+static void ray_backward(const lpo_grid* g, const lpo_mlp* m, const lpo_rays* rays, int64_t i,
+                         const double bg[3], const ray_tape* r, const double p_rgb[3],
+                         double p_alpha, double p_depth, double* const d_grid[3],
+                         double* const dW[], double* const db[], double* scratch,
+                         double* dsig_out, double* dcol_out)
+{
+    const int S = r->S, nact = r->nact, C = r->C, nl = m->n_layers;
+    const int b = rays->scene ? rays->scene[i] : 0;
+    double* dT = scratch;            /* [S+1] */
+    double* dact = scratch + (S + 1); /* [nact] */
+    for (int j = 0; j <= S; ++j) dT[j] = 0.0;
+    /* alpha = 1 - T_S ; rgb += T_S bg */
+    dT[S] += -p_alpha;
+    for (int c = 0; c < 3; ++c) dT[S] += p_rgb[c] * bg[c];
+    /* w_j = T_{j-1} - T_j enters rgb and depth */
+    for (int j = 0; j < S; ++j) {
+        double dw = p_depth * r->t[j];
+        for (int c = 0; c < 3; ++c) dw += p_rgb[c] * r->col[3 * j + c];
+        dT[j] += dw;
+        dT[j + 1] -= dw;
+    }
+    /* T_j = T_{j-1} e_j, reversed from the last sample to the first */
+    for (int j = S - 1; j >= 0; --j) {
+        const double de = dT[j + 1] * r->T[j];
+        dT[j] += dT[j + 1] * r->e[j];
+        const double dsigma = de * (-r->delta) * r->e[j];
+        double dcol[3];
+        for (int c = 0; c < 3; ++c) dcol[c] = r->w[j] * p_rgb[c];
+        if (dsig_out) dsig_out[j] = dsigma;
+        if (dcol_out)
+            for (int c = 0; c < 3; ++c) dcol_out[3 * j + c] = dcol[c];
+        /* heads: sigma = softplus(out0), c = logistic(out1..3) */
+        const double* act = r->act + (size_t)j * nact;
+        const double* pre = r->pre + (size_t)j * (nact - C);
+        for (int k = 0; k < nact; ++k) dact[k] = 0.0;
+        const int out_off = nact - 4;
+        dact[out_off + 0] = dsigma * logistic(act[out_off + 0]);
+        for (int c = 0; c < 3; ++c) {
+            const double cc = r->col[3 * j + c];
+            dact[out_off + 1 + c] = dcol[c] * cc * (1.0 - cc);
+        }
+        /* MLP layers in reverse */
+        int off_out = out_off;
+        for (int l = nl - 1; l >= 0; --l) {
+            const int nin = m->dims[l], nout = m->dims[l + 1];
+            const int off_in = off_out - nin;
+            const double* W = m->W[l];
+            for (int o = 0; o < nout; ++o) {
+                double dz = dact[off_out + o];
+                if (l + 1 < nl && !(pre[off_out - C + o] > 0.0)) dz = 0.0; /* ReLU' */
+                if (dz == 0.0) continue;
+                db[l][o] += dz;
+                for (int k = 0; k < nin; ++k) {
+                    dW[l][(int64_t)o * nin + k] += dz * act[off_in + k];
+                    dact[off_in + k] += dz * W[(int64_t)o * nin + k];
+                }
+            }
+            off_out = off_in;
+        }
+        grid_scatter(g, d_grid, b, r->x + 3 * j, dact);
+    }
+}
+
+/* d_grid, dW, db are ACCUMULATED into (the caller zeroes them). */
+int lpo_render_bwd(const lpo_grid* g, const lpo_mlp* m, const lpo_rays* rays, const double bg[3],
+                   const double* p_rgb, const double* p_alpha, const double* p_depth,
+                   double* const d_grid[3], double* const dW[], double* const db[])
+{
+    if (check_args(g, m, rays)) return 1;
+    const int nact = mlp_act_total(m);
+    const int nl = m->n_layers;
+    int fail = 0;
+#pragma omp parallel
+    {
+        ray_tape r;
+        double* scratch = (double*)malloc(sizeof(double) * (size_t)(rays->S + 1 + nact));
+        double* tW[LPO_MAX_LAYERS];
+        double* tb[LPO_MAX_LAYERS];
+        int ok = tape_alloc(&r, rays->S, nact, g->C) && scratch;
+        for (int l = 0; l < nl; ++l) {
+            tW[l] = (double*)calloc((size_t)m->dims[l] * m->dims[l + 1], sizeof(double));
+            tb[l] = (double*)calloc((size_t)m->dims[l + 1], sizeof(double));
+            ok = ok && tW[l] && tb[l];
+        }
+        if (!ok) {
+#pragma omp atomic write
+            fail = 1;
+        }
+#pragma omp barrier
+        if (!fail) {
+#pragma omp for schedule(dynamic, 16)
+            for (int64_t i = 0; i < rays->M; ++i) {
+                double rgb[3], alpha, depth;
+                ray_forward(g, m, rays, i, bg, &r, rgb, &alpha, &depth);
+                ray_backward(g, m, rays, i, bg, &r, p_rgb + 3 * i, p_alpha ? p_alpha[i] : 0.0,
+                             p_depth ? p_depth[i] : 0.0, d_grid, tW, tb, scratch, NULL, NULL);
+            }
+#pragma omp critical
+            {
+                for (int l = 0; l < nl; ++l) {
+                    const int64_t n = (int64_t)m->dims[l] * m->dims[l + 1];
+                    for (int64_t k = 0; k < n; ++k) dW[l][k] += tW[l][k];
+                    for (int k = 0; k < m->dims[l + 1]; ++k) db[l][k] += tb[l][k];
+                }
+            }
+        }
+        for (int l = 0; l < nl; ++l) { free(tW[l]); free(tb[l]); }
+        free(scratch);
+        tape_free(&r);
+    }
+    return fail ? 2 : 0;
+}
+
+/* Per-sample quantities of ONE ray, for the pins: t [S], x [S][3], feat [S][C], sigma [S],
+   col [S][3], T [S+1], w [S]; and, when p_rgb is given, dL/dsigma [S] and dL/dcol [S][3]
+   of that ray alone (gradient buffers are scratch and discarded).  Any output may be NULL. */
+int lpo_ray_trace(const lpo_grid* g, const lpo_mlp* m, const lpo_rays* rays, const double bg[3],
+                  int64_t ray, const double* p_rgb, double p_alpha, double p_depth,
+                  double* t, double* x, double* feat, double* sigma, double* col, double* T,
+                  double* w, double* dsigma, double* dcol)
+{
+    if (check_args(g, m, rays) || ray < 0 || ray >= rays->M) return 1;
+    const int nact = mlp_act_total(m), S = rays->S, C = g->C, nl = m->n_layers;
+    ray_tape r;
+    if (!tape_alloc(&r, S, nact, C)) { tape_free(&r); return 2; }
+    double rgb[3], alpha, depth;
+    ray_forward(g, m, rays, ray, bg, &r, rgb, &alpha, &depth);
+    if (t) memcpy(t, r.t, sizeof(double) * S);
+    if (x) memcpy(x, r.x, sizeof(double) * S * 3);
+    if (feat)
+        for (int j = 0; j < S; ++j) memcpy(feat + (size_t)j * C, r.act + (size_t)j * nact, sizeof(double) * C);
+    if (sigma) memcpy(sigma, r.sigma, sizeof(double) * S);
+    if (col) memcpy(col, r.col, sizeof(double) * S * 3);
+    if (T) memcpy(T, r.T, sizeof(double) * (S + 1));
+    if (w) memcpy(w, r.w, sizeof(double) * S);
+    int rc = 0;
+    if (p_rgb && (dsigma || dcol)) {
+        /* throw-away gradient buffers */
+        int64_t gsz[3] = {0, 0, 0};
+        if (g->kind == LPO_VOXEL) gsz[0] = (int64_t)g->B * g->NX * g->NY * g->NZ * C;
+        else {
+            gsz[0] = (int64_t)g->B * g->NX * g->NY * C;
+            gsz[1] = (int64_t)g->B * g->NY * g->NZ * C;
+            gsz[2] = (int64_t)g->B * g->NZ * g->NX * C;
+        }
+        double* dg[3] = {NULL, NULL, NULL};
+        double* tW[LPO_MAX_LAYERS] = {NULL};
+        double* tb[LPO_MAX_LAYERS] = {NULL};
+        double* scratch = (double*)malloc(sizeof(double) * (size_t)(S + 1 + nact));
+        int ok = scratch != NULL;
+        for (int p = 0; p < 3; ++p)
+            if (gsz[p]) { dg[p] = (double*)calloc((size_t)gsz[p], sizeof(double)); ok = ok && dg[p]; }
+        for (int l = 0; l < nl; ++l) {
+            tW[l] = (double*)calloc((size_t)m->dims[l] * m->dims[l + 1], sizeof(double));
+            tb[l] = (double*)calloc((size_t)m->dims[l + 1], sizeof(double));
+            ok = ok && tW[l] && tb[l];
+        }
+        if (ok)
+            ray_backward(g, m, rays, ray, bg, &r, p_rgb, p_alpha, p_depth, dg, tW, tb, scratch,
+                         dsigma, dcol);
+        else rc = 2;
+        for (int p = 0; p < 3; ++p) free(dg[p]);
+        for (int l = 0; l < nl; ++l) { free(tW[l]); free(tb[l]); }
+        free(scratch);
+    }
+    tape_free(&r);
+    return rc;
+}
+
+int lpo_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
