@@ -1,0 +1,146 @@
+/*
+ * lightplane.h — C ABI of the MI355X (gfx950) Lightplane Renderer library.
+ *
+ * The library computes the Renderer of "Lightplane" (arXiv 2404.19760): fused,
+ * differentiable emission-absorption ray marching over a hybrid 3D representation
+ * f = g o h (Section 3.2), where h is bi/tri-linear sampling of a triplane or voxel
+ * feature grid and g a tiny MLP, with a backward pass that stores one scalar per ray
+ * and recomputes everything else (Section 3.4).
+ *
+ * General rules
+ *   - Every pointer named "device" is a pointer to GPU memory owned by the caller
+ *     (for example a torch tensor); the small structs themselves and the pointer
+ *     arrays inside them live in HOST memory and are read during the call only.
+ *   - Calls enqueue work on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and return without waiting.  The library allocates nothing
+ *     and keeps no pointer after a call returns.
+ *   - Every function returns an lp_status and never throws or aborts; a message
+ *     for the last failure on the calling thread is available from lp_last_error().
+ *   - All floating point is IEEE binary32, tensors are dense and C-contiguous.
+ */
+#ifndef LIGHTPLANE_H
+#define LIGHTPLANE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LP_MAX_LAYERS 8 /* linear layers of the decoder MLP */
+
+typedef enum {
+    LP_OK = 0,
+    LP_ERR_INVALID_ARG = 1, /* NULL required pointer, non-positive size, dims mismatch      */
+    LP_ERR_UNSUPPORTED = 2, /* valid, but no kernel of this library covers the shape       */
+    LP_ERR_HIP = 3,         /* the HIP runtime reported an error (launch, attribute query) */
+    LP_ERR_WORKSPACE = 4    /* workspace missing or smaller than lp_bwd_workspace_bytes     */
+} lp_status;
+
+typedef enum { LP_GRID_VOXEL = 0, LP_GRID_TRIPLANE = 1 } lp_grid_kind;
+
+/*
+ * The 3D hash structure theta (Section 3.2), channel-last.
+ *   voxel   : data[0] = [B][NX][NY][NZ][C]                       (data[1], data[2] ignored)
+ *   triplane: data[0] = [B][NX][NY][C], data[1] = [B][NY][NZ][C], data[2] = [B][NZ][NX][C];
+ *             a point (x,y,z) reads plane 0 at (x,y), plane 1 at (y,z), plane 2 at (z,x)
+ *             bilinearly and SUMS the three feature vectors.
+ * World coordinate aabb_min[a] maps to index 0 and aabb_max[a] to index N_a - 1 along axis
+ * a; positions outside the box are clamped onto it.  B scenes share the MLP.
+ */
+typedef struct {
+    int32_t kind; /* lp_grid_kind */
+    int32_t B, C; /* scenes, feature channels (the paper's K) */
+    int32_t NX, NY, NZ;
+    const float* data[3]; /* device */
+    float aabb_min[3], aabb_max[3];
+} lp_grid;
+
+/*
+ * The tiny MLP g (Section 3.2): n_layers linear layers, ReLU after every layer but the
+ * last.  dims[0] == C, dims[n_layers] == 4.  Output 0 through softplus is the density
+ * sigma; outputs 1..3 through the logistic sigmoid are the colour.
+ * W[l] = [dims[l+1]][dims[l]] row-major (out, in), b[l] = [dims[l+1]].
+ */
+typedef struct {
+    int32_t n_layers;
+    int32_t dims[LP_MAX_LAYERS + 1];
+    const float* W[LP_MAX_LAYERS]; /* device */
+    const float* b[LP_MAX_LAYERS]; /* device */
+} lp_mlp;
+
+/*
+ * M rays with S samples each (Section 3.3: "M rays and R+1 points per ray").  Sample j
+ * (j = 1..S) sits at distance t_j = near + (j - 1/2) (far - near) / S from the origin along
+ * the UNIT direction, so Delta = (far - near) / S is the world distance between samples.
+ */
+typedef struct {
+    int64_t M;
+    int32_t S;
+    const float* origins; /* device [M][3] */
+    const float* dirs;    /* device [M][3], unit length (not renormalised) */
+    const float* near;    /* device [M] */
+    const float* far;     /* device [M] */
+    const int32_t* scene; /* device [M] scene index in [0,B), or NULL (all rays use scene 0) */
+} lp_rays;
+
+/* How the MLP contractions are evaluated by the matrix-core kernels. */
+typedef enum {
+    LP_MATH_DEFAULT = 0, /* the library's choice for the shape                            */
+    LP_MATH_GENERIC = 1, /* scalar fp32 kernels for any layer widths (slow)               */
+    LP_MATH_BF16X3 = 2   /* fp32 operands split into bf16 hi+lo, three MFMA products,
+                            fp32 accumulation (matrix-core kernels; supported shapes only) */
+} lp_math_mode;
+
+/*
+ * Forward (Eq. (1), Section 3.3).  With T_0 = 1, T_j = T_{j-1} exp(-sigma_j Delta),
+ * w_j = T_{j-1} - T_j:
+ *     rgb = sum_j w_j c_j + T_S bg,   alpha = 1 - T_S,   depth = sum_j w_j t_j.
+ * Outputs (device, written, not accumulated): rgb [M][3], alpha [M], depth [M], and
+ * ray_cache [M], the one scalar per ray the backward needs (Section 3.4; here the total
+ * optical depth sum_j sigma_j Delta, opaque to the caller).  alpha, depth and ray_cache
+ * may each be NULL if not wanted.  bg is a HOST array of 3 floats.  M == 0 is a no-op.
+ */
+lp_status lp_render_fwd(const lp_grid* grid, const lp_mlp* mlp, const lp_rays* rays,
+                        const float bg[3], float* rgb, float* alpha, float* depth,
+                        float* ray_cache, int32_t math_mode, void* stream);
+
+/*
+ * Backward (Eq. (2), Section 3.4): vector-Jacobian product of the forward for upstream
+ * gradients d_rgb [M][3] (required), d_alpha [M], d_depth [M] (either may be NULL = zero),
+ * all device.  Marches each ray in reverse, recomputes sampling and MLP, rebuilds the
+ * transmittance from ray_cache (as written by lp_render_fwd for the SAME inputs), and
+ * ACCUMULATES into (the caller zeroes or pre-loads them):
+ *     d_grid[p] — same shape as grid->data[p] (device; triplane: all three required),
+ *     dW[l], db[l] — same shapes as mlp->W[l], mlp->b[l] (device).
+ * No gradient is produced for rays, near, far or bg.  `workspace` is device memory of at
+ * least lp_bwd_workspace_bytes(...) bytes, 256-byte aligned, contents ignored on entry and
+ * undefined on exit.  Grid gradients are summed with floating-point atomics, so they are
+ * reproducible up to summation order only.
+ */
+lp_status lp_render_bwd(const lp_grid* grid, const lp_mlp* mlp, const lp_rays* rays,
+                        const float bg[3], const float* d_rgb, const float* d_alpha,
+                        const float* d_depth, const float* ray_cache, float* const d_grid[3],
+                        float* const dW[LP_MAX_LAYERS], float* const db[LP_MAX_LAYERS],
+                        void* workspace, size_t workspace_bytes, int32_t math_mode,
+                        void* stream);
+
+/* Bytes of workspace lp_render_bwd needs for these shapes; independent of S and of M
+   (it depends on the MLP size and the device's compute-unit count).  *bytes is written. */
+lp_status lp_bwd_workspace_bytes(const lp_grid* grid, const lp_mlp* mlp, const lp_rays* rays,
+                                 int32_t math_mode, size_t* bytes);
+
+/* 1 if the matrix-core (LP_MATH_BF16X3) kernels cover this grid kind / MLP shape, else 0. */
+int32_t lp_has_fast_path(const lp_grid* grid, const lp_mlp* mlp);
+
+/* Message of the last failure on this thread ("" if none).  Owned by the library. */
+const char* lp_last_error(void);
+
+/* Library version, major * 1000 + minor. */
+int32_t lp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LIGHTPLANE_H */

@@ -310,7 +310,7 @@ static void ray_backward(const lpo_grid* g, const lpo_mlp* m, const lpo_rays* ra
                          const double bg[3], const ray_tape* r, const double p_rgb[3],
                          double p_alpha, double p_depth, double* const d_grid[3],
                          double* const dW[], double* const db[], double* scratch,
-                         double* dsig_out, double* dcol_out)
+                         double* dsig_out, double* dcol_out, double relu_c)
 {
     const int S = r->S, nact = r->nact, C = r->C, nl = m->n_layers;
     const int b = rays->scene ? rays->scene[i] : 0;
@@ -355,7 +355,16 @@ static void ray_backward(const lpo_grid* g, const lpo_mlp* m, const lpo_rays* ra
             const double* W = m->W[l];
             for (int o = 0; o < nout; ++o) {
                 double dz = dact[off_out + o];
-                if (l + 1 < nl && !(pre[off_out - C + o] > 0.0)) dz = 0.0; /* ReLU' */
+                if (l + 1 < nl) { /* ReLU' = 1 iff pre-activation > 0 (threshold shifted only by the
+                                     kink-envelope option, see lpo_render_bwd) */
+                    double thr = 0.0;
+                    if (relu_c != 0.0) {
+                        double mag = fabs(m->b[l][o]);
+                        for (int k = 0; k < nin; ++k) mag += fabs(W[(int64_t)o * nin + k] * act[off_in + k]);
+                        thr = relu_c * mag;
+                    }
+                    if (!(pre[off_out - C + o] > thr)) dz = 0.0;
+                }
                 if (dz == 0.0) continue;
                 db[l][o] += dz;
                 for (int k = 0; k < nin; ++k) {
@@ -369,10 +378,15 @@ static void ray_backward(const lpo_grid* g, const lpo_mlp* m, const lpo_rays* ra
     }
 }
 
-/* d_grid, dW, db are ACCUMULATED into (the caller zeroes them). */
+/* d_grid, dW, db are ACCUMULATED into (the caller zeroes them).
+   relu_c = 0 is the definition (ReLU' = 1 iff z > 0).  A non-zero relu_c moves the threshold
+   to relu_c * (|b| + sum_k |W_k x_k|), a multiple of the unit's rounding-error scale: calling
+   with +c and -c brackets every gradient a finite-precision evaluation may legitimately
+   produce when a pre-activation lies within rounding of the kink (either one-sided
+   derivative is then a correct answer).  The forward is never affected. */
 int lpo_render_bwd(const lpo_grid* g, const lpo_mlp* m, const lpo_rays* rays, const double bg[3],
                    const double* p_rgb, const double* p_alpha, const double* p_depth,
-                   double* const d_grid[3], double* const dW[], double* const db[])
+                   double* const d_grid[3], double* const dW[], double* const db[], double relu_c)
 {
     if (check_args(g, m, rays)) return 1;
     const int nact = mlp_act_total(m);
@@ -401,7 +415,7 @@ int lpo_render_bwd(const lpo_grid* g, const lpo_mlp* m, const lpo_rays* rays, co
                 double rgb[3], alpha, depth;
                 ray_forward(g, m, rays, i, bg, &r, rgb, &alpha, &depth);
                 ray_backward(g, m, rays, i, bg, &r, p_rgb + 3 * i, p_alpha ? p_alpha[i] : 0.0,
-                             p_depth ? p_depth[i] : 0.0, d_grid, tW, tb, scratch, NULL, NULL);
+                             p_depth ? p_depth[i] : 0.0, d_grid, tW, tb, scratch, NULL, NULL, relu_c);
             }
 #pragma omp critical
             {
@@ -465,7 +479,7 @@ int lpo_ray_trace(const lpo_grid* g, const lpo_mlp* m, const lpo_rays* rays, con
         }
         if (ok)
             ray_backward(g, m, rays, ray, bg, &r, p_rgb, p_alpha, p_depth, dg, tW, tb, scratch,
-                         dsigma, dcol);
+                         dsigma, dcol, 0.0);
         else rc = 2;
         for (int p = 0; p < 3; ++p) free(dg[p]);
         for (int l = 0; l < nl; ++l) { free(tW[l]); free(tb[l]); }

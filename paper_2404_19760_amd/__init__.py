@@ -1,0 +1,297 @@
+"""Python binding of the MI355X Lightplane Renderer library (`liblightplane.so`).
+
+Argument marshalling only: every step of the Renderer runs in the library's HIP
+kernels.  PyTorch supplies device memory (tensors) and streams.  The functions carry
+the names of the C entry points declared in `include/lightplane.h`.
+
+There is no CPU fallback: importing this package without a built library, or calling
+it without a GPU tensor, raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import dataclasses
+import os
+from typing import List, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblightplane.so")
+
+LP_MAX_LAYERS = 8
+LP_OK, LP_ERR_INVALID_ARG, LP_ERR_UNSUPPORTED, LP_ERR_HIP, LP_ERR_WORKSPACE = range(5)
+LP_GRID_VOXEL, LP_GRID_TRIPLANE = 0, 1
+LP_MATH_DEFAULT, LP_MATH_GENERIC, LP_MATH_BF16X3 = 0, 1, 2
+
+
+class LightplaneError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"lightplane status {status}: {message}")
+        self.status = status
+
+
+class _Grid(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("B", C.c_int32), ("C", C.c_int32),
+                ("NX", C.c_int32), ("NY", C.c_int32), ("NZ", C.c_int32),
+                ("data", C.c_void_p * 3),
+                ("aabb_min", C.c_float * 3), ("aabb_max", C.c_float * 3)]
+
+
+class _Mlp(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("dims", C.c_int32 * (LP_MAX_LAYERS + 1)),
+                ("W", C.c_void_p * LP_MAX_LAYERS), ("b", C.c_void_p * LP_MAX_LAYERS)]
+
+
+class _Rays(C.Structure):
+    _fields_ = [("M", C.c_int64), ("S", C.c_int32),
+                ("origins", C.c_void_p), ("dirs", C.c_void_p),
+                ("near", C.c_void_p), ("far", C.c_void_p), ("scene", C.c_void_p)]
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_2404_19760_amd.build` "
+                          "(there is no fallback implementation)")
+    lib = C.CDLL(LIB_PATH)
+    lib.lp_last_error.restype = C.c_char_p
+    lib.lp_version.restype = C.c_int32
+    lib.lp_has_fast_path.restype = C.c_int32
+    lib.lp_has_fast_path.argtypes = [C.POINTER(_Grid), C.POINTER(_Mlp)]
+    lib.lp_render_fwd.restype = C.c_int
+    lib.lp_render_fwd.argtypes = [C.POINTER(_Grid), C.POINTER(_Mlp), C.POINTER(_Rays),
+                                  C.POINTER(C.c_float), C.c_void_p, C.c_void_p, C.c_void_p,
+                                  C.c_void_p, C.c_int32, C.c_void_p]
+    lib.lp_render_bwd.restype = C.c_int
+    lib.lp_render_bwd.argtypes = [C.POINTER(_Grid), C.POINTER(_Mlp), C.POINTER(_Rays),
+                                  C.POINTER(C.c_float), C.c_void_p, C.c_void_p, C.c_void_p,
+                                  C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
+                                  C.POINTER(C.c_void_p), C.c_void_p, C.c_size_t, C.c_int32,
+                                  C.c_void_p]
+    lib.lp_bwd_workspace_bytes.restype = C.c_int
+    lib.lp_bwd_workspace_bytes.argtypes = [C.POINTER(_Grid), C.POINTER(_Mlp), C.POINTER(_Rays),
+                                           C.c_int32, C.POINTER(C.c_size_t)]
+    return lib
+
+
+_lib = _load()
+
+
+def _check(status: int):
+    if status != LP_OK:
+        raise LightplaneError(status, _lib.lp_last_error().decode())
+
+
+def _dev_f32(t: Optional[torch.Tensor], name: str, shape=None) -> Optional[int]:
+    if t is None:
+        return None
+    if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()):
+        raise ValueError(f"{name} must be a contiguous float32 tensor on the GPU")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} has shape {tuple(t.shape)}, expected {tuple(shape)}")
+    return t.data_ptr()
+
+
+@dataclasses.dataclass
+class Grid:
+    """Voxel grid [B][NX][NY][NZ][C] (one tensor) or triplane (three tensors
+    [B][NX][NY][C], [B][NY][NZ][C], [B][NZ][NX][C]); float32, on the GPU."""
+    kind: int
+    data: List[torch.Tensor]
+    res: Sequence[int]
+    aabb_min: Sequence[float] = (-1.0, -1.0, -1.0)
+    aabb_max: Sequence[float] = (1.0, 1.0, 1.0)
+
+    @property
+    def n_scenes(self) -> int:
+        return int(self.data[0].shape[0])
+
+    @property
+    def channels(self) -> int:
+        return int(self.data[0].shape[-1])
+
+    def shapes(self):
+        b, c = self.n_scenes, self.channels
+        nx, ny, nz = self.res
+        if self.kind == LP_GRID_VOXEL:
+            return [(b, nx, ny, nz, c)]
+        return [(b, nx, ny, c), (b, ny, nz, c), (b, nz, nx, c)]
+
+    def c_struct(self) -> _Grid:
+        g = _Grid()
+        g.kind, g.B, g.C = self.kind, self.n_scenes, self.channels
+        g.NX, g.NY, g.NZ = [int(v) for v in self.res]
+        shapes = self.shapes()
+        if len(self.data) != len(shapes):
+            raise ValueError("wrong number of grid tensors for this kind")
+        for p, (t, s) in enumerate(zip(self.data, shapes)):
+            g.data[p] = _dev_f32(t, f"grid.data[{p}]", s)
+        for a in range(3):
+            g.aabb_min[a] = float(self.aabb_min[a])
+            g.aabb_max[a] = float(self.aabb_max[a])
+        return g
+
+
+@dataclasses.dataclass
+class Mlp:
+    """weights[l] = [out][in], biases[l] = [out]; float32, on the GPU."""
+    weights: List[torch.Tensor]
+    biases: List[torch.Tensor]
+
+    @property
+    def dims(self):
+        return [int(self.weights[0].shape[1])] + [int(w.shape[0]) for w in self.weights]
+
+    def c_struct(self) -> _Mlp:
+        if len(self.weights) != len(self.biases) or not 1 <= len(self.weights) <= LP_MAX_LAYERS:
+            raise ValueError("MLP needs 1..8 layers with one bias per weight matrix")
+        m = _Mlp()
+        m.n_layers = len(self.weights)
+        dims = self.dims
+        for i, d in enumerate(dims):
+            m.dims[i] = d
+        for l, (w, b) in enumerate(zip(self.weights, self.biases)):
+            m.W[l] = _dev_f32(w, f"weights[{l}]", (dims[l + 1], dims[l]))
+            m.b[l] = _dev_f32(b, f"biases[{l}]", (dims[l + 1],))
+        return m
+
+
+@dataclasses.dataclass
+class Rays:
+    origins: torch.Tensor          # [M][3]
+    dirs: torch.Tensor             # [M][3] unit
+    near: torch.Tensor             # [M]
+    far: torch.Tensor              # [M]
+    samples: int                   # S
+    scene: Optional[torch.Tensor] = None  # [M] int32
+
+    @property
+    def n_rays(self) -> int:
+        return int(self.origins.shape[0])
+
+    def c_struct(self) -> _Rays:
+        m = self.n_rays
+        r = _Rays()
+        r.M, r.S = m, int(self.samples)
+        r.origins = _dev_f32(self.origins, "origins", (m, 3))
+        r.dirs = _dev_f32(self.dirs, "dirs", (m, 3))
+        r.near = _dev_f32(self.near, "near", (m,))
+        r.far = _dev_f32(self.far, "far", (m,))
+        if self.scene is not None:
+            s = self.scene
+            if not (s.is_cuda and s.dtype == torch.int32 and s.is_contiguous() and tuple(s.shape) == (m,)):
+                raise ValueError("scene must be a contiguous int32 GPU tensor of shape [M]")
+            r.scene = s.data_ptr()
+        return r
+
+
+def _stream_ptr(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def _bg(bg) -> C.Array:
+    return (C.c_float * 3)(*[float(v) for v in bg])
+
+
+def lp_version() -> int:
+    return int(_lib.lp_version())
+
+
+def lp_has_fast_path(grid: Grid, mlp: Mlp) -> bool:
+    g, m = grid.c_struct(), mlp.c_struct()
+    return bool(_lib.lp_has_fast_path(C.byref(g), C.byref(m)))
+
+
+def lp_render_fwd(grid: Grid, mlp: Mlp, rays: Rays, bg, rgb: torch.Tensor,
+                  alpha: Optional[torch.Tensor], depth: Optional[torch.Tensor],
+                  ray_cache: Optional[torch.Tensor], math_mode: int = LP_MATH_DEFAULT,
+                  stream=None) -> None:
+    """Enqueue the forward on `stream` (default: torch's current stream); outputs are
+    caller-allocated GPU tensors rgb [M][3], alpha [M], depth [M], ray_cache [M]."""
+    m = rays.n_rays
+    g, ml, r = grid.c_struct(), mlp.c_struct(), rays.c_struct()
+    _check(_lib.lp_render_fwd(C.byref(g), C.byref(ml), C.byref(r), _bg(bg),
+                              _dev_f32(rgb, "rgb", (m, 3)), _dev_f32(alpha, "alpha", (m,)),
+                              _dev_f32(depth, "depth", (m,)), _dev_f32(ray_cache, "ray_cache", (m,)),
+                              int(math_mode), _stream_ptr(stream)))
+
+
+def lp_bwd_workspace_bytes(grid: Grid, mlp: Mlp, rays: Rays, math_mode: int = LP_MATH_DEFAULT) -> int:
+    g, ml, r = grid.c_struct(), mlp.c_struct(), rays.c_struct()
+    n = C.c_size_t(0)
+    _check(_lib.lp_bwd_workspace_bytes(C.byref(g), C.byref(ml), C.byref(r), int(math_mode), C.byref(n)))
+    return int(n.value)
+
+
+def lp_render_bwd(grid: Grid, mlp: Mlp, rays: Rays, bg, d_rgb: torch.Tensor,
+                  d_alpha: Optional[torch.Tensor], d_depth: Optional[torch.Tensor],
+                  ray_cache: torch.Tensor, d_grid: List[torch.Tensor], dW: List[torch.Tensor],
+                  db: List[torch.Tensor], workspace: torch.Tensor,
+                  math_mode: int = LP_MATH_DEFAULT, stream=None) -> None:
+    """Enqueue the backward; d_grid / dW / db are ACCUMULATED into (same shapes as the
+    grid tensors, weights and biases); `workspace` is a GPU byte tensor of at least
+    lp_bwd_workspace_bytes(...) bytes."""
+    m = rays.n_rays
+    g, ml, r = grid.c_struct(), mlp.c_struct(), rays.c_struct()
+    shapes = grid.shapes()
+    if len(d_grid) != len(shapes):
+        raise ValueError("d_grid needs one tensor per grid tensor")
+    dg = (C.c_void_p * 3)(*[_dev_f32(d_grid[p], f"d_grid[{p}]", shapes[p]) if p < len(shapes) else None
+                            for p in range(3)])
+    dims = mlp.dims
+    if len(dW) != len(mlp.weights) or len(db) != len(mlp.weights):
+        raise ValueError("dW / db need one tensor per layer")
+    dWp = (C.c_void_p * LP_MAX_LAYERS)(*[_dev_f32(w, f"dW[{l}]", (dims[l + 1], dims[l])) for l, w in enumerate(dW)])
+    dbp = (C.c_void_p * LP_MAX_LAYERS)(*[_dev_f32(b, f"db[{l}]", (dims[l + 1],)) for l, b in enumerate(db)])
+    if not (workspace.is_cuda and workspace.is_contiguous()):
+        raise ValueError("workspace must be a contiguous GPU tensor")
+    ws_bytes = workspace.numel() * workspace.element_size()
+    _check(_lib.lp_render_bwd(C.byref(g), C.byref(ml), C.byref(r), _bg(bg),
+                              _dev_f32(d_rgb, "d_rgb", (m, 3)), _dev_f32(d_alpha, "d_alpha", (m,)),
+                              _dev_f32(d_depth, "d_depth", (m,)), _dev_f32(ray_cache, "ray_cache", (m,)),
+                              dg, dWp, dbp, C.c_void_p(workspace.data_ptr()), C.c_size_t(ws_bytes),
+                              int(math_mode), _stream_ptr(stream)))
+
+
+# ---------------------------------------------------------------------------------------
+# Conveniences on top of the entry points: move host buffers to the GPU, allocate outputs.
+
+def to_device(inp, device="cuda:0"):
+    """Upload host buffers (any object with the fields of `lp_inputs.Inputs`) and return
+    (Grid, Mlp, Rays, bg) on `device`."""
+    dev = torch.device(device)
+    up = lambda a: torch.from_numpy(a).to(dev)
+    grid = Grid(kind=int(inp.kind), data=[up(g) for g in inp.grid], res=tuple(inp.res),
+                aabb_min=tuple(inp.aabb_min), aabb_max=tuple(inp.aabb_max))
+    mlp = Mlp(weights=[up(w) for w in inp.weights], biases=[up(b) for b in inp.biases])
+    rays = Rays(origins=up(inp.origins), dirs=up(inp.dirs), near=up(inp.near), far=up(inp.far),
+                samples=int(inp.samples), scene=None if inp.scene is None else up(inp.scene))
+    return grid, mlp, rays, tuple(float(v) for v in inp.bg)
+
+
+def render_fwd(grid: Grid, mlp: Mlp, rays: Rays, bg, math_mode: int = LP_MATH_DEFAULT):
+    """Allocate outputs and run lp_render_fwd.  Returns (rgb, alpha, depth, ray_cache)."""
+    dev = rays.origins.device
+    m = rays.n_rays
+    rgb = torch.empty((m, 3), dtype=torch.float32, device=dev)
+    alpha = torch.empty((m,), dtype=torch.float32, device=dev)
+    depth = torch.empty((m,), dtype=torch.float32, device=dev)
+    cache = torch.empty((m,), dtype=torch.float32, device=dev)
+    lp_render_fwd(grid, mlp, rays, bg, rgb, alpha, depth, cache, math_mode)
+    return rgb, alpha, depth, cache
+
+
+def render_bwd(grid: Grid, mlp: Mlp, rays: Rays, bg, d_rgb, ray_cache, d_alpha=None, d_depth=None,
+               math_mode: int = LP_MATH_DEFAULT, workspace: Optional[torch.Tensor] = None):
+    """Allocate zeroed gradient buffers (and a workspace) and run lp_render_bwd.
+    Returns (d_grid list, dW list, db list)."""
+    dev = rays.origins.device
+    d_grid = [torch.zeros_like(t) for t in grid.data]
+    dW = [torch.zeros_like(w) for w in mlp.weights]
+    db = [torch.zeros_like(b) for b in mlp.biases]
+    if workspace is None:
+        workspace = torch.empty(lp_bwd_workspace_bytes(grid, mlp, rays, math_mode), dtype=torch.uint8, device=dev)
+    lp_render_bwd(grid, mlp, rays, bg, d_rgb, d_alpha, d_depth, ray_cache, d_grid, dW, db, workspace, math_mode)
+    return d_grid, dW, db

@@ -1,0 +1,297 @@
+// C-ABI entry points of the library: argument validation, translation of the host
+// structs into device-side views, choice of kernel family, launches.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <string>
+
+#include "lightplane.h"
+#include "lp_kernels.h"
+
+namespace {
+
+thread_local std::string g_last_error;
+
+lp_status fail(lp_status s, const std::string& msg)
+{
+    g_last_error = msg;
+    return s;
+}
+
+constexpr size_t kMaxLds = 160 * 1024;   // LDS per compute unit on gfx950
+constexpr int kGenericLanes = 64;
+constexpr int kMaxDevices = 64;
+
+int compute_units(int* out_n_cu, std::string* err)
+{
+    static int cached[kMaxDevices] = {0};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) { *err = std::string("hipGetDevice: ") + hipGetErrorString(e); return 1; }
+    if (dev >= 0 && dev < kMaxDevices && cached[dev] > 0) { *out_n_cu = cached[dev]; return 0; }
+    int n = 0;
+    e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess || n <= 0) {
+        *err = std::string("hipDeviceGetAttribute(MultiprocessorCount): ") + hipGetErrorString(e);
+        return 1;
+    }
+    if (dev >= 0 && dev < kMaxDevices) cached[dev] = n;
+    *out_n_cu = n;
+    return 0;
+}
+
+lp_status validate(const lp_grid* grid, const lp_mlp* mlp, const lp_rays* rays)
+{
+    if (!grid || !mlp || !rays) return fail(LP_ERR_INVALID_ARG, "grid, mlp and rays must not be NULL");
+    if (grid->kind != LP_GRID_VOXEL && grid->kind != LP_GRID_TRIPLANE)
+        return fail(LP_ERR_INVALID_ARG, "grid->kind must be LP_GRID_VOXEL or LP_GRID_TRIPLANE");
+    if (grid->B < 1 || grid->C < 1) return fail(LP_ERR_INVALID_ARG, "grid->B and grid->C must be >= 1");
+    if (grid->NX < 2 || grid->NY < 2 || grid->NZ < 2)
+        return fail(LP_ERR_INVALID_ARG, "every grid resolution must be >= 2");
+    const int n_planes = grid->kind == LP_GRID_VOXEL ? 1 : 3;
+    for (int p = 0; p < n_planes; ++p)
+        if (!grid->data[p]) return fail(LP_ERR_INVALID_ARG, "grid->data has a NULL tensor");
+    for (int a = 0; a < 3; ++a) {
+        if (!std::isfinite(grid->aabb_min[a]) || !std::isfinite(grid->aabb_max[a]) ||
+            !(grid->aabb_max[a] > grid->aabb_min[a]))
+            return fail(LP_ERR_INVALID_ARG, "aabb_max must exceed aabb_min on every axis (finite values)");
+    }
+    if (mlp->n_layers < 1 || mlp->n_layers > LP_MAX_LAYERS)
+        return fail(LP_ERR_INVALID_ARG, "mlp->n_layers must be in [1, LP_MAX_LAYERS]");
+    for (int l = 0; l <= mlp->n_layers; ++l)
+        if (mlp->dims[l] < 1) return fail(LP_ERR_INVALID_ARG, "mlp->dims entries must be >= 1");
+    if (mlp->dims[0] != grid->C) return fail(LP_ERR_INVALID_ARG, "mlp->dims[0] must equal grid->C");
+    if (mlp->dims[mlp->n_layers] != 4)
+        return fail(LP_ERR_INVALID_ARG, "the last MLP layer must have 4 outputs (density + rgb)");
+    for (int l = 0; l < mlp->n_layers; ++l)
+        if (!mlp->W[l] || !mlp->b[l]) return fail(LP_ERR_INVALID_ARG, "mlp->W / mlp->b has a NULL layer");
+    if (rays->M < 0) return fail(LP_ERR_INVALID_ARG, "rays->M must be >= 0");
+    if (rays->S < 1) return fail(LP_ERR_INVALID_ARG, "rays->S must be >= 1");
+    if (rays->M > 0 && (!rays->origins || !rays->dirs || !rays->near || !rays->far))
+        return fail(LP_ERR_INVALID_ARG, "rays->origins, dirs, near and far must not be NULL");
+    return LP_OK;
+}
+
+void to_device_views(const lp_grid* grid, const lp_mlp* mlp, const lp_rays* rays, lp::GridDev* g,
+                     lp::MlpDev* m, lp::RaysDev* r)
+{
+    std::memset(g, 0, sizeof(*g));
+    g->kind = grid->kind; g->B = grid->B; g->C = grid->C;
+    g->N[0] = grid->NX; g->N[1] = grid->NY; g->N[2] = grid->NZ;
+    for (int p = 0; p < 3; ++p) g->data[p] = grid->data[p];
+    for (int a = 0; a < 3; ++a) {
+        g->amin[a] = grid->aabb_min[a];
+        g->scale[a] = (float)((double)(g->N[a] - 1) / ((double)grid->aabb_max[a] - (double)grid->aabb_min[a]));
+    }
+    std::memset(m, 0, sizeof(*m));
+    m->n_layers = mlp->n_layers;
+    int off = 0, maxw = 0, act = 0;
+    for (int l = 0; l <= mlp->n_layers; ++l) {
+        m->dims[l] = mlp->dims[l];
+        maxw = mlp->dims[l] > maxw ? mlp->dims[l] : maxw;
+        act += mlp->dims[l];
+    }
+    for (int l = 0; l < mlp->n_layers; ++l) {
+        m->W[l] = mlp->W[l];
+        m->b[l] = mlp->b[l];
+        m->w_off[l] = off; off += mlp->dims[l] * mlp->dims[l + 1];
+        m->b_off[l] = off; off += mlp->dims[l + 1];
+    }
+    m->param_total = off;
+    m->max_width = maxw;
+    m->act_total = act;
+    r->M = rays->M; r->S = rays->S;
+    r->origins = rays->origins; r->dirs = rays->dirs; r->near = rays->near; r->far = rays->far;
+    r->scene = rays->scene;
+}
+
+enum class Path { Generic, Mfma };
+
+lp_status choose_path(const lp::GridDev& g, const lp::MlpDev& m, int32_t mode, Path* path)
+{
+    const bool fast = lp::mfma_supported(g, m);
+    switch (mode) {
+        case LP_MATH_DEFAULT: *path = fast ? Path::Mfma : Path::Generic; return LP_OK;
+        case LP_MATH_GENERIC: *path = Path::Generic; return LP_OK;
+        case LP_MATH_BF16X3:
+            if (!fast) return fail(LP_ERR_UNSUPPORTED, "no matrix-core kernel for this grid kind / MLP shape");
+            *path = Path::Mfma;
+            return LP_OK;
+        default: return fail(LP_ERR_INVALID_ARG, "unknown math_mode");
+    }
+}
+
+size_t generic_fwd_lds(const lp::MlpDev& m)
+{
+    return sizeof(float) * ((size_t)m.param_total + (size_t)m.act_total * kGenericLanes);
+}
+
+size_t generic_bwd_lds(const lp::MlpDev& m)
+{
+    return sizeof(float) * (2 * (size_t)m.param_total + (size_t)m.act_total * kGenericLanes +
+                            2 * (size_t)m.max_width * kGenericLanes);
+}
+
+int ws_stride(const lp::MlpDev& m) { return (m.param_total + 63) / 64 * 64; }
+
+int generic_bwd_blocks(int n_cu) { return 4 * n_cu; }
+
+lp_status hip_fail(const char* what, hipError_t e)
+{
+    return fail(LP_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* lp_last_error(void) { return g_last_error.c_str(); }
+
+int32_t lp_version(void) { return 1000; }
+
+int32_t lp_has_fast_path(const lp_grid* grid, const lp_mlp* mlp)
+{
+    if (!grid || !mlp) return 0;
+    lp_rays dummy;
+    std::memset(&dummy, 0, sizeof(dummy));
+    dummy.S = 1;
+    if (validate(grid, mlp, &dummy) != LP_OK) return 0;
+    lp::GridDev g; lp::MlpDev m; lp::RaysDev r;
+    to_device_views(grid, mlp, &dummy, &g, &m, &r);
+    return lp::mfma_supported(g, m) ? 1 : 0;
+}
+
+lp_status lp_render_fwd(const lp_grid* grid, const lp_mlp* mlp, const lp_rays* rays,
+                        const float bg[3], float* rgb, float* alpha, float* depth,
+                        float* ray_cache, int32_t math_mode, void* stream)
+{
+    lp_status st = validate(grid, mlp, rays);
+    if (st != LP_OK) return st;
+    if (!bg) return fail(LP_ERR_INVALID_ARG, "bg must not be NULL");
+    if (rays->M > 0 && !rgb) return fail(LP_ERR_INVALID_ARG, "rgb must not be NULL");
+    lp::GridDev g; lp::MlpDev m; lp::RaysDev r;
+    to_device_views(grid, mlp, rays, &g, &m, &r);
+    Path path;
+    st = choose_path(g, m, math_mode, &path);
+    if (st != LP_OK) return st;
+    if (rays->M == 0) return LP_OK;
+
+    lp::FwdOut out;
+    out.rgb = rgb; out.alpha = alpha; out.depth = depth; out.cache = ray_cache;
+    for (int c = 0; c < 3; ++c) out.bg[c] = bg[c];
+    hipStream_t s = (hipStream_t)stream;
+    std::string err;
+    int n_cu = 0;
+    if (compute_units(&n_cu, &err)) return fail(LP_ERR_HIP, err);
+
+    if (path == Path::Mfma) {
+        hipError_t e = lp::launch_fwd_mfma(g, m, r, out, n_cu, s);
+        if (e != hipSuccess) return hip_fail("forward matrix-core kernel launch", e);
+        return LP_OK;
+    }
+    const size_t lds = generic_fwd_lds(m);
+    if (lds > kMaxLds)
+        return fail(LP_ERR_UNSUPPORTED, "MLP too large for the generic forward kernel's LDS budget");
+    hipError_t e = hipFuncSetAttribute((const void*)lp::fwd_generic_kernel,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return hip_fail("hipFuncSetAttribute(fwd_generic_kernel)", e);
+    const long long blocks = (rays->M + kGenericLanes - 1) / kGenericLanes;
+    if (blocks > 0x7fffffffLL) return fail(LP_ERR_UNSUPPORTED, "too many rays for one launch");
+    hipLaunchKernelGGL(lp::fwd_generic_kernel, dim3((unsigned)blocks), dim3(kGenericLanes), lds, s, g, m, r, out);
+    e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail("forward generic kernel launch", e);
+    return LP_OK;
+}
+
+lp_status lp_bwd_workspace_bytes(const lp_grid* grid, const lp_mlp* mlp, const lp_rays* rays,
+                                 int32_t math_mode, size_t* bytes)
+{
+    if (!bytes) return fail(LP_ERR_INVALID_ARG, "bytes must not be NULL");
+    lp_status st = validate(grid, mlp, rays);
+    if (st != LP_OK) return st;
+    lp::GridDev g; lp::MlpDev m; lp::RaysDev r;
+    to_device_views(grid, mlp, rays, &g, &m, &r);
+    Path path;
+    st = choose_path(g, m, math_mode, &path);
+    if (st != LP_OK) return st;
+    std::string err;
+    int n_cu = 0;
+    if (compute_units(&n_cu, &err)) return fail(LP_ERR_HIP, err);
+    const int records = path == Path::Mfma ? lp::mfma_bwd_records(n_cu) : generic_bwd_blocks(n_cu);
+    *bytes = sizeof(float) * (size_t)records * (size_t)ws_stride(m);
+    return LP_OK;
+}
+
+lp_status lp_render_bwd(const lp_grid* grid, const lp_mlp* mlp, const lp_rays* rays,
+                        const float bg[3], const float* d_rgb, const float* d_alpha,
+                        const float* d_depth, const float* ray_cache, float* const d_grid[3],
+                        float* const dW[LP_MAX_LAYERS], float* const db[LP_MAX_LAYERS],
+                        void* workspace, size_t workspace_bytes, int32_t math_mode, void* stream)
+{
+    lp_status st = validate(grid, mlp, rays);
+    if (st != LP_OK) return st;
+    if (!bg || !d_grid || !dW || !db) return fail(LP_ERR_INVALID_ARG, "bg, d_grid, dW and db must not be NULL");
+    const int n_planes = grid->kind == LP_GRID_VOXEL ? 1 : 3;
+    for (int p = 0; p < n_planes; ++p)
+        if (!d_grid[p]) return fail(LP_ERR_INVALID_ARG, "d_grid has a NULL tensor");
+    for (int l = 0; l < mlp->n_layers; ++l)
+        if (!dW[l] || !db[l]) return fail(LP_ERR_INVALID_ARG, "dW / db has a NULL layer");
+    if (rays->M > 0 && (!d_rgb || !ray_cache))
+        return fail(LP_ERR_INVALID_ARG, "d_rgb and ray_cache must not be NULL");
+    lp::GridDev g; lp::MlpDev m; lp::RaysDev r;
+    to_device_views(grid, mlp, rays, &g, &m, &r);
+    Path path;
+    st = choose_path(g, m, math_mode, &path);
+    if (st != LP_OK) return st;
+    if (rays->M == 0) return LP_OK;
+
+    std::string err;
+    int n_cu = 0;
+    if (compute_units(&n_cu, &err)) return fail(LP_ERR_HIP, err);
+    const int max_records = path == Path::Mfma ? lp::mfma_bwd_records(n_cu) : generic_bwd_blocks(n_cu);
+    const size_t need = sizeof(float) * (size_t)max_records * (size_t)ws_stride(m);
+    if (!workspace || workspace_bytes < need)
+        return fail(LP_ERR_WORKSPACE, "workspace is NULL or smaller than lp_bwd_workspace_bytes()");
+    if (((uintptr_t)workspace & 255u) != 0) return fail(LP_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+
+    lp::BwdIo io;
+    std::memset(&io, 0, sizeof(io));
+    io.d_rgb = d_rgb; io.d_alpha = d_alpha; io.d_depth = d_depth; io.cache = ray_cache;
+    for (int p = 0; p < 3; ++p) io.d_grid[p] = p < n_planes ? d_grid[p] : nullptr;
+    for (int l = 0; l < mlp->n_layers; ++l) { io.dW[l] = dW[l]; io.db[l] = db[l]; }
+    for (int c = 0; c < 3; ++c) io.bg[c] = bg[c];
+    io.ws = (float*)workspace;
+    io.ws_stride = ws_stride(m);
+    hipStream_t s = (hipStream_t)stream;
+
+    if (path == Path::Mfma) {
+        hipError_t e = lp::launch_bwd_mfma(g, m, r, io, n_cu, s);
+        if (e != hipSuccess) return hip_fail("backward matrix-core kernel launch", e);
+        return LP_OK;
+    }
+    const size_t lds = generic_bwd_lds(m);
+    if (lds > kMaxLds)
+        return fail(LP_ERR_UNSUPPORTED, "MLP too large for the generic backward kernel's LDS budget");
+    hipError_t e = hipFuncSetAttribute((const void*)lp::bwd_generic_kernel,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return hip_fail("hipFuncSetAttribute(bwd_generic_kernel)", e);
+    const long long n_tiles = (rays->M + kGenericLanes - 1) / kGenericLanes;
+    const long long blocks = n_tiles < max_records ? n_tiles : max_records;
+    const long long tiles_per_block = (n_tiles + blocks - 1) / blocks;
+    if (tiles_per_block > 0x7fffffffLL) return fail(LP_ERR_UNSUPPORTED, "too many rays for one launch");
+    // blocks whose first tile is past the end write an all-zero record
+    hipLaunchKernelGGL(lp::bwd_generic_kernel, dim3((unsigned)blocks), dim3(kGenericLanes), lds, s, g, m, r, io,
+                       (int)tiles_per_block);
+    e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail("backward generic kernel launch", e);
+    const int threads = 256;
+    hipLaunchKernelGGL(lp::reduce_params_kernel, dim3((m.param_total + threads - 1) / threads), dim3(threads), 0, s,
+                       m, io, (int)blocks);
+    e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail("parameter-gradient reduction launch", e);
+    return LP_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,86 @@
+// Device-side views of the C-ABI arguments and the few formulas every kernel shares:
+// sample placement, world -> grid addressing (Section 3.2 of the paper) and the
+// density / colour heads.  HIP for gfx950 only.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "lightplane.h"
+
+namespace lp {
+
+struct GridDev {
+    const float* data[3];
+    int kind, B, C;
+    int N[3];
+    float amin[3];
+    float scale[3];  // (N-1)/(max-min): world -> continuous index
+};
+
+struct MlpDev {
+    int n_layers;
+    int dims[LP_MAX_LAYERS + 1];
+    const float* W[LP_MAX_LAYERS];
+    const float* b[LP_MAX_LAYERS];
+    int w_off[LP_MAX_LAYERS];  // offsets of W[l] / b[l] in one packed float array
+    int b_off[LP_MAX_LAYERS];
+    int param_total;           // floats of all weights and biases
+    int max_width;             // widest layer input or output
+    int act_total;             // dims[0] + ... + dims[n_layers]
+};
+
+struct RaysDev {
+    long long M;
+    int S;
+    const float* origins;
+    const float* dirs;
+    const float* near;
+    const float* far;
+    const int* scene;
+};
+
+struct FwdOut {
+    float* rgb;
+    float* alpha;
+    float* depth;
+    float* cache;
+    float bg[3];
+};
+
+struct BwdIo {
+    const float* d_rgb;
+    const float* d_alpha;
+    const float* d_depth;
+    const float* cache;
+    float* d_grid[3];
+    float* dW[LP_MAX_LAYERS];
+    float* db[LP_MAX_LAYERS];
+    float bg[3];
+    float* ws;         // per-wave (or per-block) partial sums of the MLP gradients
+    int ws_stride;     // floats between consecutive partial-sum records
+};
+
+// Continuous index along one axis, clamped to the box; cell index in [0, N-2] and the
+// fraction inside the cell in [0, 1].
+__device__ __forceinline__ void axis_cell(float x, float lo, float scale, int N, int& i, float& f)
+{
+    float u = (x - lo) * scale;
+    u = fminf(fmaxf(u, 0.0f), (float)(N - 1));
+    int c = (int)u;  // u >= 0: truncation is floor
+    c = min(c, N - 2);
+    i = c;
+    f = u - (float)c;
+}
+
+// softplus(z) = max(z,0) + log1p(exp(-|z|)); its derivative is the logistic function.
+__device__ __forceinline__ float softplus_f(float z)
+{
+    return fmaxf(z, 0.0f) + log1pf(__expf(-fabsf(z)));
+}
+
+__device__ __forceinline__ float logistic_f(float z)
+{
+    return 1.0f / (1.0f + __expf(-z));
+}
+
+}  // namespace lp

@@ -1,0 +1,316 @@
+// Generic Renderer kernels: any channel count and any MLP widths, scalar fp32.
+//
+// One lane marches one ray (the paper's "one kernel instance per ray", Section 3.4): it
+// samples, decodes and composites sample after sample, keeping only the running
+// transmittance and the rendered features.  A block is a single wavefront; MLP weights
+// live in LDS, activations in LDS columns indexed [feature][lane] (conflict free).
+// These kernels are the fallback for shapes the matrix-core kernels do not cover.
+#include "lp_device.h"
+#include "lp_kernels.h"
+
+namespace lp {
+
+namespace {
+
+constexpr int kLanes = 64;
+
+// Copies all weights and biases into LDS at sW[w_off[l]...] / sW[b_off[l]...].
+__device__ void stage_params(const MlpDev& m, float* sW)
+{
+    for (int l = 0; l < m.n_layers; ++l) {
+        const int nw = m.dims[l] * m.dims[l + 1];
+        for (int i = threadIdx.x; i < nw; i += blockDim.x) sW[m.w_off[l] + i] = m.W[l][i];
+        for (int i = threadIdx.x; i < m.dims[l + 1]; i += blockDim.x) sW[m.b_off[l] + i] = m.b[l][i];
+    }
+}
+
+struct Cell {
+    int i[3];
+    float f[3];
+};
+
+__device__ __forceinline__ Cell locate(const GridDev& g, float x, float y, float z)
+{
+    Cell c;
+    axis_cell(x, g.amin[0], g.scale[0], g.N[0], c.i[0], c.f[0]);
+    axis_cell(y, g.amin[1], g.scale[1], g.N[1], c.i[1], c.f[1]);
+    axis_cell(z, g.amin[2], g.scale[2], g.N[2], c.i[2], c.f[2]);
+    return c;
+}
+
+// feat[k*64 + lane] = h(x)[k], k < C  (Section 3.2)
+__device__ void gather_feat(const GridDev& g, int scene, const Cell& c, float* feat, int lane)
+{
+    const int C = g.C;
+    if (g.kind == LP_GRID_VOXEL) {
+        const float* V = g.data[0] + (size_t)scene * g.N[0] * g.N[1] * g.N[2] * C;
+        for (int k = 0; k < C; ++k) {
+            float acc = 0.0f;
+            for (int d = 0; d < 8; ++d) {
+                const int dx = d >> 2, dy = (d >> 1) & 1, dz = d & 1;
+                const float w = (dx ? c.f[0] : 1.0f - c.f[0]) * (dy ? c.f[1] : 1.0f - c.f[1]) *
+                                (dz ? c.f[2] : 1.0f - c.f[2]);
+                const size_t off =
+                    (((size_t)(c.i[0] + dx) * g.N[1] + (c.i[1] + dy)) * g.N[2] + (c.i[2] + dz)) * C;
+                acc += w * V[off + k];
+            }
+            feat[k * kLanes + lane] = acc;
+        }
+    } else {
+        // plane p spans axes (a, b) = (0,1), (1,2), (2,0)
+        for (int k = 0; k < C; ++k) {
+            float acc = 0.0f;
+            for (int p = 0; p < 3; ++p) {
+                const int a = p, b = (p + 1) % 3;
+                const float* P = g.data[p] + (size_t)scene * g.N[a] * g.N[b] * C;
+                for (int d = 0; d < 4; ++d) {
+                    const int da = d >> 1, db = d & 1;
+                    const float w = (da ? c.f[a] : 1.0f - c.f[a]) * (db ? c.f[b] : 1.0f - c.f[b]);
+                    acc += w * P[((size_t)(c.i[a] + da) * g.N[b] + (c.i[b] + db)) * C + k];
+                }
+            }
+            feat[k * kLanes + lane] = acc;
+        }
+    }
+}
+
+// d_grid[corner] += weight * dfeat  — the transpose of gather_feat, same corners and weights.
+__device__ void scatter_feat(const GridDev& g, float* const d_grid[3], int scene, const Cell& c,
+                             const float* dfeat, int lane)
+{
+    const int C = g.C;
+    if (g.kind == LP_GRID_VOXEL) {
+        float* V = d_grid[0] + (size_t)scene * g.N[0] * g.N[1] * g.N[2] * C;
+        for (int d = 0; d < 8; ++d) {
+            const int dx = d >> 2, dy = (d >> 1) & 1, dz = d & 1;
+            const float w = (dx ? c.f[0] : 1.0f - c.f[0]) * (dy ? c.f[1] : 1.0f - c.f[1]) *
+                            (dz ? c.f[2] : 1.0f - c.f[2]);
+            const size_t off =
+                (((size_t)(c.i[0] + dx) * g.N[1] + (c.i[1] + dy)) * g.N[2] + (c.i[2] + dz)) * C;
+            for (int k = 0; k < C; ++k) atomicAdd(V + off + k, w * dfeat[k * kLanes + lane]);
+        }
+    } else {
+        for (int p = 0; p < 3; ++p) {
+            const int a = p, b = (p + 1) % 3;
+            float* P = d_grid[p] + (size_t)scene * g.N[a] * g.N[b] * C;
+            for (int d = 0; d < 4; ++d) {
+                const int da = d >> 1, db = d & 1;
+                const float w = (da ? c.f[a] : 1.0f - c.f[a]) * (db ? c.f[b] : 1.0f - c.f[b]);
+                const size_t off = ((size_t)(c.i[a] + da) * g.N[b] + (c.i[b] + db)) * C;
+                for (int k = 0; k < C; ++k) atomicAdd(P + off + k, w * dfeat[k * kLanes + lane]);
+            }
+        }
+    }
+}
+
+// Runs the MLP on the lane's column.  acts holds act_total columns: the input features
+// followed by every layer's output (post-ReLU for hidden layers, linear for the last).
+__device__ void mlp_forward(const MlpDev& m, const float* sW, float* acts, int lane)
+{
+    int off_in = 0, off_out = m.dims[0];
+    for (int l = 0; l < m.n_layers; ++l) {
+        const int nin = m.dims[l], nout = m.dims[l + 1];
+        const float* W = sW + m.w_off[l];
+        const float* B = sW + m.b_off[l];
+        const bool hidden = l + 1 < m.n_layers;
+        for (int o = 0; o < nout; ++o) {
+            float z = B[o];
+            for (int k = 0; k < nin; ++k) z += W[o * nin + k] * acts[(off_in + k) * kLanes + lane];
+            acts[(off_out + o) * kLanes + lane] = hidden ? fmaxf(z, 0.0f) : z;
+        }
+        off_in = off_out;
+        off_out += nout;
+    }
+}
+
+struct RayRegs {
+    float o[3], d[3], near, delta;
+    int scene;
+};
+
+__device__ __forceinline__ RayRegs load_ray(const RaysDev& r, long long ray)
+{
+    RayRegs q;
+    for (int a = 0; a < 3; ++a) {
+        q.o[a] = r.origins[3 * ray + a];
+        q.d[a] = r.dirs[3 * ray + a];
+    }
+    q.near = r.near[ray];
+    q.delta = (r.far[ray] - q.near) / (float)r.S;
+    q.scene = r.scene ? r.scene[ray] : 0;
+    return q;
+}
+
+}  // namespace
+
+__global__ __launch_bounds__(kLanes) void fwd_generic_kernel(GridDev g, MlpDev m, RaysDev rays,
+                                                             FwdOut out)
+{
+    extern __shared__ float smem[];
+    float* sW = smem;
+    float* acts = smem + m.param_total;
+    stage_params(m, sW);
+    __syncthreads();
+
+    const int lane = threadIdx.x;
+    const long long ray_raw = (long long)blockIdx.x * kLanes + lane;
+    const bool live = ray_raw < rays.M;
+    const long long ray = live ? ray_raw : rays.M - 1;
+    const RayRegs q = load_ray(rays, ray);
+    const int out_off = m.act_total - 4;
+
+    float T = 1.0f, tau = 0.0f, rgb[3] = {0.0f, 0.0f, 0.0f}, depth = 0.0f;
+    for (int j = 0; j < rays.S; ++j) {
+        const float t = q.near + ((float)j + 0.5f) * q.delta;
+        const Cell c = locate(g, q.o[0] + t * q.d[0], q.o[1] + t * q.d[1], q.o[2] + t * q.d[2]);
+        gather_feat(g, q.scene, c, acts, lane);
+        mlp_forward(m, sW, acts, lane);
+        const float sigma = softplus_f(acts[(out_off + 0) * kLanes + lane]);
+        const float sd = sigma * q.delta;
+        const float Tn = T * expf(-sd);
+        const float w = T - Tn;
+        for (int ch = 0; ch < 3; ++ch)
+            rgb[ch] += w * logistic_f(acts[(out_off + 1 + ch) * kLanes + lane]);
+        depth += w * t;
+        tau += sd;
+        T = Tn;
+    }
+    if (live) {
+        for (int ch = 0; ch < 3; ++ch) out.rgb[3 * ray + ch] = rgb[ch] + T * out.bg[ch];
+        if (out.alpha) out.alpha[ray] = 1.0f - T;
+        if (out.depth) out.depth[ray] = depth;
+        if (out.cache) out.cache[ray] = tau;
+    }
+}
+
+// Backward: reverse march with recomputation (Section 3.4).  Per sample q, from last to
+// first:  tau_{q-1} = tau_q - sigma_q Delta,  T = exp(-tau)  (the paper's
+// T_{q-1} = T_q exp(Delta sigma_q), kept in the log domain so that it survives T_S
+// underflowing), then Eq. (2) with the running suffix sum of w_j a_j.
+// LDS: params | dparams accumulators | acts (act_total columns) | dz (2 * max_width columns).
+__global__ __launch_bounds__(kLanes) void bwd_generic_kernel(GridDev g, MlpDev m, RaysDev rays,
+                                                             BwdIo io, int tiles_per_block)
+{
+    extern __shared__ float smem[];
+    float* sW = smem;
+    float* sdW = sW + m.param_total;
+    float* acts = sdW + m.param_total;
+    float* dz0 = acts + m.act_total * kLanes;
+    float* dz1 = dz0 + m.max_width * kLanes;
+    stage_params(m, sW);
+    for (int i = threadIdx.x; i < m.param_total; i += blockDim.x) sdW[i] = 0.0f;
+    __syncthreads();
+
+    const int lane = threadIdx.x;
+    const int out_off = m.act_total - 4;
+    const long long n_tiles = (rays.M + kLanes - 1) / kLanes;
+
+    for (int it = 0; it < tiles_per_block; ++it) {
+        const long long tile = (long long)blockIdx.x * tiles_per_block + it;
+        if (tile >= n_tiles) break;  // uniform over the block
+        const long long ray_raw = tile * kLanes + lane;
+        const bool live = ray_raw < rays.M;
+        const long long ray = live ? ray_raw : rays.M - 1;
+        const RayRegs q = load_ray(rays, ray);
+        float p[3];
+        for (int ch = 0; ch < 3; ++ch) p[ch] = live ? io.d_rgb[3 * ray + ch] : 0.0f;
+        const float p_alpha = (live && io.d_alpha) ? io.d_alpha[ray] : 0.0f;
+        const float p_depth = (live && io.d_depth) ? io.d_depth[ray] : 0.0f;
+        const float tau_S = io.cache[ray];
+        const float T_S = expf(-tau_S);
+        // d(loss)/dT_S through alpha = 1 - T_S and rgb += T_S bg
+        const float kS = T_S * (p_alpha - (p[0] * io.bg[0] + p[1] * io.bg[1] + p[2] * io.bg[2]));
+        float tau = tau_S;   // optical depth up to and including the current sample
+        float suffix = 0.0f; // sum_{j>q} w_j a_j
+
+        for (int j = rays.S - 1; j >= 0; --j) {
+            const float t = q.near + ((float)j + 0.5f) * q.delta;
+            const Cell c = locate(g, q.o[0] + t * q.d[0], q.o[1] + t * q.d[1], q.o[2] + t * q.d[2]);
+            gather_feat(g, q.scene, c, acts, lane);
+            mlp_forward(m, sW, acts, lane);
+            const float z0 = acts[(out_off + 0) * kLanes + lane];
+            const float sigma = softplus_f(z0);
+            const float sd = sigma * q.delta;
+            const float Tq = expf(-tau);          // T_q
+            const float tau_prev = tau - sd;
+            const float Tprev = expf(-tau_prev);  // T_{q-1}
+            const float w = Tprev - Tq;
+            float col[3], a = p_depth * t;
+            for (int ch = 0; ch < 3; ++ch) {
+                col[ch] = logistic_f(acts[(out_off + 1 + ch) * kLanes + lane]);
+                a += p[ch] * col[ch];
+            }
+            const float dsigma = q.delta * (Tq * a - suffix + kS);
+            suffix += w * a;
+            tau = tau_prev;
+
+            // heads
+            float* dz = dz0;
+            float* dz_next = dz1;
+            dz[0 * kLanes + lane] = live ? dsigma * logistic_f(z0) : 0.0f;
+            for (int ch = 0; ch < 3; ++ch)
+                dz[(1 + ch) * kLanes + lane] = live ? w * p[ch] * col[ch] * (1.0f - col[ch]) : 0.0f;
+
+            // layers in reverse: dz holds dL/d(pre-activation) of layer l's outputs
+            int off_out = out_off;
+            for (int l = m.n_layers - 1; l >= 0; --l) {
+                const int nin = m.dims[l], nout = m.dims[l + 1];
+                const int off_in = off_out - nin;
+                const float* W = sW + m.w_off[l];
+                __syncthreads();
+                // weight and bias gradients: each lane owns a strided set of weights and sums
+                // the outer product over the 64 rays of the tile
+                for (int idx = lane; idx < nin * nout; idx += kLanes) {
+                    const int o = idx / nin, k = idx - o * nin;
+                    float s = 0.0f;
+                    for (int r = 0; r < kLanes; ++r)
+                        s += dz[o * kLanes + r] * acts[(off_in + k) * kLanes + r];
+                    sdW[m.w_off[l] + idx] += s;
+                }
+                for (int o = lane; o < nout; o += kLanes) {
+                    float s = 0.0f;
+                    for (int r = 0; r < kLanes; ++r) s += dz[o * kLanes + r];
+                    sdW[m.b_off[l] + o] += s;
+                }
+                // input gradient of the lane's own column, through the ReLU of the layer below
+                for (int k = 0; k < nin; ++k) {
+                    float s = 0.0f;
+                    for (int o = 0; o < nout; ++o) s += W[o * nin + k] * dz[o * kLanes + lane];
+                    if (l > 0 && !(acts[(off_in + k) * kLanes + lane] > 0.0f)) s = 0.0f;
+                    dz_next[k * kLanes + lane] = s;
+                }
+                __syncthreads();
+                float* tmp = dz; dz = dz_next; dz_next = tmp;
+                off_out = off_in;
+            }
+            if (live) scatter_feat(g, io.d_grid, q.scene, c, dz, lane);
+        }
+    }
+    __syncthreads();
+    // this block's partial sums; a second kernel adds all records into dW / db
+    float* rec = io.ws + (size_t)blockIdx.x * io.ws_stride;
+    for (int i = threadIdx.x; i < m.param_total; i += blockDim.x) rec[i] = sdW[i];
+}
+
+// dW[l] += sum over records, db[l] likewise; one thread per parameter, fp64 running sum,
+// fixed order (deterministic).
+__global__ void reduce_params_kernel(MlpDev m, BwdIo io, int n_records)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= m.param_total) return;
+    double s = 0.0;
+    for (int r = 0; r < n_records; ++r) s += (double)io.ws[(size_t)r * io.ws_stride + i];
+    for (int l = 0; l < m.n_layers; ++l) {
+        const int nw = m.dims[l] * m.dims[l + 1];
+        if (i >= m.w_off[l] && i < m.w_off[l] + nw) {
+            io.dW[l][i - m.w_off[l]] += (float)s;
+            return;
+        }
+        if (i >= m.b_off[l] && i < m.b_off[l] + m.dims[l + 1]) {
+            io.db[l][i - m.b_off[l]] += (float)s;
+            return;
+        }
+    }
+}
+
+}  // namespace lp

@@ -1,0 +1,108 @@
+"""Helpers of the GPU parity tests: run the HIP library and the CPU oracle on the same
+seeded host buffers and compare element by element."""
+from __future__ import annotations
+
+import numpy as np
+
+FWD_RTOL = 1e-4   # forward outputs, fp32 relative tolerance
+BWD_RTOL = 1e-3   # gradients
+
+
+def close(gpu: np.ndarray, ref: np.ndarray, rtol: float, what: str):
+    """Per tensor, elementwise |gpu - ref| <= rtol |ref| + rtol rms(ref)."""
+    gpu = np.asarray(gpu, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert gpu.shape == ref.shape, (what, gpu.shape, ref.shape)
+    assert np.isfinite(gpu).all(), f"{what}: non-finite values from the GPU"
+    rms = float(np.sqrt(np.mean(ref * ref))) if ref.size else 0.0
+    err = np.abs(gpu - ref)
+    bound = rtol * np.abs(ref) + rtol * rms
+    if not (err <= bound).all():
+        k = int(np.argmax(err - bound))
+        raise AssertionError(
+            f"{what}: {int((err > bound).sum())} of {ref.size} elements out of tolerance {rtol:g}; "
+            f"worst at flat index {k}: gpu={gpu.reshape(-1)[k]!r} ref={ref.reshape(-1)[k]!r} "
+            f"rms(ref)={rms:g} max|err|/max|ref|={err.max() / max(np.abs(ref).max(), 1e-300):g}")
+    return float(err.max() / max(rms, 1e-300))
+
+
+RELU_C = {0: 2e-5, 1: 2e-6, 2: 2e-5}   # kink band per math mode (default, generic fp32, bf16x3)
+
+
+def close_envelope(gpu, ref, lo, hi, rtol: float, what: str):
+    """Like close(), for gradients when some ReLU pre-activations lie within rounding of
+    zero: there either one-sided derivative is a correct answer, and `lo`/`hi` are the
+    elementwise envelope of the oracle's gradients over both choices.  Outside such samples
+    lo == hi == ref and this is exactly close()."""
+    gpu = np.asarray(gpu, dtype=np.float64)
+    assert gpu.shape == ref.shape, (what, gpu.shape, ref.shape)
+    assert np.isfinite(gpu).all(), f"{what}: non-finite values from the GPU"
+    rms = float(np.sqrt(np.mean(ref * ref))) if ref.size else 0.0
+    bound = rtol * np.abs(ref) + rtol * rms
+    err = np.maximum(np.maximum(lo - gpu, gpu - hi), 0.0)
+    if not (err <= bound).all():
+        k = int(np.argmax(err - bound))
+        raise AssertionError(
+            f"{what}: {int((err > bound).sum())} of {ref.size} elements out of tolerance {rtol:g}; "
+            f"worst at flat index {k}: gpu={gpu.reshape(-1)[k]!r} ref={ref.reshape(-1)[k]!r} "
+            f"envelope=[{lo.reshape(-1)[k]!r}, {hi.reshape(-1)[k]!r}] rms(ref)={rms:g}")
+    widened = float(((hi - lo) > bound).mean()) if ref.size else 0.0
+    return float(err.max() / max(rms, 1e-300)), widened
+
+
+def mse_upstream(rgb64: np.ndarray, target: np.ndarray, scene=None, n_scenes: int = 1) -> np.ndarray:
+    """d(loss)/d(rgb) of the mean-squared error to `target` (mean over the rays of a scene
+    and the 3 channels, summed over scenes), as float32 — the value both sides receive."""
+    m = rgb64.shape[0]
+    if scene is None or n_scenes == 1:
+        per = np.full(m, m, dtype=np.float64)
+    else:
+        counts = np.bincount(scene, minlength=n_scenes).astype(np.float64)
+        per = counts[scene]
+    return (2.0 * (rgb64 - target.astype(np.float64)) / (3.0 * per[:, None])).astype(np.float32)
+
+
+def run_gpu(lp, inp, p_rgb, p_alpha=None, p_depth=None, math_mode=0, device="cuda:0"):
+    """Forward + backward on the GPU through the C ABI; everything returned as numpy."""
+    import torch
+    grid, mlp, rays, bg = lp.to_device(inp, device)
+    rgb, alpha, depth, cache = lp.render_fwd(grid, mlp, rays, bg, math_mode)
+    up = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device)
+    d_grid, dW, db = lp.render_bwd(grid, mlp, rays, bg, up(p_rgb), cache, up(p_alpha), up(p_depth), math_mode)
+    torch.cuda.synchronize()
+    cpu = lambda t: t.cpu().numpy()
+    return dict(rgb=cpu(rgb), alpha=cpu(alpha), depth=cpu(depth), cache=cpu(cache),
+                d_grid=[cpu(t) for t in d_grid], dW=[cpu(t) for t in dW], db=[cpu(t) for t in db])
+
+
+def check_case(lp, oracle, inp, math_mode=0, aux_grads=True, seed=0, label=""):
+    """Full parity of one problem: forward outputs and every gradient tensor."""
+    import lp_inputs
+    prob = oracle.Problem(inp)
+    o_rgb, o_alpha, o_depth = oracle.render_fwd(prob)
+    p_rgb = mse_upstream(o_rgb, inp.target, inp.scene, inp.n_scenes)
+    p_alpha = p_depth = None
+    if aux_grads:
+        p_alpha, p_depth = lp_inputs.upstream_grads(inp.n_rays, 77 + seed)
+    o_dg, o_dW, o_db = oracle.render_bwd(prob, p_rgb, p_alpha, p_depth)
+    c = RELU_C[math_mode]
+    plus = oracle.render_bwd(prob, p_rgb, p_alpha, p_depth, relu_c=c)
+    minus = oracle.render_bwd(prob, p_rgb, p_alpha, p_depth, relu_c=-c)
+    env = lambda i, j: (np.minimum(np.minimum(plus[i][j], minus[i][j]), (o_dg, o_dW, o_db)[i][j]),
+                        np.maximum(np.maximum(plus[i][j], minus[i][j]), (o_dg, o_dW, o_db)[i][j]))
+    g = run_gpu(lp, inp, p_rgb, p_alpha, p_depth, math_mode)
+    worst = {}
+    worst["rgb"] = close(g["rgb"], o_rgb, FWD_RTOL, f"{label} rgb")
+    worst["alpha"] = close(g["alpha"], o_alpha, FWD_RTOL, f"{label} alpha")
+    worst["depth"] = close(g["depth"], o_depth, FWD_RTOL, f"{label} depth")
+    for p, (a, b) in enumerate(zip(g["d_grid"], o_dg)):
+        worst[f"d_grid{p}"] = close_envelope(a, b, *env(0, p), BWD_RTOL, f"{label} d_grid[{p}]")
+    for l, (a, b) in enumerate(zip(g["dW"], o_dW)):
+        worst[f"dW{l}"] = close_envelope(a, b, *env(1, l), BWD_RTOL, f"{label} dW[{l}]")
+    for l, (a, b) in enumerate(zip(g["db"], o_db)):
+        worst[f"db{l}"] = close_envelope(a, b, *env(2, l), BWD_RTOL, f"{label} db[{l}]")
+    # the envelope must stay tight almost everywhere, or the comparison loses its force
+    for k, v in worst.items():
+        if isinstance(v, tuple):
+            assert v[1] < 0.05, f"{label} {k}: kink envelope widened on {v[1]:.1%} of the elements"
+    return worst

@@ -1,0 +1,76 @@
+"""The C-ABI library loads and exports every function include/*.h declares; argument
+errors are reported as statuses before anything touches a GPU.  CPU only."""
+import ctypes as C
+import glob
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2404_19760_amd", "liblightplane.so")
+
+
+def declared_functions():
+    names = []
+    for h in glob.glob(os.path.join(ROOT, "include", "*.h")):
+        src = open(h).read()
+        src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+        names += re.findall(r"\b(lp_[a-z_0-9]+)\s*\(", src)
+    return sorted(set(names))
+
+
+def test_header_declares_the_entry_points():
+    names = declared_functions()
+    for required in ("lp_render_fwd", "lp_render_bwd", "lp_bwd_workspace_bytes", "lp_last_error"):
+        assert required in names
+
+
+def test_library_exports_every_declared_symbol():
+    assert os.path.exists(LIB), "build the library first: python -m paper_2404_19760_amd.build"
+    lib = C.CDLL(LIB)
+    for name in declared_functions():
+        assert hasattr(lib, name), f"{name} is declared in include/ but not exported"
+
+
+def test_invalid_arguments_are_statuses_not_crashes():
+    import paper_2404_19760_amd as lp
+    lib = lp._lib
+    assert lp.lp_version() >= 1000
+    st = lib.lp_render_fwd(None, None, None, None, None, None, None, None, 0, None)
+    assert st == lp.LP_ERR_INVALID_ARG
+    assert b"NULL" in lib.lp_last_error()
+    g = lp._Grid(); m = lp._Mlp(); r = lp._Rays()
+    g.kind, g.B, g.C, g.NX, g.NY, g.NZ = 0, 1, 4, 1, 8, 8      # NX < 2
+    g.data[0] = 4096
+    for a in range(3):
+        g.aabb_min[a], g.aabb_max[a] = -1.0, 1.0
+    bg = (C.c_float * 3)(1, 1, 1)
+    st = lib.lp_render_fwd(C.byref(g), C.byref(m), C.byref(r), bg, None, None, None, None, 0, None)
+    assert st == lp.LP_ERR_INVALID_ARG and b"resolution" in lib.lp_last_error()
+    g.NX = 8
+    m.n_layers = 1; m.dims[0] = 4; m.dims[1] = 3                # last layer must have 4 outputs
+    m.W[0] = 4096; m.b[0] = 4096
+    r.M, r.S = 0, 4
+    st = lib.lp_render_fwd(C.byref(g), C.byref(m), C.byref(r), bg, None, None, None, None, 0, None)
+    assert st == lp.LP_ERR_INVALID_ARG and b"4 outputs" in lib.lp_last_error()
+    m.dims[1] = 4
+    r.S = 0
+    st = lib.lp_render_fwd(C.byref(g), C.byref(m), C.byref(r), bg, None, None, None, None, 0, None)
+    assert st == lp.LP_ERR_INVALID_ARG and b"rays->S" in lib.lp_last_error()
+    r.S = 4
+    st = lib.lp_render_fwd(C.byref(g), C.byref(m), C.byref(r), bg, None, None, None, None, 99, None)
+    assert st == lp.LP_ERR_INVALID_ARG and b"math_mode" in lib.lp_last_error()
+    # M == 0 with valid shapes is a successful no-op and needs no GPU
+    st = lib.lp_render_fwd(C.byref(g), C.byref(m), C.byref(r), bg, None, None, None, None, 0, None)
+    assert st == lp.LP_OK
+
+
+def test_product_path_does_not_reach_the_oracle():
+    """Nothing under the package names, imports or links the oracle."""
+    pkg = os.path.join(ROOT, "paper_2404_19760_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower(), f

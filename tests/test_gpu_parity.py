@@ -1,0 +1,176 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on the
+same seeded inputs, element by element.  Tolerances: forward 1e-4, gradients 1e-3
+(fp32 relative, per tensor: |gpu - ref| <= rtol |ref| + rtol rms(ref))."""
+import dataclasses
+
+import numpy as np
+import pytest
+
+import lp_inputs
+from lp_inputs import TRIPLANE, VOXEL
+
+from parity import BWD_RTOL, FWD_RTOL, check_case, close, mse_upstream, run_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def oracle():
+    import oracle as o
+    return o
+
+
+def _modes(lp, inp):
+    """Math modes to test for a problem: the generic kernels always, the matrix-core
+    kernels when they cover the shape."""
+    import torch
+    grid, mlp, _, _ = lp.to_device(dataclasses.replace(inp, origins=inp.origins[:1], dirs=inp.dirs[:1],
+                                                       near=inp.near[:1], far=inp.far[:1],
+                                                       scene=None if inp.scene is None else inp.scene[:1]))
+    modes = [lp.LP_MATH_GENERIC]
+    if lp.lp_has_fast_path(grid, mlp):
+        modes.append(lp.LP_MATH_BF16X3)
+    return modes
+
+
+# ------------------------------------------------------------------ small problems, odd sizes
+
+@pytest.mark.parametrize("kind", [VOXEL, TRIPLANE])
+def test_small_odd_shapes_generic(lp, oracle, kind):
+    """Channel count, widths, ray count and sample count that fit no tile: generic kernels."""
+    inp = lp_inputs.make_small(kind, channels=5, res=(6, 5, 7), mlp_dims=(5, 7, 9, 4), n_rays=131,
+                               samples=37, seed=41, n_scenes=3)
+    print(check_case(lp, oracle, inp, lp.LP_MATH_GENERIC, label=f"small kind={kind}"), flush=True)
+
+
+@pytest.mark.parametrize("kind", [VOXEL, TRIPLANE])
+def test_clamped_samples_outside_the_box(lp, oracle, kind):
+    """Box [-0.4, 0.4]^3 is much smaller than the ray span: most samples clamp to the border."""
+    inp = lp_inputs.make_small(kind, channels=16, res=(9, 8, 10), mlp_dims=(16, 32, 4), n_rays=70,
+                               samples=65, seed=43, aabb_min=(-0.4, -0.4, -0.4), aabb_max=(0.4, 0.4, 0.4))
+    for mode in _modes(lp, inp):
+        print(mode, check_case(lp, oracle, inp, mode, label=f"clamp kind={kind} mode={mode}"), flush=True)
+
+
+@pytest.mark.parametrize("kind,channels,dims", [
+    (VOXEL, 16, (16, 64, 64, 4)), (VOXEL, 32, (32, 64, 4)),
+    (TRIPLANE, 16, (16, 32, 4)), (TRIPLANE, 32, (32, 64, 64, 4)), (TRIPLANE, 32, (32, 32, 32, 4)),
+])
+@pytest.mark.parametrize("samples", [1, 64, 150])
+def test_config_shapes_ragged(lp, oracle, kind, channels, dims, samples):
+    """The MLP / grid shapes of the five configurations on small grids, with ray counts and
+    sample counts that leave ragged tails (several tiles plus a partial one)."""
+    inp = lp_inputs.make_small(kind, channels=channels, res=(12, 10, 11), mlp_dims=dims, n_rays=203,
+                               samples=samples, seed=47 + samples, n_scenes=2, grid_std=0.3,
+                               aabb_min=(-1.5, -1.5, -1.5), aabb_max=(1.5, 1.5, 1.5))
+    for mode in _modes(lp, inp):
+        print(mode, check_case(lp, oracle, inp, mode, label=f"kind={kind} dims={dims} S={samples} mode={mode}"),
+              flush=True)
+
+
+# ------------------------------------------------------------------ the five configurations
+
+def test_config_tiny_full(lp, oracle):
+    inp = lp_inputs.make_inputs("tiny")
+    for mode in _modes(lp, inp):
+        print(mode, check_case(lp, oracle, inp, mode, label=f"tiny mode={mode}"), flush=True)
+
+
+def test_config_single_scene_full(lp, oracle):
+    inp = lp_inputs.make_inputs("single_scene")
+    for mode in _modes(lp, inp)[-1:]:
+        print(mode, check_case(lp, oracle, inp, mode, aux_grads=False, label=f"single_scene mode={mode}"),
+              flush=True)
+
+
+@pytest.mark.parametrize("name,n_keep", [("voxel", 1536), ("batched", 1024), ("large", 768)])
+def test_config_large_on_ray_subsets(lp, oracle, name, n_keep):
+    """Configurations 3-5: the full grid and MLP, a deterministic strided subset of the rays
+    run as its own ray set on both sides (rays are independent; gradients are sums over rays)."""
+    inp = lp_inputs.make_inputs(name)
+    sub = inp.subset(lp_inputs.strided_ray_subset(inp.n_rays, n_keep, offset=3))
+    for mode in _modes(lp, sub)[-1:]:
+        print(mode, check_case(lp, oracle, sub, mode, label=f"{name} subset mode={mode}"), flush=True)
+
+
+# ------------------------------------------------------------------ edge cases
+
+def test_zero_rays_is_a_noop(lp):
+    import torch
+    inp = lp_inputs.make_small(VOXEL, channels=16, mlp_dims=(16, 32, 4))
+    grid, mlp, rays, bg = lp.to_device(inp.subset(np.arange(0)))
+    rgb, alpha, depth, cache = lp.render_fwd(grid, mlp, rays, bg)
+    d_rgb = torch.zeros((0, 3), device="cuda:0")
+    d_grid, dW, db = lp.render_bwd(grid, mlp, rays, bg, d_rgb, cache)
+    torch.cuda.synchronize()
+    assert rgb.shape == (0, 3) and all(float(t.abs().sum()) == 0.0 for t in d_grid + dW + db)
+
+
+def test_zero_density_renders_background_exactly(lp):
+    import torch
+    inp = lp_inputs.make_small(VOXEL, channels=16, mlp_dims=(16, 32, 4), n_rays=100, samples=70)
+    inp.weights[-1][0, :] = 0.0
+    inp.biases[-1][0] = -200.0
+    for mode in _modes(lp, inp):
+        grid, mlp, rays, bg = lp.to_device(inp)
+        rgb, alpha, depth, _ = lp.render_fwd(grid, mlp, rays, bg, mode)
+        torch.cuda.synchronize()
+        assert float(alpha.abs().max()) == 0.0 and float(depth.abs().max()) == 0.0
+        assert torch.equal(rgb, torch.tensor(bg, device="cuda:0").expand_as(rgb))
+
+
+def test_errors_through_the_abi(lp):
+    import torch
+    inp = lp_inputs.make_small(VOXEL, channels=16, mlp_dims=(16, 32, 4), n_rays=10)
+    grid, mlp, rays, bg = lp.to_device(inp)
+    rgb, alpha, depth, cache = lp.render_fwd(grid, mlp, rays, bg)
+    d_rgb = torch.zeros_like(rgb)
+    small_ws = torch.empty(16, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(lp.LightplaneError) as e:
+        lp.render_bwd(grid, mlp, rays, bg, d_rgb, cache, workspace=small_ws)
+    assert e.value.status == lp.LP_ERR_WORKSPACE
+    odd = lp_inputs.make_small(VOXEL, channels=5, mlp_dims=(5, 7, 4), n_rays=10)
+    g2, m2, r2, _ = lp.to_device(odd)
+    with pytest.raises(lp.LightplaneError) as e:
+        lp.render_fwd(g2, m2, r2, bg, lp.LP_MATH_BF16X3)
+    assert e.value.status == lp.LP_ERR_UNSUPPORTED
+
+
+def test_forward_is_bit_reproducible_and_gradients_accumulate(lp):
+    import torch
+    inp = lp_inputs.make_inputs("tiny")
+    grid, mlp, rays, bg = lp.to_device(inp)
+    a = lp.render_fwd(grid, mlp, rays, bg)
+    b = lp.render_fwd(grid, mlp, rays, bg)
+    assert all(torch.equal(x, y) for x, y in zip(a, b))
+    d_rgb = torch.randn_like(a[0]) / rays.n_rays
+    g1 = lp.render_bwd(grid, mlp, rays, bg, d_rgb, a[3])
+    # second call accumulates into the same buffers: result doubles
+    ws = torch.empty(lp.lp_bwd_workspace_bytes(grid, mlp, rays), dtype=torch.uint8, device="cuda:0")
+    d_grid = [t.clone() for t in g1[0]]; dW = [t.clone() for t in g1[1]]; db = [t.clone() for t in g1[2]]
+    lp.lp_render_bwd(grid, mlp, rays, bg, d_rgb, None, None, a[3], d_grid, dW, db, ws)
+    torch.cuda.synchronize()
+    for once, twice in zip(g1[0] + g1[1] + g1[2], d_grid + dW + db):
+        close(twice.cpu().numpy(), 2.0 * once.cpu().numpy().astype(np.float64), BWD_RTOL, "accumulate")
+
+
+def test_activation_memory_independent_of_samples(lp):
+    """Section 3.4: the only state kept between forward and backward is one scalar per ray;
+    the library allocates nothing and its workspace does not grow with S."""
+    import torch
+    inp = lp_inputs.make_inputs("tiny")
+    peaks, ws_bytes = [], []
+    for s in (64, 256):
+        q = dataclasses.replace(inp, samples=s)
+        grid, mlp, rays, bg = lp.to_device(q)
+        ws_bytes.append(lp.lp_bwd_workspace_bytes(grid, mlp, rays))
+        d_rgb = torch.zeros((rays.n_rays, 3), device="cuda:0")
+        torch.cuda.synchronize(); torch.cuda.reset_peak_memory_stats()
+        base = torch.cuda.memory_allocated()
+        out = lp.render_fwd(grid, mlp, rays, bg)
+        lp.render_bwd(grid, mlp, rays, bg, d_rgb, out[3])
+        torch.cuda.synchronize()
+        peaks.append(torch.cuda.max_memory_allocated() - base)
+        del out
+    assert ws_bytes[0] == ws_bytes[1]
+    assert peaks[0] == peaks[1], peaks
