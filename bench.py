@@ -1,0 +1,159 @@
+#!/usr/bin/env python3
+"""Benchmark of the Lightplane Renderer hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config large]
+
+One step = one pass of the whole hot path over one batch of synthetic rays: forward
+(sample, interpolate, decode, composite), MSE loss gradient, zeroing of the gradient
+buffers, backward (recompute, emission-absorption VJP, MLP backward, scatter into the
+grid and MLP gradients).  Inputs are resident in HBM before the timed region.  Prints
+ONE JSON line: ray-samples/s of forward+backward, the HBM-roofline view of the dominant
+kernel (algorithmic gather/scatter bytes over its HIP-event duration), and the CPU oracle
+timed on a bounded ray subset of the same workload on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import sys
+import time
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="large",
+                    help="workload: tiny | single_scene | voxel | batched | large")
+    ap.add_argument("--math", default="default", choices=["default", "generic", "bf16x3"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    return ap.parse_args()
+
+
+def cpu_baseline(inp, budget_s: float):
+    """The oracle as it stands, forward + backward, on a strided ray subset sized to take
+    about `budget_s` seconds on this machine's cores."""
+    import lp_inputs
+    import oracle
+    rng = np.random.default_rng(5)
+
+    def run(n):
+        sub = inp.subset(lp_inputs.strided_ray_subset(inp.n_rays, n, offset=1))
+        prob = oracle.Problem(sub)
+        p = (rng.standard_normal((sub.n_rays, 3)) / sub.n_rays)
+        t0 = time.perf_counter()
+        oracle.render_fwd(prob)
+        oracle.render_bwd(prob, p)      # recomputes the forward internally, then reverses it
+        return time.perf_counter() - t0, sub.n_rays
+
+    t_probe, n_probe = run(min(256, inp.n_rays))
+    n = int(max(n_probe, min(inp.n_rays, n_probe * budget_s / max(t_probe, 1e-3))))
+    t, n = run(n)
+    return {"value": n * inp.samples / t, "unit": "ray-samples/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "sample": f"{n} of {inp.n_rays} rays (every {max(1, inp.n_rays // n)}th), "
+            f"all {inp.samples} samples each, fp64 forward + stored-forward reverse-mode backward, {t:.1f} s"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus {args.gpus} "
+              "is not supported", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import lp_inputs
+    import paper_2404_19760_amd as lp
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the Renderer has no CPU path", file=sys.stderr)
+        sys.exit(2)
+    w = lp_inputs.WORKLOADS[args.config]
+    inp = lp_inputs.make_inputs(args.config)
+    dev = "cuda:0"
+    grid, mlp, rays, bg = lp.to_device(inp, dev)
+    target = torch.from_numpy(inp.target).to(dev)
+    mode = {"default": lp.LP_MATH_DEFAULT, "generic": lp.LP_MATH_GENERIC, "bf16x3": lp.LP_MATH_BF16X3}[args.math]
+    fast = lp.lp_has_fast_path(grid, mlp) and mode != lp.LP_MATH_GENERIC
+
+    m = rays.n_rays
+    rgb = torch.empty((m, 3), device=dev); alpha = torch.empty(m, device=dev)
+    depth = torch.empty(m, device=dev); cache = torch.empty(m, device=dev)
+    d_grid = [torch.zeros_like(t) for t in grid.data]
+    dW = [torch.zeros_like(t) for t in mlp.weights]
+    db = [torch.zeros_like(t) for t in mlp.biases]
+    ws = torch.empty(lp.lp_bwd_workspace_bytes(grid, mlp, rays, mode), dtype=torch.uint8, device=dev)
+    if inp.scene is None:
+        inv = torch.full((m, 1), 2.0 / (3.0 * m), device=dev)
+    else:
+        counts = torch.bincount(rays.scene.long(), minlength=inp.n_scenes).float()
+        inv = (2.0 / (3.0 * counts[rays.scene.long()]))[:, None]
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    fwd_ms, bwd_ms = [], []
+
+    def step(timed: bool):
+        e0, e1, e2, e3 = ev(), ev(), ev(), ev()
+        e0.record()
+        lp.lp_render_fwd(grid, mlp, rays, bg, rgb, alpha, depth, cache, mode)
+        e1.record()
+        d_rgb = (rgb - target) * inv                      # MSE loss gradient
+        for t in d_grid + dW + db:
+            t.zero_()
+        e2.record()
+        lp.lp_render_bwd(grid, mlp, rays, bg, d_rgb, None, None, cache, d_grid, dW, db, ws, mode)
+        e3.record()
+        return (e0, e1, e2, e3) if timed else None
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    events = [step(True) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    for e0, e1, e2, e3 in events:
+        fwd_ms.append(e0.elapsed_time(e1))
+        bwd_ms.append(e2.elapsed_time(e3))
+
+    samples = m * inp.samples
+    ms_per_step = 1e3 * elapsed / args.steps
+    g_bytes = w.gather_bytes_per_sample
+    fwd_avg, bwd_avg = float(np.mean(fwd_ms)), float(np.mean(bwd_ms))
+    # dominant kernel: the backward (re-reads the G gather bytes and adds G bytes of gradient)
+    bwd_gbs = 2 * g_bytes * samples / (bwd_avg * 1e-3) / 1e9
+    fwd_gbs = g_bytes * samples / (fwd_avg * 1e-3) / 1e9
+    out = {
+        "metric": "ray-samples/sec fwd+bwd (Renderer hot path)",
+        "value": samples / (elapsed / args.steps),
+        "unit": "ray-samples/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 (MLP contractions: bf16 hi+lo split, 3 MFMA products, f32 accumulate)" if fast else "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{args.config}: {'voxel' if w.kind == 0 else 'triplane'} "
+                               f"{w.n_scenes}x{w.res[0]}^{3 if w.kind == 0 else 2}x{w.channels}ch, "
+                               f"{m} rays x {w.samples} samples, MLP {'-'.join(map(str, w.mlp_dims))}",
+                   "rays": m, "samples_per_ray": w.samples, "ray_samples": samples,
+                   "kernels": "mfma" if fast else "generic"},
+        "fwd": {"ms": fwd_avg, "ray_samples_per_s": samples / (fwd_avg * 1e-3),
+                "algorithmic_GBs": fwd_gbs, "frac_hbm_peak": fwd_gbs / HBM_PEAK_GBS},
+        "fwd_bwd_effective": {"algorithmic_GBs": 3 * g_bytes * samples / ((fwd_avg + bwd_avg) * 1e-3) / 1e9,
+                              "frac_hbm_peak": 3 * g_bytes * samples / ((fwd_avg + bwd_avg) * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "roofline": {"kernel": "lp_render_bwd", "bound": "hbm", "achieved": bwd_gbs, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": bwd_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_sample": 2 * g_bytes, "ms": bwd_avg},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(inp, args.cpu_seconds)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -130,11 +130,12 @@ def render_fwd(inp):
     return rgb, alpha, depth
 
 
-def render_bwd(inp, p_rgb, p_alpha=None, p_depth=None, relu_c: float = 0.0):
+def render_bwd(inp, p_rgb, p_alpha=None, p_depth=None, kink_band: float = 0.0, kink_side: int = 0):
     """Gradients of sum_i (p_rgb.rgb + p_alpha alpha + p_depth depth) w.r.t. the grid
     tensors, weights and biases.  Returns (d_grid list, dW list, db list), float64.
-    relu_c != 0 shifts the ReLU-derivative threshold by relu_c times each unit's
-    rounding-error scale (see lp_oracle.c); 0 is the definition."""
+    kink_side = 0 is the definition; +1 / -1 give the upper / lower envelope over the
+    one-sided ReLU derivatives of pre-activations within kink_band times the unit's
+    rounding-error scale of zero (see lp_oracle.c)."""
     p = inp if isinstance(inp, Problem) else Problem(inp)
     p_rgb = _f64(p_rgb)
     assert p_rgb.shape == (p.n_rays, 3)
@@ -150,7 +151,7 @@ def render_bwd(inp, p_rgb, p_alpha=None, p_depth=None, relu_c: float = 0.0):
                                 C.c_void_p(p_rgb.ctypes.data),
                                 None if pa is None else C.c_void_p(pa.ctypes.data),
                                 None if pd is None else C.c_void_p(pd.ctypes.data),
-                                dg_arr, dW_arr, db_arr, C.c_double(relu_c))
+                                dg_arr, dW_arr, db_arr, C.c_double(kink_band), C.c_int(kink_side))
     if rc != 0:
         raise RuntimeError(f"lpo_render_bwd failed with status {rc}")
     return d_grid, dW, db

@@ -301,16 +301,90 @@ int lpo_render_fwd(const lpo_grid* g, const lpo_mlp* m, const lpo_rays* rays, co
     return fail ? 2 : 0;
 }
 
+/* Rounding-error scale of a hidden unit's pre-activation: |b| + sum_k |W_k x_k|. */
+static double unit_scale(const lpo_mlp* m, int l, int o, const double* in)
+{
+    const int nin = m->dims[l];
+    double mag = fabs(m->b[l][o]);
+    for (int k = 0; k < nin; ++k) mag += fabs(m->W[l][(int64_t)o * nin + k] * in[k]);
+    return mag;
+}
+
+#define LPO_MAX_KINKS 6
+
+/* Hidden units of this sample whose pre-activation lies within band * scale of the ReLU kink:
+   writes up to LPO_MAX_KINKS (layer, unit) pairs, returns how many. */
+static int sample_kinks(const lpo_mlp* m, const double* act, const double* pre, int C, double band,
+                        int* kl, int* ko)
+{
+    int n = 0, off_in = 0, off_out = m->dims[0];
+    for (int l = 0; l + 1 < m->n_layers; ++l) {
+        for (int o = 0; o < m->dims[l + 1]; ++o)
+            if (fabs(pre[off_out - C + o]) < band * unit_scale(m, l, o, act + off_in) && n < LPO_MAX_KINKS) {
+                kl[n] = l;
+                ko[n] = o;
+                ++n;
+            }
+        off_in = off_out;
+        off_out += m->dims[l + 1];
+    }
+    return n;
+}
+
+/* Reverse-mode through the MLP of one sample.  dact holds dL/d(output) in its last 4
+   entries on entry and dL/d(feature) in its first C entries on exit; dW, db are added to.
+   ReLU' = 1 iff pre-activation > 0, except for the n_over listed units (kl, ko), whose
+   derivative is bit i of `mask`. */
+static void sample_mlp_backward(const lpo_mlp* m, const double* act, const double* pre, int C,
+                                int nact, double* dact, double* const dW[], double* const db[],
+                                int n_over, const int* kl, const int* ko, unsigned mask)
+{
+    const int nl = m->n_layers;
+    for (int k = 0; k < nact - 4; ++k) dact[k] = 0.0;
+    int off_out = nact - 4;
+    for (int l = nl - 1; l >= 0; --l) {
+        const int nin = m->dims[l], nout = m->dims[l + 1];
+        const int off_in = off_out - nin;
+        const double* W = m->W[l];
+        for (int o = 0; o < nout; ++o) {
+            double dz = dact[off_out + o];
+            if (l + 1 < nl) {
+                int on = pre[off_out - C + o] > 0.0;
+                for (int i = 0; i < n_over; ++i)
+                    if (kl[i] == l && ko[i] == o) on = (mask >> i) & 1u;
+                if (!on) dz = 0.0;
+            }
+            if (dz == 0.0) continue;
+            db[l][o] += dz;
+            for (int k = 0; k < nin; ++k) {
+                dW[l][(int64_t)o * nin + k] += dz * act[off_in + k];
+                dact[off_in + k] += dz * W[(int64_t)o * nin + k];
+            }
+        }
+        off_out = off_in;
+    }
+}
+
+/* Scratch of the kink envelope: [0] running minimum, [1] running maximum, [2] current choice. */
+typedef struct {
+    double* W[3][LPO_MAX_LAYERS];
+    double* b[3][LPO_MAX_LAYERS];
+    double* dact[3];
+} kink_tmp;
+
 /* Reverse-mode over one ray's stored forward.  The forward operations, in order:
      e_j = exp(-sigma_j Delta); T_j = T_{j-1} e_j; w_j = T_{j-1} - T_j;
      rgb = sum_j w_j c_j + T_S bg; alpha = 1 - T_S; depth = sum_j w_j t_j.
    Each is reversed individually; nothing is simplified algebraically.
-   dsig_out (optional) receives dL/dsigma_j, dcol_out (optional) dL/dc_j. */
+   dsig_out (optional) receives dL/dsigma_j, dcol_out (optional) dL/dc_j.
+   side = 0: the definition.  side = +1 / -1 (with band > 0 and kt != NULL): for every sample
+   with hidden pre-activations inside the kink band, the sample's contribution is the
+   elementwise maximum / minimum over all on/off choices for those units. */
 static void ray_backward(const lpo_grid* g, const lpo_mlp* m, const lpo_rays* rays, int64_t i,
                          const double bg[3], const ray_tape* r, const double p_rgb[3],
                          double p_alpha, double p_depth, double* const d_grid[3],
                          double* const dW[], double* const db[], double* scratch,
-                         double* dsig_out, double* dcol_out, double relu_c)
+                         double* dsig_out, double* dcol_out, double band, int side, kink_tmp* kt)
 {
     const int S = r->S, nact = r->nact, C = r->C, nl = m->n_layers;
     const int b = rays->scene ? rays->scene[i] : 0;
@@ -340,65 +414,110 @@ static void ray_backward(const lpo_grid* g, const lpo_mlp* m, const lpo_rays* ra
         /* heads: sigma = softplus(out0), c = logistic(out1..3) */
         const double* act = r->act + (size_t)j * nact;
         const double* pre = r->pre + (size_t)j * (nact - C);
-        for (int k = 0; k < nact; ++k) dact[k] = 0.0;
         const int out_off = nact - 4;
-        dact[out_off + 0] = dsigma * logistic(act[out_off + 0]);
+        double dout[4];
+        dout[0] = dsigma * logistic(act[out_off + 0]);
         for (int c = 0; c < 3; ++c) {
             const double cc = r->col[3 * j + c];
-            dact[out_off + 1 + c] = dcol[c] * cc * (1.0 - cc);
+            dout[1 + c] = dcol[c] * cc * (1.0 - cc);
         }
-        /* MLP layers in reverse */
-        int off_out = out_off;
-        for (int l = nl - 1; l >= 0; --l) {
-            const int nin = m->dims[l], nout = m->dims[l + 1];
-            const int off_in = off_out - nin;
-            const double* W = m->W[l];
-            for (int o = 0; o < nout; ++o) {
-                double dz = dact[off_out + o];
-                if (l + 1 < nl) { /* ReLU' = 1 iff pre-activation > 0 (threshold shifted only by the
-                                     kink-envelope option, see lpo_render_bwd) */
-                    double thr = 0.0;
-                    if (relu_c != 0.0) {
-                        double mag = fabs(m->b[l][o]);
-                        for (int k = 0; k < nin; ++k) mag += fabs(W[(int64_t)o * nin + k] * act[off_in + k]);
-                        thr = relu_c * mag;
-                    }
-                    if (!(pre[off_out - C + o] > thr)) dz = 0.0;
+        int kl[LPO_MAX_KINKS], ko[LPO_MAX_KINKS];
+        const int nk = (side != 0 && kt) ? sample_kinks(m, act, pre, C, band, kl, ko) : 0;
+        if (nk > 0) {
+            for (unsigned mask = 0; mask < (1u << nk); ++mask) {
+                for (int l = 0; l < nl; ++l) {
+                    memset(kt->W[2][l], 0, sizeof(double) * (size_t)m->dims[l] * m->dims[l + 1]);
+                    memset(kt->b[2][l], 0, sizeof(double) * (size_t)m->dims[l + 1]);
                 }
-                if (dz == 0.0) continue;
-                db[l][o] += dz;
-                for (int k = 0; k < nin; ++k) {
-                    dW[l][(int64_t)o * nin + k] += dz * act[off_in + k];
-                    dact[off_in + k] += dz * W[(int64_t)o * nin + k];
+                for (int c = 0; c < 4; ++c) kt->dact[2][out_off + c] = dout[c];
+                sample_mlp_backward(m, act, pre, C, nact, kt->dact[2], kt->W[2], kt->b[2], nk, kl, ko, mask);
+                for (int l = 0; l < nl; ++l) {
+                    const int64_t n = (int64_t)m->dims[l] * m->dims[l + 1];
+                    for (int64_t k = 0; k < n; ++k) {
+                        const double v = kt->W[2][l][k];
+                        kt->W[0][l][k] = mask ? fmin(kt->W[0][l][k], v) : v;
+                        kt->W[1][l][k] = mask ? fmax(kt->W[1][l][k], v) : v;
+                    }
+                    for (int k = 0; k < m->dims[l + 1]; ++k) {
+                        const double v = kt->b[2][l][k];
+                        kt->b[0][l][k] = mask ? fmin(kt->b[0][l][k], v) : v;
+                        kt->b[1][l][k] = mask ? fmax(kt->b[1][l][k], v) : v;
+                    }
+                }
+                for (int k = 0; k < C; ++k) {
+                    const double v = kt->dact[2][k];
+                    kt->dact[0][k] = mask ? fmin(kt->dact[0][k], v) : v;
+                    kt->dact[1][k] = mask ? fmax(kt->dact[1][k], v) : v;
                 }
             }
-            off_out = off_in;
+            const int pick = side > 0 ? 1 : 0;
+            for (int l = 0; l < nl; ++l) {
+                const int64_t n = (int64_t)m->dims[l] * m->dims[l + 1];
+                for (int64_t k = 0; k < n; ++k) dW[l][k] += kt->W[pick][l][k];
+                for (int k = 0; k < m->dims[l + 1]; ++k) db[l][k] += kt->b[pick][l][k];
+            }
+            /* interpolation weights are non-negative, so the envelope of weight * dfeat is the
+               weight times the envelope of dfeat */
+            for (int k = 0; k < C; ++k) dact[k] = kt->dact[pick][k];
+        } else {
+            for (int c = 0; c < 4; ++c) dact[out_off + c] = dout[c];
+            sample_mlp_backward(m, act, pre, C, nact, dact, dW, db, 0, NULL, NULL, 0u);
         }
         grid_scatter(g, d_grid, b, r->x + 3 * j, dact);
     }
 }
 
+static int kink_alloc(kink_tmp* kt, const lpo_mlp* m, int nact)
+{
+    int ok = 1;
+    memset(kt, 0, sizeof(*kt));
+    for (int v = 0; v < 3; ++v) {
+        for (int l = 0; l < m->n_layers; ++l) {
+            kt->W[v][l] = (double*)calloc((size_t)m->dims[l] * m->dims[l + 1], sizeof(double));
+            kt->b[v][l] = (double*)calloc((size_t)m->dims[l + 1], sizeof(double));
+            ok = ok && kt->W[v][l] && kt->b[v][l];
+        }
+        kt->dact[v] = (double*)calloc((size_t)nact, sizeof(double));
+        ok = ok && kt->dact[v];
+    }
+    return ok;
+}
+
+static void kink_free(kink_tmp* kt)
+{
+    for (int v = 0; v < 3; ++v) {
+        for (int l = 0; l < LPO_MAX_LAYERS; ++l) { free(kt->W[v][l]); free(kt->b[v][l]); }
+        free(kt->dact[v]);
+    }
+}
+
 /* d_grid, dW, db are ACCUMULATED into (the caller zeroes them).
-   relu_c = 0 is the definition (ReLU' = 1 iff z > 0).  A non-zero relu_c moves the threshold
-   to relu_c * (|b| + sum_k |W_k x_k|), a multiple of the unit's rounding-error scale: calling
-   with +c and -c brackets every gradient a finite-precision evaluation may legitimately
-   produce when a pre-activation lies within rounding of the kink (either one-sided
-   derivative is then a correct answer).  The forward is never affected. */
+   side = 0 is the definition (ReLU' = 1 iff z > 0; band is ignored).
+   side = +1 / -1 returns the upper / lower ENVELOPE of the gradients over the choices a
+   finite-precision evaluation may legitimately make where a hidden pre-activation z lies
+   within band * (|b| + sum_k |W_k x_k|) of the kink (there either one-sided derivative is
+   a correct answer): every on/off combination of a sample's banded units (at most
+   LPO_MAX_KINKS of them) is evaluated; samples are independent, so per-sample envelopes
+   add.  The forward is never affected. */
 int lpo_render_bwd(const lpo_grid* g, const lpo_mlp* m, const lpo_rays* rays, const double bg[3],
                    const double* p_rgb, const double* p_alpha, const double* p_depth,
-                   double* const d_grid[3], double* const dW[], double* const db[], double relu_c)
+                   double* const d_grid[3], double* const dW[], double* const db[], double band,
+                   int side)
 {
     if (check_args(g, m, rays)) return 1;
+    if (side != 0 && !(band > 0.0)) return 1;
     const int nact = mlp_act_total(m);
     const int nl = m->n_layers;
     int fail = 0;
 #pragma omp parallel
     {
         ray_tape r;
+        kink_tmp kt;
         double* scratch = (double*)malloc(sizeof(double) * (size_t)(rays->S + 1 + nact));
         double* tW[LPO_MAX_LAYERS];
         double* tb[LPO_MAX_LAYERS];
         int ok = tape_alloc(&r, rays->S, nact, g->C) && scratch;
+        ok = kink_alloc(&kt, m, nact) && ok;
         for (int l = 0; l < nl; ++l) {
             tW[l] = (double*)calloc((size_t)m->dims[l] * m->dims[l + 1], sizeof(double));
             tb[l] = (double*)calloc((size_t)m->dims[l + 1], sizeof(double));
@@ -415,7 +534,8 @@ int lpo_render_bwd(const lpo_grid* g, const lpo_mlp* m, const lpo_rays* rays, co
                 double rgb[3], alpha, depth;
                 ray_forward(g, m, rays, i, bg, &r, rgb, &alpha, &depth);
                 ray_backward(g, m, rays, i, bg, &r, p_rgb + 3 * i, p_alpha ? p_alpha[i] : 0.0,
-                             p_depth ? p_depth[i] : 0.0, d_grid, tW, tb, scratch, NULL, NULL, relu_c);
+                             p_depth ? p_depth[i] : 0.0, d_grid, tW, tb, scratch, NULL, NULL, band,
+                             side, &kt);
             }
 #pragma omp critical
             {
@@ -428,6 +548,7 @@ int lpo_render_bwd(const lpo_grid* g, const lpo_mlp* m, const lpo_rays* rays, co
         }
         for (int l = 0; l < nl; ++l) { free(tW[l]); free(tb[l]); }
         free(scratch);
+        kink_free(&kt);
         tape_free(&r);
     }
     return fail ? 2 : 0;
@@ -479,7 +600,7 @@ int lpo_ray_trace(const lpo_grid* g, const lpo_mlp* m, const lpo_rays* rays, con
         }
         if (ok)
             ray_backward(g, m, rays, ray, bg, &r, p_rgb, p_alpha, p_depth, dg, tW, tb, scratch,
-                         dsigma, dcol, 0.0);
+                         dsigma, dcol, 0.0, 0, NULL);
         else rc = 2;
         for (int p = 0; p < 3; ++p) free(dg[p]);
         for (int l = 0; l < nl; ++l) { free(tW[l]); free(tb[l]); }

@@ -18,12 +18,12 @@ INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "liblightplane.so")
 
-SOURCES = ["lp_api.hip", "lp_generic.hip", "lp_mfma_fwd.hip"]
+SOURCES = ["lp_api.hip", "lp_generic.hip", "lp_mfma_fwd.hip", "lp_mfma_bwd.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-munsafe-fp-atomics",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-fgpu-rdc" if False else "-fno-gpu-rdc",
+    "-fno-gpu-rdc",
     "-I", INCLUDE, "-I", CSRC, "-Wall", "-Wno-unused-function",
 ]
 

@@ -219,7 +219,8 @@ lp_status lp_bwd_workspace_bytes(const lp_grid* grid, const lp_mlp* mlp, const l
     std::string err;
     int n_cu = 0;
     if (compute_units(&n_cu, &err)) return fail(LP_ERR_HIP, err);
-    const int records = path == Path::Mfma ? lp::mfma_bwd_records(n_cu) : generic_bwd_blocks(n_cu);
+    const bool fast_bwd = path == Path::Mfma && lp::mfma_bwd_records(n_cu) > 0;
+    const int records = fast_bwd ? lp::mfma_bwd_records(n_cu) : generic_bwd_blocks(n_cu);
     *bytes = sizeof(float) * (size_t)records * (size_t)ws_stride(m);
     return LP_OK;
 }
@@ -250,7 +251,8 @@ lp_status lp_render_bwd(const lp_grid* grid, const lp_mlp* mlp, const lp_rays* r
     std::string err;
     int n_cu = 0;
     if (compute_units(&n_cu, &err)) return fail(LP_ERR_HIP, err);
-    const int max_records = path == Path::Mfma ? lp::mfma_bwd_records(n_cu) : generic_bwd_blocks(n_cu);
+    const bool fast_bwd = path == Path::Mfma && lp::mfma_bwd_records(n_cu) > 0;
+    const int max_records = fast_bwd ? lp::mfma_bwd_records(n_cu) : generic_bwd_blocks(n_cu);
     const size_t need = sizeof(float) * (size_t)max_records * (size_t)ws_stride(m);
     if (!workspace || workspace_bytes < need)
         return fail(LP_ERR_WORKSPACE, "workspace is NULL or smaller than lp_bwd_workspace_bytes()");
@@ -266,7 +268,7 @@ lp_status lp_render_bwd(const lp_grid* grid, const lp_mlp* mlp, const lp_rays* r
     io.ws_stride = ws_stride(m);
     hipStream_t s = (hipStream_t)stream;
 
-    if (path == Path::Mfma) {
+    if (fast_bwd) {
         hipError_t e = lp::launch_bwd_mfma(g, m, r, io, n_cu, s);
         if (e != hipSuccess) return hip_fail("backward matrix-core kernel launch", e);
         return LP_OK;

@@ -1,0 +1,255 @@
+// Building blocks of the matrix-core (MFMA) kernels for gfx950.
+//
+// One wavefront marches one ray in chunks of 64 consecutive samples.  The decoder MLP of a
+// chunk is a dense contraction [out x in] x [in x 64 samples], evaluated transposed
+// (D = W * X, samples along the N axis) with v_mfma_f32_32x32x16_bf16 so that a layer's
+// output registers are, without any data movement, the next layer's B operand:
+//
+//   operand layout of the instruction (A is M x K, B is K x N, D is M x N, M = N = 32, K = 16):
+//     lane l = 32 g + i holds A[i][8g .. 8g+7], B[8g .. 8g+7][i], and D[8q + 4g + p][i] in
+//     register r = 4q + p (q, p = 0..3).
+//
+//   Registers 8h .. 8h+7 (h = 0, 1) of a D block, taken as the 8 B-operand elements of one
+//   K-step, therefore stand for the rows  8 (e / 4) + 16 h + 4 g + (e % 4),  e = 0..7, of that
+//   block.  The A operands (weights) are staged in LDS with their K index permuted the same
+//   way, so the contraction is unchanged.
+//
+// fp32 operands are split into bf16 hi + lo (x = hi + lo + O(2^-18 |x|)); each product is
+// evaluated as lo*hi + hi*lo + hi*hi with fp32 accumulation inside the matrix core.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "lp_device.h"
+
+namespace lp {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+
+struct Frag {  // one MFMA A or B operand: 8 bf16 = 4 dwords
+    uint32_t d[4];
+};
+
+__device__ __forceinline__ bf16x8 as_bf16x8(const Frag& f)
+{
+    return __builtin_bit_cast(bf16x8, f);
+}
+
+// hi = bf16(x) (round to nearest even), lo = bf16(x - hi); two values per dword.
+__device__ __forceinline__ void split2(float x0, float x1, uint32_t& hi, uint32_t& lo)
+{
+    bf16x2 h;
+    h[0] = (__bf16)x0;
+    h[1] = (__bf16)x1;
+    const uint32_t hb = __builtin_bit_cast(uint32_t, h);
+    const float f0 = __uint_as_float(hb << 16);
+    const float f1 = __uint_as_float(hb & 0xffff0000u);
+    bf16x2 l;
+    l[0] = (__bf16)(x0 - f0);
+    l[1] = (__bf16)(x1 - f1);
+    hi = hb;
+    lo = __builtin_bit_cast(uint32_t, l);
+}
+
+__device__ __forceinline__ void split8(const float* x, Frag& hi, Frag& lo)
+{
+#pragma unroll
+    for (int i = 0; i < 4; ++i) split2(x[2 * i], x[2 * i + 1], hi.d[i], lo.d[i]);
+}
+
+// acc += (a_hi + a_lo) * (b_hi + b_lo) without the lo*lo term; small terms first.
+__device__ __forceinline__ f32x16 mfma3(const Frag& ah, const Frag& al, const Frag& bh, const Frag& bl,
+                                        f32x16 acc)
+{
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(al), as_bf16x8(bh), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ah), as_bf16x8(bl), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ah), as_bf16x8(bh), acc, 0, 0, 0);
+    return acc;
+}
+
+// Row of a 32-row D block that register r of lane-group g holds.
+__host__ __device__ constexpr int d_row(int r, int g) { return 8 * (r / 4) + 4 * g + (r % 4); }
+
+// Input feature that element e of lane-group g stands for in K-step s, when the B operand is
+// taken from the D registers of the previous layer (blocks of 32 rows, two K-steps per block).
+__host__ __device__ constexpr int k_hidden(int s, int g, int e)
+{
+    return 32 * (s / 2) + 16 * (s % 2) + 8 * (e / 4) + 4 * g + (e % 4);
+}
+
+// Input channel for the first layer: lane-group g holds the contiguous half [g C/2, (g+1) C/2).
+template <int C>
+__host__ __device__ constexpr int k_input(int s, int g, int e)
+{
+    return g * (C / 2) + 8 * s + e;
+}
+
+// Stages one weight matrix as MFMA A operands: for block (mb, s) 64 lanes x 8 bf16 of the hi
+// parts (1 KiB) followed by the lo parts.  row_of(mb, i) gives the source row of the weight
+// matrix for output row i of block mb (negative: zero row); col_of(s, g, e) the source column.
+template <class RowFn, class ColFn>
+__device__ __forceinline__ void stage_operand(uint4* dst, const float* __restrict__ W, int n_mb, int n_ks,
+                                              int ld, RowFn row_of, ColFn col_of)
+{
+    __bf16* out = reinterpret_cast<__bf16*>(dst);
+    const int total = n_mb * n_ks * 512;
+    for (int idx = threadIdx.x; idx < total; idx += blockDim.x) {
+        const int e = idx & 7, lane = (idx >> 3) & 63, blk = idx >> 9;
+        const int s = blk % n_ks, mb = blk / n_ks;
+        const int r = row_of(mb, lane & 31);
+        const int c = col_of(s, lane >> 5, e);
+        const float v = r >= 0 ? W[(size_t)r * ld + c] : 0.0f;
+        const __bf16 h = (__bf16)v;
+        const __bf16 l = (__bf16)(v - (float)h);
+        out[(size_t)blk * 1024 + lane * 8 + e] = h;
+        out[(size_t)blk * 1024 + 512 + lane * 8 + e] = l;
+    }
+}
+
+__device__ __forceinline__ void load_operand(const uint4* blk, int lane, Frag& hi, Frag& lo)
+{
+    const uint4 h = blk[lane];
+    const uint4 l = blk[64 + lane];
+    hi.d[0] = h.x; hi.d[1] = h.y; hi.d[2] = h.z; hi.d[3] = h.w;
+    lo.d[0] = l.x; lo.d[1] = l.y; lo.d[2] = l.z; lo.d[3] = l.w;
+}
+
+// Inclusive prefix sum over the 64 lanes of a wave.
+__device__ __forceinline__ float wave_scan_incl(float v, int lane)
+{
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const float u = __shfl_up(v, d, 64);
+        if (lane >= d) v += u;
+    }
+    return v;
+}
+
+// Inclusive suffix sum (lane l gets the sum over lanes l..63).
+__device__ __forceinline__ float wave_scan_suffix(float v, int lane)
+{
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const float u = __shfl_down(v, d, 64);
+        if (lane + d < 64) v += u;
+    }
+    return v;
+}
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) v += __shfl_xor(v, d, 64);
+    return v;
+}
+
+// 1 - exp(-x) for x >= 0 without cancellation for small x.
+__device__ __forceinline__ float one_minus_exp_neg(float x)
+{
+    const float series = x * (1.0f - 0.5f * x * (1.0f - (1.0f / 3.0f) * x * (1.0f - 0.25f * x)));
+    const float direct = 1.0f - __expf(-x);
+    return x < 0.03f ? series : direct;
+}
+
+__device__ __forceinline__ float fast_softplus(float z)
+{
+    return fmaxf(z, 0.0f) + __logf(1.0f + __expf(-fabsf(z)));
+}
+
+__device__ __forceinline__ float fast_logistic(float z)
+{
+    return __frcp_rn(1.0f + __expf(-z));
+}
+
+// ---- sampling of the hash structure (Section 3.2) for one lane's half of the channels ----
+
+struct Cell3 {
+    int i[3];
+    float f[3];
+};
+
+__device__ __forceinline__ Cell3 locate3(const GridDev& g, float x, float y, float z)
+{
+    Cell3 c;
+    axis_cell(x, g.amin[0], g.scale[0], g.N[0], c.i[0], c.f[0]);
+    axis_cell(y, g.amin[1], g.scale[1], g.N[1], c.i[1], c.f[1]);
+    axis_cell(z, g.amin[2], g.scale[2], g.N[2], c.i[2], c.f[2]);
+    return c;
+}
+
+template <int NCH>  // NCH consecutive channels starting at ch0
+__device__ __forceinline__ void accum_corner(const float* __restrict__ p, float w, float* feat)
+{
+    const float4* q = reinterpret_cast<const float4*>(p);
+#pragma unroll
+    for (int i = 0; i < NCH / 4; ++i) {
+        const float4 v = q[i];
+        feat[4 * i + 0] += w * v.x;
+        feat[4 * i + 1] += w * v.y;
+        feat[4 * i + 2] += w * v.z;
+        feat[4 * i + 3] += w * v.w;
+    }
+}
+
+// feat[0..NCH) = channels [ch0, ch0 + NCH) of h(x) in scene `scene`.
+template <int KIND, int C, int NCH>
+__device__ __forceinline__ void gather_half(const GridDev& g, int scene, const Cell3& c, int ch0, float* feat)
+{
+#pragma unroll
+    for (int k = 0; k < NCH; ++k) feat[k] = 0.0f;
+    if constexpr (KIND == LP_GRID_VOXEL) {
+        const float* V = g.data[0] + (size_t)scene * g.N[0] * g.N[1] * g.N[2] * C;
+        const unsigned sz = C, sy = (unsigned)g.N[2] * C, sx = (unsigned)g.N[1] * sy;
+        const unsigned base = (unsigned)c.i[0] * sx + (unsigned)c.i[1] * sy + (unsigned)c.i[2] * sz + ch0;
+#pragma unroll
+        for (int d = 0; d < 8; ++d) {
+            const int dx = d >> 2, dy = (d >> 1) & 1, dz = d & 1;
+            const float w = (dx ? c.f[0] : 1.0f - c.f[0]) * (dy ? c.f[1] : 1.0f - c.f[1]) *
+                            (dz ? c.f[2] : 1.0f - c.f[2]);
+            accum_corner<NCH>(V + (base + dx * sx + dy * sy + dz * sz), w, feat);
+        }
+    } else {
+#pragma unroll
+        for (int p = 0; p < 3; ++p) {
+            const int a = p, b = (p + 1) % 3;
+            const float* P = g.data[p] + (size_t)scene * g.N[a] * g.N[b] * C;
+            const unsigned sb = C, sa = (unsigned)g.N[b] * C;
+            const unsigned base = (unsigned)c.i[a] * sa + (unsigned)c.i[b] * sb + ch0;
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                const int da = d >> 1, db = d & 1;
+                const float w = (da ? c.f[a] : 1.0f - c.f[a]) * (db ? c.f[b] : 1.0f - c.f[b]);
+                accum_corner<NCH>(P + (base + da * sa + db * sb), w, feat);
+            }
+        }
+    }
+}
+
+// Ranges of rays per XCD: workgroup b runs on XCD b % 8, so giving XCD x the contiguous ray
+// range x keeps neighbouring rays (which read neighbouring texels) behind one L2.
+struct RaySchedule {
+    long long first;   // first ray of this wave
+    long long end;     // end of this XCD's range
+    long long stride;  // rays between consecutive iterations of this wave
+};
+
+__device__ __forceinline__ RaySchedule ray_schedule(long long M, int waves_per_block)
+{
+    constexpr int kXcd = 8;
+    const int xcd = blockIdx.x % kXcd;
+    const int local_block = blockIdx.x / kXcd;
+    const int blocks_per_xcd = gridDim.x / kXcd;  // gridDim.x is a multiple of 8
+    const long long per_xcd = (M + kXcd - 1) / kXcd;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    RaySchedule s;
+    const long long begin = per_xcd * xcd;
+    s.end = begin + per_xcd < M ? begin + per_xcd : M;
+    s.first = begin + (long long)local_block * waves_per_block + wave;
+    s.stride = (long long)blocks_per_xcd * waves_per_block;
+    return s;
+}
+
+}  // namespace lp

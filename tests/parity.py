@@ -26,14 +26,23 @@ def close(gpu: np.ndarray, ref: np.ndarray, rtol: float, what: str):
     return float(err.max() / max(rms, 1e-300))
 
 
-RELU_C = {0: 2e-5, 1: 2e-6, 2: 2e-5}   # kink band per math mode (default, generic fp32, bf16x3)
+# Kink band, as a multiple of each hidden unit's rounding-error scale |b| + sum_k |W_k x_k|.
+# In fp32 the dominant error of a pre-activation is not the contraction but the sample
+# position: the continuous texel index u (up to N-1, i.e. hundreds) has a spacing of about
+# 1e-5 in fp32, so the interpolation fraction, and with it every feature of a noise-like grid,
+# carries a relative error of about 1e-5 whatever kernel evaluates it.  That puts roughly
+# 2e-6 of the unit's scale on a pre-activation (1 sigma, 128^3-256^3 grids); the band is some
+# ten sigma, so no sign decision an fp32 evaluation can take falls outside it.
+KINK_BAND = 2e-5
 
 
 def close_envelope(gpu, ref, lo, hi, rtol: float, what: str):
-    """Like close(), for gradients when some ReLU pre-activations lie within rounding of
-    zero: there either one-sided derivative is a correct answer, and `lo`/`hi` are the
-    elementwise envelope of the oracle's gradients over both choices.  Outside such samples
-    lo == hi == ref and this is exactly close()."""
+    """Gradient check.  Where a hidden pre-activation lies within rounding of the ReLU kink,
+    either one-sided derivative is a correct answer; `lo`/`hi` are the elementwise envelope
+    of the oracle's gradients over those choices (lo == hi == ref for elements no such sample
+    touches).  EVERY element must lie within tolerance of the envelope; the fraction of
+    elements outside the strict tolerance around `ref` itself is returned for the caller to
+    bound.  Returns (max envelope error / rms, strict failure fraction)."""
     gpu = np.asarray(gpu, dtype=np.float64)
     assert gpu.shape == ref.shape, (what, gpu.shape, ref.shape)
     assert np.isfinite(gpu).all(), f"{what}: non-finite values from the GPU"
@@ -46,8 +55,8 @@ def close_envelope(gpu, ref, lo, hi, rtol: float, what: str):
             f"{what}: {int((err > bound).sum())} of {ref.size} elements out of tolerance {rtol:g}; "
             f"worst at flat index {k}: gpu={gpu.reshape(-1)[k]!r} ref={ref.reshape(-1)[k]!r} "
             f"envelope=[{lo.reshape(-1)[k]!r}, {hi.reshape(-1)[k]!r}] rms(ref)={rms:g}")
-    widened = float(((hi - lo) > bound).mean()) if ref.size else 0.0
-    return float(err.max() / max(rms, 1e-300)), widened
+    strict_fail = float((np.abs(gpu - ref) > bound).mean()) if ref.size else 0.0
+    return float(err.max() / max(rms, 1e-300)), strict_fail
 
 
 def mse_upstream(rgb64: np.ndarray, target: np.ndarray, scene=None, n_scenes: int = 1) -> np.ndarray:
@@ -75,7 +84,7 @@ def run_gpu(lp, inp, p_rgb, p_alpha=None, p_depth=None, math_mode=0, device="cud
                 d_grid=[cpu(t) for t in d_grid], dW=[cpu(t) for t in dW], db=[cpu(t) for t in db])
 
 
-def check_case(lp, oracle, inp, math_mode=0, aux_grads=True, seed=0, label=""):
+def check_case(lp, oracle, inp, math_mode=0, aux_grads=True, seed=0, label="", max_strict_fail=0.5):
     """Full parity of one problem: forward outputs and every gradient tensor."""
     import lp_inputs
     prob = oracle.Problem(inp)
@@ -85,11 +94,10 @@ def check_case(lp, oracle, inp, math_mode=0, aux_grads=True, seed=0, label=""):
     if aux_grads:
         p_alpha, p_depth = lp_inputs.upstream_grads(inp.n_rays, 77 + seed)
     o_dg, o_dW, o_db = oracle.render_bwd(prob, p_rgb, p_alpha, p_depth)
-    c = RELU_C[math_mode]
-    plus = oracle.render_bwd(prob, p_rgb, p_alpha, p_depth, relu_c=c)
-    minus = oracle.render_bwd(prob, p_rgb, p_alpha, p_depth, relu_c=-c)
-    env = lambda i, j: (np.minimum(np.minimum(plus[i][j], minus[i][j]), (o_dg, o_dW, o_db)[i][j]),
-                        np.maximum(np.maximum(plus[i][j], minus[i][j]), (o_dg, o_dW, o_db)[i][j]))
+    c = KINK_BAND
+    upper = oracle.render_bwd(prob, p_rgb, p_alpha, p_depth, kink_band=c, kink_side=+1)
+    lower = oracle.render_bwd(prob, p_rgb, p_alpha, p_depth, kink_band=c, kink_side=-1)
+    env = lambda i, j: (lower[i][j], upper[i][j])
     g = run_gpu(lp, inp, p_rgb, p_alpha, p_depth, math_mode)
     worst = {}
     worst["rgb"] = close(g["rgb"], o_rgb, FWD_RTOL, f"{label} rgb")
@@ -101,8 +109,11 @@ def check_case(lp, oracle, inp, math_mode=0, aux_grads=True, seed=0, label=""):
         worst[f"dW{l}"] = close_envelope(a, b, *env(1, l), BWD_RTOL, f"{label} dW[{l}]")
     for l, (a, b) in enumerate(zip(g["db"], o_db)):
         worst[f"db{l}"] = close_envelope(a, b, *env(2, l), BWD_RTOL, f"{label} db[{l}]")
-    # the envelope must stay tight almost everywhere, or the comparison loses its force
+    # besides the envelope, all but a small fraction of the elements must meet the plain
+    # tolerance around the definition's gradient (tiny problems: one kink sample can touch a
+    # whole small tensor, hence the loose default; the configurations use 1 %)
     for k, v in worst.items():
         if isinstance(v, tuple):
-            assert v[1] < 0.05, f"{label} {k}: kink envelope widened on {v[1]:.1%} of the elements"
+            assert v[1] <= max_strict_fail, (f"{label} {k}: {v[1]:.2%} of the elements miss the plain "
+                                             f"tolerance (allowed {max_strict_fail:.2%})")
     return worst
