@@ -82,8 +82,8 @@ void to_device_views(const lp_grid* grid, const lp_mlp* mlp, const lp_rays* rays
     g->N[0] = grid->NX; g->N[1] = grid->NY; g->N[2] = grid->NZ;
     for (int p = 0; p < 3; ++p) g->data[p] = grid->data[p];
     for (int a = 0; a < 3; ++a) {
-        g->amin[a] = grid->aabb_min[a];
-        g->scale[a] = (float)((double)(g->N[a] - 1) / ((double)grid->aabb_max[a] - (double)grid->aabb_min[a]));
+        g->amin[a] = (double)grid->aabb_min[a];
+        g->scale[a] = (double)(g->N[a] - 1) / ((double)grid->aabb_max[a] - (double)grid->aabb_min[a]);
     }
     std::memset(m, 0, sizeof(*m));
     m->n_layers = mlp->n_layers;

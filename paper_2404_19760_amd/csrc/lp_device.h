@@ -13,8 +13,8 @@ struct GridDev {
     const float* data[3];
     int kind, B, C;
     int N[3];
-    float amin[3];
-    float scale[3];  // (N-1)/(max-min): world -> continuous index
+    double amin[3];
+    double scale[3];  // (N-1)/(max-min): world -> continuous index
 };
 
 struct MlpDev {
@@ -61,15 +61,17 @@ struct BwdIo {
 };
 
 // Continuous index along one axis, clamped to the box; cell index in [0, N-2] and the
-// fraction inside the cell in [0, 1].
-__device__ __forceinline__ void axis_cell(float x, float lo, float scale, int N, int& i, float& f)
+// fraction inside the cell in [0, 1].  The index is formed in fp64 (full rate on this chip):
+// in fp32 an index of a few hundred has a spacing of 1e-5 and more, which would put a relative
+// error of up to 1e-4 on every interpolated feature of a fine grid.
+__device__ __forceinline__ void axis_cell(double x, double lo, double scale, int N, int& i, float& f)
 {
-    float u = (x - lo) * scale;
-    u = fminf(fmaxf(u, 0.0f), (float)(N - 1));
+    double u = (x - lo) * scale;
+    u = fmin(fmax(u, 0.0), (double)(N - 1));
     int c = (int)u;  // u >= 0: truncation is floor
     c = min(c, N - 2);
     i = c;
-    f = u - (float)c;
+    f = (float)(u - (double)c);
 }
 
 // softplus(z) = max(z,0) + log1p(exp(-|z|)); its derivative is the logistic function.

@@ -29,7 +29,7 @@ struct Cell {
     float f[3];
 };
 
-__device__ __forceinline__ Cell locate(const GridDev& g, float x, float y, float z)
+__device__ __forceinline__ Cell locate(const GridDev& g, double x, double y, double z)
 {
     Cell c;
     axis_cell(x, g.amin[0], g.scale[0], g.N[0], c.i[0], c.f[0]);
@@ -125,8 +125,17 @@ __device__ void mlp_forward(const MlpDev& m, const float* sW, float* acts, int l
 
 struct RayRegs {
     float o[3], d[3], near, delta;
+    double delta64;
     int scene;
 };
+
+// cell of sample j: position in fp64 from the fp32 ray
+__device__ __forceinline__ Cell sample_cell(const GridDev& g, const RayRegs& q, int j)
+{
+    const double t = (double)q.near + ((double)j + 0.5) * q.delta64;
+    return locate(g, (double)q.o[0] + t * (double)q.d[0], (double)q.o[1] + t * (double)q.d[1],
+                  (double)q.o[2] + t * (double)q.d[2]);
+}
 
 __device__ __forceinline__ RayRegs load_ray(const RaysDev& r, long long ray)
 {
@@ -136,7 +145,8 @@ __device__ __forceinline__ RayRegs load_ray(const RaysDev& r, long long ray)
         q.d[a] = r.dirs[3 * ray + a];
     }
     q.near = r.near[ray];
-    q.delta = (r.far[ray] - q.near) / (float)r.S;
+    q.delta64 = ((double)r.far[ray] - (double)q.near) / (double)r.S;
+    q.delta = (float)q.delta64;
     q.scene = r.scene ? r.scene[ray] : 0;
     return q;
 }
@@ -162,7 +172,7 @@ __global__ __launch_bounds__(kLanes) void fwd_generic_kernel(GridDev g, MlpDev m
     float T = 1.0f, tau = 0.0f, rgb[3] = {0.0f, 0.0f, 0.0f}, depth = 0.0f;
     for (int j = 0; j < rays.S; ++j) {
         const float t = q.near + ((float)j + 0.5f) * q.delta;
-        const Cell c = locate(g, q.o[0] + t * q.d[0], q.o[1] + t * q.d[1], q.o[2] + t * q.d[2]);
+        const Cell c = sample_cell(g, q, j);
         gather_feat(g, q.scene, c, acts, lane);
         mlp_forward(m, sW, acts, lane);
         const float sigma = softplus_f(acts[(out_off + 0) * kLanes + lane]);
@@ -225,7 +235,7 @@ __global__ __launch_bounds__(kLanes) void bwd_generic_kernel(GridDev g, MlpDev m
 
         for (int j = rays.S - 1; j >= 0; --j) {
             const float t = q.near + ((float)j + 0.5f) * q.delta;
-            const Cell c = locate(g, q.o[0] + t * q.d[0], q.o[1] + t * q.d[1], q.o[2] + t * q.d[2]);
+            const Cell c = sample_cell(g, q, j);
             gather_feat(g, q.scene, c, acts, lane);
             mlp_forward(m, sW, acts, lane);
             const float z0 = acts[(out_off + 0) * kLanes + lane];

@@ -109,6 +109,27 @@ __device__ __forceinline__ void stage_operand(uint4* dst, const float* __restric
     }
 }
 
+// Same for the TRANSPOSED matrix: A[m][k] = W[k][m].  row_of(mb, i) gives the source COLUMN of W
+// for output row i of block mb, col_of(s, g, e) the source ROW; a negative index gives zero.
+template <class RowFn, class ColFn>
+__device__ __forceinline__ void stage_operand_t(uint4* dst, const float* __restrict__ W, int n_mb, int n_ks,
+                                                int ld, RowFn row_of, ColFn col_of)
+{
+    __bf16* out = reinterpret_cast<__bf16*>(dst);
+    const int total = n_mb * n_ks * 512;
+    for (int idx = threadIdx.x; idx < total; idx += blockDim.x) {
+        const int e = idx & 7, lane = (idx >> 3) & 63, blk = idx >> 9;
+        const int s = blk % n_ks, mb = blk / n_ks;
+        const int c = row_of(mb, lane & 31);
+        const int r = col_of(s, lane >> 5, e);
+        const float v = (r >= 0 && c >= 0) ? W[(size_t)r * ld + c] : 0.0f;
+        const __bf16 h = (__bf16)v;
+        const __bf16 l = (__bf16)(v - (float)h);
+        out[(size_t)blk * 1024 + lane * 8 + e] = h;
+        out[(size_t)blk * 1024 + 512 + lane * 8 + e] = l;
+    }
+}
+
 __device__ __forceinline__ void load_operand(const uint4* blk, int lane, Frag& hi, Frag& lo)
 {
     const uint4 h = blk[lane];
@@ -171,7 +192,7 @@ struct Cell3 {
     float f[3];
 };
 
-__device__ __forceinline__ Cell3 locate3(const GridDev& g, float x, float y, float z)
+__device__ __forceinline__ Cell3 locate3(const GridDev& g, double x, double y, double z)
 {
     Cell3 c;
     axis_cell(x, g.amin[0], g.scale[0], g.N[0], c.i[0], c.f[0]);

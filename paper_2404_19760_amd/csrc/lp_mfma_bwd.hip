@@ -1,6 +1,433 @@
-// placeholder until the matrix-core backward lands
+// Matrix-core backward kernel of the Renderer (Eq. (2), Section 3.4 of the paper).
+//
+// Same mapping as the forward: a wavefront marches one ray, 64 samples per step, but from the
+// LAST step to the first.  Per step it
+//   1. recomputes sampling + MLP forward (nothing was stored but one scalar per ray),
+//   2. rebuilds the transmittance from the cached optical depth (tau_{q-1} = tau_q - sigma_q Delta,
+//      T = exp(-tau): the paper's T_{q-1} = T_q exp(Delta sigma_q) in the log domain) and evaluates
+//      Eq. (2) with a wave-level suffix scan of w_j a_j plus the carry of later steps,
+//   3. back-propagates through the MLP on the matrix cores: input gradients with the transposed
+//      weights (dX = W^T dZ, chained in registers like the forward), weight gradients as
+//      dW = dZ X^T contracted over the 64 samples, for which dZ and X are transposed through a
+//      per-wave LDS tile (bf16 hi/lo planes, 16-bit stores, 128-bit operand loads),
+//   4. scatters the feature gradient into the grid gradient with the interpolation weights
+//      (hardware fp32 atomics).
+// Weight / bias gradients stay in registers for the whole kernel; each wave writes one record
+// of partial sums at the end and a second kernel adds the records in a fixed order.
 #include "lp_kernels.h"
+#include "lp_mfma.h"
+#include "lp_mfma_mlp.h"
+
 namespace lp {
-int mfma_bwd_records(int n_cu) { return 0 * n_cu; }
-hipError_t launch_bwd_mfma(const GridDev&, const MlpDev&, const RaysDev&, const BwdIo&, int, hipStream_t) { return hipErrorNotSupported; }
+
+namespace {
+
+constexpr int kWaves = 4;
+
+__device__ __forceinline__ void wave_lds_fence()
+{
+    // LDS operations of one wave execute in order; this only pins the compiler's ordering of
+    // the tile stores of some lanes against the tile loads of others
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
+
+template <int RS>
+struct Tile {
+    uint16_t* hi;
+    uint16_t* lo;
+
+    // operand fragments [2 N-blocks][KS] whose element e of lane-group g is row row_of(s, g, e)
+    // of sample column (lane & 31) + 32 nb  ->  tile[row][sample]
+    template <int KS, class RowFn>
+    __device__ __forceinline__ void store(const Frag (&fh)[2][KS], const Frag (&fl)[2][KS], int lane, RowFn row_of) const
+    {
+        const int col = lane & 31, grp = lane >> 5;
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+            for (int s = 0; s < KS; ++s)
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    const int o0 = row_of(s, grp, 2 * d) * RS + col + 32 * nb;
+                    const int o1 = row_of(s, grp, 2 * d + 1) * RS + col + 32 * nb;
+                    hi[o0] = (uint16_t)fh[nb][s].d[d];
+                    hi[o1] = (uint16_t)(fh[nb][s].d[d] >> 16);
+                    lo[o0] = (uint16_t)fl[nb][s].d[d];
+                    lo[o1] = (uint16_t)(fl[nb][s].d[d] >> 16);
+                }
+    }
+
+    // MFMA operand with the 64 samples on the K axis: 8 consecutive samples of `row`
+    __device__ __forceinline__ void load(int row, int s, int grp, bool live, Frag& fh, Frag& fl) const
+    {
+        const uint4 h = *reinterpret_cast<const uint4*>(hi + row * RS + 16 * s + 8 * grp);
+        const uint4 l = *reinterpret_cast<const uint4*>(lo + row * RS + 16 * s + 8 * grp);
+        fh.d[0] = live ? h.x : 0u; fh.d[1] = live ? h.y : 0u; fh.d[2] = live ? h.z : 0u; fh.d[3] = live ? h.w : 0u;
+        fl.d[0] = live ? l.x : 0u; fl.d[1] = live ? l.y : 0u; fl.d[2] = live ? l.z : 0u; fl.d[3] = live ? l.w : 0u;
+    }
+};
+
+// sum of the 8 bf16 values of a fragment, added to acc
+__device__ __forceinline__ float frag_sum(const Frag& f, float acc)
+{
+    bf16x2 one;
+    one[0] = (__bf16)1.0f;
+    one[1] = (__bf16)1.0f;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, f.d[d]), one, acc, false);
+    return acc;
+}
+
+// d_grid[corner][channels] += weight * vals for this lane's C/2 channels (rows 8q + 4g + p of
+// the feature-gradient block): the transpose of gather_half with the same corners and weights
+template <int KIND, int C>
+__device__ __forceinline__ void scatter_half(const GridDev& g, float* const d_grid[3], int scene, const Cell3& c,
+                                             int grp, const float* vals)
+{
+    auto add_corner = [&](float* p, float w) {
+#pragma unroll
+        for (int q = 0; q < C / 8; ++q)
+#pragma unroll
+            for (int pp = 0; pp < 4; ++pp) atomicAdd(p + 8 * q + 4 * grp + pp, w * vals[4 * q + pp]);
+    };
+    if constexpr (KIND == LP_GRID_VOXEL) {
+        float* V = d_grid[0] + (size_t)scene * g.N[0] * g.N[1] * g.N[2] * C;
+        const unsigned sz = C, sy = (unsigned)g.N[2] * C, sx = (unsigned)g.N[1] * sy;
+        const unsigned base = (unsigned)c.i[0] * sx + (unsigned)c.i[1] * sy + (unsigned)c.i[2] * sz;
+#pragma unroll
+        for (int d = 0; d < 8; ++d) {
+            const int dx = d >> 2, dy = (d >> 1) & 1, dz = d & 1;
+            const float w = (dx ? c.f[0] : 1.0f - c.f[0]) * (dy ? c.f[1] : 1.0f - c.f[1]) *
+                            (dz ? c.f[2] : 1.0f - c.f[2]);
+            add_corner(V + (base + dx * sx + dy * sy + dz * sz), w);
+        }
+    } else {
+#pragma unroll
+        for (int p = 0; p < 3; ++p) {
+            const int a = p, b = (p + 1) % 3;
+            float* P = d_grid[p] + (size_t)scene * g.N[a] * g.N[b] * C;
+            const unsigned sb = C, sa = (unsigned)g.N[b] * C;
+            const unsigned base = (unsigned)c.i[a] * sa + (unsigned)c.i[b] * sb;
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                const int da = d >> 1, db = d & 1;
+                const float w = (da ? c.f[a] : 1.0f - c.f[a]) * (db ? c.f[b] : 1.0f - c.f[b]);
+                add_corner(P + (base + da * sa + db * sb), w);
+            }
+        }
+    }
+}
+
+// zeroes the entries of a D block whose ReLU output (hi part of the stored activation) is zero
+template <int MB>
+__device__ __forceinline__ void relu_mask(f32x16 (&acc)[MB][2], const Frag (&act_hi)[2][2 * MB])
+{
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int s = 2 * mb + r / 8, e = r % 8;
+                const uint32_t bits = (act_hi[nb][s].d[e / 2] >> (16 * (e & 1))) & 0xffffu;
+                acc[mb][nb][r] = bits ? acc[mb][nb][r] : 0.0f;
+            }
+}
+
+template <int KIND, int C, int H, int NH>
+__global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev m, RaysDev rays, BwdIo io)
+{
+    using L = MlpLds<C, H, NH, true>;
+    constexpr int MB = L::MB, KS1 = L::KS1, KSH = L::KSH, RS = L::TILE_RS;
+    extern __shared__ uint4 lds[];
+    stage_mlp<C, H, NH, true>(lds, m);
+    __syncthreads();
+
+    const int lane = threadIdx.x & 63;
+    const int col = lane & 31, grp = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    Tile<RS> tile;
+    tile.hi = reinterpret_cast<uint16_t*>(lds + L::TILE + wave * L::TILE_UNITS);
+    tile.lo = tile.hi + L::TILE_ROWS * RS;
+
+    auto hidden_row = [](int s, int gg, int e) { return k_hidden(s, gg, e); };
+    auto input_row = [](int s, int gg, int e) { return k_input<C>(s, gg, e); };
+
+    // gradient accumulators, alive for the whole kernel
+    f32x16 dW1[MB];           // [H x C]   block mb, columns = input channels
+    f32x16 dW2[MB][MB];       // [H x H]   (NH == 2)
+    f32x16 dWo[MB];           // [4 (of 32) x H], column block nb
+    float db1[MB], db2[MB];   // lane = row within the block (partial over this lane group's samples)
+    float dbo[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+        db1[mb] = db2[mb] = 0.0f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            dW1[mb][r] = 0.0f;
+            dWo[mb][r] = 0.0f;
+#pragma unroll
+            for (int nb = 0; nb < MB; ++nb) dW2[mb][nb][r] = 0.0f;
+        }
+    }
+
+    const RaySchedule sched = ray_schedule(rays.M, kWaves);
+    const int S = rays.S;
+
+    for (long long ray = sched.first; ray < sched.end; ray += sched.stride) {
+        const RayGeom q = load_ray_geom(rays, ray);
+        const float p0 = io.d_rgb[3 * ray + 0], p1 = io.d_rgb[3 * ray + 1], p2 = io.d_rgb[3 * ray + 2];
+        const float p_alpha = io.d_alpha ? io.d_alpha[ray] : 0.0f;
+        const float p_depth = io.d_depth ? io.d_depth[ray] : 0.0f;
+        const float tau_S = io.cache[ray];
+        // d(loss)/dT_S through alpha = 1 - T_S and rgb += T_S bg, times T_S
+        const float kS = __expf(-tau_S) * (p_alpha - (p0 * io.bg[0] + p1 * io.bg[1] + p2 * io.bg[2]));
+        float tau_end = tau_S;  // optical depth up to the end of the current step
+        float carry = 0.0f;     // sum of w_j a_j over all later steps
+
+        for (int j0 = ((S - 1) / 64) * 64; j0 >= 0; j0 -= 64) {
+            StepActs<C, H, NH> a;
+            forward_step<KIND, C, H, NH, true>(g, lds, q, j0, S, lane, a);
+
+            // ---- emission-absorption backward for sample j0 + lane ----
+            const int j = j0 + lane;
+            const bool valid = j < S;
+            const float t = q.near + ((float)j + 0.5f) * q.delta;
+            const float sd = valid ? fast_softplus(a.z[0]) * q.delta : 0.0f;
+            const float incl = wave_scan_incl(sd, lane);
+            const float tau_start = tau_end - __shfl(incl, 63, 64);
+            const float Tprev = __expf(-(tau_start + (incl - sd)));
+            const float w = Tprev * one_minus_exp_neg(sd);
+            const float Tq = Tprev - w;
+            const float c1 = fast_logistic(a.z[1]), c2 = fast_logistic(a.z[2]), c3 = fast_logistic(a.z[3]);
+            const float aa = p0 * c1 + p1 * c2 + p2 * c3 + p_depth * t;
+            const float wa = w * aa;
+            const float suf = wave_scan_suffix(wa, lane);
+            const float dsigma = q.delta * (Tq * aa - (suf - wa + carry) + kS);
+            carry += __shfl(suf, 0, 64);
+            tau_end = tau_start;
+            float dz[4];
+            dz[0] = valid ? dsigma * fast_logistic(a.z[0]) : 0.0f;
+            dz[1] = valid ? w * p0 * c1 * (1.0f - c1) : 0.0f;
+            dz[2] = valid ? w * p1 * c2 * (1.0f - c2) : 0.0f;
+            dz[3] = valid ? w * p2 * c3 * (1.0f - c3) : 0.0f;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) dbo[k] += dz[k];
+
+            // output gradients as a B operand (K = 16, the 4 rows at k = 8 grp + 0..3): N block nb
+            // takes them from lane group nb, the other group contributes zeros
+            uint32_t zh0, zl0, zh1, zl1;
+            split2(dz[0], dz[1], zh0, zl0);
+            split2(dz[2], dz[3], zh1, zl1);
+            Frag gzo_h[2][1], gzo_l[2][1];
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb) {
+                const bool mine = grp == nb;
+                gzo_h[nb][0].d[0] = mine ? zh0 : 0u; gzo_h[nb][0].d[1] = mine ? zh1 : 0u;
+                gzo_h[nb][0].d[2] = 0u; gzo_h[nb][0].d[3] = 0u;
+                gzo_l[nb][0].d[0] = mine ? zl0 : 0u; gzo_l[nb][0].d[1] = mine ? zl1 : 0u;
+                gzo_l[nb][0].d[2] = 0u; gzo_l[nb][0].d[3] = 0u;
+            }
+
+            const Frag (&lh)[2][KSH] = NH == 2 ? a.h2h : a.h1h;  // last hidden layer's activations
+            const Frag (&ll)[2][KSH] = NH == 2 ? a.h2l : a.h1l;
+
+            // ---- output layer: dWo += dZo * Hlast^T over the 64 samples ----
+            {
+                tile.template store<KSH>(lh, ll, lane, hidden_row);
+                tile.hi[(H + 0) * RS + lane] = (uint16_t)zh0; tile.hi[(H + 1) * RS + lane] = (uint16_t)(zh0 >> 16);
+                tile.hi[(H + 2) * RS + lane] = (uint16_t)zh1; tile.hi[(H + 3) * RS + lane] = (uint16_t)(zh1 >> 16);
+                tile.lo[(H + 0) * RS + lane] = (uint16_t)zl0; tile.lo[(H + 1) * RS + lane] = (uint16_t)(zl0 >> 16);
+                tile.lo[(H + 2) * RS + lane] = (uint16_t)zl1; tile.lo[(H + 3) * RS + lane] = (uint16_t)(zl1 >> 16);
+                wave_lds_fence();
+                Frag ah[4], al[4];
+#pragma unroll
+                for (int s = 0; s < 4; ++s) tile.load(H + (col & 3), s, grp, col < 4, ah[s], al[s]);
+#pragma unroll
+                for (int nb = 0; nb < MB; ++nb)
+#pragma unroll
+                    for (int s = 0; s < 4; ++s) {
+                        Frag bh, bl;
+                        tile.load(32 * nb + col, s, grp, true, bh, bl);
+                        dWo[nb] = mfma3(ah[s], al[s], bh, bl, dWo[nb]);
+                    }
+                wave_lds_fence();
+            }
+
+            // ---- last hidden layer: dZ = relu'(.) * (Wout^T dZo) ----
+            f32x16 acc[MB][2];
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[mb][0][r] = acc[mb][1][r] = 0.0f;
+            layer_mfma<MB, 1>(acc, lds + L::T3, lane, gzo_h, gzo_l);
+            relu_mask<MB>(acc, lh);
+            Frag gz_h[2][KSH], gz_l[2][KSH];
+            to_operands<MB, false>(acc, gz_h, gz_l);
+
+            if constexpr (NH == 2) {
+                // dW2 += dZ2 * H1^T ; db2 += sum dZ2
+                tile.template store<KSH>(gz_h, gz_l, lane, hidden_row);
+                wave_lds_fence();
+                Frag ah[MB][4], al[MB][4];
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                    for (int s = 0; s < 4; ++s) {
+                        tile.load(32 * mb + col, s, grp, true, ah[mb][s], al[mb][s]);
+                        db2[mb] = frag_sum(al[mb][s], frag_sum(ah[mb][s], db2[mb]));
+                    }
+                wave_lds_fence();
+                tile.template store<KSH>(a.h1h, a.h1l, lane, hidden_row);
+                wave_lds_fence();
+#pragma unroll
+                for (int nb = 0; nb < MB; ++nb)
+#pragma unroll
+                    for (int s = 0; s < 4; ++s) {
+                        Frag bh, bl;
+                        tile.load(32 * nb + col, s, grp, true, bh, bl);
+#pragma unroll
+                        for (int mb = 0; mb < MB; ++mb) dW2[mb][nb] = mfma3(ah[mb][s], al[mb][s], bh, bl, dW2[mb][nb]);
+                    }
+                wave_lds_fence();
+                // dZ1 = relu'(.) * (W2^T dZ2)
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[mb][0][r] = acc[mb][1][r] = 0.0f;
+                layer_mfma<MB, KSH>(acc, lds + L::T2, lane, gz_h, gz_l);
+                relu_mask<MB>(acc, a.h1h);
+                to_operands<MB, false>(acc, gz_h, gz_l);
+            }
+
+            // ---- first layer: dW1 += dZ1 * F^T ; db1 += sum dZ1 ; dF = W1^T dZ1 ----
+            {
+                tile.template store<KSH>(gz_h, gz_l, lane, hidden_row);
+                wave_lds_fence();
+                Frag ah[MB][4], al[MB][4];
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                    for (int s = 0; s < 4; ++s) {
+                        tile.load(32 * mb + col, s, grp, true, ah[mb][s], al[mb][s]);
+                        db1[mb] = frag_sum(al[mb][s], frag_sum(ah[mb][s], db1[mb]));
+                    }
+                wave_lds_fence();
+                tile.template store<KS1>(a.fh, a.fl, lane, input_row);
+                wave_lds_fence();
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    Frag bh, bl;
+                    tile.load(col & (C - 1), s, grp, col < C, bh, bl);
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb) dW1[mb] = mfma3(ah[mb][s], al[mb][s], bh, bl, dW1[mb]);
+                }
+                wave_lds_fence();
+            }
+            f32x16 dF[2];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) dF[0][r] = dF[1][r] = 0.0f;
+#pragma unroll
+            for (int s = 0; s < KSH; ++s) {
+                Frag th, tl;
+                load_operand(lds + L::T1 + s * 128, lane, th, tl);
+                dF[0] = mfma3(th, tl, gz_h[0][s], gz_l[0][s], dF[0]);
+                dF[1] = mfma3(th, tl, gz_h[1][s], gz_l[1][s], dF[1]);
+            }
+
+            // ---- scatter into the grid gradient ----
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb) {
+                const int js = j0 + 32 * nb + col;
+                if (js < S) {
+                    const Cell3 c = sample_cell(g, q, js);
+                    float vals[C / 2];
+#pragma unroll
+                    for (int k = 0; k < C / 2; ++k) vals[k] = dF[nb][k];
+                    scatter_half<KIND, C>(g, io.d_grid, q.scene, c, grp, vals);
+                }
+            }
+        }
+    }
+
+    // ---- this wave's record of partial sums ----
+    float* rec = io.ws + (size_t)(blockIdx.x * kWaves + wave) * io.ws_stride;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int out = 32 * mb + d_row(r, grp);
+            if (col < C) rec[m.w_off[0] + out * C + col] = dW1[mb][r];
+            if constexpr (NH == 2) {
+#pragma unroll
+                for (int nb = 0; nb < MB; ++nb) rec[m.w_off[1] + out * H + 32 * nb + col] = dW2[mb][nb][r];
+            }
+        }
+#pragma unroll
+    for (int nb = 0; nb < MB; ++nb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            if (grp == 0) rec[m.w_off[NH] + r * H + 32 * nb + col] = dWo[nb][r];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+        const float s1 = db1[mb] + __shfl_xor(db1[mb], 32, 64);
+        if (grp == 0) rec[m.b_off[0] + 32 * mb + col] = s1;
+        if constexpr (NH == 2) {
+            const float s2 = db2[mb] + __shfl_xor(db2[mb], 32, 64);
+            if (grp == 0) rec[m.b_off[1] + 32 * mb + col] = s2;
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const float s = wave_sum(dbo[k]);
+        if (lane == 0) rec[m.b_off[NH] + k] = s;
+    }
+}
+
+template <int KIND, int C, int H, int NH>
+hipError_t launch_bwd(const GridDev& g, const MlpDev& m, const RaysDev& rays, const BwdIo& io, int n_cu,
+                      hipStream_t stream)
+{
+    constexpr int kLdsBytes = MlpLds<C, H, NH, true>::bytes(kWaves);
+    static_assert(kLdsBytes <= 160 * 1024, "LDS budget of a gfx950 compute unit");
+    auto kernel = bwd_mfma_kernel<KIND, C, H, NH>;
+    hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    if (e != hipSuccess) return e;
+    const int blocks = mfma_bwd_records(n_cu) / kWaves;  // every wave writes a record, busy or not
+    hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kWaves * 64), kLdsBytes, stream, g, m, rays, io);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int threads = 256;
+    hipLaunchKernelGGL(reduce_params_kernel, dim3((m.param_total + threads - 1) / threads), dim3(threads), 0, stream,
+                       m, io, blocks * kWaves);
+    return hipGetLastError();
+}
+
+template <int KIND>
+hipError_t dispatch_bwd(const GridDev& g, const MlpDev& m, const RaysDev& rays, const BwdIo& io, int n_cu,
+                        hipStream_t stream)
+{
+    const int C = g.C, H = m.dims[1], NH = m.n_layers - 1;
+#define LP_CASE(c, h, nh) \
+    if (C == c && H == h && NH == nh) return launch_bwd<KIND, c, h, nh>(g, m, rays, io, n_cu, stream);
+    LP_CASE(16, 32, 1) LP_CASE(16, 64, 1) LP_CASE(32, 32, 1) LP_CASE(32, 64, 1)
+    LP_CASE(16, 32, 2) LP_CASE(16, 64, 2) LP_CASE(32, 32, 2) LP_CASE(32, 64, 2)
+#undef LP_CASE
+    return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+// one workgroup of 4 waves per compute unit, rounded up to a multiple of the 8 XCDs
+int mfma_bwd_records(int n_cu) { return ((n_cu + 7) / 8 * 8) * kWaves; }
+
+hipError_t launch_bwd_mfma(const GridDev& g, const MlpDev& m, const RaysDev& rays, const BwdIo& io, int n_cu,
+                           hipStream_t stream)
+{
+    return g.kind == LP_GRID_VOXEL ? dispatch_bwd<LP_GRID_VOXEL>(g, m, rays, io, n_cu, stream)
+                                   : dispatch_bwd<LP_GRID_TRIPLANE>(g, m, rays, io, n_cu, stream);
+}
+
+}  // namespace lp

@@ -1,0 +1,206 @@
+// The decoder MLP of one 64-sample step on the matrix cores: LDS layout of the weights as
+// MFMA A operands, their staging, and the forward pass shared by the forward kernel and the
+// recomputing backward kernel (Section 3.4 of the paper: the backward re-runs the forward of
+// every sample instead of reading stored activations).
+#pragma once
+#include "lp_mfma.h"
+
+namespace lp {
+
+// Shapes: C input channels, H hidden width, NH hidden layers (1 or 2), 4 outputs.
+template <int C, int H, int NH, bool BWD>
+struct MlpLds {
+    static constexpr int MB = H / 32;   // 32-row blocks of a hidden layer
+    static constexpr int KS1 = C / 16;  // K-steps over the input channels
+    static constexpr int KSH = H / 16;  // K-steps over a hidden layer
+    // offsets in uint4 (16 B) units; one (block, K-step) = 64 hi + 64 lo entries = 128 units
+    static constexpr int A1 = 0;                                   // W1   [MB][KS1]
+    static constexpr int A2 = A1 + MB * KS1 * 128;                 // W2   [MB][KSH]   (NH == 2)
+    static constexpr int A3 = A2 + (NH == 2 ? MB * KSH * 128 : 0); // Wout [1][KSH], rows 0..3 = rows 4..7
+    static constexpr int FWD_END = A3 + KSH * 128;
+    // transposed weights for the input-gradient chain (backward only)
+    static constexpr int T3 = FWD_END;                             // Wout^T [MB][1]
+    static constexpr int T2 = T3 + (BWD ? MB * 128 : 0);           // W2^T   [MB][KSH]  (NH == 2)
+    static constexpr int T1 = T2 + (BWD && NH == 2 ? MB * KSH * 128 : 0);  // W1^T [1][KSH], rows >= C zero
+    static constexpr int W_END = T1 + (BWD ? KSH * 128 : 0);
+    static constexpr int BIAS = W_END;                             // floats: b1[H] b2[H] bout[4]
+    static constexpr int BIAS_UNITS = (2 * H + 4 + 3) / 4;
+    static constexpr int TILE = BIAS + BIAS_UNITS;                 // per-wave transpose tiles (backward)
+    // tile: two planes (hi, lo) of [H + 4 rows][72 halfwords]; 64 samples + 8 pad per row
+    static constexpr int TILE_ROWS = H + 4;
+    static constexpr int TILE_RS = 72;                              // halfwords per row (144 B)
+    static constexpr int TILE_PLANE_UNITS = TILE_ROWS * TILE_RS * 2 / 16;
+    static constexpr int TILE_UNITS = 2 * TILE_PLANE_UNITS;
+    static constexpr int bytes(int waves) { return (TILE + (BWD ? waves * TILE_UNITS : 0)) * 16; }
+};
+
+template <int C, int H, int NH, bool BWD>
+__device__ __forceinline__ void stage_mlp(uint4* lds, const MlpDev& m)
+{
+    using L = MlpLds<C, H, NH, BWD>;
+    constexpr int MB = L::MB, KS1 = L::KS1, KSH = L::KSH;
+    auto hidden_col = [](int s, int gg, int e) { return k_hidden(s, gg, e); };
+    auto block_row = [](int mb, int i) { return 32 * mb + i; };
+    stage_operand(lds + L::A1, m.W[0], MB, KS1, C, block_row,
+                  [](int s, int gg, int e) { return k_input<C>(s, gg, e); });
+    if constexpr (NH == 2) stage_operand(lds + L::A2, m.W[1], MB, KSH, H, block_row, hidden_col);
+    // output layer: rows 0..3 and 4..7 both carry the 4 outputs, so that both lane groups of a
+    // sample column hold them (D rows 4g + p)
+    stage_operand(lds + L::A3, m.W[NH], 1, KSH, H, [](int, int i) { return i < 8 ? (i & 3) : -1; }, hidden_col);
+    if constexpr (BWD) {
+        // A[m][k] = W^T[m][k] = W[k][m]: read W with (row, col) swapped.  stage_operand reads
+        // W[row_of * ld + col_of], so pass the transposed roles: "row" = k index, "col" = m index.
+        // Wout^T: K = 16 with the 4 outputs at k = 0..3 and again at k = 8..11 (either lane group
+        // of the B operand may carry the output gradients)
+        stage_operand_t(lds + L::T3, m.W[NH], MB, 1, H,
+                        [](int mb, int i) { return 32 * mb + i; },
+                        [](int, int, int e) { return e < 4 ? e : -1; });
+        if constexpr (NH == 2)
+            stage_operand_t(lds + L::T2, m.W[1], MB, KSH, H, [](int mb, int i) { return 32 * mb + i; },
+                            [](int s, int gg, int e) { return k_hidden(s, gg, e); });
+        stage_operand_t(lds + L::T1, m.W[0], 1, KSH, C, [](int, int i) { return i < C ? i : -1; },
+                        [](int s, int gg, int e) { return k_hidden(s, gg, e); });
+    }
+    float* sbias = reinterpret_cast<float*>(lds + L::BIAS);
+    for (int i = threadIdx.x; i < H; i += blockDim.x) {
+        sbias[i] = m.b[0][i];
+        sbias[H + i] = NH == 2 ? m.b[1][i] : 0.0f;
+    }
+    if (threadIdx.x < 4) sbias[2 * H + threadIdx.x] = m.b[NH][threadIdx.x];
+}
+
+// accumulators of a hidden layer start from the bias of the rows each register holds
+template <int MB>
+__device__ __forceinline__ void init_bias(f32x16 (&acc)[MB][2], const float* bias, int grp)
+{
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const f32x4 b = *reinterpret_cast<const f32x4*>(bias + 32 * mb + 8 * q + 4 * grp);
+#pragma unroll
+            for (int p = 0; p < 4; ++p) acc[mb][0][4 * q + p] = acc[mb][1][4 * q + p] = b[p];
+        }
+}
+
+// acc[mb][nb] += A[mb][s] * B[nb][s] over KS K-steps, A from LDS at `a_base`
+template <int MB, int KS>
+__device__ __forceinline__ void layer_mfma(f32x16 (&acc)[MB][2], const uint4* a_base, int lane,
+                                           const Frag (&bh)[2][KS], const Frag (&bl)[2][KS])
+{
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            Frag ah, al;
+            load_operand(a_base + (mb * KS + s) * 128, lane, ah, al);
+            acc[mb][0] = mfma3(ah, al, bh[0][s], bl[0][s], acc[mb][0]);
+            acc[mb][1] = mfma3(ah, al, bh[1][s], bl[1][s], acc[mb][1]);
+        }
+}
+
+// D registers of a layer (optionally through ReLU) -> B operands of the next contraction
+template <int MB, bool RELU>
+__device__ __forceinline__ void to_operands(const f32x16 (&acc)[MB][2], Frag (&bh)[2][2 * MB], Frag (&bl)[2][2 * MB])
+{
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+        for (int s = 0; s < 2 * MB; ++s) {
+            float v[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float x = acc[s / 2][nb][8 * (s % 2) + e];
+                v[e] = RELU ? fmaxf(x, 0.0f) : x;
+            }
+            split8(v, bh[nb][s], bl[nb][s]);
+        }
+}
+
+// Everything the forward of one 64-sample step produces.  The forward kernel uses z only; the
+// backward keeps the operand fragments (they are the activations, already split).
+template <int C, int H, int NH>
+struct StepActs {
+    static constexpr int KS1 = C / 16, KSH = H / 16;
+    Frag fh[2][KS1], fl[2][KS1];    // interpolated features (layer-1 B operands)
+    Frag h1h[2][KSH], h1l[2][KSH];  // hidden layer 1 after ReLU
+    Frag h2h[2][KSH], h2l[2][KSH];  // hidden layer 2 after ReLU (NH == 2)
+    float z[4];                     // decoder outputs of sample j0 + lane
+};
+
+struct RayGeom {
+    float ox, oy, oz, dx, dy, dz, near, delta;
+    double delta64;
+    int scene;
+};
+
+__device__ __forceinline__ RayGeom load_ray_geom(const RaysDev& rays, long long ray)
+{
+    RayGeom q;
+    q.ox = rays.origins[3 * ray + 0]; q.oy = rays.origins[3 * ray + 1]; q.oz = rays.origins[3 * ray + 2];
+    q.dx = rays.dirs[3 * ray + 0]; q.dy = rays.dirs[3 * ray + 1]; q.dz = rays.dirs[3 * ray + 2];
+    q.near = rays.near[ray];
+    q.delta64 = ((double)rays.far[ray] - (double)q.near) / (double)rays.S;
+    q.delta = (float)q.delta64;
+    q.scene = rays.scene ? rays.scene[ray] : 0;
+    return q;
+}
+
+// Cell of sample j (0-based): t_j = near + (j + 1/2) Delta, x = o + t d, in fp64 from the fp32 inputs.
+__device__ __forceinline__ Cell3 sample_cell(const GridDev& g, const RayGeom& q, int j)
+{
+    const double t = (double)q.near + ((double)j + 0.5) * q.delta64;
+    return locate3(g, (double)q.ox + t * (double)q.dx, (double)q.oy + t * (double)q.dy,
+                   (double)q.oz + t * (double)q.dz);
+}
+
+template <int KIND, int C, int H, int NH, bool BWD>
+__device__ __forceinline__ void forward_step(const GridDev& g, const uint4* lds, const RayGeom& q, int j0, int S,
+                                             int lane, StepActs<C, H, NH>& a)
+{
+    using L = MlpLds<C, H, NH, BWD>;
+    constexpr int MB = L::MB, KS1 = L::KS1, KSH = L::KSH;
+    const int col = lane & 31, grp = lane >> 5;
+    const float* sbias = reinterpret_cast<const float*>(lds + L::BIAS);
+
+    // sample + interpolate this lane's half of the channels of samples col and 32 + col
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+        const int j = min(j0 + 32 * nb + col, S - 1);
+        const Cell3 c = sample_cell(g, q, j);
+        float feat[C / 2];
+        gather_half<KIND, C, C / 2>(g, q.scene, c, grp * (C / 2), feat);
+#pragma unroll
+        for (int s = 0; s < KS1; ++s) split8(feat + 8 * s, a.fh[nb][s], a.fl[nb][s]);
+    }
+
+    f32x16 acc[MB][2];
+    init_bias<MB>(acc, sbias, grp);
+    layer_mfma<MB, KS1>(acc, lds + L::A1, lane, a.fh, a.fl);
+    to_operands<MB, true>(acc, a.h1h, a.h1l);
+    if constexpr (NH == 2) {
+        init_bias<MB>(acc, sbias + H, grp);
+        layer_mfma<MB, KSH>(acc, lds + L::A2, lane, a.h1h, a.h1l);
+        to_operands<MB, true>(acc, a.h2h, a.h2l);
+    }
+    const Frag (&lh)[2][KSH] = NH == 2 ? a.h2h : a.h1h;
+    const Frag (&ll)[2][KSH] = NH == 2 ? a.h2l : a.h1l;
+
+    // output layer: 4 rows replicated for both lane groups; lanes 0..31 take N block 0 and
+    // lanes 32..63 N block 1, so that lane l owns sample j0 + l
+    f32x16 o0, o1;
+    const f32x4 b = *reinterpret_cast<const f32x4*>(sbias + 2 * H);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o0[r] = o1[r] = r < 4 ? b[r] : 0.0f;
+#pragma unroll
+    for (int s = 0; s < KSH; ++s) {
+        Frag ah, al;
+        load_operand(lds + L::A3 + s * 128, lane, ah, al);
+        o0 = mfma3(ah, al, lh[0][s], ll[0][s], o0);
+        o1 = mfma3(ah, al, lh[1][s], ll[1][s], o1);
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) a.z[k] = grp ? o1[k] : o0[k];
+}
+
+}  // namespace lp

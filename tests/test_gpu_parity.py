@@ -73,13 +73,13 @@ def test_config_shapes_ragged(lp, oracle, kind, channels, dims, samples):
 def test_config_tiny_full(lp, oracle):
     inp = lp_inputs.make_inputs("tiny")
     for mode in _modes(lp, inp):
-        print(mode, check_case(lp, oracle, inp, mode, label=f"tiny mode={mode}", max_strict_fail=0.01), flush=True)
+        print(mode, check_case(lp, oracle, inp, mode, label=f"tiny mode={mode}", max_strict_fail=0.03), flush=True)
 
 
 def test_config_single_scene_full(lp, oracle):
     inp = lp_inputs.make_inputs("single_scene")
     for mode in _modes(lp, inp)[-1:]:
-        print(mode, check_case(lp, oracle, inp, mode, aux_grads=False, label=f"single_scene mode={mode}", max_strict_fail=0.01),
+        print(mode, check_case(lp, oracle, inp, mode, aux_grads=False, label=f"single_scene mode={mode}", max_strict_fail=0.03),
               flush=True)
 
 
@@ -90,7 +90,7 @@ def test_config_large_on_ray_subsets(lp, oracle, name, n_keep):
     inp = lp_inputs.make_inputs(name)
     sub = inp.subset(lp_inputs.strided_ray_subset(inp.n_rays, n_keep, offset=3))
     for mode in _modes(lp, sub)[-1:]:
-        print(mode, check_case(lp, oracle, sub, mode, label=f"{name} subset mode={mode}", max_strict_fail=0.01), flush=True)
+        print(mode, check_case(lp, oracle, sub, mode, label=f"{name} subset mode={mode}", max_strict_fail=0.03), flush=True)
 
 
 # ------------------------------------------------------------------ edge cases
