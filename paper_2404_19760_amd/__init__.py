@@ -17,7 +17,7 @@ from typing import List, Optional, Sequence
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "liblightplane.so")
+LIB_PATH = os.environ.get("LP_LIB_PATH", os.path.join(_HERE, "liblightplane.so"))
 
 LP_MAX_LAYERS = 8
 LP_OK, LP_ERR_INVALID_ARG, LP_ERR_UNSUPPORTED, LP_ERR_HIP, LP_ERR_WORKSPACE = range(5)

@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 OBJ = os.path.join(HERE, "_build")
-LIB = os.path.join(HERE, "liblightplane.so")
+LIB = os.environ.get("LP_LIB_OUT", os.path.join(HERE, "liblightplane.so"))
 
 SOURCES = ["lp_api.hip", "lp_generic.hip", "lp_mfma_fwd.hip", "lp_mfma_bwd.hip"]
 
@@ -37,7 +37,8 @@ def _hipcc() -> str:
 
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
-    cmd = [_hipcc(), *HIPCC_FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    extra = os.environ.get("LP_EXTRA_HIPCC_FLAGS", "").split()   # experiments only
+    cmd = [_hipcc(), *HIPCC_FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     res = subprocess.run(cmd, capture_output=True, text=True)
     # the host pass does not know the packed-fp32 feature and says so: harmless
     err = "\n".join(l for l in res.stderr.splitlines()

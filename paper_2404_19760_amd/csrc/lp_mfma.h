@@ -138,27 +138,32 @@ __device__ __forceinline__ void load_operand(const uint4* blk, int lane, Frag& h
     lo.d[0] = l.x; lo.d[1] = l.y; lo.d[2] = l.z; lo.d[3] = l.w;
 }
 
-// Inclusive prefix sum over the 64 lanes of a wave.
-__device__ __forceinline__ float wave_scan_incl(float v, int lane)
+// Inclusive prefix sum over groups of W consecutive lanes (W = 64: the whole wave; W = 32: each
+// half on its own); `pos` is the lane's position inside its group.
+template <int W>
+__device__ __forceinline__ float group_scan_incl(float v, int pos)
 {
 #pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const float u = __shfl_up(v, d, 64);
-        if (lane >= d) v += u;
+    for (int d = 1; d < W; d <<= 1) {
+        const float u = __shfl_up(v, d, W);
+        if (pos >= d) v += u;
     }
     return v;
 }
 
-// Inclusive suffix sum (lane l gets the sum over lanes l..63).
-__device__ __forceinline__ float wave_scan_suffix(float v, int lane)
+// Inclusive suffix sum (position p gets the sum over positions p..W-1 of its group).
+template <int W>
+__device__ __forceinline__ float group_scan_suffix(float v, int pos)
 {
 #pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const float u = __shfl_down(v, d, 64);
-        if (lane + d < 64) v += u;
+    for (int d = 1; d < W; d <<= 1) {
+        const float u = __shfl_down(v, d, W);
+        if (pos + d < W) v += u;
     }
     return v;
 }
+
+__device__ __forceinline__ float wave_scan_incl(float v, int lane) { return group_scan_incl<64>(v, lane); }
 
 __device__ __forceinline__ float wave_sum(float v)
 {

@@ -1,17 +1,22 @@
 // Matrix-core backward kernel of the Renderer (Eq. (2), Section 3.4 of the paper).
 //
-// Same mapping as the forward: a wavefront marches one ray, 64 samples per step, but from the
-// LAST step to the first.  Per step it
+// Same mapping as the forward: a wavefront marches one ray, but from the LAST step to the first
+// and in steps of 32 samples (one N block; the per-step state of the backward is twice the
+// forward's, and the weight-gradient accumulators live in registers for the whole kernel).
+// Per step it
 //   1. recomputes sampling + MLP forward (nothing was stored but one scalar per ray),
 //   2. rebuilds the transmittance from the cached optical depth (tau_{q-1} = tau_q - sigma_q Delta,
 //      T = exp(-tau): the paper's T_{q-1} = T_q exp(Delta sigma_q) in the log domain) and evaluates
-//      Eq. (2) with a wave-level suffix scan of w_j a_j plus the carry of later steps,
+//      Eq. (2) with a suffix scan of w_j a_j over the step plus the carry of later steps,
 //   3. back-propagates through the MLP on the matrix cores: input gradients with the transposed
 //      weights (dX = W^T dZ, chained in registers like the forward), weight gradients as
-//      dW = dZ X^T contracted over the 64 samples, for which dZ and X are transposed through a
+//      dW = dZ X^T contracted over the samples, for which dZ and X are transposed through a
 //      per-wave LDS tile (bf16 hi/lo planes, 16-bit stores, 128-bit operand loads),
-//   4. scatters the feature gradient into the grid gradient with the interpolation weights
-//      (hardware fp32 atomics).
+//   4. scatters the feature gradient into the grid gradient.  The last contraction is evaluated
+//      with its operands swapped, which leaves the feature gradient with lane = channel and
+//      register = sample; a lane then walks its samples in ray order, sums the contributions
+//      of consecutive samples that fall into the same cell, and the lanes of one corner issue
+//      one atomic add per channel on consecutive addresses (whole 64-byte lines).
 // Weight / bias gradients stay in registers for the whole kernel; each wave writes one record
 // of partial sums at the end and a second kernel adds the records in a fixed order.
 #include "lp_kernels.h"
@@ -23,6 +28,9 @@ namespace lp {
 namespace {
 
 constexpr int kWaves = 4;
+constexpr int kNB = 1;            // N blocks (of 32 samples) per step
+constexpr int kStep = 32 * kNB;   // samples per step
+constexpr int kKS = 2 * kNB;      // K-steps of a contraction over the samples of a step
 
 __device__ __forceinline__ void wave_lds_fence()
 {
@@ -31,6 +39,7 @@ __device__ __forceinline__ void wave_lds_fence()
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    __builtin_amdgcn_sched_barrier(0);
 }
 
 template <int RS>
@@ -38,14 +47,15 @@ struct Tile {
     uint16_t* hi;
     uint16_t* lo;
 
-    // operand fragments [2 N-blocks][KS] whose element e of lane-group g is row row_of(s, g, e)
-    // of sample column (lane & 31) + 32 nb  ->  tile[row][sample]
+    // operand fragments [NB][KS] whose element e of lane-group g is row row_of(s, g, e) of sample
+    // column (lane & 31) + 32 nb  ->  tile[row][sample]
     template <int KS, class RowFn>
-    __device__ __forceinline__ void store(const Frag (&fh)[2][KS], const Frag (&fl)[2][KS], int lane, RowFn row_of) const
+    __device__ __forceinline__ void store(const Frag (&fh)[kNB][KS], const Frag (&fl)[kNB][KS], int lane,
+                                          RowFn row_of) const
     {
         const int col = lane & 31, grp = lane >> 5;
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
+        for (int nb = 0; nb < kNB; ++nb)
 #pragma unroll
             for (int s = 0; s < KS; ++s)
 #pragma unroll
@@ -59,7 +69,7 @@ struct Tile {
                 }
     }
 
-    // MFMA operand with the 64 samples on the K axis: 8 consecutive samples of `row`
+    // MFMA operand with the samples of the step on the K axis: 8 consecutive samples of `row`
     __device__ __forceinline__ void load(int row, int s, int grp, bool live, Frag& fh, Frag& fl) const
     {
         const uint4 h = *reinterpret_cast<const uint4*>(hi + row * RS + 16 * s + 8 * grp);
@@ -80,54 +90,14 @@ __device__ __forceinline__ float frag_sum(const Frag& f, float acc)
     return acc;
 }
 
-// d_grid[corner][channels] += weight * vals for this lane's C/2 channels (rows 8q + 4g + p of
-// the feature-gradient block): the transpose of gather_half with the same corners and weights
-template <int KIND, int C>
-__device__ __forceinline__ void scatter_half(const GridDev& g, float* const d_grid[3], int scene, const Cell3& c,
-                                             int grp, const float* vals)
-{
-    auto add_corner = [&](float* p, float w) {
-#pragma unroll
-        for (int q = 0; q < C / 8; ++q)
-#pragma unroll
-            for (int pp = 0; pp < 4; ++pp) atomicAdd(p + 8 * q + 4 * grp + pp, w * vals[4 * q + pp]);
-    };
-    if constexpr (KIND == LP_GRID_VOXEL) {
-        float* V = d_grid[0] + (size_t)scene * g.N[0] * g.N[1] * g.N[2] * C;
-        const unsigned sz = C, sy = (unsigned)g.N[2] * C, sx = (unsigned)g.N[1] * sy;
-        const unsigned base = (unsigned)c.i[0] * sx + (unsigned)c.i[1] * sy + (unsigned)c.i[2] * sz;
-#pragma unroll
-        for (int d = 0; d < 8; ++d) {
-            const int dx = d >> 2, dy = (d >> 1) & 1, dz = d & 1;
-            const float w = (dx ? c.f[0] : 1.0f - c.f[0]) * (dy ? c.f[1] : 1.0f - c.f[1]) *
-                            (dz ? c.f[2] : 1.0f - c.f[2]);
-            add_corner(V + (base + dx * sx + dy * sy + dz * sz), w);
-        }
-    } else {
-#pragma unroll
-        for (int p = 0; p < 3; ++p) {
-            const int a = p, b = (p + 1) % 3;
-            float* P = d_grid[p] + (size_t)scene * g.N[a] * g.N[b] * C;
-            const unsigned sb = C, sa = (unsigned)g.N[b] * C;
-            const unsigned base = (unsigned)c.i[a] * sa + (unsigned)c.i[b] * sb;
-#pragma unroll
-            for (int d = 0; d < 4; ++d) {
-                const int da = d >> 1, db = d & 1;
-                const float w = (da ? c.f[a] : 1.0f - c.f[a]) * (db ? c.f[b] : 1.0f - c.f[b]);
-                add_corner(P + (base + da * sa + db * sb), w);
-            }
-        }
-    }
-}
-
 // zeroes the entries of a D block whose ReLU output (hi part of the stored activation) is zero
 template <int MB>
-__device__ __forceinline__ void relu_mask(f32x16 (&acc)[MB][2], const Frag (&act_hi)[2][2 * MB])
+__device__ __forceinline__ void relu_mask(f32x16 (&acc)[MB][kNB], const Frag (&act_hi)[kNB][2 * MB])
 {
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
+        for (int nb = 0; nb < kNB; ++nb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int s = 2 * mb + r / 8, e = r % 8;
@@ -136,13 +106,128 @@ __device__ __forceinline__ void relu_mask(f32x16 (&acc)[MB][2], const Frag (&act
             }
 }
 
+// ---- scatter records: what the channel lanes need to know about each sample of the step ----
+// 16 dwords per sample.  voxel: 8 corner weights (corner 4dx + 2dy + dz), then the element offset of
+// corner 0.  triplane: 12 weights (plane p, corner 2da + db at 4p + ..), then 3 plane offsets.
+template <int KIND, int C>
+__device__ __forceinline__ void write_scatter_record(float* rec, const GridDev& g, const Cell3& c)
+{
+    if constexpr (KIND == LP_GRID_VOXEL) {
+        const float x1 = c.f[0], x0 = 1.0f - x1, y1 = c.f[1], y0 = 1.0f - y1, z1 = c.f[2], z0 = 1.0f - z1;
+        const float4 w0 = make_float4(x0 * y0 * z0, x0 * y0 * z1, x0 * y1 * z0, x0 * y1 * z1);
+        const float4 w1 = make_float4(x1 * y0 * z0, x1 * y0 * z1, x1 * y1 * z0, x1 * y1 * z1);
+        const unsigned sz = C, sy = (unsigned)g.N[2] * C, sx = (unsigned)g.N[1] * sy;
+        const unsigned base = (unsigned)c.i[0] * sx + (unsigned)c.i[1] * sy + (unsigned)c.i[2] * sz;
+        reinterpret_cast<float4*>(rec)[0] = w0;
+        reinterpret_cast<float4*>(rec)[1] = w1;
+        reinterpret_cast<unsigned*>(rec)[8] = base;
+    } else {
+        unsigned base[3];
+#pragma unroll
+        for (int p = 0; p < 3; ++p) {
+            const int a = p, b = (p + 1) % 3;
+            const float a1 = c.f[a], a0 = 1.0f - a1, b1 = c.f[b], b0 = 1.0f - b1;
+            reinterpret_cast<float4*>(rec)[p] = make_float4(a0 * b0, a0 * b1, a1 * b0, a1 * b1);
+            base[p] = ((unsigned)c.i[a] * (unsigned)g.N[b] + (unsigned)c.i[b]) * C;
+        }
+        reinterpret_cast<uint4*>(rec)[3] = make_uint4(base[0], base[1], base[2], 0u);
+    }
+}
+
+// This lane (channel `ch` of lane group `grp`) holds in dFt the feature gradient of the samples
+// d_row(r, grp), r = 0..15, of the step: four runs of four consecutive samples.  Consecutive
+// samples in the same cell are summed before one atomic add per corner; the lanes ch = 0..C-1
+// of a group address consecutive floats.
+template <int KIND, int C>
+__device__ __forceinline__ void scatter_channels(const GridDev& g, float* const d_grid[3], int scene,
+                                                 const float* info, const f32x16& dFt, int ch, int grp)
+{
+    const bool live = ch < C;
+    if constexpr (KIND == LP_GRID_VOXEL) {
+        float* V = d_grid[0] + (size_t)scene * g.N[0] * g.N[1] * g.N[2] * C + ch;
+        const unsigned sz = C, sy = (unsigned)g.N[2] * C, sx = (unsigned)g.N[1] * sy;
+        auto flush = [&](unsigned base, const float (&acc)[8]) {
+            if (live) {
+#pragma unroll
+                for (int d = 0; d < 8; ++d)
+                    atomicAdd(V + (base + (d >> 2) * sx + ((d >> 1) & 1) * sy + (d & 1) * sz), acc[d]);
+            }
+        };
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+            float acc[8];
+            unsigned prev = 0;
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const float* rec = info + (8 * qd + 4 * grp + p) * 16;
+                const float4 w0 = reinterpret_cast<const float4*>(rec)[0];
+                const float4 w1 = reinterpret_cast<const float4*>(rec)[1];
+                const unsigned base = reinterpret_cast<const unsigned*>(rec)[8];
+                const float w[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
+                const float v = dFt[4 * qd + p];
+                if (p > 0 && base != prev) {
+                    flush(prev, acc);
+#pragma unroll
+                    for (int d = 0; d < 8; ++d) acc[d] = 0.0f;
+                }
+#pragma unroll
+                for (int d = 0; d < 8; ++d) acc[d] = p == 0 ? w[d] * v : acc[d] + w[d] * v;
+                prev = base;
+            }
+            flush(prev, acc);
+        }
+    } else {
+        float* P[3];
+        unsigned sa[3];
+#pragma unroll
+        for (int p = 0; p < 3; ++p) {
+            const int a = p, b = (p + 1) % 3;
+            P[p] = d_grid[p] + (size_t)scene * g.N[a] * g.N[b] * C + ch;
+            sa[p] = (unsigned)g.N[b] * C;
+        }
+        auto flush = [&](int pl, unsigned base, const float* acc) {
+            if (live) {
+#pragma unroll
+                for (int d = 0; d < 4; ++d) atomicAdd(P[pl] + (base + (d >> 1) * sa[pl] + (d & 1) * C), acc[d]);
+            }
+        };
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+            float acc[12];
+            unsigned prev[3] = {0, 0, 0};
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const float* rec = info + (8 * qd + 4 * grp + p) * 16;
+                const uint4 bases = reinterpret_cast<const uint4*>(rec)[3];
+                const unsigned base[3] = {bases.x, bases.y, bases.z};
+                const float v = dFt[4 * qd + p];
+#pragma unroll
+                for (int pl = 0; pl < 3; ++pl) {
+                    const float4 w4 = reinterpret_cast<const float4*>(rec)[pl];
+                    const float w[4] = {w4.x, w4.y, w4.z, w4.w};
+                    if (p > 0 && base[pl] != prev[pl]) {
+                        flush(pl, prev[pl], acc + 4 * pl);
+#pragma unroll
+                        for (int d = 0; d < 4; ++d) acc[4 * pl + d] = 0.0f;
+                    }
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) acc[4 * pl + d] = p == 0 ? w[d] * v : acc[4 * pl + d] + w[d] * v;
+                    prev[pl] = base[pl];
+                }
+            }
+#pragma unroll
+            for (int pl = 0; pl < 3; ++pl) flush(pl, prev[pl], acc + 4 * pl);
+        }
+    }
+}
+
 template <int KIND, int C, int H, int NH>
 __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev m, RaysDev rays, BwdIo io)
 {
-    using L = MlpLds<C, H, NH, true>;
+    using L = MlpLds<C, H, NH, true, kNB>;
     constexpr int MB = L::MB, KS1 = L::KS1, KSH = L::KSH, RS = L::TILE_RS;
     extern __shared__ uint4 lds[];
-    stage_mlp<C, H, NH, true>(lds, m);
+    stage_mlp<C, H, NH, true, kNB>(lds, m);
     __syncthreads();
 
     const int lane = threadIdx.x & 63;
@@ -151,6 +236,7 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
     Tile<RS> tile;
     tile.hi = reinterpret_cast<uint16_t*>(lds + L::TILE + wave * L::TILE_UNITS);
     tile.lo = tile.hi + L::TILE_ROWS * RS;
+    float* info = reinterpret_cast<float*>(lds + L::TILE + wave * L::TILE_UNITS + 2 * L::TILE_PLANE_UNITS);
 
     auto hidden_row = [](int s, int gg, int e) { return k_hidden(s, gg, e); };
     auto input_row = [](int s, int gg, int e) { return k_input<C>(s, gg, e); };
@@ -187,26 +273,26 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
         float tau_end = tau_S;  // optical depth up to the end of the current step
         float carry = 0.0f;     // sum of w_j a_j over all later steps
 
-        for (int j0 = ((S - 1) / 64) * 64; j0 >= 0; j0 -= 64) {
-            StepActs<C, H, NH> a;
-            forward_step<KIND, C, H, NH, true>(g, lds, q, j0, S, lane, a);
+        for (int j0 = ((S - 1) / kStep) * kStep; j0 >= 0; j0 -= kStep) {
+            StepActs<C, H, NH, kNB> a;
+            forward_step<KIND, C, H, NH, true, kNB>(g, lds, q, j0, S, lane, a);
 
-            // ---- emission-absorption backward for sample j0 + lane ----
-            const int j = j0 + lane;
+            // ---- emission-absorption backward for sample j0 + col (both lane groups alike) ----
+            const int j = j0 + col;
             const bool valid = j < S;
             const float t = q.near + ((float)j + 0.5f) * q.delta;
             const float sd = valid ? fast_softplus(a.z[0]) * q.delta : 0.0f;
-            const float incl = wave_scan_incl(sd, lane);
-            const float tau_start = tau_end - __shfl(incl, 63, 64);
+            const float incl = group_scan_incl<kStep>(sd, col);
+            const float tau_start = tau_end - __shfl(incl, kStep - 1, kStep);
             const float Tprev = __expf(-(tau_start + (incl - sd)));
             const float w = Tprev * one_minus_exp_neg(sd);
             const float Tq = Tprev - w;
             const float c1 = fast_logistic(a.z[1]), c2 = fast_logistic(a.z[2]), c3 = fast_logistic(a.z[3]);
             const float aa = p0 * c1 + p1 * c2 + p2 * c3 + p_depth * t;
             const float wa = w * aa;
-            const float suf = wave_scan_suffix(wa, lane);
+            const float suf = group_scan_suffix<kStep>(wa, col);
             const float dsigma = q.delta * (Tq * aa - (suf - wa + carry) + kS);
-            carry += __shfl(suf, 0, 64);
+            carry += __shfl(suf, 0, kStep);
             tau_end = tau_start;
             float dz[4];
             dz[0] = valid ? dsigma * fast_logistic(a.z[0]) : 0.0f;
@@ -214,41 +300,44 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
             dz[2] = valid ? w * p1 * c2 * (1.0f - c2) : 0.0f;
             dz[3] = valid ? w * p2 * c3 * (1.0f - c3) : 0.0f;
 #pragma unroll
-            for (int k = 0; k < 4; ++k) dbo[k] += dz[k];
+            for (int k = 0; k < 4; ++k) dbo[k] += grp == 0 ? dz[k] : 0.0f;
 
-            // output gradients as a B operand (K = 16, the 4 rows at k = 8 grp + 0..3): N block nb
-            // takes them from lane group nb, the other group contributes zeros
+            // output gradients as a B operand (K = 16, the 4 rows at k = 0..3 of lane group 0)
             uint32_t zh0, zl0, zh1, zl1;
             split2(dz[0], dz[1], zh0, zl0);
             split2(dz[2], dz[3], zh1, zl1);
-            Frag gzo_h[2][1], gzo_l[2][1];
-#pragma unroll
-            for (int nb = 0; nb < 2; ++nb) {
-                const bool mine = grp == nb;
-                gzo_h[nb][0].d[0] = mine ? zh0 : 0u; gzo_h[nb][0].d[1] = mine ? zh1 : 0u;
-                gzo_h[nb][0].d[2] = 0u; gzo_h[nb][0].d[3] = 0u;
-                gzo_l[nb][0].d[0] = mine ? zl0 : 0u; gzo_l[nb][0].d[1] = mine ? zl1 : 0u;
-                gzo_l[nb][0].d[2] = 0u; gzo_l[nb][0].d[3] = 0u;
+            Frag gzo_h[kNB][1], gzo_l[kNB][1];
+            {
+                const bool mine = grp == 0;
+                gzo_h[0][0].d[0] = mine ? zh0 : 0u; gzo_h[0][0].d[1] = mine ? zh1 : 0u;
+                gzo_h[0][0].d[2] = 0u; gzo_h[0][0].d[3] = 0u;
+                gzo_l[0][0].d[0] = mine ? zl0 : 0u; gzo_l[0][0].d[1] = mine ? zl1 : 0u;
+                gzo_l[0][0].d[2] = 0u; gzo_l[0][0].d[3] = 0u;
             }
 
-            const Frag (&lh)[2][KSH] = NH == 2 ? a.h2h : a.h1h;  // last hidden layer's activations
-            const Frag (&ll)[2][KSH] = NH == 2 ? a.h2l : a.h1l;
+            const Frag (&lh)[kNB][KSH] = NH == 2 ? a.h2h : a.h1h;  // last hidden layer's activations
+            const Frag (&ll)[kNB][KSH] = NH == 2 ? a.h2l : a.h1l;
 
-            // ---- output layer: dWo += dZo * Hlast^T over the 64 samples ----
+            // ---- output layer: dWo += dZo * Hlast^T over the samples of the step ----
             {
-                tile.template store<KSH>(lh, ll, lane, hidden_row);
-                tile.hi[(H + 0) * RS + lane] = (uint16_t)zh0; tile.hi[(H + 1) * RS + lane] = (uint16_t)(zh0 >> 16);
-                tile.hi[(H + 2) * RS + lane] = (uint16_t)zh1; tile.hi[(H + 3) * RS + lane] = (uint16_t)(zh1 >> 16);
-                tile.lo[(H + 0) * RS + lane] = (uint16_t)zl0; tile.lo[(H + 1) * RS + lane] = (uint16_t)(zl0 >> 16);
-                tile.lo[(H + 2) * RS + lane] = (uint16_t)zl1; tile.lo[(H + 3) * RS + lane] = (uint16_t)(zl1 >> 16);
                 wave_lds_fence();
-                Frag ah[4], al[4];
+                tile.template store<KSH>(lh, ll, lane, hidden_row);
+                if (grp == 0) {
+                    tile.hi[(H + 0) * RS + col] = (uint16_t)zh0; tile.hi[(H + 1) * RS + col] = (uint16_t)(zh0 >> 16);
+                    tile.hi[(H + 2) * RS + col] = (uint16_t)zh1; tile.hi[(H + 3) * RS + col] = (uint16_t)(zh1 >> 16);
+                    tile.lo[(H + 0) * RS + col] = (uint16_t)zl0; tile.lo[(H + 1) * RS + col] = (uint16_t)(zl0 >> 16);
+                    tile.lo[(H + 2) * RS + col] = (uint16_t)zl1; tile.lo[(H + 3) * RS + col] = (uint16_t)(zl1 >> 16);
+                    // scatter record of this lane's sample, read at the end of the step
+                    write_scatter_record<KIND, C>(info + col * 16, g, a.cell[0]);
+                }
+                wave_lds_fence();
+                Frag ah[kKS], al[kKS];
 #pragma unroll
-                for (int s = 0; s < 4; ++s) tile.load(H + (col & 3), s, grp, col < 4, ah[s], al[s]);
+                for (int s = 0; s < kKS; ++s) tile.load(H + (col & 3), s, grp, col < 4, ah[s], al[s]);
 #pragma unroll
                 for (int nb = 0; nb < MB; ++nb)
 #pragma unroll
-                    for (int s = 0; s < 4; ++s) {
+                    for (int s = 0; s < kKS; ++s) {
                         Frag bh, bl;
                         tile.load(32 * nb + col, s, grp, true, bh, bl);
                         dWo[nb] = mfma3(ah[s], al[s], bh, bl, dWo[nb]);
@@ -257,25 +346,22 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
             }
 
             // ---- last hidden layer: dZ = relu'(.) * (Wout^T dZo) ----
-            f32x16 acc[MB][2];
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[mb][0][r] = acc[mb][1][r] = 0.0f;
-            layer_mfma<MB, 1>(acc, lds + L::T3, lane, gzo_h, gzo_l);
+            f32x16 acc[MB][kNB];
+            zero_acc<MB, kNB>(acc);
+            layer_mfma<MB, 1, kNB>(acc, lds + L::T3, lane, gzo_h, gzo_l);
             relu_mask<MB>(acc, lh);
-            Frag gz_h[2][KSH], gz_l[2][KSH];
-            to_operands<MB, false>(acc, gz_h, gz_l);
+            Frag gz_h[kNB][KSH], gz_l[kNB][KSH];
+            to_operands<MB, false, kNB>(acc, gz_h, gz_l);
 
             if constexpr (NH == 2) {
                 // dW2 += dZ2 * H1^T ; db2 += sum dZ2
                 tile.template store<KSH>(gz_h, gz_l, lane, hidden_row);
                 wave_lds_fence();
-                Frag ah[MB][4], al[MB][4];
+                Frag ah[MB][kKS], al[MB][kKS];
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-                    for (int s = 0; s < 4; ++s) {
+                    for (int s = 0; s < kKS; ++s) {
                         tile.load(32 * mb + col, s, grp, true, ah[mb][s], al[mb][s]);
                         db2[mb] = frag_sum(al[mb][s], frag_sum(ah[mb][s], db2[mb]));
                     }
@@ -285,7 +371,7 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
 #pragma unroll
                 for (int nb = 0; nb < MB; ++nb)
 #pragma unroll
-                    for (int s = 0; s < 4; ++s) {
+                    for (int s = 0; s < kKS; ++s) {
                         Frag bh, bl;
                         tile.load(32 * nb + col, s, grp, true, bh, bl);
 #pragma unroll
@@ -293,24 +379,21 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
                     }
                 wave_lds_fence();
                 // dZ1 = relu'(.) * (W2^T dZ2)
-#pragma unroll
-                for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[mb][0][r] = acc[mb][1][r] = 0.0f;
-                layer_mfma<MB, KSH>(acc, lds + L::T2, lane, gz_h, gz_l);
+                zero_acc<MB, kNB>(acc);
+                layer_mfma<MB, KSH, kNB>(acc, lds + L::T2, lane, gz_h, gz_l);
                 relu_mask<MB>(acc, a.h1h);
-                to_operands<MB, false>(acc, gz_h, gz_l);
+                to_operands<MB, false, kNB>(acc, gz_h, gz_l);
             }
 
-            // ---- first layer: dW1 += dZ1 * F^T ; db1 += sum dZ1 ; dF = W1^T dZ1 ----
+            // ---- first layer: dW1 += dZ1 * F^T ; db1 += sum dZ1 ----
             {
                 tile.template store<KSH>(gz_h, gz_l, lane, hidden_row);
                 wave_lds_fence();
-                Frag ah[MB][4], al[MB][4];
+                Frag ah[MB][kKS], al[MB][kKS];
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-                    for (int s = 0; s < 4; ++s) {
+                    for (int s = 0; s < kKS; ++s) {
                         tile.load(32 * mb + col, s, grp, true, ah[mb][s], al[mb][s]);
                         db1[mb] = frag_sum(al[mb][s], frag_sum(ah[mb][s], db1[mb]));
                     }
@@ -318,37 +401,25 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
                 tile.template store<KS1>(a.fh, a.fl, lane, input_row);
                 wave_lds_fence();
 #pragma unroll
-                for (int s = 0; s < 4; ++s) {
+                for (int s = 0; s < kKS; ++s) {
                     Frag bh, bl;
                     tile.load(col & (C - 1), s, grp, col < C, bh, bl);
 #pragma unroll
                     for (int mb = 0; mb < MB; ++mb) dW1[mb] = mfma3(ah[mb][s], al[mb][s], bh, bl, dW1[mb]);
                 }
-                wave_lds_fence();
             }
-            f32x16 dF[2];
+
+            // ---- feature gradient, transposed: dF^T[sample][channel] = dZ1^T W1, then scatter ----
+            f32x16 dFt;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) dF[0][r] = dF[1][r] = 0.0f;
+            for (int r = 0; r < 16; ++r) dFt[r] = 0.0f;
 #pragma unroll
             for (int s = 0; s < KSH; ++s) {
                 Frag th, tl;
                 load_operand(lds + L::T1 + s * 128, lane, th, tl);
-                dF[0] = mfma3(th, tl, gz_h[0][s], gz_l[0][s], dF[0]);
-                dF[1] = mfma3(th, tl, gz_h[1][s], gz_l[1][s], dF[1]);
+                dFt = mfma3(gz_h[0][s], gz_l[0][s], th, tl, dFt);
             }
-
-            // ---- scatter into the grid gradient ----
-#pragma unroll
-            for (int nb = 0; nb < 2; ++nb) {
-                const int js = j0 + 32 * nb + col;
-                if (js < S) {
-                    const Cell3 c = sample_cell(g, q, js);
-                    float vals[C / 2];
-#pragma unroll
-                    for (int k = 0; k < C / 2; ++k) vals[k] = dF[nb][k];
-                    scatter_half<KIND, C>(g, io.d_grid, q.scene, c, grp, vals);
-                }
-            }
+            scatter_channels<KIND, C>(g, io.d_grid, q.scene, info, dFt, col, grp);
         }
     }
 
@@ -390,7 +461,7 @@ template <int KIND, int C, int H, int NH>
 hipError_t launch_bwd(const GridDev& g, const MlpDev& m, const RaysDev& rays, const BwdIo& io, int n_cu,
                       hipStream_t stream)
 {
-    constexpr int kLdsBytes = MlpLds<C, H, NH, true>::bytes(kWaves);
+    constexpr int kLdsBytes = MlpLds<C, H, NH, true, kNB>::bytes(kWaves);
     static_assert(kLdsBytes <= 160 * 1024, "LDS budget of a gfx950 compute unit");
     auto kernel = bwd_mfma_kernel<KIND, C, H, NH>;
     hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);

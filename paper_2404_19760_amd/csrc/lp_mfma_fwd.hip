@@ -20,7 +20,7 @@ template <int KIND, int C, int H, int NH>
 __global__ __launch_bounds__(kWaves * 64) void fwd_mfma_kernel(GridDev g, MlpDev m, RaysDev rays, FwdOut out)
 {
     extern __shared__ uint4 lds[];
-    stage_mlp<C, H, NH, false>(lds, m);
+    stage_mlp<C, H, NH, false, 2>(lds, m);
     __syncthreads();
 
     const int lane = threadIdx.x & 63;
@@ -33,8 +33,8 @@ __global__ __launch_bounds__(kWaves * 64) void fwd_mfma_kernel(GridDev g, MlpDev
         float acc_r = 0.0f, acc_g = 0.0f, acc_b = 0.0f, acc_d = 0.0f;  // per-lane partial sums
 
         for (int j0 = 0; j0 < S; j0 += 64) {
-            StepActs<C, H, NH> a;
-            forward_step<KIND, C, H, NH, false>(g, lds, q, j0, S, lane, a);
+            StepActs<C, H, NH, 2> a;
+            forward_step<KIND, C, H, NH, false, 2>(g, lds, q, j0, S, lane, a);
 
             // heads and emission-absorption update; lane l owns sample j0 + l
             const int j = j0 + lane;
@@ -70,7 +70,7 @@ template <int KIND, int C, int H, int NH>
 hipError_t launch_fwd(const GridDev& g, const MlpDev& m, const RaysDev& rays, const FwdOut& out, int n_cu,
                       hipStream_t stream)
 {
-    constexpr int kLdsBytes = MlpLds<C, H, NH, false>::bytes(kWaves);
+    constexpr int kLdsBytes = MlpLds<C, H, NH, false, 2>::bytes(kWaves);
     auto kernel = fwd_mfma_kernel<KIND, C, H, NH>;
     hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (e != hipSuccess) return e;

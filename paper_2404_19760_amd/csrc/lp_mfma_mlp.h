@@ -8,7 +8,8 @@
 namespace lp {
 
 // Shapes: C input channels, H hidden width, NH hidden layers (1 or 2), 4 outputs.
-template <int C, int H, int NH, bool BWD>
+// NB = N blocks of 32 samples per step (2 in the forward kernel, 1 in the backward).
+template <int C, int H, int NH, bool BWD, int NB = 2>
 struct MlpLds {
     static constexpr int MB = H / 32;   // 32-row blocks of a hidden layer
     static constexpr int KS1 = C / 16;  // K-steps over the input channels
@@ -26,18 +27,21 @@ struct MlpLds {
     static constexpr int BIAS = W_END;                             // floats: b1[H] b2[H] bout[4]
     static constexpr int BIAS_UNITS = (2 * H + 4 + 3) / 4;
     static constexpr int TILE = BIAS + BIAS_UNITS;                 // per-wave transpose tiles (backward)
-    // tile: two planes (hi, lo) of [H + 4 rows][72 halfwords]; 64 samples + 8 pad per row
+    // tile: two planes (hi, lo) of [H + 4 rows][32 NB samples + 8 pad] halfwords; the pad makes
+    // the 128-bit operand loads of 8 consecutive lanes fall into distinct banks
     static constexpr int TILE_ROWS = H + 4;
-    static constexpr int TILE_RS = 72;                              // halfwords per row (144 B)
+    static constexpr int TILE_RS = 32 * NB + 8;                     // halfwords per row
     static constexpr int TILE_PLANE_UNITS = TILE_ROWS * TILE_RS * 2 / 16;
-    static constexpr int TILE_UNITS = 2 * TILE_PLANE_UNITS;
+    // per-sample scatter records: 32 NB samples x 16 dwords (weights and corner offsets)
+    static constexpr int INFO_UNITS = 32 * NB * 4;
+    static constexpr int TILE_UNITS = 2 * TILE_PLANE_UNITS + INFO_UNITS;
     static constexpr int bytes(int waves) { return (TILE + (BWD ? waves * TILE_UNITS : 0)) * 16; }
 };
 
-template <int C, int H, int NH, bool BWD>
+template <int C, int H, int NH, bool BWD, int NB>
 __device__ __forceinline__ void stage_mlp(uint4* lds, const MlpDev& m)
 {
-    using L = MlpLds<C, H, NH, BWD>;
+    using L = MlpLds<C, H, NH, BWD, NB>;
     constexpr int MB = L::MB, KS1 = L::KS1, KSH = L::KSH;
     auto hidden_col = [](int s, int gg, int e) { return k_hidden(s, gg, e); };
     auto block_row = [](int mb, int i) { return 32 * mb + i; };
@@ -70,8 +74,8 @@ __device__ __forceinline__ void stage_mlp(uint4* lds, const MlpDev& m)
 }
 
 // accumulators of a hidden layer start from the bias of the rows each register holds
-template <int MB>
-__device__ __forceinline__ void init_bias(f32x16 (&acc)[MB][2], const float* bias, int grp)
+template <int MB, int NB>
+__device__ __forceinline__ void init_bias(f32x16 (&acc)[MB][NB], const float* bias, int grp)
 {
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
@@ -79,14 +83,27 @@ __device__ __forceinline__ void init_bias(f32x16 (&acc)[MB][2], const float* bia
         for (int q = 0; q < 4; ++q) {
             const f32x4 b = *reinterpret_cast<const f32x4*>(bias + 32 * mb + 8 * q + 4 * grp);
 #pragma unroll
-            for (int p = 0; p < 4; ++p) acc[mb][0][4 * q + p] = acc[mb][1][4 * q + p] = b[p];
+            for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                for (int p = 0; p < 4; ++p) acc[mb][nb][4 * q + p] = b[p];
         }
 }
 
+template <int MB, int NB>
+__device__ __forceinline__ void zero_acc(f32x16 (&acc)[MB][NB])
+{
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mb][nb][r] = 0.0f;
+}
+
 // acc[mb][nb] += A[mb][s] * B[nb][s] over KS K-steps, A from LDS at `a_base`
-template <int MB, int KS>
-__device__ __forceinline__ void layer_mfma(f32x16 (&acc)[MB][2], const uint4* a_base, int lane,
-                                           const Frag (&bh)[2][KS], const Frag (&bl)[2][KS])
+template <int MB, int KS, int NB>
+__device__ __forceinline__ void layer_mfma(f32x16 (&acc)[MB][NB], const uint4* a_base, int lane,
+                                           const Frag (&bh)[NB][KS], const Frag (&bl)[NB][KS])
 {
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
@@ -94,17 +111,17 @@ __device__ __forceinline__ void layer_mfma(f32x16 (&acc)[MB][2], const uint4* a_
         for (int s = 0; s < KS; ++s) {
             Frag ah, al;
             load_operand(a_base + (mb * KS + s) * 128, lane, ah, al);
-            acc[mb][0] = mfma3(ah, al, bh[0][s], bl[0][s], acc[mb][0]);
-            acc[mb][1] = mfma3(ah, al, bh[1][s], bl[1][s], acc[mb][1]);
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = mfma3(ah, al, bh[nb][s], bl[nb][s], acc[mb][nb]);
         }
 }
 
 // D registers of a layer (optionally through ReLU) -> B operands of the next contraction
-template <int MB, bool RELU>
-__device__ __forceinline__ void to_operands(const f32x16 (&acc)[MB][2], Frag (&bh)[2][2 * MB], Frag (&bl)[2][2 * MB])
+template <int MB, bool RELU, int NB>
+__device__ __forceinline__ void to_operands(const f32x16 (&acc)[MB][NB], Frag (&bh)[NB][2 * MB], Frag (&bl)[NB][2 * MB])
 {
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb)
+    for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
         for (int s = 0; s < 2 * MB; ++s) {
             float v[8];
@@ -119,13 +136,15 @@ __device__ __forceinline__ void to_operands(const f32x16 (&acc)[MB][2], Frag (&b
 
 // Everything the forward of one 64-sample step produces.  The forward kernel uses z only; the
 // backward keeps the operand fragments (they are the activations, already split).
-template <int C, int H, int NH>
+template <int C, int H, int NH, int NB>
 struct StepActs {
     static constexpr int KS1 = C / 16, KSH = H / 16;
-    Frag fh[2][KS1], fl[2][KS1];    // interpolated features (layer-1 B operands)
-    Frag h1h[2][KSH], h1l[2][KSH];  // hidden layer 1 after ReLU
-    Frag h2h[2][KSH], h2l[2][KSH];  // hidden layer 2 after ReLU (NH == 2)
-    float z[4];                     // decoder outputs of sample j0 + lane
+    Frag fh[NB][KS1], fl[NB][KS1];    // interpolated features (layer-1 B operands)
+    Frag h1h[NB][KSH], h1l[NB][KSH];  // hidden layer 1 after ReLU
+    Frag h2h[NB][KSH], h2l[NB][KSH];  // hidden layer 2 after ReLU (NH == 2)
+    float z[4];                       // decoder outputs of the lane's sample: j0 + lane for NB = 2,
+                                      // j0 + (lane & 31) in both lane groups for NB = 1
+    Cell3 cell[NB];                   // grid cell of sample (lane & 31) of every N block
 };
 
 struct RayGeom {
@@ -154,53 +173,57 @@ __device__ __forceinline__ Cell3 sample_cell(const GridDev& g, const RayGeom& q,
                    (double)q.oz + t * (double)q.dz);
 }
 
-template <int KIND, int C, int H, int NH, bool BWD>
+template <int KIND, int C, int H, int NH, bool BWD, int NB>
 __device__ __forceinline__ void forward_step(const GridDev& g, const uint4* lds, const RayGeom& q, int j0, int S,
-                                             int lane, StepActs<C, H, NH>& a)
+                                             int lane, StepActs<C, H, NH, NB>& a)
 {
-    using L = MlpLds<C, H, NH, BWD>;
+    using L = MlpLds<C, H, NH, BWD, NB>;
     constexpr int MB = L::MB, KS1 = L::KS1, KSH = L::KSH;
     const int col = lane & 31, grp = lane >> 5;
     const float* sbias = reinterpret_cast<const float*>(lds + L::BIAS);
 
-    // sample + interpolate this lane's half of the channels of samples col and 32 + col
+    // sample + interpolate this lane's half of the channels of sample col of every N block
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
+    for (int nb = 0; nb < NB; ++nb) {
         const int j = min(j0 + 32 * nb + col, S - 1);
         const Cell3 c = sample_cell(g, q, j);
+        a.cell[nb] = c;
         float feat[C / 2];
         gather_half<KIND, C, C / 2>(g, q.scene, c, grp * (C / 2), feat);
 #pragma unroll
         for (int s = 0; s < KS1; ++s) split8(feat + 8 * s, a.fh[nb][s], a.fl[nb][s]);
     }
 
-    f32x16 acc[MB][2];
-    init_bias<MB>(acc, sbias, grp);
-    layer_mfma<MB, KS1>(acc, lds + L::A1, lane, a.fh, a.fl);
-    to_operands<MB, true>(acc, a.h1h, a.h1l);
+    f32x16 acc[MB][NB];
+    init_bias<MB, NB>(acc, sbias, grp);
+    layer_mfma<MB, KS1, NB>(acc, lds + L::A1, lane, a.fh, a.fl);
+    to_operands<MB, true, NB>(acc, a.h1h, a.h1l);
     if constexpr (NH == 2) {
-        init_bias<MB>(acc, sbias + H, grp);
-        layer_mfma<MB, KSH>(acc, lds + L::A2, lane, a.h1h, a.h1l);
-        to_operands<MB, true>(acc, a.h2h, a.h2l);
+        init_bias<MB, NB>(acc, sbias + H, grp);
+        layer_mfma<MB, KSH, NB>(acc, lds + L::A2, lane, a.h1h, a.h1l);
+        to_operands<MB, true, NB>(acc, a.h2h, a.h2l);
     }
-    const Frag (&lh)[2][KSH] = NH == 2 ? a.h2h : a.h1h;
-    const Frag (&ll)[2][KSH] = NH == 2 ? a.h2l : a.h1l;
+    const Frag (&lh)[NB][KSH] = NH == 2 ? a.h2h : a.h1h;
+    const Frag (&ll)[NB][KSH] = NH == 2 ? a.h2l : a.h1l;
 
-    // output layer: 4 rows replicated for both lane groups; lanes 0..31 take N block 0 and
-    // lanes 32..63 N block 1, so that lane l owns sample j0 + l
-    f32x16 o0, o1;
+    // output layer: its 4 rows are replicated in rows 0..3 and 4..7, so both lane groups of a
+    // sample column hold them.  NB = 2: lanes 0..31 take N block 0, lanes 32..63 N block 1, so
+    // that lane l owns sample j0 + l.  NB = 1: both lane groups own sample j0 + col.
+    f32x16 o[NB];
     const f32x4 b = *reinterpret_cast<const f32x4*>(sbias + 2 * H);
 #pragma unroll
-    for (int r = 0; r < 16; ++r) o0[r] = o1[r] = r < 4 ? b[r] : 0.0f;
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[nb][r] = r < 4 ? b[r] : 0.0f;
 #pragma unroll
     for (int s = 0; s < KSH; ++s) {
         Frag ah, al;
         load_operand(lds + L::A3 + s * 128, lane, ah, al);
-        o0 = mfma3(ah, al, lh[0][s], ll[0][s], o0);
-        o1 = mfma3(ah, al, lh[1][s], ll[1][s], o1);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) o[nb] = mfma3(ah, al, lh[nb][s], ll[nb][s], o[nb]);
     }
 #pragma unroll
-    for (int k = 0; k < 4; ++k) a.z[k] = grp ? o1[k] : o0[k];
+    for (int k = 0; k < 4; ++k) a.z[k] = (NB == 2 && grp) ? o[NB - 1][k] : o[0][k];
 }
 
 }  // namespace lp
