@@ -33,6 +33,8 @@ def parse():
     ap.add_argument("--math", default="default", choices=["default", "generic", "bf16x3"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device-to-device copy kernel (reference for HBM counters)")
     return ap.parse_args()
 
 
@@ -109,6 +111,16 @@ def main():
         lp.lp_render_bwd(grid, mlp, rays, bg, d_rgb, None, None, cache, d_grid, dW, db, ws, mode)
         e3.record()
         return (e0, e1, e2, e3) if timed else None
+
+    if args.calibrate_copy:
+        # a copy kernel of known traffic (1 GiB read + 1 GiB written) for scaling the
+        # FETCH_SIZE / WRITE_SIZE counters of a profiler run of this same command
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step(False)

@@ -38,20 +38,32 @@ __device__ __forceinline__ bf16x8 as_bf16x8(const Frag& f)
     return __builtin_bit_cast(bf16x8, f);
 }
 
-// hi = bf16(x) (round to nearest even), lo = bf16(x - hi); two values per dword.
+// hi = bf16(x) (round to nearest even), lo = bf16(x - hi); two values per dword.  The
+// residuals x - hi are exact in fp32; each is one dot-product instruction on the packed hi
+// pair: x0 + (hi0, hi1).(-1, 0) and x1 + (hi0, hi1).(0, -1).
 __device__ __forceinline__ void split2(float x0, float x1, uint32_t& hi, uint32_t& lo)
 {
     bf16x2 h;
     h[0] = (__bf16)x0;
     h[1] = (__bf16)x1;
-    const uint32_t hb = __builtin_bit_cast(uint32_t, h);
-    const float f0 = __uint_as_float(hb << 16);
-    const float f1 = __uint_as_float(hb & 0xffff0000u);
+    // (-1, -0): the natural (-1, +0) = 0x0000bf80 is turned into the inline constant "-1.0",
+    // which this instruction does not read as a packed bf16 pair
+    const bf16x2 sel0 = __builtin_bit_cast(bf16x2, 0x8000bf80u);
+    const bf16x2 sel1 = __builtin_bit_cast(bf16x2, 0xbf800000u);  // (0, -1)
+    const float r0 = __builtin_amdgcn_fdot2_f32_bf16(h, sel0, x0, false);
+    const float r1 = __builtin_amdgcn_fdot2_f32_bf16(h, sel1, x1, false);
     bf16x2 l;
-    l[0] = (__bf16)(x0 - f0);
-    l[1] = (__bf16)(x1 - f1);
-    hi = hb;
+    l[0] = (__bf16)r0;
+    l[1] = (__bf16)r1;
+    hi = __builtin_bit_cast(uint32_t, h);
     lo = __builtin_bit_cast(uint32_t, l);
+}
+
+// max(x, 0) as one integer instruction: a float with its sign bit set is a negative integer
+// (-0.0 included), any other float is unchanged.
+__device__ __forceinline__ float relu_f(float x)
+{
+    return __int_as_float(max(__float_as_int(x), 0));
 }
 
 __device__ __forceinline__ void split8(const float* x, Frag& hi, Frag& lo)

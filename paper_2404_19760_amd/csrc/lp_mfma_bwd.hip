@@ -134,15 +134,19 @@ __device__ __forceinline__ void write_scatter_record(float* rec, const GridDev& 
     }
 }
 
-// This lane (channel `ch` of lane group `grp`) holds in dFt the feature gradient of the samples
-// d_row(r, grp), r = 0..15, of the step: four runs of four consecutive samples.  Consecutive
-// samples in the same cell are summed before one atomic add per corner; the lanes ch = 0..C-1
-// of a group address consecutive floats.
+// This lane (channel `ch` of lane group `grp`) holds in dFt[r] the feature gradient of MFMA
+// column d_row(r, grp), which (permuted step) is sample 16 grp + r of the step: 16 consecutive
+// samples in ray order.  Consecutive samples in the same cell are summed before one atomic add
+// per corner; the lanes ch = 0..C-1 of a group address consecutive floats.
 template <int KIND, int C>
 __device__ __forceinline__ void scatter_channels(const GridDev& g, float* const d_grid[3], int scene,
                                                  const float* info, const f32x16& dFt, int ch, int grp)
 {
+#ifdef LP_X_NOSCATTER
+    const bool live = ch < C && dFt[0] == 12345.0f;
+#else
     const bool live = ch < C;
+#endif
     if constexpr (KIND == LP_GRID_VOXEL) {
         float* V = d_grid[0] + (size_t)scene * g.N[0] * g.N[1] * g.N[2] * C + ch;
         const unsigned sz = C, sy = (unsigned)g.N[2] * C, sx = (unsigned)g.N[1] * sy;
@@ -153,29 +157,26 @@ __device__ __forceinline__ void scatter_channels(const GridDev& g, float* const 
                     atomicAdd(V + (base + (d >> 2) * sx + ((d >> 1) & 1) * sy + (d & 1) * sz), acc[d]);
             }
         };
+        float acc[8];
+        unsigned prev = 0;
 #pragma unroll
-        for (int qd = 0; qd < 4; ++qd) {
-            float acc[8];
-            unsigned prev = 0;
+        for (int r = 0; r < 16; ++r) {
+            const float* rec = info + d_row(r, grp) * 16;
+            const float4 w0 = reinterpret_cast<const float4*>(rec)[0];
+            const float4 w1 = reinterpret_cast<const float4*>(rec)[1];
+            const unsigned base = reinterpret_cast<const unsigned*>(rec)[8];
+            const float w[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
+            const float v = dFt[r];
+            if (r > 0 && base != prev) {
+                flush(prev, acc);
 #pragma unroll
-            for (int p = 0; p < 4; ++p) {
-                const float* rec = info + (8 * qd + 4 * grp + p) * 16;
-                const float4 w0 = reinterpret_cast<const float4*>(rec)[0];
-                const float4 w1 = reinterpret_cast<const float4*>(rec)[1];
-                const unsigned base = reinterpret_cast<const unsigned*>(rec)[8];
-                const float w[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
-                const float v = dFt[4 * qd + p];
-                if (p > 0 && base != prev) {
-                    flush(prev, acc);
-#pragma unroll
-                    for (int d = 0; d < 8; ++d) acc[d] = 0.0f;
-                }
-#pragma unroll
-                for (int d = 0; d < 8; ++d) acc[d] = p == 0 ? w[d] * v : acc[d] + w[d] * v;
-                prev = base;
+                for (int d = 0; d < 8; ++d) acc[d] = 0.0f;
             }
-            flush(prev, acc);
+#pragma unroll
+            for (int d = 0; d < 8; ++d) acc[d] = r == 0 ? w[d] * v : acc[d] + w[d] * v;
+            prev = base;
         }
+        flush(prev, acc);
     } else {
         float* P[3];
         unsigned sa[3];
@@ -191,33 +192,30 @@ __device__ __forceinline__ void scatter_channels(const GridDev& g, float* const 
                 for (int d = 0; d < 4; ++d) atomicAdd(P[pl] + (base + (d >> 1) * sa[pl] + (d & 1) * C), acc[d]);
             }
         };
+        float acc[12];
+        unsigned prev[3] = {0, 0, 0};
 #pragma unroll
-        for (int qd = 0; qd < 4; ++qd) {
-            float acc[12];
-            unsigned prev[3] = {0, 0, 0};
+        for (int r = 0; r < 16; ++r) {
+            const float* rec = info + d_row(r, grp) * 16;
+            const uint4 bases = reinterpret_cast<const uint4*>(rec)[3];
+            const unsigned base[3] = {bases.x, bases.y, bases.z};
+            const float v = dFt[r];
 #pragma unroll
-            for (int p = 0; p < 4; ++p) {
-                const float* rec = info + (8 * qd + 4 * grp + p) * 16;
-                const uint4 bases = reinterpret_cast<const uint4*>(rec)[3];
-                const unsigned base[3] = {bases.x, bases.y, bases.z};
-                const float v = dFt[4 * qd + p];
+            for (int pl = 0; pl < 3; ++pl) {
+                const float4 w4 = reinterpret_cast<const float4*>(rec)[pl];
+                const float w[4] = {w4.x, w4.y, w4.z, w4.w};
+                if (r > 0 && base[pl] != prev[pl]) {
+                    flush(pl, prev[pl], acc + 4 * pl);
 #pragma unroll
-                for (int pl = 0; pl < 3; ++pl) {
-                    const float4 w4 = reinterpret_cast<const float4*>(rec)[pl];
-                    const float w[4] = {w4.x, w4.y, w4.z, w4.w};
-                    if (p > 0 && base[pl] != prev[pl]) {
-                        flush(pl, prev[pl], acc + 4 * pl);
-#pragma unroll
-                        for (int d = 0; d < 4; ++d) acc[4 * pl + d] = 0.0f;
-                    }
-#pragma unroll
-                    for (int d = 0; d < 4; ++d) acc[4 * pl + d] = p == 0 ? w[d] * v : acc[4 * pl + d] + w[d] * v;
-                    prev[pl] = base[pl];
+                    for (int d = 0; d < 4; ++d) acc[4 * pl + d] = 0.0f;
                 }
-            }
 #pragma unroll
-            for (int pl = 0; pl < 3; ++pl) flush(pl, prev[pl], acc + 4 * pl);
+                for (int d = 0; d < 4; ++d) acc[4 * pl + d] = r == 0 ? w[d] * v : acc[4 * pl + d] + w[d] * v;
+                prev[pl] = base[pl];
+            }
         }
+#pragma unroll
+        for (int pl = 0; pl < 3; ++pl) flush(pl, prev[pl], acc + 4 * pl);
     }
 }
 
@@ -275,24 +273,29 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
 
         for (int j0 = ((S - 1) / kStep) * kStep; j0 >= 0; j0 -= kStep) {
             StepActs<C, H, NH, kNB> a;
-            forward_step<KIND, C, H, NH, true, kNB>(g, lds, q, j0, S, lane, a);
+            forward_step<KIND, C, H, NH, true, kNB, true>(g, lds, q, j0, S, lane, a);
 
-            // ---- emission-absorption backward for sample j0 + col (both lane groups alike) ----
-            const int j = j0 + col;
+            // ---- emission-absorption backward; MFMA column col stands for sample
+            //      j0 + slot_to_sample(col) (both lane groups alike), so the scans along the
+            //      ray run on values moved into sample order and their results are moved back ----
+            const int to_slot = sample_to_slot(col), to_smp = slot_to_sample(col);
+            const int j = j0 + to_smp;
             const bool valid = j < S;
             const float t = q.near + ((float)j + 0.5f) * q.delta;
             const float sd = valid ? fast_softplus(a.z[0]) * q.delta : 0.0f;
-            const float incl = group_scan_incl<kStep>(sd, col);
-            const float tau_start = tau_end - __shfl(incl, kStep - 1, kStep);
+            const float incl_ord = group_scan_incl<kStep>(__shfl(sd, to_slot, kStep), col);
+            const float incl = __shfl(incl_ord, to_smp, kStep);
+            const float tau_start = tau_end - __shfl(incl_ord, kStep - 1, kStep);
             const float Tprev = __expf(-(tau_start + (incl - sd)));
             const float w = Tprev * one_minus_exp_neg(sd);
             const float Tq = Tprev - w;
             const float c1 = fast_logistic(a.z[1]), c2 = fast_logistic(a.z[2]), c3 = fast_logistic(a.z[3]);
             const float aa = p0 * c1 + p1 * c2 + p2 * c3 + p_depth * t;
             const float wa = w * aa;
-            const float suf = group_scan_suffix<kStep>(wa, col);
+            const float suf_ord = group_scan_suffix<kStep>(__shfl(wa, to_slot, kStep), col);
+            const float suf = __shfl(suf_ord, to_smp, kStep);
             const float dsigma = q.delta * (Tq * aa - (suf - wa + carry) + kS);
-            carry += __shfl(suf, 0, kStep);
+            carry += __shfl(suf_ord, 0, kStep);
             tau_end = tau_start;
             float dz[4];
             dz[0] = valid ? dsigma * fast_logistic(a.z[0]) : 0.0f;

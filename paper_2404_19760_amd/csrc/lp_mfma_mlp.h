@@ -128,7 +128,7 @@ __device__ __forceinline__ void to_operands(const f32x16 (&acc)[MB][NB], Frag (&
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const float x = acc[s / 2][nb][8 * (s % 2) + e];
-                v[e] = RELU ? fmaxf(x, 0.0f) : x;
+                v[e] = RELU ? relu_f(x) : x;
             }
             split8(v, bh[nb][s], bl[nb][s]);
         }
@@ -173,7 +173,19 @@ __device__ __forceinline__ Cell3 sample_cell(const GridDev& g, const RayGeom& q,
                    (double)q.oz + t * (double)q.dz);
 }
 
-template <int KIND, int C, int H, int NH, bool BWD, int NB>
+// Sample (within a 32-sample step) that MFMA column `slot` stands for when the step is
+// permuted so that each lane group's D registers of a [sample x channel] block hold 16
+// CONSECUTIVE samples: slot 8q + 4g + p  <->  sample 16g + 4q + p.
+__host__ __device__ constexpr int slot_to_sample(int slot)
+{
+    return 16 * ((slot >> 2) & 1) + 4 * (slot >> 3) + (slot & 3);
+}
+__host__ __device__ constexpr int sample_to_slot(int smp)
+{
+    return 8 * ((smp >> 2) & 3) + 4 * (smp >> 4) + (smp & 3);
+}
+
+template <int KIND, int C, int H, int NH, bool BWD, int NB, bool PERM = false>
 __device__ __forceinline__ void forward_step(const GridDev& g, const uint4* lds, const RayGeom& q, int j0, int S,
                                              int lane, StepActs<C, H, NH, NB>& a)
 {
@@ -185,7 +197,7 @@ __device__ __forceinline__ void forward_step(const GridDev& g, const uint4* lds,
     // sample + interpolate this lane's half of the channels of sample col of every N block
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
-        const int j = min(j0 + 32 * nb + col, S - 1);
+        const int j = min(j0 + 32 * nb + (PERM ? slot_to_sample(col) : col), S - 1);
         const Cell3 c = sample_cell(g, q, j);
         a.cell[nb] = c;
         float feat[C / 2];
