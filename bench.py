@@ -22,6 +22,11 @@ import numpy as np
 
 HBM_PEAK_GBS = 8000.0
 
+# HBM bytes per launch of the backward kernel from two rocprofv3 --pmc runs (FETCH_SIZE scaled
+# by 2.0, WRITE_SIZE by 1.0 against a 1 GiB copy kernel in the same run); the summary with the
+# commands is profiles/large_voxel256_fwd_bwd_kernels.md.  None = not measured for that workload.
+MEASURED_BWD_HBM_BYTES = {"large": 0.263e9 + 65.42e9}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -32,7 +37,7 @@ def parse():
                     help="workload: tiny | single_scene | voxel | batched | large")
     ap.add_argument("--math", default="default", choices=["default", "generic", "bf16x3"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--cpu-seconds", type=float, default=20.0)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy kernel (reference for HBM counters)")
     return ap.parse_args()
@@ -54,7 +59,7 @@ def cpu_baseline(inp, budget_s: float):
         oracle.render_bwd(prob, p)      # recomputes the forward internally, then reverses it
         return time.perf_counter() - t0, sub.n_rays
 
-    t_probe, n_probe = run(min(256, inp.n_rays))
+    t_probe, n_probe = run(min(1024, inp.n_rays))
     n = int(max(n_probe, min(inp.n_rays, n_probe * budget_s / max(t_probe, 1e-3))))
     t, n = run(n)
     return {"value": n * inp.samples / t, "unit": "ray-samples/s", "cores": oracle.num_threads(),
@@ -159,7 +164,8 @@ def main():
         "fwd_bwd_effective": {"algorithmic_GBs": 3 * g_bytes * samples / ((fwd_avg + bwd_avg) * 1e-3) / 1e9,
                               "frac_hbm_peak": 3 * g_bytes * samples / ((fwd_avg + bwd_avg) * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "roofline": {"kernel": "lp_render_bwd", "bound": "hbm", "achieved": bwd_gbs, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": bwd_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "unit": "GB/s", "frac": bwd_gbs / HBM_PEAK_GBS,
+                     "traffic": MEASURED_BWD_HBM_BYTES.get(args.config) if fast else None,
                      "bytes_per_sample": 2 * g_bytes, "ms": bwd_avg},
     }
     if not args.no_cpu_baseline:

@@ -16,11 +16,15 @@ namespace {
 
 constexpr int kWaves = 4;
 
-template <int KIND, int C, int H, int NH>
+// NB = N blocks of 32 samples per step.  NB = 2: lane l owns sample l of the 64-sample step.
+// NB = 1 (half the registers, two waves per SIMD for the wide MLPs): both lane groups hold the
+// decoder outputs of sample (lane & 31); group 0 alone accumulates.
+template <int KIND, int C, int H, int NH, int NB>
 __global__ __launch_bounds__(kWaves * 64) void fwd_mfma_kernel(GridDev g, MlpDev m, RaysDev rays, FwdOut out)
 {
+    constexpr int kStep = 32 * NB;
     extern __shared__ uint4 lds[];
-    stage_mlp<C, H, NH, false, 2>(lds, m);
+    stage_mlp<C, H, NH, false, NB>(lds, m);
     __syncthreads();
 
     const int lane = threadIdx.x & 63;
@@ -32,22 +36,23 @@ __global__ __launch_bounds__(kWaves * 64) void fwd_mfma_kernel(GridDev g, MlpDev
         float tau = 0.0f;                                              // optical depth of earlier steps
         float acc_r = 0.0f, acc_g = 0.0f, acc_b = 0.0f, acc_d = 0.0f;  // per-lane partial sums
 
-        for (int j0 = 0; j0 < S; j0 += 64) {
-            StepActs<C, H, NH, 2> a;
-            forward_step<KIND, C, H, NH, false, 2>(g, lds, q, j0, S, lane, a);
+        for (int j0 = 0; j0 < S; j0 += kStep) {
+            StepActs<C, H, NH, NB> a;
+            forward_step<KIND, C, H, NH, false, NB>(g, lds, q, j0, S, lane, a);
 
-            // heads and emission-absorption update; lane l owns sample j0 + l
-            const int j = j0 + lane;
+            // heads and emission-absorption update; the lane owns sample j0 + pos
+            const int pos = lane & (kStep - 1);
+            const int j = j0 + pos;
             const float t = q.near + ((float)j + 0.5f) * q.delta;
             const float sd = j < S ? fast_softplus(a.z[0]) * q.delta : 0.0f;
-            const float incl = wave_scan_incl(sd, lane);
+            const float incl = group_scan_incl<kStep>(sd, pos);
             const float Tprev = __expf(-(tau + (incl - sd)));
-            const float w = Tprev * one_minus_exp_neg(sd);
+            const float w = (NB == 2 || lane < 32) ? Tprev * one_minus_exp_neg(sd) : 0.0f;
             acc_r += w * fast_logistic(a.z[1]);
             acc_g += w * fast_logistic(a.z[2]);
             acc_b += w * fast_logistic(a.z[3]);
             acc_d += w * t;
-            tau += __shfl(incl, 63, 64);
+            tau += __shfl(incl, kStep - 1, kStep);
         }
 
         acc_r = wave_sum(acc_r);
@@ -66,16 +71,16 @@ __global__ __launch_bounds__(kWaves * 64) void fwd_mfma_kernel(GridDev g, MlpDev
     }
 }
 
-template <int KIND, int C, int H, int NH>
+template <int KIND, int C, int H, int NH, int NB>
 hipError_t launch_fwd(const GridDev& g, const MlpDev& m, const RaysDev& rays, const FwdOut& out, int n_cu,
                       hipStream_t stream)
 {
-    constexpr int kLdsBytes = MlpLds<C, H, NH, false, 2>::bytes(kWaves);
-    auto kernel = fwd_mfma_kernel<KIND, C, H, NH>;
+    constexpr int kLdsBytes = MlpLds<C, H, NH, false, NB>::bytes(kWaves);
+    auto kernel = fwd_mfma_kernel<KIND, C, H, NH, NB>;
     hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (e != hipSuccess) return e;
-    // persistent grid: two workgroups per compute unit, a multiple of the 8 XCDs, no more than the rays need
-    long long blocks = 2LL * n_cu;
+    // persistent grid: as many workgroups as fit a compute unit's registers, a multiple of the 8 XCDs, no more than the rays need
+    long long blocks = (long long)(NB == 1 ? 3 : 2) * n_cu;
     const long long need = (rays.M + kWaves - 1) / kWaves;
     if (blocks > need) blocks = need;
     blocks = (blocks + 7) / 8 * 8;
@@ -89,7 +94,7 @@ hipError_t dispatch_fwd(const GridDev& g, const MlpDev& m, const RaysDev& rays, 
 {
     const int C = g.C, H = m.dims[1], NH = m.n_layers - 1;
 #define LP_CASE(c, h, nh) \
-    if (C == c && H == h && NH == nh) return launch_fwd<KIND, c, h, nh>(g, m, rays, out, n_cu, stream);
+    if (C == c && H == h && NH == nh) return launch_fwd<KIND, c, h, nh, 2>(g, m, rays, out, n_cu, stream);
     LP_CASE(16, 32, 1) LP_CASE(16, 64, 1) LP_CASE(32, 32, 1) LP_CASE(32, 64, 1)
     LP_CASE(16, 32, 2) LP_CASE(16, 64, 2) LP_CASE(32, 32, 2) LP_CASE(32, 64, 2)
 #undef LP_CASE
