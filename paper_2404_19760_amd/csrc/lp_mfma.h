@@ -150,28 +150,25 @@ __device__ __forceinline__ void load_operand(const uint4* blk, int lane, Frag& h
     lo.d[0] = l.x; lo.d[1] = l.y; lo.d[2] = l.z; lo.d[3] = l.w;
 }
 
-// Inclusive prefix sum over groups of W consecutive lanes (W = 64: the whole wave; W = 32: each
-// half on its own); `pos` is the lane's position inside its group.
-template <int W>
-__device__ __forceinline__ float group_scan_incl(float v, int pos)
+// v shifted by data-parallel-primitive control `CTRL` (lanes without a source get 0).
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_or_zero(float v)
 {
-#pragma unroll
-    for (int d = 1; d < W; d <<= 1) {
-        const float u = __shfl_up(v, d, W);
-        if (pos >= d) v += u;
-    }
-    return v;
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xf, false));
 }
 
-// Inclusive suffix sum (position p gets the sum over positions p..W-1 of its group).
+// Inclusive prefix sum over groups of W consecutive lanes (W = 64: the whole wave; W = 32: each
+// half on its own), on the DPP network: shifts by 1, 2, 4, 8 inside rows of 16 lanes, then
+// the last lane of a row is broadcast into the next row (and of lane 31 into the upper half).
 template <int W>
-__device__ __forceinline__ float group_scan_suffix(float v, int pos)
+__device__ __forceinline__ float group_scan_incl(float v, int /*pos*/)
 {
-#pragma unroll
-    for (int d = 1; d < W; d <<= 1) {
-        const float u = __shfl_down(v, d, W);
-        if (pos + d < W) v += u;
-    }
+    v += dpp_or_zero<0x111, 0xf>(v);  // row_shr:1
+    v += dpp_or_zero<0x112, 0xf>(v);  // row_shr:2
+    v += dpp_or_zero<0x114, 0xf>(v);  // row_shr:4
+    v += dpp_or_zero<0x118, 0xf>(v);  // row_shr:8
+    v += dpp_or_zero<0x142, 0xa>(v);  // row_bcast:15 into rows 1 and 3
+    if constexpr (W == 64) v += dpp_or_zero<0x143, 0xc>(v);  // row_bcast:31 into rows 2 and 3
     return v;
 }
 

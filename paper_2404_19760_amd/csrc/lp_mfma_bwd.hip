@@ -148,13 +148,16 @@ __device__ __forceinline__ void scatter_channels(const GridDev& g, float* const 
     const bool live = ch < C;
 #endif
     if constexpr (KIND == LP_GRID_VOXEL) {
-        float* V = d_grid[0] + (size_t)scene * g.N[0] * g.N[1] * g.N[2] * C + ch;
+        // uniform base pointer + 32-bit byte offset per lane (a scene's tensor is below 4 GiB)
+        char* V = reinterpret_cast<char*>(d_grid[0] + (size_t)scene * g.N[0] * g.N[1] * g.N[2] * C);
         const unsigned sz = C, sy = (unsigned)g.N[2] * C, sx = (unsigned)g.N[1] * sy;
         auto flush = [&](unsigned base, const float (&acc)[8]) {
             if (live) {
 #pragma unroll
-                for (int d = 0; d < 8; ++d)
-                    atomicAdd(V + (base + (d >> 2) * sx + ((d >> 1) & 1) * sy + (d & 1) * sz), acc[d]);
+                for (int d = 0; d < 8; ++d) {
+                    const unsigned off = 4u * (base + (d >> 2) * sx + ((d >> 1) & 1) * sy + (d & 1) * sz + ch);
+                    atomicAdd(reinterpret_cast<float*>(V + off), acc[d]);
+                }
             }
         };
         float acc[8];
@@ -178,18 +181,21 @@ __device__ __forceinline__ void scatter_channels(const GridDev& g, float* const 
         }
         flush(prev, acc);
     } else {
-        float* P[3];
+        char* P[3];
         unsigned sa[3];
 #pragma unroll
         for (int p = 0; p < 3; ++p) {
             const int a = p, b = (p + 1) % 3;
-            P[p] = d_grid[p] + (size_t)scene * g.N[a] * g.N[b] * C + ch;
+            P[p] = reinterpret_cast<char*>(d_grid[p] + (size_t)scene * g.N[a] * g.N[b] * C);
             sa[p] = (unsigned)g.N[b] * C;
         }
         auto flush = [&](int pl, unsigned base, const float* acc) {
             if (live) {
 #pragma unroll
-                for (int d = 0; d < 4; ++d) atomicAdd(P[pl] + (base + (d >> 1) * sa[pl] + (d & 1) * C), acc[d]);
+                for (int d = 0; d < 4; ++d) {
+                    const unsigned off = 4u * (base + (d >> 1) * sa[pl] + (d & 1) * C + ch);
+                    atomicAdd(reinterpret_cast<float*>(P[pl] + off), acc[d]);
+                }
             }
         };
         float acc[12];
@@ -292,10 +298,13 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
             const float c1 = fast_logistic(a.z[1]), c2 = fast_logistic(a.z[2]), c3 = fast_logistic(a.z[3]);
             const float aa = p0 * c1 + p1 * c2 + p2 * c3 + p_depth * t;
             const float wa = w * aa;
-            const float suf_ord = group_scan_suffix<kStep>(__shfl(wa, to_slot, kStep), col);
-            const float suf = __shfl(suf_ord, to_smp, kStep);
+            // inclusive suffix sum = total - inclusive prefix + own value
+            const float wa_ord = __shfl(wa, to_slot, kStep);
+            const float pre_ord = group_scan_incl<kStep>(wa_ord, col);
+            const float wa_total = __shfl(pre_ord, kStep - 1, kStep);
+            const float suf = __shfl(wa_total - pre_ord + wa_ord, to_smp, kStep);
             const float dsigma = q.delta * (Tq * aa - (suf - wa + carry) + kS);
-            carry += __shfl(suf_ord, 0, kStep);
+            carry += wa_total;
             tau_end = tau_start;
             float dz[4];
             dz[0] = valid ? dsigma * fast_logistic(a.z[0]) : 0.0f;

@@ -110,14 +110,14 @@ bool mfma_supported(const GridDev& g, const MlpDev& m)
     const int H = m.dims[1];
     if (H != 32 && H != 64) return false;
     if (m.n_layers == 3 && m.dims[2] != H) return false;
-    // 32-bit element offsets inside one scene's tensor, 16-byte aligned tensors
+    // 32-bit byte offsets inside one scene's tensor (below 4 GiB), 16-byte aligned tensors
     const unsigned long long n0 = (unsigned long long)g.N[0], n1 = (unsigned long long)g.N[1], n2 = (unsigned long long)g.N[2];
     const unsigned long long per_scene = n0 * n1 * n2 * g.C;  // voxel tensor of one scene
     if (g.kind == LP_GRID_VOXEL) {
-        if (per_scene >= (1ull << 31)) return false;
+        if (per_scene >= (1ull << 30)) return false;
         if ((uintptr_t)g.data[0] & 15u) return false;
     } else {
-        if (n0 * n1 * g.C >= (1ull << 31) || n1 * n2 * g.C >= (1ull << 31) || n2 * n0 * g.C >= (1ull << 31)) return false;
+        if (n0 * n1 * g.C >= (1ull << 30) || n1 * n2 * g.C >= (1ull << 30) || n2 * n0 * g.C >= (1ull << 30)) return false;
         for (int p = 0; p < 3; ++p)
             if ((uintptr_t)g.data[p] & 15u) return false;
     }
