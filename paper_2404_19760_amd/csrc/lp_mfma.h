@@ -43,18 +43,18 @@ __device__ __forceinline__ bf16x8 as_bf16x8(const Frag& f)
 // pair: x0 + (hi0, hi1).(-1, 0) and x1 + (hi0, hi1).(0, -1).
 __device__ __forceinline__ void split2(float x0, float x1, uint32_t& hi, uint32_t& lo)
 {
-    bf16x2 h;
-    h[0] = (__bf16)x0;
-    h[1] = (__bf16)x1;
+    typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
+    // one packed conversion per pair (a vector conversion keeps the two halves together)
+    const f32x2 x = {x0, x1};
+    const bf16x2 h = __builtin_convertvector(x, bf16x2);
     // (-1, -0): the natural (-1, +0) = 0x0000bf80 is turned into the inline constant "-1.0",
     // which this instruction does not read as a packed bf16 pair
     const bf16x2 sel0 = __builtin_bit_cast(bf16x2, 0x8000bf80u);
     const bf16x2 sel1 = __builtin_bit_cast(bf16x2, 0xbf800000u);  // (0, -1)
     const float r0 = __builtin_amdgcn_fdot2_f32_bf16(h, sel0, x0, false);
     const float r1 = __builtin_amdgcn_fdot2_f32_bf16(h, sel1, x1, false);
-    bf16x2 l;
-    l[0] = (__bf16)r0;
-    l[1] = (__bf16)r1;
+    const f32x2 r = {r0, r1};
+    const bf16x2 l = __builtin_convertvector(r, bf16x2);
     hi = __builtin_bit_cast(uint32_t, h);
     lo = __builtin_bit_cast(uint32_t, l);
 }
