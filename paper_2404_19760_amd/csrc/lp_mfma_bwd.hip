@@ -134,10 +134,36 @@ __device__ __forceinline__ void write_scatter_record(float* rec, const GridDev& 
     }
 }
 
+// Accumulators of the 2^NBITS corners of the current cell while a lane walks its samples in ray
+// order.  When the ray steps into the neighbouring cell along ONE axis, the corners on the
+// shared face stay (their sums move to the mirrored corner index) and only the corners left
+// behind are added to memory; any other move flushes all corners.
+template <int NBITS>
+struct CornerAcc {
+    static constexpr int N = 1 << NBITS;
+    float acc[N];
+
+    // BIT = corner-index bit of the axis stepped along; `up` = towards larger index.
+    // flush(d, value) adds `value` to corner d of the OLD cell.
+    template <int BIT, class Flush>
+    __device__ __forceinline__ void step_axis(bool up, Flush flush)
+    {
+#pragma unroll
+        for (int d = 0; d < N; ++d) {
+            if (d & BIT) continue;
+            const float lo = acc[d], hi = acc[d | BIT];
+            flush(up ? d : (d | BIT), up ? lo : hi);   // the face left behind
+            acc[d] = up ? hi : 0.0f;                   // the shared face changes side
+            acc[d | BIT] = up ? 0.0f : lo;
+        }
+    }
+};
+
 // This lane (channel `ch` of lane group `grp`) holds in dFt[r] the feature gradient of MFMA
 // column d_row(r, grp), which (permuted step) is sample 16 grp + r of the step: 16 consecutive
-// samples in ray order.  Consecutive samples in the same cell are summed before one atomic add
-// per corner; the lanes ch = 0..C-1 of a group address consecutive floats.
+// samples in ray order.  Contributions are summed per corner while the ray stays in a cell
+// (and on shared corners across a step into a neighbouring cell) before one atomic add per
+// corner; the lanes ch = 0..C-1 of a group address consecutive floats.
 template <int KIND, int C>
 __device__ __forceinline__ void scatter_channels(const GridDev& g, float* const d_grid[3], int scene,
                                                  const float* info, const f32x16& dFt, int ch, int grp)
@@ -151,17 +177,14 @@ __device__ __forceinline__ void scatter_channels(const GridDev& g, float* const 
         // uniform base pointer + 32-bit byte offset per lane (a scene's tensor is below 4 GiB)
         char* V = reinterpret_cast<char*>(d_grid[0] + (size_t)scene * g.N[0] * g.N[1] * g.N[2] * C);
         const unsigned sz = C, sy = (unsigned)g.N[2] * C, sx = (unsigned)g.N[1] * sy;
-        auto flush = [&](unsigned base, const float (&acc)[8]) {
+        CornerAcc<3> ca;
+        unsigned prev = 0;
+        auto add = [&](int d, float v) {
             if (live) {
-#pragma unroll
-                for (int d = 0; d < 8; ++d) {
-                    const unsigned off = 4u * (base + (d >> 2) * sx + ((d >> 1) & 1) * sy + (d & 1) * sz + ch);
-                    atomicAdd(reinterpret_cast<float*>(V + off), acc[d]);
-                }
+                const unsigned off = 4u * (prev + (d >> 2) * sx + ((d >> 1) & 1) * sy + (d & 1) * sz + ch);
+                atomicAdd(reinterpret_cast<float*>(V + off), v);
             }
         };
-        float acc[8];
-        unsigned prev = 0;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const float* rec = info + d_row(r, grp) * 16;
@@ -171,57 +194,64 @@ __device__ __forceinline__ void scatter_channels(const GridDev& g, float* const 
             const float w[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
             const float v = dFt[r];
             if (r > 0 && base != prev) {
-                flush(prev, acc);
+                // Keeping shared corners across a cell change pays when changes are rare; with a
+                // few samples per cell (fine voxel grids) the extra selects cost more than the
+                // atomic requests they save (measured), so voxel cells are simply flushed.
+                constexpr bool kCarryVoxel = false;
+                const bool up = base > prev;
+                const unsigned dist = up ? base - prev : prev - base;
+                if (kCarryVoxel && dist == sz) ca.template step_axis<1>(up, add);
+                else if (kCarryVoxel && dist == sy) ca.template step_axis<2>(up, add);
+                else if (kCarryVoxel && dist == sx) ca.template step_axis<4>(up, add);
+                else {
 #pragma unroll
-                for (int d = 0; d < 8; ++d) acc[d] = 0.0f;
+                    for (int d = 0; d < 8; ++d) { add(d, ca.acc[d]); ca.acc[d] = 0.0f; }
+                }
             }
-#pragma unroll
-            for (int d = 0; d < 8; ++d) acc[d] = r == 0 ? w[d] * v : acc[d] + w[d] * v;
             prev = base;
+#pragma unroll
+            for (int d = 0; d < 8; ++d) ca.acc[d] = r == 0 ? w[d] * v : ca.acc[d] + w[d] * v;
         }
-        flush(prev, acc);
+#pragma unroll
+        for (int d = 0; d < 8; ++d) add(d, ca.acc[d]);
     } else {
-        char* P[3];
-        unsigned sa[3];
 #pragma unroll
-        for (int p = 0; p < 3; ++p) {
-            const int a = p, b = (p + 1) % 3;
-            P[p] = reinterpret_cast<char*>(d_grid[p] + (size_t)scene * g.N[a] * g.N[b] * C);
-            sa[p] = (unsigned)g.N[b] * C;
-        }
-        auto flush = [&](int pl, unsigned base, const float* acc) {
-            if (live) {
-#pragma unroll
-                for (int d = 0; d < 4; ++d) {
-                    const unsigned off = 4u * (base + (d >> 1) * sa[pl] + (d & 1) * C + ch);
-                    atomicAdd(reinterpret_cast<float*>(P[pl] + off), acc[d]);
+        for (int pl = 0; pl < 3; ++pl) {
+            const int a = pl, b = (pl + 1) % 3;
+            char* P = reinterpret_cast<char*>(d_grid[pl] + (size_t)scene * g.N[a] * g.N[b] * C);
+            const unsigned sb = C, sa = (unsigned)g.N[b] * C;
+            CornerAcc<2> ca;
+            unsigned prev = 0;
+            auto add = [&](int d, float v) {
+                if (live) {
+                    const unsigned off = 4u * (prev + (d >> 1) * sa + (d & 1) * sb + ch);
+                    atomicAdd(reinterpret_cast<float*>(P + off), v);
                 }
-            }
-        };
-        float acc[12];
-        unsigned prev[3] = {0, 0, 0};
+            };
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const float* rec = info + d_row(r, grp) * 16;
-            const uint4 bases = reinterpret_cast<const uint4*>(rec)[3];
-            const unsigned base[3] = {bases.x, bases.y, bases.z};
-            const float v = dFt[r];
-#pragma unroll
-            for (int pl = 0; pl < 3; ++pl) {
+            for (int r = 0; r < 16; ++r) {
+                const float* rec = info + d_row(r, grp) * 16;
                 const float4 w4 = reinterpret_cast<const float4*>(rec)[pl];
+                const unsigned base = reinterpret_cast<const unsigned*>(rec)[12 + pl];
                 const float w[4] = {w4.x, w4.y, w4.z, w4.w};
-                if (r > 0 && base[pl] != prev[pl]) {
-                    flush(pl, prev[pl], acc + 4 * pl);
+                const float v = dFt[r];
+                if (r > 0 && base != prev) {
+                    const bool up = base > prev;
+                    const unsigned dist = up ? base - prev : prev - base;
+                    if (dist == sb) ca.template step_axis<1>(up, add);
+                    else if (dist == sa) ca.template step_axis<2>(up, add);
+                    else {
 #pragma unroll
-                    for (int d = 0; d < 4; ++d) acc[4 * pl + d] = 0.0f;
+                        for (int d = 0; d < 4; ++d) { add(d, ca.acc[d]); ca.acc[d] = 0.0f; }
+                    }
                 }
+                prev = base;
 #pragma unroll
-                for (int d = 0; d < 4; ++d) acc[4 * pl + d] = r == 0 ? w[d] * v : acc[4 * pl + d] + w[d] * v;
-                prev[pl] = base[pl];
+                for (int d = 0; d < 4; ++d) ca.acc[d] = r == 0 ? w[d] * v : ca.acc[d] + w[d] * v;
             }
-        }
 #pragma unroll
-        for (int pl = 0; pl < 3; ++pl) flush(pl, prev[pl], acc + 4 * pl);
+            for (int d = 0; d < 4; ++d) add(d, ca.acc[d]);
+        }
     }
 }
 
