@@ -174,3 +174,75 @@ def test_activation_memory_independent_of_samples(lp):
         del out
     assert ws_bytes[0] == ws_bytes[1]
     assert peaks[0] == peaks[1], peaks
+
+
+# ------------------------------------------------------------------ full size, bench launch configuration
+
+@pytest.fixture(scope="module")
+def large_full(lp):
+    """The largest configuration at full size on the GPU (640 000 rays x 512 samples), as bench.py runs it."""
+    import torch
+    inp = lp_inputs.make_inputs("large")
+    grid, mlp, rays, bg = lp.to_device(inp)
+    out = lp.render_fwd(grid, mlp, rays, bg)
+    torch.cuda.synchronize()
+    return inp, grid, mlp, rays, bg, out
+
+
+def test_large_full_size_forward_on_sampled_rays(lp, oracle, large_full):
+    """Full-size forward launch; 600 sampled rays (every 1066th, plus the first and last rays of
+    the launch and of each XCD's range) against the oracle, ray by ray."""
+    inp, grid, mlp, rays, bg, (rgb, alpha, depth, cache) = large_full
+    m = inp.n_rays
+    per_xcd = (m + 7) // 8
+    edges = [x for k in range(8) for x in (k * per_xcd, min(m, (k + 1) * per_xcd) - 1)]
+    idx = np.unique(np.concatenate([lp_inputs.strided_ray_subset(m, 580, offset=11), np.array(edges + [0, m - 1])]))
+    o_rgb, o_alpha, o_depth = oracle.render_fwd(inp.subset(idx))
+    close(rgb.cpu().numpy()[idx], o_rgb, FWD_RTOL, "large full rgb")
+    close(alpha.cpu().numpy()[idx], o_alpha, FWD_RTOL, "large full alpha")
+    close(depth.cpu().numpy()[idx], o_depth, FWD_RTOL, "large full depth")
+    # the cached scalar is the optical depth: alpha = 1 - exp(-cache)
+    np.testing.assert_allclose(1.0 - np.exp(-cache.cpu().numpy()[idx].astype(np.float64)), o_alpha, rtol=2e-4, atol=1e-6)
+
+
+def test_large_full_size_gradient_properties(lp, large_full):
+    """Properties that hold at any size, in the launch configuration bench.py times:
+    (1) gradients are additive over a partition of the rays (the full launch equals the sum of two
+        half launches, up to summation order);
+    (2) the bias gradient of the output layer predicts the change of the loss under a small shift
+        of those biases (central difference of two more forward launches, fp64 loss sums)."""
+    import torch
+    inp, grid, mlp, rays, bg, (rgb, alpha, depth, cache) = large_full
+    m = inp.n_rays
+    target = torch.from_numpy(inp.target).to("cuda:0")
+    d_rgb = (2.0 * (rgb - target) / (3.0 * m)).contiguous()
+    full = lp.render_bwd(grid, mlp, rays, bg, d_rgb, cache)
+    half = m // 2 + 37
+
+    def part(lo, hi):
+        r = lp.Rays(origins=rays.origins[lo:hi].contiguous(), dirs=rays.dirs[lo:hi].contiguous(),
+                    near=rays.near[lo:hi].contiguous(), far=rays.far[lo:hi].contiguous(), samples=rays.samples)
+        return lp.render_bwd(grid, mlp, r, bg, d_rgb[lo:hi].contiguous(), cache[lo:hi].contiguous())
+
+    a, b = part(0, half), part(half, m)
+    torch.cuda.synchronize()
+    for grp in range(3):
+        for f, x, y in zip(full[grp], a[grp], b[grp]):
+            f64 = f.double()
+            s64 = x.double() + y.double()
+            l2 = float((f64 - s64).norm() / f64.norm())
+            assert l2 < 1e-4, (grp, l2)
+
+    # directional derivative along a shift of the output-layer biases
+    direction = torch.tensor([0.3, -0.5, 0.7, 0.2], device="cuda:0")
+    eps = 2e-2
+
+    def loss(shift):
+        biases = [b.clone() for b in mlp.biases]
+        biases[-1] = biases[-1] + shift * direction
+        r, _, _, _ = lp.render_fwd(grid, lp.Mlp(weights=mlp.weights, biases=biases), rays, bg)
+        return float(((r.double() - target.double()) ** 2).sum() / (3.0 * m))
+
+    fd = (loss(+eps) - loss(-eps)) / (2 * eps)
+    predicted = float((full[2][-1].double() * direction.double()).sum())
+    assert predicted == pytest.approx(fd, rel=2e-3), (predicted, fd)
