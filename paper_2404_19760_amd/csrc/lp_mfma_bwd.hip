@@ -179,11 +179,13 @@ __device__ __forceinline__ void scatter_channels(const GridDev& g, float* const 
         const unsigned sz = C, sy = (unsigned)g.N[2] * C, sx = (unsigned)g.N[1] * sy;
         CornerAcc<3> ca;
         unsigned prev = 0;
+        // one uniform pointer per corner, so that a flush needs a single per-lane offset
+        char* Vd[8];
+#pragma unroll
+        for (int d = 0; d < 8; ++d)
+            Vd[d] = V + 4u * (size_t)((d >> 2) * sx + ((d >> 1) & 1) * sy + (d & 1) * sz);
         auto add = [&](int d, float v) {
-            if (live) {
-                const unsigned off = 4u * (prev + (d >> 2) * sx + ((d >> 1) & 1) * sy + (d & 1) * sz + ch);
-                atomicAdd(reinterpret_cast<float*>(V + off), v);
-            }
+            if (live) atomicAdd(reinterpret_cast<float*>(Vd[d] + 4u * (prev + ch)), v);
         };
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -222,11 +224,11 @@ __device__ __forceinline__ void scatter_channels(const GridDev& g, float* const 
             const unsigned sb = C, sa = (unsigned)g.N[b] * C;
             CornerAcc<2> ca;
             unsigned prev = 0;
+            char* Pd[4];
+#pragma unroll
+            for (int d = 0; d < 4; ++d) Pd[d] = P + 4u * (size_t)((d >> 1) * sa + (d & 1) * sb);
             auto add = [&](int d, float v) {
-                if (live) {
-                    const unsigned off = 4u * (prev + (d >> 1) * sa + (d & 1) * sb + ch);
-                    atomicAdd(reinterpret_cast<float*>(P + off), v);
-                }
+                if (live) atomicAdd(reinterpret_cast<float*>(Pd[d] + 4u * (prev + ch)), v);
             };
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
