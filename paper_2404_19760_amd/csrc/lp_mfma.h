@@ -82,6 +82,17 @@ __device__ __forceinline__ f32x16 mfma3(const Frag& ah, const Frag& al, const Fr
     return acc;
 }
 
+// Same, starting a new accumulation: the first product takes the constant 0 as its C operand
+// (an inline constant of the instruction), so no register has to be cleared beforehand.
+__device__ __forceinline__ f32x16 mfma3_first(const Frag& ah, const Frag& al, const Frag& bh, const Frag& bl)
+{
+    const f32x16 zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+    f32x16 acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(al), as_bf16x8(bh), zero, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ah), as_bf16x8(bl), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ah), as_bf16x8(bh), acc, 0, 0, 0);
+    return acc;
+}
+
 // Row of a 32-row D block that register r of lane-group g holds.
 __host__ __device__ constexpr int d_row(int r, int g) { return 8 * (r / 4) + 4 * g + (r % 4); }
 

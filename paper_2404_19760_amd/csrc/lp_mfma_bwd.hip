@@ -362,19 +362,30 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
             const Frag (&lh)[kNB][KSH] = NH == 2 ? a.h2h : a.h1h;  // last hidden layer's activations
             const Frag (&ll)[kNB][KSH] = NH == 2 ? a.h2l : a.h1l;
 
-            // ---- output layer: dWo += dZo * Hlast^T over the samples of the step ----
+            // The phases below alternate "store a tensor into the tile" / "work that does not touch
+            // the tile" / "load the transposed operands", so that the LDS round trip of every
+            // transposition is covered by matrix-core or vector work.
+
+            // ---- output layer ----
+            wave_lds_fence();
+            tile.template store<KSH>(lh, ll, lane, hidden_row);          // Hlast^T
+            if (grp == 0) {
+                tile.hi[(H + 0) * RS + col] = (uint16_t)zh0; tile.hi[(H + 1) * RS + col] = (uint16_t)(zh0 >> 16);
+                tile.hi[(H + 2) * RS + col] = (uint16_t)zh1; tile.hi[(H + 3) * RS + col] = (uint16_t)(zh1 >> 16);
+                tile.lo[(H + 0) * RS + col] = (uint16_t)zl0; tile.lo[(H + 1) * RS + col] = (uint16_t)(zl0 >> 16);
+                tile.lo[(H + 2) * RS + col] = (uint16_t)zl1; tile.lo[(H + 3) * RS + col] = (uint16_t)(zl1 >> 16);
+                // scatter record of this lane's sample, read at the end of the step
+                write_scatter_record<KIND, C>(info + col * 16, g, a.cell[0]);
+            }
+            // meanwhile: dZ of the last hidden layer = relu'(.) * (Wout^T dZo)
+            f32x16 acc[MB][kNB];
+            layer_mfma<MB, 1, kNB, true>(acc, lds + L::T3, lane, gzo_h, gzo_l);
+            relu_mask<MB>(acc, lh);
+            Frag gz_h[kNB][KSH], gz_l[kNB][KSH];
+            to_operands<MB, false, kNB>(acc, gz_h, gz_l);
+            wave_lds_fence();
             {
-                wave_lds_fence();
-                tile.template store<KSH>(lh, ll, lane, hidden_row);
-                if (grp == 0) {
-                    tile.hi[(H + 0) * RS + col] = (uint16_t)zh0; tile.hi[(H + 1) * RS + col] = (uint16_t)(zh0 >> 16);
-                    tile.hi[(H + 2) * RS + col] = (uint16_t)zh1; tile.hi[(H + 3) * RS + col] = (uint16_t)(zh1 >> 16);
-                    tile.lo[(H + 0) * RS + col] = (uint16_t)zl0; tile.lo[(H + 1) * RS + col] = (uint16_t)(zl0 >> 16);
-                    tile.lo[(H + 2) * RS + col] = (uint16_t)zl1; tile.lo[(H + 3) * RS + col] = (uint16_t)(zl1 >> 16);
-                    // scatter record of this lane's sample, read at the end of the step
-                    write_scatter_record<KIND, C>(info + col * 16, g, a.cell[0]);
-                }
-                wave_lds_fence();
+                // dWo += dZo * Hlast^T over the samples of the step
                 Frag ah[kKS], al[kKS];
 #pragma unroll
                 for (int s = 0; s < kKS; ++s) tile.load(H + (col & 3), s, grp, col < 4, ah[s], al[s]);
@@ -386,20 +397,13 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
                         tile.load(32 * nb + col, s, grp, true, bh, bl);
                         dWo[nb] = mfma3(ah[s], al[s], bh, bl, dWo[nb]);
                     }
-                wave_lds_fence();
             }
-
-            // ---- last hidden layer: dZ = relu'(.) * (Wout^T dZo) ----
-            f32x16 acc[MB][kNB];
-            zero_acc<MB, kNB>(acc);
-            layer_mfma<MB, 1, kNB>(acc, lds + L::T3, lane, gzo_h, gzo_l);
-            relu_mask<MB>(acc, lh);
-            Frag gz_h[kNB][KSH], gz_l[kNB][KSH];
-            to_operands<MB, false, kNB>(acc, gz_h, gz_l);
+            wave_lds_fence();
 
             if constexpr (NH == 2) {
-                // dW2 += dZ2 * H1^T ; db2 += sum dZ2
-                tile.template store<KSH>(gz_h, gz_l, lane, hidden_row);
+                // ---- second hidden layer: dW2 += dZ2 * H1^T ; db2 += sum dZ2 ; dZ1 = relu'(.) * (W2^T dZ2) ----
+                tile.template store<KSH>(gz_h, gz_l, lane, hidden_row);  // dZ2^T
+                layer_mfma<MB, KSH, kNB, true>(acc, lds + L::T2, lane, gz_h, gz_l);   // meanwhile: W2^T dZ2
                 wave_lds_fence();
                 Frag ah[MB][kKS], al[MB][kKS];
 #pragma unroll
@@ -410,7 +414,9 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
                         db2[mb] = frag_sum(al[mb][s], frag_sum(ah[mb][s], db2[mb]));
                     }
                 wave_lds_fence();
-                tile.template store<KSH>(a.h1h, a.h1l, lane, hidden_row);
+                tile.template store<KSH>(a.h1h, a.h1l, lane, hidden_row);  // H1^T
+                relu_mask<MB>(acc, a.h1h);                                 // meanwhile: dZ1
+                to_operands<MB, false, kNB>(acc, gz_h, gz_l);
                 wave_lds_fence();
 #pragma unroll
                 for (int nb = 0; nb < MB; ++nb)
@@ -422,17 +428,20 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
                         for (int mb = 0; mb < MB; ++mb) dW2[mb][nb] = mfma3(ah[mb][s], al[mb][s], bh, bl, dW2[mb][nb]);
                     }
                 wave_lds_fence();
-                // dZ1 = relu'(.) * (W2^T dZ2)
-                zero_acc<MB, kNB>(acc);
-                layer_mfma<MB, KSH, kNB>(acc, lds + L::T2, lane, gz_h, gz_l);
-                relu_mask<MB>(acc, a.h1h);
-                to_operands<MB, false, kNB>(acc, gz_h, gz_l);
             }
 
-            // ---- first layer: dW1 += dZ1 * F^T ; db1 += sum dZ1 ----
+            // ---- first layer: dW1 += dZ1 * F^T ; db1 += sum dZ1 ; feature gradient, transposed:
+            //      dF^T[sample][channel] = dZ1^T W1 ----
+            tile.template store<KSH>(gz_h, gz_l, lane, hidden_row);      // dZ1^T
+            f32x16 dFt;
+#pragma unroll
+            for (int s = 0; s < KSH; ++s) {                              // meanwhile: dF^T
+                Frag th, tl;
+                load_operand(lds + L::T1 + s * 128, lane, th, tl);
+                dFt = s == 0 ? mfma3_first(gz_h[0][s], gz_l[0][s], th, tl) : mfma3(gz_h[0][s], gz_l[0][s], th, tl, dFt);
+            }
+            wave_lds_fence();
             {
-                tile.template store<KSH>(gz_h, gz_l, lane, hidden_row);
-                wave_lds_fence();
                 Frag ah[MB][kKS], al[MB][kKS];
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb)
@@ -442,7 +451,7 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
                         db1[mb] = frag_sum(al[mb][s], frag_sum(ah[mb][s], db1[mb]));
                     }
                 wave_lds_fence();
-                tile.template store<KS1>(a.fh, a.fl, lane, input_row);
+                tile.template store<KS1>(a.fh, a.fl, lane, input_row);   // F^T
                 wave_lds_fence();
 #pragma unroll
                 for (int s = 0; s < kKS; ++s) {
@@ -451,17 +460,6 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
 #pragma unroll
                     for (int mb = 0; mb < MB; ++mb) dW1[mb] = mfma3(ah[mb][s], al[mb][s], bh, bl, dW1[mb]);
                 }
-            }
-
-            // ---- feature gradient, transposed: dF^T[sample][channel] = dZ1^T W1, then scatter ----
-            f32x16 dFt;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) dFt[r] = 0.0f;
-#pragma unroll
-            for (int s = 0; s < KSH; ++s) {
-                Frag th, tl;
-                load_operand(lds + L::T1 + s * 128, lane, th, tl);
-                dFt = mfma3(gz_h[0][s], gz_l[0][s], th, tl, dFt);
             }
             scatter_channels<KIND, C>(g, io.d_grid, q.scene, info, dFt, col, grp);
         }

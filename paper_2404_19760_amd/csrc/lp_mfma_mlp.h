@@ -100,8 +100,9 @@ __device__ __forceinline__ void zero_acc(f32x16 (&acc)[MB][NB])
             for (int r = 0; r < 16; ++r) acc[mb][nb][r] = 0.0f;
 }
 
-// acc[mb][nb] += A[mb][s] * B[nb][s] over KS K-steps, A from LDS at `a_base`
-template <int MB, int KS, int NB>
+// acc[mb][nb] (+)= A[mb][s] * B[nb][s] over KS K-steps, A from LDS at `a_base`; FRESH starts the
+// accumulation from zero instead of adding to acc
+template <int MB, int KS, int NB, bool FRESH = false>
 __device__ __forceinline__ void layer_mfma(f32x16 (&acc)[MB][NB], const uint4* a_base, int lane,
                                            const Frag (&bh)[NB][KS], const Frag (&bl)[NB][KS])
 {
@@ -112,7 +113,9 @@ __device__ __forceinline__ void layer_mfma(f32x16 (&acc)[MB][NB], const uint4* a
             Frag ah, al;
             load_operand(a_base + (mb * KS + s) * 128, lane, ah, al);
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = mfma3(ah, al, bh[nb][s], bl[nb][s], acc[mb][nb]);
+            for (int nb = 0; nb < NB; ++nb)
+                acc[mb][nb] = (FRESH && s == 0) ? mfma3_first(ah, al, bh[nb][s], bl[nb][s])
+                                                : mfma3(ah, al, bh[nb][s], bl[nb][s], acc[mb][nb]);
         }
 }
 
