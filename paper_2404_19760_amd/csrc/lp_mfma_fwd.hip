@@ -37,8 +37,15 @@ __global__ __launch_bounds__(kWaves * 64) void fwd_mfma_kernel(GridDev g, MlpDev
         float acc_r = 0.0f, acc_g = 0.0f, acc_b = 0.0f, acc_d = 0.0f;  // per-lane partial sums
 
         for (int j0 = 0; j0 < S; j0 += kStep) {
-            StepActs<C, H, NH, NB> a;
-            forward_step<KIND, C, H, NH, false, NB>(g, lds, q, j0, S, lane, a);
+            struct { float z[4]; } a;
+            if constexpr (NB == 2) {
+                forward_outputs<KIND, C, H, NH>(g, lds, q, j0, S, lane, a.z);
+            } else {
+                StepActs<C, H, NH, NB> full;
+                forward_step<KIND, C, H, NH, false, NB>(g, lds, q, j0, S, lane, full);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) a.z[k] = full.z[k];
+            }
 
             // heads and emission-absorption update; the lane owns sample j0 + pos
             const int pos = lane & (kStep - 1);

@@ -241,4 +241,69 @@ __device__ __forceinline__ void forward_step(const GridDev& g, const uint4* lds,
     for (int k = 0; k < 4; ++k) a.z[k] = (NB == 2 && grp) ? o[NB - 1][k] : o[0][k];
 }
 
+// Forward of one 64-sample step for the forward kernel, which keeps nothing but the decoder
+// outputs: the first layer runs on both N blocks at once (sharing the weight operands), the
+// remaining layers one N block after the other, so that at most one block's accumulators and
+// activations are alive at a time (registers for a second wave per SIMD).  z = outputs of
+// sample j0 + lane.
+template <int KIND, int C, int H, int NH>
+__device__ __forceinline__ void forward_outputs(const GridDev& g, const uint4* lds, const RayGeom& q, int j0,
+                                                int S, int lane, float (&z)[4])
+{
+    using L = MlpLds<C, H, NH, false, 2>;
+    constexpr int MB = L::MB, KS1 = L::KS1, KSH = L::KSH;
+    const int col = lane & 31, grp = lane >> 5;
+    const float* sbias = reinterpret_cast<const float*>(lds + L::BIAS);
+
+    Frag fh[2][KS1], fl[2][KS1];
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+        const int j = min(j0 + 32 * nb + col, S - 1);
+        const Cell3 c = sample_cell(g, q, j);
+        float feat[C / 2];
+        gather_half<KIND, C, C / 2>(g, q.scene, c, grp * (C / 2), feat);
+#pragma unroll
+        for (int s = 0; s < KS1; ++s) split8(feat + 8 * s, fh[nb][s], fl[nb][s]);
+    }
+    Frag h1h[2][KSH], h1l[2][KSH];
+    {
+        f32x16 acc[MB][2];
+        init_bias<MB, 2>(acc, sbias, grp);
+        layer_mfma<MB, KS1, 2>(acc, lds + L::A1, lane, fh, fl);
+        to_operands<MB, true, 2>(acc, h1h, h1l);
+    }
+    const f32x4 bo = *reinterpret_cast<const f32x4*>(sbias + 2 * H);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+        Frag lh[1][KSH], ll[1][KSH];
+        if constexpr (NH == 2) {
+            Frag inh[1][KSH], inl[1][KSH];
+#pragma unroll
+            for (int s = 0; s < KSH; ++s) { inh[0][s] = h1h[nb][s]; inl[0][s] = h1l[nb][s]; }
+            f32x16 acc[MB][1];
+            init_bias<MB, 1>(acc, sbias + H, grp);
+            layer_mfma<MB, KSH, 1>(acc, lds + L::A2, lane, inh, inl);
+            to_operands<MB, true, 1>(acc, lh, ll);
+        } else {
+#pragma unroll
+            for (int s = 0; s < KSH; ++s) { lh[0][s] = h1h[nb][s]; ll[0][s] = h1l[nb][s]; }
+        }
+        f32x16 o;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[r] = r < 4 ? bo[r] : 0.0f;
+#pragma unroll
+        for (int s = 0; s < KSH; ++s) {
+            Frag ah, al;
+            load_operand(lds + L::A3 + s * 128, lane, ah, al);
+            o = mfma3(ah, al, lh[0][s], ll[0][s], o);
+        }
+        // lanes 0..31 own the samples of N block 0, lanes 32..63 those of N block 1
+#pragma unroll
+        for (int k = 0; k < 4; ++k) z[k] = (nb == 0 || grp) ? o[k] : z[k];
+        // keep the two N blocks apart: interleaving them would double the live registers
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
 }  // namespace lp
