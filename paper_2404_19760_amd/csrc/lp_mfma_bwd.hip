@@ -53,6 +53,7 @@ struct Tile {
     __device__ __forceinline__ void store(const Frag (&fh)[kNB][KS], const Frag (&fl)[kNB][KS], int lane,
                                           RowFn row_of) const
     {
+
         const int col = lane & 31, grp = lane >> 5;
 #pragma unroll
         for (int nb = 0; nb < kNB; ++nb)
@@ -72,6 +73,7 @@ struct Tile {
     // MFMA operand with the samples of the step on the K axis: 8 consecutive samples of `row`
     __device__ __forceinline__ void load(int row, int s, int grp, bool live, Frag& fh, Frag& fl) const
     {
+
         const uint4 h = *reinterpret_cast<const uint4*>(hi + row * RS + 16 * s + 8 * grp);
         const uint4 l = *reinterpret_cast<const uint4*>(lo + row * RS + 16 * s + 8 * grp);
         fh.d[0] = live ? h.x : 0u; fh.d[1] = live ? h.y : 0u; fh.d[2] = live ? h.z : 0u; fh.d[3] = live ? h.w : 0u;
@@ -168,11 +170,7 @@ template <int KIND, int C>
 __device__ __forceinline__ void scatter_channels(const GridDev& g, float* const d_grid[3], int scene,
                                                  const float* info, const f32x16& dFt, int ch, int grp)
 {
-#ifdef LP_X_NOSCATTER
-    const bool live = ch < C && dFt[0] == 12345.0f;
-#else
     const bool live = ch < C;
-#endif
     if constexpr (KIND == LP_GRID_VOXEL) {
         // uniform base pointer + 32-bit byte offset per lane (a scene's tensor is below 4 GiB)
         char* V = reinterpret_cast<char*>(d_grid[0] + (size_t)scene * g.N[0] * g.N[1] * g.N[2] * C);
