@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the backward kernel from two rocprofv3 --pmc runs (FETCH_SIZE scaled
 # by 2.0, WRITE_SIZE by 1.0 against a 1 GiB copy kernel in the same run); the summary with the
 # commands is profiles/large_voxel256_fwd_bwd_kernels.md.  None = not measured for that workload.
-MEASURED_BWD_HBM_BYTES = {"large": 0.263e9 + 65.42e9}
+MEASURED_BWD_HBM_BYTES = {"large": 0.288e9 + 65.42e9}
 
 
 def parse():
@@ -38,6 +38,8 @@ def parse():
     ap.add_argument("--math", default="default", choices=["default", "generic", "bf16x3"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
+    ap.add_argument("--also", default="single_scene",
+                    help="second workload reported for context under 'also' ('' to skip)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy kernel (reference for HBM counters)")
     return ap.parse_args()
@@ -67,25 +69,14 @@ def cpu_baseline(inp, budget_s: float):
             f"all {inp.samples} samples each, fp64 forward + stored-forward reverse-mode backward, {t:.1f} s"}
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print(f"bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus {args.gpus} "
-              "is not supported", file=sys.stderr)
-        sys.exit(2)
-    import torch
+def measure(lp, torch, name, mode, steps, warmup, calibrate_copy=False):
+    """Times `steps` forward+backward steps of workload `name`; returns the result fields."""
     import lp_inputs
-    import paper_2404_19760_amd as lp
-
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible; the Renderer has no CPU path", file=sys.stderr)
-        sys.exit(2)
-    w = lp_inputs.WORKLOADS[args.config]
-    inp = lp_inputs.make_inputs(args.config)
+    w = lp_inputs.WORKLOADS[name]
+    inp = lp_inputs.make_inputs(name)
     dev = "cuda:0"
     grid, mlp, rays, bg = lp.to_device(inp, dev)
     target = torch.from_numpy(inp.target).to(dev)
-    mode = {"default": lp.LP_MATH_DEFAULT, "generic": lp.LP_MATH_GENERIC, "bf16x3": lp.LP_MATH_BF16X3}[args.math]
     fast = lp.lp_has_fast_path(grid, mlp) and mode != lp.LP_MATH_GENERIC
 
     m = rays.n_rays
@@ -102,9 +93,9 @@ def main():
         inv = (2.0 / (3.0 * counts[rays.scene.long()]))[:, None]
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
-    fwd_ms, bwd_ms = [], []
 
     def step(timed: bool):
+        # events on torch's current stream, which is the stream the library launches on
         e0, e1, e2, e3 = ev(), ev(), ev(), ev()
         e0.record()
         lp.lp_render_fwd(grid, mlp, rays, bg, rgb, alpha, depth, cache, mode)
@@ -117,7 +108,7 @@ def main():
         e3.record()
         return (e0, e1, e2, e3) if timed else None
 
-    if args.calibrate_copy:
+    if calibrate_copy:
         # a copy kernel of known traffic (1 GiB read + 1 GiB written) for scaling the
         # FETCH_SIZE / WRITE_SIZE counters of a profiler run of this same command
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
@@ -127,21 +118,38 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step(False)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    events = [step(True) for _ in range(args.steps)]
+    events = [step(True) for _ in range(steps)]
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    for e0, e1, e2, e3 in events:
-        fwd_ms.append(e0.elapsed_time(e1))
-        bwd_ms.append(e2.elapsed_time(e3))
+    fwd_ms = float(np.mean([e0.elapsed_time(e1) for e0, e1, _, _ in events]))
+    bwd_ms = float(np.mean([e2.elapsed_time(e3) for _, _, e2, e3 in events]))
+    return dict(w=w, inp=inp, fast=fast, rays=m, samples=m * inp.samples, elapsed=elapsed,
+                fwd_ms=fwd_ms, bwd_ms=bwd_ms)
 
-    samples = m * inp.samples
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus {args.gpus} "
+              "is not supported", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2404_19760_amd as lp
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the Renderer has no CPU path", file=sys.stderr)
+        sys.exit(2)
+    mode = {"default": lp.LP_MATH_DEFAULT, "generic": lp.LP_MATH_GENERIC, "bf16x3": lp.LP_MATH_BF16X3}[args.math]
+    r = measure(lp, torch, args.config, mode, args.steps, args.warmup, args.calibrate_copy)
+    w, inp, fast, m, samples = r["w"], r["inp"], r["fast"], r["rays"], r["samples"]
+    elapsed, fwd_avg, bwd_avg = r["elapsed"], r["fwd_ms"], r["bwd_ms"]
+
     ms_per_step = 1e3 * elapsed / args.steps
     g_bytes = w.gather_bytes_per_sample
-    fwd_avg, bwd_avg = float(np.mean(fwd_ms)), float(np.mean(bwd_ms))
     # dominant kernel: the backward (re-reads the G gather bytes and adds G bytes of gradient)
     bwd_gbs = 2 * g_bytes * samples / (bwd_avg * 1e-3) / 1e9
     fwd_gbs = g_bytes * samples / (fwd_avg * 1e-3) / 1e9
@@ -168,6 +176,17 @@ def main():
                      "traffic": MEASURED_BWD_HBM_BYTES.get(args.config) if fast else None,
                      "bytes_per_sample": 2 * g_bytes, "ms": bwd_avg},
     }
+    if args.also and args.also != args.config:
+        # a second workload for context (short run), e.g. the single-scene configuration
+        del r
+        torch.cuda.empty_cache()
+        o = measure(lp, torch, args.also, mode, max(3, args.steps // 2), 2)
+        ow = o["w"]
+        out["also"] = {"workload": args.also, "ray_samples": o["samples"],
+                       "value": o["samples"] / (o["elapsed"] / max(3, args.steps // 2)), "unit": "ray-samples/s",
+                       "fwd_ms": o["fwd_ms"], "bwd_ms": o["bwd_ms"],
+                       "fwd_bwd_frac_hbm_peak": 3 * ow.gather_bytes_per_sample * o["samples"]
+                       / ((o["fwd_ms"] + o["bwd_ms"]) * 1e-3) / 1e9 / HBM_PEAK_GBS}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(inp, args.cpu_seconds)
     print(json.dumps(out))

@@ -1,0 +1,55 @@
+"""The seeded input generators: deterministic, shaped as the configurations say, rays as the
+library requires them (unit directions, every sample inside the grid box).  CPU only."""
+import numpy as np
+import pytest
+
+import lp_inputs
+
+
+def test_workload_table_matches_the_configurations():
+    w = lp_inputs.WORKLOADS
+    assert [w[k].cfg_id for k in lp_inputs.WORKLOAD_ORDER] == [1, 2, 3, 4, 5]
+    assert (w["tiny"].rays, w["tiny"].samples, w["tiny"].mlp_dims) == (1024, 64, (16, 32, 4))
+    assert (w["single_scene"].rays, w["single_scene"].ray_samples) == (16384, 2097152)
+    assert (w["voxel"].rays, w["voxel"].ray_samples, w["voxel"].gather_bytes_per_sample) == (262144, 67108864, 1024)
+    assert (w["batched"].rays, w["batched"].ray_samples, w["batched"].gather_bytes_per_sample) == (2097152, 402653184, 1536)
+    assert (w["large"].rays, w["large"].ray_samples, w["large"].gather_bytes_per_sample) == (640000, 327680000, 512)
+    assert w["large"].mlp_flop_per_sample == 10752 and w["single_scene"].mlp_flop_per_sample == 12800
+
+
+@pytest.mark.parametrize("name", ["tiny", "single_scene"])
+def test_inputs_are_deterministic_and_well_formed(name):
+    a = lp_inputs.make_inputs(name)
+    b = lp_inputs.make_inputs(name)
+    for x, y in zip(a.grid + a.weights + a.biases + [a.origins, a.dirs, a.near, a.far, a.target],
+                    b.grid + b.weights + b.biases + [b.origins, b.dirs, b.near, b.far, b.target]):
+        assert x.dtype == np.float32 and x.flags["C_CONTIGUOUS"] and np.array_equal(x, y)
+    w = lp_inputs.WORKLOADS[name]
+    assert [g.shape for g in a.grid] == lp_inputs.grid_shapes(w.kind, w.n_scenes, w.res, w.channels)
+    assert abs(float(np.std(a.grid[0])) - w.grid_std) < 0.02 * w.grid_std
+    # unit directions to float32 rounding
+    n = np.linalg.norm(a.dirs.astype(np.float64), axis=1)
+    assert np.abs(n - 1.0).max() < 2e-7
+    # every sample of every ray lies inside the grid box, so no sample is clamped
+    t = np.array([w.near, w.far])
+    pts = a.origins[:, None, :].astype(np.float64) + t[None, :, None] * a.dirs[:, None, :].astype(np.float64)
+    assert np.abs(pts).max() < w.aabb
+
+
+def test_four_camera_rays_and_scene_indices():
+    w = lp_inputs.WORKLOADS["batched"]
+    o, d, near, far, scene = lp_inputs.make_rays(w)
+    assert o.shape == (w.rays, 3) and scene.dtype == np.int32
+    assert np.array_equal(np.bincount(scene), np.full(8, 4 * 256 * 256))
+    cams = lp_inputs.cameras_for(w)
+    assert len(cams) == 4
+    for rot, pos in cams:
+        assert abs(np.linalg.norm(pos) - 2.5) < 1e-12
+        assert np.allclose(rot.T @ rot, np.eye(3), atol=1e-12)
+        assert np.allclose(rot[:, 2], pos / 2.5)          # the camera looks at the origin
+
+
+def test_strided_subset_is_a_deterministic_set_of_distinct_rays():
+    idx = lp_inputs.strided_ray_subset(640000, 768, offset=3)
+    assert len(idx) == 768 and len(set(idx.tolist())) == 768 and idx.max() < 640000
+    assert np.array_equal(idx, lp_inputs.strided_ray_subset(640000, 768, offset=3))
