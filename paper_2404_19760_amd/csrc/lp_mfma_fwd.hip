@@ -87,7 +87,7 @@ hipError_t launch_fwd(const GridDev& g, const MlpDev& m, const RaysDev& rays, co
     hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (e != hipSuccess) return e;
     // persistent grid: as many workgroups as fit a compute unit's registers, a multiple of the 8 XCDs, no more than the rays need
-    long long blocks = (long long)(NB == 1 ? 3 : 2) * n_cu;
+    long long blocks = 3LL * n_cu;
     const long long need = (rays.M + kWaves - 1) / kWaves;
     if (blocks > need) blocks = need;
     blocks = (blocks + 7) / 8 * 8;
