@@ -1,0 +1,198 @@
+// Pieces shared by the matrix-core backward kernels: wave-level LDS fence, ReLU-derivative
+// masking, bias-gradient sums, and the scatter of the feature gradient into the grid gradient.
+#pragma once
+#include "lp_mfma.h"
+#include "lp_mfma_mlp.h"
+
+namespace lp {
+
+constexpr int kBwdNB = 1;               // N blocks (of 32 samples) per backward step
+constexpr int kBwdStep = 32 * kBwdNB;   // samples per step
+constexpr int kBwdKS = 2 * kBwdNB;      // K-steps of a contraction over the samples of a step
+
+__device__ __forceinline__ void wave_lds_fence()
+{
+    // LDS operations of one wave execute in order; this only pins the compiler's ordering of
+    // the tile stores of some lanes against the tile loads of others
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+// sum of the 8 bf16 values of a fragment, added to acc
+__device__ __forceinline__ float frag_sum(const Frag& f, float acc)
+{
+    bf16x2 one;
+    one[0] = (__bf16)1.0f;
+    one[1] = (__bf16)1.0f;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, f.d[d]), one, acc, false);
+    return acc;
+}
+
+// zeroes the entries of a D block whose ReLU output (hi part of the stored activation) is zero
+template <int MB>
+__device__ __forceinline__ void relu_mask(f32x16 (&acc)[MB][kBwdNB], const Frag (&act_hi)[kBwdNB][2 * MB])
+{
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < kBwdNB; ++nb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int s = 2 * mb + r / 8, e = r % 8;
+                const uint32_t bits = (act_hi[nb][s].d[e / 2] >> (16 * (e & 1))) & 0xffffu;
+                acc[mb][nb][r] = bits ? acc[mb][nb][r] : 0.0f;
+            }
+}
+
+// ---- scatter records: what the channel lanes need to know about each sample of the step ----
+// 16 dwords per sample.  voxel: 8 corner weights (corner 4dx + 2dy + dz), then the element offset of
+// corner 0.  triplane: 12 weights (plane p, corner 2da + db at 4p + ..), then 3 plane offsets.
+template <int KIND, int C>
+__device__ __forceinline__ void write_scatter_record(float* rec, const GridDev& g, const Cell3& c)
+{
+    if constexpr (KIND == LP_GRID_VOXEL) {
+        const float x1 = c.f[0], x0 = 1.0f - x1, y1 = c.f[1], y0 = 1.0f - y1, z1 = c.f[2], z0 = 1.0f - z1;
+        const float4 w0 = make_float4(x0 * y0 * z0, x0 * y0 * z1, x0 * y1 * z0, x0 * y1 * z1);
+        const float4 w1 = make_float4(x1 * y0 * z0, x1 * y0 * z1, x1 * y1 * z0, x1 * y1 * z1);
+        const unsigned sz = C, sy = (unsigned)g.N[2] * C, sx = (unsigned)g.N[1] * sy;
+        const unsigned base = (unsigned)c.i[0] * sx + (unsigned)c.i[1] * sy + (unsigned)c.i[2] * sz;
+        reinterpret_cast<float4*>(rec)[0] = w0;
+        reinterpret_cast<float4*>(rec)[1] = w1;
+        reinterpret_cast<unsigned*>(rec)[8] = base;
+    } else {
+        unsigned base[3];
+#pragma unroll
+        for (int p = 0; p < 3; ++p) {
+            const int a = p, b = (p + 1) % 3;
+            const float a1 = c.f[a], a0 = 1.0f - a1, b1 = c.f[b], b0 = 1.0f - b1;
+            reinterpret_cast<float4*>(rec)[p] = make_float4(a0 * b0, a0 * b1, a1 * b0, a1 * b1);
+            base[p] = ((unsigned)c.i[a] * (unsigned)g.N[b] + (unsigned)c.i[b]) * C;
+        }
+        reinterpret_cast<uint4*>(rec)[3] = make_uint4(base[0], base[1], base[2], 0u);
+    }
+}
+
+// Accumulators of the 2^NBITS corners of the current cell while a lane walks its samples in ray
+// order.  When the ray steps into the neighbouring cell along ONE axis, the corners on the
+// shared face stay (their sums move to the mirrored corner index) and only the corners left
+// behind are added to memory; any other move flushes all corners.
+template <int NBITS>
+struct CornerAcc {
+    static constexpr int N = 1 << NBITS;
+    float acc[N];
+
+    // BIT = corner-index bit of the axis stepped along; `up` = towards larger index.
+    // flush(d, value) adds `value` to corner d of the OLD cell.
+    template <int BIT, class Flush>
+    __device__ __forceinline__ void step_axis(bool up, Flush flush)
+    {
+#pragma unroll
+        for (int d = 0; d < N; ++d) {
+            if (d & BIT) continue;
+            const float lo = acc[d], hi = acc[d | BIT];
+            flush(up ? d : (d | BIT), up ? lo : hi);   // the face left behind
+            acc[d] = up ? hi : 0.0f;                   // the shared face changes side
+            acc[d | BIT] = up ? 0.0f : lo;
+        }
+    }
+};
+
+// This lane (channel `ch` of lane group `grp`) holds in dFt[r] the feature gradient of MFMA
+// column d_row(r, grp), which (permuted step) is sample 16 grp + r of the step: 16 consecutive
+// samples in ray order.  Contributions are summed per corner while the ray stays in a cell
+// (and on shared corners across a step into a neighbouring cell) before one atomic add per
+// corner; the lanes ch = 0..C-1 of a group address consecutive floats.
+template <int KIND, int C>
+__device__ __forceinline__ void scatter_channels(const GridDev& g, float* const d_grid[3], int scene,
+                                                 const float* info, const f32x16& dFt, int ch, int grp)
+{
+    const bool live = ch < C;
+    if constexpr (KIND == LP_GRID_VOXEL) {
+        // uniform base pointer + 32-bit byte offset per lane (a scene's tensor is below 4 GiB)
+        char* V = reinterpret_cast<char*>(d_grid[0] + (size_t)scene * g.N[0] * g.N[1] * g.N[2] * C);
+        const unsigned sz = C, sy = (unsigned)g.N[2] * C, sx = (unsigned)g.N[1] * sy;
+        CornerAcc<3> ca;
+        unsigned prev = 0;
+        // one uniform pointer per corner, so that a flush needs a single per-lane offset
+        char* Vd[8];
+#pragma unroll
+        for (int d = 0; d < 8; ++d)
+            Vd[d] = V + 4u * (size_t)((d >> 2) * sx + ((d >> 1) & 1) * sy + (d & 1) * sz);
+        auto add = [&](int d, float v) {
+            if (live) atomicAdd(reinterpret_cast<float*>(Vd[d] + 4u * (prev + ch)), v);
+        };
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const float* rec = info + d_row(r, grp) * 16;
+            const float4 w0 = reinterpret_cast<const float4*>(rec)[0];
+            const float4 w1 = reinterpret_cast<const float4*>(rec)[1];
+            const unsigned base = reinterpret_cast<const unsigned*>(rec)[8];
+            const float w[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
+            const float v = dFt[r];
+            if (r > 0 && base != prev) {
+                // Keeping shared corners across a cell change costs selects and saves atomic
+                // requests.  Measured: it pays where a corner spans two 64-byte lines (32 channels,
+                // the kernel then runs at the atomic units' request rate) and loses where a corner
+                // is one line and the kernel is bound by its own instruction stream (16 channels).
+                constexpr bool kCarryVoxel = C >= 32;
+                const bool up = base > prev;
+                const unsigned dist = up ? base - prev : prev - base;
+                if (kCarryVoxel && dist == sz) ca.template step_axis<1>(up, add);
+                else if (kCarryVoxel && dist == sy) ca.template step_axis<2>(up, add);
+                else if (kCarryVoxel && dist == sx) ca.template step_axis<4>(up, add);
+                else {
+#pragma unroll
+                    for (int d = 0; d < 8; ++d) { add(d, ca.acc[d]); ca.acc[d] = 0.0f; }
+                }
+            }
+            prev = base;
+#pragma unroll
+            for (int d = 0; d < 8; ++d) ca.acc[d] = r == 0 ? w[d] * v : ca.acc[d] + w[d] * v;
+        }
+#pragma unroll
+        for (int d = 0; d < 8; ++d) add(d, ca.acc[d]);
+    } else {
+#pragma unroll
+        for (int pl = 0; pl < 3; ++pl) {
+            const int a = pl, b = (pl + 1) % 3;
+            char* P = reinterpret_cast<char*>(d_grid[pl] + (size_t)scene * g.N[a] * g.N[b] * C);
+            const unsigned sb = C, sa = (unsigned)g.N[b] * C;
+            CornerAcc<2> ca;
+            unsigned prev = 0;
+            char* Pd[4];
+#pragma unroll
+            for (int d = 0; d < 4; ++d) Pd[d] = P + 4u * (size_t)((d >> 1) * sa + (d & 1) * sb);
+            auto add = [&](int d, float v) {
+                if (live) atomicAdd(reinterpret_cast<float*>(Pd[d] + 4u * (prev + ch)), v);
+            };
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float* rec = info + d_row(r, grp) * 16;
+                const float4 w4 = reinterpret_cast<const float4*>(rec)[pl];
+                const unsigned base = reinterpret_cast<const unsigned*>(rec)[12 + pl];
+                const float w[4] = {w4.x, w4.y, w4.z, w4.w};
+                const float v = dFt[r];
+                if (r > 0 && base != prev) {
+                    const bool up = base > prev;
+                    const unsigned dist = up ? base - prev : prev - base;
+                    if (dist == sb) ca.template step_axis<1>(up, add);
+                    else if (dist == sa) ca.template step_axis<2>(up, add);
+                    else {
+#pragma unroll
+                        for (int d = 0; d < 4; ++d) { add(d, ca.acc[d]); ca.acc[d] = 0.0f; }
+                    }
+                }
+                prev = base;
+#pragma unroll
+                for (int d = 0; d < 4; ++d) ca.acc[d] = r == 0 ? w[d] * v : ca.acc[d] + w[d] * v;
+            }
+#pragma unroll
+            for (int d = 0; d < 4; ++d) add(d, ca.acc[d]);
+        }
+    }
+}
+
+}  // namespace lp

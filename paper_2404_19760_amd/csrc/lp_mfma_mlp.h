@@ -26,16 +26,10 @@ struct MlpLds {
     static constexpr int W_END = T1 + (BWD ? KSH * 128 : 0);
     static constexpr int BIAS = W_END;                             // floats: b1[H] b2[H] bout[4]
     static constexpr int BIAS_UNITS = (2 * H + 4 + 3) / 4;
-    static constexpr int TILE = BIAS + BIAS_UNITS;                 // per-wave transpose tiles (backward)
-    // tile: two planes (hi, lo) of [H + 4 rows][32 NB samples + 8 pad] halfwords; the pad makes
-    // the 128-bit operand loads of 8 consecutive lanes fall into distinct banks
-    static constexpr int TILE_ROWS = H + 4;
-    static constexpr int TILE_RS = 32 * NB + 8;                     // halfwords per row
-    static constexpr int TILE_PLANE_UNITS = TILE_ROWS * TILE_RS * 2 / 16;
-    // per-sample scatter records: 32 NB samples x 16 dwords (weights and corner offsets)
+    static constexpr int END = BIAS + BIAS_UNITS;                  // first unit after weights and biases
+    // per-sample scatter records of a backward wave: 32 NB samples x 16 dwords (weights, corner offsets)
     static constexpr int INFO_UNITS = 32 * NB * 4;
-    static constexpr int TILE_UNITS = 2 * TILE_PLANE_UNITS + INFO_UNITS;
-    static constexpr int bytes(int waves) { return (TILE + (BWD ? waves * TILE_UNITS : 0)) * 16; }
+    static constexpr int bytes(int waves) { return (END + (BWD ? waves * INFO_UNITS : 0)) * 16; }
 };
 
 template <int C, int H, int NH, bool BWD, int NB>
