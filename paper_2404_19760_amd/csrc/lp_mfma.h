@@ -226,26 +226,19 @@ __device__ __forceinline__ Cell3 locate3(const GridDev& g, double x, double y, d
     return c;
 }
 
-template <int NCH>  // NCH consecutive channels starting at ch0
-__device__ __forceinline__ void accum_corner(const float* __restrict__ p, float w, float* feat)
-{
-    const float4* q = reinterpret_cast<const float4*>(p);
-#pragma unroll
-    for (int i = 0; i < NCH / 4; ++i) {
-        const float4 v = q[i];
-        feat[4 * i + 0] += w * v.x;
-        feat[4 * i + 1] += w * v.y;
-        feat[4 * i + 2] += w * v.z;
-        feat[4 * i + 3] += w * v.w;
-    }
-}
+// The texels one lane reads for a sample: NCH consecutive channels of every corner (voxel: corner
+// 4dx + 2dy + dz; triplane: plane p, corner 2da + db at 4p + ..).  Loading and interpolating are
+// separate steps so that a kernel can issue the loads early and do other work while they fly.
+template <int KIND, int NCH>
+struct GatherRaw {
+    static constexpr int kCorners = KIND == LP_GRID_VOXEL ? 8 : 12;
+    float4 v[kCorners][NCH / 4];
+};
 
-// feat[0..NCH) = channels [ch0, ch0 + NCH) of h(x) in scene `scene`.
 template <int KIND, int C, int NCH>
-__device__ __forceinline__ void gather_half(const GridDev& g, int scene, const Cell3& c, int ch0, float* feat)
+__device__ __forceinline__ void gather_issue(const GridDev& g, int scene, const Cell3& c, int ch0,
+                                             GatherRaw<KIND, NCH>& raw)
 {
-#pragma unroll
-    for (int k = 0; k < NCH; ++k) feat[k] = 0.0f;
     if constexpr (KIND == LP_GRID_VOXEL) {
         const float* V = g.data[0] + (size_t)scene * g.N[0] * g.N[1] * g.N[2] * C;
         const unsigned sz = C, sy = (unsigned)g.N[2] * C, sx = (unsigned)g.N[1] * sy;
@@ -253,25 +246,62 @@ __device__ __forceinline__ void gather_half(const GridDev& g, int scene, const C
 #pragma unroll
         for (int d = 0; d < 8; ++d) {
             const int dx = d >> 2, dy = (d >> 1) & 1, dz = d & 1;
-            const float w = (dx ? c.f[0] : 1.0f - c.f[0]) * (dy ? c.f[1] : 1.0f - c.f[1]) *
-                            (dz ? c.f[2] : 1.0f - c.f[2]);
-            accum_corner<NCH>(V + (base + dx * sx + dy * sy + dz * sz), w, feat);
+            const float4* p = reinterpret_cast<const float4*>(V + (base + dx * sx + dy * sy + dz * sz));
+#pragma unroll
+            for (int i = 0; i < NCH / 4; ++i) raw.v[d][i] = p[i];
         }
     } else {
 #pragma unroll
-        for (int p = 0; p < 3; ++p) {
-            const int a = p, b = (p + 1) % 3;
-            const float* P = g.data[p] + (size_t)scene * g.N[a] * g.N[b] * C;
+        for (int pl = 0; pl < 3; ++pl) {
+            const int a = pl, b = (pl + 1) % 3;
+            const float* P = g.data[pl] + (size_t)scene * g.N[a] * g.N[b] * C;
             const unsigned sb = C, sa = (unsigned)g.N[b] * C;
             const unsigned base = (unsigned)c.i[a] * sa + (unsigned)c.i[b] * sb + ch0;
 #pragma unroll
             for (int d = 0; d < 4; ++d) {
                 const int da = d >> 1, db = d & 1;
-                const float w = (da ? c.f[a] : 1.0f - c.f[a]) * (db ? c.f[b] : 1.0f - c.f[b]);
-                accum_corner<NCH>(P + (base + da * sa + db * sb), w, feat);
+                const float4* p = reinterpret_cast<const float4*>(P + (base + da * sa + db * sb));
+#pragma unroll
+                for (int i = 0; i < NCH / 4; ++i) raw.v[4 * pl + d][i] = p[i];
             }
         }
     }
+}
+
+// feat[0..NCH) = the interpolated channels (Section 3.2: trilinear / sum of three bilinear)
+template <int KIND, int NCH>
+__device__ __forceinline__ void gather_finish(const Cell3& c, const GatherRaw<KIND, NCH>& raw, float* feat)
+{
+#pragma unroll
+    for (int k = 0; k < NCH; ++k) feat[k] = 0.0f;
+#pragma unroll
+    for (int d = 0; d < GatherRaw<KIND, NCH>::kCorners; ++d) {
+        float w;
+        if constexpr (KIND == LP_GRID_VOXEL) {
+            const int dx = d >> 2, dy = (d >> 1) & 1, dz = d & 1;
+            w = (dx ? c.f[0] : 1.0f - c.f[0]) * (dy ? c.f[1] : 1.0f - c.f[1]) * (dz ? c.f[2] : 1.0f - c.f[2]);
+        } else {
+            const int a = d >> 2, b = (a + 1) % 3, da = (d >> 1) & 1, db = d & 1;
+            w = (da ? c.f[a] : 1.0f - c.f[a]) * (db ? c.f[b] : 1.0f - c.f[b]);
+        }
+#pragma unroll
+        for (int i = 0; i < NCH / 4; ++i) {
+            const float4 v = raw.v[d][i];
+            feat[4 * i + 0] += w * v.x;
+            feat[4 * i + 1] += w * v.y;
+            feat[4 * i + 2] += w * v.z;
+            feat[4 * i + 3] += w * v.w;
+        }
+    }
+}
+
+// feat[0..NCH) = channels [ch0, ch0 + NCH) of h(x) in scene `scene`.
+template <int KIND, int C, int NCH>
+__device__ __forceinline__ void gather_half(const GridDev& g, int scene, const Cell3& c, int ch0, float* feat)
+{
+    GatherRaw<KIND, NCH> raw;
+    gather_issue<KIND, C, NCH>(g, scene, c, ch0, raw);
+    gather_finish<KIND, NCH>(c, raw, feat);
 }
 
 // Ranges of rays per XCD: workgroup b runs on XCD b % 8, so giving XCD x the contiguous ray

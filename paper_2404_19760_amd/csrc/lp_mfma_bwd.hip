@@ -79,7 +79,8 @@ __device__ __forceinline__ Frag selection(int j, int grp, IndexFn index_of)
 }
 
 template <int KIND, int C, int H, int NH>
-__global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev m, RaysDev rays, BwdIo io)
+__global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev m, RaysDev rays, BwdIo io,
+                                                               long long group_mul)
 {
     using L = MlpLds<C, H, NH, true, kBwdNB>;
     constexpr int MB = L::MB, KS1 = L::KS1, KSH = L::KSH;
@@ -135,22 +136,59 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) db1[mb] = db2[mb] = 0.0f;
 
-    const RaySchedule sched = ray_schedule(rays.M, kWaves);
+    // Rays are taken in groups of kWaves neighbours (one per wave of a workgroup), and the groups
+    // in a scrambled order: neighbouring rays add into the same lines of the grid gradient, and
+    // atomic adds of many waves to one line queue up behind each other at its L2 channel.
+    const long long n_groups = (rays.M + kWaves - 1) / kWaves;
+    const RaySchedule sched = ray_schedule(n_groups * kWaves, kWaves);
     const int S = rays.S;
 
-    for (long long ray = sched.first; ray < sched.end; ray += sched.stride) {
-        const RayGeom q = load_ray_geom(rays, ray);
+    const int j_last = ((S - 1) / kBwdStep) * kBwdStep;
+    auto ray_of = [&](long long seq) { return ((seq / kWaves) * group_mul % n_groups) * kWaves + seq % kWaves; };
+    // first / next sequence number of this wave that stands for a ray (the last group is padded)
+    auto valid_from = [&](long long seq) {
+        while (seq < sched.end && ray_of(seq) >= rays.M) seq += sched.stride;
+        return seq;
+    };
+
+    // Cell and input features of the step about to be processed.  Those of the following step
+    // (of this ray, or the last step of the wave's next ray) are sampled while the current
+    // step's last contractions run and BEFORE its scatter: the wait for these loads must not
+    // come after the scatter's atomic adds (memory operations complete in order, and an atomic
+    // add takes much longer than a cached load).
+    long long seq = valid_from(sched.first);
+    RayGeom q_next;
+    Cell3 cell;
+    Frag fh[KS1], fl[KS1];
+    if (seq < sched.end) {  // a wave without rays only writes its (zero) record
+        q_next = load_ray_geom(rays, ray_of(seq));
+        cell = sample_cell(g, q_next, min(j_last + slot_to_sample(col), S - 1));
+        float feat[C / 2];
+        gather_half<KIND, C, C / 2>(g, q_next.scene, cell, grp * (C / 2), feat);
+#pragma unroll
+        for (int s = 0; s < KS1; ++s) split8(feat + 8 * s, fh[s], fl[s]);
+    }
+
+    while (seq < sched.end) {
+        const long long ray = ray_of(seq);
+        const RayGeom q = q_next;
+        seq = valid_from(seq + sched.stride);
+        if (seq < sched.end) q_next = load_ray_geom(rays, ray_of(seq));  // else: a harmless re-sample of this ray
         const float p0 = io.d_rgb[3 * ray + 0], p1 = io.d_rgb[3 * ray + 1], p2 = io.d_rgb[3 * ray + 2];
         const float p_alpha = io.d_alpha ? io.d_alpha[ray] : 0.0f;
         const float p_depth = io.d_depth ? io.d_depth[ray] : 0.0f;
         const float tau_S = io.cache[ray];
+        // d(loss)/dT_S through alpha = 1 - T_S and rgb += T_S bg, times T_S
         const float kS = __expf(-tau_S) * (p_alpha - (p0 * io.bg[0] + p1 * io.bg[1] + p2 * io.bg[2]));
         float tau_end = tau_S;  // optical depth up to the end of the current step
         float carry = 0.0f;     // sum of w_j a_j over all later steps
 
-        for (int j0 = ((S - 1) / kBwdStep) * kBwdStep; j0 >= 0; j0 -= kBwdStep) {
+        for (int j0 = j_last; j0 >= 0; j0 -= kBwdStep) {
             StepActs<C, H, NH, kBwdNB> a;
-            forward_step<KIND, C, H, NH, true, kBwdNB, true>(g, lds, q, j0, S, lane, a);
+            a.cell[0] = cell;
+#pragma unroll
+            for (int s = 0; s < KS1; ++s) { a.fh[0][s] = fh[s]; a.fl[0][s] = fl[s]; }
+            mlp_forward<C, H, NH, true, kBwdNB>(lds, lane, a);
 
             // ---- emission-absorption backward; MFMA column col stands for sample
             //      j0 + slot_to_sample(col) (both lane groups alike), so the scans along the
@@ -202,7 +240,10 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
             const Frag (&lh)[kBwdNB][KSH] = NH == 2 ? a.h2h : a.h1h;  // last hidden layer's activations
             const Frag (&ll)[kBwdNB][KSH] = NH == 2 ? a.h2l : a.h1l;
 
-            // ---- output layer: dWo += dZo * Hlast^T over the samples of the step ----
+            // ---- output layer: dWo += dZo * Hlast^T over the samples of the step ;
+            //      last hidden layer: dZ = relu'(.) * (Wout^T dZo) ----
+            f32x16 acc[MB][kBwdNB];
+            layer_mfma<MB, 1, kBwdNB, true>(acc, lds + L::T3, lane, gzo_h, gzo_l);
             {
                 Frag ah[kBwdKS], al[kBwdKS];
                 pack_exact(mfma1(gzo_h[0][0], sel_o, zero16()), ah);
@@ -216,18 +257,13 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
                     park(dWo[nb2]);
                 }
             }
-            __builtin_amdgcn_sched_barrier(0);
-
-            // ---- last hidden layer: dZ = relu'(.) * (Wout^T dZo) ----
-            f32x16 acc[MB][kBwdNB];
-            layer_mfma<MB, 1, kBwdNB, true>(acc, lds + L::T3, lane, gzo_h, gzo_l);
             relu_mask<MB>(acc, lh);
             Frag gz_h[kBwdNB][KSH], gz_l[kBwdNB][KSH];
             to_operands<MB, false, kBwdNB>(acc, gz_h, gz_l);
             __builtin_amdgcn_sched_barrier(0);
 
             if constexpr (NH == 2) {
-                // ---- dW2 += dZ2 * H1^T ; db2 += sum dZ2 ----
+                // ---- dW2 += dZ2 * H1^T ; db2 += sum dZ2 ; dZ1 = relu'(.) * (W2^T dZ2) ----
                 Frag ah[MB][kBwdKS], al[MB][kBwdKS];
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb) {
@@ -235,6 +271,7 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
 #pragma unroll
                     for (int ks = 0; ks < kBwdKS; ++ks) db2[mb] = frag_sum(al[mb][ks], frag_sum(ah[mb][ks], db2[mb]));
                 }
+                layer_mfma<MB, KSH, kBwdNB, true>(acc, lds + L::T2, lane, gz_h, gz_l);
 #pragma unroll
                 for (int nb2 = 0; nb2 < MB; ++nb2) {
                     Frag bh[kBwdKS], bl[kBwdKS];
@@ -246,15 +283,13 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
                         park(dW2[mb][nb2]);
                     }
                 }
-                __builtin_amdgcn_sched_barrier(0);
-                // ---- dZ1 = relu'(.) * (W2^T dZ2) ----
-                layer_mfma<MB, KSH, kBwdNB, true>(acc, lds + L::T2, lane, gz_h, gz_l);
                 relu_mask<MB>(acc, a.h1h);
                 to_operands<MB, false, kBwdNB>(acc, gz_h, gz_l);
                 __builtin_amdgcn_sched_barrier(0);
             }
 
-            // ---- first layer: dW1 += dZ1 * F^T ; db1 += sum dZ1 ----
+            // ---- first layer: dW1 += dZ1 * F^T ; db1 += sum dZ1 ; feature gradient, transposed:
+            //      dF^T[sample][channel] = dZ1^T W1 ; meanwhile the sampling of the next step ----
             {
                 Frag bh[kBwdKS], bl[kBwdKS];
                 {
@@ -279,9 +314,6 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
                     park(dW1[mb]);
                 }
             }
-            __builtin_amdgcn_sched_barrier(0);
-
-            // ---- feature gradient, transposed: dF^T[sample][channel] = dZ1^T W1, then scatter ----
             f32x16 dFt;
 #pragma unroll
             for (int s = 0; s < KSH; ++s) {
@@ -289,6 +321,23 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
                 load_operand(lds + L::T1 + s * 128, lane, th, tl);
                 dFt = s == 0 ? mfma3_first(gz_h[0][s], gz_l[0][s], th, tl) : mfma3(gz_h[0][s], gz_l[0][s], th, tl, dFt);
             }
+            // cell of the next step of this ray, or of the last step of the next ray
+            const bool same = j0 > 0;
+            const RayGeom& qn = same ? q : q_next;
+            cell = sample_cell(g, qn, min((same ? j0 - kBwdStep : j_last) + slot_to_sample(col), S - 1));
+            __builtin_amdgcn_sched_barrier(0);
+            {
+                float feat[C / 2];
+                gather_half<KIND, C, C / 2>(g, qn.scene, cell, grp * (C / 2), feat);
+#pragma unroll
+                for (int s = 0; s < KS1; ++s) split8(feat + 8 * s, fh[s], fl[s]);
+            }
+            // the sampled features must be complete here (not sunk below the scatter)
+#pragma unroll
+            for (int s = 0; s < KS1; ++s)
+#pragma unroll
+                for (int w = 0; w < 4; ++w) asm volatile("" : "+v"(fh[s].d[w]), "+v"(fl[s].d[w]));
+            __builtin_amdgcn_sched_barrier(0);
             wave_lds_fence();
             scatter_channels<KIND, C>(g, io.d_grid, q.scene, info, dFt, col, grp);
         }
@@ -338,7 +387,14 @@ hipError_t launch_bwd(const GridDev& g, const MlpDev& m, const RaysDev& rays, co
     hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (e != hipSuccess) return e;
     const int blocks = mfma_bwd_records(n_cu) / kWaves;  // every wave writes a record, busy or not
-    hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kWaves * 64), kLdsBytes, stream, g, m, rays, io);
+    // multiplier of the ray-group scramble: a prime that does not divide the number of groups,
+    // so that group -> group * mul mod n_groups is a bijection
+    const long long n_groups = (rays.M + kWaves - 1) / kWaves;
+    long long group_mul = 1;
+    for (long long p : {7919LL, 7907LL, 7901LL, 7883LL})
+        if (n_groups > p && n_groups % p != 0) { group_mul = p; break; }
+    hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kWaves * 64), kLdsBytes, stream, g, m, rays, io,
+                       group_mul);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int threads = 256;

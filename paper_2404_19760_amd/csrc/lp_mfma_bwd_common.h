@@ -48,15 +48,19 @@ __device__ __forceinline__ void relu_mask(f32x16 (&acc)[MB][kBwdNB], const Frag 
 }
 
 // ---- scatter records: what the channel lanes need to know about each sample of the step ----
-// 16 dwords per sample.  voxel: 8 corner weights (corner 4dx + 2dy + dz), then the element offset of
-// corner 0.  triplane: 12 weights (plane p, corner 2da + db at 4p + ..), then 3 plane offsets.
+// 16 dwords per sample.  voxel: 8 corner weights, then the element offset of corner 0; the
+// weights are in corner order 4dx + 2dy + dz for 32 channels and in order 4dz + 2dx + dy for 16
+// channels (where the two halves of a lane group take the corners of one dz each).
+// triplane: 12 weights (plane p, corner 2da + db at 4p + ..), then 3 plane offsets.
 template <int KIND, int C>
 __device__ __forceinline__ void write_scatter_record(float* rec, const GridDev& g, const Cell3& c)
 {
     if constexpr (KIND == LP_GRID_VOXEL) {
         const float x1 = c.f[0], x0 = 1.0f - x1, y1 = c.f[1], y0 = 1.0f - y1, z1 = c.f[2], z0 = 1.0f - z1;
-        const float4 w0 = make_float4(x0 * y0 * z0, x0 * y0 * z1, x0 * y1 * z0, x0 * y1 * z1);
-        const float4 w1 = make_float4(x1 * y0 * z0, x1 * y0 * z1, x1 * y1 * z0, x1 * y1 * z1);
+        const float4 w0 = C == 16 ? make_float4(x0 * y0 * z0, x0 * y1 * z0, x1 * y0 * z0, x1 * y1 * z0)
+                                  : make_float4(x0 * y0 * z0, x0 * y0 * z1, x0 * y1 * z0, x0 * y1 * z1);
+        const float4 w1 = C == 16 ? make_float4(x0 * y0 * z1, x0 * y1 * z1, x1 * y0 * z1, x1 * y1 * z1)
+                                  : make_float4(x1 * y0 * z0, x1 * y0 * z1, x1 * y1 * z0, x1 * y1 * z1);
         const unsigned sz = C, sy = (unsigned)g.N[2] * C, sx = (unsigned)g.N[1] * sy;
         const unsigned base = (unsigned)c.i[0] * sx + (unsigned)c.i[1] * sy + (unsigned)c.i[2] * sz;
         reinterpret_cast<float4*>(rec)[0] = w0;
@@ -110,7 +114,38 @@ __device__ __forceinline__ void scatter_channels(const GridDev& g, float* const 
                                                  const float* info, const f32x16& dFt, int ch, int grp)
 {
     const bool live = ch < C;
-    if constexpr (KIND == LP_GRID_VOXEL) {
+    if constexpr (KIND == LP_GRID_VOXEL && C == 16) {
+        // 16 channels fill half a lane group: lanes 16..31 hold the same feature gradients as lanes
+        // 0..15 (the transposed first-layer weights are staged twice), and each half takes the four
+        // corners of one dz, so that a flush is four instructions on two full 64-byte lines each
+        const int c16 = ch & 15, dz = ch >> 4;
+        const unsigned sz = C, sy = (unsigned)g.N[2] * C, sx = (unsigned)g.N[1] * sy;
+        char* V = reinterpret_cast<char*>(d_grid[0] + (size_t)scene * g.N[0] * g.N[1] * g.N[2] * C);
+        char* Vd[4];  // uniform pointer per (dx, dy)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) Vd[k] = V + 4u * (size_t)((k >> 1) * sx + (k & 1) * sy);
+        const unsigned lane_off = dz * sz + c16;
+        float acc[4];
+        unsigned prev = 0;
+        auto flush = [&]() {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) atomicAdd(reinterpret_cast<float*>(Vd[k] + 4u * (prev + lane_off)), acc[k]);
+        };
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const float* rec = info + d_row(r, grp) * 16;
+            const float4 w4 = reinterpret_cast<const float4*>(rec)[dz];
+            const unsigned base = reinterpret_cast<const unsigned*>(rec)[8];
+            const float w[4] = {w4.x, w4.y, w4.z, w4.w};
+            const float v = dFt[r];
+            if (r > 0 && base != prev) flush();
+            const bool fresh = r == 0 || base != prev;
+            prev = base;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) acc[k] = fresh ? w[k] * v : acc[k] + w[k] * v;
+        }
+        flush();
+    } else if constexpr (KIND == LP_GRID_VOXEL) {
         // uniform base pointer + 32-bit byte offset per lane (a scene's tensor is below 4 GiB)
         char* V = reinterpret_cast<char*>(d_grid[0] + (size_t)scene * g.N[0] * g.N[1] * g.N[2] * C);
         const unsigned sz = C, sy = (unsigned)g.N[2] * C, sx = (unsigned)g.N[1] * sy;

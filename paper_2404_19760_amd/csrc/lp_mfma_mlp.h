@@ -22,7 +22,7 @@ struct MlpLds {
     // transposed weights for the input-gradient chain (backward only)
     static constexpr int T3 = FWD_END;                             // Wout^T [MB][1]
     static constexpr int T2 = T3 + (BWD ? MB * 128 : 0);           // W2^T   [MB][KSH]  (NH == 2)
-    static constexpr int T1 = T2 + (BWD && NH == 2 ? MB * KSH * 128 : 0);  // W1^T [1][KSH], rows >= C zero
+    static constexpr int T1 = T2 + (BWD && NH == 2 ? MB * KSH * 128 : 0);  // W1^T [1][KSH], 32 rows
     static constexpr int W_END = T1 + (BWD ? KSH * 128 : 0);
     static constexpr int BIAS = W_END;                             // floats: b1[H] b2[H] bout[4]
     static constexpr int BIAS_UNITS = (2 * H + 4 + 3) / 4;
@@ -56,7 +56,9 @@ __device__ __forceinline__ void stage_mlp(uint4* lds, const MlpDev& m)
         if constexpr (NH == 2)
             stage_operand_t(lds + L::T2, m.W[1], MB, KSH, H, [](int mb, int i) { return 32 * mb + i; },
                             [](int s, int gg, int e) { return k_hidden(s, gg, e); });
-        stage_operand_t(lds + L::T1, m.W[0], 1, KSH, C, [](int, int i) { return i < C ? i : -1; },
+        // rows >= C: zero for C = 32 (none), a second copy of the 16 rows for C = 16 (the scatter of
+        // the backward kernel uses both halves of a lane group)
+        stage_operand_t(lds + L::T1, m.W[0], 1, KSH, C, [](int, int i) { return i & (C - 1); },
                         [](int s, int gg, int e) { return k_hidden(s, gg, e); });
     }
     float* sbias = reinterpret_cast<float*>(lds + L::BIAS);
@@ -182,26 +184,15 @@ __host__ __device__ constexpr int sample_to_slot(int smp)
     return 8 * ((smp >> 2) & 3) + 4 * (smp >> 4) + (smp & 3);
 }
 
-template <int KIND, int C, int H, int NH, bool BWD, int NB, bool PERM = false>
-__device__ __forceinline__ void forward_step(const GridDev& g, const uint4* lds, const RayGeom& q, int j0, int S,
-                                             int lane, StepActs<C, H, NH, NB>& a)
+// MLP forward of one step from the input features a.fh / a.fl: fills the hidden activations and
+// the decoder outputs a.z.
+template <int C, int H, int NH, bool BWD, int NB>
+__device__ __forceinline__ void mlp_forward(const uint4* lds, int lane, StepActs<C, H, NH, NB>& a)
 {
     using L = MlpLds<C, H, NH, BWD, NB>;
     constexpr int MB = L::MB, KS1 = L::KS1, KSH = L::KSH;
-    const int col = lane & 31, grp = lane >> 5;
+    const int grp = lane >> 5;
     const float* sbias = reinterpret_cast<const float*>(lds + L::BIAS);
-
-    // sample + interpolate this lane's half of the channels of sample col of every N block
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-        const int j = min(j0 + 32 * nb + (PERM ? slot_to_sample(col) : col), S - 1);
-        const Cell3 c = sample_cell(g, q, j);
-        a.cell[nb] = c;
-        float feat[C / 2];
-        gather_half<KIND, C, C / 2>(g, q.scene, c, grp * (C / 2), feat);
-#pragma unroll
-        for (int s = 0; s < KS1; ++s) split8(feat + 8 * s, a.fh[nb][s], a.fl[nb][s]);
-    }
 
     f32x16 acc[MB][NB];
     init_bias<MB, NB>(acc, sbias, grp);
@@ -233,6 +224,27 @@ __device__ __forceinline__ void forward_step(const GridDev& g, const uint4* lds,
     }
 #pragma unroll
     for (int k = 0; k < 4; ++k) a.z[k] = (NB == 2 && grp) ? o[NB - 1][k] : o[0][k];
+}
+
+// Sampling + MLP forward of one step: lane (col, grp) samples its half of the channels of
+// sample col of every N block (PERM: of the permuted step, see slot_to_sample).
+template <int KIND, int C, int H, int NH, bool BWD, int NB, bool PERM = false>
+__device__ __forceinline__ void forward_step(const GridDev& g, const uint4* lds, const RayGeom& q, int j0, int S,
+                                             int lane, StepActs<C, H, NH, NB>& a)
+{
+    constexpr int KS1 = C / 16;
+    const int col = lane & 31, grp = lane >> 5;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        const int j = min(j0 + 32 * nb + (PERM ? slot_to_sample(col) : col), S - 1);
+        const Cell3 c = sample_cell(g, q, j);
+        a.cell[nb] = c;
+        float feat[C / 2];
+        gather_half<KIND, C, C / 2>(g, q.scene, c, grp * (C / 2), feat);
+#pragma unroll
+        for (int s = 0; s < KS1; ++s) split8(feat + 8 * s, a.fh[nb][s], a.fl[nb][s]);
+    }
+    mlp_forward<C, H, NH, BWD, NB>(lds, lane, a);
 }
 
 // Forward of one 64-sample step for the forward kernel, which keeps nothing but the decoder
