@@ -145,6 +145,7 @@ class Inputs:
     samples: int
     bg: Tuple[float, float, float]
     target: Optional[np.ndarray] = None  # [M][3] float32 (for the MSE loss)
+    contract_a: float = 0.0           # > 0: contract coordinates with this foreground scale
 
     @property
     def n_rays(self) -> int:

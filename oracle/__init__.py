@@ -36,7 +36,8 @@ class _Grid(C.Structure):
     _fields_ = [("kind", C.c_int32), ("B", C.c_int32), ("C", C.c_int32),
                 ("NX", C.c_int32), ("NY", C.c_int32), ("NZ", C.c_int32),
                 ("data", C.c_void_p * 3),
-                ("aabb_min", C.c_double * 3), ("aabb_max", C.c_double * 3)]
+                ("aabb_min", C.c_double * 3), ("aabb_max", C.c_double * 3),
+                ("contract_a", C.c_double)]
 
 
 class _Mlp(C.Structure):
@@ -93,6 +94,8 @@ class Problem:
         for a in range(3):
             g.aabb_min[a] = float(inp.aabb_min[a])
             g.aabb_max[a] = float(inp.aabb_max[a])
+        # the library takes the scale as float32; widen that value exactly
+        g.contract_a = float(np.float32(getattr(inp, "contract_a", 0.0)))
         self.c_grid = g
 
         m = _Mlp()

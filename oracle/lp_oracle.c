@@ -23,6 +23,10 @@
  *   - one MLP C -> ... -> 4: ReLU hidden layers, linear last layer; output 0 through
  *     softplus is the density, outputs 1..3 through the logistic sigmoid are the colour.
  *   - depth = sum_j w_j t_j (a rendered feature like any other); rgb gets + T_S * bg.
+ *   - contract coordinates (appendix, "Experimental Details", the equation CC(x)): when the
+ *     scale a is positive, every axis of a sample position goes through CC on its own (the
+ *     text says the axes are converted independently, so ||x|| and x/||x|| are |x| and
+ *     sign(x)) before the box mapping; sample spacing Delta stays the world distance.
  *
  * All arithmetic is double.  Parallel over rays only (OpenMP); grid gradients are
  * added with atomic updates, weight gradients in per-thread buffers summed at the end.
@@ -43,6 +47,7 @@ typedef struct {
     int32_t kind, B, C, NX, NY, NZ;
     const double* data[3];
     double aabb_min[3], aabb_max[3];
+    double contract_a; /* 0: no contraction; else the foreground scale a of CC */
 } lpo_grid;
 
 typedef struct {
@@ -63,6 +68,22 @@ typedef struct {
 } lpo_rays;
 
 /* ---- Section 3.2: the hashing scheme h (bi/tri-linear interpolation) ---------- */
+
+/* CC of one coordinate: 0.5 a x inside the unit interval; outside, magnitude
+ * 0.5 ((2 - a)(1 - 1/|x|) + a) with the sign of x.  Maps the real line into (-1, 1). */
+static double contract_axis(double x, double a)
+{
+    double m = fabs(x);
+    if (m <= 1.0) return 0.5 * a * x;
+    double r = 0.5 * ((2.0 - a) * (1.0 - 1.0 / m) + a);
+    return x < 0.0 ? -r : r;
+}
+
+/* position the hash structure is read at: the sample position, contracted if asked for */
+static void grid_position(const lpo_grid* g, const double x[3], double y[3])
+{
+    for (int a = 0; a < 3; ++a) y[a] = g->contract_a > 0.0 ? contract_axis(x[a], g->contract_a) : x[a];
+}
 
 /* continuous index along one axis -> cell index i in [0, N-2] and fraction f in [0,1] */
 static void axis_cell(double x, double lo, double hi, int N, int* i, double* f)
@@ -107,9 +128,10 @@ static void plane_scatter(double* P, int NB, int C, int ia, int ib, double fa, d
 static void grid_gather(const lpo_grid* g, int b, const double x[3], double* feat)
 {
     int i[3];
-    double f[3];
+    double f[3], y[3];
     const int N[3] = {g->NX, g->NY, g->NZ};
-    for (int a = 0; a < 3; ++a) axis_cell(x[a], g->aabb_min[a], g->aabb_max[a], N[a], &i[a], &f[a]);
+    grid_position(g, x, y);
+    for (int a = 0; a < 3; ++a) axis_cell(y[a], g->aabb_min[a], g->aabb_max[a], N[a], &i[a], &f[a]);
     const int C = g->C;
     for (int k = 0; k < C; ++k) feat[k] = 0.0;
     if (g->kind == LPO_VOXEL) {
@@ -136,9 +158,10 @@ static void grid_scatter(const lpo_grid* g, double* const d_grid[3], int b, cons
                          const double* dfeat)
 {
     int i[3];
-    double f[3];
+    double f[3], y[3];
     const int N[3] = {g->NX, g->NY, g->NZ};
-    for (int a = 0; a < 3; ++a) axis_cell(x[a], g->aabb_min[a], g->aabb_max[a], N[a], &i[a], &f[a]);
+    grid_position(g, x, y);
+    for (int a = 0; a < 3; ++a) axis_cell(y[a], g->aabb_min[a], g->aabb_max[a], N[a], &i[a], &f[a]);
     const int C = g->C;
     if (g->kind == LPO_VOXEL) {
         double* V = d_grid[0] + (int64_t)b * g->NX * g->NY * g->NZ * C;
