@@ -38,8 +38,8 @@ def parse():
     ap.add_argument("--math", default="default", choices=["default", "generic", "bf16x3"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
-    ap.add_argument("--also", default="single_scene",
-                    help="second workload reported for context under 'also' ('' to skip)")
+    ap.add_argument("--also", default="single_scene,contract",
+                    help="further workloads reported for context under 'also' (comma-separated, '' to skip)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy kernel (reference for HBM counters)")
     return ap.parse_args()
@@ -176,17 +176,21 @@ def main():
                      "traffic": MEASURED_BWD_HBM_BYTES.get(args.config) if fast else None,
                      "bytes_per_sample": 2 * g_bytes, "ms": bwd_avg},
     }
-    if args.also and args.also != args.config:
-        # a second workload for context (short run), e.g. the single-scene configuration
-        del r
+    # further workloads for context (short runs), e.g. the single-scene configuration and the
+    # paper's experimental Renderer shape with contract coordinates
+    del r
+    for name in [n for n in args.also.split(",") if n and n != args.config]:
         torch.cuda.empty_cache()
-        o = measure(lp, torch, args.also, mode, max(3, args.steps // 2), 2)
+        k = max(3, args.steps // 2)
+        o = measure(lp, torch, name, mode, k, 2)
         ow = o["w"]
-        out["also"] = {"workload": args.also, "ray_samples": o["samples"],
-                       "value": o["samples"] / (o["elapsed"] / max(3, args.steps // 2)), "unit": "ray-samples/s",
-                       "fwd_ms": o["fwd_ms"], "bwd_ms": o["bwd_ms"],
-                       "fwd_bwd_frac_hbm_peak": 3 * ow.gather_bytes_per_sample * o["samples"]
-                       / ((o["fwd_ms"] + o["bwd_ms"]) * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        out.setdefault("also", []).append(
+            {"workload": name, "ray_samples": o["samples"], "value": o["samples"] / (o["elapsed"] / k),
+             "unit": "ray-samples/s", "fwd_ms": o["fwd_ms"], "bwd_ms": o["bwd_ms"],
+             "contract_a": ow.contract_a,
+             "fwd_bwd_frac_hbm_peak": 3 * ow.gather_bytes_per_sample * o["samples"]
+             / ((o["fwd_ms"] + o["bwd_ms"]) * 1e-3) / 1e9 / HBM_PEAK_GBS})
+        del o
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(inp, args.cpu_seconds)
     print(json.dumps(out))

@@ -48,6 +48,12 @@ typedef enum { LP_GRID_VOXEL = 0, LP_GRID_TRIPLANE = 1 } lp_grid_kind;
  *             bilinearly and SUMS the three feature vectors.
  * World coordinate aabb_min[a] maps to index 0 and aabb_max[a] to index N_a - 1 along axis
  * a; positions outside the box are clamped onto it.  B scenes share the MLP.
+ * contract_a: 0 = off.  In (0, 2]: contract coordinates (appendix, "Experimental Details",
+ * equation CC) with foreground scale a: every axis of a sample position is first mapped by
+ * CC(x) = 0.5 a x for |x| <= 1 and 0.5 ((2 - a)(1 - 1/|x|) + a) sign(x) beyond (the paper
+ * converts the axes independently), which sends the whole line into (-1, 1) and the unit
+ * interval onto [-a/2, a/2]; the box mapping above then applies to the contracted position
+ * (use the box [-1, 1]^3).  Sample spacing stays the world distance along the ray.
  */
 typedef struct {
     int32_t kind; /* lp_grid_kind */
@@ -55,6 +61,7 @@ typedef struct {
     int32_t NX, NY, NZ;
     const float* data[3]; /* device */
     float aabb_min[3], aabb_max[3];
+    float contract_a;
 } lp_grid;
 
 /*

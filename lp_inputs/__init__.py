@@ -40,6 +40,7 @@ class Workload:
     far: float = 4.0
     aabb: float = 2.75        # grid spans [-aabb, aabb]^3
     cfg_id: int = 0
+    contract_a: float = 0.0   # > 0: contract coordinates with this foreground scale (grid spans [-1, 1]^3)
 
     @property
     def rays(self) -> int:
@@ -76,6 +77,11 @@ WORKLOADS = {
                         (32, 64, 64, 4), 256, 4, 192, cfg_id=4),
     "large": Workload("large", VOXEL, 1, 16, (256, 256, 256), 0.05,
                       (16, 64, 64, 4), 800, 1, 512, cfg_id=5),
+    # The Renderer shape of the paper's experiments (appendix, "Experimental Details"): 160^3 voxel
+    # grid with 32 features, 3-layer MLP of width 64, 256^2 image, 384 points per ray, contract
+    # coordinates (unbounded scene: the rays run far beyond the unit cube).
+    "contract": Workload("contract", VOXEL, 1, 32, (160, 160, 160), 0.1, (32, 64, 64, 4),
+                         256, 1, 384, near=0.5, far=12.0, aabb=1.0, cfg_id=6, contract_a=1.0),
 }
 WORKLOAD_ORDER = ["tiny", "single_scene", "voxel", "batched", "large"]
 
@@ -230,7 +236,8 @@ def make_inputs(name: str, aabb: Optional[float] = None, with_grid: bool = True)
     return Inputs(kind=w.kind, n_scenes=w.n_scenes, channels=w.channels, res=w.res, grid=grid,
                   aabb_min=(-a, -a, -a), aabb_max=(a, a, a), mlp_dims=w.mlp_dims,
                   weights=ws, biases=bs, origins=origins, dirs=dirs, near=near, far=far,
-                  scene=scene, samples=w.samples, bg=(1.0, 1.0, 1.0), target=target)
+                  scene=scene, samples=w.samples, bg=(1.0, 1.0, 1.0), target=target,
+                  contract_a=w.contract_a)
 
 
 def strided_ray_subset(n_rays: int, n_keep: int, offset: int = 0) -> np.ndarray:

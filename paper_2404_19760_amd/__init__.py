@@ -35,7 +35,7 @@ class _Grid(C.Structure):
     _fields_ = [("kind", C.c_int32), ("B", C.c_int32), ("C", C.c_int32),
                 ("NX", C.c_int32), ("NY", C.c_int32), ("NZ", C.c_int32),
                 ("data", C.c_void_p * 3),
-                ("aabb_min", C.c_float * 3), ("aabb_max", C.c_float * 3)]
+                ("aabb_min", C.c_float * 3), ("aabb_max", C.c_float * 3), ("contract_a", C.c_float)]
 
 
 class _Mlp(C.Structure):
@@ -101,6 +101,7 @@ class Grid:
     res: Sequence[int]
     aabb_min: Sequence[float] = (-1.0, -1.0, -1.0)
     aabb_max: Sequence[float] = (1.0, 1.0, 1.0)
+    contract_a: float = 0.0
 
     @property
     def n_scenes(self) -> int:
@@ -129,6 +130,7 @@ class Grid:
         for a in range(3):
             g.aabb_min[a] = float(self.aabb_min[a])
             g.aabb_max[a] = float(self.aabb_max[a])
+        g.contract_a = float(self.contract_a)
         return g
 
 
@@ -264,7 +266,8 @@ def to_device(inp, device="cuda:0"):
     dev = torch.device(device)
     up = lambda a: torch.from_numpy(a).to(dev)
     grid = Grid(kind=int(inp.kind), data=[up(g) for g in inp.grid], res=tuple(inp.res),
-                aabb_min=tuple(inp.aabb_min), aabb_max=tuple(inp.aabb_max))
+                aabb_min=tuple(inp.aabb_min), aabb_max=tuple(inp.aabb_max),
+                contract_a=float(getattr(inp, "contract_a", 0.0)))
     mlp = Mlp(weights=[up(w) for w in inp.weights], biases=[up(b) for b in inp.biases])
     rays = Rays(origins=up(inp.origins), dirs=up(inp.dirs), near=up(inp.near), far=up(inp.far),
                 samples=int(inp.samples), scene=None if inp.scene is None else up(inp.scene))

@@ -15,6 +15,7 @@ struct GridDev {
     int N[3];
     double amin[3];
     double scale[3];  // (N-1)/(max-min): world -> continuous index
+    double contract;  // foreground scale a of the contract coordinates, 0 = off
 };
 
 struct MlpDev {
@@ -64,8 +65,21 @@ struct BwdIo {
 // fraction inside the cell in [0, 1].  The index is formed in fp64 (full rate on this chip):
 // in fp32 an index of a few hundred has a spacing of 1e-5 and more, which would put a relative
 // error of up to 1e-4 on every interpolated feature of a fine grid.
-__device__ __forceinline__ void axis_cell(double x, double lo, double scale, int N, int& i, float& f)
+// CC = true: the coordinate first goes through the contraction of the paper's appendix with
+// foreground scale a = `contract` (0.5 a x inside the unit interval,
+// 0.5 ((2 - a)(1 - 1/|x|) + a) sign(x) beyond), each axis on its own.  1/|x| from the fp32
+// reciprocal plus one Newton step in fp64 (relative error ~1e-14).
+template <bool CC = false>
+__device__ __forceinline__ void axis_cell(double x, double lo, double scale, int N, double contract, int& i,
+                                          float& f)
 {
+    if constexpr (CC) {
+        const double m = fmax(fabs(x), 1.0);
+        double r = (double)__frcp_rn((float)m);
+        r = r * (2.0 - m * r);
+        const double far = copysign(0.5 * ((2.0 - contract) * (1.0 - r) + contract), x);
+        x = fabs(x) <= 1.0 ? 0.5 * contract * x : far;
+    }
     double u = (x - lo) * scale;
     u = fmin(fmax(u, 0.0), (double)(N - 1));
     int c = (int)u;  // u >= 0: truncation is floor

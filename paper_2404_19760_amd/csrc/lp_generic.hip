@@ -32,9 +32,12 @@ struct Cell {
 __device__ __forceinline__ Cell locate(const GridDev& g, double x, double y, double z)
 {
     Cell c;
-    axis_cell(x, g.amin[0], g.scale[0], g.N[0], c.i[0], c.f[0]);
-    axis_cell(y, g.amin[1], g.scale[1], g.N[1], c.i[1], c.f[1]);
-    axis_cell(z, g.amin[2], g.scale[2], g.N[2], c.i[2], c.f[2]);
+    if (g.contract > 0.0) axis_cell<true>(x, g.amin[0], g.scale[0], g.N[0], g.contract, c.i[0], c.f[0]);
+    else axis_cell<false>(x, g.amin[0], g.scale[0], g.N[0], g.contract, c.i[0], c.f[0]);
+    if (g.contract > 0.0) axis_cell<true>(y, g.amin[1], g.scale[1], g.N[1], g.contract, c.i[1], c.f[1]);
+    else axis_cell<false>(y, g.amin[1], g.scale[1], g.N[1], g.contract, c.i[1], c.f[1]);
+    if (g.contract > 0.0) axis_cell<true>(z, g.amin[2], g.scale[2], g.N[2], g.contract, c.i[2], c.f[2]);
+    else axis_cell<false>(z, g.amin[2], g.scale[2], g.N[2], g.contract, c.i[2], c.f[2]);
     return c;
 }
 

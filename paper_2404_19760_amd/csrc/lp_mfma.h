@@ -217,12 +217,13 @@ struct Cell3 {
     float f[3];
 };
 
+template <bool CC>
 __device__ __forceinline__ Cell3 locate3(const GridDev& g, double x, double y, double z)
 {
     Cell3 c;
-    axis_cell(x, g.amin[0], g.scale[0], g.N[0], c.i[0], c.f[0]);
-    axis_cell(y, g.amin[1], g.scale[1], g.N[1], c.i[1], c.f[1]);
-    axis_cell(z, g.amin[2], g.scale[2], g.N[2], c.i[2], c.f[2]);
+    axis_cell<CC>(x, g.amin[0], g.scale[0], g.N[0], g.contract, c.i[0], c.f[0]);
+    axis_cell<CC>(y, g.amin[1], g.scale[1], g.N[1], g.contract, c.i[1], c.f[1]);
+    axis_cell<CC>(z, g.amin[2], g.scale[2], g.N[2], g.contract, c.i[2], c.f[2]);
     return c;
 }
 

@@ -78,7 +78,7 @@ __device__ __forceinline__ Frag selection(int j, int grp, IndexFn index_of)
     return f;
 }
 
-template <int KIND, int C, int H, int NH>
+template <int KIND, int C, int H, int NH, bool CC>
 __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev m, RaysDev rays, BwdIo io,
                                                                long long group_mul)
 {
@@ -162,7 +162,7 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
     Frag fh[KS1], fl[KS1];
     if (seq < sched.end) {  // a wave without rays only writes its (zero) record
         q_next = load_ray_geom(rays, ray_of(seq));
-        cell = sample_cell(g, q_next, min(j_last + slot_to_sample(col), S - 1));
+        cell = sample_cell<CC>(g, q_next, min(j_last + slot_to_sample(col), S - 1));
         float feat[C / 2];
         gather_half<KIND, C, C / 2>(g, q_next.scene, cell, grp * (C / 2), feat);
 #pragma unroll
@@ -324,7 +324,7 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
             // cell of the next step of this ray, or of the last step of the next ray
             const bool same = j0 > 0;
             const RayGeom& qn = same ? q : q_next;
-            cell = sample_cell(g, qn, min((same ? j0 - kBwdStep : j_last) + slot_to_sample(col), S - 1));
+            cell = sample_cell<CC>(g, qn, min((same ? j0 - kBwdStep : j_last) + slot_to_sample(col), S - 1));
             __builtin_amdgcn_sched_barrier(0);
             {
                 float feat[C / 2];
@@ -377,13 +377,13 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
     }
 }
 
-template <int KIND, int C, int H, int NH>
+template <int KIND, int C, int H, int NH, bool CC>
 hipError_t launch_bwd(const GridDev& g, const MlpDev& m, const RaysDev& rays, const BwdIo& io, int n_cu,
                        hipStream_t stream)
 {
     constexpr int kLdsBytes = MlpLds<C, H, NH, true, kBwdNB>::bytes(kWaves);
     static_assert(kLdsBytes <= 160 * 1024, "LDS budget of a gfx950 compute unit");
-    auto kernel = bwd_mfma_kernel<KIND, C, H, NH>;
+    auto kernel = bwd_mfma_kernel<KIND, C, H, NH, CC>;
     hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (e != hipSuccess) return e;
     const int blocks = mfma_bwd_records(n_cu) / kWaves;  // every wave writes a record, busy or not
@@ -409,7 +409,9 @@ hipError_t dispatch_bwd(const GridDev& g, const MlpDev& m, const RaysDev& rays, 
 {
     const int C = g.C, H = m.dims[1], NH = m.n_layers - 1;
 #define LP_CASE(c, h, nh) \
-    if (C == c && H == h && NH == nh) return launch_bwd<KIND, c, h, nh>(g, m, rays, io, n_cu, stream);
+    if (C == c && H == h && NH == nh)                                                       \
+        return g.contract > 0.0 ? launch_bwd<KIND, c, h, nh, true>(g, m, rays, io, n_cu, stream) \
+                                : launch_bwd<KIND, c, h, nh, false>(g, m, rays, io, n_cu, stream);
     LP_CASE(16, 32, 1) LP_CASE(16, 64, 1) LP_CASE(32, 32, 1) LP_CASE(32, 64, 1)
     LP_CASE(16, 32, 2) LP_CASE(16, 64, 2) LP_CASE(32, 32, 2) LP_CASE(32, 64, 2)
 #undef LP_CASE

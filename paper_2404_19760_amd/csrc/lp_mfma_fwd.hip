@@ -19,7 +19,7 @@ constexpr int kWaves = 4;
 // NB = N blocks of 32 samples per step.  NB = 2: lane l owns sample l of the 64-sample step.
 // NB = 1 (half the registers, two waves per SIMD for the wide MLPs): both lane groups hold the
 // decoder outputs of sample (lane & 31); group 0 alone accumulates.
-template <int KIND, int C, int H, int NH, int NB>
+template <int KIND, int C, int H, int NH, int NB, bool CC>
 __global__ __launch_bounds__(kWaves * 64) void fwd_mfma_kernel(GridDev g, MlpDev m, RaysDev rays, FwdOut out)
 {
     constexpr int kStep = 32 * NB;
@@ -39,10 +39,10 @@ __global__ __launch_bounds__(kWaves * 64) void fwd_mfma_kernel(GridDev g, MlpDev
         for (int j0 = 0; j0 < S; j0 += kStep) {
             struct { float z[4]; } a;
             if constexpr (NB == 2) {
-                forward_outputs<KIND, C, H, NH>(g, lds, q, j0, S, lane, a.z);
+                forward_outputs<KIND, C, H, NH, CC>(g, lds, q, j0, S, lane, a.z);
             } else {
                 StepActs<C, H, NH, NB> full;
-                forward_step<KIND, C, H, NH, false, NB>(g, lds, q, j0, S, lane, full);
+                forward_step<KIND, C, H, NH, false, NB, false, CC>(g, lds, q, j0, S, lane, full);
 #pragma unroll
                 for (int k = 0; k < 4; ++k) a.z[k] = full.z[k];
             }
@@ -78,12 +78,12 @@ __global__ __launch_bounds__(kWaves * 64) void fwd_mfma_kernel(GridDev g, MlpDev
     }
 }
 
-template <int KIND, int C, int H, int NH, int NB>
+template <int KIND, int C, int H, int NH, int NB, bool CC>
 hipError_t launch_fwd(const GridDev& g, const MlpDev& m, const RaysDev& rays, const FwdOut& out, int n_cu,
                       hipStream_t stream)
 {
     constexpr int kLdsBytes = MlpLds<C, H, NH, false, NB>::bytes(kWaves);
-    auto kernel = fwd_mfma_kernel<KIND, C, H, NH, NB>;
+    auto kernel = fwd_mfma_kernel<KIND, C, H, NH, NB, CC>;
     hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (e != hipSuccess) return e;
     // persistent grid: as many workgroups as fit a compute unit's registers, a multiple of the 8 XCDs, no more than the rays need
@@ -101,7 +101,9 @@ hipError_t dispatch_fwd(const GridDev& g, const MlpDev& m, const RaysDev& rays, 
 {
     const int C = g.C, H = m.dims[1], NH = m.n_layers - 1;
 #define LP_CASE(c, h, nh) \
-    if (C == c && H == h && NH == nh) return launch_fwd<KIND, c, h, nh, 2>(g, m, rays, out, n_cu, stream);
+    if (C == c && H == h && NH == nh)                                                            \
+        return g.contract > 0.0 ? launch_fwd<KIND, c, h, nh, 2, true>(g, m, rays, out, n_cu, stream) \
+                                : launch_fwd<KIND, c, h, nh, 2, false>(g, m, rays, out, n_cu, stream);
     LP_CASE(16, 32, 1) LP_CASE(16, 64, 1) LP_CASE(32, 32, 1) LP_CASE(32, 64, 1)
     LP_CASE(16, 32, 2) LP_CASE(16, 64, 2) LP_CASE(32, 32, 2) LP_CASE(32, 64, 2)
 #undef LP_CASE

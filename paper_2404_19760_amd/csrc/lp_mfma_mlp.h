@@ -165,10 +165,11 @@ __device__ __forceinline__ RayGeom load_ray_geom(const RaysDev& rays, long long 
 }
 
 // Cell of sample j (0-based): t_j = near + (j + 1/2) Delta, x = o + t d, in fp64 from the fp32 inputs.
+template <bool CC>
 __device__ __forceinline__ Cell3 sample_cell(const GridDev& g, const RayGeom& q, int j)
 {
     const double t = (double)q.near + ((double)j + 0.5) * q.delta64;
-    return locate3(g, (double)q.ox + t * (double)q.dx, (double)q.oy + t * (double)q.dy,
+    return locate3<CC>(g, (double)q.ox + t * (double)q.dx, (double)q.oy + t * (double)q.dy,
                    (double)q.oz + t * (double)q.dz);
 }
 
@@ -228,7 +229,7 @@ __device__ __forceinline__ void mlp_forward(const uint4* lds, int lane, StepActs
 
 // Sampling + MLP forward of one step: lane (col, grp) samples its half of the channels of
 // sample col of every N block (PERM: of the permuted step, see slot_to_sample).
-template <int KIND, int C, int H, int NH, bool BWD, int NB, bool PERM = false>
+template <int KIND, int C, int H, int NH, bool BWD, int NB, bool PERM = false, bool CC = false>
 __device__ __forceinline__ void forward_step(const GridDev& g, const uint4* lds, const RayGeom& q, int j0, int S,
                                              int lane, StepActs<C, H, NH, NB>& a)
 {
@@ -237,7 +238,7 @@ __device__ __forceinline__ void forward_step(const GridDev& g, const uint4* lds,
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
         const int j = min(j0 + 32 * nb + (PERM ? slot_to_sample(col) : col), S - 1);
-        const Cell3 c = sample_cell(g, q, j);
+        const Cell3 c = sample_cell<CC>(g, q, j);
         a.cell[nb] = c;
         float feat[C / 2];
         gather_half<KIND, C, C / 2>(g, q.scene, c, grp * (C / 2), feat);
@@ -252,7 +253,7 @@ __device__ __forceinline__ void forward_step(const GridDev& g, const uint4* lds,
 // remaining layers one N block after the other, so that at most one block's accumulators and
 // activations are alive at a time (registers for a second wave per SIMD).  z = outputs of
 // sample j0 + lane.
-template <int KIND, int C, int H, int NH>
+template <int KIND, int C, int H, int NH, bool CC>
 __device__ __forceinline__ void forward_outputs(const GridDev& g, const uint4* lds, const RayGeom& q, int j0,
                                                 int S, int lane, float (&z)[4])
 {
@@ -265,7 +266,7 @@ __device__ __forceinline__ void forward_outputs(const GridDev& g, const uint4* l
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
         const int j = min(j0 + 32 * nb + col, S - 1);
-        const Cell3 c = sample_cell(g, q, j);
+        const Cell3 c = sample_cell<CC>(g, q, j);
         float feat[C / 2];
         gather_half<KIND, C, C / 2>(g, q.scene, c, grp * (C / 2), feat);
 #pragma unroll

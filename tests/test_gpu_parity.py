@@ -68,6 +68,37 @@ def test_config_shapes_ragged(lp, oracle, kind, channels, dims, samples):
               flush=True)
 
 
+# ------------------------------------------------------------------ contract coordinates
+
+@pytest.mark.parametrize("kind", [VOXEL, TRIPLANE])
+@pytest.mark.parametrize("a_scale", [1.0, 1.6])
+def test_contract_coordinates(lp, oracle, kind, a_scale):
+    """Rays that start inside the unit cube and run far beyond it (the contraction's two
+    branches and the seam between them), generic and matrix-core kernels."""
+    small = lp_inputs.make_small(kind, channels=5, res=(6, 5, 7), mlp_dims=(5, 7, 4), n_rays=67, samples=41,
+                                 seed=61, origin_radius=0.8, near=(0.0, 0.3), far=(6.0, 30.0))
+    small = dataclasses.replace(small, contract_a=a_scale)
+    print(check_case(lp, oracle, small, lp.LP_MATH_GENERIC, label=f"contract small kind={kind}"), flush=True)
+    inp = lp_inputs.make_small(kind, channels=16 if kind == VOXEL else 32, res=(14, 12, 13),
+                               mlp_dims=(16, 64, 64, 4) if kind == VOXEL else (32, 64, 4), n_rays=150,
+                               samples=100, seed=62, grid_std=0.3, origin_radius=1.4, near=(0.0, 0.3),
+                               far=(6.0, 30.0))
+    inp = dataclasses.replace(inp, contract_a=a_scale)
+    for mode in _modes(lp, inp):
+        print(mode, check_case(lp, oracle, inp, mode, label=f"contract kind={kind} a={a_scale} mode={mode}"),
+              flush=True)
+
+
+def test_contract_workload_on_a_ray_subset(lp, oracle):
+    """The paper's experimental Renderer shape (160^3 x 32, width-64 MLP, 384 points per ray,
+    contract coordinates), a strided subset of its rays."""
+    inp = lp_inputs.make_inputs("contract")
+    sub = inp.subset(lp_inputs.strided_ray_subset(inp.n_rays, 1024, offset=5))
+    for mode in _modes(lp, sub)[-1:]:
+        print(mode, check_case(lp, oracle, sub, mode, label=f"contract subset mode={mode}", max_strict_fail=0.03),
+              flush=True)
+
+
 # ------------------------------------------------------------------ the five configurations
 
 def test_config_tiny_full(lp, oracle):
@@ -134,6 +165,10 @@ def test_errors_through_the_abi(lp):
     with pytest.raises(lp.LightplaneError) as e:
         lp.render_fwd(g2, m2, r2, bg, lp.LP_MATH_BF16X3)
     assert e.value.status == lp.LP_ERR_UNSUPPORTED
+    for bad in (-0.5, 2.5, float("nan")):
+        with pytest.raises(lp.LightplaneError) as e:
+            lp.render_fwd(dataclasses.replace(grid, contract_a=bad), mlp, rays, bg)
+        assert e.value.status == lp.LP_ERR_INVALID_ARG
 
 
 def test_forward_is_bit_reproducible_and_gradients_accumulate(lp):

@@ -53,3 +53,13 @@ def test_strided_subset_is_a_deterministic_set_of_distinct_rays():
     idx = lp_inputs.strided_ray_subset(640000, 768, offset=3)
     assert len(idx) == 768 and len(set(idx.tolist())) == 768 and idx.max() < 640000
     assert np.array_equal(idx, lp_inputs.strided_ray_subset(640000, 768, offset=3))
+
+
+def test_contract_workload_has_the_papers_experimental_shape():
+    """Appendix, "Experimental Details": 160^3 voxels x 32 features, 3-layer width-64 MLP,
+    256 x 256 image, 384 points per ray, contract coordinates over the [-1, 1] cube."""
+    w = lp_inputs.WORKLOADS["contract"]
+    assert (w.res, w.channels, w.mlp_dims, w.image, w.samples) == ((160, 160, 160), 32, (32, 64, 64, 4), 256, 384)
+    inp = lp_inputs.make_inputs("contract", with_grid=False)
+    assert inp.contract_a == 1.0 and inp.aabb_min == (-1.0, -1.0, -1.0) and inp.aabb_max == (1.0, 1.0, 1.0)
+    assert inp.n_rays == 256 * 256 and float(inp.far.max()) > 10.0
