@@ -131,6 +131,36 @@ def cameras_for(w: Workload):
 
 
 @dataclasses.dataclass
+class Decoder:
+    """The paper's two-MLP decoder: opacity MLP C -> ... -> 1 and feature MLP
+    (C + E) -> ... -> F with E = 3 + 6 n_freq encoded view-direction inputs."""
+    dims_s: Tuple[int, ...]
+    weights_s: List[np.ndarray]
+    biases_s: List[np.ndarray]
+    dims_v: Tuple[int, ...]
+    weights_v: List[np.ndarray]
+    biases_v: List[np.ndarray]
+    n_freq: int
+    n_feat: int
+    feat_act: int = 0                 # 0: logistic sigmoid, 1: identity
+
+    @property
+    def n_enc(self) -> int:
+        return 3 + 6 * self.n_freq
+
+
+def make_decoder(channels: int, hidden_s, hidden_v, n_freq: int, n_feat: int, seed: int,
+                 bias_std: float = 0.0, feat_act: int = 0) -> Decoder:
+    """He-normal weights for both MLPs; hidden_s / hidden_v are the hidden widths."""
+    dims_s = (channels, *hidden_s, 1)
+    dims_v = (channels + 3 + 6 * n_freq, *hidden_v, n_feat)
+    ws, bs = make_mlp(dims_s, seed, bias_std)
+    wv, bv = make_mlp(dims_v, seed + 1, bias_std)
+    return Decoder(dims_s=tuple(dims_s), weights_s=ws, biases_s=bs, dims_v=tuple(dims_v), weights_v=wv,
+                   biases_v=bv, n_freq=n_freq, n_feat=n_feat, feat_act=feat_act)
+
+
+@dataclasses.dataclass
 class Inputs:
     """Host buffers for one call of the Renderer."""
     kind: int
@@ -152,6 +182,7 @@ class Inputs:
     bg: Tuple[float, float, float]
     target: Optional[np.ndarray] = None  # [M][3] float32 (for the MSE loss)
     contract_a: float = 0.0           # > 0: contract coordinates with this foreground scale
+    decoder: Optional[Decoder] = None  # set: the two-MLP decoder is used (bg / target have n_feat channels)
 
     @property
     def n_rays(self) -> int:

@@ -45,6 +45,11 @@ class _Mlp(C.Structure):
                 ("W", C.c_void_p * _MAX_LAYERS), ("b", C.c_void_p * _MAX_LAYERS)]
 
 
+class _Decoder(C.Structure):
+    _fields_ = [("opacity", _Mlp), ("color", _Mlp), ("n_freq", C.c_int32), ("n_feat", C.c_int32),
+                ("feat_act", C.c_int32)]
+
+
 class _Rays(C.Structure):
     _fields_ = [("M", C.c_int64), ("S", C.c_int32),
                 ("origins", C.c_void_p), ("dirs", C.c_void_p),
@@ -59,6 +64,9 @@ def _load():
         _lib.lpo_render_bwd.restype = C.c_int
         _lib.lpo_ray_trace.restype = C.c_int
         _lib.lpo_num_threads.restype = C.c_int
+        _lib.lpo_render2_fwd.restype = C.c_int
+        _lib.lpo_render2_bwd.restype = C.c_int
+        _lib.lpo_dir_encode.restype = C.c_int
     return _lib
 
 
@@ -84,7 +92,7 @@ class Problem:
         self.far = _f64(inp.far)
         self.scene = None if inp.scene is None else np.ascontiguousarray(inp.scene, dtype=np.int32)
         # the library takes bg as float32; widen that value exactly
-        self.bg = (C.c_double * 3)(*[float(np.float32(v)) for v in inp.bg])
+        self.bg = (C.c_double * len(inp.bg))(*[float(np.float32(v)) for v in inp.bg])
 
         g = _Grid()
         g.kind, g.B, g.C = inp.kind, inp.n_scenes, inp.channels
@@ -107,6 +115,27 @@ class Problem:
             m.W[l] = self.W[l].ctypes.data
             m.b[l] = self.b[l].ctypes.data
         self.c_mlp = m
+
+        self.c_decoder = None
+        dec = getattr(inp, "decoder", None)
+        if dec is not None:
+            self.Ws = [_f64(w) for w in dec.weights_s]
+            self.bs = [_f64(b) for b in dec.biases_s]
+            self.Wv = [_f64(w) for w in dec.weights_v]
+            self.bv = [_f64(b) for b in dec.biases_v]
+            d = _Decoder()
+            for mm, dims, Ws, bs in ((d.opacity, dec.dims_s, self.Ws, self.bs),
+                                     (d.color, dec.dims_v, self.Wv, self.bv)):
+                mm.n_layers = len(Ws)
+                for i, v in enumerate(dims):
+                    mm.dims[i] = int(v)
+                for l in range(len(Ws)):
+                    assert Ws[l].shape == (dims[l + 1], dims[l])
+                    mm.W[l] = Ws[l].ctypes.data
+                    mm.b[l] = bs[l].ctypes.data
+            d.n_freq, d.n_feat, d.feat_act = int(dec.n_freq), int(dec.n_feat), int(dec.feat_act)
+            self.c_decoder = d
+            self.bg = (C.c_double * dec.n_feat)(*[float(np.float32(v)) for v in inp.bg])
 
         r = _Rays()
         r.M, r.S = self.origins.shape[0], int(inp.samples)
@@ -184,3 +213,55 @@ def ray_trace(inp, ray: int, p_rgb=None, p_alpha: float = 0.0, p_depth: float = 
     if rc != 0:
         raise RuntimeError(f"lpo_ray_trace failed with status {rc}")
     return out
+
+
+# ---- the paper's two-MLP, view-dependent decoder (Section 3.3, below Eq. (1)) ----------------
+
+def dir_encode(d, n_freq: int) -> np.ndarray:
+    """enc(d) of one direction: (d, sin(2^k pi d), cos(2^k pi d) for k < n_freq)."""
+    d = _f64(d).reshape(3)
+    enc = np.zeros(3 + 6 * n_freq)
+    rc = _load().lpo_dir_encode(C.c_void_p(d.ctypes.data), C.c_int(n_freq), C.c_void_p(enc.ctypes.data))
+    if rc != 0:
+        raise RuntimeError(f"lpo_dir_encode failed with status {rc}")
+    return enc
+
+
+def render2_fwd(inp):
+    """Rendered features [M][F], alpha [M], depth [M] with the decoder `inp.decoder`."""
+    p = inp if isinstance(inp, Problem) else Problem(inp)
+    assert p.c_decoder is not None, "inputs carry no decoder"
+    m, f = p.n_rays, int(p.c_decoder.n_feat)
+    out = np.zeros((m, f)); alpha = np.zeros(m); depth = np.zeros(m)
+    rc = _load().lpo_render2_fwd(C.byref(p.c_grid), C.byref(p.c_decoder), C.byref(p.c_rays), p.bg,
+                                 C.c_void_p(out.ctypes.data), C.c_void_p(alpha.ctypes.data),
+                                 C.c_void_p(depth.ctypes.data))
+    if rc != 0:
+        raise RuntimeError(f"lpo_render2_fwd failed with status {rc}")
+    return out, alpha, depth
+
+
+def render2_bwd(inp, p_out, p_alpha=None, p_depth=None, kink_band: float = 0.0, kink_side: int = 0):
+    """Gradients with the two-MLP decoder.  Returns (d_grid, dWs, dbs, dWv, dbv): lists of
+    float64 arrays for the grid tensors, the opacity MLP and the feature MLP."""
+    p = inp if isinstance(inp, Problem) else Problem(inp)
+    assert p.c_decoder is not None, "inputs carry no decoder"
+    f = int(p.c_decoder.n_feat)
+    p_out = _f64(p_out)
+    assert p_out.shape == (p.n_rays, f)
+    pa = None if p_alpha is None else _f64(p_alpha)
+    pd = None if p_depth is None else _f64(p_depth)
+    d_grid = [np.zeros_like(g) for g in p.grid]
+    dWs = [np.zeros_like(w) for w in p.Ws]; dbs = [np.zeros_like(b) for b in p.bs]
+    dWv = [np.zeros_like(w) for w in p.Wv]; dbv = [np.zeros_like(b) for b in p.bv]
+    arr = lambda lst: (C.c_void_p * _MAX_LAYERS)(*[a.ctypes.data for a in lst])
+    dg_arr = (C.c_void_p * 3)(*[d_grid[i].ctypes.data if i < len(d_grid) else None for i in range(3)])
+    rc = _load().lpo_render2_bwd(C.byref(p.c_grid), C.byref(p.c_decoder), C.byref(p.c_rays), p.bg,
+                                 C.c_void_p(p_out.ctypes.data),
+                                 None if pa is None else C.c_void_p(pa.ctypes.data),
+                                 None if pd is None else C.c_void_p(pd.ctypes.data),
+                                 dg_arr, arr(dWs), arr(dbs), arr(dWv), arr(dbv),
+                                 C.c_double(kink_band), C.c_int(kink_side))
+    if rc != 0:
+        raise RuntimeError(f"lpo_render2_bwd failed with status {rc}")
+    return d_grid, dWs, dbs, dWv, dbv

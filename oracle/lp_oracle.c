@@ -641,3 +641,372 @@ int lpo_num_threads(void)
     return 1;
 #endif
 }
+
+/* ==== The Renderer with the paper's own decoder (Section 3.3, below Eq. (1)) =================
+ *
+ * "feeds the feature to an MLP g_sigma to calculate the opacity"; the rendered feature
+ * f_v "is calculated by another MLP g_v taking the sampled feature and view directions as
+ * inputs", and the rendered quantity is a feature vector of any width ("e.g. colors, depths").
+ *
+ *   sigma_j = softplus( g_sigma( h(x_j) )[0] )                 g_sigma : C -> ... -> 1
+ *   f_j     = act( g_v( [ h(x_j) ; enc(d) ] ) )                g_v     : C + E -> ... -> F
+ *   v       = sum_j w_j f_j + T_S bg            (F channels),  alpha, depth as before.
+ *
+ * Readings (the paper does not say): enc(d) is the view direction followed by n_freq octaves
+ * of sin / cos, enc = (d, sin(2^0 pi d), cos(2^0 pi d), ..., sin(2^{L-1} pi d), cos(2^{L-1} pi d)),
+ * each applied per component, E = 3 + 6 L (L = 0: the raw direction); act is the logistic
+ * sigmoid (colours, as in the single-MLP decoder) or the identity (feat_act = 1); the same
+ * sampled feature feeds both MLPs; no gradient with respect to the direction.
+ */
+
+typedef struct {
+    lpo_mlp opacity;  /* g_sigma */
+    lpo_mlp color;    /* g_v */
+    int32_t n_freq;   /* L */
+    int32_t n_feat;   /* F */
+    int32_t feat_act; /* 0 logistic sigmoid, 1 identity */
+} lpo_decoder;
+
+static const double LPO_PI = 3.14159265358979323846264338327950288;
+
+static void dir_encode(const double d[3], int L, double* enc)
+{
+    for (int a = 0; a < 3; ++a) enc[a] = d[a];
+    double f = LPO_PI;
+    for (int k = 0; k < L; ++k) {
+        for (int a = 0; a < 3; ++a) {
+            enc[3 + 6 * k + a] = sin(f * d[a]);
+            enc[3 + 6 * k + 3 + a] = cos(f * d[a]);
+        }
+        f *= 2.0;
+    }
+}
+
+typedef struct {
+    int S, C, E, F, na_s, na_v; /* na_*: act_total of the two MLPs */
+    double delta;
+    double *t, *x;
+    double *act_s, *pre_s; /* [S][na_s], [S][na_s - C]       */
+    double *act_v, *pre_v; /* [S][na_v], [S][na_v - (C + E)] */
+    double *sigma, *feat;  /* [S], [S][F] (after act)        */
+    double *e, *T, *w;
+} dec_tape;
+
+static int dec_tape_alloc(dec_tape* r, int S, int C, int E, int F, int na_s, int na_v)
+{
+    memset(r, 0, sizeof(*r));
+    r->S = S; r->C = C; r->E = E; r->F = F; r->na_s = na_s; r->na_v = na_v;
+    r->t = (double*)malloc(sizeof(double) * S);
+    r->x = (double*)malloc(sizeof(double) * S * 3);
+    r->act_s = (double*)malloc(sizeof(double) * (size_t)S * na_s);
+    r->pre_s = (double*)malloc(sizeof(double) * (size_t)S * na_s);
+    r->act_v = (double*)malloc(sizeof(double) * (size_t)S * na_v);
+    r->pre_v = (double*)malloc(sizeof(double) * (size_t)S * na_v);
+    r->sigma = (double*)malloc(sizeof(double) * S);
+    r->feat = (double*)malloc(sizeof(double) * (size_t)S * F);
+    r->e = (double*)malloc(sizeof(double) * S);
+    r->T = (double*)malloc(sizeof(double) * (S + 1));
+    r->w = (double*)malloc(sizeof(double) * S);
+    return r->t && r->x && r->act_s && r->pre_s && r->act_v && r->pre_v && r->sigma && r->feat &&
+           r->e && r->T && r->w;
+}
+
+static void dec_tape_free(dec_tape* r)
+{
+    free(r->t); free(r->x); free(r->act_s); free(r->pre_s); free(r->act_v); free(r->pre_v);
+    free(r->sigma); free(r->feat); free(r->e); free(r->T); free(r->w);
+}
+
+static int dec_check(const lpo_grid* g, const lpo_decoder* dc, const lpo_rays* rays)
+{
+    if (!g || !dc || !rays) return 1;
+    if (g->B < 1 || g->C < 1 || g->NX < 2 || g->NY < 2 || g->NZ < 2) return 1;
+    const lpo_mlp* ms = &dc->opacity;
+    const lpo_mlp* mv = &dc->color;
+    if (ms->n_layers < 1 || ms->n_layers > LPO_MAX_LAYERS) return 1;
+    if (mv->n_layers < 1 || mv->n_layers > LPO_MAX_LAYERS) return 1;
+    if (dc->n_freq < 0 || dc->n_feat < 1) return 1;
+    if (ms->dims[0] != g->C || ms->dims[ms->n_layers] != 1) return 1;
+    if (mv->dims[0] != g->C + 3 + 6 * dc->n_freq || mv->dims[mv->n_layers] != dc->n_feat) return 1;
+    if (rays->M < 0 || rays->S < 1) return 1;
+    return 0;
+}
+
+/* forward of one ray, everything stored */
+static void dec_ray_forward(const lpo_grid* g, const lpo_decoder* dc, const lpo_rays* rays, int64_t i,
+                            const double* bg, dec_tape* r, double* out, double* alpha, double* depth)
+{
+    const int S = r->S, C = r->C, E = r->E, F = r->F;
+    const double* o = rays->origins + 3 * i;
+    const double* d = rays->dirs + 3 * i;
+    const double nr = rays->near[i], fr = rays->far[i];
+    const int b = rays->scene ? rays->scene[i] : 0;
+    const int out_s = r->na_s - 1, out_v = r->na_v - F;
+    r->delta = (fr - nr) / (double)S;
+    r->T[0] = 1.0;
+    for (int k = 0; k < F; ++k) out[k] = 0.0;
+    *depth = 0.0;
+    for (int j = 0; j < S; ++j) {
+        const double t = nr + ((double)j + 0.5) * r->delta;
+        r->t[j] = t;
+        for (int a = 0; a < 3; ++a) r->x[3 * j + a] = o[a] + t * d[a];
+        double* as = r->act_s + (size_t)j * r->na_s;
+        double* av = r->act_v + (size_t)j * r->na_v;
+        grid_gather(g, b, r->x + 3 * j, as);
+        for (int k = 0; k < C; ++k) av[k] = as[k];
+        dir_encode(d, dc->n_freq, av + C);
+        mlp_forward(&dc->opacity, as, r->pre_s + (size_t)j * r->na_s);
+        mlp_forward(&dc->color, av, r->pre_v + (size_t)j * r->na_v);
+        r->sigma[j] = softplus(as[out_s]);
+        for (int k = 0; k < F; ++k)
+            r->feat[(size_t)j * F + k] = dc->feat_act == 0 ? logistic(av[out_v + k]) : av[out_v + k];
+        r->e[j] = exp(-r->sigma[j] * r->delta);
+        r->T[j + 1] = r->T[j] * r->e[j];
+        r->w[j] = r->T[j] - r->T[j + 1];
+        for (int k = 0; k < F; ++k) out[k] += r->w[j] * r->feat[(size_t)j * F + k];
+        *depth += r->w[j] * t;
+    }
+    for (int k = 0; k < F; ++k) out[k] += r->T[S] * bg[k];
+    *alpha = 1.0 - r->T[S];
+    (void)E;
+}
+
+int lpo_render2_fwd(const lpo_grid* g, const lpo_decoder* dc, const lpo_rays* rays, const double* bg,
+                    double* out, double* alpha, double* depth)
+{
+    if (dec_check(g, dc, rays)) return 1;
+    const int na_s = mlp_act_total(&dc->opacity), na_v = mlp_act_total(&dc->color);
+    const int E = 3 + 6 * dc->n_freq, F = dc->n_feat;
+    int fail = 0;
+#pragma omp parallel
+    {
+        dec_tape r;
+        if (!dec_tape_alloc(&r, rays->S, g->C, E, F, na_s, na_v)) {
+#pragma omp atomic write
+            fail = 1;
+        }
+#pragma omp barrier
+        if (!fail) {
+#pragma omp for schedule(dynamic, 16)
+            for (int64_t i = 0; i < rays->M; ++i)
+                dec_ray_forward(g, dc, rays, i, bg, &r, out + (size_t)F * i, alpha + i, depth + i);
+        }
+        dec_tape_free(&r);
+    }
+    return fail ? 2 : 0;
+}
+
+/* Reverse-mode through one MLP of one sample, any number of outputs.  dact holds
+   dL/d(output) in its last n_out entries on entry and dL/d(input) in its first dims[0]
+   entries on exit; dW, db are added to.  pre is indexed like act minus dims[0].
+   ReLU' = 1 iff pre-activation > 0, except for the listed units, whose derivative is bit i
+   of `mask`. */
+static void mlp_backward_sample(const lpo_mlp* m, const double* act, const double* pre, int nact,
+                                double* dact, double* const dW[], double* const db[], int n_over,
+                                const int* kl, const int* ko, unsigned mask)
+{
+    const int nl = m->n_layers, n_in = m->dims[0], n_out = m->dims[nl];
+    for (int k = 0; k < nact - n_out; ++k) dact[k] = 0.0;
+    int off_out = nact - n_out;
+    for (int l = nl - 1; l >= 0; --l) {
+        const int nin = m->dims[l], nout = m->dims[l + 1];
+        const int off_in = off_out - nin;
+        const double* W = m->W[l];
+        for (int o = 0; o < nout; ++o) {
+            double dz = dact[off_out + o];
+            if (l + 1 < nl) {
+                int on = pre[off_out - n_in + o] > 0.0;
+                for (int i = 0; i < n_over; ++i)
+                    if (kl[i] == l && ko[i] == o) on = (mask >> i) & 1u;
+                if (!on) dz = 0.0;
+            }
+            if (dz == 0.0) continue;
+            db[l][o] += dz;
+            for (int k = 0; k < nin; ++k) {
+                dW[l][(int64_t)o * nin + k] += dz * act[off_in + k];
+                dact[off_in + k] += dz * W[(int64_t)o * nin + k];
+            }
+        }
+        off_out = off_in;
+    }
+}
+
+/* One MLP of one sample: the definition (side = 0) or the upper / lower envelope over the
+   on/off choices of its hidden units inside the kink band (see lpo_render_bwd).  dout holds
+   the n_out output gradients.  Adds to dW, db; writes dL/d(input) to din[0 .. dims[0]). */
+static void mlp_backward_choice(const lpo_mlp* m, const double* act, const double* pre, int nact,
+                                const double* dout, double band, int side, kink_tmp* kt,
+                                double* const dW[], double* const db[], double* dact, double* din)
+{
+    const int nl = m->n_layers, n_in = m->dims[0], n_out = m->dims[nl];
+    int kl[LPO_MAX_KINKS], ko[LPO_MAX_KINKS];
+    const int nk = (side != 0 && kt) ? sample_kinks(m, act, pre, n_in, band, kl, ko) : 0;
+    if (nk == 0) {
+        for (int c = 0; c < n_out; ++c) dact[nact - n_out + c] = dout[c];
+        mlp_backward_sample(m, act, pre, nact, dact, dW, db, 0, NULL, NULL, 0u);
+        for (int k = 0; k < n_in; ++k) din[k] = dact[k];
+        return;
+    }
+    for (unsigned mask = 0; mask < (1u << nk); ++mask) {
+        for (int l = 0; l < nl; ++l) {
+            memset(kt->W[2][l], 0, sizeof(double) * (size_t)m->dims[l] * m->dims[l + 1]);
+            memset(kt->b[2][l], 0, sizeof(double) * (size_t)m->dims[l + 1]);
+        }
+        for (int c = 0; c < n_out; ++c) kt->dact[2][nact - n_out + c] = dout[c];
+        mlp_backward_sample(m, act, pre, nact, kt->dact[2], kt->W[2], kt->b[2], nk, kl, ko, mask);
+        for (int l = 0; l < nl; ++l) {
+            const int64_t n = (int64_t)m->dims[l] * m->dims[l + 1];
+            for (int64_t k = 0; k < n; ++k) {
+                const double v = kt->W[2][l][k];
+                kt->W[0][l][k] = mask ? fmin(kt->W[0][l][k], v) : v;
+                kt->W[1][l][k] = mask ? fmax(kt->W[1][l][k], v) : v;
+            }
+            for (int k = 0; k < m->dims[l + 1]; ++k) {
+                const double v = kt->b[2][l][k];
+                kt->b[0][l][k] = mask ? fmin(kt->b[0][l][k], v) : v;
+                kt->b[1][l][k] = mask ? fmax(kt->b[1][l][k], v) : v;
+            }
+        }
+        for (int k = 0; k < n_in; ++k) {
+            const double v = kt->dact[2][k];
+            kt->dact[0][k] = mask ? fmin(kt->dact[0][k], v) : v;
+            kt->dact[1][k] = mask ? fmax(kt->dact[1][k], v) : v;
+        }
+    }
+    const int pick = side > 0 ? 1 : 0;
+    for (int l = 0; l < nl; ++l) {
+        const int64_t n = (int64_t)m->dims[l] * m->dims[l + 1];
+        for (int64_t k = 0; k < n; ++k) dW[l][k] += kt->W[pick][l][k];
+        for (int k = 0; k < m->dims[l + 1]; ++k) db[l][k] += kt->b[pick][l][k];
+    }
+    for (int k = 0; k < n_in; ++k) din[k] = kt->dact[pick][k];
+}
+
+/* Reverse of dec_ray_forward, operation by operation.  The two MLPs of a sample choose their
+   kink units independently, and the sample's feature gradient is the sum of the two input
+   gradients, so the envelope of the sum is the sum of the envelopes. */
+static void dec_ray_backward(const lpo_grid* g, const lpo_decoder* dc, const lpo_rays* rays, int64_t i,
+                             const double* bg, const dec_tape* r, const double* p_out, double p_alpha,
+                             double p_depth, double* const d_grid[3], double* const dWs[],
+                             double* const dbs[], double* const dWv[], double* const dbv[],
+                             double* scratch, double band, int side, kink_tmp* kts, kink_tmp* ktv)
+{
+    const int S = r->S, C = r->C, F = r->F;
+    const int b = rays->scene ? rays->scene[i] : 0;
+    double* dT = scratch;                    /* [S+1]  */
+    double* dact_s = dT + (S + 1);           /* [na_s] */
+    double* dact_v = dact_s + r->na_s;       /* [na_v] */
+    double* din_s = dact_v + r->na_v;        /* [C]     */
+    double* din_v = din_s + C;               /* [C + E] */
+    double* dout_v = din_v + (C + r->E);     /* [F]     */
+    for (int j = 0; j <= S; ++j) dT[j] = 0.0;
+    dT[S] += -p_alpha;
+    for (int k = 0; k < F; ++k) dT[S] += p_out[k] * bg[k];
+    for (int j = 0; j < S; ++j) {
+        double dw = p_depth * r->t[j];
+        for (int k = 0; k < F; ++k) dw += p_out[k] * r->feat[(size_t)j * F + k];
+        dT[j] += dw;
+        dT[j + 1] -= dw;
+    }
+    for (int j = S - 1; j >= 0; --j) {
+        const double de = dT[j + 1] * r->T[j];
+        dT[j] += dT[j + 1] * r->e[j];
+        const double dsigma = de * (-r->delta) * r->e[j];
+        const double* as = r->act_s + (size_t)j * r->na_s;
+        const double* av = r->act_v + (size_t)j * r->na_v;
+        const double dout_s = dsigma * logistic(as[r->na_s - 1]);
+        for (int k = 0; k < F; ++k) {
+            const double df = r->w[j] * p_out[k];
+            const double f = r->feat[(size_t)j * F + k];
+            dout_v[k] = dc->feat_act == 0 ? df * f * (1.0 - f) : df;
+        }
+        mlp_backward_choice(&dc->opacity, as, r->pre_s + (size_t)j * r->na_s, r->na_s, &dout_s, band, side,
+                            kts, dWs, dbs, dact_s, din_s);
+        mlp_backward_choice(&dc->color, av, r->pre_v + (size_t)j * r->na_v, r->na_v, dout_v, band, side,
+                            ktv, dWv, dbv, dact_v, din_v);
+        for (int k = 0; k < C; ++k) din_s[k] += din_v[k];
+        grid_scatter(g, d_grid, b, r->x + 3 * j, din_s);
+    }
+}
+
+/* d_grid and the four gradient lists are ACCUMULATED into.  band / side as in lpo_render_bwd. */
+int lpo_render2_bwd(const lpo_grid* g, const lpo_decoder* dc, const lpo_rays* rays, const double* bg,
+                    const double* p_out, const double* p_alpha, const double* p_depth,
+                    double* const d_grid[3], double* const dWs[], double* const dbs[],
+                    double* const dWv[], double* const dbv[], double band, int side)
+{
+    if (dec_check(g, dc, rays)) return 1;
+    if (side != 0 && !(band > 0.0)) return 1;
+    const lpo_mlp* ms = &dc->opacity;
+    const lpo_mlp* mv = &dc->color;
+    const int na_s = mlp_act_total(ms), na_v = mlp_act_total(mv);
+    const int C = g->C, E = 3 + 6 * dc->n_freq, F = dc->n_feat;
+    int fail = 0;
+#pragma omp parallel
+    {
+        dec_tape r;
+        kink_tmp kts, ktv;
+        double* scratch = (double*)malloc(sizeof(double) * (size_t)(rays->S + 1 + na_s + na_v + 2 * C + E + F));
+        double* tWs[LPO_MAX_LAYERS] = {NULL};
+        double* tbs[LPO_MAX_LAYERS] = {NULL};
+        double* tWv[LPO_MAX_LAYERS] = {NULL};
+        double* tbv[LPO_MAX_LAYERS] = {NULL};
+        int ok = dec_tape_alloc(&r, rays->S, C, E, F, na_s, na_v) && scratch;
+        ok = kink_alloc(&kts, ms, na_s) && ok;
+        ok = kink_alloc(&ktv, mv, na_v) && ok;
+        for (int l = 0; l < ms->n_layers; ++l) {
+            tWs[l] = (double*)calloc((size_t)ms->dims[l] * ms->dims[l + 1], sizeof(double));
+            tbs[l] = (double*)calloc((size_t)ms->dims[l + 1], sizeof(double));
+            ok = ok && tWs[l] && tbs[l];
+        }
+        for (int l = 0; l < mv->n_layers; ++l) {
+            tWv[l] = (double*)calloc((size_t)mv->dims[l] * mv->dims[l + 1], sizeof(double));
+            tbv[l] = (double*)calloc((size_t)mv->dims[l + 1], sizeof(double));
+            ok = ok && tWv[l] && tbv[l];
+        }
+        if (!ok) {
+#pragma omp atomic write
+            fail = 1;
+        }
+#pragma omp barrier
+        if (!fail) {
+            double* out = (double*)malloc(sizeof(double) * (size_t)F);
+#pragma omp for schedule(dynamic, 16)
+            for (int64_t i = 0; i < rays->M; ++i) {
+                double alpha, depth;
+                dec_ray_forward(g, dc, rays, i, bg, &r, out, &alpha, &depth);
+                dec_ray_backward(g, dc, rays, i, bg, &r, p_out + (size_t)F * i, p_alpha ? p_alpha[i] : 0.0,
+                                 p_depth ? p_depth[i] : 0.0, d_grid, tWs, tbs, tWv, tbv, scratch, band, side,
+                                 &kts, &ktv);
+            }
+            free(out);
+#pragma omp critical
+            {
+                for (int l = 0; l < ms->n_layers; ++l) {
+                    const int64_t n = (int64_t)ms->dims[l] * ms->dims[l + 1];
+                    for (int64_t k = 0; k < n; ++k) dWs[l][k] += tWs[l][k];
+                    for (int k = 0; k < ms->dims[l + 1]; ++k) dbs[l][k] += tbs[l][k];
+                }
+                for (int l = 0; l < mv->n_layers; ++l) {
+                    const int64_t n = (int64_t)mv->dims[l] * mv->dims[l + 1];
+                    for (int64_t k = 0; k < n; ++k) dWv[l][k] += tWv[l][k];
+                    for (int k = 0; k < mv->dims[l + 1]; ++k) dbv[l][k] += tbv[l][k];
+                }
+            }
+        }
+        for (int l = 0; l < LPO_MAX_LAYERS; ++l) { free(tWs[l]); free(tbs[l]); free(tWv[l]); free(tbv[l]); }
+        free(scratch);
+        kink_free(&kts);
+        kink_free(&ktv);
+        dec_tape_free(&r);
+    }
+    return fail ? 2 : 0;
+}
+
+/* enc(d) of one direction, for the pins: enc has 3 + 6 L entries */
+int lpo_dir_encode(const double d[3], int n_freq, double* enc)
+{
+    if (!d || !enc || n_freq < 0) return 1;
+    dir_encode(d, n_freq, enc);
+    return 0;
+}
