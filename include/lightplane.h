@@ -28,7 +28,8 @@
 extern "C" {
 #endif
 
-#define LP_MAX_LAYERS 8 /* linear layers of the decoder MLP */
+#define LP_MAX_LAYERS 8    /* linear layers of a decoder MLP */
+#define LP_MAX_FEATURES 16 /* rendered feature channels of the two-MLP decoder */
 
 typedef enum {
     LP_OK = 0,
@@ -140,6 +141,57 @@ lp_status lp_bwd_workspace_bytes(const lp_grid* grid, const lp_mlp* mlp, const l
 
 /* 1 if the matrix-core (LP_MATH_BF16X3) kernels cover this grid kind / MLP shape, else 0. */
 int32_t lp_has_fast_path(const lp_grid* grid, const lp_mlp* mlp);
+
+/* ---- The Renderer with the paper's own decoder (Section 3.3, text below Eq. (1)) ----------
+ *
+ * Two MLPs instead of one: the opacity MLP g_sigma maps the sampled feature to the density
+ * (one output, through softplus); the feature MLP g_v maps the sampled feature AND the
+ * encoded view direction to the n_feat rendered features f_v ("e.g. colors"):
+ *     sigma_j = softplus(g_sigma(h(x_j))),   f_j = act(g_v([h(x_j) ; enc(d)])),
+ *     out = sum_j w_j f_j + T_S bg   (n_feat channels),   alpha, depth as in lp_render_fwd.
+ * enc(d) = (d, sin(2^k pi d), cos(2^k pi d) for k = 0 .. n_freq-1), component by component:
+ * 3 + 6 n_freq values (the paper does not give the form; n_freq = 0 is the raw direction).
+ * act = logistic sigmoid (LP_FEAT_SIGMOID) or identity (LP_FEAT_IDENTITY).
+ * opacity.dims[0] == C, last == 1; feature.dims[0] == C + 3 + 6 n_freq, last == n_feat;
+ * both MLPs need at least one hidden layer (n_layers >= 2); 1 <= n_feat <= LP_MAX_FEATURES;
+ * 0 <= n_freq <= 4.  No gradient is produced for the directions.
+ */
+typedef enum { LP_FEAT_SIGMOID = 0, LP_FEAT_IDENTITY = 1 } lp_feat_act;
+
+typedef struct {
+    lp_mlp opacity; /* g_sigma */
+    lp_mlp feature; /* g_v */
+    int32_t n_freq;
+    int32_t n_feat;
+    int32_t feat_act; /* lp_feat_act */
+} lp_decoder;
+
+/* Bytes of device workspace the two calls below need (either pointer may be NULL).
+   Independent of S and M.  The workspace holds the two MLPs merged into one block-structured
+   MLP (and, for the backward, its gradient and the partial-sum records). */
+lp_status lp_dec_workspace_bytes(const lp_grid* grid, const lp_decoder* dec, const lp_rays* rays,
+                                 int32_t math_mode, size_t* fwd_bytes, size_t* bwd_bytes);
+
+/* Forward.  out [M][n_feat], alpha [M], depth [M], ray_cache [M] (device; the last three may
+   be NULL); bg is a HOST array of n_feat floats; workspace: device, 256-byte aligned, at least
+   the fwd_bytes of lp_dec_workspace_bytes, contents ignored on entry, undefined on exit. */
+lp_status lp_render_dec_fwd(const lp_grid* grid, const lp_decoder* dec, const lp_rays* rays,
+                            const float* bg, float* out, float* alpha, float* depth, float* ray_cache,
+                            void* workspace, size_t workspace_bytes, int32_t math_mode, void* stream);
+
+/* Backward: upstream gradients d_out [M][n_feat] (required), d_alpha, d_depth (may be NULL);
+   ACCUMULATES into d_grid (as lp_render_bwd) and into dW_opacity[l], db_opacity[l],
+   dW_feature[l], db_feature[l] (device, shapes of the decoder's weights and biases).
+   workspace: at least the bwd_bytes of lp_dec_workspace_bytes. */
+lp_status lp_render_dec_bwd(const lp_grid* grid, const lp_decoder* dec, const lp_rays* rays,
+                            const float* bg, const float* d_out, const float* d_alpha,
+                            const float* d_depth, const float* ray_cache, float* const d_grid[3],
+                            float* const dW_opacity[LP_MAX_LAYERS], float* const db_opacity[LP_MAX_LAYERS],
+                            float* const dW_feature[LP_MAX_LAYERS], float* const db_feature[LP_MAX_LAYERS],
+                            void* workspace, size_t workspace_bytes, int32_t math_mode, void* stream);
+
+/* 1 if the matrix-core kernels cover this grid kind / decoder shape, else 0. */
+int32_t lp_dec_has_fast_path(const lp_grid* grid, const lp_decoder* dec);
 
 /* Message of the last failure on this thread ("" if none).  Owned by the library. */
 const char* lp_last_error(void);

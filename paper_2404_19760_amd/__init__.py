@@ -43,6 +43,11 @@ class _Mlp(C.Structure):
                 ("W", C.c_void_p * LP_MAX_LAYERS), ("b", C.c_void_p * LP_MAX_LAYERS)]
 
 
+class _Decoder(C.Structure):
+    _fields_ = [("opacity", _Mlp), ("feature", _Mlp), ("n_freq", C.c_int32), ("n_feat", C.c_int32),
+                ("feat_act", C.c_int32)]
+
+
 class _Rays(C.Structure):
     _fields_ = [("M", C.c_int64), ("S", C.c_int32),
                 ("origins", C.c_void_p), ("dirs", C.c_void_p),
@@ -71,6 +76,21 @@ def _load() -> C.CDLL:
     lib.lp_bwd_workspace_bytes.restype = C.c_int
     lib.lp_bwd_workspace_bytes.argtypes = [C.POINTER(_Grid), C.POINTER(_Mlp), C.POINTER(_Rays),
                                            C.c_int32, C.POINTER(C.c_size_t)]
+    lib.lp_dec_has_fast_path.restype = C.c_int32
+    lib.lp_dec_has_fast_path.argtypes = [C.POINTER(_Grid), C.POINTER(_Decoder)]
+    lib.lp_dec_workspace_bytes.restype = C.c_int
+    lib.lp_dec_workspace_bytes.argtypes = [C.POINTER(_Grid), C.POINTER(_Decoder), C.POINTER(_Rays), C.c_int32,
+                                           C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
+    lib.lp_render_dec_fwd.restype = C.c_int
+    lib.lp_render_dec_fwd.argtypes = [C.POINTER(_Grid), C.POINTER(_Decoder), C.POINTER(_Rays),
+                                      C.POINTER(C.c_float), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                      C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p]
+    lib.lp_render_dec_bwd.restype = C.c_int
+    lib.lp_render_dec_bwd.argtypes = [C.POINTER(_Grid), C.POINTER(_Decoder), C.POINTER(_Rays),
+                                      C.POINTER(C.c_float), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                      C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
+                                      C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_void_p, C.c_size_t,
+                                      C.c_int32, C.c_void_p]
     return lib
 
 
@@ -156,6 +176,23 @@ class Mlp:
             m.W[l] = _dev_f32(w, f"weights[{l}]", (dims[l + 1], dims[l]))
             m.b[l] = _dev_f32(b, f"biases[{l}]", (dims[l + 1],))
         return m
+
+
+@dataclasses.dataclass
+class Decoder:
+    """The two-MLP decoder: opacity MLP (C -> ... -> 1) and feature MLP
+    (C + 3 + 6 n_freq -> ... -> n_feat); feat_act LP_FEAT_SIGMOID or LP_FEAT_IDENTITY."""
+    opacity: Mlp
+    feature: Mlp
+    n_freq: int
+    n_feat: int
+    feat_act: int = 0
+
+    def c_struct(self) -> _Decoder:
+        d = _Decoder()
+        d.opacity, d.feature = self.opacity.c_struct(), self.feature.c_struct()
+        d.n_freq, d.n_feat, d.feat_act = int(self.n_freq), int(self.n_feat), int(self.feat_act)
+        return d
 
 
 @dataclasses.dataclass
@@ -257,6 +294,71 @@ def lp_render_bwd(grid: Grid, mlp: Mlp, rays: Rays, bg, d_rgb: torch.Tensor,
                               int(math_mode), _stream_ptr(stream)))
 
 
+def lp_dec_has_fast_path(grid: Grid, dec: Decoder) -> bool:
+    g, d = grid.c_struct(), dec.c_struct()
+    return bool(_lib.lp_dec_has_fast_path(C.byref(g), C.byref(d)))
+
+
+def lp_dec_workspace_bytes(grid: Grid, dec: Decoder, rays: Rays, math_mode: int = LP_MATH_DEFAULT):
+    """(forward bytes, backward bytes) of workspace for the two-MLP decoder calls."""
+    g, d, r = grid.c_struct(), dec.c_struct(), rays.c_struct()
+    nf, nb = C.c_size_t(0), C.c_size_t(0)
+    _check(_lib.lp_dec_workspace_bytes(C.byref(g), C.byref(d), C.byref(r), int(math_mode), C.byref(nf), C.byref(nb)))
+    return int(nf.value), int(nb.value)
+
+
+def _workspace(workspace: torch.Tensor):
+    if not (workspace.is_cuda and workspace.is_contiguous()):
+        raise ValueError("workspace must be a contiguous GPU tensor")
+    return C.c_void_p(workspace.data_ptr()), C.c_size_t(workspace.numel() * workspace.element_size())
+
+
+def lp_render_dec_fwd(grid: Grid, dec: Decoder, rays: Rays, bg, out: torch.Tensor,
+                      alpha: Optional[torch.Tensor], depth: Optional[torch.Tensor],
+                      ray_cache: Optional[torch.Tensor], workspace: torch.Tensor,
+                      math_mode: int = LP_MATH_DEFAULT, stream=None) -> None:
+    """Forward with the two-MLP decoder; out [M][n_feat]; bg has n_feat entries."""
+    m, f = rays.n_rays, int(dec.n_feat)
+    g, d, r = grid.c_struct(), dec.c_struct(), rays.c_struct()
+    wp, wn = _workspace(workspace)
+    _check(_lib.lp_render_dec_fwd(C.byref(g), C.byref(d), C.byref(r), (C.c_float * f)(*[float(v) for v in bg]),
+                                  _dev_f32(out, "out", (m, f)), _dev_f32(alpha, "alpha", (m,)),
+                                  _dev_f32(depth, "depth", (m,)), _dev_f32(ray_cache, "ray_cache", (m,)),
+                                  wp, wn, int(math_mode), _stream_ptr(stream)))
+
+
+def lp_render_dec_bwd(grid: Grid, dec: Decoder, rays: Rays, bg, d_out: torch.Tensor,
+                      d_alpha: Optional[torch.Tensor], d_depth: Optional[torch.Tensor],
+                      ray_cache: torch.Tensor, d_grid: List[torch.Tensor],
+                      dW_opacity: List[torch.Tensor], db_opacity: List[torch.Tensor],
+                      dW_feature: List[torch.Tensor], db_feature: List[torch.Tensor],
+                      workspace: torch.Tensor, math_mode: int = LP_MATH_DEFAULT, stream=None) -> None:
+    """Backward with the two-MLP decoder; all gradient tensors are ACCUMULATED into."""
+    m, f = rays.n_rays, int(dec.n_feat)
+    g, d, r = grid.c_struct(), dec.c_struct(), rays.c_struct()
+    shapes = grid.shapes()
+    if len(d_grid) != len(shapes):
+        raise ValueError("d_grid needs one tensor per grid tensor")
+    dg = (C.c_void_p * 3)(*[_dev_f32(d_grid[p], f"d_grid[{p}]", shapes[p]) if p < len(shapes) else None
+                            for p in range(3)])
+
+    def lists(mlp, dW, db, name):
+        dims = mlp.dims
+        if len(dW) != len(mlp.weights) or len(db) != len(mlp.weights):
+            raise ValueError(f"dW_{name} / db_{name} need one tensor per layer")
+        return ((C.c_void_p * LP_MAX_LAYERS)(*[_dev_f32(w, f"dW_{name}[{l}]", (dims[l + 1], dims[l]))
+                                               for l, w in enumerate(dW)]),
+                (C.c_void_p * LP_MAX_LAYERS)(*[_dev_f32(b, f"db_{name}[{l}]", (dims[l + 1],))
+                                               for l, b in enumerate(db)]))
+    dWs, dbs = lists(dec.opacity, dW_opacity, db_opacity, "opacity")
+    dWv, dbv = lists(dec.feature, dW_feature, db_feature, "feature")
+    wp, wn = _workspace(workspace)
+    _check(_lib.lp_render_dec_bwd(C.byref(g), C.byref(d), C.byref(r), (C.c_float * f)(*[float(v) for v in bg]),
+                                  _dev_f32(d_out, "d_out", (m, f)), _dev_f32(d_alpha, "d_alpha", (m,)),
+                                  _dev_f32(d_depth, "d_depth", (m,)), _dev_f32(ray_cache, "ray_cache", (m,)),
+                                  dg, dWs, dbs, dWv, dbv, wp, wn, int(math_mode), _stream_ptr(stream)))
+
+
 # ---------------------------------------------------------------------------------------
 # Conveniences on top of the entry points: move host buffers to the GPU, allocate outputs.
 
@@ -272,6 +374,42 @@ def to_device(inp, device="cuda:0"):
     rays = Rays(origins=up(inp.origins), dirs=up(inp.dirs), near=up(inp.near), far=up(inp.far),
                 samples=int(inp.samples), scene=None if inp.scene is None else up(inp.scene))
     return grid, mlp, rays, tuple(float(v) for v in inp.bg)
+
+
+def decoder_to_device(dec, device="cuda:0") -> Decoder:
+    """Upload a host decoder (fields of `lp_inputs.Decoder`)."""
+    dev = torch.device(device)
+    up = lambda a: torch.from_numpy(a).to(dev)
+    return Decoder(opacity=Mlp([up(w) for w in dec.weights_s], [up(b) for b in dec.biases_s]),
+                   feature=Mlp([up(w) for w in dec.weights_v], [up(b) for b in dec.biases_v]),
+                   n_freq=int(dec.n_freq), n_feat=int(dec.n_feat), feat_act=int(dec.feat_act))
+
+
+def render_dec_fwd(grid: Grid, dec: Decoder, rays: Rays, bg, math_mode: int = LP_MATH_DEFAULT):
+    """Allocate outputs and workspace and run lp_render_dec_fwd.  Returns (out, alpha, depth, ray_cache)."""
+    dev = rays.origins.device
+    m = rays.n_rays
+    out = torch.empty((m, dec.n_feat), dtype=torch.float32, device=dev)
+    alpha = torch.empty((m,), dtype=torch.float32, device=dev)
+    depth = torch.empty((m,), dtype=torch.float32, device=dev)
+    cache = torch.empty((m,), dtype=torch.float32, device=dev)
+    ws = torch.empty(lp_dec_workspace_bytes(grid, dec, rays, math_mode)[0], dtype=torch.uint8, device=dev)
+    lp_render_dec_fwd(grid, dec, rays, bg, out, alpha, depth, cache, ws, math_mode)
+    return out, alpha, depth, cache
+
+
+def render_dec_bwd(grid: Grid, dec: Decoder, rays: Rays, bg, d_out, ray_cache, d_alpha=None, d_depth=None,
+                   math_mode: int = LP_MATH_DEFAULT):
+    """Allocate zeroed gradient buffers and a workspace and run lp_render_dec_bwd.
+    Returns (d_grid, dW_opacity, db_opacity, dW_feature, db_feature)."""
+    dev = rays.origins.device
+    d_grid = [torch.zeros_like(t) for t in grid.data]
+    z = lambda lst: [torch.zeros_like(t) for t in lst]
+    dWs, dbs, dWv, dbv = z(dec.opacity.weights), z(dec.opacity.biases), z(dec.feature.weights), z(dec.feature.biases)
+    ws = torch.empty(lp_dec_workspace_bytes(grid, dec, rays, math_mode)[1], dtype=torch.uint8, device=dev)
+    lp_render_dec_bwd(grid, dec, rays, bg, d_out, d_alpha, d_depth, ray_cache, d_grid, dWs, dbs, dWv, dbv, ws,
+                      math_mode)
+    return d_grid, dWs, dbs, dWv, dbv
 
 
 def render_fwd(grid: Grid, mlp: Mlp, rays: Rays, bg, math_mode: int = LP_MATH_DEFAULT):

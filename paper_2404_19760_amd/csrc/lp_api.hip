@@ -105,6 +105,7 @@ void to_device_views(const lp_grid* grid, const lp_mlp* mlp, const lp_rays* rays
     m->param_total = off;
     m->max_width = maxw;
     m->act_total = act;
+    m->n_freq = 0; m->n_enc = 0; m->n_feat = 3; m->feat_act = 0;
     r->M = rays->M; r->S = rays->S;
     r->origins = rays->origins; r->dirs = rays->dirs; r->near = rays->near; r->far = rays->far;
     r->scene = rays->scene;
@@ -128,13 +129,13 @@ lp_status choose_path(const lp::GridDev& g, const lp::MlpDev& m, int32_t mode, P
 
 size_t generic_fwd_lds(const lp::MlpDev& m)
 {
-    return sizeof(float) * ((size_t)m.param_total + (size_t)m.act_total * kGenericLanes);
+    return sizeof(float) * ((size_t)m.param_total + ((size_t)m.act_total + m.n_feat) * kGenericLanes);
 }
 
 size_t generic_bwd_lds(const lp::MlpDev& m)
 {
     return sizeof(float) * (2 * (size_t)m.param_total + (size_t)m.act_total * kGenericLanes +
-                            2 * (size_t)m.max_width * kGenericLanes);
+                            (2 * (size_t)m.max_width + m.n_feat) * kGenericLanes);
 }
 
 int ws_stride(const lp::MlpDev& m) { return (m.param_total + 63) / 64 * 64; }
@@ -145,6 +146,139 @@ lp_status hip_fail(const char* what, hipError_t e)
 {
     return fail(LP_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
 }
+
+lp_status run_fwd(const lp::GridDev& g, const lp::MlpDev& m, const lp::RaysDev& r, const lp::FwdOut& out, Path path,
+                  int n_cu, hipStream_t s)
+{
+    if (path == Path::Mfma) {
+        hipError_t e = lp::launch_fwd_mfma(g, m, r, out, n_cu, s);
+        if (e != hipSuccess) return hip_fail("forward matrix-core kernel launch", e);
+        return LP_OK;
+    }
+    const size_t lds = generic_fwd_lds(m);
+    if (lds > kMaxLds)
+        return fail(LP_ERR_UNSUPPORTED, "MLP too large for the generic forward kernel's LDS budget");
+    hipError_t e = hipFuncSetAttribute((const void*)lp::fwd_generic_kernel,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return hip_fail("hipFuncSetAttribute(fwd_generic_kernel)", e);
+    const long long blocks = (r.M + kGenericLanes - 1) / kGenericLanes;
+    if (blocks > 0x7fffffffLL) return fail(LP_ERR_UNSUPPORTED, "too many rays for one launch");
+    hipLaunchKernelGGL(lp::fwd_generic_kernel, dim3((unsigned)blocks), dim3(kGenericLanes), lds, s, g, m, r, out);
+    e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail("forward generic kernel launch", e);
+    return LP_OK;
+}
+
+// Backward kernels plus the reduction of the per-wave / per-block records into io.dW / io.db.
+lp_status run_bwd(const lp::GridDev& g, const lp::MlpDev& m, const lp::RaysDev& r, const lp::BwdIo& io,
+                  bool fast_bwd, int max_records, int n_cu, hipStream_t s)
+{
+    if (fast_bwd) {
+        hipError_t e = lp::launch_bwd_mfma(g, m, r, io, n_cu, s);
+        if (e != hipSuccess) return hip_fail("backward matrix-core kernel launch", e);
+        return LP_OK;
+    }
+    const size_t lds = generic_bwd_lds(m);
+    if (lds > kMaxLds)
+        return fail(LP_ERR_UNSUPPORTED, "MLP too large for the generic backward kernel's LDS budget");
+    hipError_t e = hipFuncSetAttribute((const void*)lp::bwd_generic_kernel,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return hip_fail("hipFuncSetAttribute(bwd_generic_kernel)", e);
+    const long long n_tiles = (r.M + kGenericLanes - 1) / kGenericLanes;
+    const long long blocks = n_tiles < max_records ? n_tiles : max_records;
+    const long long tiles_per_block = (n_tiles + blocks - 1) / blocks;
+    if (tiles_per_block > 0x7fffffffLL) return fail(LP_ERR_UNSUPPORTED, "too many rays for one launch");
+    // blocks whose first tile is past the end write an all-zero record
+    hipLaunchKernelGGL(lp::bwd_generic_kernel, dim3((unsigned)blocks), dim3(kGenericLanes), lds, s, g, m, r, io,
+                       (int)tiles_per_block);
+    e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail("backward generic kernel launch", e);
+    const int threads = 256;
+    hipLaunchKernelGGL(lp::reduce_params_kernel, dim3((m.param_total + threads - 1) / threads), dim3(threads), 0, s,
+                       m, io, (int)blocks);
+    e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail("parameter-gradient reduction launch", e);
+    return LP_OK;
+}
+
+// ---- the two-MLP decoder ----------------------------------------------------------------
+
+lp_status validate_mlp_ptrs(const lp_mlp& m, const char* name)
+{
+    if (m.n_layers < 2 || m.n_layers > LP_MAX_LAYERS)
+        return fail(LP_ERR_UNSUPPORTED, std::string(name) + ": n_layers must be in [2, LP_MAX_LAYERS] (at least one hidden layer)");
+    for (int l = 0; l <= m.n_layers; ++l)
+        if (m.dims[l] < 1) return fail(LP_ERR_INVALID_ARG, std::string(name) + ": dims entries must be >= 1");
+    for (int l = 0; l < m.n_layers; ++l)
+        if (!m.W[l] || !m.b[l]) return fail(LP_ERR_INVALID_ARG, std::string(name) + ": W / b has a NULL layer");
+    return LP_OK;
+}
+
+// Validates grid, decoder and rays and builds the device views: the merged MLP `m` (its W / b
+// point into `packed`, which may be NULL when only sizes are wanted) and the layout `d`.
+lp_status decoder_views(const lp_grid* grid, const lp_decoder* dec, const lp_rays* rays, float* packed,
+                        lp::GridDev* g, lp::MlpDev* m, lp::RaysDev* r, lp::DecLayout* d)
+{
+    if (!dec) return fail(LP_ERR_INVALID_ARG, "dec must not be NULL");
+    // grid and rays are checked by the single-MLP validator with a stand-in MLP of the right ends
+    lp_mlp stand_in;
+    std::memset(&stand_in, 0, sizeof(stand_in));
+    stand_in.n_layers = 1;
+    stand_in.dims[0] = grid ? grid->C : 1;
+    stand_in.dims[1] = 4;
+    static const float dummy = 0.0f;
+    stand_in.W[0] = &dummy; stand_in.b[0] = &dummy;
+    lp_status st = validate(grid, &stand_in, rays);
+    if (st != LP_OK) return st;
+    if ((st = validate_mlp_ptrs(dec->opacity, "dec->opacity")) != LP_OK) return st;
+    if ((st = validate_mlp_ptrs(dec->feature, "dec->feature")) != LP_OK) return st;
+    if (dec->n_freq < 0 || dec->n_freq > 4) return fail(LP_ERR_INVALID_ARG, "dec->n_freq must be in [0, 4]");
+    if (dec->n_feat < 1 || dec->n_feat > LP_MAX_FEATURES)
+        return fail(LP_ERR_INVALID_ARG, "dec->n_feat must be in [1, LP_MAX_FEATURES]");
+    if (dec->feat_act != LP_FEAT_SIGMOID && dec->feat_act != LP_FEAT_IDENTITY)
+        return fail(LP_ERR_INVALID_ARG, "dec->feat_act must be LP_FEAT_SIGMOID or LP_FEAT_IDENTITY");
+    const int C = grid->C, E = 3 + 6 * dec->n_freq;
+    if (dec->opacity.dims[0] != C || dec->opacity.dims[dec->opacity.n_layers] != 1)
+        return fail(LP_ERR_INVALID_ARG, "dec->opacity must map grid->C inputs to 1 output");
+    if (dec->feature.dims[0] != C + E || dec->feature.dims[dec->feature.n_layers] != dec->n_feat)
+        return fail(LP_ERR_INVALID_ARG, "dec->feature must map grid->C + 3 + 6 n_freq inputs to n_feat outputs");
+
+    lp_mlp none;
+    std::memset(&none, 0, sizeof(none));
+    none.n_layers = 1; none.dims[0] = C; none.dims[1] = 4;
+    to_device_views(grid, &none, rays, g, m, r);   // fills g and r; m is rebuilt below
+
+    std::memset(d, 0, sizeof(*d));
+    d->Ls = dec->opacity.n_layers; d->Lv = dec->feature.n_layers;
+    d->L = d->Ls > d->Lv ? d->Ls : d->Lv;
+    d->C = C; d->E = E;
+    for (int l = 0; l <= d->Ls; ++l) d->dims_s[l] = dec->opacity.dims[l];
+    for (int l = 0; l <= d->Lv; ++l) d->dims_v[l] = dec->feature.dims[l];
+    for (int l = 0; l < d->Ls; ++l) { d->Ws[l] = dec->opacity.W[l]; d->bs[l] = dec->opacity.b[l]; }
+    for (int l = 0; l < d->Lv; ++l) { d->Wv[l] = dec->feature.W[l]; d->bv[l] = dec->feature.b[l]; }
+
+    std::memset(m, 0, sizeof(*m));
+    m->n_layers = d->L;
+    lp::dec_combined_dims(*d, C + E, m->dims);
+    int off = 0, maxw = 0, act = 0;
+    for (int l = 0; l <= m->n_layers; ++l) {
+        maxw = m->dims[l] > maxw ? m->dims[l] : maxw;
+        act += m->dims[l];
+    }
+    for (int l = 0; l < m->n_layers; ++l) {
+        m->w_off[l] = off; off += m->dims[l] * m->dims[l + 1];
+        m->b_off[l] = off; off += m->dims[l + 1];
+        m->W[l] = packed ? packed + m->w_off[l] : nullptr;
+        m->b[l] = packed ? packed + m->b_off[l] : nullptr;
+    }
+    m->param_total = off;
+    m->max_width = maxw;
+    m->act_total = act;
+    m->n_freq = dec->n_freq; m->n_enc = E; m->n_feat = dec->n_feat; m->feat_act = dec->feat_act;
+    return LP_OK;
+}
+
+size_t align256(size_t n) { return (n + 255) / 256 * 256; }
 
 }  // namespace
 
@@ -189,23 +323,7 @@ lp_status lp_render_fwd(const lp_grid* grid, const lp_mlp* mlp, const lp_rays* r
     int n_cu = 0;
     if (compute_units(&n_cu, &err)) return fail(LP_ERR_HIP, err);
 
-    if (path == Path::Mfma) {
-        hipError_t e = lp::launch_fwd_mfma(g, m, r, out, n_cu, s);
-        if (e != hipSuccess) return hip_fail("forward matrix-core kernel launch", e);
-        return LP_OK;
-    }
-    const size_t lds = generic_fwd_lds(m);
-    if (lds > kMaxLds)
-        return fail(LP_ERR_UNSUPPORTED, "MLP too large for the generic forward kernel's LDS budget");
-    hipError_t e = hipFuncSetAttribute((const void*)lp::fwd_generic_kernel,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return hip_fail("hipFuncSetAttribute(fwd_generic_kernel)", e);
-    const long long blocks = (rays->M + kGenericLanes - 1) / kGenericLanes;
-    if (blocks > 0x7fffffffLL) return fail(LP_ERR_UNSUPPORTED, "too many rays for one launch");
-    hipLaunchKernelGGL(lp::fwd_generic_kernel, dim3((unsigned)blocks), dim3(kGenericLanes), lds, s, g, m, r, out);
-    e = hipGetLastError();
-    if (e != hipSuccess) return hip_fail("forward generic kernel launch", e);
-    return LP_OK;
+    return run_fwd(g, m, r, out, path, n_cu, s);
 }
 
 lp_status lp_bwd_workspace_bytes(const lp_grid* grid, const lp_mlp* mlp, const lp_rays* rays,
@@ -271,31 +389,113 @@ lp_status lp_render_bwd(const lp_grid* grid, const lp_mlp* mlp, const lp_rays* r
     io.ws_stride = ws_stride(m);
     hipStream_t s = (hipStream_t)stream;
 
-    if (fast_bwd) {
-        hipError_t e = lp::launch_bwd_mfma(g, m, r, io, n_cu, s);
-        if (e != hipSuccess) return hip_fail("backward matrix-core kernel launch", e);
-        return LP_OK;
-    }
-    const size_t lds = generic_bwd_lds(m);
-    if (lds > kMaxLds)
-        return fail(LP_ERR_UNSUPPORTED, "MLP too large for the generic backward kernel's LDS budget");
-    hipError_t e = hipFuncSetAttribute((const void*)lp::bwd_generic_kernel,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return hip_fail("hipFuncSetAttribute(bwd_generic_kernel)", e);
-    const long long n_tiles = (rays->M + kGenericLanes - 1) / kGenericLanes;
-    const long long blocks = n_tiles < max_records ? n_tiles : max_records;
-    const long long tiles_per_block = (n_tiles + blocks - 1) / blocks;
-    if (tiles_per_block > 0x7fffffffLL) return fail(LP_ERR_UNSUPPORTED, "too many rays for one launch");
-    // blocks whose first tile is past the end write an all-zero record
-    hipLaunchKernelGGL(lp::bwd_generic_kernel, dim3((unsigned)blocks), dim3(kGenericLanes), lds, s, g, m, r, io,
-                       (int)tiles_per_block);
-    e = hipGetLastError();
-    if (e != hipSuccess) return hip_fail("backward generic kernel launch", e);
-    const int threads = 256;
-    hipLaunchKernelGGL(lp::reduce_params_kernel, dim3((m.param_total + threads - 1) / threads), dim3(threads), 0, s,
-                       m, io, (int)blocks);
-    e = hipGetLastError();
-    if (e != hipSuccess) return hip_fail("parameter-gradient reduction launch", e);
+    return run_bwd(g, m, r, io, fast_bwd, max_records, n_cu, s);
+}
+
+int32_t lp_dec_has_fast_path(const lp_grid* grid, const lp_decoder* dec)
+{
+    (void)grid; (void)dec;
+    return 0;
+}
+
+lp_status lp_dec_workspace_bytes(const lp_grid* grid, const lp_decoder* dec, const lp_rays* rays,
+                                 int32_t math_mode, size_t* fwd_bytes, size_t* bwd_bytes)
+{
+    lp::GridDev g; lp::MlpDev m; lp::RaysDev r; lp::DecLayout d;
+    lp_status st = decoder_views(grid, dec, rays, nullptr, &g, &m, &r, &d);
+    if (st != LP_OK) return st;
+    if (math_mode != LP_MATH_DEFAULT && math_mode != LP_MATH_GENERIC)
+        return fail(math_mode == LP_MATH_BF16X3 ? LP_ERR_UNSUPPORTED : LP_ERR_INVALID_ARG,
+                    "the two-MLP decoder runs on the generic kernels only");
+    std::string err;
+    int n_cu = 0;
+    if (compute_units(&n_cu, &err)) return fail(LP_ERR_HIP, err);
+    const size_t params = align256(sizeof(float) * (size_t)m.param_total);
+    if (fwd_bytes) *fwd_bytes = params;
+    if (bwd_bytes) *bwd_bytes = 2 * params + sizeof(float) * (size_t)generic_bwd_blocks(n_cu) * (size_t)ws_stride(m);
+    return LP_OK;
+}
+
+lp_status lp_render_dec_fwd(const lp_grid* grid, const lp_decoder* dec, const lp_rays* rays,
+                            const float* bg, float* out, float* alpha, float* depth, float* ray_cache,
+                            void* workspace, size_t workspace_bytes, int32_t math_mode, void* stream)
+{
+    size_t need = 0;
+    lp_status st = lp_dec_workspace_bytes(grid, dec, rays, math_mode, &need, nullptr);
+    if (st != LP_OK) return st;
+    if (!bg) return fail(LP_ERR_INVALID_ARG, "bg must not be NULL");
+    if (rays->M > 0 && !out) return fail(LP_ERR_INVALID_ARG, "out must not be NULL");
+    if (rays->M == 0) return LP_OK;
+    if (!workspace || workspace_bytes < need)
+        return fail(LP_ERR_WORKSPACE, "workspace is NULL or smaller than lp_dec_workspace_bytes()");
+    if (((uintptr_t)workspace & 255u) != 0) return fail(LP_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+    lp::GridDev g; lp::MlpDev m; lp::RaysDev r; lp::DecLayout d;
+    st = decoder_views(grid, dec, rays, (float*)workspace, &g, &m, &r, &d);
+    if (st != LP_OK) return st;
+    hipStream_t s = (hipStream_t)stream;
+    std::string err;
+    int n_cu = 0;
+    if (compute_units(&n_cu, &err)) return fail(LP_ERR_HIP, err);
+    hipError_t e = lp::launch_dec_pack(d, m, (float*)workspace, nullptr, s);
+    if (e != hipSuccess) return hip_fail("decoder merge kernel launch", e);
+    lp::FwdOut fo;
+    fo.rgb = out; fo.alpha = alpha; fo.depth = depth; fo.cache = ray_cache;
+    for (int c = 0; c < LP_MAX_FEATURES; ++c) fo.bg[c] = c < dec->n_feat ? bg[c] : 0.0f;
+    return run_fwd(g, m, r, fo, Path::Generic, n_cu, s);
+}
+
+lp_status lp_render_dec_bwd(const lp_grid* grid, const lp_decoder* dec, const lp_rays* rays,
+                            const float* bg, const float* d_out, const float* d_alpha,
+                            const float* d_depth, const float* ray_cache, float* const d_grid[3],
+                            float* const dW_opacity[LP_MAX_LAYERS], float* const db_opacity[LP_MAX_LAYERS],
+                            float* const dW_feature[LP_MAX_LAYERS], float* const db_feature[LP_MAX_LAYERS],
+                            void* workspace, size_t workspace_bytes, int32_t math_mode, void* stream)
+{
+    size_t need = 0;
+    lp_status st = lp_dec_workspace_bytes(grid, dec, rays, math_mode, nullptr, &need);
+    if (st != LP_OK) return st;
+    if (!bg || !d_grid || !dW_opacity || !db_opacity || !dW_feature || !db_feature)
+        return fail(LP_ERR_INVALID_ARG, "bg, d_grid and the four gradient lists must not be NULL");
+    const int n_planes = grid->kind == LP_GRID_VOXEL ? 1 : 3;
+    for (int p = 0; p < n_planes; ++p)
+        if (!d_grid[p]) return fail(LP_ERR_INVALID_ARG, "d_grid has a NULL tensor");
+    for (int l = 0; l < dec->opacity.n_layers; ++l)
+        if (!dW_opacity[l] || !db_opacity[l]) return fail(LP_ERR_INVALID_ARG, "dW_opacity / db_opacity has a NULL layer");
+    for (int l = 0; l < dec->feature.n_layers; ++l)
+        if (!dW_feature[l] || !db_feature[l]) return fail(LP_ERR_INVALID_ARG, "dW_feature / db_feature has a NULL layer");
+    if (rays->M > 0 && (!d_out || !ray_cache)) return fail(LP_ERR_INVALID_ARG, "d_out and ray_cache must not be NULL");
+    if (rays->M == 0) return LP_OK;
+    if (!workspace || workspace_bytes < need)
+        return fail(LP_ERR_WORKSPACE, "workspace is NULL or smaller than lp_dec_workspace_bytes()");
+    if (((uintptr_t)workspace & 255u) != 0) return fail(LP_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+    lp::GridDev g; lp::MlpDev m; lp::RaysDev r; lp::DecLayout d;
+    st = decoder_views(grid, dec, rays, (float*)workspace, &g, &m, &r, &d);
+    if (st != LP_OK) return st;
+    for (int l = 0; l < d.Ls; ++l) { d.dWs[l] = dW_opacity[l]; d.dbs[l] = db_opacity[l]; }
+    for (int l = 0; l < d.Lv; ++l) { d.dWv[l] = dW_feature[l]; d.dbv[l] = db_feature[l]; }
+    hipStream_t s = (hipStream_t)stream;
+    std::string err;
+    int n_cu = 0;
+    if (compute_units(&n_cu, &err)) return fail(LP_ERR_HIP, err);
+    // workspace: merged parameters | merged gradient (zeroed by the merge kernel) | records
+    const size_t params = align256(sizeof(float) * (size_t)m.param_total);
+    float* packed = (float*)workspace;
+    float* grads = (float*)((char*)workspace + params);
+    hipError_t e = lp::launch_dec_pack(d, m, packed, grads, s);
+    if (e != hipSuccess) return hip_fail("decoder merge kernel launch", e);
+
+    lp::BwdIo io;
+    std::memset(&io, 0, sizeof(io));
+    io.d_rgb = d_out; io.d_alpha = d_alpha; io.d_depth = d_depth; io.cache = ray_cache;
+    for (int p = 0; p < 3; ++p) io.d_grid[p] = p < n_planes ? d_grid[p] : nullptr;
+    for (int l = 0; l < m.n_layers; ++l) { io.dW[l] = grads + m.w_off[l]; io.db[l] = grads + m.b_off[l]; }
+    for (int c = 0; c < dec->n_feat; ++c) io.bg[c] = bg[c];
+    io.ws = (float*)((char*)workspace + 2 * params);
+    io.ws_stride = ws_stride(m);
+    st = run_bwd(g, m, r, io, false, generic_bwd_blocks(n_cu), n_cu, s);
+    if (st != LP_OK) return st;
+    e = lp::launch_dec_unpack(d, m, grads, s);
+    if (e != hipSuccess) return hip_fail("decoder gradient hand-back kernel launch", e);
     return LP_OK;
 }
 

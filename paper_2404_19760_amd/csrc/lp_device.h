@@ -28,6 +28,12 @@ struct MlpDev {
     int param_total;           // floats of all weights and biases
     int max_width;             // widest layer input or output
     int act_total;             // dims[0] + ... + dims[n_layers]
+    // decoder shape: dims[0] = grid channels + n_enc direction inputs (+ zero padding);
+    // the last layer has 1 + n_feat outputs (density, then the rendered features)
+    int n_freq;                // octaves of the direction encoding (unused when n_enc == 0)
+    int n_enc;                 // 0: no direction input, else 3 + 6 n_freq
+    int n_feat;                // rendered feature channels (3 for the single-MLP decoder)
+    int feat_act;              // 0 logistic sigmoid, 1 identity
 };
 
 struct RaysDev {
@@ -41,11 +47,11 @@ struct RaysDev {
 };
 
 struct FwdOut {
-    float* rgb;
+    float* rgb;   // [M][n_feat]
     float* alpha;
     float* depth;
     float* cache;
-    float bg[3];
+    float bg[LP_MAX_FEATURES];
 };
 
 struct BwdIo {
@@ -56,7 +62,7 @@ struct BwdIo {
     float* d_grid[3];
     float* dW[LP_MAX_LAYERS];
     float* db[LP_MAX_LAYERS];
-    float bg[3];
+    float bg[LP_MAX_FEATURES];
     float* ws;         // per-wave (or per-block) partial sums of the MLP gradients
     int ws_stride;     // floats between consecutive partial-sum records
 };
@@ -86,6 +92,17 @@ __device__ __forceinline__ void axis_cell(double x, double lo, double scale, int
     c = min(c, N - 2);
     i = c;
     f = (float)(u - (double)c);
+}
+
+// Entry e of the view-direction encoding (Section 3.3: the feature MLP takes "the sampled feature
+// and view directions"; the form is this library's reading): the direction itself, then per
+// octave k the sines and the cosines of 2^k pi d, component by component.
+__device__ __forceinline__ float dir_encoding(const float d[3], int e)
+{
+    if (e < 3) return d[e];
+    const int k = (e - 3) / 6, r = (e - 3) % 6;
+    const float x = (float)(1 << k) * d[r % 3];
+    return r < 3 ? sinpif(x) : cospif(x);
 }
 
 // softplus(z) = max(z,0) + log1p(exp(-|z|)); its derivative is the logistic function.

@@ -154,6 +154,20 @@ __device__ __forceinline__ RayRegs load_ray(const RaysDev& r, long long ray)
     return q;
 }
 
+// Inputs of the MLP beyond the grid channels: the encoded view direction of the lane's ray
+// (constant along the ray), then zero padding up to dims[0].
+__device__ void set_direction_inputs(const GridDev& g, const MlpDev& m, const RayRegs& q, float* acts, int lane)
+{
+    for (int e = g.C; e < m.dims[0]; ++e)
+        acts[e * kLanes + lane] = e - g.C < m.n_enc ? dir_encoding(q.d, e - g.C) : 0.0f;
+}
+
+// rendered feature from the MLP output: logistic sigmoid (colours) or identity
+__device__ __forceinline__ float feature_act(const MlpDev& m, float z)
+{
+    return m.feat_act == 0 ? logistic_f(z) : z;
+}
+
 }  // namespace
 
 __global__ __launch_bounds__(kLanes) void fwd_generic_kernel(GridDev g, MlpDev m, RaysDev rays,
@@ -170,9 +184,12 @@ __global__ __launch_bounds__(kLanes) void fwd_generic_kernel(GridDev g, MlpDev m
     const bool live = ray_raw < rays.M;
     const long long ray = live ? ray_raw : rays.M - 1;
     const RayRegs q = load_ray(rays, ray);
-    const int out_off = m.act_total - 4;
+    const int F = m.n_feat, out_off = m.act_total - (1 + F);
+    float* racc = acts + m.act_total * kLanes;  // F columns: the rendered features
+    set_direction_inputs(g, m, q, acts, lane);
+    for (int ch = 0; ch < F; ++ch) racc[ch * kLanes + lane] = 0.0f;
 
-    float T = 1.0f, tau = 0.0f, rgb[3] = {0.0f, 0.0f, 0.0f}, depth = 0.0f;
+    float T = 1.0f, tau = 0.0f, depth = 0.0f;
     for (int j = 0; j < rays.S; ++j) {
         const float t = q.near + ((float)j + 0.5f) * q.delta;
         const Cell c = sample_cell(g, q, j);
@@ -182,14 +199,14 @@ __global__ __launch_bounds__(kLanes) void fwd_generic_kernel(GridDev g, MlpDev m
         const float sd = sigma * q.delta;
         const float Tn = T * expf(-sd);
         const float w = T - Tn;
-        for (int ch = 0; ch < 3; ++ch)
-            rgb[ch] += w * logistic_f(acts[(out_off + 1 + ch) * kLanes + lane]);
+        for (int ch = 0; ch < F; ++ch)
+            racc[ch * kLanes + lane] += w * feature_act(m, acts[(out_off + 1 + ch) * kLanes + lane]);
         depth += w * t;
         tau += sd;
         T = Tn;
     }
     if (live) {
-        for (int ch = 0; ch < 3; ++ch) out.rgb[3 * ray + ch] = rgb[ch] + T * out.bg[ch];
+        for (int ch = 0; ch < F; ++ch) out.rgb[F * ray + ch] = racc[ch * kLanes + lane] + T * out.bg[ch];
         if (out.alpha) out.alpha[ray] = 1.0f - T;
         if (out.depth) out.depth[ray] = depth;
         if (out.cache) out.cache[ray] = tau;
@@ -200,7 +217,8 @@ __global__ __launch_bounds__(kLanes) void fwd_generic_kernel(GridDev g, MlpDev m
 // first:  tau_{q-1} = tau_q - sigma_q Delta,  T = exp(-tau)  (the paper's
 // T_{q-1} = T_q exp(Delta sigma_q), kept in the log domain so that it survives T_S
 // underflowing), then Eq. (2) with the running suffix sum of w_j a_j.
-// LDS: params | dparams accumulators | acts (act_total columns) | dz (2 * max_width columns).
+// LDS: params | dparams accumulators | acts (act_total columns) | dz (2 * max_width columns) |
+// upstream feature gradients (n_feat columns).
 __global__ __launch_bounds__(kLanes) void bwd_generic_kernel(GridDev g, MlpDev m, RaysDev rays,
                                                              BwdIo io, int tiles_per_block)
 {
@@ -210,12 +228,13 @@ __global__ __launch_bounds__(kLanes) void bwd_generic_kernel(GridDev g, MlpDev m
     float* acts = sdW + m.param_total;
     float* dz0 = acts + m.act_total * kLanes;
     float* dz1 = dz0 + m.max_width * kLanes;
+    float* pcol = dz1 + m.max_width * kLanes;
     stage_params(m, sW);
     for (int i = threadIdx.x; i < m.param_total; i += blockDim.x) sdW[i] = 0.0f;
     __syncthreads();
 
     const int lane = threadIdx.x;
-    const int out_off = m.act_total - 4;
+    const int F = m.n_feat, out_off = m.act_total - (1 + F);
     const long long n_tiles = (rays.M + kLanes - 1) / kLanes;
 
     for (int it = 0; it < tiles_per_block; ++it) {
@@ -225,14 +244,19 @@ __global__ __launch_bounds__(kLanes) void bwd_generic_kernel(GridDev g, MlpDev m
         const bool live = ray_raw < rays.M;
         const long long ray = live ? ray_raw : rays.M - 1;
         const RayRegs q = load_ray(rays, ray);
-        float p[3];
-        for (int ch = 0; ch < 3; ++ch) p[ch] = live ? io.d_rgb[3 * ray + ch] : 0.0f;
+        set_direction_inputs(g, m, q, acts, lane);
+        float pbg = 0.0f;  // p . bg
+        for (int ch = 0; ch < F; ++ch) {
+            const float p = live ? io.d_rgb[F * ray + ch] : 0.0f;
+            pcol[ch * kLanes + lane] = p;
+            pbg += p * io.bg[ch];
+        }
         const float p_alpha = (live && io.d_alpha) ? io.d_alpha[ray] : 0.0f;
         const float p_depth = (live && io.d_depth) ? io.d_depth[ray] : 0.0f;
         const float tau_S = io.cache[ray];
         const float T_S = expf(-tau_S);
-        // d(loss)/dT_S through alpha = 1 - T_S and rgb += T_S bg
-        const float kS = T_S * (p_alpha - (p[0] * io.bg[0] + p[1] * io.bg[1] + p[2] * io.bg[2]));
+        // d(loss)/dT_S through alpha = 1 - T_S and the background term
+        const float kS = T_S * (p_alpha - pbg);
         float tau = tau_S;   // optical depth up to and including the current sample
         float suffix = 0.0f; // sum_{j>q} w_j a_j
 
@@ -248,11 +272,9 @@ __global__ __launch_bounds__(kLanes) void bwd_generic_kernel(GridDev g, MlpDev m
             const float tau_prev = tau - sd;
             const float Tprev = expf(-tau_prev);  // T_{q-1}
             const float w = Tprev - Tq;
-            float col[3], a = p_depth * t;
-            for (int ch = 0; ch < 3; ++ch) {
-                col[ch] = logistic_f(acts[(out_off + 1 + ch) * kLanes + lane]);
-                a += p[ch] * col[ch];
-            }
+            float a = p_depth * t;
+            for (int ch = 0; ch < F; ++ch)
+                a += pcol[ch * kLanes + lane] * feature_act(m, acts[(out_off + 1 + ch) * kLanes + lane]);
             const float dsigma = q.delta * (Tq * a - suffix + kS);
             suffix += w * a;
             tau = tau_prev;
@@ -261,8 +283,11 @@ __global__ __launch_bounds__(kLanes) void bwd_generic_kernel(GridDev g, MlpDev m
             float* dz = dz0;
             float* dz_next = dz1;
             dz[0 * kLanes + lane] = live ? dsigma * logistic_f(z0) : 0.0f;
-            for (int ch = 0; ch < 3; ++ch)
-                dz[(1 + ch) * kLanes + lane] = live ? w * p[ch] * col[ch] * (1.0f - col[ch]) : 0.0f;
+            for (int ch = 0; ch < F; ++ch) {
+                const float f = feature_act(m, acts[(out_off + 1 + ch) * kLanes + lane]);
+                const float df = m.feat_act == 0 ? f * (1.0f - f) : 1.0f;
+                dz[(1 + ch) * kLanes + lane] = live ? w * pcol[ch * kLanes + lane] * df : 0.0f;
+            }
 
             // layers in reverse: dz holds dL/d(pre-activation) of layer l's outputs
             int off_out = out_off;

@@ -20,4 +20,26 @@ hipError_t launch_fwd_mfma(const GridDev& g, const MlpDev& m, const RaysDev& ray
 hipError_t launch_bwd_mfma(const GridDev& g, const MlpDev& m, const RaysDev& rays, const BwdIo& io,
                            int n_cu, hipStream_t stream);
 
+
+// ---- the two-MLP decoder as ONE block-structured MLP (lp_decoder.hip) ------------------
+// Combined layer l has the opacity MLP's rows first, then the feature MLP's; a shallower MLP
+// is carried through the extra layers by identity blocks (exact behind a ReLU); the first
+// layer's columns are the grid channels, the direction encoding, zero padding.
+struct DecLayout {
+    int L, Ls, Lv;                   // layers: combined, opacity, feature
+    int dims_s[LP_MAX_LAYERS + 1], dims_v[LP_MAX_LAYERS + 1];
+    int C, E;                        // grid channels, direction-encoding width
+    const float* Ws[LP_MAX_LAYERS]; const float* bs[LP_MAX_LAYERS];
+    const float* Wv[LP_MAX_LAYERS]; const float* bv[LP_MAX_LAYERS];
+    float* dWs[LP_MAX_LAYERS]; float* dbs[LP_MAX_LAYERS];  // backward only
+    float* dWv[LP_MAX_LAYERS]; float* dbv[LP_MAX_LAYERS];
+};
+// layer widths of the merged MLP: dims[0] = in_width (>= C + E), dims[L] = 1 + n_feat
+void dec_combined_dims(const DecLayout& d, int in_width, int dims[LP_MAX_LAYERS + 1]);
+// packed[i] = value of combined parameter i (layout of MlpDev::w_off / b_off); grads, if not
+// NULL, is zeroed (param_total floats)
+hipError_t launch_dec_pack(const DecLayout& d, const MlpDev& m, float* packed, float* grads, hipStream_t stream);
+// adds the combined gradient `grads` into the two MLPs' gradient buffers of `d`
+hipError_t launch_dec_unpack(const DecLayout& d, const MlpDev& m, const float* grads, hipStream_t stream);
+
 }  // namespace lp

@@ -124,3 +124,49 @@ def check_case(lp, oracle, inp, math_mode=0, aux_grads=True, seed=0, label="", m
             assert v[1] <= max_strict_fail, (f"{label} {k}: {v[1]:.2%} of the elements miss the plain "
                                              f"tolerance (allowed {max_strict_fail:.2%})")
     return worst
+
+
+# ---- the two-MLP, view-dependent decoder ----------------------------------------------------
+
+def run_gpu_dec(lp, inp, p_out, p_alpha=None, p_depth=None, math_mode=0, device="cuda:0"):
+    """Forward + backward with `inp.decoder` through the C ABI; everything returned as numpy."""
+    import torch
+    grid, _, rays, bg = lp.to_device(inp, device)
+    dec = lp.decoder_to_device(inp.decoder, device)
+    out, alpha, depth, cache = lp.render_dec_fwd(grid, dec, rays, bg, math_mode)
+    up = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device)
+    d_grid, dWs, dbs, dWv, dbv = lp.render_dec_bwd(grid, dec, rays, bg, up(p_out), cache, up(p_alpha), up(p_depth),
+                                                   math_mode)
+    torch.cuda.synchronize()
+    cpu = lambda t: t.cpu().numpy()
+    lst = lambda ts: [cpu(t) for t in ts]
+    return dict(out=cpu(out), alpha=cpu(alpha), depth=cpu(depth), d_grid=lst(d_grid), dWs=lst(dWs), dbs=lst(dbs),
+                dWv=lst(dWv), dbv=lst(dbv))
+
+
+def check_case_dec(lp, oracle, inp, math_mode=0, aux_grads=True, seed=0, label="", max_strict_fail=0.5):
+    """Full parity of one problem with the two-MLP decoder: outputs and every gradient tensor."""
+    import lp_inputs
+    prob = oracle.Problem(inp)
+    o_out, o_alpha, o_depth = oracle.render2_fwd(prob)
+    f = o_out.shape[1]
+    p_out = mse_upstream(o_out, inp.target, inp.scene, inp.n_scenes) * np.float32(3.0 / f)
+    p_alpha = p_depth = None
+    if aux_grads:
+        p_alpha, p_depth = lp_inputs.upstream_grads(inp.n_rays, 77 + seed)
+    ref = oracle.render2_bwd(prob, p_out, p_alpha, p_depth)
+    upper = oracle.render2_bwd(prob, p_out, p_alpha, p_depth, kink_band=KINK_BAND, kink_side=+1)
+    lower = oracle.render2_bwd(prob, p_out, p_alpha, p_depth, kink_band=KINK_BAND, kink_side=-1)
+    g = run_gpu_dec(lp, inp, p_out, p_alpha, p_depth, math_mode)
+    worst = {"out": close(g["out"], o_out, FWD_RTOL, f"{label} out"),
+             "alpha": close(g["alpha"], o_alpha, FWD_RTOL, f"{label} alpha"),
+             "depth": close(g["depth"], o_depth, FWD_RTOL, f"{label} depth")}
+    for i, name in enumerate(("d_grid", "dWs", "dbs", "dWv", "dbv")):
+        for j, a in enumerate(g[name]):
+            worst[f"{name}{j}"] = close_envelope(a, ref[i][j], lower[i][j], upper[i][j], BWD_RTOL,
+                                                 f"{label} {name}[{j}]")
+    for k, v in worst.items():
+        if isinstance(v, tuple) and k.startswith("d_grid"):
+            assert v[1] <= max_strict_fail, (f"{label} {k}: {v[1]:.2%} of the elements miss the plain "
+                                             f"tolerance (allowed {max_strict_fail:.2%})")
+    return worst

@@ -1,0 +1,65 @@
+"""GPU parity of the Renderer with the paper's two-MLP, view-dependent decoder against the
+CPU oracle, through the C ABI (tolerances as in test_gpu_parity.py)."""
+import dataclasses
+
+import numpy as np
+import pytest
+
+import lp_inputs
+from lp_inputs import TRIPLANE, VOXEL
+
+from parity import check_case_dec
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def oracle():
+    import oracle as o
+    return o
+
+
+def problem(kind, *, channels, hidden_s, hidden_v, n_freq, n_feat, feat_act=0, seed=0, n_rays=100, samples=40,
+            n_scenes=1, bias_std=0.2, **kw):
+    inp = lp_inputs.make_small(kind, channels=channels, mlp_dims=(channels, 4), n_rays=n_rays, samples=samples,
+                               seed=seed, n_scenes=n_scenes, **kw)
+    dec = lp_inputs.make_decoder(channels, hidden_s, hidden_v, n_freq, n_feat, seed + 100, bias_std, feat_act)
+    rng = np.random.default_rng(seed + 7)
+    return dataclasses.replace(inp, decoder=dec, bg=tuple(rng.random(n_feat).astype(np.float32).tolist()),
+                               target=rng.random((n_rays, n_feat), dtype=np.float32))
+
+
+@pytest.mark.parametrize("kind", [VOXEL, TRIPLANE])
+@pytest.mark.parametrize("hidden_s,hidden_v,n_freq,n_feat,feat_act", [
+    ((7,), (9,), 0, 3, 0),          # equal depth, raw direction
+    ((6,), (9, 8), 1, 5, 1),        # shallower opacity MLP (identity carry), identity features
+    ((8, 5), (7,), 2, 1, 0),        # shallower feature MLP, one rendered channel
+    ((16, 16), (24, 24), 4, 16, 0),  # the limits: four octaves, 16 features
+])
+def test_decoder_generic(lp, oracle, kind, hidden_s, hidden_v, n_freq, n_feat, feat_act):
+    inp = problem(kind, channels=5, hidden_s=hidden_s, hidden_v=hidden_v, n_freq=n_freq, n_feat=n_feat,
+                  feat_act=feat_act, seed=71, n_rays=131, samples=37, n_scenes=3, res=(6, 5, 7))
+    print(check_case_dec(lp, oracle, inp, lp.LP_MATH_GENERIC, label=f"dec kind={kind} {hidden_s}/{hidden_v}"),
+          flush=True)
+
+
+def test_decoder_errors(lp):
+    import torch
+    inp = problem(VOXEL, channels=4, hidden_s=(6,), hidden_v=(6,), n_freq=1, n_feat=3, n_rays=9)
+    grid, _, rays, bg = lp.to_device(inp)
+    dec = lp.decoder_to_device(inp.decoder)
+    with pytest.raises(lp.LightplaneError) as e:
+        lp.render_dec_fwd(grid, dataclasses.replace(dec, n_freq=2), rays, bg)     # input width no longer fits
+    assert e.value.status == lp.LP_ERR_INVALID_ARG
+    with pytest.raises(lp.LightplaneError) as e:
+        lp.render_dec_fwd(grid, dataclasses.replace(dec, n_feat=2), rays, bg)
+    assert e.value.status == lp.LP_ERR_INVALID_ARG
+    lin = lp.Mlp(dec.opacity.weights[:1], dec.opacity.biases[:1])                   # no hidden layer
+    with pytest.raises(lp.LightplaneError) as e:
+        lp.render_dec_fwd(grid, dataclasses.replace(dec, opacity=lin), rays, bg)
+    assert e.value.status == lp.LP_ERR_UNSUPPORTED
+    out = torch.empty((9, 3), device="cuda:0")
+    tiny = torch.empty(16, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(lp.LightplaneError) as e:
+        lp.lp_render_dec_fwd(grid, dec, rays, bg, out, None, None, None, tiny)
+    assert e.value.status == lp.LP_ERR_WORKSPACE
