@@ -192,9 +192,11 @@ def test_forward_is_bit_reproducible_and_gradients_accumulate(lp):
 def test_activation_memory_independent_of_samples(lp):
     """Section 3.4: the only state kept between forward and backward is one scalar per ray;
     the library allocates nothing and its workspace does not grow with S."""
+    import gc
     import torch
     inp = lp_inputs.make_inputs("tiny")
     peaks, ws_bytes = [], []
+    gc.collect()   # tensors of earlier tests still held by reference cycles would be freed mid-measurement
     for s in (64, 256):
         q = dataclasses.replace(inp, samples=s)
         grid, mlp, rays, bg = lp.to_device(q)
