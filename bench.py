@@ -38,7 +38,7 @@ def parse():
     ap.add_argument("--math", default="default", choices=["default", "generic", "bf16x3"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
-    ap.add_argument("--also", default="single_scene,contract",
+    ap.add_argument("--also", default="single_scene,contract,decoder",
                     help="further workloads reported for context under 'also' (comma-separated, '' to skip)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy kernel (reference for HBM counters)")
@@ -77,15 +77,23 @@ def measure(lp, torch, name, mode, steps, warmup, calibrate_copy=False):
     dev = "cuda:0"
     grid, mlp, rays, bg = lp.to_device(inp, dev)
     target = torch.from_numpy(inp.target).to(dev)
-    fast = lp.lp_has_fast_path(grid, mlp) and mode != lp.LP_MATH_GENERIC
+    dec = lp.decoder_to_device(inp.decoder, dev) if inp.decoder is not None else None
+    if dec is None:
+        fast = lp.lp_has_fast_path(grid, mlp) and mode != lp.LP_MATH_GENERIC
+    else:
+        fast = lp.lp_dec_has_fast_path(grid, dec) and mode != lp.LP_MATH_GENERIC
 
     m = rays.n_rays
     rgb = torch.empty((m, 3), device=dev); alpha = torch.empty(m, device=dev)
     depth = torch.empty(m, device=dev); cache = torch.empty(m, device=dev)
     d_grid = [torch.zeros_like(t) for t in grid.data]
-    dW = [torch.zeros_like(t) for t in mlp.weights]
-    db = [torch.zeros_like(t) for t in mlp.biases]
-    ws = torch.empty(lp.lp_bwd_workspace_bytes(grid, mlp, rays, mode), dtype=torch.uint8, device=dev)
+    if dec is None:
+        params = [mlp.weights, mlp.biases]
+        ws = torch.empty(lp.lp_bwd_workspace_bytes(grid, mlp, rays, mode), dtype=torch.uint8, device=dev)
+    else:
+        params = [dec.opacity.weights, dec.opacity.biases, dec.feature.weights, dec.feature.biases]
+        ws = torch.empty(lp.lp_dec_workspace_bytes(grid, dec, rays, mode)[1], dtype=torch.uint8, device=dev)
+    grads = [[torch.zeros_like(t) for t in lst] for lst in params]
     if inp.scene is None:
         inv = torch.full((m, 1), 2.0 / (3.0 * m), device=dev)
     else:
@@ -98,13 +106,19 @@ def measure(lp, torch, name, mode, steps, warmup, calibrate_copy=False):
         # events on torch's current stream, which is the stream the library launches on
         e0, e1, e2, e3 = ev(), ev(), ev(), ev()
         e0.record()
-        lp.lp_render_fwd(grid, mlp, rays, bg, rgb, alpha, depth, cache, mode)
+        if dec is None:
+            lp.lp_render_fwd(grid, mlp, rays, bg, rgb, alpha, depth, cache, mode)
+        else:
+            lp.lp_render_dec_fwd(grid, dec, rays, bg, rgb, alpha, depth, cache, ws, mode)
         e1.record()
         d_rgb = (rgb - target) * inv                      # MSE loss gradient
-        for t in d_grid + dW + db:
+        for t in d_grid + [t for lst in grads for t in lst]:
             t.zero_()
         e2.record()
-        lp.lp_render_bwd(grid, mlp, rays, bg, d_rgb, None, None, cache, d_grid, dW, db, ws, mode)
+        if dec is None:
+            lp.lp_render_bwd(grid, mlp, rays, bg, d_rgb, None, None, cache, d_grid, grads[0], grads[1], ws, mode)
+        else:
+            lp.lp_render_dec_bwd(grid, dec, rays, bg, d_rgb, None, None, cache, d_grid, *grads, ws, mode)
         e3.record()
         return (e0, e1, e2, e3) if timed else None
 
@@ -187,7 +201,7 @@ def main():
         out.setdefault("also", []).append(
             {"workload": name, "ray_samples": o["samples"], "value": o["samples"] / (o["elapsed"] / k),
              "unit": "ray-samples/s", "fwd_ms": o["fwd_ms"], "bwd_ms": o["bwd_ms"],
-             "contract_a": ow.contract_a,
+             "contract_a": ow.contract_a, "two_mlp_decoder": ow.dec_hidden is not None, "kernels": "mfma" if o["fast"] else "generic",
              "fwd_bwd_frac_hbm_peak": 3 * ow.gather_bytes_per_sample * o["samples"]
              / ((o["fwd_ms"] + o["bwd_ms"]) * 1e-3) / 1e9 / HBM_PEAK_GBS})
         del o

@@ -41,6 +41,8 @@ class Workload:
     aabb: float = 2.75        # grid spans [-aabb, aabb]^3
     cfg_id: int = 0
     contract_a: float = 0.0   # > 0: contract coordinates with this foreground scale (grid spans [-1, 1]^3)
+    dec_hidden: Optional[Tuple[Tuple[int, ...], Tuple[int, ...]]] = None  # two-MLP decoder: hidden widths (opacity, feature)
+    dec_freq: int = 0         # octaves of its view-direction encoding
 
     @property
     def rays(self) -> int:
@@ -82,6 +84,10 @@ WORKLOADS = {
     # coordinates (unbounded scene: the rays run far beyond the unit cube).
     "contract": Workload("contract", VOXEL, 1, 32, (160, 160, 160), 0.1, (32, 64, 64, 4),
                          256, 1, 384, near=0.5, far=12.0, aabb=1.0, cfg_id=6, contract_a=1.0),
+    # The paper's decoder (opacity MLP + view-dependent feature MLP, Section 3.3) at a size the
+    # matrix-core kernels take: 16 grid channels, two hidden layers of 32 + 32, 15 direction inputs.
+    "decoder": Workload("decoder", VOXEL, 1, 16, (128, 128, 128), 0.1, (16, 64, 64, 4),
+                        256, 1, 256, cfg_id=7, dec_hidden=((32, 32), (32, 32)), dec_freq=2),
 }
 WORKLOAD_ORDER = ["tiny", "single_scene", "voxel", "batched", "large"]
 
@@ -264,7 +270,10 @@ def make_inputs(name: str, aabb: Optional[float] = None, with_grid: bool = True)
     origins, dirs, near, far, scene = make_rays(w)
     rng = np.random.default_rng(_seed(w.cfg_id, 2))
     target = rng.random((origins.shape[0], 3), dtype=np.float32)
-    return Inputs(kind=w.kind, n_scenes=w.n_scenes, channels=w.channels, res=w.res, grid=grid,
+    decoder = None
+    if w.dec_hidden is not None:
+        decoder = make_decoder(w.channels, w.dec_hidden[0], w.dec_hidden[1], w.dec_freq, 3, _seed(w.cfg_id, 3))
+    return Inputs(kind=w.kind, n_scenes=w.n_scenes, channels=w.channels, res=w.res, grid=grid, decoder=decoder,
                   aabb_min=(-a, -a, -a), aabb_max=(a, a, a), mlp_dims=w.mlp_dims,
                   weights=ws, biases=bs, origins=origins, dirs=dirs, near=near, far=far,
                   scene=scene, samples=w.samples, bg=(1.0, 1.0, 1.0), target=target,

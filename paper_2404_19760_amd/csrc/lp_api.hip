@@ -259,7 +259,8 @@ lp_status decoder_views(const lp_grid* grid, const lp_decoder* dec, const lp_ray
 
     std::memset(m, 0, sizeof(*m));
     m->n_layers = d->L;
-    lp::dec_combined_dims(*d, C + E, m->dims);
+    // 16 grid channels: pad the inputs to 32 (zero columns), the width the matrix-core kernels take
+    lp::dec_combined_dims(*d, (C == 16 && C + E <= 32) ? 32 : C + E, m->dims);
     int off = 0, maxw = 0, act = 0;
     for (int l = 0; l <= m->n_layers; ++l) {
         maxw = m->dims[l] > maxw ? m->dims[l] : maxw;
@@ -394,8 +395,24 @@ lp_status lp_render_bwd(const lp_grid* grid, const lp_mlp* mlp, const lp_rays* r
 
 int32_t lp_dec_has_fast_path(const lp_grid* grid, const lp_decoder* dec)
 {
-    (void)grid; (void)dec;
-    return 0;
+    lp_rays dummy;
+    std::memset(&dummy, 0, sizeof(dummy));
+    dummy.S = 1;
+    lp::GridDev g; lp::MlpDev m; lp::RaysDev r; lp::DecLayout d;
+    if (decoder_views(grid, dec, &dummy, nullptr, &g, &m, &r, &d) != LP_OK) return 0;
+    return lp::mfma_supported(g, m) ? 1 : 0;
+}
+
+// kernel family and number of partial-sum records for a decoder call
+lp_status decoder_path(const lp::GridDev& g, const lp::MlpDev& m, int32_t math_mode, Path* path, int* records)
+{
+    lp_status st = choose_path(g, m, math_mode, path);
+    if (st != LP_OK) return st;
+    std::string err;
+    int n_cu = 0;
+    if (compute_units(&n_cu, &err)) return fail(LP_ERR_HIP, err);
+    *records = *path == Path::Mfma ? lp::mfma_bwd_records(n_cu) : generic_bwd_blocks(n_cu);
+    return LP_OK;
 }
 
 lp_status lp_dec_workspace_bytes(const lp_grid* grid, const lp_decoder* dec, const lp_rays* rays,
@@ -404,15 +421,14 @@ lp_status lp_dec_workspace_bytes(const lp_grid* grid, const lp_decoder* dec, con
     lp::GridDev g; lp::MlpDev m; lp::RaysDev r; lp::DecLayout d;
     lp_status st = decoder_views(grid, dec, rays, nullptr, &g, &m, &r, &d);
     if (st != LP_OK) return st;
-    if (math_mode != LP_MATH_DEFAULT && math_mode != LP_MATH_GENERIC)
-        return fail(math_mode == LP_MATH_BF16X3 ? LP_ERR_UNSUPPORTED : LP_ERR_INVALID_ARG,
-                    "the two-MLP decoder runs on the generic kernels only");
-    std::string err;
-    int n_cu = 0;
-    if (compute_units(&n_cu, &err)) return fail(LP_ERR_HIP, err);
+    Path path;
+    int records = 0;
+    // alignment of the grid tensors decides the path too; sizes take the larger record count
+    st = decoder_path(g, m, math_mode, &path, &records);
+    if (st != LP_OK) return st;
     const size_t params = align256(sizeof(float) * (size_t)m.param_total);
     if (fwd_bytes) *fwd_bytes = params;
-    if (bwd_bytes) *bwd_bytes = 2 * params + sizeof(float) * (size_t)generic_bwd_blocks(n_cu) * (size_t)ws_stride(m);
+    if (bwd_bytes) *bwd_bytes = 2 * params + sizeof(float) * (size_t)records * (size_t)ws_stride(m);
     return LP_OK;
 }
 
@@ -441,7 +457,11 @@ lp_status lp_render_dec_fwd(const lp_grid* grid, const lp_decoder* dec, const lp
     lp::FwdOut fo;
     fo.rgb = out; fo.alpha = alpha; fo.depth = depth; fo.cache = ray_cache;
     for (int c = 0; c < LP_MAX_FEATURES; ++c) fo.bg[c] = c < dec->n_feat ? bg[c] : 0.0f;
-    return run_fwd(g, m, r, fo, Path::Generic, n_cu, s);
+    Path path;
+    int records = 0;
+    st = decoder_path(g, m, math_mode, &path, &records);
+    if (st != LP_OK) return st;
+    return run_fwd(g, m, r, fo, path, n_cu, s);
 }
 
 lp_status lp_render_dec_bwd(const lp_grid* grid, const lp_decoder* dec, const lp_rays* rays,
@@ -492,7 +512,11 @@ lp_status lp_render_dec_bwd(const lp_grid* grid, const lp_decoder* dec, const lp
     for (int c = 0; c < dec->n_feat; ++c) io.bg[c] = bg[c];
     io.ws = (float*)((char*)workspace + 2 * params);
     io.ws_stride = ws_stride(m);
-    st = run_bwd(g, m, r, io, false, generic_bwd_blocks(n_cu), n_cu, s);
+    Path path;
+    int records = 0;
+    st = decoder_path(g, m, math_mode, &path, &records);
+    if (st != LP_OK) return st;
+    st = run_bwd(g, m, r, io, path == Path::Mfma, records, n_cu, s);
     if (st != LP_OK) return st;
     e = lp::launch_dec_unpack(d, m, grads, s);
     if (e != hipSuccess) return hip_fail("decoder gradient hand-back kernel launch", e);

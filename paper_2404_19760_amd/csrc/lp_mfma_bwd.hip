@@ -78,14 +78,14 @@ __device__ __forceinline__ Frag selection(int j, int grp, IndexFn index_of)
     return f;
 }
 
-template <int KIND, int C, int H, int NH, bool CC>
+template <int KIND, int C, int H, int NH, bool CC, int CG>
 __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev m, RaysDev rays, BwdIo io,
                                                                long long group_mul)
 {
     using L = MlpLds<C, H, NH, true, kBwdNB>;
     constexpr int MB = L::MB, KS1 = L::KS1, KSH = L::KSH;
     extern __shared__ uint4 lds[];
-    stage_mlp<C, H, NH, true, kBwdNB>(lds, m);
+    stage_mlp<C, H, NH, true, kBwdNB, CG>(lds, m);
     __syncthreads();
 
     const int lane = threadIdx.x & 63;
@@ -162,18 +162,19 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
     Frag fh[KS1], fl[KS1];
     if (seq < sched.end) {  // a wave without rays only writes its (zero) record
         q_next = load_ray_geom(rays, ray_of(seq));
+        if constexpr (CG != C) set_direction_inputs(m, q_next);
         cell = sample_cell<CC>(g, q_next, min(j_last + slot_to_sample(col), S - 1));
-        float feat[C / 2];
-        gather_half<KIND, C, C / 2>(g, q_next.scene, cell, grp * (C / 2), feat);
-#pragma unroll
-        for (int s = 0; s < KS1; ++s) split8(feat + 8 * s, fh[s], fl[s]);
+        sample_features<KIND, C, CG>(g, q_next, cell, grp, fh, fl);
     }
 
     while (seq < sched.end) {
         const long long ray = ray_of(seq);
         const RayGeom q = q_next;
         seq = valid_from(seq + sched.stride);
-        if (seq < sched.end) q_next = load_ray_geom(rays, ray_of(seq));  // else: a harmless re-sample of this ray
+        if (seq < sched.end) {  // else: a harmless re-sample of this ray
+            q_next = load_ray_geom(rays, ray_of(seq));
+            if constexpr (CG != C) set_direction_inputs(m, q_next);
+        }
         const float p0 = io.d_rgb[3 * ray + 0], p1 = io.d_rgb[3 * ray + 1], p2 = io.d_rgb[3 * ray + 2];
         const float p_alpha = io.d_alpha ? io.d_alpha[ray] : 0.0f;
         const float p_depth = io.d_depth ? io.d_depth[ray] : 0.0f;
@@ -235,7 +236,7 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
             }
             // scatter record of this lane's sample, read at the end of the step
             wave_lds_fence();
-            if (grp == 0) write_scatter_record<KIND, C>(info + col * 16, g, a.cell[0]);
+            if (grp == 0) write_scatter_record<KIND, CG>(info + col * 16, g, a.cell[0]);
 
             const Frag (&lh)[kBwdNB][KSH] = NH == 2 ? a.h2h : a.h1h;  // last hidden layer's activations
             const Frag (&ll)[kBwdNB][KSH] = NH == 2 ? a.h2l : a.h1l;
@@ -326,12 +327,7 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
             const RayGeom& qn = same ? q : q_next;
             cell = sample_cell<CC>(g, qn, min((same ? j0 - kBwdStep : j_last) + slot_to_sample(col), S - 1));
             __builtin_amdgcn_sched_barrier(0);
-            {
-                float feat[C / 2];
-                gather_half<KIND, C, C / 2>(g, qn.scene, cell, grp * (C / 2), feat);
-#pragma unroll
-                for (int s = 0; s < KS1; ++s) split8(feat + 8 * s, fh[s], fl[s]);
-            }
+            sample_features<KIND, C, CG>(g, qn, cell, grp, fh, fl);
             // the sampled features must be complete here (not sunk below the scatter)
 #pragma unroll
             for (int s = 0; s < KS1; ++s)
@@ -339,7 +335,7 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
                 for (int w = 0; w < 4; ++w) asm volatile("" : "+v"(fh[s].d[w]), "+v"(fl[s].d[w]));
             __builtin_amdgcn_sched_barrier(0);
             wave_lds_fence();
-            scatter_channels<KIND, C>(g, io.d_grid, q.scene, info, dFt, col, grp);
+            scatter_channels<KIND, CG>(g, io.d_grid, q.scene, info, dFt, col, grp);
         }
     }
 
@@ -377,13 +373,13 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
     }
 }
 
-template <int KIND, int C, int H, int NH, bool CC>
+template <int KIND, int C, int H, int NH, bool CC, int CG>
 hipError_t launch_bwd(const GridDev& g, const MlpDev& m, const RaysDev& rays, const BwdIo& io, int n_cu,
                        hipStream_t stream)
 {
     constexpr int kLdsBytes = MlpLds<C, H, NH, true, kBwdNB>::bytes(kWaves);
     static_assert(kLdsBytes <= 160 * 1024, "LDS budget of a gfx950 compute unit");
-    auto kernel = bwd_mfma_kernel<KIND, C, H, NH, CC>;
+    auto kernel = bwd_mfma_kernel<KIND, C, H, NH, CC, CG>;
     hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (e != hipSuccess) return e;
     const int blocks = mfma_bwd_records(n_cu) / kWaves;  // every wave writes a record, busy or not
@@ -407,13 +403,20 @@ template <int KIND>
 hipError_t dispatch_bwd(const GridDev& g, const MlpDev& m, const RaysDev& rays, const BwdIo& io, int n_cu,
                          hipStream_t stream)
 {
-    const int C = g.C, H = m.dims[1], NH = m.n_layers - 1;
-#define LP_CASE(c, h, nh) \
-    if (C == c && H == h && NH == nh)                                                       \
-        return g.contract > 0.0 ? launch_bwd<KIND, c, h, nh, true>(g, m, rays, io, n_cu, stream) \
-                                : launch_bwd<KIND, c, h, nh, false>(g, m, rays, io, n_cu, stream);
-    LP_CASE(16, 32, 1) LP_CASE(16, 64, 1) LP_CASE(32, 32, 1) LP_CASE(32, 64, 1)
-    LP_CASE(16, 32, 2) LP_CASE(16, 64, 2) LP_CASE(32, 32, 2) LP_CASE(32, 64, 2)
+    const int C = m.dims[0], CG = g.C, H = m.dims[1], NH = m.n_layers - 1;
+#define LP_CASE(c, cg, h, nh)                                                                     \
+    if (C == c && CG == cg && H == h && NH == nh)                                                 \
+        return g.contract > 0.0 ? launch_bwd<KIND, c, h, nh, true, cg>(g, m, rays, io, n_cu, stream) \
+                                : launch_bwd<KIND, c, h, nh, false, cg>(g, m, rays, io, n_cu, stream);
+    LP_CASE(16, 16, 32, 1) LP_CASE(16, 16, 64, 1) LP_CASE(32, 32, 32, 1) LP_CASE(32, 32, 64, 1)
+    LP_CASE(16, 16, 32, 2) LP_CASE(16, 16, 64, 2) LP_CASE(32, 32, 32, 2) LP_CASE(32, 32, 64, 2)
+#undef LP_CASE
+    // 16 grid channels + direction inputs (the two-MLP decoder merged into one MLP of 32 inputs);
+    // without contract coordinates (that combination runs on the generic kernels)
+#define LP_CASE(h, nh) \
+    if (C == 32 && CG == 16 && H == h && NH == nh && !(g.contract > 0.0)) \
+        return launch_bwd<KIND, 32, h, nh, false, 16>(g, m, rays, io, n_cu, stream);
+    LP_CASE(32, 1) LP_CASE(64, 1) LP_CASE(32, 2) LP_CASE(64, 2)
 #undef LP_CASE
     return hipErrorInvalidValue;
 }

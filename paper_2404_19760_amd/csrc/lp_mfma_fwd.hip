@@ -19,12 +19,12 @@ constexpr int kWaves = 4;
 // NB = N blocks of 32 samples per step.  NB = 2: lane l owns sample l of the 64-sample step.
 // NB = 1 (half the registers, two waves per SIMD for the wide MLPs): both lane groups hold the
 // decoder outputs of sample (lane & 31); group 0 alone accumulates.
-template <int KIND, int C, int H, int NH, int NB, bool CC>
+template <int KIND, int C, int H, int NH, int NB, bool CC, int CG>
 __global__ __launch_bounds__(kWaves * 64) void fwd_mfma_kernel(GridDev g, MlpDev m, RaysDev rays, FwdOut out)
 {
     constexpr int kStep = 32 * NB;
     extern __shared__ uint4 lds[];
-    stage_mlp<C, H, NH, false, NB>(lds, m);
+    stage_mlp<C, H, NH, false, NB, CG>(lds, m);
     __syncthreads();
 
     const int lane = threadIdx.x & 63;
@@ -32,17 +32,18 @@ __global__ __launch_bounds__(kWaves * 64) void fwd_mfma_kernel(GridDev g, MlpDev
     const int S = rays.S;
 
     for (long long ray = sched.first; ray < sched.end; ray += sched.stride) {
-        const RayGeom q = load_ray_geom(rays, ray);
+        RayGeom q = load_ray_geom(rays, ray);
+        if constexpr (CG != C) set_direction_inputs(m, q);
         float tau = 0.0f;                                              // optical depth of earlier steps
         float acc_r = 0.0f, acc_g = 0.0f, acc_b = 0.0f, acc_d = 0.0f;  // per-lane partial sums
 
         for (int j0 = 0; j0 < S; j0 += kStep) {
             struct { float z[4]; } a;
             if constexpr (NB == 2) {
-                forward_outputs<KIND, C, H, NH, CC>(g, lds, q, j0, S, lane, a.z);
+                forward_outputs<KIND, C, H, NH, CC, CG>(g, lds, q, j0, S, lane, a.z);
             } else {
                 StepActs<C, H, NH, NB> full;
-                forward_step<KIND, C, H, NH, false, NB, false, CC>(g, lds, q, j0, S, lane, full);
+                forward_step<KIND, C, H, NH, false, NB, false, CC, CG>(g, lds, q, j0, S, lane, full);
 #pragma unroll
                 for (int k = 0; k < 4; ++k) a.z[k] = full.z[k];
             }
@@ -78,12 +79,12 @@ __global__ __launch_bounds__(kWaves * 64) void fwd_mfma_kernel(GridDev g, MlpDev
     }
 }
 
-template <int KIND, int C, int H, int NH, int NB, bool CC>
+template <int KIND, int C, int H, int NH, int NB, bool CC, int CG>
 hipError_t launch_fwd(const GridDev& g, const MlpDev& m, const RaysDev& rays, const FwdOut& out, int n_cu,
                       hipStream_t stream)
 {
     constexpr int kLdsBytes = MlpLds<C, H, NH, false, NB>::bytes(kWaves);
-    auto kernel = fwd_mfma_kernel<KIND, C, H, NH, NB, CC>;
+    auto kernel = fwd_mfma_kernel<KIND, C, H, NH, NB, CC, CG>;
     hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (e != hipSuccess) return e;
     // persistent grid: as many workgroups as fit a compute unit's registers, a multiple of the 8 XCDs, no more than the rays need
@@ -99,13 +100,20 @@ template <int KIND>
 hipError_t dispatch_fwd(const GridDev& g, const MlpDev& m, const RaysDev& rays, const FwdOut& out, int n_cu,
                         hipStream_t stream)
 {
-    const int C = g.C, H = m.dims[1], NH = m.n_layers - 1;
-#define LP_CASE(c, h, nh) \
-    if (C == c && H == h && NH == nh)                                                            \
-        return g.contract > 0.0 ? launch_fwd<KIND, c, h, nh, 2, true>(g, m, rays, out, n_cu, stream) \
-                                : launch_fwd<KIND, c, h, nh, 2, false>(g, m, rays, out, n_cu, stream);
-    LP_CASE(16, 32, 1) LP_CASE(16, 64, 1) LP_CASE(32, 32, 1) LP_CASE(32, 64, 1)
-    LP_CASE(16, 32, 2) LP_CASE(16, 64, 2) LP_CASE(32, 32, 2) LP_CASE(32, 64, 2)
+    const int C = m.dims[0], CG = g.C, H = m.dims[1], NH = m.n_layers - 1;
+#define LP_CASE(c, cg, h, nh)                                                                          \
+    if (C == c && CG == cg && H == h && NH == nh)                                                      \
+        return g.contract > 0.0 ? launch_fwd<KIND, c, h, nh, 2, true, cg>(g, m, rays, out, n_cu, stream) \
+                                : launch_fwd<KIND, c, h, nh, 2, false, cg>(g, m, rays, out, n_cu, stream);
+    LP_CASE(16, 16, 32, 1) LP_CASE(16, 16, 64, 1) LP_CASE(32, 32, 32, 1) LP_CASE(32, 32, 64, 1)
+    LP_CASE(16, 16, 32, 2) LP_CASE(16, 16, 64, 2) LP_CASE(32, 32, 32, 2) LP_CASE(32, 32, 64, 2)
+#undef LP_CASE
+    // 16 grid channels + direction inputs (the two-MLP decoder merged into one MLP of 32 inputs);
+    // without contract coordinates (that combination runs on the generic kernels)
+#define LP_CASE(h, nh) \
+    if (C == 32 && CG == 16 && H == h && NH == nh && !(g.contract > 0.0)) \
+        return launch_fwd<KIND, 32, h, nh, 2, false, 16>(g, m, rays, out, n_cu, stream);
+    LP_CASE(32, 1) LP_CASE(64, 1) LP_CASE(32, 2) LP_CASE(64, 2)
 #undef LP_CASE
     return hipErrorInvalidValue;
 }
@@ -114,7 +122,11 @@ hipError_t dispatch_fwd(const GridDev& g, const MlpDev& m, const RaysDev& rays, 
 
 bool mfma_supported(const GridDev& g, const MlpDev& m)
 {
-    if (g.C != 16 && g.C != 32) return false;
+    // inputs: all of them grid channels (16 or 32), or 16 grid channels + 16 direction inputs
+    const bool plain = m.n_enc == 0 && m.dims[0] == g.C && (g.C == 16 || g.C == 32);
+    const bool with_dir = m.n_enc > 0 && g.C == 16 && m.dims[0] == 32 && m.n_enc <= 16 && !(g.contract > 0.0);
+    if (!plain && !with_dir) return false;
+    if (m.n_feat != 3 || m.feat_act != 0 || m.dims[m.n_layers] != 4) return false;
     if (m.n_layers != 2 && m.n_layers != 3) return false;
     const int H = m.dims[1];
     if (H != 32 && H != 64) return false;

@@ -32,7 +32,9 @@ struct MlpLds {
     static constexpr int bytes(int waves) { return (END + (BWD ? waves * INFO_UNITS : 0)) * 16; }
 };
 
-template <int C, int H, int NH, bool BWD, int NB>
+// CG = channels of the grid (the gradient of the first CG inputs is scattered); CG < C: the
+// other inputs are per-ray direction inputs.
+template <int C, int H, int NH, bool BWD, int NB, int CG = C>
 __device__ __forceinline__ void stage_mlp(uint4* lds, const MlpDev& m)
 {
     using L = MlpLds<C, H, NH, BWD, NB>;
@@ -56,9 +58,9 @@ __device__ __forceinline__ void stage_mlp(uint4* lds, const MlpDev& m)
         if constexpr (NH == 2)
             stage_operand_t(lds + L::T2, m.W[1], MB, KSH, H, [](int mb, int i) { return 32 * mb + i; },
                             [](int s, int gg, int e) { return k_hidden(s, gg, e); });
-        // rows >= C: zero for C = 32 (none), a second copy of the 16 rows for C = 16 (the scatter of
-        // the backward kernel uses both halves of a lane group)
-        stage_operand_t(lds + L::T1, m.W[0], 1, KSH, C, [](int, int i) { return i & (C - 1); },
+        // 32 rows: for 16 grid channels a second copy of their 16 rows (the scatter of the
+        // backward kernel uses both halves of a lane group)
+        stage_operand_t(lds + L::T1, m.W[0], 1, KSH, C, [](int, int i) { return i & (CG - 1); },
                         [](int s, int gg, int e) { return k_hidden(s, gg, e); });
     }
     float* sbias = reinterpret_cast<float*>(lds + L::BIAS);
@@ -150,7 +152,16 @@ struct RayGeom {
     float ox, oy, oz, dx, dy, dz, near, delta;
     double delta64;
     int scene;
+    float extra[16];  // direction inputs of the MLP (only when the MLP has more inputs than the grid has channels)
 };
+
+// the encoded view direction, then zeros
+__device__ __forceinline__ void set_direction_inputs(const MlpDev& m, RayGeom& q)
+{
+    const float d[3] = {q.dx, q.dy, q.dz};
+#pragma unroll
+    for (int e = 0; e < 16; ++e) q.extra[e] = e < m.n_enc ? dir_encoding(d, e) : 0.0f;
+}
 
 __device__ __forceinline__ RayGeom load_ray_geom(const RaysDev& rays, long long ray)
 {
@@ -183,6 +194,29 @@ __host__ __device__ constexpr int slot_to_sample(int slot)
 __host__ __device__ constexpr int sample_to_slot(int smp)
 {
     return 8 * ((smp >> 2) & 3) + 4 * (smp >> 4) + (smp & 3);
+}
+
+// Input features of one sample column as operand fragments: lane (col, grp) holds inputs
+// [grp C/2, (grp+1) C/2).  CG == C: all inputs are grid channels.  CG == C/2: lane group 0 holds
+// the CG grid channels, lane group 1 the per-ray direction inputs q.extra.
+template <int KIND, int C, int CG>
+__device__ __forceinline__ void sample_features(const GridDev& g, const RayGeom& q, const Cell3& c, int grp,
+                                                Frag (&fh)[C / 16], Frag (&fl)[C / 16])
+{
+    float feat[C / 2];
+    if constexpr (CG == C) {
+        gather_half<KIND, C, C / 2>(g, q.scene, c, grp * (C / 2), feat);
+    } else {
+        static_assert(2 * CG == C && CG == 16, "direction inputs take the second half of 32 inputs");
+        if (grp == 0) {
+            gather_half<KIND, CG, CG>(g, q.scene, c, 0, feat);
+        } else {
+#pragma unroll
+            for (int e = 0; e < CG; ++e) feat[e] = q.extra[e];
+        }
+    }
+#pragma unroll
+    for (int s = 0; s < C / 16; ++s) split8(feat + 8 * s, fh[s], fl[s]);
 }
 
 // MLP forward of one step from the input features a.fh / a.fl: fills the hidden activations and
@@ -229,21 +263,17 @@ __device__ __forceinline__ void mlp_forward(const uint4* lds, int lane, StepActs
 
 // Sampling + MLP forward of one step: lane (col, grp) samples its half of the channels of
 // sample col of every N block (PERM: of the permuted step, see slot_to_sample).
-template <int KIND, int C, int H, int NH, bool BWD, int NB, bool PERM = false, bool CC = false>
+template <int KIND, int C, int H, int NH, bool BWD, int NB, bool PERM = false, bool CC = false, int CG = C>
 __device__ __forceinline__ void forward_step(const GridDev& g, const uint4* lds, const RayGeom& q, int j0, int S,
                                              int lane, StepActs<C, H, NH, NB>& a)
 {
-    constexpr int KS1 = C / 16;
     const int col = lane & 31, grp = lane >> 5;
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
         const int j = min(j0 + 32 * nb + (PERM ? slot_to_sample(col) : col), S - 1);
         const Cell3 c = sample_cell<CC>(g, q, j);
         a.cell[nb] = c;
-        float feat[C / 2];
-        gather_half<KIND, C, C / 2>(g, q.scene, c, grp * (C / 2), feat);
-#pragma unroll
-        for (int s = 0; s < KS1; ++s) split8(feat + 8 * s, a.fh[nb][s], a.fl[nb][s]);
+        sample_features<KIND, C, CG>(g, q, c, grp, a.fh[nb], a.fl[nb]);
     }
     mlp_forward<C, H, NH, BWD, NB>(lds, lane, a);
 }
@@ -253,7 +283,7 @@ __device__ __forceinline__ void forward_step(const GridDev& g, const uint4* lds,
 // remaining layers one N block after the other, so that at most one block's accumulators and
 // activations are alive at a time (registers for a second wave per SIMD).  z = outputs of
 // sample j0 + lane.
-template <int KIND, int C, int H, int NH, bool CC>
+template <int KIND, int C, int H, int NH, bool CC, int CG = C>
 __device__ __forceinline__ void forward_outputs(const GridDev& g, const uint4* lds, const RayGeom& q, int j0,
                                                 int S, int lane, float (&z)[4])
 {
@@ -267,10 +297,7 @@ __device__ __forceinline__ void forward_outputs(const GridDev& g, const uint4* l
     for (int nb = 0; nb < 2; ++nb) {
         const int j = min(j0 + 32 * nb + col, S - 1);
         const Cell3 c = sample_cell<CC>(g, q, j);
-        float feat[C / 2];
-        gather_half<KIND, C, C / 2>(g, q.scene, c, grp * (C / 2), feat);
-#pragma unroll
-        for (int s = 0; s < KS1; ++s) split8(feat + 8 * s, fh[nb][s], fl[nb][s]);
+        sample_features<KIND, C, CG>(g, q, c, grp, fh[nb], fl[nb]);
     }
     Frag h1h[2][KSH], h1l[2][KSH];
     {

@@ -43,6 +43,42 @@ def test_decoder_generic(lp, oracle, kind, hidden_s, hidden_v, n_freq, n_feat, f
           flush=True)
 
 
+@pytest.mark.parametrize("kind", [VOXEL, TRIPLANE])
+@pytest.mark.parametrize("hidden_s,hidden_v,n_freq,samples", [
+    ((16,), (16,), 0, 64),           # merged: 32 inputs (16 grid + 3 direction + zeros), width 32, one hidden layer
+    ((32, 32), (32, 32), 2, 150),    # width 64, two hidden layers, 15 direction inputs
+    ((24,), (40, 40), 1, 37),        # unequal widths, the opacity MLP carried through an identity block
+])
+def test_decoder_matrix_core(lp, oracle, kind, hidden_s, hidden_v, n_freq, samples):
+    """16 grid channels, three sigmoid features: the merged MLP fits the matrix-core kernels."""
+    inp = problem(kind, channels=16, hidden_s=hidden_s, hidden_v=hidden_v, n_freq=n_freq, n_feat=3, seed=83,
+                  n_rays=203, samples=samples, n_scenes=2, res=(12, 10, 11), grid_std=0.3,
+                  aabb_min=(-1.5, -1.5, -1.5), aabb_max=(1.5, 1.5, 1.5))
+    grid, _, _, _ = lp.to_device(inp)
+    assert lp.lp_dec_has_fast_path(grid, lp.decoder_to_device(inp.decoder))
+    for mode in (lp.LP_MATH_GENERIC, lp.LP_MATH_BF16X3):
+        print(mode, check_case_dec(lp, oracle, inp, mode, label=f"dec mfma kind={kind} {hidden_s}/{hidden_v} mode={mode}"),
+              flush=True)
+
+
+def test_decoder_fast_path_limits(lp):
+    mk = lambda **kw: problem(VOXEL, **{**dict(channels=16, hidden_s=(16,), hidden_v=(16,), n_freq=1, n_feat=3, n_rays=8), **kw})
+    def fast(inp):
+        grid, _, _, _ = lp.to_device(inp)
+        return lp.lp_dec_has_fast_path(grid, lp.decoder_to_device(inp.decoder))
+    assert fast(mk())
+    assert not fast(mk(n_feat=4))                      # three features only
+    assert not fast(mk(feat_act=1))                    # sigmoid only
+    assert not fast(mk(hidden_s=(16,), hidden_v=(20,)))  # merged width must be 32 or 64
+    assert not fast(mk(channels=32, hidden_s=(16,), hidden_v=(16,)))
+    assert not fast(dataclasses.replace(mk(), contract_a=1.0))
+    inp = mk(feat_act=1)
+    grid, _, rays, bg = lp.to_device(inp)
+    with pytest.raises(lp.LightplaneError) as e:
+        lp.render_dec_fwd(grid, lp.decoder_to_device(inp.decoder), rays, bg, lp.LP_MATH_BF16X3)
+    assert e.value.status == lp.LP_ERR_UNSUPPORTED
+
+
 def test_decoder_errors(lp):
     import torch
     inp = problem(VOXEL, channels=4, hidden_s=(6,), hidden_v=(6,), n_freq=1, n_feat=3, n_rays=9)
@@ -63,3 +99,12 @@ def test_decoder_errors(lp):
     with pytest.raises(lp.LightplaneError) as e:
         lp.lp_render_dec_fwd(grid, dec, rays, bg, out, None, None, None, tiny)
     assert e.value.status == lp.LP_ERR_WORKSPACE
+
+
+def test_decoder_workload_on_a_ray_subset(lp, oracle):
+    """The `decoder` workload of bench.py (128^3 x 16 voxels, two hidden layers of 32 + 32, two
+    octaves of direction encoding), a strided subset of its rays, matrix-core kernels."""
+    inp = lp_inputs.make_inputs("decoder")
+    sub = inp.subset(lp_inputs.strided_ray_subset(inp.n_rays, 1024, offset=5))
+    print(check_case_dec(lp, oracle, sub, lp.LP_MATH_BF16X3, aux_grads=False, label="decoder workload subset",
+                         max_strict_fail=0.03), flush=True)
