@@ -325,3 +325,70 @@ def upstream_grads(n_rays: int, seed: int):
     p_alpha = (rng.standard_normal(n_rays) / n_rays).astype(np.float32)
     p_depth = (rng.standard_normal(n_rays) / n_rays).astype(np.float32)
     return p_alpha, p_depth
+
+
+# ---- Splatter inputs ----------------------------------------------------------------------
+
+@dataclasses.dataclass
+class SplatInputs:
+    """Host buffers for one call of the Splatter: M pixels (rays + feature vectors) pushed
+    into a target hash structure of `channels` channels; optional prior structure and MLP."""
+    kind: int
+    n_scenes: int
+    channels: int                     # channels of the target structure
+    res: Tuple[int, int, int]
+    aabb_min: Tuple[float, float, float]
+    aabb_max: Tuple[float, float, float]
+    origins: np.ndarray               # [M][3] float32
+    dirs: np.ndarray                  # [M][3] float32, unit length
+    near: np.ndarray
+    far: np.ndarray
+    scene: Optional[np.ndarray]
+    samples: int
+    feats: np.ndarray                 # [M][n_in] float32 pixel features
+    n_freq: int = -1                  # octaves of the direction encoding fed to the MLP, -1: none
+    prior: Optional[List[np.ndarray]] = None   # prior structure (same kind and box), float32
+    prior_res: Optional[Tuple[int, int, int]] = None
+    prior_channels: int = 0
+    mlp_dims: Optional[Tuple[int, ...]] = None  # None: naive Splatter (n_in == channels)
+    weights: Optional[List[np.ndarray]] = None
+    biases: Optional[List[np.ndarray]] = None
+    contract_a: float = 0.0
+
+    @property
+    def n_rays(self) -> int:
+        return int(self.origins.shape[0])
+
+    @property
+    def n_in(self) -> int:
+        return int(self.feats.shape[1])
+
+    @property
+    def n_enc(self) -> int:
+        return 0 if self.n_freq < 0 else 3 + 6 * self.n_freq
+
+
+def make_splat_small(kind: int, *, n_scenes=1, channels=4, res=(5, 4, 6), n_in=None, hidden=None,
+                     n_freq=-1, prior_channels=0, prior_res=(4, 5, 3), n_rays=6, samples=7, seed=0,
+                     bias_std=0.3, **ray_kw) -> SplatInputs:
+    """A small random Splatter problem: the rays of `make_small`, random pixel features,
+    optionally a random prior structure and a He-normal MLP with hidden widths `hidden`."""
+    base = make_small(kind, n_scenes=n_scenes, channels=channels, res=res, mlp_dims=(channels, 4),
+                      n_rays=n_rays, samples=samples, seed=seed, **ray_kw)
+    rng = np.random.default_rng(seed + 50)
+    n_in = channels if n_in is None else n_in
+    feats = rng.standard_normal((n_rays, n_in)).astype(np.float32)
+    prior = None
+    if prior_channels:
+        prior = make_grid(kind, n_scenes, prior_res, prior_channels, 0.5, seed + 51)
+    dims = ws = bs = None
+    if hidden is not None:
+        n_enc = 0 if n_freq < 0 else 3 + 6 * n_freq
+        dims = (n_in + prior_channels + n_enc, *hidden, channels)
+        ws, bs = make_mlp(dims, seed + 52, bias_std)
+    return SplatInputs(kind=kind, n_scenes=n_scenes, channels=channels, res=tuple(res),
+                       aabb_min=base.aabb_min, aabb_max=base.aabb_max, origins=base.origins, dirs=base.dirs,
+                       near=base.near, far=base.far, scene=base.scene, samples=samples, feats=feats,
+                       n_freq=n_freq if hidden is not None else -1, prior=prior,
+                       prior_res=tuple(prior_res) if prior_channels else None, prior_channels=prior_channels,
+                       mlp_dims=dims, weights=ws, biases=bs)

@@ -265,3 +265,105 @@ def render2_bwd(inp, p_out, p_alpha=None, p_depth=None, kink_band: float = 0.0, 
     if rc != 0:
         raise RuntimeError(f"lpo_render2_bwd failed with status {rc}")
     return d_grid, dWs, dbs, dWv, dbv
+
+
+# ---- Splatter (Section 3.3 and the appendix's normalisation paragraph) -----------------------
+
+class _Splat(C.Structure):
+    _fields_ = [("n_in", C.c_int32), ("n_freq", C.c_int32), ("feats", C.c_void_p),
+                ("prior", C.POINTER(_Grid)), ("mlp", C.POINTER(_Mlp))]
+
+
+class SplatProblem:
+    """Float64 copies of one `lp_inputs.SplatInputs` plus the C structs that point at them."""
+
+    def __init__(self, sp):
+        self.sp = sp
+        self.origins, self.dirs = _f64(sp.origins), _f64(sp.dirs)
+        self.near, self.far = _f64(sp.near), _f64(sp.far)
+        self.scene = None if sp.scene is None else np.ascontiguousarray(sp.scene, dtype=np.int32)
+        self.feats = _f64(sp.feats)
+
+        def grid_struct(res, channels, arrays):
+            g = _Grid()
+            g.kind, g.B, g.C = sp.kind, sp.n_scenes, channels
+            g.NX, g.NY, g.NZ = res
+            for p, arr in enumerate(arrays or []):
+                g.data[p] = arr.ctypes.data
+            for a in range(3):
+                g.aabb_min[a] = float(sp.aabb_min[a])
+                g.aabb_max[a] = float(sp.aabb_max[a])
+            g.contract_a = float(np.float32(sp.contract_a))
+            return g
+        self.c_target = grid_struct(sp.res, sp.channels, None)
+        self.prior = None if sp.prior is None else [_f64(g) for g in sp.prior]
+        self.c_prior = None if sp.prior is None else grid_struct(sp.prior_res, sp.prior_channels, self.prior)
+        self.W = self.b = None
+        self.c_mlp = None
+        if sp.mlp_dims is not None:
+            self.W = [_f64(w) for w in sp.weights]
+            self.b = [_f64(b) for b in sp.biases]
+            m = _Mlp()
+            m.n_layers = len(self.W)
+            for i, d in enumerate(sp.mlp_dims):
+                m.dims[i] = int(d)
+            for l in range(len(self.W)):
+                assert self.W[l].shape == (sp.mlp_dims[l + 1], sp.mlp_dims[l])
+                m.W[l] = self.W[l].ctypes.data
+                m.b[l] = self.b[l].ctypes.data
+            self.c_mlp = m
+        r = _Rays()
+        r.M, r.S = self.origins.shape[0], int(sp.samples)
+        r.origins, r.dirs = self.origins.ctypes.data, self.dirs.ctypes.data
+        r.near, r.far = self.near.ctypes.data, self.far.ctypes.data
+        r.scene = None if self.scene is None else self.scene.ctypes.data
+        self.c_rays = r
+        s = _Splat()
+        s.n_in, s.n_freq, s.feats = int(sp.n_in), int(sp.n_freq), self.feats.ctypes.data
+        s.prior = C.pointer(self.c_prior) if self.c_prior is not None else None
+        s.mlp = C.pointer(self.c_mlp) if self.c_mlp is not None else None
+        self.c_splat = s
+
+    def shapes(self, channels):
+        sp = self.sp
+        b, (nx, ny, nz) = sp.n_scenes, sp.res
+        if sp.kind == 0:
+            return [(b, nx, ny, nz, channels)]
+        return [(b, nx, ny, channels), (b, ny, nz, channels), (b, nz, nx, channels)]
+
+
+def _ptr3(arrs):
+    return (C.c_void_p * 3)(*[arrs[i].ctypes.data if i < len(arrs) else None for i in range(3)])
+
+
+def splat_fwd(sp):
+    """Returns (theta list, theta_w list): the normalised target structure and the weight sums."""
+    p = sp if isinstance(sp, SplatProblem) else SplatProblem(sp)
+    theta = [np.zeros(s) for s in p.shapes(p.sp.channels)]
+    theta_w = [np.zeros(s[:-1]) for s in p.shapes(1)]
+    lib = _load()
+    lib.lpo_splat_fwd.restype = C.c_int
+    rc = lib.lpo_splat_fwd(C.byref(p.c_target), C.byref(p.c_rays), C.byref(p.c_splat), _ptr3(theta), _ptr3(theta_w))
+    if rc != 0:
+        raise RuntimeError(f"lpo_splat_fwd failed with status {rc}")
+    return theta, theta_w
+
+
+def splat_bwd(sp, theta_w, d_out, kink_band: float = 0.0, kink_side: int = 0):
+    """Gradients of sum(d_out * out).  Returns (d_feats [M][n_in], d_prior list, dW list, db list)."""
+    p = sp if isinstance(sp, SplatProblem) else SplatProblem(sp)
+    theta_w = [_f64(a) for a in theta_w]
+    d_out = [_f64(a) for a in d_out]
+    d_feats = np.zeros_like(p.feats)
+    d_prior = [] if p.prior is None else [np.zeros_like(g) for g in p.prior]
+    dW = [] if p.W is None else [np.zeros_like(w) for w in p.W]
+    db = [] if p.b is None else [np.zeros_like(b) for b in p.b]
+    arr = lambda lst: (C.c_void_p * _MAX_LAYERS)(*[a.ctypes.data for a in lst])
+    lib = _load()
+    lib.lpo_splat_bwd.restype = C.c_int
+    rc = lib.lpo_splat_bwd(C.byref(p.c_target), C.byref(p.c_rays), C.byref(p.c_splat), _ptr3(theta_w), _ptr3(d_out),
+                           C.c_void_p(d_feats.ctypes.data), _ptr3(d_prior), arr(dW), arr(db),
+                           C.c_double(kink_band), C.c_int(kink_side))
+    if rc != 0:
+        raise RuntimeError(f"lpo_splat_bwd failed with status {rc}")
+    return d_feats, d_prior, dW, db

@@ -1010,3 +1010,218 @@ int lpo_dir_encode(const double d[3], int n_freq, double* enc)
     dir_encode(d, n_freq, enc);
     return 0;
 }
+
+/* ==== Splatter (Section 3.3, "Splatter"; appendix "Normalization Process in Splatter") ========
+ *
+ * The dual of the Renderer: M pixels with feature vectors v_i are expanded into rays of S
+ * points (the same placement as the Renderer's samples); every point pushes a feature vector
+ * into the hash cell that contains it, with the SAME bi/tri-linear weights the Renderer uses to
+ * read that cell, and every cell is finally divided by the sum of the weights that landed on it:
+ *     theta[corner]   += weight * vt_ij        theta_w[corner] += weight        (all i, j)
+ *     out = theta / theta_w    (0 where nothing landed)
+ * naive Splatter:  vt_ij = v_i.   With the MLP g_s (the paper's Eq. for the splatted feature):
+ *     vt_ij = g_s( [ v_i ; h_prior(x_ij) ; enc(d_i) ] )
+ * with h_prior the prior hash structure read by interpolation and enc the direction encoding
+ * (n_freq = -1: no direction input; form as for the Renderer's decoder).  g_s: ReLU hidden
+ * layers, linear output of the target's channel count.
+ *
+ * Backward, given G = dL/d(out): the weights depend on the ray geometry only, so
+ * dL/dtheta = G / theta_w (the appendix: theta_w is kept to normalise the gradients), the
+ * gradient of a splatted feature is that field READ at the point (the Renderer's forward
+ * read), and from there ordinary reverse mode through g_s: dW, db, d(prior) (scattered like
+ * the Renderer's grid gradient) and d(v_i) summed over the points of the ray.
+ */
+
+typedef struct {
+    int32_t n_in;          /* channels of the pixel features */
+    int32_t n_freq;        /* octaves of the direction encoding, -1: none */
+    const double* feats;   /* [M][n_in] */
+    const lpo_grid* prior; /* NULL: none */
+    const lpo_mlp* mlp;    /* NULL: naive Splatter (n_in == target channels) */
+} lpo_splat;
+
+static int64_t grid_elems(const lpo_grid* g, int p)
+{
+    if (g->kind == LPO_VOXEL) return p == 0 ? (int64_t)g->B * g->NX * g->NY * g->NZ : 0;
+    const int64_t n[3] = {(int64_t)g->NX * g->NY, (int64_t)g->NY * g->NZ, (int64_t)g->NZ * g->NX};
+    return (int64_t)g->B * n[p];
+}
+
+static int splat_check(const lpo_grid* tgt, const lpo_rays* rays, const lpo_splat* sp)
+{
+    if (!tgt || !rays || !sp || !sp->feats) return 1;
+    if (tgt->B < 1 || tgt->C < 1 || tgt->NX < 2 || tgt->NY < 2 || tgt->NZ < 2) return 1;
+    if (rays->M < 0 || rays->S < 1 || sp->n_in < 1 || sp->n_freq < -1) return 1;
+    const int E = sp->n_freq < 0 ? 0 : 3 + 6 * sp->n_freq;
+    const int Cp = sp->prior ? sp->prior->C : 0;
+    if (sp->prior && (sp->prior->kind != tgt->kind || sp->prior->B != tgt->B)) return 1;
+    if (!sp->mlp) return (sp->n_in != tgt->C || sp->prior || E) ? 1 : 0;
+    if (sp->mlp->n_layers < 1 || sp->mlp->n_layers > LPO_MAX_LAYERS) return 1;
+    if (sp->mlp->dims[0] != sp->n_in + Cp + E || sp->mlp->dims[sp->mlp->n_layers] != tgt->C) return 1;
+    return 0;
+}
+
+/* inputs of g_s for point x of ray i: [v_i ; h_prior(x) ; enc(d_i)] */
+static void splat_inputs(const lpo_rays* rays, const lpo_splat* sp, int64_t i, int b, const double x[3],
+                         double* in)
+{
+    int n = 0;
+    for (int k = 0; k < sp->n_in; ++k) in[n++] = sp->feats[(size_t)i * sp->n_in + k];
+    if (sp->prior) {
+        grid_gather(sp->prior, b, x, in + n);
+        n += sp->prior->C;
+    }
+    if (sp->n_freq >= 0) dir_encode(rays->dirs + 3 * i, sp->n_freq, in + n);
+}
+
+/* theta [p] and theta_w [p] are written (normalised features, weight sums); shapes of the
+   target grid with C and 1 channels. */
+int lpo_splat_fwd(const lpo_grid* tgt, const lpo_rays* rays, const lpo_splat* sp, double* const theta[3],
+                  double* const theta_w[3])
+{
+    if (splat_check(tgt, rays, sp)) return 1;
+    const int C = tgt->C, S = rays->S, np = tgt->kind == LPO_VOXEL ? 1 : 3;
+    lpo_grid wgrid = *tgt;
+    wgrid.C = 1;
+    for (int p = 0; p < np; ++p) {
+        memset(theta[p], 0, sizeof(double) * (size_t)grid_elems(tgt, p) * C);
+        memset(theta_w[p], 0, sizeof(double) * (size_t)grid_elems(tgt, p));
+    }
+    const int nact = sp->mlp ? mlp_act_total(sp->mlp) : 0;
+    int fail = 0;
+#pragma omp parallel
+    {
+        double* act = (double*)malloc(sizeof(double) * (size_t)(nact + 1));
+        double* pre = (double*)malloc(sizeof(double) * (size_t)(nact + 1));
+        if (!act || !pre) {
+#pragma omp atomic write
+            fail = 1;
+        }
+#pragma omp barrier
+        if (!fail) {
+#pragma omp for schedule(dynamic, 16)
+            for (int64_t i = 0; i < rays->M; ++i) {
+                const double* o = rays->origins + 3 * i;
+                const double* d = rays->dirs + 3 * i;
+                const double nr = rays->near[i], delta = (rays->far[i] - nr) / (double)S;
+                const int b = rays->scene ? rays->scene[i] : 0;
+                const double one = 1.0;
+                for (int j = 0; j < S; ++j) {
+                    const double t = nr + ((double)j + 0.5) * delta;
+                    const double x[3] = {o[0] + t * d[0], o[1] + t * d[1], o[2] + t * d[2]};
+                    const double* vt = sp->feats + (size_t)i * sp->n_in;
+                    if (sp->mlp) {
+                        splat_inputs(rays, sp, i, b, x, act);
+                        mlp_forward(sp->mlp, act, pre);
+                        vt = act + nact - C;
+                    }
+                    grid_scatter(tgt, theta, b, x, vt);
+                    grid_scatter(&wgrid, theta_w, b, x, &one);
+                }
+            }
+        }
+        free(act);
+        free(pre);
+    }
+    if (fail) return 2;
+    for (int p = 0; p < np; ++p) {
+        const int64_t n = grid_elems(tgt, p);
+        for (int64_t c = 0; c < n; ++c) {
+            const double w = theta_w[p][c];
+            for (int k = 0; k < C; ++k) theta[p][c * C + k] = w > 0.0 ? theta[p][c * C + k] / w : 0.0;
+        }
+    }
+    return 0;
+}
+
+/* d_feats [M][n_in] is written; d_prior, dW, db are ACCUMULATED into (d_prior may be NULL
+   without a prior, dW / db without an MLP).  band / side as in lpo_render_bwd. */
+int lpo_splat_bwd(const lpo_grid* tgt, const lpo_rays* rays, const lpo_splat* sp,
+                  const double* const theta_w[3], const double* const d_out[3], double* d_feats,
+                  double* const d_prior[3], double* const dW[], double* const db[], double band, int side)
+{
+    if (splat_check(tgt, rays, sp)) return 1;
+    if (side != 0 && !(band > 0.0)) return 1;
+    const int C = tgt->C, S = rays->S, np = tgt->kind == LPO_VOXEL ? 1 : 3;
+    /* dL/dtheta = G / theta_w as a grid that is then read by interpolation */
+    lpo_grid ggrid = *tgt;
+    double* gbuf[3] = {NULL, NULL, NULL};
+    for (int p = 0; p < np; ++p) {
+        const int64_t n = grid_elems(tgt, p);
+        gbuf[p] = (double*)malloc(sizeof(double) * (size_t)n * C);
+        if (!gbuf[p]) { for (int q = 0; q < 3; ++q) free(gbuf[q]); return 2; }
+        for (int64_t c = 0; c < n; ++c) {
+            const double w = theta_w[p][c];
+            for (int k = 0; k < C; ++k) gbuf[p][c * C + k] = w > 0.0 ? d_out[p][c * C + k] / w : 0.0;
+        }
+        ggrid.data[p] = gbuf[p];
+    }
+    const lpo_mlp* m = sp->mlp;
+    const int nact = m ? mlp_act_total(m) : 0, n_in = sp->n_in;
+    const int Cp = sp->prior ? sp->prior->C : 0;
+    memset(d_feats, 0, sizeof(double) * (size_t)rays->M * n_in);
+    int fail = 0;
+#pragma omp parallel
+    {
+        kink_tmp kt;
+        memset(&kt, 0, sizeof(kt));
+        double* act = (double*)malloc(sizeof(double) * (size_t)(nact + 1));
+        double* pre = (double*)malloc(sizeof(double) * (size_t)(nact + 1));
+        double* dact = (double*)malloc(sizeof(double) * (size_t)(nact + 1));
+        double* din = (double*)malloc(sizeof(double) * (size_t)(nact + 1));
+        double* dvt = (double*)malloc(sizeof(double) * (size_t)C);
+        double* tW[LPO_MAX_LAYERS] = {NULL};
+        double* tb[LPO_MAX_LAYERS] = {NULL};
+        int ok = act && pre && dact && din && dvt;
+        if (m) {
+            ok = kink_alloc(&kt, m, nact) && ok;
+            for (int l = 0; l < m->n_layers; ++l) {
+                tW[l] = (double*)calloc((size_t)m->dims[l] * m->dims[l + 1], sizeof(double));
+                tb[l] = (double*)calloc((size_t)m->dims[l + 1], sizeof(double));
+                ok = ok && tW[l] && tb[l];
+            }
+        }
+        if (!ok) {
+#pragma omp atomic write
+            fail = 1;
+        }
+#pragma omp barrier
+        if (!fail) {
+#pragma omp for schedule(dynamic, 16)
+            for (int64_t i = 0; i < rays->M; ++i) {
+                const double* o = rays->origins + 3 * i;
+                const double* d = rays->dirs + 3 * i;
+                const double nr = rays->near[i], delta = (rays->far[i] - nr) / (double)S;
+                const int b = rays->scene ? rays->scene[i] : 0;
+                for (int j = 0; j < S; ++j) {
+                    const double t = nr + ((double)j + 0.5) * delta;
+                    const double x[3] = {o[0] + t * d[0], o[1] + t * d[1], o[2] + t * d[2]};
+                    grid_gather(&ggrid, b, x, dvt); /* dL/d(vt_ij) */
+                    if (!m) {
+                        for (int k = 0; k < n_in; ++k) d_feats[(size_t)i * n_in + k] += dvt[k];
+                        continue;
+                    }
+                    splat_inputs(rays, sp, i, b, x, act);
+                    mlp_forward(m, act, pre);
+                    mlp_backward_choice(m, act, pre, nact, dvt, band, side, &kt, tW, tb, dact, din);
+                    for (int k = 0; k < n_in; ++k) d_feats[(size_t)i * n_in + k] += din[k];
+                    if (sp->prior) grid_scatter(sp->prior, d_prior, b, x, din + n_in);
+                }
+            }
+            if (m) {
+#pragma omp critical
+                for (int l = 0; l < m->n_layers; ++l) {
+                    const int64_t n = (int64_t)m->dims[l] * m->dims[l + 1];
+                    for (int64_t k = 0; k < n; ++k) dW[l][k] += tW[l][k];
+                    for (int k = 0; k < m->dims[l + 1]; ++k) db[l][k] += tb[l][k];
+                }
+            }
+        }
+        for (int l = 0; l < LPO_MAX_LAYERS; ++l) { free(tW[l]); free(tb[l]); }
+        free(act); free(pre); free(dact); free(din); free(dvt);
+        if (m) kink_free(&kt);
+    }
+    for (int p = 0; p < 3; ++p) free(gbuf[p]);
+    (void)Cp;
+    return fail ? 2 : 0;
+}
