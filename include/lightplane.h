@@ -193,6 +193,49 @@ lp_status lp_render_dec_bwd(const lp_grid* grid, const lp_decoder* dec, const lp
 /* 1 if the matrix-core kernels cover this grid kind / decoder shape, else 0. */
 int32_t lp_dec_has_fast_path(const lp_grid* grid, const lp_decoder* dec);
 
+/* ---- Splatter (Section 3.3 "Splatter"; appendix "Normalization Process in Splatter") ---------
+ *
+ * The dual of the Renderer: M pixels with feature vectors are expanded into rays of S points
+ * (placed like the Renderer's samples); every point pushes a feature vector into the target
+ * hash structure with the interpolation weights the Renderer reads that cell with, and each
+ * cell is finally divided by the sum of the weights that landed on it:
+ *     theta[corner] += weight * vt_ij,  theta_w[corner] += weight,  out = theta / theta_w
+ * (0 where nothing landed).  Naive Splatter (mlp == NULL, n_in == target->C): vt_ij = v_i.
+ * With the MLP g_s: vt_ij = g_s([v_i ; h_prior(x_ij) ; enc(d_i)]) with h_prior the prior
+ * structure read at the point (prior == NULL: none) and enc the direction encoding of the
+ * two-MLP decoder above (n_freq = -1: none); ReLU hidden layers, linear output;
+ * mlp->dims[0] == n_in + prior->C + (3 + 6 n_freq), mlp->dims[last] == target->C.
+ * The prior has the target's kind, scene count, box and contraction; its own resolution.
+ */
+typedef struct {
+    int32_t n_in;         /* channels of the pixel features */
+    int32_t n_freq;       /* octaves of the direction encoding fed to the MLP, -1: none */
+    const float* feats;   /* device [M][n_in] */
+    const lp_grid* prior; /* NULL: none */
+    const lp_mlp* mlp;    /* NULL: naive Splatter */
+} lp_splat;
+
+/* Forward.  target gives kind, B, C, resolution, box and contraction of the structure to
+   build (its data pointers are ignored).  theta[p] (shape of the target's tensors) and
+   theta_w[p] (same without the channel axis) are device buffers that are WRITTEN: the
+   normalised structure and the weight sums (the backward needs the latter). */
+lp_status lp_splat_fwd(const lp_grid* target, const lp_rays* rays, const lp_splat* splat,
+                       float* const theta[3], float* const theta_w[3], void* stream);
+
+/* Backward for d_theta[p] = dL/d(out) (device).  The weights depend on the ray geometry only,
+   so dL/dtheta = d_theta / theta_w; the gradient of a pushed feature is that field read at
+   the point.  d_feats [M][n_in] is WRITTEN; d_prior[p] (shapes of the prior's tensors),
+   dW[l], db[l] are ACCUMULATED into (NULL lists are allowed where there is no prior / MLP).
+   workspace: device, 256-byte aligned, lp_splat_bwd_workspace_bytes bytes. */
+lp_status lp_splat_bwd(const lp_grid* target, const lp_rays* rays, const lp_splat* splat,
+                       const float* const theta_w[3], const float* const d_theta[3], float* d_feats,
+                       float* const d_prior[3], float* const dW[LP_MAX_LAYERS],
+                       float* const db[LP_MAX_LAYERS], void* workspace, size_t workspace_bytes,
+                       void* stream);
+
+lp_status lp_splat_bwd_workspace_bytes(const lp_grid* target, const lp_rays* rays, const lp_splat* splat,
+                                       size_t* bytes);
+
 /* Message of the last failure on this thread ("" if none).  Owned by the library. */
 const char* lp_last_error(void);
 

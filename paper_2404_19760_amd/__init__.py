@@ -14,6 +14,7 @@ import dataclasses
 import os
 from typing import List, Optional, Sequence
 
+import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -46,6 +47,11 @@ class _Mlp(C.Structure):
 class _Decoder(C.Structure):
     _fields_ = [("opacity", _Mlp), ("feature", _Mlp), ("n_freq", C.c_int32), ("n_feat", C.c_int32),
                 ("feat_act", C.c_int32)]
+
+
+class _Splat(C.Structure):
+    _fields_ = [("n_in", C.c_int32), ("n_freq", C.c_int32), ("feats", C.c_void_p),
+                ("prior", C.POINTER(_Grid)), ("mlp", C.POINTER(_Mlp))]
 
 
 class _Rays(C.Structure):
@@ -91,6 +97,16 @@ def _load() -> C.CDLL:
                                       C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
                                       C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_void_p, C.c_size_t,
                                       C.c_int32, C.c_void_p]
+    lib.lp_splat_fwd.restype = C.c_int
+    lib.lp_splat_fwd.argtypes = [C.POINTER(_Grid), C.POINTER(_Rays), C.POINTER(_Splat), C.POINTER(C.c_void_p),
+                                 C.POINTER(C.c_void_p), C.c_void_p]
+    lib.lp_splat_bwd_workspace_bytes.restype = C.c_int
+    lib.lp_splat_bwd_workspace_bytes.argtypes = [C.POINTER(_Grid), C.POINTER(_Rays), C.POINTER(_Splat),
+                                                 C.POINTER(C.c_size_t)]
+    lib.lp_splat_bwd.restype = C.c_int
+    lib.lp_splat_bwd.argtypes = [C.POINTER(_Grid), C.POINTER(_Rays), C.POINTER(_Splat), C.POINTER(C.c_void_p),
+                                 C.POINTER(C.c_void_p), C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
+                                 C.POINTER(C.c_void_p), C.c_void_p, C.c_size_t, C.c_void_p]
     return lib
 
 
@@ -359,6 +375,106 @@ def lp_render_dec_bwd(grid: Grid, dec: Decoder, rays: Rays, bg, d_out: torch.Ten
                                   dg, dWs, dbs, dWv, dbv, wp, wn, int(math_mode), _stream_ptr(stream)))
 
 
+@dataclasses.dataclass
+class Splat:
+    """Arguments of the Splatter besides target and rays: pixel features [M][n_in], optional
+    prior structure (a Grid of the target's kind) and MLP, octaves of the direction encoding."""
+    feats: torch.Tensor
+    prior: Optional[Grid] = None
+    mlp: Optional[Mlp] = None
+    n_freq: int = -1
+
+    def c_struct(self):
+        """Returns (struct, keep-alive objects)."""
+        s = _Splat()
+        m, n_in = int(self.feats.shape[0]), int(self.feats.shape[1])
+        s.n_in, s.n_freq = n_in, int(self.n_freq)
+        s.feats = _dev_f32(self.feats, "feats", (m, n_in))
+        keep = []
+        if self.prior is not None:
+            g = self.prior.c_struct()
+            keep.append(g)
+            s.prior = C.pointer(g)
+        if self.mlp is not None:
+            ml = self.mlp.c_struct()
+            keep.append(ml)
+            s.mlp = C.pointer(ml)
+        return s, keep
+
+
+def target_struct(kind: int, n_scenes: int, channels: int, res, aabb_min=(-1.0, -1.0, -1.0),
+                  aabb_max=(1.0, 1.0, 1.0), contract_a: float = 0.0) -> _Grid:
+    """lp_grid describing the structure a Splatter call builds (no data pointers)."""
+    g = _Grid()
+    g.kind, g.B, g.C = int(kind), int(n_scenes), int(channels)
+    g.NX, g.NY, g.NZ = [int(v) for v in res]
+    for a in range(3):
+        g.aabb_min[a] = float(aabb_min[a])
+        g.aabb_max[a] = float(aabb_max[a])
+    g.contract_a = float(contract_a)
+    return g
+
+
+def _target_shapes(t: _Grid, channels: Optional[int]):
+    b, nx, ny, nz = t.B, t.NX, t.NY, t.NZ
+    c = () if channels is None else (channels,)
+    if t.kind == LP_GRID_VOXEL:
+        return [(b, nx, ny, nz) + c]
+    return [(b, nx, ny) + c, (b, ny, nz) + c, (b, nz, nx) + c]
+
+
+def _ptr3(tensors, shapes, name):
+    if len(tensors) != len(shapes):
+        raise ValueError(f"{name} needs {len(shapes)} tensors")
+    return (C.c_void_p * 3)(*[_dev_f32(tensors[p], f"{name}[{p}]", shapes[p]) if p < len(shapes) else None
+                              for p in range(3)])
+
+
+def lp_splat_fwd(target: _Grid, rays: Rays, splat: Splat, theta: List[torch.Tensor],
+                 theta_w: List[torch.Tensor], stream=None) -> None:
+    """Enqueue the Splatter forward: theta (shapes of the target's tensors) and theta_w (same
+    without the channel axis) are written."""
+    r = rays.c_struct()
+    s, keep = splat.c_struct()
+    _check(_lib.lp_splat_fwd(C.byref(target), C.byref(r), C.byref(s),
+                             _ptr3(theta, _target_shapes(target, target.C), "theta"),
+                             _ptr3(theta_w, _target_shapes(target, None), "theta_w"), _stream_ptr(stream)))
+    del keep
+
+
+def lp_splat_bwd_workspace_bytes(target: _Grid, rays: Rays, splat: Splat) -> int:
+    r = rays.c_struct()
+    s, keep = splat.c_struct()
+    n = C.c_size_t(0)
+    _check(_lib.lp_splat_bwd_workspace_bytes(C.byref(target), C.byref(r), C.byref(s), C.byref(n)))
+    del keep
+    return int(n.value)
+
+
+def lp_splat_bwd(target: _Grid, rays: Rays, splat: Splat, theta_w: List[torch.Tensor],
+                 d_theta: List[torch.Tensor], d_feats: torch.Tensor, d_prior: Optional[List[torch.Tensor]],
+                 dW: Optional[List[torch.Tensor]], db: Optional[List[torch.Tensor]], workspace: torch.Tensor,
+                 stream=None) -> None:
+    """Enqueue the Splatter backward: d_feats is written; d_prior, dW, db are accumulated into."""
+    r = rays.c_struct()
+    s, keep = splat.c_struct()
+    m, n_in = int(splat.feats.shape[0]), int(splat.feats.shape[1])
+    dp = (C.c_void_p * 3)()
+    if splat.prior is not None:
+        dp = _ptr3(d_prior, splat.prior.shapes(), "d_prior")
+    dWp, dbp = (C.c_void_p * LP_MAX_LAYERS)(), (C.c_void_p * LP_MAX_LAYERS)()
+    if splat.mlp is not None:
+        dims = splat.mlp.dims
+        dWp = (C.c_void_p * LP_MAX_LAYERS)(*[_dev_f32(w, f"dW[{l}]", (dims[l + 1], dims[l])) for l, w in enumerate(dW)])
+        dbp = (C.c_void_p * LP_MAX_LAYERS)(*[_dev_f32(b, f"db[{l}]", (dims[l + 1],)) for l, b in enumerate(db)])
+    wp, wn = _workspace(workspace)
+    _check(_lib.lp_splat_bwd(C.byref(target), C.byref(r), C.byref(s),
+                             _ptr3(theta_w, _target_shapes(target, None), "theta_w"),
+                             _ptr3(d_theta, _target_shapes(target, target.C), "d_theta"),
+                             _dev_f32(d_feats, "d_feats", (m, n_in)), dp, dWp, dbp, wp, wn, _stream_ptr(stream)))
+    del keep
+
+
 # ---------------------------------------------------------------------------------------
 # Conveniences on top of the entry points: move host buffers to the GPU, allocate outputs.
 
@@ -436,3 +552,40 @@ def render_bwd(grid: Grid, mlp: Mlp, rays: Rays, bg, d_rgb, ray_cache, d_alpha=N
         workspace = torch.empty(lp_bwd_workspace_bytes(grid, mlp, rays, math_mode), dtype=torch.uint8, device=dev)
     lp_render_bwd(grid, mlp, rays, bg, d_rgb, d_alpha, d_depth, ray_cache, d_grid, dW, db, workspace, math_mode)
     return d_grid, dW, db
+
+
+def splat_to_device(sp, device="cuda:0"):
+    """Upload host buffers with the fields of `lp_inputs.SplatInputs`.  Returns (target, Rays, Splat)."""
+    dev = torch.device(device)
+    up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    target = target_struct(sp.kind, sp.n_scenes, sp.channels, sp.res, sp.aabb_min, sp.aabb_max, sp.contract_a)
+    rays = Rays(origins=up(sp.origins), dirs=up(sp.dirs), near=up(sp.near), far=up(sp.far),
+                samples=int(sp.samples), scene=None if sp.scene is None else up(sp.scene))
+    prior = None
+    if sp.prior is not None:
+        prior = Grid(kind=int(sp.kind), data=[up(g) for g in sp.prior], res=tuple(sp.prior_res),
+                     aabb_min=tuple(sp.aabb_min), aabb_max=tuple(sp.aabb_max), contract_a=float(sp.contract_a))
+    mlp = None if sp.mlp_dims is None else Mlp([up(w) for w in sp.weights], [up(b) for b in sp.biases])
+    return target, rays, Splat(feats=up(sp.feats), prior=prior, mlp=mlp, n_freq=int(sp.n_freq))
+
+
+def splat_fwd(target: _Grid, rays: Rays, splat: Splat):
+    """Allocate outputs and run lp_splat_fwd.  Returns (theta list, theta_w list)."""
+    dev = rays.origins.device
+    theta = [torch.empty(s, dtype=torch.float32, device=dev) for s in _target_shapes(target, target.C)]
+    theta_w = [torch.empty(s, dtype=torch.float32, device=dev) for s in _target_shapes(target, None)]
+    lp_splat_fwd(target, rays, splat, theta, theta_w)
+    return theta, theta_w
+
+
+def splat_bwd(target: _Grid, rays: Rays, splat: Splat, theta_w, d_theta):
+    """Allocate gradient buffers and workspace and run lp_splat_bwd.
+    Returns (d_feats, d_prior list, dW list, db list)."""
+    dev = rays.origins.device
+    d_feats = torch.empty_like(splat.feats)
+    d_prior = [] if splat.prior is None else [torch.zeros_like(t) for t in splat.prior.data]
+    dW = [] if splat.mlp is None else [torch.zeros_like(w) for w in splat.mlp.weights]
+    db = [] if splat.mlp is None else [torch.zeros_like(b) for b in splat.mlp.biases]
+    ws = torch.empty(lp_splat_bwd_workspace_bytes(target, rays, splat), dtype=torch.uint8, device=dev)
+    lp_splat_bwd(target, rays, splat, theta_w, d_theta, d_feats, d_prior, dW, db, ws)
+    return d_feats, d_prior, dW, db

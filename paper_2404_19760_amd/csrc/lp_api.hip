@@ -281,6 +281,99 @@ lp_status decoder_views(const lp_grid* grid, const lp_decoder* dec, const lp_ray
 
 size_t align256(size_t n) { return (n + 255) / 256 * 256; }
 
+// ---- Splatter ---------------------------------------------------------------------------
+
+long long plane_cells(const lp_grid* g, int p)
+{
+    if (g->kind == LP_GRID_VOXEL) return (long long)g->B * g->NX * g->NY * g->NZ;
+    const long long n[3] = {(long long)g->NX * g->NY, (long long)g->NY * g->NZ, (long long)g->NZ * g->NX};
+    return (long long)g->B * n[p];
+}
+
+// Validates the arguments of a Splatter call and builds the device views.
+lp_status splat_views(const lp_grid* target, const lp_rays* rays, const lp_splat* sp, lp::GridDev* g,
+                      lp::MlpDev* m, lp::RaysDev* r, lp::SplatDev* sd)
+{
+    if (!sp) return fail(LP_ERR_INVALID_ARG, "splat must not be NULL");
+    lp_mlp stand_in;
+    std::memset(&stand_in, 0, sizeof(stand_in));
+    stand_in.n_layers = 1;
+    stand_in.dims[0] = target ? target->C : 1;
+    stand_in.dims[1] = 4;
+    static const float dummy = 0.0f;
+    stand_in.W[0] = &dummy; stand_in.b[0] = &dummy;
+    lp_grid tgt_checked;
+    if (target) {   // the target's data pointers are not used: give the validator something non-NULL
+        tgt_checked = *target;
+        for (int p = 0; p < 3; ++p) tgt_checked.data[p] = &dummy;
+    }
+    lp_status st = validate(target ? &tgt_checked : nullptr, &stand_in, rays);
+    if (st != LP_OK) return st;
+    if (sp->n_in < 1) return fail(LP_ERR_INVALID_ARG, "splat->n_in must be >= 1");
+    if (rays->M > 0 && !sp->feats) return fail(LP_ERR_INVALID_ARG, "splat->feats must not be NULL");
+    if (sp->n_freq < -1 || sp->n_freq > 4) return fail(LP_ERR_INVALID_ARG, "splat->n_freq must be in [-1, 4]");
+    const int E = sp->n_freq < 0 ? 0 : 3 + 6 * sp->n_freq;
+    lp_mlp none;
+    std::memset(&none, 0, sizeof(none));
+    none.n_layers = 1; none.dims[0] = target->C; none.dims[1] = 4;
+    to_device_views(&tgt_checked, &none, rays, g, m, r);
+    for (int p = 0; p < 3; ++p) g->data[p] = nullptr;
+    std::memset(sd, 0, sizeof(*sd));
+    sd->n_in = sp->n_in;
+    sd->feats = sp->feats;
+    int Cp = 0;
+    if (sp->prior) {
+        if (!sp->mlp) return fail(LP_ERR_INVALID_ARG, "a prior structure needs the MLP that consumes it");
+        if (sp->prior->kind != target->kind || sp->prior->B != target->B)
+            return fail(LP_ERR_INVALID_ARG, "splat->prior must have the target's kind and scene count");
+        lp_mlp pm = none;
+        pm.dims[0] = sp->prior->C;
+        lp_mlp stand_p = stand_in;
+        stand_p.dims[0] = sp->prior->C;
+        st = validate(sp->prior, &stand_p, rays);
+        if (st != LP_OK) return st;
+        lp::MlpDev tmp; lp::RaysDev tr;
+        to_device_views(sp->prior, &pm, rays, &sd->prior, &tmp, &tr);
+        sd->has_prior = 1;
+        Cp = sp->prior->C;
+    }
+    std::memset(m, 0, sizeof(*m));
+    if (!sp->mlp) {
+        if (sp->n_in != target->C) return fail(LP_ERR_INVALID_ARG, "the naive Splatter needs splat->n_in == target->C");
+        if (E) return fail(LP_ERR_INVALID_ARG, "a direction encoding needs the MLP that consumes it");
+        m->n_layers = 0;
+        m->dims[0] = target->C;
+        m->max_width = target->C;
+        m->act_total = target->C;
+        return LP_OK;
+    }
+    const lp_mlp* mlp = sp->mlp;
+    if (mlp->n_layers < 1 || mlp->n_layers > LP_MAX_LAYERS)
+        return fail(LP_ERR_INVALID_ARG, "splat->mlp->n_layers must be in [1, LP_MAX_LAYERS]");
+    for (int l = 0; l <= mlp->n_layers; ++l)
+        if (mlp->dims[l] < 1) return fail(LP_ERR_INVALID_ARG, "splat->mlp->dims entries must be >= 1");
+    for (int l = 0; l < mlp->n_layers; ++l)
+        if (!mlp->W[l] || !mlp->b[l]) return fail(LP_ERR_INVALID_ARG, "splat->mlp W / b has a NULL layer");
+    if (mlp->dims[0] != sp->n_in + Cp + E || mlp->dims[mlp->n_layers] != target->C)
+        return fail(LP_ERR_INVALID_ARG, "splat->mlp must map n_in + prior->C + (3 + 6 n_freq) inputs to target->C outputs");
+    m->n_layers = mlp->n_layers;
+    int off = 0, maxw = 0, act = 0;
+    for (int l = 0; l <= mlp->n_layers; ++l) {
+        m->dims[l] = mlp->dims[l];
+        maxw = mlp->dims[l] > maxw ? mlp->dims[l] : maxw;
+        act += mlp->dims[l];
+    }
+    for (int l = 0; l < mlp->n_layers; ++l) {
+        m->W[l] = mlp->W[l];
+        m->b[l] = mlp->b[l];
+        m->w_off[l] = off; off += mlp->dims[l] * mlp->dims[l + 1];
+        m->b_off[l] = off; off += mlp->dims[l + 1];
+    }
+    m->param_total = off; m->max_width = maxw; m->act_total = act;
+    m->n_freq = sp->n_freq < 0 ? 0 : sp->n_freq; m->n_enc = E; m->n_feat = target->C; m->feat_act = 1;
+    return LP_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -520,6 +613,134 @@ lp_status lp_render_dec_bwd(const lp_grid* grid, const lp_decoder* dec, const lp
     if (st != LP_OK) return st;
     e = lp::launch_dec_unpack(d, m, grads, s);
     if (e != hipSuccess) return hip_fail("decoder gradient hand-back kernel launch", e);
+    return LP_OK;
+}
+
+lp_status lp_splat_fwd(const lp_grid* target, const lp_rays* rays, const lp_splat* splat,
+                       float* const theta[3], float* const theta_w[3], void* stream)
+{
+    lp::GridDev g; lp::MlpDev m; lp::RaysDev r; lp::SplatDev sd;
+    lp_status st = splat_views(target, rays, splat, &g, &m, &r, &sd);
+    if (st != LP_OK) return st;
+    if (!theta || !theta_w) return fail(LP_ERR_INVALID_ARG, "theta and theta_w must not be NULL");
+    const int n_planes = target->kind == LP_GRID_VOXEL ? 1 : 3;
+    for (int p = 0; p < n_planes; ++p) {
+        if (!theta[p] || !theta_w[p]) return fail(LP_ERR_INVALID_ARG, "theta / theta_w has a NULL tensor");
+        sd.theta[p] = theta[p];
+        sd.theta_w[p] = theta_w[p];
+    }
+    hipStream_t s = (hipStream_t)stream;
+    const int threads = 256;
+    for (int p = 0; p < n_planes; ++p) {
+        const long long cells = plane_cells(target, p);
+        hipLaunchKernelGGL(lp::fill_zero_kernel, dim3((unsigned)((cells * target->C + threads - 1) / threads)),
+                           dim3(threads), 0, s, theta[p], cells * target->C);
+        hipLaunchKernelGGL(lp::fill_zero_kernel, dim3((unsigned)((cells + threads - 1) / threads)), dim3(threads), 0,
+                           s, theta_w[p], cells);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail("Splatter clear kernels", e);
+    if (rays->M > 0) {
+        const size_t lds = sizeof(float) * ((size_t)m.param_total + (size_t)m.act_total * kGenericLanes);
+        if (lds > kMaxLds) return fail(LP_ERR_UNSUPPORTED, "MLP too large for the Splatter kernel's LDS budget");
+        e = hipFuncSetAttribute((const void*)lp::splat_fwd_generic_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds);
+        if (e != hipSuccess) return hip_fail("hipFuncSetAttribute(splat_fwd_generic_kernel)", e);
+        const long long blocks = (rays->M + kGenericLanes - 1) / kGenericLanes;
+        if (blocks > 0x7fffffffLL) return fail(LP_ERR_UNSUPPORTED, "too many rays for one launch");
+        hipLaunchKernelGGL(lp::splat_fwd_generic_kernel, dim3((unsigned)blocks), dim3(kGenericLanes), lds, s, g, m, r,
+                           sd);
+        e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail("Splatter forward kernel launch", e);
+    }
+    for (int p = 0; p < n_planes; ++p) {
+        const long long cells = plane_cells(target, p);
+        hipLaunchKernelGGL(lp::splat_normalise_kernel, dim3((unsigned)((cells + threads - 1) / threads)), dim3(threads),
+                           0, s, theta[p], theta_w[p], cells, target->C);
+    }
+    e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail("Splatter normalisation kernel launch", e);
+    return LP_OK;
+}
+
+lp_status lp_splat_bwd_workspace_bytes(const lp_grid* target, const lp_rays* rays, const lp_splat* splat,
+                                       size_t* bytes)
+{
+    if (!bytes) return fail(LP_ERR_INVALID_ARG, "bytes must not be NULL");
+    lp::GridDev g; lp::MlpDev m; lp::RaysDev r; lp::SplatDev sd;
+    lp_status st = splat_views(target, rays, splat, &g, &m, &r, &sd);
+    if (st != LP_OK) return st;
+    std::string err;
+    int n_cu = 0;
+    if (compute_units(&n_cu, &err)) return fail(LP_ERR_HIP, err);
+    *bytes = align256(sizeof(float) * (size_t)generic_bwd_blocks(n_cu) * (size_t)ws_stride(m)) + 256;
+    return LP_OK;
+}
+
+lp_status lp_splat_bwd(const lp_grid* target, const lp_rays* rays, const lp_splat* splat,
+                       const float* const theta_w[3], const float* const d_theta[3], float* d_feats,
+                       float* const d_prior[3], float* const dW[LP_MAX_LAYERS],
+                       float* const db[LP_MAX_LAYERS], void* workspace, size_t workspace_bytes,
+                       void* stream)
+{
+    size_t need = 0;
+    lp_status st = lp_splat_bwd_workspace_bytes(target, rays, splat, &need);
+    if (st != LP_OK) return st;
+    lp::GridDev g; lp::MlpDev m; lp::RaysDev r; lp::SplatDev sd;
+    st = splat_views(target, rays, splat, &g, &m, &r, &sd);
+    if (st != LP_OK) return st;
+    if (!theta_w || !d_theta) return fail(LP_ERR_INVALID_ARG, "theta_w and d_theta must not be NULL");
+    if (rays->M > 0 && !d_feats) return fail(LP_ERR_INVALID_ARG, "d_feats must not be NULL");
+    const int n_planes = target->kind == LP_GRID_VOXEL ? 1 : 3;
+    lp::BwdIo io;
+    std::memset(&io, 0, sizeof(io));
+    for (int p = 0; p < n_planes; ++p) {
+        if (!theta_w[p] || !d_theta[p]) return fail(LP_ERR_INVALID_ARG, "theta_w / d_theta has a NULL tensor");
+        sd.theta_w_in[p] = theta_w[p];
+        sd.d_theta[p] = d_theta[p];
+        if (sd.has_prior) {
+            if (!d_prior || !d_prior[p]) return fail(LP_ERR_INVALID_ARG, "d_prior has a NULL tensor");
+            io.d_grid[p] = d_prior[p];
+        }
+    }
+    for (int l = 0; l < m.n_layers; ++l) {
+        if (!dW || !db || !dW[l] || !db[l]) return fail(LP_ERR_INVALID_ARG, "dW / db has a NULL layer");
+        io.dW[l] = dW[l];
+        io.db[l] = db[l];
+    }
+    sd.d_feats = d_feats;
+    if (rays->M == 0) return LP_OK;
+    if (!workspace || workspace_bytes < need)
+        return fail(LP_ERR_WORKSPACE, "workspace is NULL or smaller than lp_splat_bwd_workspace_bytes()");
+    if (((uintptr_t)workspace & 255u) != 0) return fail(LP_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+    io.ws = (float*)workspace;
+    io.ws_stride = ws_stride(m);
+    hipStream_t s = (hipStream_t)stream;
+    std::string err;
+    int n_cu = 0;
+    if (compute_units(&n_cu, &err)) return fail(LP_ERR_HIP, err);
+    const size_t lds = sizeof(float) * (2 * (size_t)m.param_total +
+                                        ((size_t)m.act_total + 2 * (size_t)m.max_width + sd.n_in) * kGenericLanes);
+    if (lds > kMaxLds) return fail(LP_ERR_UNSUPPORTED, "MLP too large for the Splatter backward kernel's LDS budget");
+    hipError_t e = hipFuncSetAttribute((const void*)lp::splat_bwd_generic_kernel,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return hip_fail("hipFuncSetAttribute(splat_bwd_generic_kernel)", e);
+    const int max_records = generic_bwd_blocks(n_cu);
+    const long long n_tiles = (rays->M + kGenericLanes - 1) / kGenericLanes;
+    const long long blocks = n_tiles < max_records ? n_tiles : max_records;
+    const long long tiles_per_block = (n_tiles + blocks - 1) / blocks;
+    if (tiles_per_block > 0x7fffffffLL) return fail(LP_ERR_UNSUPPORTED, "too many rays for one launch");
+    hipLaunchKernelGGL(lp::splat_bwd_generic_kernel, dim3((unsigned)blocks), dim3(kGenericLanes), lds, s, g, m, r, sd,
+                       io, (int)tiles_per_block);
+    e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail("Splatter backward kernel launch", e);
+    if (m.param_total > 0) {
+        const int threads = 256;
+        hipLaunchKernelGGL(lp::reduce_params_kernel, dim3((m.param_total + threads - 1) / threads), dim3(threads), 0,
+                           s, m, io, (int)blocks);
+        e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail("parameter-gradient reduction launch", e);
+    }
     return LP_OK;
 }
 

@@ -67,6 +67,20 @@ struct BwdIo {
     int ws_stride;     // floats between consecutive partial-sum records
 };
 
+// Splatter arguments (Section 3.3 "Splatter"): pixel features, optional prior structure, the
+// accumulators of the forward, the inputs and outputs of the backward.
+struct SplatDev {
+    int n_in;               // channels of the pixel features
+    int has_prior;
+    const float* feats;     // [M][n_in]
+    GridDev prior;          // valid when has_prior
+    float* theta[3];        // forward: target accumulators, then the normalised result
+    float* theta_w[3];      // forward: weight sums
+    const float* d_theta[3];     // backward: gradient of the normalised result
+    const float* theta_w_in[3];  // backward: weight sums of the forward
+    float* d_feats;         // backward: [M][n_in], written
+};
+
 // Continuous index along one axis, clamped to the box; cell index in [0, N-2] and the
 // fraction inside the cell in [0, 1].  The index is formed in fp64 (full rate on this chip):
 // in fp32 an index of a few hundred has a spacing of 1e-5 and more, which would put a relative

@@ -154,6 +154,46 @@ __device__ __forceinline__ RayRegs load_ray(const RaysDev& r, long long ray)
     return q;
 }
 
+// Reverse of mlp_forward for the 64 columns of a tile.  dz holds dL/d(output) of the last layer
+// (rows [0, dims[n_layers])), dz_next is scratch of the same size (max_width rows).  Adds the
+// weight / bias gradients of the tile into sdW and returns the buffer that holds dL/d(input)
+// (rows [0, dims[0])).  Every lane of the block must call it (it synchronises).
+__device__ float* mlp_backward(const MlpDev& m, const float* sW, float* sdW, const float* acts, float* dz,
+                               float* dz_next, int lane)
+{
+    int off_out = m.act_total - m.dims[m.n_layers];
+    for (int l = m.n_layers - 1; l >= 0; --l) {
+        const int nin = m.dims[l], nout = m.dims[l + 1];
+        const int off_in = off_out - nin;
+        const float* W = sW + m.w_off[l];
+        __syncthreads();
+        // weight and bias gradients: each lane owns a strided set of weights and sums
+        // the outer product over the 64 rays of the tile
+        for (int idx = lane; idx < nin * nout; idx += kLanes) {
+            const int o = idx / nin, k = idx - o * nin;
+            float s = 0.0f;
+            for (int r = 0; r < kLanes; ++r) s += dz[o * kLanes + r] * acts[(off_in + k) * kLanes + r];
+            sdW[m.w_off[l] + idx] += s;
+        }
+        for (int o = lane; o < nout; o += kLanes) {
+            float s = 0.0f;
+            for (int r = 0; r < kLanes; ++r) s += dz[o * kLanes + r];
+            sdW[m.b_off[l] + o] += s;
+        }
+        // input gradient of the lane's own column, through the ReLU of the layer below
+        for (int k = 0; k < nin; ++k) {
+            float s = 0.0f;
+            for (int o = 0; o < nout; ++o) s += W[o * nin + k] * dz[o * kLanes + lane];
+            if (l > 0 && !(acts[(off_in + k) * kLanes + lane] > 0.0f)) s = 0.0f;
+            dz_next[k * kLanes + lane] = s;
+        }
+        __syncthreads();
+        float* tmp = dz; dz = dz_next; dz_next = tmp;
+        off_out = off_in;
+    }
+    return dz;
+}
+
 // Inputs of the MLP beyond the grid channels: the encoded view direction of the lane's ray
 // (constant along the ray), then zero padding up to dims[0].
 __device__ void set_direction_inputs(const GridDev& g, const MlpDev& m, const RayRegs& q, float* acts, int lane)
@@ -167,6 +207,183 @@ __device__ __forceinline__ float feature_act(const MlpDev& m, float z)
 {
     return m.feat_act == 0 ? logistic_f(z) : z;
 }
+
+// ---- Splatter (Section 3.3 "Splatter"; appendix "Normalization Process in Splatter") ----------
+// One lane per pixel / ray, like the generic Renderer kernels.  Forward: every point of the ray
+// pushes its feature vector (the pixel's, or the MLP's output for [pixel feature ; prior
+// structure read at the point ; direction encoding]) into the target structure with the
+// Renderer's interpolation weights, and the weight itself into a one-channel structure; a
+// second kernel divides.  Backward: the gradient of a pushed feature is the normalised output
+// gradient READ at the point; from there through the MLP as in the Renderer's backward.
+
+// d_w[corner] += weight   (one channel, same cells and weights as scatter_feat)
+__device__ void scatter_weight(const GridDev& g, float* const d_w[3], int scene, const Cell& c)
+{
+    if (g.kind == LP_GRID_VOXEL) {
+        float* V = d_w[0] + (size_t)scene * g.N[0] * g.N[1] * g.N[2];
+        for (int d = 0; d < 8; ++d) {
+            const int dx = d >> 2, dy = (d >> 1) & 1, dz = d & 1;
+            const float w = (dx ? c.f[0] : 1.0f - c.f[0]) * (dy ? c.f[1] : 1.0f - c.f[1]) *
+                            (dz ? c.f[2] : 1.0f - c.f[2]);
+            atomicAdd(V + ((size_t)(c.i[0] + dx) * g.N[1] + (c.i[1] + dy)) * g.N[2] + (c.i[2] + dz), w);
+        }
+    } else {
+        for (int p = 0; p < 3; ++p) {
+            const int a = p, b = (p + 1) % 3;
+            float* P = d_w[p] + (size_t)scene * g.N[a] * g.N[b];
+            for (int d = 0; d < 4; ++d) {
+                const int da = d >> 1, db = d & 1;
+                const float w = (da ? c.f[a] : 1.0f - c.f[a]) * (db ? c.f[b] : 1.0f - c.f[b]);
+                atomicAdd(P + (size_t)(c.i[a] + da) * g.N[b] + (c.i[b] + db), w);
+            }
+        }
+    }
+}
+
+// feat[k*64 + lane] = sum_corners weight * G[corner][k] / W[corner]   (0 where W == 0), k < C:
+// the normalised output gradient read at the point
+__device__ void gather_normalised(const GridDev& g, const float* const G[3], const float* const Wt[3], int scene,
+                                  const Cell& c, float* feat, int lane)
+{
+    const int C = g.C;
+    for (int k = 0; k < C; ++k) feat[k * kLanes + lane] = 0.0f;
+    if (g.kind == LP_GRID_VOXEL) {
+        const size_t cells = (size_t)scene * g.N[0] * g.N[1] * g.N[2];
+        for (int d = 0; d < 8; ++d) {
+            const int dx = d >> 2, dy = (d >> 1) & 1, dz = d & 1;
+            const float w = (dx ? c.f[0] : 1.0f - c.f[0]) * (dy ? c.f[1] : 1.0f - c.f[1]) *
+                            (dz ? c.f[2] : 1.0f - c.f[2]);
+            const size_t cell = cells + ((size_t)(c.i[0] + dx) * g.N[1] + (c.i[1] + dy)) * g.N[2] + (c.i[2] + dz);
+            const float ws = Wt[0][cell];
+            const float s = ws > 0.0f ? w / ws : 0.0f;
+            for (int k = 0; k < C; ++k) feat[k * kLanes + lane] += s * G[0][cell * C + k];
+        }
+    } else {
+        for (int p = 0; p < 3; ++p) {
+            const int a = p, b = (p + 1) % 3;
+            const size_t cells = (size_t)scene * g.N[a] * g.N[b];
+            for (int d = 0; d < 4; ++d) {
+                const int da = d >> 1, db = d & 1;
+                const float w = (da ? c.f[a] : 1.0f - c.f[a]) * (db ? c.f[b] : 1.0f - c.f[b]);
+                const size_t cell = cells + (size_t)(c.i[a] + da) * g.N[b] + (c.i[b] + db);
+                const float ws = Wt[p][cell];
+                const float s = ws > 0.0f ? w / ws : 0.0f;
+                for (int k = 0; k < C; ++k) feat[k * kLanes + lane] += s * G[p][cell * C + k];
+            }
+        }
+    }
+}
+
+// per-ray inputs of the Splatter's MLP: the pixel feature (columns [0, n_in)) and the direction
+// encoding (columns after the prior's channels)
+__device__ void set_splat_ray_inputs(const SplatDev& sp, const MlpDev& m, const RayRegs& q, long long ray,
+                                     float* acts, int lane)
+{
+    for (int k = 0; k < sp.n_in; ++k) acts[k * kLanes + lane] = sp.feats[(size_t)ray * sp.n_in + k];
+    const int e0 = sp.n_in + (sp.has_prior ? sp.prior.C : 0);
+    for (int e = 0; e < m.n_enc; ++e) acts[(e0 + e) * kLanes + lane] = dir_encoding(q.d, e);
+}
+
+}  // namespace
+
+__global__ __launch_bounds__(kLanes) void splat_fwd_generic_kernel(GridDev tgt, MlpDev m, RaysDev rays, SplatDev sp)
+{
+    extern __shared__ float smem[];
+    float* sW = smem;
+    float* acts = smem + m.param_total;
+    stage_params(m, sW);
+    __syncthreads();
+    const int lane = threadIdx.x;
+    const long long ray_raw = (long long)blockIdx.x * kLanes + lane;
+    const bool live = ray_raw < rays.M;
+    const long long ray = live ? ray_raw : rays.M - 1;
+    const RayRegs q = load_ray(rays, ray);
+    const int out_off = m.act_total - tgt.C;
+    set_splat_ray_inputs(sp, m, q, ray, acts, lane);
+    for (int j = 0; j < rays.S; ++j) {
+        const Cell c = sample_cell(tgt, q, j);
+        if (m.n_layers > 0) {
+            if (sp.has_prior) gather_feat(sp.prior, q.scene, sample_cell(sp.prior, q, j), acts + sp.n_in * kLanes, lane);
+            mlp_forward(m, sW, acts, lane);
+        }
+        if (live) {
+            scatter_feat(tgt, sp.theta, q.scene, c, acts + out_off * kLanes, lane);
+            scatter_weight(tgt, sp.theta_w, q.scene, c);
+        }
+    }
+}
+
+// theta[cell][k] /= theta_w[cell] (0 where nothing landed); one thread per cell
+__global__ void splat_normalise_kernel(float* theta, const float* theta_w, long long cells, int C)
+{
+    const long long c = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= cells) return;
+    const float w = theta_w[c];
+    const float s = w > 0.0f ? 1.0f / w : 0.0f;
+    for (int k = 0; k < C; ++k) theta[c * C + k] = w > 0.0f ? theta[c * C + k] * s : 0.0f;
+}
+
+__global__ void fill_zero_kernel(float* p, long long n)
+{
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0.0f;
+}
+
+// LDS: params | dparams accumulators | acts (act_total columns) | dz (2 * max_width columns) |
+// pixel-feature gradients (n_in columns)
+__global__ __launch_bounds__(kLanes) void splat_bwd_generic_kernel(GridDev tgt, MlpDev m, RaysDev rays, SplatDev sp,
+                                                                   BwdIo io, int tiles_per_block)
+{
+    extern __shared__ float smem[];
+    float* sW = smem;
+    float* sdW = sW + m.param_total;
+    float* acts = sdW + m.param_total;
+    float* dz0 = acts + m.act_total * kLanes;
+    float* dz1 = dz0 + m.max_width * kLanes;
+    stage_params(m, sW);
+    for (int i = threadIdx.x; i < m.param_total; i += blockDim.x) sdW[i] = 0.0f;
+    __syncthreads();
+    const int lane = threadIdx.x;
+    const long long n_tiles = (rays.M + kLanes - 1) / kLanes;
+
+    for (int it = 0; it < tiles_per_block; ++it) {
+        const long long tile = (long long)blockIdx.x * tiles_per_block + it;
+        if (tile >= n_tiles) break;  // uniform over the block
+        const long long ray_raw = tile * kLanes + lane;
+        const bool live = ray_raw < rays.M;
+        const long long ray = live ? ray_raw : rays.M - 1;
+        const RayRegs q = load_ray(rays, ray);
+        set_splat_ray_inputs(sp, m, q, ray, acts, lane);
+        // gradient of the pixel feature, summed over the points of the ray: n_in columns after dz1
+        float* dfe = dz1 + m.max_width * kLanes;
+        for (int k = 0; k < sp.n_in; ++k) dfe[k * kLanes + lane] = 0.0f;
+        for (int j = 0; j < rays.S; ++j) {
+            const Cell c = sample_cell(tgt, q, j);
+            float* dz = dz0;
+            gather_normalised(tgt, sp.d_theta, sp.theta_w_in, q.scene, c, dz, lane);
+            if (!live)
+                for (int k = 0; k < tgt.C; ++k) dz[k * kLanes + lane] = 0.0f;
+            if (m.n_layers > 0) {
+                Cell cp = c;
+                if (sp.has_prior) {
+                    cp = sample_cell(sp.prior, q, j);
+                    gather_feat(sp.prior, q.scene, cp, acts + sp.n_in * kLanes, lane);
+                }
+                mlp_forward(m, sW, acts, lane);
+                dz = mlp_backward(m, sW, sdW, acts, dz, dz1, lane);
+                if (live && sp.has_prior) scatter_feat(sp.prior, io.d_grid, q.scene, cp, dz + sp.n_in * kLanes, lane);
+            }
+            for (int k = 0; k < sp.n_in; ++k) dfe[k * kLanes + lane] += dz[k * kLanes + lane];
+        }
+        if (live)
+            for (int k = 0; k < sp.n_in; ++k) sp.d_feats[(size_t)ray * sp.n_in + k] = dfe[k * kLanes + lane];
+    }
+    __syncthreads();
+    float* rec = io.ws + (size_t)blockIdx.x * io.ws_stride;
+    for (int i = threadIdx.x; i < m.param_total; i += blockDim.x) rec[i] = sdW[i];
+}
+
+namespace {
 
 }  // namespace
 
@@ -289,38 +506,7 @@ __global__ __launch_bounds__(kLanes) void bwd_generic_kernel(GridDev g, MlpDev m
                 dz[(1 + ch) * kLanes + lane] = live ? w * pcol[ch * kLanes + lane] * df : 0.0f;
             }
 
-            // layers in reverse: dz holds dL/d(pre-activation) of layer l's outputs
-            int off_out = out_off;
-            for (int l = m.n_layers - 1; l >= 0; --l) {
-                const int nin = m.dims[l], nout = m.dims[l + 1];
-                const int off_in = off_out - nin;
-                const float* W = sW + m.w_off[l];
-                __syncthreads();
-                // weight and bias gradients: each lane owns a strided set of weights and sums
-                // the outer product over the 64 rays of the tile
-                for (int idx = lane; idx < nin * nout; idx += kLanes) {
-                    const int o = idx / nin, k = idx - o * nin;
-                    float s = 0.0f;
-                    for (int r = 0; r < kLanes; ++r)
-                        s += dz[o * kLanes + r] * acts[(off_in + k) * kLanes + r];
-                    sdW[m.w_off[l] + idx] += s;
-                }
-                for (int o = lane; o < nout; o += kLanes) {
-                    float s = 0.0f;
-                    for (int r = 0; r < kLanes; ++r) s += dz[o * kLanes + r];
-                    sdW[m.b_off[l] + o] += s;
-                }
-                // input gradient of the lane's own column, through the ReLU of the layer below
-                for (int k = 0; k < nin; ++k) {
-                    float s = 0.0f;
-                    for (int o = 0; o < nout; ++o) s += W[o * nin + k] * dz[o * kLanes + lane];
-                    if (l > 0 && !(acts[(off_in + k) * kLanes + lane] > 0.0f)) s = 0.0f;
-                    dz_next[k * kLanes + lane] = s;
-                }
-                __syncthreads();
-                float* tmp = dz; dz = dz_next; dz_next = tmp;
-                off_out = off_in;
-            }
+            dz = mlp_backward(m, sW, sdW, acts, dz, dz_next, lane);
             if (live) scatter_feat(g, io.d_grid, q.scene, c, dz, lane);
         }
     }

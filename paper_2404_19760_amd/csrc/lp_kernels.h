@@ -8,6 +8,11 @@ namespace lp {
 __global__ void fwd_generic_kernel(GridDev g, MlpDev m, RaysDev rays, FwdOut out);
 __global__ void bwd_generic_kernel(GridDev g, MlpDev m, RaysDev rays, BwdIo io, int tiles_per_block);
 __global__ void reduce_params_kernel(MlpDev m, BwdIo io, int n_records);
+__global__ void splat_fwd_generic_kernel(GridDev tgt, MlpDev m, RaysDev rays, SplatDev sp);
+__global__ void splat_normalise_kernel(float* theta, const float* theta_w, long long cells, int C);
+__global__ void fill_zero_kernel(float* p, long long n);
+__global__ void splat_bwd_generic_kernel(GridDev tgt, MlpDev m, RaysDev rays, SplatDev sp, BwdIo io,
+                                         int tiles_per_block);
 
 // ---- matrix-core kernels (lp_mfma_fwd.hip / lp_mfma_bwd.hip) -------------------------
 // Shapes covered: C in {16, 32}, one or two hidden layers of equal width in {32, 64}.

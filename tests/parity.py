@@ -170,3 +170,33 @@ def check_case_dec(lp, oracle, inp, math_mode=0, aux_grads=True, seed=0, label="
             assert v[1] <= max_strict_fail, (f"{label} {k}: {v[1]:.2%} of the elements miss the plain "
                                              f"tolerance (allowed {max_strict_fail:.2%})")
     return worst
+
+
+# ---- Splatter ---------------------------------------------------------------------------------
+
+def check_case_splat(lp, oracle, sp, seed=0, label=""):
+    """Splatter parity: normalised structure, weight sums and every gradient against the oracle."""
+    import torch
+    prob = oracle.SplatProblem(sp)
+    o_theta, o_w = oracle.splat_fwd(prob)
+    rng = np.random.default_rng(900 + seed)
+    G = [(rng.standard_normal(t.shape) / max(1, t.size) ** 0.5).astype(np.float32) for t in o_theta]
+    ref = oracle.splat_bwd(prob, o_w, G)
+    upper = oracle.splat_bwd(prob, o_w, G, kink_band=KINK_BAND, kink_side=+1)
+    lower = oracle.splat_bwd(prob, o_w, G, kink_band=KINK_BAND, kink_side=-1)
+    target, rays, splat = lp.splat_to_device(sp)
+    theta, theta_w = lp.splat_fwd(target, rays, splat)
+    # the backward takes the oracle's weight sums rounded to float32?  No: the library's own, as a caller would
+    d_feats, d_prior, dW, db = lp.splat_bwd(target, rays, splat, theta_w, [torch.from_numpy(g).to("cuda:0") for g in G])
+    torch.cuda.synchronize()
+    cpu = lambda t: t.cpu().numpy()
+    worst = {}
+    for p in range(len(o_theta)):
+        worst[f"theta_w{p}"] = close(cpu(theta_w[p]), o_w[p], FWD_RTOL, f"{label} theta_w[{p}]")
+        worst[f"theta{p}"] = close(cpu(theta[p]), o_theta[p], FWD_RTOL, f"{label} theta[{p}]")
+    flat = lambda r: [("d_feats", r[0])] + [(f"d_prior{i}", a) for i, a in enumerate(r[1])] \
+        + [(f"dW{i}", a) for i, a in enumerate(r[2])] + [(f"db{i}", a) for i, a in enumerate(r[3])]
+    gpu = [d_feats] + list(d_prior) + list(dW) + list(db)
+    for (name, r), (_, lo), (_, hi), g in zip(flat(ref), flat(lower), flat(upper), gpu):
+        worst[name] = close_envelope(cpu(g), r, lo, hi, BWD_RTOL, f"{label} {name}")
+    return worst

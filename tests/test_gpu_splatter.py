@@ -1,0 +1,62 @@
+"""GPU parity of the Splatter against the CPU oracle, through the C ABI."""
+import dataclasses
+
+import numpy as np
+import pytest
+
+import lp_inputs
+from lp_inputs import TRIPLANE, VOXEL
+
+from parity import check_case_splat
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def oracle():
+    import oracle as o
+    return o
+
+
+@pytest.mark.parametrize("kind", [VOXEL, TRIPLANE])
+def test_naive_splatter(lp, oracle, kind):
+    """No MLP: every point pushes its pixel's feature vector."""
+    sp = lp_inputs.make_splat_small(kind, channels=5, res=(9, 8, 10), n_rays=131, samples=37, seed=91, n_scenes=3)
+    print(check_case_splat(lp, oracle, sp, label=f"naive splat kind={kind}"), flush=True)
+
+
+@pytest.mark.parametrize("kind", [VOXEL, TRIPLANE])
+@pytest.mark.parametrize("hidden,n_freq,prior_channels", [((9,), -1, 0), ((8, 7), 1, 3), ((), 0, 2)])
+def test_splatter_with_mlp(lp, oracle, kind, hidden, n_freq, prior_channels):
+    """MLP on [pixel feature ; prior read ; direction encoding], ragged ray and sample counts."""
+    sp = lp_inputs.make_splat_small(kind, channels=6, res=(9, 8, 10), n_in=4, hidden=hidden, n_freq=n_freq,
+                                    prior_channels=prior_channels, prior_res=(7, 6, 5), n_rays=131, samples=37,
+                                    seed=93, n_scenes=2)
+    print(check_case_splat(lp, oracle, sp, label=f"splat kind={kind} hidden={hidden}"), flush=True)
+
+
+def test_splatter_with_contraction_and_empty_cells(lp, oracle):
+    """Contract coordinates; a fine target that most rays never touch (cells with zero weight)."""
+    sp = lp_inputs.make_splat_small(VOXEL, channels=4, res=(20, 18, 22), n_in=3, hidden=(8,), n_freq=0,
+                                    n_rays=40, samples=30, seed=95, origin_radius=1.5, near=(0.0, 0.3), far=(6.0, 20.0))
+    sp = dataclasses.replace(sp, contract_a=1.2)
+    w = check_case_splat(lp, oracle, sp, label="splat contract")
+    print(w, flush=True)
+
+
+def test_splatter_errors_and_empty_input(lp):
+    import torch
+    sp = lp_inputs.make_splat_small(VOXEL, channels=4, n_rays=5)
+    target, rays, splat = lp.splat_to_device(sp)
+    with pytest.raises(lp.LightplaneError) as e:       # naive Splatter needs n_in == channels
+        lp.splat_fwd(lp.target_struct(VOXEL, 1, 3, sp.res), rays, splat)
+    assert e.value.status == lp.LP_ERR_INVALID_ARG
+    with pytest.raises(lp.LightplaneError) as e:
+        lp.splat_fwd(target, rays, dataclasses.replace(splat, n_freq=1))   # encoding without an MLP
+    assert e.value.status == lp.LP_ERR_INVALID_ARG
+    none = dataclasses.replace(sp, origins=sp.origins[:0], dirs=sp.dirs[:0], near=sp.near[:0], far=sp.far[:0],
+                               feats=sp.feats[:0])
+    target, rays, splat = lp.splat_to_device(none)
+    theta, theta_w = lp.splat_fwd(target, rays, splat)
+    torch.cuda.synchronize()
+    assert float(theta[0].abs().max()) == 0.0 and float(theta_w[0].abs().max()) == 0.0
