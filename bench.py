@@ -38,7 +38,7 @@ def parse():
     ap.add_argument("--math", default="default", choices=["default", "generic", "bf16x3"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
-    ap.add_argument("--also", default="single_scene,contract,decoder",
+    ap.add_argument("--also", default="single_scene,contract,decoder,splat_naive,splat_mlp",
                     help="further workloads reported for context under 'also' (comma-separated, '' to skip)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy kernel (reference for HBM counters)")
@@ -145,6 +145,40 @@ def measure(lp, torch, name, mode, steps, warmup, calibrate_copy=False):
                 fwd_ms=fwd_ms, bwd_ms=bwd_ms)
 
 
+def measure_splat(lp, torch, name, steps, warmup):
+    """Times the Splatter (forward: push + normalise; backward for a random output gradient)."""
+    import lp_inputs
+    w = lp_inputs.SPLAT_WORKLOADS[name]
+    sp = lp_inputs.make_splat_inputs(name)
+    target, rays, splat = lp.splat_to_device(sp)
+    theta, theta_w = lp.splat_fwd(target, rays, splat)
+    g = [torch.randn_like(t) for t in theta]
+    d_feats = torch.empty_like(splat.feats)
+    d_prior = [] if splat.prior is None else [torch.zeros_like(t) for t in splat.prior.data]
+    dW = [] if splat.mlp is None else [torch.zeros_like(t) for t in splat.mlp.weights]
+    db = [] if splat.mlp is None else [torch.zeros_like(t) for t in splat.mlp.biases]
+    ws = torch.empty(lp.lp_splat_bwd_workspace_bytes(target, rays, splat), dtype=torch.uint8, device="cuda:0")
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    times = []
+    for it in range(warmup + steps):
+        e0, e1, e2 = ev(), ev(), ev()
+        e0.record()
+        lp.lp_splat_fwd(target, rays, splat, theta, theta_w)
+        e1.record()
+        for t in d_prior + dW + db:
+            t.zero_()
+        lp.lp_splat_bwd(target, rays, splat, theta_w, g, d_feats, d_prior, dW, db, ws)
+        e2.record()
+        torch.cuda.synchronize()
+        if it >= warmup:
+            times.append((e0.elapsed_time(e1), e1.elapsed_time(e2)))
+    fwd_ms, bwd_ms = [float(np.mean(x)) for x in zip(*times)]
+    pts = w.ray_samples
+    return {"workload": name, "points": pts, "value": pts / ((fwd_ms + bwd_ms) * 1e-3), "unit": "points/s fwd+bwd",
+            "fwd_ms": fwd_ms, "bwd_ms": bwd_ms, "mlp": w.hidden is not None,
+            "fwd_push_GBs": w.push_bytes_per_sample * pts / (fwd_ms * 1e-3) / 1e9}
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -195,6 +229,9 @@ def main():
     del r
     for name in [n for n in args.also.split(",") if n and n != args.config]:
         torch.cuda.empty_cache()
+        if name in __import__("lp_inputs").SPLAT_WORKLOADS:
+            out.setdefault("also", []).append(measure_splat(lp, torch, name, max(3, args.steps // 2), 2))
+            continue
         k = max(3, args.steps // 2)
         o = measure(lp, torch, name, mode, k, 2)
         ow = o["w"]

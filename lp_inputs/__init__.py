@@ -392,3 +392,71 @@ def make_splat_small(kind: int, *, n_scenes=1, channels=4, res=(5, 4, 6), n_in=N
                        n_freq=n_freq if hidden is not None else -1, prior=prior,
                        prior_res=tuple(prior_res) if prior_channels else None, prior_channels=prior_channels,
                        mlp_dims=dims, weights=ws, biases=bs)
+
+
+@dataclasses.dataclass(frozen=True)
+class SplatWorkload:
+    """Shapes of a Splatter benchmark: `n_cameras` views of `image`^2 pixels with `n_in`-channel
+    features pushed into a `res` structure of `channels` channels, `samples` points per ray."""
+    name: str
+    kind: int
+    channels: int
+    res: Tuple[int, int, int]
+    n_in: int
+    image: int
+    n_cameras: int
+    samples: int
+    hidden: Optional[Tuple[int, ...]] = None   # None: naive Splatter
+    prior_channels: int = 0
+    n_freq: int = -1
+    near: float = 1.0
+    far: float = 4.0
+    aabb: float = 2.75
+    cfg_id: int = 0
+
+    @property
+    def rays(self) -> int:
+        return self.n_cameras * self.image * self.image
+
+    @property
+    def ray_samples(self) -> int:
+        return self.rays * self.samples
+
+    @property
+    def push_bytes_per_sample(self) -> int:
+        """Algorithmic bytes one point adds to the target (corners x (C + 1) x 4)."""
+        corners = 8 if self.kind == VOXEL else 12
+        return corners * (self.channels + 1) * 4
+
+
+# The paper's Splatter setting (appendix, "Experimental Details"): 160^3 voxel grid, 32-dimensional
+# image features, 160 points per ray, 3-layer MLP of width 64; four views of 128^2 pixels.
+SPLAT_WORKLOADS = {
+    "splat_naive": SplatWorkload("splat_naive", VOXEL, 32, (160, 160, 160), 32, 128, 4, 160, cfg_id=8),
+    # with the MLP, at a size the generic kernels' LDS budget takes (16-channel features, prior and
+    # target, two hidden layers of 32, raw direction), fewer rays
+    "splat_mlp": SplatWorkload("splat_mlp", VOXEL, 16, (160, 160, 160), 16, 64, 4, 160, hidden=(32, 32),
+                               prior_channels=16, n_freq=0, cfg_id=9),
+}
+
+
+def make_splat_inputs(name: str) -> SplatInputs:
+    w = SPLAT_WORKLOADS[name]
+    cam = Workload(name, w.kind, 1, w.channels, w.res, 0.1, (w.channels, 4), w.image, w.n_cameras, w.samples,
+                   near=w.near, far=w.far, aabb=w.aabb)
+    origins, dirs, near, far, scene = make_rays(cam)
+    rng = np.random.default_rng(_seed(w.cfg_id, 0))
+    feats = rng.standard_normal((origins.shape[0], w.n_in), dtype=np.float32)
+    prior = dims = ws = bs = None
+    if w.prior_channels:
+        prior = make_grid(w.kind, 1, w.res, w.prior_channels, 0.1, _seed(w.cfg_id, 1))
+    if w.hidden is not None:
+        n_enc = 0 if w.n_freq < 0 else 3 + 6 * w.n_freq
+        dims = (w.n_in + w.prior_channels + n_enc, *w.hidden, w.channels)
+        ws, bs = make_mlp(dims, _seed(w.cfg_id, 2))
+    a = w.aabb
+    return SplatInputs(kind=w.kind, n_scenes=1, channels=w.channels, res=w.res, aabb_min=(-a, -a, -a),
+                       aabb_max=(a, a, a), origins=origins, dirs=dirs, near=near, far=far, scene=scene,
+                       samples=w.samples, feats=feats, n_freq=w.n_freq if w.hidden is not None else -1, prior=prior,
+                       prior_res=w.res if w.prior_channels else None, prior_channels=w.prior_channels,
+                       mlp_dims=dims, weights=ws, biases=bs)

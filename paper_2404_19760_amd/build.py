@@ -18,7 +18,7 @@ INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.environ.get("LP_LIB_OUT", os.path.join(HERE, "liblightplane.so"))
 
-SOURCES = ["lp_api.hip", "lp_decoder.hip", "lp_generic.hip", "lp_mfma_fwd.hip", "lp_mfma_bwd.hip"]
+SOURCES = ["lp_api.hip", "lp_decoder.hip", "lp_generic.hip", "lp_mfma_fwd.hip", "lp_mfma_bwd.hip", "lp_splat_fast.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-munsafe-fp-atomics",

@@ -640,7 +640,14 @@ lp_status lp_splat_fwd(const lp_grid* target, const lp_rays* rays, const lp_spla
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail("Splatter clear kernels", e);
-    if (rays->M > 0) {
+    if (rays->M > 0 && m.n_layers == 0 && lp::splat_naive_supported(g)) {
+        // naive Splatter with 16 or 32 channels: wavefront per ray, run-merged whole-line atomics
+        std::string err;
+        int n_cu = 0;
+        if (compute_units(&n_cu, &err)) return fail(LP_ERR_HIP, err);
+        e = lp::launch_splat_naive(g, r, sd, n_cu, s);
+        if (e != hipSuccess) return hip_fail("Splatter forward kernel launch", e);
+    } else if (rays->M > 0) {
         const size_t lds = sizeof(float) * ((size_t)m.param_total + (size_t)m.act_total * kGenericLanes);
         if (lds > kMaxLds) return fail(LP_ERR_UNSUPPORTED, "MLP too large for the Splatter kernel's LDS budget");
         e = hipFuncSetAttribute((const void*)lp::splat_fwd_generic_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,

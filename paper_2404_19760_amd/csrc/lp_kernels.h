@@ -26,6 +26,11 @@ hipError_t launch_bwd_mfma(const GridDev& g, const MlpDev& m, const RaysDev& ray
                            int n_cu, hipStream_t stream);
 
 
+// ---- naive Splatter forward, wavefront per ray (lp_splat_fast.hip): 16 or 32 channels ----
+bool splat_naive_supported(const GridDev& tgt);
+hipError_t launch_splat_naive(const GridDev& tgt, const RaysDev& rays, const SplatDev& sp, int n_cu,
+                              hipStream_t stream);
+
 // ---- the two-MLP decoder as ONE block-structured MLP (lp_decoder.hip) ------------------
 // Combined layer l has the opacity MLP's rows first, then the feature MLP's; a shallower MLP
 // is carried through the extra layers by identity blocks (exact behind a ReLU); the first

@@ -1,0 +1,148 @@
+// Naive Splatter forward (Section 3.3 "Splatter": every point of a pixel's ray pushes the pixel's
+// feature vector into the cell that contains it), wavefront per ray.
+//
+// The push is the Renderer's backward scatter with a feature gradient that is constant along
+// the ray, so it runs on the same machinery: a step is 32 points; lane (col, grp) of the step
+// places point slot col and publishes its corner weights and cell offset in LDS; then the lanes
+// turn into channels, walk 16 consecutive points each, sum the weights of runs that stay in one
+// cell and issue one atomic add per corner on whole 64-byte lines (value = pixel feature times
+// summed weight).  The weight sums go to the one-channel structure the same way, one lane per
+// corner.  Ray groups are visited in scrambled order like the Renderer's backward (atomic adds
+// of neighbouring rays queue up at the same L2 channel).
+#include "lp_kernels.h"
+#include "lp_mfma.h"
+#include "lp_mfma_mlp.h"
+#include "lp_mfma_bwd_common.h"
+
+namespace lp {
+
+namespace {
+
+constexpr int kWaves = 4;
+
+// Weight sums: lane `corner` (< 8 voxel, < 12 triplane) of each lane group walks the group's 16
+// points and adds the summed weight of every run into theta_w.
+template <int KIND, int C>
+__device__ __forceinline__ void scatter_weights(const GridDev& g, float* const theta_w[3], int scene,
+                                                const float* info, int corner, int grp)
+{
+    constexpr int NC = KIND == LP_GRID_VOXEL ? 8 : 12;
+    const bool live = corner < NC;
+    const int cid = live ? corner : 0;
+    float* dst;
+    int widx, bidx;
+    if constexpr (KIND == LP_GRID_VOXEL) {
+        // record order of the 8 weights: 4dx + 2dy + dz (32 channels), 4dz + 2dx + dy (16 channels)
+        const int dx = C == 16 ? (cid >> 1) & 1 : cid >> 2;
+        const int dy = C == 16 ? cid & 1 : (cid >> 1) & 1;
+        const int dz = C == 16 ? cid >> 2 : cid & 1;
+        dst = theta_w[0] + (size_t)scene * g.N[0] * g.N[1] * g.N[2] + ((size_t)dx * g.N[1] + dy) * g.N[2] + dz;
+        widx = cid;
+        bidx = 8;
+    } else {
+        const int p = cid >> 2, a = p, b = (p + 1) % 3, da = (cid >> 1) & 1, db = cid & 1;
+        dst = theta_w[p] + (size_t)scene * g.N[a] * g.N[b] + (size_t)da * g.N[b] + db;
+        widx = cid;
+        bidx = 12 + p;
+    }
+    float acc = 0.0f;
+    unsigned prev = 0;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const float* rec = info + d_row(r, grp) * 16;
+        const float w = rec[widx];
+        const unsigned base = reinterpret_cast<const unsigned*>(rec)[bidx];
+        if (r > 0 && base != prev) {
+            if (live) atomicAdd(dst + prev / C, acc);
+            acc = 0.0f;
+        }
+        prev = base;
+        acc += w;
+    }
+    if (live) atomicAdd(dst + prev / C, acc);
+}
+
+template <int KIND, int C, bool CC>
+__global__ __launch_bounds__(kWaves * 64) void splat_naive_kernel(GridDev tgt, RaysDev rays, SplatDev sp,
+                                                                  long long group_mul)
+{
+    __shared__ float info_all[kWaves][32 * 16];
+    const int lane = threadIdx.x & 63;
+    const int col = lane & 31, grp = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    float* info = info_all[wave];
+
+    const long long n_groups = (rays.M + kWaves - 1) / kWaves;
+    const RaySchedule sched = ray_schedule(n_groups * kWaves, kWaves);
+    const int S = rays.S;
+    for (long long seq = sched.first; seq < sched.end; seq += sched.stride) {
+        const long long ray = ((seq / kWaves) * group_mul % n_groups) * kWaves + seq % kWaves;
+        if (ray >= rays.M) continue;
+        const RayGeom q = load_ray_geom(rays, ray);
+        // the pixel's feature of this lane's channel (16 channels: both halves of a lane group)
+        const float v = sp.feats[(size_t)ray * C + (col & (C - 1))];
+        f32x16 val;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) val[r] = v;
+        for (int j0 = 0; j0 < S; j0 += kBwdStep) {
+            const int j = j0 + slot_to_sample(col);
+            const Cell3 c = sample_cell<CC>(tgt, q, min(j, S - 1));
+            wave_lds_fence();
+            if (grp == 0) {
+                float* rec = info + col * 16;
+                write_scatter_record<KIND, C>(rec, tgt, c);
+                if (j >= S) {  // a point past the end of the ray pushes nothing
+#pragma unroll
+                    for (int k = 0; k < (KIND == LP_GRID_VOXEL ? 8 : 12); ++k) rec[k] = 0.0f;
+                }
+            }
+            wave_lds_fence();
+            scatter_channels<KIND, C>(tgt, sp.theta, q.scene, info, val, col, grp);
+            scatter_weights<KIND, C>(tgt, sp.theta_w, q.scene, info, col, grp);
+        }
+    }
+}
+
+template <int KIND, int C, bool CC>
+hipError_t launch(const GridDev& tgt, const RaysDev& rays, const SplatDev& sp, int n_cu, hipStream_t stream)
+{
+    long long blocks = 4LL * n_cu;   // small kernel: four workgroups per compute unit
+    const long long need = (rays.M + kWaves - 1) / kWaves;
+    if (blocks > need) blocks = need;
+    blocks = (blocks + 7) / 8 * 8;
+    const long long n_groups = need;
+    long long group_mul = 1;
+    for (long long p : {7919LL, 7907LL, 7901LL, 7883LL})
+        if (n_groups > p && n_groups % p != 0) { group_mul = p; break; }
+    hipLaunchKernelGGL((splat_naive_kernel<KIND, C, CC>), dim3((unsigned)blocks), dim3(kWaves * 64), 0, stream, tgt,
+                       rays, sp, group_mul);
+    return hipGetLastError();
+}
+
+template <int KIND>
+hipError_t dispatch(const GridDev& tgt, const RaysDev& rays, const SplatDev& sp, int n_cu, hipStream_t stream)
+{
+    const bool cc = tgt.contract > 0.0;
+    if (tgt.C == 16) return cc ? launch<KIND, 16, true>(tgt, rays, sp, n_cu, stream) : launch<KIND, 16, false>(tgt, rays, sp, n_cu, stream);
+    if (tgt.C == 32) return cc ? launch<KIND, 32, true>(tgt, rays, sp, n_cu, stream) : launch<KIND, 32, false>(tgt, rays, sp, n_cu, stream);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+bool splat_naive_supported(const GridDev& tgt)
+{
+    if (tgt.C != 16 && tgt.C != 32) return false;
+    const unsigned long long n0 = (unsigned long long)tgt.N[0], n1 = (unsigned long long)tgt.N[1], n2 = (unsigned long long)tgt.N[2];
+    if (tgt.kind == LP_GRID_VOXEL) return n0 * n1 * n2 * tgt.C < (1ull << 30);   // 32-bit byte offsets in a scene
+    return n0 * n1 * tgt.C < (1ull << 30) && n1 * n2 * tgt.C < (1ull << 30) && n2 * n0 * tgt.C < (1ull << 30);
+}
+
+hipError_t launch_splat_naive(const GridDev& tgt, const RaysDev& rays, const SplatDev& sp, int n_cu,
+                              hipStream_t stream)
+{
+    return tgt.kind == LP_GRID_VOXEL ? dispatch<LP_GRID_VOXEL>(tgt, rays, sp, n_cu, stream)
+                                     : dispatch<LP_GRID_TRIPLANE>(tgt, rays, sp, n_cu, stream);
+}
+
+}  // namespace lp

@@ -26,6 +26,19 @@ def test_naive_splatter(lp, oracle, kind):
 
 
 @pytest.mark.parametrize("kind", [VOXEL, TRIPLANE])
+@pytest.mark.parametrize("channels", [16, 32])
+@pytest.mark.parametrize("samples", [1, 32, 75])
+def test_naive_splatter_wave_per_ray(lp, oracle, kind, channels, samples):
+    """16 / 32 channels run on the wavefront-per-ray kernel: ragged point counts, several scenes,
+    once with contract coordinates."""
+    sp = lp_inputs.make_splat_small(kind, channels=channels, res=(12, 10, 11), n_rays=203, samples=samples,
+                                    seed=97 + samples, n_scenes=2, far=(2.2, 6.0))
+    if samples == 75:
+        sp = dataclasses.replace(sp, contract_a=1.3)
+    print(check_case_splat(lp, oracle, sp, label=f"naive splat fast kind={kind} C={channels} S={samples}"), flush=True)
+
+
+@pytest.mark.parametrize("kind", [VOXEL, TRIPLANE])
 @pytest.mark.parametrize("hidden,n_freq,prior_channels", [((9,), -1, 0), ((8, 7), 1, 3), ((), 0, 2)])
 def test_splatter_with_mlp(lp, oracle, kind, hidden, n_freq, prior_channels):
     """MLP on [pixel feature ; prior read ; direction encoding], ragged ray and sample counts."""

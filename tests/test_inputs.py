@@ -63,3 +63,15 @@ def test_contract_workload_has_the_papers_experimental_shape():
     inp = lp_inputs.make_inputs("contract", with_grid=False)
     assert inp.contract_a == 1.0 and inp.aabb_min == (-1.0, -1.0, -1.0) and inp.aabb_max == (1.0, 1.0, 1.0)
     assert inp.n_rays == 256 * 256 and float(inp.far.max()) > 10.0
+
+
+def test_splat_workloads():
+    """Appendix, "Experimental Details": 160^3 voxel grid, 160 points per ray; the naive workload
+    carries the 32-dimensional features of the paper."""
+    w = lp_inputs.SPLAT_WORKLOADS["splat_naive"]
+    assert (w.res, w.channels, w.n_in, w.samples) == ((160, 160, 160), 32, 32, 160)
+    sp = lp_inputs.make_splat_inputs("splat_mlp")
+    assert sp.mlp_dims == (16 + 16 + 3, 32, 32, 16) and sp.prior[0].shape == (1, 160, 160, 160, 16)
+    assert sp.n_rays == 4 * 64 * 64 and sp.feats.shape == (sp.n_rays, 16)
+    a = lp_inputs.make_splat_inputs("splat_mlp")
+    assert np.array_equal(a.feats, sp.feats) and np.array_equal(a.weights[1], sp.weights[1])
