@@ -36,6 +36,8 @@ def parse():
     ap.add_argument("--config", default="large",
                     help="workload: tiny | single_scene | voxel | batched | large")
     ap.add_argument("--math", default="default", choices=["default", "generic", "bf16x3"])
+    ap.add_argument("--grid-dtype", default="f32", choices=["f32", "bf16", "f16"],
+                    help="storage type of the grid on the GPU (gradients stay f32)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
     ap.add_argument("--also", default="single_scene,contract,decoder,splat_naive,splat_mlp",
@@ -69,13 +71,15 @@ def cpu_baseline(inp, budget_s: float):
             f"all {inp.samples} samples each, fp64 forward + stored-forward reverse-mode backward, {t:.1f} s"}
 
 
-def measure(lp, torch, name, mode, steps, warmup, calibrate_copy=False):
+def measure(lp, torch, name, mode, steps, warmup, calibrate_copy=False, grid_dtype="f32"):
     """Times `steps` forward+backward steps of workload `name`; returns the result fields."""
     import lp_inputs
     w = lp_inputs.WORKLOADS[name]
     inp = lp_inputs.make_inputs(name)
     dev = "cuda:0"
     grid, mlp, rays, bg = lp.to_device(inp, dev)
+    if grid_dtype != "f32":
+        grid.data = [t.to(torch.bfloat16 if grid_dtype == "bf16" else torch.float16) for t in grid.data]
     target = torch.from_numpy(inp.target).to(dev)
     dec = lp.decoder_to_device(inp.decoder, dev) if inp.decoder is not None else None
     if dec is None:
@@ -86,7 +90,7 @@ def measure(lp, torch, name, mode, steps, warmup, calibrate_copy=False):
     m = rays.n_rays
     rgb = torch.empty((m, 3), device=dev); alpha = torch.empty(m, device=dev)
     depth = torch.empty(m, device=dev); cache = torch.empty(m, device=dev)
-    d_grid = [torch.zeros_like(t) for t in grid.data]
+    d_grid = [torch.zeros_like(t, dtype=torch.float32) for t in grid.data]
     if dec is None:
         params = [mlp.weights, mlp.biases]
         ws = torch.empty(lp.lp_bwd_workspace_bytes(grid, mlp, rays, mode), dtype=torch.uint8, device=dev)
@@ -192,14 +196,15 @@ def main():
         print("bench.py: no GPU visible; the Renderer has no CPU path", file=sys.stderr)
         sys.exit(2)
     mode = {"default": lp.LP_MATH_DEFAULT, "generic": lp.LP_MATH_GENERIC, "bf16x3": lp.LP_MATH_BF16X3}[args.math]
-    r = measure(lp, torch, args.config, mode, args.steps, args.warmup, args.calibrate_copy)
+    r = measure(lp, torch, args.config, mode, args.steps, args.warmup, args.calibrate_copy, args.grid_dtype)
     w, inp, fast, m, samples = r["w"], r["inp"], r["fast"], r["rays"], r["samples"]
     elapsed, fwd_avg, bwd_avg = r["elapsed"], r["fwd_ms"], r["bwd_ms"]
 
     ms_per_step = 1e3 * elapsed / args.steps
-    g_bytes = w.gather_bytes_per_sample
-    # dominant kernel: the backward (re-reads the G gather bytes and adds G bytes of gradient)
-    bwd_gbs = 2 * g_bytes * samples / (bwd_avg * 1e-3) / 1e9
+    g_write = w.gather_bytes_per_sample                                   # fp32 gradient bytes per sample
+    g_bytes = g_write if args.grid_dtype == "f32" else g_write // 2       # bytes a sample reads from the grid
+    # dominant kernel: the backward (re-reads the gather bytes and adds the fp32 gradient bytes)
+    bwd_gbs = (g_bytes + g_write) * samples / (bwd_avg * 1e-3) / 1e9
     fwd_gbs = g_bytes * samples / (fwd_avg * 1e-3) / 1e9
     out = {
         "metric": "ray-samples/sec fwd+bwd (Renderer hot path)",
@@ -213,16 +218,17 @@ def main():
         "config": {"workload": f"{args.config}: {'voxel' if w.kind == 0 else 'triplane'} "
                                f"{w.n_scenes}x{w.res[0]}^{3 if w.kind == 0 else 2}x{w.channels}ch, "
                                f"{m} rays x {w.samples} samples, MLP {'-'.join(map(str, w.mlp_dims))}",
-                   "rays": m, "samples_per_ray": w.samples, "ray_samples": samples,
+                   "rays": m, "samples_per_ray": w.samples, "ray_samples": samples, "grid_dtype": args.grid_dtype,
                    "kernels": "mfma" if fast else "generic"},
         "fwd": {"ms": fwd_avg, "ray_samples_per_s": samples / (fwd_avg * 1e-3),
                 "algorithmic_GBs": fwd_gbs, "frac_hbm_peak": fwd_gbs / HBM_PEAK_GBS},
-        "fwd_bwd_effective": {"algorithmic_GBs": 3 * g_bytes * samples / ((fwd_avg + bwd_avg) * 1e-3) / 1e9,
-                              "frac_hbm_peak": 3 * g_bytes * samples / ((fwd_avg + bwd_avg) * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "fwd_bwd_effective": {"algorithmic_GBs": (2 * g_bytes + g_write) * samples / ((fwd_avg + bwd_avg) * 1e-3) / 1e9,
+                              "frac_hbm_peak": (2 * g_bytes + g_write) * samples / ((fwd_avg + bwd_avg) * 1e-3) / 1e9
+                              / HBM_PEAK_GBS},
         "roofline": {"kernel": "lp_render_bwd", "bound": "hbm", "achieved": bwd_gbs, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": bwd_gbs / HBM_PEAK_GBS,
-                     "traffic": MEASURED_BWD_HBM_BYTES.get(args.config) if fast else None,
-                     "bytes_per_sample": 2 * g_bytes, "ms": bwd_avg},
+                     "traffic": MEASURED_BWD_HBM_BYTES.get(args.config) if fast and args.grid_dtype == "f32" else None,
+                     "bytes_per_sample": g_bytes + g_write, "ms": bwd_avg},
     }
     # further workloads for context (short runs), e.g. the single-scene configuration and the
     # paper's experimental Renderer shape with contract coordinates

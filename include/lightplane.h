@@ -41,6 +41,11 @@ typedef enum {
 
 typedef enum { LP_GRID_VOXEL = 0, LP_GRID_TRIPLANE = 1 } lp_grid_kind;
 
+/* Storage type of the values of a hash structure that is READ (Section 3.2 notes that the
+   hashing scheme is where precision and layout can be traded).  Gradients and the Splatter's
+   outputs are always fp32. */
+typedef enum { LP_F32 = 0, LP_BF16 = 1, LP_F16 = 2 } lp_dtype;
+
 /*
  * The 3D hash structure theta (Section 3.2), channel-last.
  *   voxel   : data[0] = [B][NX][NY][NZ][C]                       (data[1], data[2] ignored)
@@ -60,9 +65,10 @@ typedef struct {
     int32_t kind; /* lp_grid_kind */
     int32_t B, C; /* scenes, feature channels (the paper's K) */
     int32_t NX, NY, NZ;
-    const float* data[3]; /* device */
+    const void* data[3]; /* device; elements of type `dtype` */
     float aabb_min[3], aabb_max[3];
     float contract_a;
+    int32_t dtype; /* lp_dtype; LP_BF16 / LP_F16 halve the bytes a sample reads */
 } lp_grid;
 
 /*

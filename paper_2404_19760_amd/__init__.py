@@ -24,6 +24,8 @@ LP_MAX_LAYERS = 8
 LP_OK, LP_ERR_INVALID_ARG, LP_ERR_UNSUPPORTED, LP_ERR_HIP, LP_ERR_WORKSPACE = range(5)
 LP_GRID_VOXEL, LP_GRID_TRIPLANE = 0, 1
 LP_MATH_DEFAULT, LP_MATH_GENERIC, LP_MATH_BF16X3 = 0, 1, 2
+LP_FEAT_SIGMOID, LP_FEAT_IDENTITY = 0, 1
+LP_F32, LP_BF16, LP_F16 = 0, 1, 2
 
 
 class LightplaneError(RuntimeError):
@@ -36,7 +38,8 @@ class _Grid(C.Structure):
     _fields_ = [("kind", C.c_int32), ("B", C.c_int32), ("C", C.c_int32),
                 ("NX", C.c_int32), ("NY", C.c_int32), ("NZ", C.c_int32),
                 ("data", C.c_void_p * 3),
-                ("aabb_min", C.c_float * 3), ("aabb_max", C.c_float * 3), ("contract_a", C.c_float)]
+                ("aabb_min", C.c_float * 3), ("aabb_max", C.c_float * 3), ("contract_a", C.c_float),
+                ("dtype", C.c_int32)]
 
 
 class _Mlp(C.Structure):
@@ -128,10 +131,14 @@ def _dev_f32(t: Optional[torch.Tensor], name: str, shape=None) -> Optional[int]:
     return t.data_ptr()
 
 
+_GRID_DTYPES = {torch.float32: LP_F32, torch.bfloat16: LP_BF16, torch.float16: LP_F16}
+
+
 @dataclasses.dataclass
 class Grid:
     """Voxel grid [B][NX][NY][NZ][C] (one tensor) or triplane (three tensors
-    [B][NX][NY][C], [B][NY][NZ][C], [B][NZ][NX][C]); float32, on the GPU."""
+    [B][NX][NY][C], [B][NY][NZ][C], [B][NZ][NX][C]); float32, bfloat16 or float16 (all tensors
+    alike), on the GPU."""
     kind: int
     data: List[torch.Tensor]
     res: Sequence[int]
@@ -161,8 +168,15 @@ class Grid:
         shapes = self.shapes()
         if len(self.data) != len(shapes):
             raise ValueError("wrong number of grid tensors for this kind")
+        dt = self.data[0].dtype
+        if dt not in _GRID_DTYPES:
+            raise ValueError("grid tensors must be float32, bfloat16 or float16")
+        g.dtype = _GRID_DTYPES[dt]
         for p, (t, s) in enumerate(zip(self.data, shapes)):
-            g.data[p] = _dev_f32(t, f"grid.data[{p}]", s)
+            if not (t.is_cuda and t.dtype == dt and t.is_contiguous() and tuple(t.shape) == tuple(s)):
+                raise ValueError(f"grid.data[{p}] must be a contiguous GPU tensor of shape {tuple(s)} and the "
+                                 "dtype of grid.data[0]")
+            g.data[p] = t.data_ptr()
         for a in range(3):
             g.aabb_min[a] = float(self.aabb_min[a])
             g.aabb_max[a] = float(self.aabb_max[a])
@@ -519,7 +533,7 @@ def render_dec_bwd(grid: Grid, dec: Decoder, rays: Rays, bg, d_out, ray_cache, d
     """Allocate zeroed gradient buffers and a workspace and run lp_render_dec_bwd.
     Returns (d_grid, dW_opacity, db_opacity, dW_feature, db_feature)."""
     dev = rays.origins.device
-    d_grid = [torch.zeros_like(t) for t in grid.data]
+    d_grid = [torch.zeros_like(t, dtype=torch.float32) for t in grid.data]   # gradients are float32 whatever the storage
     z = lambda lst: [torch.zeros_like(t) for t in lst]
     dWs, dbs, dWv, dbv = z(dec.opacity.weights), z(dec.opacity.biases), z(dec.feature.weights), z(dec.feature.biases)
     ws = torch.empty(lp_dec_workspace_bytes(grid, dec, rays, math_mode)[1], dtype=torch.uint8, device=dev)
@@ -545,7 +559,7 @@ def render_bwd(grid: Grid, mlp: Mlp, rays: Rays, bg, d_rgb, ray_cache, d_alpha=N
     """Allocate zeroed gradient buffers (and a workspace) and run lp_render_bwd.
     Returns (d_grid list, dW list, db list)."""
     dev = rays.origins.device
-    d_grid = [torch.zeros_like(t) for t in grid.data]
+    d_grid = [torch.zeros_like(t, dtype=torch.float32) for t in grid.data]   # gradients are float32 whatever the storage
     dW = [torch.zeros_like(w) for w in mlp.weights]
     db = [torch.zeros_like(b) for b in mlp.biases]
     if workspace is None:

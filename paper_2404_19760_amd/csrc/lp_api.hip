@@ -58,6 +58,8 @@ lp_status validate(const lp_grid* grid, const lp_mlp* mlp, const lp_rays* rays)
             !(grid->aabb_max[a] > grid->aabb_min[a]))
             return fail(LP_ERR_INVALID_ARG, "aabb_max must exceed aabb_min on every axis (finite values)");
     }
+    if (grid->dtype != LP_F32 && grid->dtype != LP_BF16 && grid->dtype != LP_F16)
+        return fail(LP_ERR_INVALID_ARG, "grid->dtype must be LP_F32, LP_BF16 or LP_F16");
     if (!(grid->contract_a >= 0.0f && grid->contract_a <= 2.0f))
         return fail(LP_ERR_INVALID_ARG, "grid->contract_a must be 0 (off) or in (0, 2]");
     if (mlp->n_layers < 1 || mlp->n_layers > LP_MAX_LAYERS)
@@ -88,6 +90,7 @@ void to_device_views(const lp_grid* grid, const lp_mlp* mlp, const lp_rays* rays
         g->scale[a] = (double)(g->N[a] - 1) / ((double)grid->aabb_max[a] - (double)grid->aabb_min[a]);
     }
     g->contract = (double)grid->contract_a;
+    g->dtype = grid->dtype;
     std::memset(m, 0, sizeof(*m));
     m->n_layers = mlp->n_layers;
     int off = 0, maxw = 0, act = 0;

@@ -2,6 +2,7 @@
 // sample placement, world -> grid addressing (Section 3.2 of the paper) and the
 // density / colour heads.  HIP for gfx950 only.
 #pragma once
+#include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -10,8 +11,9 @@
 namespace lp {
 
 struct GridDev {
-    const float* data[3];
+    const void* data[3];  // elements of type dtype
     int kind, B, C;
+    int dtype;            // lp_dtype
     int N[3];
     double amin[3];
     double scale[3];  // (N-1)/(max-min): world -> continuous index
@@ -66,6 +68,15 @@ struct BwdIo {
     float* ws;         // per-wave (or per-block) partial sums of the MLP gradients
     int ws_stride;     // floats between consecutive partial-sum records
 };
+
+// element `idx` of a grid tensor as fp32
+__device__ __forceinline__ float grid_load(const GridDev& g, const void* base, size_t idx)
+{
+    if (g.dtype == LP_F32) return reinterpret_cast<const float*>(base)[idx];
+    const unsigned short h = reinterpret_cast<const unsigned short*>(base)[idx];
+    if (g.dtype == LP_BF16) return __uint_as_float((unsigned)h << 16);
+    return __half2float(__ushort_as_half(h));
+}
 
 // Splatter arguments (Section 3.3 "Splatter"): pixel features, optional prior structure, the
 // accumulators of the forward, the inputs and outputs of the backward.

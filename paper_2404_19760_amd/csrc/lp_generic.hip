@@ -46,7 +46,7 @@ __device__ void gather_feat(const GridDev& g, int scene, const Cell& c, float* f
 {
     const int C = g.C;
     if (g.kind == LP_GRID_VOXEL) {
-        const float* V = g.data[0] + (size_t)scene * g.N[0] * g.N[1] * g.N[2] * C;
+        const size_t V = (size_t)scene * g.N[0] * g.N[1] * g.N[2] * C;  // first element of the scene
         for (int k = 0; k < C; ++k) {
             float acc = 0.0f;
             for (int d = 0; d < 8; ++d) {
@@ -55,7 +55,7 @@ __device__ void gather_feat(const GridDev& g, int scene, const Cell& c, float* f
                                 (dz ? c.f[2] : 1.0f - c.f[2]);
                 const size_t off =
                     (((size_t)(c.i[0] + dx) * g.N[1] + (c.i[1] + dy)) * g.N[2] + (c.i[2] + dz)) * C;
-                acc += w * V[off + k];
+                acc += w * grid_load(g, g.data[0], V + off + k);
             }
             feat[k * kLanes + lane] = acc;
         }
@@ -65,11 +65,11 @@ __device__ void gather_feat(const GridDev& g, int scene, const Cell& c, float* f
             float acc = 0.0f;
             for (int p = 0; p < 3; ++p) {
                 const int a = p, b = (p + 1) % 3;
-                const float* P = g.data[p] + (size_t)scene * g.N[a] * g.N[b] * C;
+                const size_t P = (size_t)scene * g.N[a] * g.N[b] * C;
                 for (int d = 0; d < 4; ++d) {
                     const int da = d >> 1, db = d & 1;
                     const float w = (da ? c.f[a] : 1.0f - c.f[a]) * (db ? c.f[b] : 1.0f - c.f[b]);
-                    acc += w * P[((size_t)(c.i[a] + da) * g.N[b] + (c.i[b] + db)) * C + k];
+                    acc += w * grid_load(g, g.data[p], P + ((size_t)(c.i[a] + da) * g.N[b] + (c.i[b] + db)) * C + k);
                 }
             }
             feat[k * kLanes + lane] = acc;

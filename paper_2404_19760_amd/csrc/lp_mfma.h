@@ -228,55 +228,84 @@ __device__ __forceinline__ Cell3 locate3(const GridDev& g, double x, double y, d
 }
 
 // The texels one lane reads for a sample: NCH consecutive channels of every corner (voxel: corner
-// 4dx + 2dy + dz; triplane: plane p, corner 2da + db at 4p + ..).  Loading and interpolating are
-// separate steps so that a kernel can issue the loads early and do other work while they fly.
-template <int KIND, int NCH>
+// 4dx + 2dy + dz; triplane: plane p, corner 2da + db at 4p + ..), as 16-byte loads of the grid's
+// storage type GT (lp_dtype: 4 fp32 or 8 bf16 / fp16 values each).  Loading and interpolating
+// are separate steps so that a kernel can issue the loads early and do other work meanwhile.
+template <int KIND, int NCH, int GT>
 struct GatherRaw {
     static constexpr int kCorners = KIND == LP_GRID_VOXEL ? 8 : 12;
-    float4 v[kCorners][NCH / 4];
+    static constexpr int kPerVec = GT == LP_F32 ? 4 : 8;
+    static constexpr int kVecs = NCH / kPerVec;
+    uint4 v[kCorners][kVecs];
 };
 
-template <int KIND, int C, int NCH>
+template <int KIND, int C, int NCH, int GT>
 __device__ __forceinline__ void gather_issue(const GridDev& g, int scene, const Cell3& c, int ch0,
-                                             GatherRaw<KIND, NCH>& raw)
+                                             GatherRaw<KIND, NCH, GT>& raw)
 {
+    constexpr int kVecs = GatherRaw<KIND, NCH, GT>::kVecs;
+    constexpr unsigned kElem = GT == LP_F32 ? 4u : 2u;  // bytes per stored value
     if constexpr (KIND == LP_GRID_VOXEL) {
-        const float* V = g.data[0] + (size_t)scene * g.N[0] * g.N[1] * g.N[2] * C;
+        const char* V = reinterpret_cast<const char*>(g.data[0]) + (size_t)scene * g.N[0] * g.N[1] * g.N[2] * C * kElem;
         const unsigned sz = C, sy = (unsigned)g.N[2] * C, sx = (unsigned)g.N[1] * sy;
         const unsigned base = (unsigned)c.i[0] * sx + (unsigned)c.i[1] * sy + (unsigned)c.i[2] * sz + ch0;
 #pragma unroll
         for (int d = 0; d < 8; ++d) {
             const int dx = d >> 2, dy = (d >> 1) & 1, dz = d & 1;
-            const float4* p = reinterpret_cast<const float4*>(V + (base + dx * sx + dy * sy + dz * sz));
+            const uint4* p = reinterpret_cast<const uint4*>(V + (size_t)(base + dx * sx + dy * sy + dz * sz) * kElem);
 #pragma unroll
-            for (int i = 0; i < NCH / 4; ++i) raw.v[d][i] = p[i];
+            for (int i = 0; i < kVecs; ++i) raw.v[d][i] = p[i];
         }
     } else {
 #pragma unroll
         for (int pl = 0; pl < 3; ++pl) {
             const int a = pl, b = (pl + 1) % 3;
-            const float* P = g.data[pl] + (size_t)scene * g.N[a] * g.N[b] * C;
+            const char* P = reinterpret_cast<const char*>(g.data[pl]) + (size_t)scene * g.N[a] * g.N[b] * C * kElem;
             const unsigned sb = C, sa = (unsigned)g.N[b] * C;
             const unsigned base = (unsigned)c.i[a] * sa + (unsigned)c.i[b] * sb + ch0;
 #pragma unroll
             for (int d = 0; d < 4; ++d) {
                 const int da = d >> 1, db = d & 1;
-                const float4* p = reinterpret_cast<const float4*>(P + (base + da * sa + db * sb));
+                const uint4* p = reinterpret_cast<const uint4*>(P + (size_t)(base + da * sa + db * sb) * kElem);
 #pragma unroll
-                for (int i = 0; i < NCH / 4; ++i) raw.v[4 * pl + d][i] = p[i];
+                for (int i = 0; i < kVecs; ++i) raw.v[4 * pl + d][i] = p[i];
             }
         }
     }
 }
 
-// feat[0..NCH) = the interpolated channels (Section 3.2: trilinear / sum of three bilinear)
-template <int KIND, int NCH>
-__device__ __forceinline__ void gather_finish(const Cell3& c, const GatherRaw<KIND, NCH>& raw, float* feat)
+// the stored values of one 16-byte load as fp32
+template <int GT>
+__device__ __forceinline__ void unpack_values(const uint4& u, float* out)
 {
+    const unsigned w[4] = {u.x, u.y, u.z, u.w};
+    if constexpr (GT == LP_F32) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) out[i] = __uint_as_float(w[i]);
+    } else if constexpr (GT == LP_BF16) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            out[2 * i] = __uint_as_float(w[i] << 16);
+            out[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            out[2 * i] = __half2float(__ushort_as_half((unsigned short)(w[i] & 0xffffu)));
+            out[2 * i + 1] = __half2float(__ushort_as_half((unsigned short)(w[i] >> 16)));
+        }
+    }
+}
+
+// feat[0..NCH) = the interpolated channels (Section 3.2: trilinear / sum of three bilinear)
+template <int KIND, int NCH, int GT>
+__device__ __forceinline__ void gather_finish(const Cell3& c, const GatherRaw<KIND, NCH, GT>& raw, float* feat)
+{
+    using R = GatherRaw<KIND, NCH, GT>;
 #pragma unroll
     for (int k = 0; k < NCH; ++k) feat[k] = 0.0f;
 #pragma unroll
-    for (int d = 0; d < GatherRaw<KIND, NCH>::kCorners; ++d) {
+    for (int d = 0; d < R::kCorners; ++d) {
         float w;
         if constexpr (KIND == LP_GRID_VOXEL) {
             const int dx = d >> 2, dy = (d >> 1) & 1, dz = d & 1;
@@ -286,23 +315,22 @@ __device__ __forceinline__ void gather_finish(const Cell3& c, const GatherRaw<KI
             w = (da ? c.f[a] : 1.0f - c.f[a]) * (db ? c.f[b] : 1.0f - c.f[b]);
         }
 #pragma unroll
-        for (int i = 0; i < NCH / 4; ++i) {
-            const float4 v = raw.v[d][i];
-            feat[4 * i + 0] += w * v.x;
-            feat[4 * i + 1] += w * v.y;
-            feat[4 * i + 2] += w * v.z;
-            feat[4 * i + 3] += w * v.w;
+        for (int i = 0; i < R::kVecs; ++i) {
+            float v[R::kPerVec];
+            unpack_values<GT>(raw.v[d][i], v);
+#pragma unroll
+            for (int e = 0; e < R::kPerVec; ++e) feat[R::kPerVec * i + e] += w * v[e];
         }
     }
 }
 
 // feat[0..NCH) = channels [ch0, ch0 + NCH) of h(x) in scene `scene`.
-template <int KIND, int C, int NCH>
+template <int KIND, int C, int NCH, int GT = LP_F32>
 __device__ __forceinline__ void gather_half(const GridDev& g, int scene, const Cell3& c, int ch0, float* feat)
 {
-    GatherRaw<KIND, NCH> raw;
-    gather_issue<KIND, C, NCH>(g, scene, c, ch0, raw);
-    gather_finish<KIND, NCH>(c, raw, feat);
+    GatherRaw<KIND, NCH, GT> raw;
+    gather_issue<KIND, C, NCH, GT>(g, scene, c, ch0, raw);
+    gather_finish<KIND, NCH, GT>(c, raw, feat);
 }
 
 // Ranges of rays per XCD: workgroup b runs on XCD b % 8, so giving XCD x the contiguous ray

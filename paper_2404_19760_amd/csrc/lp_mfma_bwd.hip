@@ -78,7 +78,7 @@ __device__ __forceinline__ Frag selection(int j, int grp, IndexFn index_of)
     return f;
 }
 
-template <int KIND, int C, int H, int NH, bool CC, int CG>
+template <int KIND, int C, int H, int NH, bool CC, int CG, int GT>
 __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev m, RaysDev rays, BwdIo io,
                                                                long long group_mul)
 {
@@ -164,7 +164,7 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
         q_next = load_ray_geom(rays, ray_of(seq));
         if constexpr (CG != C) set_direction_inputs(m, q_next);
         cell = sample_cell<CC>(g, q_next, min(j_last + slot_to_sample(col), S - 1));
-        sample_features<KIND, C, CG>(g, q_next, cell, grp, fh, fl);
+        sample_features<KIND, C, CG, GT>(g, q_next, cell, grp, fh, fl);
     }
 
     while (seq < sched.end) {
@@ -327,7 +327,7 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
             const RayGeom& qn = same ? q : q_next;
             cell = sample_cell<CC>(g, qn, min((same ? j0 - kBwdStep : j_last) + slot_to_sample(col), S - 1));
             __builtin_amdgcn_sched_barrier(0);
-            sample_features<KIND, C, CG>(g, qn, cell, grp, fh, fl);
+            sample_features<KIND, C, CG, GT>(g, qn, cell, grp, fh, fl);
             // the sampled features must be complete here (not sunk below the scatter)
 #pragma unroll
             for (int s = 0; s < KS1; ++s)
@@ -373,13 +373,13 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
     }
 }
 
-template <int KIND, int C, int H, int NH, bool CC, int CG>
+template <int KIND, int C, int H, int NH, bool CC, int CG, int GT = LP_F32>
 hipError_t launch_bwd(const GridDev& g, const MlpDev& m, const RaysDev& rays, const BwdIo& io, int n_cu,
                        hipStream_t stream)
 {
     constexpr int kLdsBytes = MlpLds<C, H, NH, true, kBwdNB>::bytes(kWaves);
     static_assert(kLdsBytes <= 160 * 1024, "LDS budget of a gfx950 compute unit");
-    auto kernel = bwd_mfma_kernel<KIND, C, H, NH, CC, CG>;
+    auto kernel = bwd_mfma_kernel<KIND, C, H, NH, CC, CG, GT>;
     hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (e != hipSuccess) return e;
     const int blocks = mfma_bwd_records(n_cu) / kWaves;  // every wave writes a record, busy or not
@@ -404,6 +404,15 @@ hipError_t dispatch_bwd(const GridDev& g, const MlpDev& m, const RaysDev& rays, 
                          hipStream_t stream)
 {
     const int C = m.dims[0], CG = g.C, H = m.dims[1], NH = m.n_layers - 1;
+    // grids stored in bf16 / fp16: plain inputs, no contract coordinates
+#define LP_CASE(c, h, nh)                                                                                  \
+    if (C == c && CG == c && H == h && NH == nh && g.dtype != LP_F32 && !(g.contract > 0.0))               \
+        return g.dtype == LP_BF16 ? launch_bwd<KIND, c, h, nh, false, c, LP_BF16>(g, m, rays, io, n_cu, stream) \
+                                  : launch_bwd<KIND, c, h, nh, false, c, LP_F16>(g, m, rays, io, n_cu, stream);
+    LP_CASE(16, 32, 1) LP_CASE(16, 64, 1) LP_CASE(32, 32, 1) LP_CASE(32, 64, 1)
+    LP_CASE(16, 32, 2) LP_CASE(16, 64, 2) LP_CASE(32, 32, 2) LP_CASE(32, 64, 2)
+#undef LP_CASE
+    if (g.dtype != LP_F32) return hipErrorInvalidValue;
 #define LP_CASE(c, cg, h, nh)                                                                     \
     if (C == c && CG == cg && H == h && NH == nh)                                                 \
         return g.contract > 0.0 ? launch_bwd<KIND, c, h, nh, true, cg>(g, m, rays, io, n_cu, stream) \

@@ -19,7 +19,7 @@ constexpr int kWaves = 4;
 // NB = N blocks of 32 samples per step.  NB = 2: lane l owns sample l of the 64-sample step.
 // NB = 1 (half the registers, two waves per SIMD for the wide MLPs): both lane groups hold the
 // decoder outputs of sample (lane & 31); group 0 alone accumulates.
-template <int KIND, int C, int H, int NH, int NB, bool CC, int CG>
+template <int KIND, int C, int H, int NH, int NB, bool CC, int CG, int GT>
 __global__ __launch_bounds__(kWaves * 64) void fwd_mfma_kernel(GridDev g, MlpDev m, RaysDev rays, FwdOut out)
 {
     constexpr int kStep = 32 * NB;
@@ -40,10 +40,10 @@ __global__ __launch_bounds__(kWaves * 64) void fwd_mfma_kernel(GridDev g, MlpDev
         for (int j0 = 0; j0 < S; j0 += kStep) {
             struct { float z[4]; } a;
             if constexpr (NB == 2) {
-                forward_outputs<KIND, C, H, NH, CC, CG>(g, lds, q, j0, S, lane, a.z);
+                forward_outputs<KIND, C, H, NH, CC, CG, GT>(g, lds, q, j0, S, lane, a.z);
             } else {
                 StepActs<C, H, NH, NB> full;
-                forward_step<KIND, C, H, NH, false, NB, false, CC, CG>(g, lds, q, j0, S, lane, full);
+                forward_step<KIND, C, H, NH, false, NB, false, CC, CG, GT>(g, lds, q, j0, S, lane, full);
 #pragma unroll
                 for (int k = 0; k < 4; ++k) a.z[k] = full.z[k];
             }
@@ -79,12 +79,12 @@ __global__ __launch_bounds__(kWaves * 64) void fwd_mfma_kernel(GridDev g, MlpDev
     }
 }
 
-template <int KIND, int C, int H, int NH, int NB, bool CC, int CG>
+template <int KIND, int C, int H, int NH, int NB, bool CC, int CG, int GT = LP_F32>
 hipError_t launch_fwd(const GridDev& g, const MlpDev& m, const RaysDev& rays, const FwdOut& out, int n_cu,
                       hipStream_t stream)
 {
     constexpr int kLdsBytes = MlpLds<C, H, NH, false, NB>::bytes(kWaves);
-    auto kernel = fwd_mfma_kernel<KIND, C, H, NH, NB, CC, CG>;
+    auto kernel = fwd_mfma_kernel<KIND, C, H, NH, NB, CC, CG, GT>;
     hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (e != hipSuccess) return e;
     // persistent grid: as many workgroups as fit a compute unit's registers, a multiple of the 8 XCDs, no more than the rays need
@@ -101,6 +101,15 @@ hipError_t dispatch_fwd(const GridDev& g, const MlpDev& m, const RaysDev& rays, 
                         hipStream_t stream)
 {
     const int C = m.dims[0], CG = g.C, H = m.dims[1], NH = m.n_layers - 1;
+    // grids stored in bf16 / fp16: plain inputs, no contract coordinates
+#define LP_CASE(c, h, nh)                                                                                     \
+    if (C == c && CG == c && H == h && NH == nh && g.dtype != LP_F32 && !(g.contract > 0.0))                  \
+        return g.dtype == LP_BF16 ? launch_fwd<KIND, c, h, nh, 2, false, c, LP_BF16>(g, m, rays, out, n_cu, stream) \
+                                  : launch_fwd<KIND, c, h, nh, 2, false, c, LP_F16>(g, m, rays, out, n_cu, stream);
+    LP_CASE(16, 32, 1) LP_CASE(16, 64, 1) LP_CASE(32, 32, 1) LP_CASE(32, 64, 1)
+    LP_CASE(16, 32, 2) LP_CASE(16, 64, 2) LP_CASE(32, 32, 2) LP_CASE(32, 64, 2)
+#undef LP_CASE
+    if (g.dtype != LP_F32) return hipErrorInvalidValue;
 #define LP_CASE(c, cg, h, nh)                                                                          \
     if (C == c && CG == cg && H == h && NH == nh)                                                      \
         return g.contract > 0.0 ? launch_fwd<KIND, c, h, nh, 2, true, cg>(g, m, rays, out, n_cu, stream) \
@@ -126,6 +135,7 @@ bool mfma_supported(const GridDev& g, const MlpDev& m)
     const bool plain = m.n_enc == 0 && m.dims[0] == g.C && (g.C == 16 || g.C == 32);
     const bool with_dir = m.n_enc > 0 && g.C == 16 && m.dims[0] == 32 && m.n_enc <= 16 && !(g.contract > 0.0);
     if (!plain && !with_dir) return false;
+    if (g.dtype != LP_F32 && (!plain || g.contract > 0.0)) return false;
     if (m.n_feat != 3 || m.feat_act != 0 || m.dims[m.n_layers] != 4) return false;
     if (m.n_layers != 2 && m.n_layers != 3) return false;
     const int H = m.dims[1];

@@ -199,17 +199,17 @@ __host__ __device__ constexpr int sample_to_slot(int smp)
 // Input features of one sample column as operand fragments: lane (col, grp) holds inputs
 // [grp C/2, (grp+1) C/2).  CG == C: all inputs are grid channels.  CG == C/2: lane group 0 holds
 // the CG grid channels, lane group 1 the per-ray direction inputs q.extra.
-template <int KIND, int C, int CG>
+template <int KIND, int C, int CG, int GT = LP_F32>
 __device__ __forceinline__ void sample_features(const GridDev& g, const RayGeom& q, const Cell3& c, int grp,
                                                 Frag (&fh)[C / 16], Frag (&fl)[C / 16])
 {
     float feat[C / 2];
     if constexpr (CG == C) {
-        gather_half<KIND, C, C / 2>(g, q.scene, c, grp * (C / 2), feat);
+        gather_half<KIND, C, C / 2, GT>(g, q.scene, c, grp * (C / 2), feat);
     } else {
         static_assert(2 * CG == C && CG == 16, "direction inputs take the second half of 32 inputs");
         if (grp == 0) {
-            gather_half<KIND, CG, CG>(g, q.scene, c, 0, feat);
+            gather_half<KIND, CG, CG, GT>(g, q.scene, c, 0, feat);
         } else {
 #pragma unroll
             for (int e = 0; e < CG; ++e) feat[e] = q.extra[e];
@@ -263,7 +263,7 @@ __device__ __forceinline__ void mlp_forward(const uint4* lds, int lane, StepActs
 
 // Sampling + MLP forward of one step: lane (col, grp) samples its half of the channels of
 // sample col of every N block (PERM: of the permuted step, see slot_to_sample).
-template <int KIND, int C, int H, int NH, bool BWD, int NB, bool PERM = false, bool CC = false, int CG = C>
+template <int KIND, int C, int H, int NH, bool BWD, int NB, bool PERM = false, bool CC = false, int CG = C, int GT = LP_F32>
 __device__ __forceinline__ void forward_step(const GridDev& g, const uint4* lds, const RayGeom& q, int j0, int S,
                                              int lane, StepActs<C, H, NH, NB>& a)
 {
@@ -273,7 +273,7 @@ __device__ __forceinline__ void forward_step(const GridDev& g, const uint4* lds,
         const int j = min(j0 + 32 * nb + (PERM ? slot_to_sample(col) : col), S - 1);
         const Cell3 c = sample_cell<CC>(g, q, j);
         a.cell[nb] = c;
-        sample_features<KIND, C, CG>(g, q, c, grp, a.fh[nb], a.fl[nb]);
+        sample_features<KIND, C, CG, GT>(g, q, c, grp, a.fh[nb], a.fl[nb]);
     }
     mlp_forward<C, H, NH, BWD, NB>(lds, lane, a);
 }
@@ -283,7 +283,7 @@ __device__ __forceinline__ void forward_step(const GridDev& g, const uint4* lds,
 // remaining layers one N block after the other, so that at most one block's accumulators and
 // activations are alive at a time (registers for a second wave per SIMD).  z = outputs of
 // sample j0 + lane.
-template <int KIND, int C, int H, int NH, bool CC, int CG = C>
+template <int KIND, int C, int H, int NH, bool CC, int CG = C, int GT = LP_F32>
 __device__ __forceinline__ void forward_outputs(const GridDev& g, const uint4* lds, const RayGeom& q, int j0,
                                                 int S, int lane, float (&z)[4])
 {
@@ -297,7 +297,7 @@ __device__ __forceinline__ void forward_outputs(const GridDev& g, const uint4* l
     for (int nb = 0; nb < 2; ++nb) {
         const int j = min(j0 + 32 * nb + col, S - 1);
         const Cell3 c = sample_cell<CC>(g, q, j);
-        sample_features<KIND, C, CG>(g, q, c, grp, fh[nb], fl[nb]);
+        sample_features<KIND, C, CG, GT>(g, q, c, grp, fh[nb], fl[nb]);
     }
     Frag h1h[2][KSH], h1l[2][KSH];
     {

@@ -76,10 +76,13 @@ def mse_upstream(rgb64: np.ndarray, target: np.ndarray, scene=None, n_scenes: in
     return (2.0 * (rgb64 - target.astype(np.float64)) / (3.0 * per[:, None])).astype(np.float32)
 
 
-def run_gpu(lp, inp, p_rgb, p_alpha=None, p_depth=None, math_mode=0, device="cuda:0"):
-    """Forward + backward on the GPU through the C ABI; everything returned as numpy."""
+def run_gpu(lp, inp, p_rgb, p_alpha=None, p_depth=None, math_mode=0, device="cuda:0", grid_dtype=None):
+    """Forward + backward on the GPU through the C ABI; everything returned as numpy.
+    grid_dtype: torch dtype the grid is STORED in on the GPU (gradients stay float32)."""
     import torch
     grid, mlp, rays, bg = lp.to_device(inp, device)
+    if grid_dtype is not None:
+        grid.data = [t.to(grid_dtype) for t in grid.data]
     rgb, alpha, depth, cache = lp.render_fwd(grid, mlp, rays, bg, math_mode)
     up = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device)
     d_grid, dW, db = lp.render_bwd(grid, mlp, rays, bg, up(p_rgb), cache, up(p_alpha), up(p_depth), math_mode)
@@ -89,7 +92,7 @@ def run_gpu(lp, inp, p_rgb, p_alpha=None, p_depth=None, math_mode=0, device="cud
                 d_grid=[cpu(t) for t in d_grid], dW=[cpu(t) for t in dW], db=[cpu(t) for t in db])
 
 
-def check_case(lp, oracle, inp, math_mode=0, aux_grads=True, seed=0, label="", max_strict_fail=0.5):
+def check_case(lp, oracle, inp, math_mode=0, aux_grads=True, seed=0, label="", max_strict_fail=0.5, grid_dtype=None):
     """Full parity of one problem: forward outputs and every gradient tensor."""
     import lp_inputs
     prob = oracle.Problem(inp)
@@ -103,7 +106,7 @@ def check_case(lp, oracle, inp, math_mode=0, aux_grads=True, seed=0, label="", m
     upper = oracle.render_bwd(prob, p_rgb, p_alpha, p_depth, kink_band=c, kink_side=+1)
     lower = oracle.render_bwd(prob, p_rgb, p_alpha, p_depth, kink_band=c, kink_side=-1)
     env = lambda i, j: (lower[i][j], upper[i][j])
-    g = run_gpu(lp, inp, p_rgb, p_alpha, p_depth, math_mode)
+    g = run_gpu(lp, inp, p_rgb, p_alpha, p_depth, math_mode, grid_dtype=grid_dtype)
     worst = {}
     worst["rgb"] = close(g["rgb"], o_rgb, FWD_RTOL, f"{label} rgb")
     worst["alpha"] = close(g["alpha"], o_alpha, FWD_RTOL, f"{label} alpha")

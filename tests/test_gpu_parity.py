@@ -99,6 +99,25 @@ def test_contract_workload_on_a_ray_subset(lp, oracle):
               flush=True)
 
 
+
+# ------------------------------------------------------------------ reduced-precision grid storage
+
+@pytest.mark.parametrize("kind", [VOXEL, TRIPLANE])
+@pytest.mark.parametrize("dtype", ["bfloat16", "float16"])
+def test_reduced_precision_grid_storage(lp, oracle, kind, dtype):
+    """Grid stored in bf16 / fp16 (half the bytes per sample), gradients in fp32.  The stored
+    values are exactly representable, so the oracle simply receives them widened: same tolerances."""
+    import torch
+    tdt = getattr(torch, dtype)
+    for channels, dims in ((5, (5, 7, 4)), (16, (16, 32, 4)), (32, (32, 64, 64, 4))):
+        inp = lp_inputs.make_small(kind, channels=channels, res=(9, 8, 10), mlp_dims=dims, n_rays=400, samples=70,
+                                   seed=59, n_scenes=2, grid_std=0.4)
+        stored = [torch.from_numpy(g).to(tdt) for g in inp.grid]
+        widened = dataclasses.replace(inp, grid=[t.to(torch.float32).numpy() for t in stored])
+        for mode in _modes(lp, widened):
+            print(mode, check_case(lp, oracle, widened, mode, label=f"{dtype} kind={kind} C={channels} mode={mode}",
+                                   grid_dtype=tdt), flush=True)
+
 # ------------------------------------------------------------------ the five configurations
 
 def test_config_tiny_full(lp, oracle):
