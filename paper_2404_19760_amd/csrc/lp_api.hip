@@ -173,15 +173,20 @@ lp_status run_fwd(const lp::GridDev& g, const lp::MlpDev& m, const lp::RaysDev& 
 }
 
 // Backward kernels plus the reduction of the per-wave / per-block records into io.dW / io.db.
-lp_status run_bwd(const lp::GridDev& g, const lp::MlpDev& m, const lp::RaysDev& r, const lp::BwdIo& io,
+lp_status run_bwd(const lp::GridDev& g, const lp::MlpDev& m, const lp::RaysDev& r, const lp::BwdIo& io_in,
                   bool fast_bwd, int max_records, int n_cu, hipStream_t s)
 {
     if (fast_bwd) {
-        hipError_t e = lp::launch_bwd_mfma(g, m, r, io, n_cu, s);
+        hipError_t e = lp::launch_bwd_mfma(g, m, r, io_in, n_cu, s);
         if (e != hipSuccess) return hip_fail("backward matrix-core kernel launch", e);
         return LP_OK;
     }
-    const size_t lds = generic_bwd_lds(m);
+    size_t lds = generic_bwd_lds(m);
+    lp::BwdIo io = io_in;
+    if (lds > kMaxLds) {   // keep one copy of the parameters in LDS, accumulate gradients in the records
+        lds -= sizeof(float) * (size_t)m.param_total;
+        io.acc_in_record = 1;
+    }
     if (lds > kMaxLds)
         return fail(LP_ERR_UNSUPPORTED, "MLP too large for the generic backward kernel's LDS budget");
     hipError_t e = hipFuncSetAttribute((const void*)lp::bwd_generic_kernel,
@@ -729,8 +734,12 @@ lp_status lp_splat_bwd(const lp_grid* target, const lp_rays* rays, const lp_spla
     std::string err;
     int n_cu = 0;
     if (compute_units(&n_cu, &err)) return fail(LP_ERR_HIP, err);
-    const size_t lds = sizeof(float) * (2 * (size_t)m.param_total +
-                                        ((size_t)m.act_total + 2 * (size_t)m.max_width + sd.n_in) * kGenericLanes);
+    size_t lds = sizeof(float) * (2 * (size_t)m.param_total +
+                                  ((size_t)m.act_total + 2 * (size_t)m.max_width + sd.n_in) * kGenericLanes);
+    if (lds > kMaxLds) {   // keep one copy of the parameters in LDS, accumulate gradients in the records
+        lds -= sizeof(float) * (size_t)m.param_total;
+        io.acc_in_record = 1;
+    }
     if (lds > kMaxLds) return fail(LP_ERR_UNSUPPORTED, "MLP too large for the Splatter backward kernel's LDS budget");
     hipError_t e = hipFuncSetAttribute((const void*)lp::splat_bwd_generic_kernel,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

@@ -67,6 +67,7 @@ struct BwdIo {
     float bg[LP_MAX_FEATURES];
     float* ws;         // per-wave (or per-block) partial sums of the MLP gradients
     int ws_stride;     // floats between consecutive partial-sum records
+    int acc_in_record; // generic kernels: accumulate MLP gradients in the record itself, not in LDS
 };
 
 // element `idx` of a grid tensor as fp32

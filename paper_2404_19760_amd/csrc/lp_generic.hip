@@ -336,8 +336,11 @@ __global__ __launch_bounds__(kLanes) void splat_bwd_generic_kernel(GridDev tgt, 
 {
     extern __shared__ float smem[];
     float* sW = smem;
-    float* sdW = sW + m.param_total;
-    float* acts = sdW + m.param_total;
+    // gradient accumulators of the block: in LDS, or (MLPs whose two copies do not fit) directly in
+    // the block's record in the workspace; every element has one owner lane either way
+    float* rec = io.ws + (size_t)blockIdx.x * io.ws_stride;
+    float* sdW = io.acc_in_record ? rec : sW + m.param_total;
+    float* acts = sW + (io.acc_in_record ? 1 : 2) * m.param_total;
     float* dz0 = acts + m.act_total * kLanes;
     float* dz1 = dz0 + m.max_width * kLanes;
     stage_params(m, sW);
@@ -379,8 +382,8 @@ __global__ __launch_bounds__(kLanes) void splat_bwd_generic_kernel(GridDev tgt, 
             for (int k = 0; k < sp.n_in; ++k) sp.d_feats[(size_t)ray * sp.n_in + k] = dfe[k * kLanes + lane];
     }
     __syncthreads();
-    float* rec = io.ws + (size_t)blockIdx.x * io.ws_stride;
-    for (int i = threadIdx.x; i < m.param_total; i += blockDim.x) rec[i] = sdW[i];
+    if (!io.acc_in_record)
+        for (int i = threadIdx.x; i < m.param_total; i += blockDim.x) rec[i] = sdW[i];
 }
 
 namespace {
@@ -441,8 +444,11 @@ __global__ __launch_bounds__(kLanes) void bwd_generic_kernel(GridDev g, MlpDev m
 {
     extern __shared__ float smem[];
     float* sW = smem;
-    float* sdW = sW + m.param_total;
-    float* acts = sdW + m.param_total;
+    // gradient accumulators of the block: in LDS, or (MLPs whose two copies do not fit) directly in
+    // the block's record in the workspace; every element has one owner lane either way
+    float* rec = io.ws + (size_t)blockIdx.x * io.ws_stride;
+    float* sdW = io.acc_in_record ? rec : sW + m.param_total;
+    float* acts = sW + (io.acc_in_record ? 1 : 2) * m.param_total;
     float* dz0 = acts + m.act_total * kLanes;
     float* dz1 = dz0 + m.max_width * kLanes;
     float* pcol = dz1 + m.max_width * kLanes;
@@ -512,8 +518,8 @@ __global__ __launch_bounds__(kLanes) void bwd_generic_kernel(GridDev g, MlpDev m
     }
     __syncthreads();
     // this block's partial sums; a second kernel adds all records into dW / db
-    float* rec = io.ws + (size_t)blockIdx.x * io.ws_stride;
-    for (int i = threadIdx.x; i < m.param_total; i += blockDim.x) rec[i] = sdW[i];
+    if (!io.acc_in_record)
+        for (int i = threadIdx.x; i < m.param_total; i += blockDim.x) rec[i] = sdW[i];
 }
 
 // dW[l] += sum over records, db[l] likewise; one thread per parameter, fp64 running sum,

@@ -43,6 +43,19 @@ def test_small_odd_shapes_generic(lp, oracle, kind):
     print(check_case(lp, oracle, inp, lp.LP_MATH_GENERIC, label=f"small kind={kind}"), flush=True)
 
 
+def test_wide_mlp_on_the_generic_kernels(lp, oracle):
+    """An MLP whose parameters no longer fit twice into LDS: the generic backward accumulates the
+    weight gradients in its workspace records; one that does not fit at all is refused."""
+    inp = lp_inputs.make_small(VOXEL, channels=24, res=(6, 5, 7), mlp_dims=(24, 96, 96, 4), n_rays=90, samples=21,
+                               seed=45, grid_std=0.3)
+    print(check_case(lp, oracle, inp, lp.LP_MATH_GENERIC, label="wide generic"), flush=True)
+    huge = lp_inputs.make_small(VOXEL, channels=8, mlp_dims=(8, 256, 256, 4), n_rays=8)
+    grid, mlp, rays, bg = lp.to_device(huge)
+    with pytest.raises(lp.LightplaneError) as e:
+        lp.render_fwd(grid, mlp, rays, bg, lp.LP_MATH_GENERIC)
+    assert e.value.status == lp.LP_ERR_UNSUPPORTED
+
+
 @pytest.mark.parametrize("kind", [VOXEL, TRIPLANE])
 def test_clamped_samples_outside_the_box(lp, oracle, kind):
     """Box [-0.4, 0.4]^3 is much smaller than the ray span: most samples clamp to the border."""

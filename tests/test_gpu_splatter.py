@@ -48,6 +48,17 @@ def test_splatter_with_mlp(lp, oracle, kind, hidden, n_freq, prior_channels):
     print(check_case_splat(lp, oracle, sp, label=f"splat kind={kind} hidden={hidden}"), flush=True)
 
 
+def test_splatter_with_the_papers_mlp_size(lp, oracle):
+    """32-channel features, prior and target, 3-layer MLP of width 64 (appendix, "Experimental
+    Details"): two copies of the parameters no longer fit in LDS, the backward accumulates the
+    MLP gradients in its records instead."""
+    sp = lp_inputs.make_splat_small(VOXEL, channels=32, res=(9, 8, 10), n_in=32, hidden=(64, 64), n_freq=0,
+                                    prior_channels=32, prior_res=(7, 6, 5), n_rays=150, samples=20, seed=99,
+                                    bias_std=0.1)
+    assert sp.mlp_dims == (67, 64, 64, 32)
+    print(check_case_splat(lp, oracle, sp, label="splat paper-size MLP"), flush=True)
+
+
 def test_splatter_with_contraction_and_empty_cells(lp, oracle):
     """Contract coordinates; a fine target that most rays never touch (cells with zero weight)."""
     sp = lp_inputs.make_splat_small(VOXEL, channels=4, res=(20, 18, 22), n_in=3, hidden=(8,), n_freq=0,

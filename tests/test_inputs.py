@@ -71,7 +71,7 @@ def test_splat_workloads():
     w = lp_inputs.SPLAT_WORKLOADS["splat_naive"]
     assert (w.res, w.channels, w.n_in, w.samples) == ((160, 160, 160), 32, 32, 160)
     sp = lp_inputs.make_splat_inputs("splat_mlp")
-    assert sp.mlp_dims == (16 + 16 + 3, 32, 32, 16) and sp.prior[0].shape == (1, 160, 160, 160, 16)
-    assert sp.n_rays == 4 * 64 * 64 and sp.feats.shape == (sp.n_rays, 16)
+    assert sp.mlp_dims == (32 + 32 + 3, 64, 64, 32) and sp.prior[0].shape == (1, 160, 160, 160, 32)
+    assert sp.n_rays == 4 * 64 * 64 and sp.feats.shape == (sp.n_rays, 32)
     a = lp_inputs.make_splat_inputs("splat_mlp")
     assert np.array_equal(a.feats, sp.feats) and np.array_equal(a.weights[1], sp.weights[1])
