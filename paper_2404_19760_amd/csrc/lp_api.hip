@@ -201,8 +201,7 @@ lp_status run_bwd(const lp::GridDev& g, const lp::MlpDev& m, const lp::RaysDev& 
                        (int)tiles_per_block);
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail("backward generic kernel launch", e);
-    const int threads = 256;
-    hipLaunchKernelGGL(lp::reduce_params_kernel, dim3((m.param_total + threads - 1) / threads), dim3(threads), 0, s,
+    hipLaunchKernelGGL(lp::reduce_params_kernel, dim3((m.param_total + 63) / 64), dim3(lp::kReduceThreads), 0, s,
                        m, io, (int)blocks);
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail("parameter-gradient reduction launch", e);
@@ -670,8 +669,8 @@ lp_status lp_splat_fwd(const lp_grid* target, const lp_rays* rays, const lp_spla
     }
     for (int p = 0; p < n_planes; ++p) {
         const long long cells = plane_cells(target, p);
-        hipLaunchKernelGGL(lp::splat_normalise_kernel, dim3((unsigned)((cells + threads - 1) / threads)), dim3(threads),
-                           0, s, theta[p], theta_w[p], cells, target->C);
+        hipLaunchKernelGGL(lp::splat_normalise_kernel, dim3((unsigned)((cells * target->C + threads - 1) / threads)),
+                           dim3(threads), 0, s, theta[p], theta_w[p], cells, target->C);
     }
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail("Splatter normalisation kernel launch", e);
@@ -754,8 +753,7 @@ lp_status lp_splat_bwd(const lp_grid* target, const lp_rays* rays, const lp_spla
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail("Splatter backward kernel launch", e);
     if (m.param_total > 0) {
-        const int threads = 256;
-        hipLaunchKernelGGL(lp::reduce_params_kernel, dim3((m.param_total + threads - 1) / threads), dim3(threads), 0,
+        hipLaunchKernelGGL(lp::reduce_params_kernel, dim3((m.param_total + 63) / 64), dim3(lp::kReduceThreads), 0,
                            s, m, io, (int)blocks);
         e = hipGetLastError();
         if (e != hipSuccess) return hip_fail("parameter-gradient reduction launch", e);

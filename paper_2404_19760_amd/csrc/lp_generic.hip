@@ -313,14 +313,13 @@ __global__ __launch_bounds__(kLanes) void splat_fwd_generic_kernel(GridDev tgt, 
     }
 }
 
-// theta[cell][k] /= theta_w[cell] (0 where nothing landed); one thread per cell
+// theta[cell][k] /= theta_w[cell] (0 where nothing landed); one thread per element
 __global__ void splat_normalise_kernel(float* theta, const float* theta_w, long long cells, int C)
 {
-    const long long c = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (c >= cells) return;
-    const float w = theta_w[c];
-    const float s = w > 0.0f ? 1.0f / w : 0.0f;
-    for (int k = 0; k < C; ++k) theta[c * C + k] = w > 0.0f ? theta[c * C + k] * s : 0.0f;
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= cells * C) return;
+    const float w = theta_w[i / C];
+    theta[i] = w > 0.0f ? theta[i] / w : 0.0f;
 }
 
 __global__ void fill_zero_kernel(float* p, long long n)
@@ -522,14 +521,21 @@ __global__ __launch_bounds__(kLanes) void bwd_generic_kernel(GridDev g, MlpDev m
         for (int i = threadIdx.x; i < m.param_total; i += blockDim.x) rec[i] = sdW[i];
 }
 
-// dW[l] += sum over records, db[l] likewise; one thread per parameter, fp64 running sum,
-// fixed order (deterministic).
-__global__ void reduce_params_kernel(MlpDev m, BwdIo io, int n_records)
+// dW[l] += sum over records, db[l] likewise.  A block of 1024 threads handles 64 consecutive
+// parameters: thread (p, q) sums records q, q + 16, q + 32, ... of parameter p in fp64, then the
+// 16 partial sums of a parameter are added in a fixed order (deterministic).
+__global__ __launch_bounds__(kReduceThreads) void reduce_params_kernel(MlpDev m, BwdIo io, int n_records)
 {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= m.param_total) return;
+    __shared__ double part[kReduceThreads];
+    const int p = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const int i = blockIdx.x * 64 + p;
     double s = 0.0;
-    for (int r = 0; r < n_records; ++r) s += (double)io.ws[(size_t)r * io.ws_stride + i];
+    if (i < m.param_total)
+        for (int r = q; r < n_records; r += kReduceThreads / 64) s += (double)io.ws[(size_t)r * io.ws_stride + i];
+    part[threadIdx.x] = s;
+    __syncthreads();
+    if (q != 0 || i >= m.param_total) return;
+    for (int k = 1; k < kReduceThreads / 64; ++k) s += part[k * 64 + p];
     for (int l = 0; l < m.n_layers; ++l) {
         const int nw = m.dims[l] * m.dims[l + 1];
         if (i >= m.w_off[l] && i < m.w_off[l] + nw) {

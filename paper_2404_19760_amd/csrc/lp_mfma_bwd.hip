@@ -393,8 +393,7 @@ hipError_t launch_bwd(const GridDev& g, const MlpDev& m, const RaysDev& rays, co
                        group_mul);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const int threads = 256;
-    hipLaunchKernelGGL(reduce_params_kernel, dim3((m.param_total + threads - 1) / threads), dim3(threads), 0, stream,
+    hipLaunchKernelGGL(reduce_params_kernel, dim3((m.param_total + 63) / 64), dim3(kReduceThreads), 0, stream,
                        m, io, blocks * kWaves);
     return hipGetLastError();
 }
