@@ -169,6 +169,19 @@ def test_zero_rays_is_a_noop(lp):
     assert rgb.shape == (0, 3) and all(float(t.abs().sum()) == 0.0 for t in d_grid + dW + db)
 
 
+def test_optional_outputs_may_be_null(lp):
+    """alpha, depth and the ray cache are optional outputs of the forward, in both kernel families."""
+    import torch
+    inp = lp_inputs.make_small(VOXEL, channels=16, mlp_dims=(16, 32, 4), n_rays=77, samples=40, seed=5)
+    grid, mlp, rays, bg = lp.to_device(inp)
+    for mode in (lp.LP_MATH_GENERIC, lp.LP_MATH_BF16X3):
+        full = lp.render_fwd(grid, mlp, rays, bg, mode)
+        rgb = torch.empty_like(full[0])
+        lp.lp_render_fwd(grid, mlp, rays, bg, rgb, None, None, None, mode)
+        torch.cuda.synchronize()
+        assert torch.equal(rgb, full[0])
+
+
 def test_zero_density_renders_background_exactly(lp):
     import torch
     inp = lp_inputs.make_small(VOXEL, channels=16, mlp_dims=(16, 32, 4), n_rays=100, samples=70)
