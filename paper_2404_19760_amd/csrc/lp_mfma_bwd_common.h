@@ -131,18 +131,36 @@ __device__ __forceinline__ void scatter_channels(const GridDev& g, float* const 
 #pragma unroll
             for (int k = 0; k < 4; ++k) atomicAdd(reinterpret_cast<float*>(Vd[k] + 4u * (prev + lane_off)), acc[k]);
         };
+        // the records are read two samples ahead of their use, so that the LDS latency is covered by
+        // the work on the samples in between
+        constexpr int kAhead = 2;
+        float4 wq[kAhead];
+        unsigned bq[kAhead];
+#pragma unroll
+        for (int r = 0; r < kAhead; ++r) {
+            const float* rec = info + d_row(r, grp) * 16;
+            wq[r] = reinterpret_cast<const float4*>(rec)[dz];
+            bq[r] = reinterpret_cast<const unsigned*>(rec)[8];
+        }
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const float* rec = info + d_row(r, grp) * 16;
-            const float4 w4 = reinterpret_cast<const float4*>(rec)[dz];
-            const unsigned base = reinterpret_cast<const unsigned*>(rec)[8];
+            const float4 w4 = wq[r % kAhead];
+            const unsigned base = bq[r % kAhead];
+            if (r + kAhead < 16) {
+                const float* rec = info + d_row(r + kAhead, grp) * 16;
+                wq[r % kAhead] = reinterpret_cast<const float4*>(rec)[dz];
+                bq[r % kAhead] = reinterpret_cast<const unsigned*>(rec)[8];
+            }
             const float w[4] = {w4.x, w4.y, w4.z, w4.w};
             const float v = dFt[r];
-            if (r > 0 && base != prev) flush();
-            const bool fresh = r == 0 || base != prev;
+            if (r > 0 && base != prev) {
+                flush();
+#pragma unroll
+                for (int k = 0; k < 4; ++k) acc[k] = 0.0f;
+            }
             prev = base;
 #pragma unroll
-            for (int k = 0; k < 4; ++k) acc[k] = fresh ? w[k] * v : acc[k] + w[k] * v;
+            for (int k = 0; k < 4; ++k) acc[k] = r == 0 ? w[k] * v : acc[k] + w[k] * v;
         }
         flush();
     } else if constexpr (KIND == LP_GRID_VOXEL) {
