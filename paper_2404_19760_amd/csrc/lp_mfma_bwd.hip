@@ -80,7 +80,7 @@ __device__ __forceinline__ Frag selection(int j, int grp, IndexFn index_of)
 
 template <int KIND, int C, int H, int NH, bool CC, int CG, int GT>
 __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev m, RaysDev rays, BwdIo io,
-                                                               long long group_mul)
+                                                               long long group_mul, long long group_step)
 {
     using L = MlpLds<C, H, NH, true, kBwdNB>;
     constexpr int MB = L::MB, KS1 = L::KS1, KSH = L::KSH;
@@ -139,40 +139,51 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
     // Rays are taken in groups of kWaves neighbours (one per wave of a workgroup), and the groups
     // in a scrambled order: neighbouring rays add into the same lines of the grid gradient, and
     // atomic adds of many waves to one line queue up behind each other at its L2 channel.
+    // Workgroup (xcd, b) visits the group sequence numbers xcd_begin + b, + blocks_per_xcd, ...;
+    // sequence number s stands for group (s * mul) mod n_groups, advanced incrementally
+    // (group_step = blocks_per_xcd * mul mod n_groups) so that the loop needs no division.
     const long long n_groups = (rays.M + kWaves - 1) / kWaves;
-    const RaySchedule sched = ray_schedule(n_groups * kWaves, kWaves);
     const int S = rays.S;
-
     const int j_last = ((S - 1) / kBwdStep) * kBwdStep;
-    auto ray_of = [&](long long seq) { return ((seq / kWaves) * group_mul % n_groups) * kWaves + seq % kWaves; };
-    // first / next sequence number of this wave that stands for a ray (the last group is padded)
-    auto valid_from = [&](long long seq) {
-        while (seq < sched.end && ray_of(seq) >= rays.M) seq += sched.stride;
-        return seq;
+    const int blocks_per_xcd = gridDim.x / 8;
+    const long long per_xcd = (n_groups + 7) / 8;
+    const long long seq_begin = per_xcd * (blockIdx.x % 8) + blockIdx.x / 8;
+    const long long seq_last = min(per_xcd * (blockIdx.x % 8 + 1), n_groups);   // end of this XCD's range
+    struct Cursor { long long seq, group; };
+    auto ray_of = [&](const Cursor& c) { return c.group * kWaves + wave; };
+    // next position of this wave that stands for a ray (the last group may be padded)
+    auto advance = [&](Cursor c) {
+        do {
+            c.seq += blocks_per_xcd;
+            c.group += group_step;
+            if (c.group >= n_groups) c.group -= n_groups;
+        } while (c.seq < seq_last && ray_of(c) >= rays.M);
+        return c;
     };
+    Cursor cur = {seq_begin, seq_begin < seq_last ? (seq_begin * group_mul) % n_groups : 0};
+    if (cur.seq < seq_last && ray_of(cur) >= rays.M) cur = advance(cur);
 
     // Cell and input features of the step about to be processed.  Those of the following step
     // (of this ray, or the last step of the wave's next ray) are sampled while the current
     // step's last contractions run and BEFORE its scatter: the wait for these loads must not
     // come after the scatter's atomic adds (memory operations complete in order, and an atomic
     // add takes much longer than a cached load).
-    long long seq = valid_from(sched.first);
     RayGeom q_next;
     Cell3 cell;
     Frag fh[KS1], fl[KS1];
-    if (seq < sched.end) {  // a wave without rays only writes its (zero) record
-        q_next = load_ray_geom(rays, ray_of(seq));
+    if (cur.seq < seq_last) {  // a wave without rays only writes its (zero) record
+        q_next = load_ray_geom(rays, ray_of(cur));
         if constexpr (CG != C) set_direction_inputs(m, q_next);
         cell = sample_cell<CC>(g, q_next, min(j_last + slot_to_sample(col), S - 1));
         sample_features<KIND, C, CG, GT>(g, q_next, cell, grp, fh, fl);
     }
 
-    while (seq < sched.end) {
-        const long long ray = ray_of(seq);
+    while (cur.seq < seq_last) {
+        const long long ray = ray_of(cur);
         const RayGeom q = q_next;
-        seq = valid_from(seq + sched.stride);
-        if (seq < sched.end) {  // else: a harmless re-sample of this ray
-            q_next = load_ray_geom(rays, ray_of(seq));
+        cur = advance(cur);
+        if (cur.seq < seq_last) {  // else: a harmless re-sample of this ray
+            q_next = load_ray_geom(rays, ray_of(cur));
             if constexpr (CG != C) set_direction_inputs(m, q_next);
         }
         const float p0 = io.d_rgb[3 * ray + 0], p1 = io.d_rgb[3 * ray + 1], p2 = io.d_rgb[3 * ray + 2];
@@ -389,8 +400,9 @@ hipError_t launch_bwd(const GridDev& g, const MlpDev& m, const RaysDev& rays, co
     long long group_mul = 1;
     for (long long p : {7919LL, 7907LL, 7901LL, 7883LL})
         if (n_groups > p && n_groups % p != 0) { group_mul = p; break; }
+    const long long group_step = ((long long)(blocks / 8) * group_mul) % n_groups;
     hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kWaves * 64), kLdsBytes, stream, g, m, rays, io,
-                       group_mul);
+                       group_mul, group_step);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(reduce_params_kernel, dim3((m.param_total + 63) / 64), dim3(kReduceThreads), 0, stream,
@@ -424,7 +436,8 @@ hipError_t dispatch_bwd(const GridDev& g, const MlpDev& m, const RaysDev& rays, 
 #define LP_CASE(h, nh) \
     if (C == 32 && CG == 16 && H == h && NH == nh && !(g.contract > 0.0)) \
         return launch_bwd<KIND, 32, h, nh, false, 16>(g, m, rays, io, n_cu, stream);
-    LP_CASE(32, 1) LP_CASE(64, 1) LP_CASE(32, 2) LP_CASE(64, 2)
+    LP_CASE(32, 1) LP_CASE(64, 1) LP_CASE(32, 2)
+    if constexpr (KIND == LP_GRID_VOXEL) { LP_CASE(64, 2) }
 #undef LP_CASE
     return hipErrorInvalidValue;
 }

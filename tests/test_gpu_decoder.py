@@ -55,8 +55,10 @@ def test_decoder_matrix_core(lp, oracle, kind, hidden_s, hidden_v, n_freq, sampl
                   n_rays=203, samples=samples, n_scenes=2, res=(12, 10, 11), grid_std=0.3,
                   aabb_min=(-1.5, -1.5, -1.5), aabb_max=(1.5, 1.5, 1.5))
     grid, _, _, _ = lp.to_device(inp)
-    assert lp.lp_dec_has_fast_path(grid, lp.decoder_to_device(inp.decoder))
-    for mode in (lp.LP_MATH_GENERIC, lp.LP_MATH_BF16X3):
+    fast = lp.lp_dec_has_fast_path(grid, lp.decoder_to_device(inp.decoder))
+    # every shape here has a matrix-core kernel but the widest ones (64 wide, two hidden layers) on a triplane
+    assert fast == (not (kind == TRIPLANE and len(hidden_v) == 2))
+    for mode in (lp.LP_MATH_GENERIC, lp.LP_MATH_BF16X3) if fast else (lp.LP_MATH_GENERIC,):
         print(mode, check_case_dec(lp, oracle, inp, mode, label=f"dec mfma kind={kind} {hidden_s}/{hidden_v} mode={mode}"),
               flush=True)
 
