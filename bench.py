@@ -36,6 +36,9 @@ def parse():
     ap.add_argument("--config", default="large",
                     help="workload: tiny | single_scene | voxel | batched | large")
     ap.add_argument("--math", default="default", choices=["default", "generic", "bf16x3"])
+    ap.add_argument("--aabb", type=float, default=None,
+                    help="half-width of the grid box (default: the workload's, which contains every sample; "
+                         "1.0 = the object box, about half the samples clamp to the border)")
     ap.add_argument("--grid-dtype", default="f32", choices=["f32", "bf16", "f16"],
                     help="storage type of the grid on the GPU (gradients stay f32)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -71,11 +74,11 @@ def cpu_baseline(inp, budget_s: float):
             f"all {inp.samples} samples each, fp64 forward + stored-forward reverse-mode backward, {t:.1f} s"}
 
 
-def measure(lp, torch, name, mode, steps, warmup, calibrate_copy=False, grid_dtype="f32"):
+def measure(lp, torch, name, mode, steps, warmup, calibrate_copy=False, grid_dtype="f32", aabb=None):
     """Times `steps` forward+backward steps of workload `name`; returns the result fields."""
     import lp_inputs
     w = lp_inputs.WORKLOADS[name]
-    inp = lp_inputs.make_inputs(name)
+    inp = lp_inputs.make_inputs(name, aabb=aabb)
     dev = "cuda:0"
     grid, mlp, rays, bg = lp.to_device(inp, dev)
     if grid_dtype != "f32":
@@ -145,8 +148,9 @@ def measure(lp, torch, name, mode, steps, warmup, calibrate_copy=False, grid_dty
     elapsed = time.perf_counter() - t0
     fwd_ms = float(np.mean([e0.elapsed_time(e1) for e0, e1, _, _ in events]))
     bwd_ms = float(np.mean([e2.elapsed_time(e3) for _, _, e2, e3 in events]))
+    mid_ms = float(np.mean([e1.elapsed_time(e2) for _, e1, e2, _ in events]))   # loss gradient + zeroing
     return dict(w=w, inp=inp, fast=fast, rays=m, samples=m * inp.samples, elapsed=elapsed,
-                fwd_ms=fwd_ms, bwd_ms=bwd_ms)
+                fwd_ms=fwd_ms, bwd_ms=bwd_ms, mid_ms=mid_ms)
 
 
 def measure_splat(lp, torch, name, steps, warmup):
@@ -196,7 +200,7 @@ def main():
         print("bench.py: no GPU visible; the Renderer has no CPU path", file=sys.stderr)
         sys.exit(2)
     mode = {"default": lp.LP_MATH_DEFAULT, "generic": lp.LP_MATH_GENERIC, "bf16x3": lp.LP_MATH_BF16X3}[args.math]
-    r = measure(lp, torch, args.config, mode, args.steps, args.warmup, args.calibrate_copy, args.grid_dtype)
+    r = measure(lp, torch, args.config, mode, args.steps, args.warmup, args.calibrate_copy, args.grid_dtype, args.aabb)
     w, inp, fast, m, samples = r["w"], r["inp"], r["fast"], r["rays"], r["samples"]
     elapsed, fwd_avg, bwd_avg = r["elapsed"], r["fwd_ms"], r["bwd_ms"]
 
@@ -206,6 +210,11 @@ def main():
     # dominant kernel: the backward (re-reads the gather bytes and adds the fp32 gradient bytes)
     bwd_gbs = (g_bytes + g_write) * samples / (bwd_avg * 1e-3) / 1e9
     fwd_gbs = g_bytes * samples / (fwd_avg * 1e-3) / 1e9
+    # arithmetic view: MLP FLOPs per sample F (forward), 4 F forward + backward (recompute, dX, dW),
+    # plus the interpolation (2 FLOP per corner and channel, again in the backward's recompute and scatter)
+    interp = 2 * w.corners * w.channels
+    f_fwd, f_all = w.mlp_flop_per_sample + interp, 4 * w.mlp_flop_per_sample + 3 * interp
+    step_s = elapsed / args.steps
     out = {
         "metric": "ray-samples/sec fwd+bwd (Renderer hot path)",
         "value": samples / (elapsed / args.steps),
@@ -219,12 +228,18 @@ def main():
                                f"{w.n_scenes}x{w.res[0]}^{3 if w.kind == 0 else 2}x{w.channels}ch, "
                                f"{m} rays x {w.samples} samples, MLP {'-'.join(map(str, w.mlp_dims))}",
                    "rays": m, "samples_per_ray": w.samples, "ray_samples": samples, "grid_dtype": args.grid_dtype,
+                   "aabb_half_width": inp.aabb_max[0],
                    "kernels": "mfma" if fast else "generic"},
         "fwd": {"ms": fwd_avg, "ray_samples_per_s": samples / (fwd_avg * 1e-3),
                 "algorithmic_GBs": fwd_gbs, "frac_hbm_peak": fwd_gbs / HBM_PEAK_GBS},
         "fwd_bwd_effective": {"algorithmic_GBs": (2 * g_bytes + g_write) * samples / ((fwd_avg + bwd_avg) * 1e-3) / 1e9,
                               "frac_hbm_peak": (2 * g_bytes + g_write) * samples / ((fwd_avg + bwd_avg) * 1e-3) / 1e9
                               / HBM_PEAK_GBS},
+        "loss_grad_and_zeroing_ms": r["mid_ms"],
+        "alu_view": {"flop_per_sample_fwd": f_fwd, "flop_per_sample_fwd_bwd": f_all,
+                     "fwd_TFLOPs": f_fwd * samples / (fwd_avg * 1e-3) / 1e12,
+                     "fwd_bwd_TFLOPs": f_all * samples / step_s / 1e12,
+                     "fwd_bwd_frac_fp32_vector_peak": f_all * samples / step_s / 1e12 / 157.3},
         "roofline": {"kernel": "lp_render_bwd", "bound": "hbm", "achieved": bwd_gbs, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": bwd_gbs / HBM_PEAK_GBS,
                      "traffic": MEASURED_BWD_HBM_BYTES.get(args.config) if fast and args.grid_dtype == "f32" else None,
