@@ -103,6 +103,8 @@ def _load() -> C.CDLL:
     lib.lp_splat_fwd.restype = C.c_int
     lib.lp_splat_fwd.argtypes = [C.POINTER(_Grid), C.POINTER(_Rays), C.POINTER(_Splat), C.POINTER(C.c_void_p),
                                  C.POINTER(C.c_void_p), C.c_void_p]
+    lib.lp_splat_has_fast_path.restype = C.c_int32
+    lib.lp_splat_has_fast_path.argtypes = [C.POINTER(_Grid), C.POINTER(_Splat)]
     lib.lp_splat_bwd_workspace_bytes.restype = C.c_int
     lib.lp_splat_bwd_workspace_bytes.argtypes = [C.POINTER(_Grid), C.POINTER(_Rays), C.POINTER(_Splat),
                                                  C.POINTER(C.c_size_t)]
@@ -454,6 +456,13 @@ def lp_splat_fwd(target: _Grid, rays: Rays, splat: Splat, theta: List[torch.Tens
                              _ptr3(theta, _target_shapes(target, target.C), "theta"),
                              _ptr3(theta_w, _target_shapes(target, None), "theta_w"), _stream_ptr(stream)))
     del keep
+
+
+def lp_splat_has_fast_path(target: _Grid, splat: Splat) -> bool:
+    s, keep = splat.c_struct()
+    fast = bool(_lib.lp_splat_has_fast_path(C.byref(target), C.byref(s)))
+    del keep
+    return fast
 
 
 def lp_splat_bwd_workspace_bytes(target: _Grid, rays: Rays, splat: Splat) -> int:

@@ -18,7 +18,8 @@ INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.environ.get("LP_LIB_OUT", os.path.join(HERE, "liblightplane.so"))
 
-SOURCES = ["lp_api.hip", "lp_decoder.hip", "lp_generic.hip", "lp_mfma_fwd.hip", "lp_mfma_bwd.hip", "lp_splat_fast.hip"]
+SOURCES = ["lp_api.hip", "lp_decoder.hip", "lp_generic.hip", "lp_mfma_fwd.hip", "lp_mfma_bwd.hip", "lp_splat_fast.hip",
+           "lp_splat_mfma.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-munsafe-fp-atomics",
@@ -41,7 +42,8 @@ def _hipcc() -> str:
 # forward; the backward parks its long-lived weight-gradient accumulators in the accumulation
 # registers explicitly and gets 4-7 % faster.
 PER_SOURCE_FLAGS = {"lp_mfma_fwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
-                    "lp_mfma_bwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+                    "lp_mfma_bwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+                    "lp_splat_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 
 def _compile(src: str) -> str:

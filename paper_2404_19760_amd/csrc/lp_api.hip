@@ -654,6 +654,13 @@ lp_status lp_splat_fwd(const lp_grid* target, const lp_rays* rays, const lp_spla
         if (compute_units(&n_cu, &err)) return fail(LP_ERR_HIP, err);
         e = lp::launch_splat_naive(g, r, sd, n_cu, s);
         if (e != hipSuccess) return hip_fail("Splatter forward kernel launch", e);
+    } else if (rays->M > 0 && m.n_layers > 0 && lp::splat_mfma_supported(g, m, sd)) {
+        // MLP of the covered shapes: wavefront per ray, MLP on the matrix cores, the same push
+        std::string err;
+        int n_cu = 0;
+        if (compute_units(&n_cu, &err)) return fail(LP_ERR_HIP, err);
+        e = lp::launch_splat_mfma(g, m, r, sd, n_cu, s);
+        if (e != hipSuccess) return hip_fail("Splatter forward kernel launch", e);
     } else if (rays->M > 0) {
         const size_t lds = sizeof(float) * ((size_t)m.param_total + (size_t)m.act_total * kGenericLanes);
         if (lds > kMaxLds) return fail(LP_ERR_UNSUPPORTED, "MLP too large for the Splatter kernel's LDS budget");
@@ -675,6 +682,17 @@ lp_status lp_splat_fwd(const lp_grid* target, const lp_rays* rays, const lp_spla
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail("Splatter normalisation kernel launch", e);
     return LP_OK;
+}
+
+int32_t lp_splat_has_fast_path(const lp_grid* target, const lp_splat* splat)
+{
+    lp_rays dummy;
+    std::memset(&dummy, 0, sizeof(dummy));
+    dummy.S = 1;
+    lp::GridDev g; lp::MlpDev m; lp::RaysDev r; lp::SplatDev sd;
+    if (splat_views(target, &dummy, splat, &g, &m, &r, &sd) != LP_OK) return 0;
+    if (m.n_layers == 0) return lp::splat_naive_supported(g) ? 1 : 0;
+    return lp::splat_mfma_supported(g, m, sd) ? 1 : 0;
 }
 
 lp_status lp_splat_bwd_workspace_bytes(const lp_grid* target, const lp_rays* rays, const lp_splat* splat,

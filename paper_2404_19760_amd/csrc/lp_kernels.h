@@ -32,6 +32,13 @@ bool splat_naive_supported(const GridDev& tgt);
 hipError_t launch_splat_naive(const GridDev& tgt, const RaysDev& rays, const SplatDev& sp, int n_cu,
                               hipStream_t stream);
 
+// ---- Splatter forward with an MLP on the matrix cores (lp_splat_mfma.hip) ----------------
+// Shapes covered: prior and target with the same 16 or 32 fp32 channels, no contraction; one or
+// two hidden layers of width 64; pixel feature + direction encoding of at most 48 inputs.
+bool splat_mfma_supported(const GridDev& tgt, const MlpDev& m, const SplatDev& sp);
+hipError_t launch_splat_mfma(const GridDev& tgt, const MlpDev& m, const RaysDev& rays, const SplatDev& sp,
+                             int n_cu, hipStream_t stream);
+
 // ---- the two-MLP decoder as ONE block-structured MLP (lp_decoder.hip) ------------------
 // Combined layer l has the opacity MLP's rows first, then the feature MLP's; a shallower MLP
 // is carried through the extra layers by identity blocks (exact behind a ReLU); the first

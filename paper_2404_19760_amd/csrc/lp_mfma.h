@@ -112,7 +112,8 @@ __host__ __device__ constexpr int k_input(int s, int g, int e)
 
 // Stages one weight matrix as MFMA A operands: for block (mb, s) 64 lanes x 8 bf16 of the hi
 // parts (1 KiB) followed by the lo parts.  row_of(mb, i) gives the source row of the weight
-// matrix for output row i of block mb (negative: zero row); col_of(s, g, e) the source column.
+// matrix for output row i of block mb (negative: zero row); col_of(s, g, e) the source column
+// (negative: zero).
 template <class RowFn, class ColFn>
 __device__ __forceinline__ void stage_operand(uint4* dst, const float* __restrict__ W, int n_mb, int n_ks,
                                               int ld, RowFn row_of, ColFn col_of)
@@ -124,7 +125,7 @@ __device__ __forceinline__ void stage_operand(uint4* dst, const float* __restric
         const int s = blk % n_ks, mb = blk / n_ks;
         const int r = row_of(mb, lane & 31);
         const int c = col_of(s, lane >> 5, e);
-        const float v = r >= 0 ? W[(size_t)r * ld + c] : 0.0f;
+        const float v = (r >= 0 && c >= 0) ? W[(size_t)r * ld + c] : 0.0f;
         const __bf16 h = (__bf16)v;
         const __bf16 l = (__bf16)(v - (float)h);
         out[(size_t)blk * 1024 + lane * 8 + e] = h;

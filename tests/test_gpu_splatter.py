@@ -48,6 +48,34 @@ def test_splatter_with_mlp(lp, oracle, kind, hidden, n_freq, prior_channels):
     print(check_case_splat(lp, oracle, sp, label=f"splat kind={kind} hidden={hidden}"), flush=True)
 
 
+@pytest.mark.parametrize("kind", [VOXEL, TRIPLANE])
+@pytest.mark.parametrize("channels,n_in,hidden,n_freq", [(16, 5, (64,), -1), (16, 16, (64, 64), 0),
+                                                         (32, 7, (64, 64), 1), (32, 32, (64,), 1),
+                                                         (32, 33, (64, 64), 2)])
+def test_splatter_mlp_on_matrix_cores(lp, oracle, kind, channels, n_in, hidden, n_freq):
+    """Prior and target of 16 / 32 channels, hidden width 64: the forward runs on the
+    wavefront-per-ray matrix-core kernel (1, 2 or 3 K-steps of per-ray inputs; point counts that
+    are not a multiple of the 32-point step; several scenes)."""
+    sp = lp_inputs.make_splat_small(kind, channels=channels, res=(12, 10, 11), n_in=n_in, hidden=hidden,
+                                    n_freq=n_freq, prior_channels=channels, prior_res=(7, 6, 5), n_rays=203,
+                                    samples=41, seed=101 + n_in, n_scenes=2, bias_std=0.1, far=(2.2, 6.0))
+    target, _, splat = lp.splat_to_device(sp)
+    assert lp.lp_splat_has_fast_path(target, splat)
+    print(check_case_splat(lp, oracle, sp, label=f"splat mfma kind={kind} C={channels} n_in={n_in}"), flush=True)
+
+
+def test_splatter_fast_path_query(lp):
+    for kw, fast in [(dict(channels=32, n_in=32, hidden=(64, 64), n_freq=0, prior_channels=32), True),
+                     (dict(channels=32, n_in=32, hidden=(64, 32), n_freq=0, prior_channels=32), False),
+                     (dict(channels=32, n_in=32, hidden=(64,), n_freq=0, prior_channels=16), False),
+                     (dict(channels=32, n_in=32, hidden=(64,), n_freq=2, prior_channels=32), True),
+                     (dict(channels=32, n_in=34, hidden=(64,), n_freq=2, prior_channels=32), False),
+                     (dict(channels=16), True), (dict(channels=6), False)]:
+        sp = lp_inputs.make_splat_small(VOXEL, n_rays=5, **kw)
+        target, _, splat = lp.splat_to_device(sp)
+        assert lp.lp_splat_has_fast_path(target, splat) == fast, kw
+
+
 def test_splatter_with_the_papers_mlp_size(lp, oracle):
     """32-channel features, prior and target, 3-layer MLP of width 64 (appendix, "Experimental
     Details"): two copies of the parameters no longer fit in LDS, the backward accumulates the
