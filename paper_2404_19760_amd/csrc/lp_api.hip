@@ -705,7 +705,9 @@ lp_status lp_splat_bwd_workspace_bytes(const lp_grid* target, const lp_rays* ray
     std::string err;
     int n_cu = 0;
     if (compute_units(&n_cu, &err)) return fail(LP_ERR_HIP, err);
-    *bytes = align256(sizeof(float) * (size_t)generic_bwd_blocks(n_cu) * (size_t)ws_stride(m)) + 256;
+    const bool fast = m.n_layers > 0 && lp::splat_mfma_supported(g, m, sd);
+    const int records = fast ? lp::mfma_bwd_records(n_cu) : generic_bwd_blocks(n_cu);
+    *bytes = align256(sizeof(float) * (size_t)records * (size_t)ws_stride(m)) + 256;
     return LP_OK;
 }
 
@@ -751,6 +753,12 @@ lp_status lp_splat_bwd(const lp_grid* target, const lp_rays* rays, const lp_spla
     std::string err;
     int n_cu = 0;
     if (compute_units(&n_cu, &err)) return fail(LP_ERR_HIP, err);
+    if (m.n_layers > 0 && lp::splat_mfma_supported(g, m, sd)) {
+        // covered MLP shapes: wavefront per ray, MLP forward and backward on the matrix cores
+        hipError_t e = lp::launch_splat_mfma_bwd(g, m, r, sd, io, n_cu, s);
+        if (e != hipSuccess) return hip_fail("Splatter backward kernel launch", e);
+        return LP_OK;
+    }
     size_t lds = sizeof(float) * (2 * (size_t)m.param_total +
                                   ((size_t)m.act_total + 2 * (size_t)m.max_width + sd.n_in) * kGenericLanes);
     if (lds > kMaxLds) {   // keep one copy of the parameters in LDS, accumulate gradients in the records

@@ -38,6 +38,13 @@ hipError_t launch_splat_naive(const GridDev& tgt, const RaysDev& rays, const Spl
 bool splat_mfma_supported(const GridDev& tgt, const MlpDev& m, const SplatDev& sp);
 hipError_t launch_splat_mfma(const GridDev& tgt, const MlpDev& m, const RaysDev& rays, const SplatDev& sp,
                              int n_cu, hipStream_t stream);
+// backward of the same shapes (lp_splat_mfma_bwd.hip): one record of partial sums per wave,
+// mfma_bwd_records(n_cu) of them, added up by reduce_params_kernel (launched by this call)
+hipError_t launch_splat_mfma_bwd(const GridDev& tgt, const MlpDev& m, const RaysDev& rays, const SplatDev& sp,
+                                 const BwdIo& io, int n_cu, hipStream_t stream);
+// the part of it for 32-channel triplanes (lp_splat_mfma_bwd_t32.hip, built with other flags)
+hipError_t launch_splat_mfma_bwd_triplane32(const GridDev& tgt, const MlpDev& m, const RaysDev& rays,
+                                            const SplatDev& sp, const BwdIo& io, int n_cu, hipStream_t stream);
 
 // ---- the two-MLP decoder as ONE block-structured MLP (lp_decoder.hip) ------------------
 // Combined layer l has the opacity MLP's rows first, then the feature MLP's; a shallower MLP

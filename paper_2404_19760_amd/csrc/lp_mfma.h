@@ -120,6 +120,7 @@ __device__ __forceinline__ void stage_operand(uint4* dst, const float* __restric
 {
     __bf16* out = reinterpret_cast<__bf16*>(dst);
     const int total = n_mb * n_ks * 512;
+#pragma unroll 1
     for (int idx = threadIdx.x; idx < total; idx += blockDim.x) {
         const int e = idx & 7, lane = (idx >> 3) & 63, blk = idx >> 9;
         const int s = blk % n_ks, mb = blk / n_ks;
@@ -141,6 +142,7 @@ __device__ __forceinline__ void stage_operand_t(uint4* dst, const float* __restr
 {
     __bf16* out = reinterpret_cast<__bf16*>(dst);
     const int total = n_mb * n_ks * 512;
+#pragma unroll 1
     for (int idx = threadIdx.x; idx < total; idx += blockDim.x) {
         const int e = idx & 7, lane = (idx >> 3) & 63, blk = idx >> 9;
         const int s = blk % n_ks, mb = blk / n_ks;

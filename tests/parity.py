@@ -57,10 +57,18 @@ def close_envelope(gpu, ref, lo, hi, rtol: float, what: str):
             f"worst at flat index {k}: gpu={gpu.reshape(-1)[k]!r} ref={ref.reshape(-1)[k]!r} "
             f"envelope=[{lo.reshape(-1)[k]!r}, {hi.reshape(-1)[k]!r}] rms(ref)={rms:g}")
     strict_fail = float((np.abs(gpu - ref) > bound).mean()) if ref.size else 0.0
-    # whole-tensor check around the definition's gradient: kink samples are few, so they
-    # move the tensor as a whole by far less than they move single elements
-    l2 = float(np.linalg.norm(gpu - ref) / max(np.linalg.norm(ref), 1e-300))
-    assert l2 <= 3.0 * rtol, f"{what}: relative L2 error {l2:g} exceeds {3.0 * rtol:g}"
+    # whole-tensor checks.  The part of the difference that no choice at a kink explains (the
+    # distance to the envelope) is bounded like an ordinary error.  Around the definition's own
+    # gradient the bound grows by the width of the envelope: kink samples are usually few and
+    # independent, so that width is far below the tolerance, but points of a ray that are clamped
+    # to the same border position of a structure share their pre-activations and flip together.
+    norm = max(float(np.linalg.norm(ref)), 1e-300)
+    l2_env = float(np.linalg.norm(err)) / norm
+    assert l2_env <= 3.0 * rtol, f"{what}: relative L2 distance to the kink envelope {l2_env:g} exceeds {3.0 * rtol:g}"
+    l2 = float(np.linalg.norm(gpu - ref)) / norm
+    width = float(np.linalg.norm(hi - lo)) / norm
+    assert l2 <= 3.0 * rtol + width, \
+        f"{what}: relative L2 error {l2:g} exceeds {3.0 * rtol:g} + envelope width {width:g}"
     return float(err.max() / max(rms, 1e-300)), strict_fail
 
 
