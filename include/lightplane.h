@@ -228,8 +228,8 @@ typedef struct {
 lp_status lp_splat_fwd(const lp_grid* target, const lp_rays* rays, const lp_splat* splat,
                        float* const theta[3], float* const theta_w[3], void* stream);
 
-/* 1 if lp_splat_fwd runs this target / splat on the wavefront-per-ray kernels, else 0 (generic
-   kernel, same results).  Covered: targets of 16 or 32 channels; with an MLP also a prior of
+/* 1 if lp_splat_fwd (and, with an MLP, lp_splat_bwd) runs this target / splat on the
+   wavefront-per-ray kernels, else 0 (generic kernels, same results).  Covered: targets of 16 or 32 channels; with an MLP also a prior of
    the same channel count in fp32, no contraction, one or two hidden layers of width 64, and at
    most 48 pixel-feature plus direction-encoding inputs.  Nothing behind the device pointers is read. */
 int32_t lp_splat_has_fast_path(const lp_grid* target, const lp_splat* splat);

@@ -3,9 +3,10 @@
 // direction) into the target structure), wavefront per ray.
 //
 // A step is 32 points.  The MLP runs transposed like the Renderer's (hidden layers D = W X with
-// the points along N); its inputs are ordered for the kernel: first the prior's channels
-// (gathered per point), then the per-ray inputs (pixel feature, direction encoding, zeros up to
-// a multiple of 16), whose operand fragments are built once per ray.  The last layer is taken
+// the points along N).  The pixel feature and the direction encoding are the same for every
+// point of a ray, so their part of the first layer, W1[:, per-ray inputs] x, is evaluated once per
+// ray and joins the bias; a step's first layer then contracts the prior's channels (gathered
+// per point) only.  The last layer is taken
 // with the roles swapped, V = H^T Wout^T (points along M, channels along N), which leaves lane =
 // channel and registers = 16 consecutive points: the layout the run-merging scatter of the
 // Renderer's backward works on, so the push shares that code.
@@ -22,29 +23,37 @@ namespace {
 constexpr int kWaves = 4;
 constexpr int kHidden = 64;
 
-// KSP K-steps of prior channels (16 each), KSE K-steps of per-ray inputs
+// LDS layout in 16-byte units.  KSP K-steps of prior channels (16 each), KSE K-steps of per-ray
+// inputs (pixel feature, direction encoding, zeros); element e of lane group g in K-step s is
+// input 16 s + 8 g + e of its kind.
 template <int KSP, int KSE, int NH>
 struct SplatLds {
-    using W = MlpLds<16 * (KSP + KSE), kHidden, NH, false, 1>;
-    static constexpr int BIAS_OUT = W::END;            // 32 floats
-    static constexpr int INFO = BIAS_OUT + 8;          // per wave 32 records of 16 dwords
-    static constexpr int UNITS = INFO + kWaves * 128;
+    static constexpr int MB = kHidden / 32, KSH = kHidden / 16;
+    static constexpr int A1P = 0;                                   // W1, prior columns   [MB][KSP]
+    static constexpr int A1E = A1P + MB * KSP * 128;                // W1, per-ray columns [MB][KSE]
+    static constexpr int A2 = A1E + MB * KSE * 128;                 // W2   [MB][KSH]  (NH == 2)
+    static constexpr int A3 = A2 + (NH == 2 ? MB * KSH * 128 : 0);  // Wout as B operand [1][KSH]
+    static constexpr int BIAS = A3 + KSH * 128;                     // floats b1[64] b2[64] bout[32]
+    static constexpr int WAVE = BIAS + (2 * kHidden + 32) / 4;      // per-wave areas
+    // a wave's area: 32 scatter records of 16 dwords, the ray's first-layer bias, its 48 inputs
+    static constexpr int W_INFO = 0, W_BIAS = 128, W_X = W_BIAS + kHidden / 4, W_UNITS = W_X + 48 / 4;
+    static constexpr int UNITS = WAVE + kWaves * W_UNITS;
+    static_assert(UNITS * 16 <= 64 * 1024, "static LDS of a workgroup");
 };
 
 template <int KSP, int KSE, int NH, int CO>
 __device__ __forceinline__ void stage_splat_mlp(uint4* lds, const MlpDev& m, int n_in)
 {
-    using S = SplatLds<KSP, KSE, NH>;
-    using L = typename S::W;
-    constexpr int MB = L::MB, KS1 = L::KS1, KSH = L::KSH, CP = 16 * KSP;
+    using L = SplatLds<KSP, KSE, NH>;
+    constexpr int MB = L::MB, KSH = L::KSH, CP = 16 * KSP;
     auto hidden_col = [](int s, int gg, int e) { return k_hidden(s, gg, e); };
     auto block_row = [](int mb, int i) { return 32 * mb + i; };
     const int n_extra = n_in + m.n_enc;
-    // kernel input (s, g, e) -> column of the first layer: the caller's order is pixel feature,
-    // prior channels, direction encoding
-    stage_operand(lds + L::A1, m.W[0], MB, KS1, m.dims[0], block_row, [=](int s, int gg, int e) {
-        if (s < KSP) return n_in + 16 * s + 8 * gg + e;
-        const int x = 16 * (s - KSP) + 8 * gg + e;
+    // the caller's column order is pixel feature, prior channels, direction encoding
+    stage_operand(lds + L::A1P, m.W[0], MB, KSP, m.dims[0], block_row,
+                  [=](int s, int gg, int e) { return n_in + 16 * s + 8 * gg + e; });
+    stage_operand(lds + L::A1E, m.W[0], MB, KSE, m.dims[0], block_row, [=](int s, int gg, int e) {
+        const int x = 16 * s + 8 * gg + e;
         return x < n_in ? x : x < n_extra ? CP + x : -1;
     });
     if constexpr (NH == 2) stage_operand(lds + L::A2, m.W[1], MB, KSH, kHidden, block_row, hidden_col);
@@ -56,28 +65,29 @@ __device__ __forceinline__ void stage_splat_mlp(uint4* lds, const MlpDev& m, int
         sbias[i] = m.b[0][i];
         sbias[kHidden + i] = NH == 2 ? m.b[1][i] : 0.0f;
     }
-    float* bias_out = reinterpret_cast<float*>(lds + S::BIAS_OUT);
-    if (threadIdx.x < 32) bias_out[threadIdx.x] = m.b[NH][threadIdx.x & (CO - 1)];
+    if (threadIdx.x < 32) sbias[2 * kHidden + threadIdx.x] = m.b[NH][threadIdx.x & (CO - 1)];
 }
 
 template <int KIND, int KSP, int KSE, int NH>
-__global__ __launch_bounds__(kWaves * 64) void splat_mfma_kernel(GridDev tgt, MlpDev m, RaysDev rays,
-                                                                    SplatDev sp, long long group_mul)
+__global__ __launch_bounds__(kWaves * 64) void splat_mfma_kernel(GridDev tgt, MlpDev m, RaysDev rays, SplatDev sp,
+                                                                 long long group_mul)
 {
     constexpr int CO = 16 * KSP;  // the target has the prior's channel count
-    using SL = SplatLds<KSP, KSE, NH>;
-    using L = typename SL::W;
-    constexpr int MB = L::MB, KS1 = L::KS1, KSH = L::KSH;
-    __shared__ uint4 lds[SL::UNITS];
+    using L = SplatLds<KSP, KSE, NH>;
+    constexpr int MB = L::MB, KSH = L::KSH;
+    __shared__ uint4 lds[L::UNITS];
     stage_splat_mlp<KSP, KSE, NH, CO>(lds, m, sp.n_in);
     __syncthreads();
 
     const int lane = threadIdx.x & 63;
     const int col = lane & 31, grp = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    float* info = reinterpret_cast<float*>(lds + SL::INFO + wave * 128);
+    uint4* wave_area = lds + L::WAVE + wave * L::W_UNITS;
+    float* info = reinterpret_cast<float*>(wave_area + L::W_INFO);
+    float* ray_bias = reinterpret_cast<float*>(wave_area + L::W_BIAS);
+    float* ray_x = reinterpret_cast<float*>(wave_area + L::W_X);
     const float* sbias = reinterpret_cast<const float*>(lds + L::BIAS);
-    const float bias_out = reinterpret_cast<const float*>(lds + SL::BIAS_OUT)[col];
+    const float bias_out = sbias[2 * kHidden + col];
     const int n_in = sp.n_in, n_extra = sp.n_in + m.n_enc;
 
     const long long n_groups = (rays.M + kWaves - 1) / kWaves;
@@ -87,25 +97,38 @@ __global__ __launch_bounds__(kWaves * 64) void splat_mfma_kernel(GridDev tgt, Ml
         const long long ray = ((seq / kWaves) * group_mul % n_groups) * kWaves + seq % kWaves;
         if (ray >= rays.M) continue;
         const RayGeom q = load_ray_geom(rays, ray);
-        // per-ray inputs as operand fragments: element e of K-step s is input 16 s + 8 grp + e
-        Frag eh[KSE], el[KSE];
+        // ---- the ray's inputs x (pixel feature, direction encoding, zeros), one per lane, and its
+        //      first-layer bias b1 + W1[:, per-ray inputs] x ----
         {
             const float d[3] = {q.dx, q.dy, q.dz};
+            const float x_lane = lane < n_in ? sp.feats[(size_t)ray * n_in + lane]
+                                             : lane < n_extra ? dir_encoding(d, lane - n_in) : 0.0f;
+            wave_lds_fence();
+            if (lane < 48) ray_x[lane] = x_lane;
+            wave_lds_fence();
+            f32x16 acc[MB][1];
+            init_bias<MB, 1>(acc, sbias, grp);
+            Frag eh[1][KSE], el[1][KSE];
 #pragma unroll
             for (int s = 0; s < KSE; ++s) {
                 float x[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const int k = 16 * s + 8 * grp + e;
-                    x[e] = k < n_in ? sp.feats[(size_t)ray * n_in + k] : k < n_extra ? dir_encoding(d, k - n_in) : 0.0f;
-                }
-                split8(x, eh[s], el[s]);
+                *reinterpret_cast<f32x4*>(x) = *reinterpret_cast<const f32x4*>(ray_x + 16 * s + 8 * grp);
+                *reinterpret_cast<f32x4*>(x + 4) = *reinterpret_cast<const f32x4*>(ray_x + 16 * s + 8 * grp + 4);
+                split8(x, eh[0][s], el[0][s]);
             }
+            layer_mfma<MB, KSE, 1>(acc, lds + L::A1E, lane, eh, el);
+            if (col == 0) {  // every column holds the same values
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) ray_bias[32 * mb + d_row(r, grp)] = acc[mb][0][r];
+            }
+            wave_lds_fence();
         }
         for (int j0 = 0; j0 < S; j0 += kBwdStep) {
             const int j = j0 + slot_to_sample(col);
             const int jj = min(j, S - 1);
-            Frag fh[1][KS1], fl[1][KS1];
+            Frag fh[1][KSP], fl[1][KSP];
             {
                 const Cell3 cp = sample_cell<false>(sp.prior, q, jj);
 #pragma unroll
@@ -114,8 +137,6 @@ __global__ __launch_bounds__(kWaves * 64) void splat_mfma_kernel(GridDev tgt, Ml
                     gather_half<KIND, CO, 8, LP_F32>(sp.prior, q.scene, cp, 16 * s + 8 * grp, feat);
                     split8(feat, fh[0][s], fl[0][s]);
                 }
-#pragma unroll
-                for (int s = 0; s < KSE; ++s) { fh[0][KSP + s] = eh[s]; fl[0][KSP + s] = el[s]; }
             }
             const Cell3 ct = sample_cell<false>(tgt, q, jj);
             wave_lds_fence();
@@ -130,8 +151,8 @@ __global__ __launch_bounds__(kWaves * 64) void splat_mfma_kernel(GridDev tgt, Ml
             Frag lh[1][KSH], ll[1][KSH];
             {
                 f32x16 acc[MB][1];
-                init_bias<MB, 1>(acc, sbias, grp);
-                layer_mfma<MB, KS1, 1>(acc, lds + L::A1, lane, fh, fl);
+                init_bias<MB, 1>(acc, ray_bias, grp);
+                layer_mfma<MB, KSP, 1>(acc, lds + L::A1P, lane, fh, fl);
                 to_operands<MB, true, 1>(acc, lh, ll);
                 if constexpr (NH == 2) {
                     init_bias<MB, 1>(acc, sbias + kHidden, grp);

@@ -78,13 +78,26 @@ def test_splatter_fast_path_query(lp):
 
 def test_splatter_with_the_papers_mlp_size(lp, oracle):
     """32-channel features, prior and target, 3-layer MLP of width 64 (appendix, "Experimental
-    Details"): two copies of the parameters no longer fit in LDS, the backward accumulates the
-    MLP gradients in its records instead."""
+    Details"): runs on the matrix-core kernels, forward and backward."""
     sp = lp_inputs.make_splat_small(VOXEL, channels=32, res=(9, 8, 10), n_in=32, hidden=(64, 64), n_freq=0,
                                     prior_channels=32, prior_res=(7, 6, 5), n_rays=150, samples=20, seed=99,
                                     bias_std=0.1)
     assert sp.mlp_dims == (67, 64, 64, 32)
+    target, _, splat = lp.splat_to_device(sp)
+    assert lp.lp_splat_has_fast_path(target, splat)
     print(check_case_splat(lp, oracle, sp, label="splat paper-size MLP"), flush=True)
+
+
+def test_splatter_generic_kernel_with_a_large_mlp(lp, oracle):
+    """An MLP of about the same size that the matrix-core kernels do not cover (hidden widths 64
+    and 60): two copies of the parameters no longer fit in LDS, so the generic backward
+    accumulates the MLP gradients in its records instead."""
+    sp = lp_inputs.make_splat_small(VOXEL, channels=32, res=(9, 8, 10), n_in=32, hidden=(64, 60), n_freq=0,
+                                    prior_channels=32, prior_res=(7, 6, 5), n_rays=150, samples=20, seed=99,
+                                    bias_std=0.1)
+    target, _, splat = lp.splat_to_device(sp)
+    assert not lp.lp_splat_has_fast_path(target, splat)
+    print(check_case_splat(lp, oracle, sp, label="splat large generic MLP"), flush=True)
 
 
 def test_splatter_with_contraction_and_empty_cells(lp, oracle):
