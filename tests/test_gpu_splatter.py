@@ -100,6 +100,25 @@ def test_splatter_generic_kernel_with_a_large_mlp(lp, oracle):
     print(check_case_splat(lp, oracle, sp, label="splat large generic MLP"), flush=True)
 
 
+def test_splat_naive_workload_at_full_size(lp, oracle):
+    """The benchmark's naive Splatter workload (160^3 x 32 voxels, 65 536 rays of 160 points),
+    whole: every cell of the result, the weight sums and the pixel-feature gradients."""
+    sp = lp_inputs.make_splat_inputs("splat_naive")
+    target, _, splat = lp.splat_to_device(sp)
+    assert lp.lp_splat_has_fast_path(target, splat)
+    print(check_case_splat(lp, oracle, sp, label="splat_naive workload"), flush=True)
+
+
+def test_splat_mlp_workload_at_full_size(lp, oracle):
+    """The benchmark's Splatter workload with MLP (160^3 x 32 voxels, prior of the same size, MLP
+    67-64-64-32, 16 384 rays of 160 points), whole, in the launch configuration the benchmark
+    times: every cell of the result and every gradient against the oracle."""
+    sp = lp_inputs.make_splat_inputs("splat_mlp")
+    target, _, splat = lp.splat_to_device(sp)
+    assert lp.lp_splat_has_fast_path(target, splat)
+    print(check_case_splat(lp, oracle, sp, label="splat_mlp workload"), flush=True)
+
+
 def test_splatter_with_contraction_and_empty_cells(lp, oracle):
     """Contract coordinates; a fine target that most rays never touch (cells with zero weight)."""
     sp = lp_inputs.make_splat_small(VOXEL, channels=4, res=(20, 18, 22), n_in=3, hidden=(8,), n_freq=0,
