@@ -18,7 +18,8 @@ INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.environ.get("LP_LIB_OUT", os.path.join(HERE, "liblightplane.so"))
 
-SOURCES = ["lp_api.hip", "lp_decoder.hip", "lp_generic.hip", "lp_mfma_fwd.hip", "lp_mfma_bwd.hip", "lp_splat_fast.hip",
+SOURCES = ["lp_api.hip", "lp_decoder.hip", "lp_generic.hip", "lp_mfma_fwd.hip", "lp_mfma_bwd.hip", "lp_mfma_bwd_b.hip",
+           "lp_splat_fast.hip",
            "lp_splat_mfma.hip", "lp_splat_mfma_bwd.hip", "lp_splat_mfma_bwd_t32.hip"]
 
 HIPCC_FLAGS = [

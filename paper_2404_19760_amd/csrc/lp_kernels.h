@@ -25,6 +25,10 @@ hipError_t launch_fwd_mfma(const GridDev& g, const MlpDev& m, const RaysDev& ray
                            int n_cu, hipStream_t stream);
 hipError_t launch_bwd_mfma(const GridDev& g, const MlpDev& m, const RaysDev& rays, const BwdIo& io,
                            int n_cu, hipStream_t stream);
+// the part of it that lp_mfma_bwd_b.hip builds with other flags (direction inputs with contract
+// coordinates or with two 64-wide hidden layers on a triplane)
+hipError_t launch_bwd_mfma_b(const GridDev& g, const MlpDev& m, const RaysDev& rays, const BwdIo& io,
+                             int n_cu, hipStream_t stream);
 
 
 // ---- naive Splatter forward, wavefront per ray (lp_splat_fast.hip): 16 or 32 channels ----

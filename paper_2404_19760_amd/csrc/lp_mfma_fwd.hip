@@ -117,13 +117,12 @@ hipError_t dispatch_fwd(const GridDev& g, const MlpDev& m, const RaysDev& rays, 
     LP_CASE(16, 16, 32, 1) LP_CASE(16, 16, 64, 1) LP_CASE(32, 32, 32, 1) LP_CASE(32, 32, 64, 1)
     LP_CASE(16, 16, 32, 2) LP_CASE(16, 16, 64, 2) LP_CASE(32, 32, 32, 2) LP_CASE(32, 32, 64, 2)
 #undef LP_CASE
-    // 16 grid channels + direction inputs (the two-MLP decoder merged into one MLP of 32 inputs);
-    // without contract coordinates (that combination runs on the generic kernels)
-#define LP_CASE(h, nh) \
-    if (C == 32 && CG == 16 && H == h && NH == nh && !(g.contract > 0.0)) \
-        return launch_fwd<KIND, 32, h, nh, 2, false, 16>(g, m, rays, out, n_cu, stream);
-    LP_CASE(32, 1) LP_CASE(64, 1) LP_CASE(32, 2)
-    if constexpr (KIND == LP_GRID_VOXEL) { LP_CASE(64, 2) }
+    // 16 grid channels + direction inputs (the two-MLP decoder merged into one MLP of 32 inputs)
+#define LP_CASE(h, nh)                                                                                  \
+    if (C == 32 && CG == 16 && H == h && NH == nh)                                                      \
+        return g.contract > 0.0 ? launch_fwd<KIND, 32, h, nh, 2, true, 16>(g, m, rays, out, n_cu, stream) \
+                                : launch_fwd<KIND, 32, h, nh, 2, false, 16>(g, m, rays, out, n_cu, stream);
+    LP_CASE(32, 1) LP_CASE(64, 1) LP_CASE(32, 2) LP_CASE(64, 2)
 #undef LP_CASE
     return hipErrorInvalidValue;
 }
@@ -134,11 +133,8 @@ bool mfma_supported(const GridDev& g, const MlpDev& m)
 {
     // inputs: all of them grid channels (16 or 32), or 16 grid channels + 16 direction inputs
     const bool plain = m.n_enc == 0 && m.dims[0] == g.C && (g.C == 16 || g.C == 32);
-    const bool with_dir = m.n_enc > 0 && g.C == 16 && m.dims[0] == 32 && m.n_enc <= 16 && !(g.contract > 0.0);
+    const bool with_dir = m.n_enc > 0 && g.C == 16 && m.dims[0] == 32 && m.n_enc <= 16;
     if (!plain && !with_dir) return false;
-    // the widest decoder variant on a triplane does not fit the backward kernel's registers (and its
-    // compilation is not reliable): it is left to the generic kernels
-    if (with_dir && g.kind == LP_GRID_TRIPLANE && m.dims[1] == 64 && m.n_layers == 3) return false;
     if (g.dtype != LP_F32 && (!plain || g.contract > 0.0)) return false;
     if (m.n_feat != 3 || m.feat_act != 0 || m.dims[m.n_layers] != 4) return false;
     if (m.n_layers != 2 && m.n_layers != 3) return false;

@@ -55,12 +55,25 @@ def test_decoder_matrix_core(lp, oracle, kind, hidden_s, hidden_v, n_freq, sampl
                   n_rays=203, samples=samples, n_scenes=2, res=(12, 10, 11), grid_std=0.3,
                   aabb_min=(-1.5, -1.5, -1.5), aabb_max=(1.5, 1.5, 1.5))
     grid, _, _, _ = lp.to_device(inp)
-    fast = lp.lp_dec_has_fast_path(grid, lp.decoder_to_device(inp.decoder))
-    # every shape here has a matrix-core kernel but the widest ones (64 wide, two hidden layers) on a triplane
-    assert fast == (not (kind == TRIPLANE and len(hidden_v) == 2))
-    for mode in (lp.LP_MATH_GENERIC, lp.LP_MATH_BF16X3) if fast else (lp.LP_MATH_GENERIC,):
+    assert lp.lp_dec_has_fast_path(grid, lp.decoder_to_device(inp.decoder))
+    for mode in (lp.LP_MATH_GENERIC, lp.LP_MATH_BF16X3):
         print(mode, check_case_dec(lp, oracle, inp, mode, label=f"dec mfma kind={kind} {hidden_s}/{hidden_v} mode={mode}"),
               flush=True)
+
+
+@pytest.mark.parametrize("kind", [VOXEL, TRIPLANE])
+@pytest.mark.parametrize("hidden_s,hidden_v,n_freq", [((16,), (16,), 0), ((32, 32), (32, 32), 2), ((16, 16), (16, 16), 1),
+                                                      ((24,), (40,), 1)])
+def test_decoder_matrix_core_with_contract_coordinates(lp, oracle, kind, hidden_s, hidden_v, n_freq):
+    """The two-MLP decoder together with contract coordinates: rays that run far beyond the box."""
+    inp = problem(kind, channels=16, hidden_s=hidden_s, hidden_v=hidden_v, n_freq=n_freq, n_feat=3, seed=87,
+                  n_rays=150, samples=70, n_scenes=2, res=(12, 10, 11), grid_std=0.3, origin_radius=1.5,
+                  near=(0.0, 0.3), far=(6.0, 20.0))
+    inp = dataclasses.replace(inp, contract_a=1.3)
+    grid, _, _, _ = lp.to_device(inp)
+    assert lp.lp_dec_has_fast_path(grid, lp.decoder_to_device(inp.decoder))
+    print(check_case_dec(lp, oracle, inp, lp.LP_MATH_BF16X3, label=f"dec mfma contract kind={kind} {hidden_s}/{hidden_v}"),
+          flush=True)
 
 
 def test_decoder_fast_path_limits(lp):
@@ -73,7 +86,7 @@ def test_decoder_fast_path_limits(lp):
     assert not fast(mk(feat_act=1))                    # sigmoid only
     assert not fast(mk(hidden_s=(16,), hidden_v=(20,)))  # merged width must be 32 or 64
     assert not fast(mk(channels=32, hidden_s=(16,), hidden_v=(16,)))
-    assert not fast(dataclasses.replace(mk(), contract_a=1.0))
+    assert fast(dataclasses.replace(mk(), contract_a=1.0))
     inp = mk(feat_act=1)
     grid, _, rays, bg = lp.to_device(inp)
     with pytest.raises(lp.LightplaneError) as e:
