@@ -66,6 +66,62 @@ def test_invalid_arguments_are_statuses_not_crashes():
     assert st == lp.LP_OK
 
 
+def test_fast_path_queries_are_host_logic():
+    """Which shapes the matrix-core / wavefront-per-ray kernels cover is decided on the host from
+    the argument structs alone (the device pointers are only checked for NULL and alignment)."""
+    import paper_2404_19760_amd as lp
+    lib = lp._lib
+
+    def grid(kind, channels, res=(8, 8, 8), contract=0.0):
+        g = lp._Grid()
+        g.kind, g.B, g.C = kind, 1, channels
+        g.NX, g.NY, g.NZ = res
+        for p in range(3):
+            g.data[p] = 4096
+            g.aabb_min[p], g.aabb_max[p] = -1.0, 1.0
+        g.contract_a = contract
+        g.dtype = lp.LP_F32
+        return g
+
+    def mlp(*dims):
+        m = lp._Mlp()
+        m.n_layers = len(dims) - 1
+        for i, d in enumerate(dims):
+            m.dims[i] = d
+        for l in range(m.n_layers):
+            m.W[l] = 4096
+            m.b[l] = 4096
+        return m
+
+    render = lambda g, m: lib.lp_has_fast_path(C.byref(g), C.byref(m))
+    assert render(grid(0, 16), mlp(16, 64, 64, 4)) == 1
+    assert render(grid(1, 32), mlp(32, 64, 4)) == 1
+    assert render(grid(0, 16, contract=1.0), mlp(16, 32, 4)) == 1
+    assert render(grid(0, 24), mlp(24, 64, 4)) == 0          # 16 or 32 channels
+    assert render(grid(0, 16), mlp(16, 48, 4)) == 0          # hidden width 32 or 64
+    assert render(grid(0, 16), mlp(16, 64, 32, 4)) == 0      # equal hidden widths
+    assert render(grid(0, 16), mlp(16, 64, 64, 64, 4)) == 0  # at most two hidden layers
+
+    def splat(target, n_in, n_freq=-1, prior=None, m=None):
+        s = lp._Splat()
+        s.n_in, s.n_freq, s.feats = n_in, n_freq, 4096
+        s.prior = C.pointer(prior) if prior is not None else None
+        s.mlp = C.pointer(m) if m is not None else None
+        return lib.lp_splat_has_fast_path(C.byref(target), C.byref(s))
+
+    assert splat(grid(0, 32), 32) == 1                                                   # naive, 32 channels
+    assert splat(grid(1, 16), 16) == 1
+    assert splat(grid(0, 8), 8) == 0
+    assert splat(grid(0, 32), 32, 0, grid(0, 32, (5, 6, 7)), mlp(67, 64, 64, 32)) == 1   # the paper's MLP
+    assert splat(grid(1, 16), 20, 1, grid(1, 16), mlp(45, 64, 16)) == 1
+    assert splat(grid(0, 32), 32, 0, grid(0, 32), mlp(67, 64, 60, 32)) == 0              # hidden width 64 only
+    assert splat(grid(0, 32), 32, 0, grid(0, 16), mlp(51, 64, 32)) == 0                  # prior and target alike
+    assert splat(grid(0, 32), 46, 0, grid(0, 32), mlp(81, 64, 32)) == 0                  # at most 48 per-ray inputs
+    assert splat(grid(0, 32, contract=1.0), 32, 0, grid(0, 32, contract=1.0), mlp(67, 64, 32)) == 0
+    assert splat(grid(0, 32), 32, 0, None, mlp(35, 64, 32)) == 0                         # needs a prior
+    assert splat(grid(0, 32), 30, 0, grid(0, 32), mlp(67, 64, 32)) == 0                  # inconsistent widths
+
+
 def test_product_path_does_not_reach_the_oracle():
     """Nothing under the package names, imports or links the oracle."""
     pkg = os.path.join(ROOT, "paper_2404_19760_amd")
