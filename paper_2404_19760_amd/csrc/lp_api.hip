@@ -130,15 +130,36 @@ lp_status choose_path(const lp::GridDev& g, const lp::MlpDev& m, int32_t mode, P
     }
 }
 
-size_t generic_fwd_lds(const lp::MlpDev& m)
+// LDS of the generic kernels for `lanes` rays per block: the parameters (the backward: a second
+// copy as gradient accumulators unless they are accumulated in the records), then `columns` floats
+// per ray (activations and the kernels' own per-ray columns).
+size_t generic_lds(const lp::MlpDev& m, int param_copies, size_t columns, int lanes)
 {
-    return sizeof(float) * ((size_t)m.param_total + ((size_t)m.act_total + m.n_feat) * kGenericLanes);
+    return sizeof(float) * ((size_t)param_copies * (size_t)m.param_total + columns * (size_t)lanes);
 }
 
-size_t generic_bwd_lds(const lp::MlpDev& m)
+// Rays per block (64, or a partial wavefront of 32 / 16 / 8 when the activation columns of 64 rays
+// would not fit beside the weights) and, for a backward, whether the gradients are accumulated in
+// the records instead of in a second LDS copy of the parameters.  Returns false if nothing fits.
+struct GenericShape {
+    int lanes;
+    int acc_in_record;
+    size_t lds;
+};
+
+bool generic_shape(const lp::MlpDev& m, size_t columns, bool backward, GenericShape* out)
 {
-    return sizeof(float) * (2 * (size_t)m.param_total + (size_t)m.act_total * kGenericLanes +
-                            (2 * (size_t)m.max_width + m.n_feat) * kGenericLanes);
+    for (int lanes = kGenericLanes; lanes >= 8; lanes /= 2)
+        for (int in_record = 0; in_record <= (backward ? 1 : 0); ++in_record) {
+            const size_t lds = generic_lds(m, backward && !in_record ? 2 : 1, columns, lanes);
+            if (lds <= kMaxLds) {
+                out->lanes = lanes;
+                out->acc_in_record = in_record;
+                out->lds = lds;
+                return true;
+            }
+        }
+    return false;
 }
 
 int ws_stride(const lp::MlpDev& m) { return (m.param_total + 63) / 64 * 64; }
@@ -158,15 +179,15 @@ lp_status run_fwd(const lp::GridDev& g, const lp::MlpDev& m, const lp::RaysDev& 
         if (e != hipSuccess) return hip_fail("forward matrix-core kernel launch", e);
         return LP_OK;
     }
-    const size_t lds = generic_fwd_lds(m);
-    if (lds > kMaxLds)
+    GenericShape shape;
+    if (!generic_shape(m, (size_t)m.act_total + m.n_feat, false, &shape))
         return fail(LP_ERR_UNSUPPORTED, "MLP too large for the generic forward kernel's LDS budget");
     hipError_t e = hipFuncSetAttribute((const void*)lp::fwd_generic_kernel,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)shape.lds);
     if (e != hipSuccess) return hip_fail("hipFuncSetAttribute(fwd_generic_kernel)", e);
-    const long long blocks = (r.M + kGenericLanes - 1) / kGenericLanes;
+    const long long blocks = (r.M + shape.lanes - 1) / shape.lanes;
     if (blocks > 0x7fffffffLL) return fail(LP_ERR_UNSUPPORTED, "too many rays for one launch");
-    hipLaunchKernelGGL(lp::fwd_generic_kernel, dim3((unsigned)blocks), dim3(kGenericLanes), lds, s, g, m, r, out);
+    hipLaunchKernelGGL(lp::fwd_generic_kernel, dim3((unsigned)blocks), dim3(shape.lanes), shape.lds, s, g, m, r, out);
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail("forward generic kernel launch", e);
     return LP_OK;
@@ -181,23 +202,20 @@ lp_status run_bwd(const lp::GridDev& g, const lp::MlpDev& m, const lp::RaysDev& 
         if (e != hipSuccess) return hip_fail("backward matrix-core kernel launch", e);
         return LP_OK;
     }
-    size_t lds = generic_bwd_lds(m);
-    lp::BwdIo io = io_in;
-    if (lds > kMaxLds) {   // keep one copy of the parameters in LDS, accumulate gradients in the records
-        lds -= sizeof(float) * (size_t)m.param_total;
-        io.acc_in_record = 1;
-    }
-    if (lds > kMaxLds)
+    GenericShape shape;
+    if (!generic_shape(m, (size_t)m.act_total + 2 * (size_t)m.max_width + m.n_feat, true, &shape))
         return fail(LP_ERR_UNSUPPORTED, "MLP too large for the generic backward kernel's LDS budget");
+    lp::BwdIo io = io_in;
+    io.acc_in_record = shape.acc_in_record;
     hipError_t e = hipFuncSetAttribute((const void*)lp::bwd_generic_kernel,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)shape.lds);
     if (e != hipSuccess) return hip_fail("hipFuncSetAttribute(bwd_generic_kernel)", e);
-    const long long n_tiles = (r.M + kGenericLanes - 1) / kGenericLanes;
+    const long long n_tiles = (r.M + shape.lanes - 1) / shape.lanes;
     const long long blocks = n_tiles < max_records ? n_tiles : max_records;
     const long long tiles_per_block = (n_tiles + blocks - 1) / blocks;
     if (tiles_per_block > 0x7fffffffLL) return fail(LP_ERR_UNSUPPORTED, "too many rays for one launch");
     // blocks whose first tile is past the end write an all-zero record
-    hipLaunchKernelGGL(lp::bwd_generic_kernel, dim3((unsigned)blocks), dim3(kGenericLanes), lds, s, g, m, r, io,
+    hipLaunchKernelGGL(lp::bwd_generic_kernel, dim3((unsigned)blocks), dim3(shape.lanes), shape.lds, s, g, m, r, io,
                        (int)tiles_per_block);
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail("backward generic kernel launch", e);
@@ -552,11 +570,17 @@ lp_status lp_render_dec_fwd(const lp_grid* grid, const lp_decoder* dec, const lp
     std::string err;
     int n_cu = 0;
     if (compute_units(&n_cu, &err)) return fail(LP_ERR_HIP, err);
-    hipError_t e = lp::launch_dec_pack(d, m, (float*)workspace, nullptr, s);
-    if (e != hipSuccess) return hip_fail("decoder merge kernel launch", e);
     lp::FwdOut fo;
     fo.rgb = out; fo.alpha = alpha; fo.depth = depth; fo.cache = ray_cache;
     for (int c = 0; c < LP_MAX_FEATURES; ++c) fo.bg[c] = c < dec->n_feat ? bg[c] : 0.0f;
+    if (math_mode == LP_MATH_DEFAULT && !lp::mfma_supported(g, m) && lp::dec2_supported(g, d, m.n_feat, m.feat_act)) {
+        // two 3-layer MLPs of width 64: two chains on the matrix cores, nothing to merge
+        hipError_t e2 = lp::launch_dec2_fwd(g, lp::dec2_view(d), r, fo, n_cu, s);
+        if (e2 != hipSuccess) return hip_fail("two-chain decoder forward kernel launch", e2);
+        return LP_OK;
+    }
+    hipError_t e = lp::launch_dec_pack(d, m, (float*)workspace, nullptr, s);
+    if (e != hipSuccess) return hip_fail("decoder merge kernel launch", e);
     Path path;
     int records = 0;
     st = decoder_path(g, m, math_mode, &path, &records);
@@ -662,15 +686,16 @@ lp_status lp_splat_fwd(const lp_grid* target, const lp_rays* rays, const lp_spla
         e = lp::launch_splat_mfma(g, m, r, sd, n_cu, s);
         if (e != hipSuccess) return hip_fail("Splatter forward kernel launch", e);
     } else if (rays->M > 0) {
-        const size_t lds = sizeof(float) * ((size_t)m.param_total + (size_t)m.act_total * kGenericLanes);
-        if (lds > kMaxLds) return fail(LP_ERR_UNSUPPORTED, "MLP too large for the Splatter kernel's LDS budget");
+        GenericShape shape;
+        if (!generic_shape(m, (size_t)m.act_total, false, &shape))
+            return fail(LP_ERR_UNSUPPORTED, "MLP too large for the Splatter kernel's LDS budget");
         e = hipFuncSetAttribute((const void*)lp::splat_fwd_generic_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)lds);
+                                (int)shape.lds);
         if (e != hipSuccess) return hip_fail("hipFuncSetAttribute(splat_fwd_generic_kernel)", e);
-        const long long blocks = (rays->M + kGenericLanes - 1) / kGenericLanes;
+        const long long blocks = (rays->M + shape.lanes - 1) / shape.lanes;
         if (blocks > 0x7fffffffLL) return fail(LP_ERR_UNSUPPORTED, "too many rays for one launch");
-        hipLaunchKernelGGL(lp::splat_fwd_generic_kernel, dim3((unsigned)blocks), dim3(kGenericLanes), lds, s, g, m, r,
-                           sd);
+        hipLaunchKernelGGL(lp::splat_fwd_generic_kernel, dim3((unsigned)blocks), dim3(shape.lanes), shape.lds, s, g, m,
+                           r, sd);
         e = hipGetLastError();
         if (e != hipSuccess) return hip_fail("Splatter forward kernel launch", e);
     }
@@ -759,23 +784,20 @@ lp_status lp_splat_bwd(const lp_grid* target, const lp_rays* rays, const lp_spla
         if (e != hipSuccess) return hip_fail("Splatter backward kernel launch", e);
         return LP_OK;
     }
-    size_t lds = sizeof(float) * (2 * (size_t)m.param_total +
-                                  ((size_t)m.act_total + 2 * (size_t)m.max_width + sd.n_in) * kGenericLanes);
-    if (lds > kMaxLds) {   // keep one copy of the parameters in LDS, accumulate gradients in the records
-        lds -= sizeof(float) * (size_t)m.param_total;
-        io.acc_in_record = 1;
-    }
-    if (lds > kMaxLds) return fail(LP_ERR_UNSUPPORTED, "MLP too large for the Splatter backward kernel's LDS budget");
+    GenericShape shape;
+    if (!generic_shape(m, (size_t)m.act_total + 2 * (size_t)m.max_width + sd.n_in, true, &shape))
+        return fail(LP_ERR_UNSUPPORTED, "MLP too large for the Splatter backward kernel's LDS budget");
+    io.acc_in_record = shape.acc_in_record;
     hipError_t e = hipFuncSetAttribute((const void*)lp::splat_bwd_generic_kernel,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)shape.lds);
     if (e != hipSuccess) return hip_fail("hipFuncSetAttribute(splat_bwd_generic_kernel)", e);
     const int max_records = generic_bwd_blocks(n_cu);
-    const long long n_tiles = (rays->M + kGenericLanes - 1) / kGenericLanes;
+    const long long n_tiles = (rays->M + shape.lanes - 1) / shape.lanes;
     const long long blocks = n_tiles < max_records ? n_tiles : max_records;
     const long long tiles_per_block = (n_tiles + blocks - 1) / blocks;
     if (tiles_per_block > 0x7fffffffLL) return fail(LP_ERR_UNSUPPORTED, "too many rays for one launch");
-    hipLaunchKernelGGL(lp::splat_bwd_generic_kernel, dim3((unsigned)blocks), dim3(kGenericLanes), lds, s, g, m, r, sd,
-                       io, (int)tiles_per_block);
+    hipLaunchKernelGGL(lp::splat_bwd_generic_kernel, dim3((unsigned)blocks), dim3(shape.lanes), shape.lds, s, g, m, r,
+                       sd, io, (int)tiles_per_block);
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail("Splatter backward kernel launch", e);
     if (m.param_total > 0) {

@@ -4,6 +4,8 @@
 // samples, decodes and composites sample after sample, keeping only the running
 // transmittance and the rendered features.  A block is a single wavefront; MLP weights
 // live in LDS, activations in LDS columns indexed [feature][lane] (conflict free).
+// The host launches a block with fewer than 64 lanes (a partial wavefront) when the
+// activation columns of 64 rays would not fit in LDS beside the weights.
 // These kernels are the fallback for shapes the matrix-core kernels do not cover.
 #include "lp_device.h"
 #include "lp_kernels.h"
@@ -12,7 +14,10 @@ namespace lp {
 
 namespace {
 
-constexpr int kLanes = 64;
+constexpr int kMaxLanes = 64;
+
+// rays (= lanes) of this block
+__device__ __forceinline__ int block_lanes() { return (int)blockDim.x; }
 
 // Copies all weights and biases into LDS at sW[w_off[l]...] / sW[b_off[l]...].
 __device__ void stage_params(const MlpDev& m, float* sW)
@@ -41,7 +46,7 @@ __device__ __forceinline__ Cell locate(const GridDev& g, double x, double y, dou
     return c;
 }
 
-// feat[k*64 + lane] = h(x)[k], k < C  (Section 3.2)
+// feat[k*lanes + lane] = h(x)[k], k < C  (Section 3.2)
 __device__ void gather_feat(const GridDev& g, int scene, const Cell& c, float* feat, int lane)
 {
     const int C = g.C;
@@ -57,7 +62,7 @@ __device__ void gather_feat(const GridDev& g, int scene, const Cell& c, float* f
                     (((size_t)(c.i[0] + dx) * g.N[1] + (c.i[1] + dy)) * g.N[2] + (c.i[2] + dz)) * C;
                 acc += w * grid_load(g, g.data[0], V + off + k);
             }
-            feat[k * kLanes + lane] = acc;
+            feat[k * block_lanes() + lane] = acc;
         }
     } else {
         // plane p spans axes (a, b) = (0,1), (1,2), (2,0)
@@ -72,7 +77,7 @@ __device__ void gather_feat(const GridDev& g, int scene, const Cell& c, float* f
                     acc += w * grid_load(g, g.data[p], P + ((size_t)(c.i[a] + da) * g.N[b] + (c.i[b] + db)) * C + k);
                 }
             }
-            feat[k * kLanes + lane] = acc;
+            feat[k * block_lanes() + lane] = acc;
         }
     }
 }
@@ -90,7 +95,7 @@ __device__ void scatter_feat(const GridDev& g, float* const d_grid[3], int scene
                             (dz ? c.f[2] : 1.0f - c.f[2]);
             const size_t off =
                 (((size_t)(c.i[0] + dx) * g.N[1] + (c.i[1] + dy)) * g.N[2] + (c.i[2] + dz)) * C;
-            for (int k = 0; k < C; ++k) atomicAdd(V + off + k, w * dfeat[k * kLanes + lane]);
+            for (int k = 0; k < C; ++k) atomicAdd(V + off + k, w * dfeat[k * block_lanes() + lane]);
         }
     } else {
         for (int p = 0; p < 3; ++p) {
@@ -100,7 +105,7 @@ __device__ void scatter_feat(const GridDev& g, float* const d_grid[3], int scene
                 const int da = d >> 1, db = d & 1;
                 const float w = (da ? c.f[a] : 1.0f - c.f[a]) * (db ? c.f[b] : 1.0f - c.f[b]);
                 const size_t off = ((size_t)(c.i[a] + da) * g.N[b] + (c.i[b] + db)) * C;
-                for (int k = 0; k < C; ++k) atomicAdd(P + off + k, w * dfeat[k * kLanes + lane]);
+                for (int k = 0; k < C; ++k) atomicAdd(P + off + k, w * dfeat[k * block_lanes() + lane]);
             }
         }
     }
@@ -118,8 +123,8 @@ __device__ void mlp_forward(const MlpDev& m, const float* sW, float* acts, int l
         const bool hidden = l + 1 < m.n_layers;
         for (int o = 0; o < nout; ++o) {
             float z = B[o];
-            for (int k = 0; k < nin; ++k) z += W[o * nin + k] * acts[(off_in + k) * kLanes + lane];
-            acts[(off_out + o) * kLanes + lane] = hidden ? fmaxf(z, 0.0f) : z;
+            for (int k = 0; k < nin; ++k) z += W[o * nin + k] * acts[(off_in + k) * block_lanes() + lane];
+            acts[(off_out + o) * block_lanes() + lane] = hidden ? fmaxf(z, 0.0f) : z;
         }
         off_in = off_out;
         off_out += nout;
@@ -169,23 +174,23 @@ __device__ float* mlp_backward(const MlpDev& m, const float* sW, float* sdW, con
         __syncthreads();
         // weight and bias gradients: each lane owns a strided set of weights and sums
         // the outer product over the 64 rays of the tile
-        for (int idx = lane; idx < nin * nout; idx += kLanes) {
+        for (int idx = lane; idx < nin * nout; idx += block_lanes()) {
             const int o = idx / nin, k = idx - o * nin;
             float s = 0.0f;
-            for (int r = 0; r < kLanes; ++r) s += dz[o * kLanes + r] * acts[(off_in + k) * kLanes + r];
+            for (int r = 0; r < block_lanes(); ++r) s += dz[o * block_lanes() + r] * acts[(off_in + k) * block_lanes() + r];
             sdW[m.w_off[l] + idx] += s;
         }
-        for (int o = lane; o < nout; o += kLanes) {
+        for (int o = lane; o < nout; o += block_lanes()) {
             float s = 0.0f;
-            for (int r = 0; r < kLanes; ++r) s += dz[o * kLanes + r];
+            for (int r = 0; r < block_lanes(); ++r) s += dz[o * block_lanes() + r];
             sdW[m.b_off[l] + o] += s;
         }
         // input gradient of the lane's own column, through the ReLU of the layer below
         for (int k = 0; k < nin; ++k) {
             float s = 0.0f;
-            for (int o = 0; o < nout; ++o) s += W[o * nin + k] * dz[o * kLanes + lane];
-            if (l > 0 && !(acts[(off_in + k) * kLanes + lane] > 0.0f)) s = 0.0f;
-            dz_next[k * kLanes + lane] = s;
+            for (int o = 0; o < nout; ++o) s += W[o * nin + k] * dz[o * block_lanes() + lane];
+            if (l > 0 && !(acts[(off_in + k) * block_lanes() + lane] > 0.0f)) s = 0.0f;
+            dz_next[k * block_lanes() + lane] = s;
         }
         __syncthreads();
         float* tmp = dz; dz = dz_next; dz_next = tmp;
@@ -199,7 +204,7 @@ __device__ float* mlp_backward(const MlpDev& m, const float* sW, float* sdW, con
 __device__ void set_direction_inputs(const GridDev& g, const MlpDev& m, const RayRegs& q, float* acts, int lane)
 {
     for (int e = g.C; e < m.dims[0]; ++e)
-        acts[e * kLanes + lane] = e - g.C < m.n_enc ? dir_encoding(q.d, e - g.C) : 0.0f;
+        acts[e * block_lanes() + lane] = e - g.C < m.n_enc ? dir_encoding(q.d, e - g.C) : 0.0f;
 }
 
 // rendered feature from the MLP output: logistic sigmoid (colours) or identity
@@ -240,13 +245,13 @@ __device__ void scatter_weight(const GridDev& g, float* const d_w[3], int scene,
     }
 }
 
-// feat[k*64 + lane] = sum_corners weight * G[corner][k] / W[corner]   (0 where W == 0), k < C:
+// feat[k*lanes + lane] = sum_corners weight * G[corner][k] / W[corner]   (0 where W == 0), k < C:
 // the normalised output gradient read at the point
 __device__ void gather_normalised(const GridDev& g, const float* const G[3], const float* const Wt[3], int scene,
                                   const Cell& c, float* feat, int lane)
 {
     const int C = g.C;
-    for (int k = 0; k < C; ++k) feat[k * kLanes + lane] = 0.0f;
+    for (int k = 0; k < C; ++k) feat[k * block_lanes() + lane] = 0.0f;
     if (g.kind == LP_GRID_VOXEL) {
         const size_t cells = (size_t)scene * g.N[0] * g.N[1] * g.N[2];
         for (int d = 0; d < 8; ++d) {
@@ -256,7 +261,7 @@ __device__ void gather_normalised(const GridDev& g, const float* const G[3], con
             const size_t cell = cells + ((size_t)(c.i[0] + dx) * g.N[1] + (c.i[1] + dy)) * g.N[2] + (c.i[2] + dz);
             const float ws = Wt[0][cell];
             const float s = ws > 0.0f ? w / ws : 0.0f;
-            for (int k = 0; k < C; ++k) feat[k * kLanes + lane] += s * G[0][cell * C + k];
+            for (int k = 0; k < C; ++k) feat[k * block_lanes() + lane] += s * G[0][cell * C + k];
         }
     } else {
         for (int p = 0; p < 3; ++p) {
@@ -268,7 +273,7 @@ __device__ void gather_normalised(const GridDev& g, const float* const G[3], con
                 const size_t cell = cells + (size_t)(c.i[a] + da) * g.N[b] + (c.i[b] + db);
                 const float ws = Wt[p][cell];
                 const float s = ws > 0.0f ? w / ws : 0.0f;
-                for (int k = 0; k < C; ++k) feat[k * kLanes + lane] += s * G[p][cell * C + k];
+                for (int k = 0; k < C; ++k) feat[k * block_lanes() + lane] += s * G[p][cell * C + k];
             }
         }
     }
@@ -279,14 +284,14 @@ __device__ void gather_normalised(const GridDev& g, const float* const G[3], con
 __device__ void set_splat_ray_inputs(const SplatDev& sp, const MlpDev& m, const RayRegs& q, long long ray,
                                      float* acts, int lane)
 {
-    for (int k = 0; k < sp.n_in; ++k) acts[k * kLanes + lane] = sp.feats[(size_t)ray * sp.n_in + k];
+    for (int k = 0; k < sp.n_in; ++k) acts[k * block_lanes() + lane] = sp.feats[(size_t)ray * sp.n_in + k];
     const int e0 = sp.n_in + (sp.has_prior ? sp.prior.C : 0);
-    for (int e = 0; e < m.n_enc; ++e) acts[(e0 + e) * kLanes + lane] = dir_encoding(q.d, e);
+    for (int e = 0; e < m.n_enc; ++e) acts[(e0 + e) * block_lanes() + lane] = dir_encoding(q.d, e);
 }
 
 }  // namespace
 
-__global__ __launch_bounds__(kLanes) void splat_fwd_generic_kernel(GridDev tgt, MlpDev m, RaysDev rays, SplatDev sp)
+__global__ __launch_bounds__(kMaxLanes) void splat_fwd_generic_kernel(GridDev tgt, MlpDev m, RaysDev rays, SplatDev sp)
 {
     extern __shared__ float smem[];
     float* sW = smem;
@@ -294,7 +299,7 @@ __global__ __launch_bounds__(kLanes) void splat_fwd_generic_kernel(GridDev tgt, 
     stage_params(m, sW);
     __syncthreads();
     const int lane = threadIdx.x;
-    const long long ray_raw = (long long)blockIdx.x * kLanes + lane;
+    const long long ray_raw = (long long)blockIdx.x * block_lanes() + lane;
     const bool live = ray_raw < rays.M;
     const long long ray = live ? ray_raw : rays.M - 1;
     const RayRegs q = load_ray(rays, ray);
@@ -303,11 +308,11 @@ __global__ __launch_bounds__(kLanes) void splat_fwd_generic_kernel(GridDev tgt, 
     for (int j = 0; j < rays.S; ++j) {
         const Cell c = sample_cell(tgt, q, j);
         if (m.n_layers > 0) {
-            if (sp.has_prior) gather_feat(sp.prior, q.scene, sample_cell(sp.prior, q, j), acts + sp.n_in * kLanes, lane);
+            if (sp.has_prior) gather_feat(sp.prior, q.scene, sample_cell(sp.prior, q, j), acts + sp.n_in * block_lanes(), lane);
             mlp_forward(m, sW, acts, lane);
         }
         if (live) {
-            scatter_feat(tgt, sp.theta, q.scene, c, acts + out_off * kLanes, lane);
+            scatter_feat(tgt, sp.theta, q.scene, c, acts + out_off * block_lanes(), lane);
             scatter_weight(tgt, sp.theta_w, q.scene, c);
         }
     }
@@ -330,7 +335,7 @@ __global__ void fill_zero_kernel(float* p, long long n)
 
 // LDS: params | dparams accumulators | acts (act_total columns) | dz (2 * max_width columns) |
 // pixel-feature gradients (n_in columns)
-__global__ __launch_bounds__(kLanes) void splat_bwd_generic_kernel(GridDev tgt, MlpDev m, RaysDev rays, SplatDev sp,
+__global__ __launch_bounds__(kMaxLanes) void splat_bwd_generic_kernel(GridDev tgt, MlpDev m, RaysDev rays, SplatDev sp,
                                                                    BwdIo io, int tiles_per_block)
 {
     extern __shared__ float smem[];
@@ -340,45 +345,45 @@ __global__ __launch_bounds__(kLanes) void splat_bwd_generic_kernel(GridDev tgt, 
     float* rec = io.ws + (size_t)blockIdx.x * io.ws_stride;
     float* sdW = io.acc_in_record ? rec : sW + m.param_total;
     float* acts = sW + (io.acc_in_record ? 1 : 2) * m.param_total;
-    float* dz0 = acts + m.act_total * kLanes;
-    float* dz1 = dz0 + m.max_width * kLanes;
+    float* dz0 = acts + m.act_total * block_lanes();
+    float* dz1 = dz0 + m.max_width * block_lanes();
     stage_params(m, sW);
     for (int i = threadIdx.x; i < m.param_total; i += blockDim.x) sdW[i] = 0.0f;
     __syncthreads();
     const int lane = threadIdx.x;
-    const long long n_tiles = (rays.M + kLanes - 1) / kLanes;
+    const long long n_tiles = (rays.M + block_lanes() - 1) / block_lanes();
 
     for (int it = 0; it < tiles_per_block; ++it) {
         const long long tile = (long long)blockIdx.x * tiles_per_block + it;
         if (tile >= n_tiles) break;  // uniform over the block
-        const long long ray_raw = tile * kLanes + lane;
+        const long long ray_raw = tile * block_lanes() + lane;
         const bool live = ray_raw < rays.M;
         const long long ray = live ? ray_raw : rays.M - 1;
         const RayRegs q = load_ray(rays, ray);
         set_splat_ray_inputs(sp, m, q, ray, acts, lane);
         // gradient of the pixel feature, summed over the points of the ray: n_in columns after dz1
-        float* dfe = dz1 + m.max_width * kLanes;
-        for (int k = 0; k < sp.n_in; ++k) dfe[k * kLanes + lane] = 0.0f;
+        float* dfe = dz1 + m.max_width * block_lanes();
+        for (int k = 0; k < sp.n_in; ++k) dfe[k * block_lanes() + lane] = 0.0f;
         for (int j = 0; j < rays.S; ++j) {
             const Cell c = sample_cell(tgt, q, j);
             float* dz = dz0;
             gather_normalised(tgt, sp.d_theta, sp.theta_w_in, q.scene, c, dz, lane);
             if (!live)
-                for (int k = 0; k < tgt.C; ++k) dz[k * kLanes + lane] = 0.0f;
+                for (int k = 0; k < tgt.C; ++k) dz[k * block_lanes() + lane] = 0.0f;
             if (m.n_layers > 0) {
                 Cell cp = c;
                 if (sp.has_prior) {
                     cp = sample_cell(sp.prior, q, j);
-                    gather_feat(sp.prior, q.scene, cp, acts + sp.n_in * kLanes, lane);
+                    gather_feat(sp.prior, q.scene, cp, acts + sp.n_in * block_lanes(), lane);
                 }
                 mlp_forward(m, sW, acts, lane);
                 dz = mlp_backward(m, sW, sdW, acts, dz, dz1, lane);
-                if (live && sp.has_prior) scatter_feat(sp.prior, io.d_grid, q.scene, cp, dz + sp.n_in * kLanes, lane);
+                if (live && sp.has_prior) scatter_feat(sp.prior, io.d_grid, q.scene, cp, dz + sp.n_in * block_lanes(), lane);
             }
-            for (int k = 0; k < sp.n_in; ++k) dfe[k * kLanes + lane] += dz[k * kLanes + lane];
+            for (int k = 0; k < sp.n_in; ++k) dfe[k * block_lanes() + lane] += dz[k * block_lanes() + lane];
         }
         if (live)
-            for (int k = 0; k < sp.n_in; ++k) sp.d_feats[(size_t)ray * sp.n_in + k] = dfe[k * kLanes + lane];
+            for (int k = 0; k < sp.n_in; ++k) sp.d_feats[(size_t)ray * sp.n_in + k] = dfe[k * block_lanes() + lane];
     }
     __syncthreads();
     if (!io.acc_in_record)
@@ -389,7 +394,7 @@ namespace {
 
 }  // namespace
 
-__global__ __launch_bounds__(kLanes) void fwd_generic_kernel(GridDev g, MlpDev m, RaysDev rays,
+__global__ __launch_bounds__(kMaxLanes) void fwd_generic_kernel(GridDev g, MlpDev m, RaysDev rays,
                                                              FwdOut out)
 {
     extern __shared__ float smem[];
@@ -399,14 +404,14 @@ __global__ __launch_bounds__(kLanes) void fwd_generic_kernel(GridDev g, MlpDev m
     __syncthreads();
 
     const int lane = threadIdx.x;
-    const long long ray_raw = (long long)blockIdx.x * kLanes + lane;
+    const long long ray_raw = (long long)blockIdx.x * block_lanes() + lane;
     const bool live = ray_raw < rays.M;
     const long long ray = live ? ray_raw : rays.M - 1;
     const RayRegs q = load_ray(rays, ray);
     const int F = m.n_feat, out_off = m.act_total - (1 + F);
-    float* racc = acts + m.act_total * kLanes;  // F columns: the rendered features
+    float* racc = acts + m.act_total * block_lanes();  // F columns: the rendered features
     set_direction_inputs(g, m, q, acts, lane);
-    for (int ch = 0; ch < F; ++ch) racc[ch * kLanes + lane] = 0.0f;
+    for (int ch = 0; ch < F; ++ch) racc[ch * block_lanes() + lane] = 0.0f;
 
     float T = 1.0f, tau = 0.0f, depth = 0.0f;
     for (int j = 0; j < rays.S; ++j) {
@@ -414,18 +419,18 @@ __global__ __launch_bounds__(kLanes) void fwd_generic_kernel(GridDev g, MlpDev m
         const Cell c = sample_cell(g, q, j);
         gather_feat(g, q.scene, c, acts, lane);
         mlp_forward(m, sW, acts, lane);
-        const float sigma = softplus_f(acts[(out_off + 0) * kLanes + lane]);
+        const float sigma = softplus_f(acts[(out_off + 0) * block_lanes() + lane]);
         const float sd = sigma * q.delta;
         const float Tn = T * expf(-sd);
         const float w = T - Tn;
         for (int ch = 0; ch < F; ++ch)
-            racc[ch * kLanes + lane] += w * feature_act(m, acts[(out_off + 1 + ch) * kLanes + lane]);
+            racc[ch * block_lanes() + lane] += w * feature_act(m, acts[(out_off + 1 + ch) * block_lanes() + lane]);
         depth += w * t;
         tau += sd;
         T = Tn;
     }
     if (live) {
-        for (int ch = 0; ch < F; ++ch) out.rgb[F * ray + ch] = racc[ch * kLanes + lane] + T * out.bg[ch];
+        for (int ch = 0; ch < F; ++ch) out.rgb[F * ray + ch] = racc[ch * block_lanes() + lane] + T * out.bg[ch];
         if (out.alpha) out.alpha[ray] = 1.0f - T;
         if (out.depth) out.depth[ray] = depth;
         if (out.cache) out.cache[ray] = tau;
@@ -438,7 +443,7 @@ __global__ __launch_bounds__(kLanes) void fwd_generic_kernel(GridDev g, MlpDev m
 // underflowing), then Eq. (2) with the running suffix sum of w_j a_j.
 // LDS: params | dparams accumulators | acts (act_total columns) | dz (2 * max_width columns) |
 // upstream feature gradients (n_feat columns).
-__global__ __launch_bounds__(kLanes) void bwd_generic_kernel(GridDev g, MlpDev m, RaysDev rays,
+__global__ __launch_bounds__(kMaxLanes) void bwd_generic_kernel(GridDev g, MlpDev m, RaysDev rays,
                                                              BwdIo io, int tiles_per_block)
 {
     extern __shared__ float smem[];
@@ -448,21 +453,21 @@ __global__ __launch_bounds__(kLanes) void bwd_generic_kernel(GridDev g, MlpDev m
     float* rec = io.ws + (size_t)blockIdx.x * io.ws_stride;
     float* sdW = io.acc_in_record ? rec : sW + m.param_total;
     float* acts = sW + (io.acc_in_record ? 1 : 2) * m.param_total;
-    float* dz0 = acts + m.act_total * kLanes;
-    float* dz1 = dz0 + m.max_width * kLanes;
-    float* pcol = dz1 + m.max_width * kLanes;
+    float* dz0 = acts + m.act_total * block_lanes();
+    float* dz1 = dz0 + m.max_width * block_lanes();
+    float* pcol = dz1 + m.max_width * block_lanes();
     stage_params(m, sW);
     for (int i = threadIdx.x; i < m.param_total; i += blockDim.x) sdW[i] = 0.0f;
     __syncthreads();
 
     const int lane = threadIdx.x;
     const int F = m.n_feat, out_off = m.act_total - (1 + F);
-    const long long n_tiles = (rays.M + kLanes - 1) / kLanes;
+    const long long n_tiles = (rays.M + block_lanes() - 1) / block_lanes();
 
     for (int it = 0; it < tiles_per_block; ++it) {
         const long long tile = (long long)blockIdx.x * tiles_per_block + it;
         if (tile >= n_tiles) break;  // uniform over the block
-        const long long ray_raw = tile * kLanes + lane;
+        const long long ray_raw = tile * block_lanes() + lane;
         const bool live = ray_raw < rays.M;
         const long long ray = live ? ray_raw : rays.M - 1;
         const RayRegs q = load_ray(rays, ray);
@@ -470,7 +475,7 @@ __global__ __launch_bounds__(kLanes) void bwd_generic_kernel(GridDev g, MlpDev m
         float pbg = 0.0f;  // p . bg
         for (int ch = 0; ch < F; ++ch) {
             const float p = live ? io.d_rgb[F * ray + ch] : 0.0f;
-            pcol[ch * kLanes + lane] = p;
+            pcol[ch * block_lanes() + lane] = p;
             pbg += p * io.bg[ch];
         }
         const float p_alpha = (live && io.d_alpha) ? io.d_alpha[ray] : 0.0f;
@@ -487,7 +492,7 @@ __global__ __launch_bounds__(kLanes) void bwd_generic_kernel(GridDev g, MlpDev m
             const Cell c = sample_cell(g, q, j);
             gather_feat(g, q.scene, c, acts, lane);
             mlp_forward(m, sW, acts, lane);
-            const float z0 = acts[(out_off + 0) * kLanes + lane];
+            const float z0 = acts[(out_off + 0) * block_lanes() + lane];
             const float sigma = softplus_f(z0);
             const float sd = sigma * q.delta;
             const float Tq = expf(-tau);          // T_q
@@ -496,7 +501,7 @@ __global__ __launch_bounds__(kLanes) void bwd_generic_kernel(GridDev g, MlpDev m
             const float w = Tprev - Tq;
             float a = p_depth * t;
             for (int ch = 0; ch < F; ++ch)
-                a += pcol[ch * kLanes + lane] * feature_act(m, acts[(out_off + 1 + ch) * kLanes + lane]);
+                a += pcol[ch * block_lanes() + lane] * feature_act(m, acts[(out_off + 1 + ch) * block_lanes() + lane]);
             const float dsigma = q.delta * (Tq * a - suffix + kS);
             suffix += w * a;
             tau = tau_prev;
@@ -504,11 +509,11 @@ __global__ __launch_bounds__(kLanes) void bwd_generic_kernel(GridDev g, MlpDev m
             // heads
             float* dz = dz0;
             float* dz_next = dz1;
-            dz[0 * kLanes + lane] = live ? dsigma * logistic_f(z0) : 0.0f;
+            dz[0 * block_lanes() + lane] = live ? dsigma * logistic_f(z0) : 0.0f;
             for (int ch = 0; ch < F; ++ch) {
-                const float f = feature_act(m, acts[(out_off + 1 + ch) * kLanes + lane]);
+                const float f = feature_act(m, acts[(out_off + 1 + ch) * block_lanes() + lane]);
                 const float df = m.feat_act == 0 ? f * (1.0f - f) : 1.0f;
-                dz[(1 + ch) * kLanes + lane] = live ? w * pcol[ch * kLanes + lane] * df : 0.0f;
+                dz[(1 + ch) * block_lanes() + lane] = live ? w * pcol[ch * block_lanes() + lane] * df : 0.0f;
             }
 
             dz = mlp_backward(m, sW, sdW, acts, dz, dz_next, lane);

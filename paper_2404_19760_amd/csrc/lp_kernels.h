@@ -71,4 +71,20 @@ hipError_t launch_dec_pack(const DecLayout& d, const MlpDev& m, float* packed, f
 // adds the combined gradient `grads` into the two MLPs' gradient buffers of `d`
 hipError_t launch_dec_unpack(const DecLayout& d, const MlpDev& m, const float* grads, hipStream_t stream);
 
+// ---- two-MLP decoder with two 3-layer MLPs of width 64 as two chains (lp_mfma_dec2*.hip) ----
+// Device pointers of the two MLPs (three layers each; opacity [64][C], [64][64], [1][64];
+// feature [64][C+E], [64][64], [3][64]) and, for the backward, of their gradients.
+struct Dec2Dev {
+    const float* Ws[3]; const float* bs[3];
+    const float* Wv[3]; const float* bv[3];
+    float* dWs[3]; float* dbs[3];
+    float* dWv[3]; float* dbv[3];
+    int E;   // width of the direction encoding (at most 16)
+};
+// grids of 16 / 32 fp32 channels, both MLPs with two hidden layers of 64, three sigmoid features
+bool dec2_supported(const GridDev& g, const DecLayout& d, int n_feat, int feat_act);
+Dec2Dev dec2_view(const DecLayout& d);
+hipError_t launch_dec2_fwd(const GridDev& g, const Dec2Dev& d, const RaysDev& rays, const FwdOut& out, int n_cu,
+                           hipStream_t stream);
+
 }  // namespace lp

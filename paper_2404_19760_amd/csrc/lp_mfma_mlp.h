@@ -278,31 +278,25 @@ __device__ __forceinline__ void forward_step(const GridDev& g, const uint4* lds,
     mlp_forward<C, H, NH, BWD, NB>(lds, lane, a);
 }
 
-// Forward of one 64-sample step for the forward kernel, which keeps nothing but the decoder
-// outputs: the first layer runs on both N blocks at once (sharing the weight operands), the
-// remaining layers one N block after the other, so that at most one block's accumulators and
-// activations are alive at a time (registers for a second wave per SIMD).  z = outputs of
+// MLP of one 64-sample step from the input fragments of its two N blocks, keeping nothing but
+// the decoder outputs: the first layer runs on both N blocks at once (sharing the weight
+// operands), the remaining layers one N block after the other, so that at most one block's
+// accumulators and activations are alive at a time (registers for a second wave per SIMD).
+// `lds` points at the MLP's weights (layout MlpLds), `bias1` at the first layer's bias (the
+// layout's own, or one that holds a ray's constant inputs already contracted).  z = outputs of
 // sample j0 + lane.
-template <int KIND, int C, int H, int NH, bool CC, int CG = C, int GT = LP_F32>
-__device__ __forceinline__ void forward_outputs(const GridDev& g, const uint4* lds, const RayGeom& q, int j0,
-                                                int S, int lane, float (&z)[4])
+template <int C, int H, int NH>
+__device__ __forceinline__ void mlp_outputs(const uint4* lds, const float* bias1, int lane,
+                                            const Frag (&fh)[2][C / 16], const Frag (&fl)[2][C / 16], float (&z)[4])
 {
     using L = MlpLds<C, H, NH, false, 2>;
     constexpr int MB = L::MB, KS1 = L::KS1, KSH = L::KSH;
-    const int col = lane & 31, grp = lane >> 5;
+    const int grp = lane >> 5;
     const float* sbias = reinterpret_cast<const float*>(lds + L::BIAS);
-
-    Frag fh[2][KS1], fl[2][KS1];
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
-        const int j = min(j0 + 32 * nb + col, S - 1);
-        const Cell3 c = sample_cell<CC>(g, q, j);
-        sample_features<KIND, C, CG, GT>(g, q, c, grp, fh[nb], fl[nb]);
-    }
     Frag h1h[2][KSH], h1l[2][KSH];
     {
         f32x16 acc[MB][2];
-        init_bias<MB, 2>(acc, sbias, grp);
+        init_bias<MB, 2>(acc, bias1, grp);
         layer_mfma<MB, KS1, 2>(acc, lds + L::A1, lane, fh, fl);
         to_operands<MB, true, 2>(acc, h1h, h1l);
     }
@@ -338,6 +332,24 @@ __device__ __forceinline__ void forward_outputs(const GridDev& g, const uint4* l
         // keep the two N blocks apart: interleaving them would double the live registers
         __builtin_amdgcn_sched_barrier(0);
     }
+}
+
+// Sampling + MLP of one 64-sample step for the forward kernel.  z = outputs of sample j0 + lane.
+template <int KIND, int C, int H, int NH, bool CC, int CG = C, int GT = LP_F32>
+__device__ __forceinline__ void forward_outputs(const GridDev& g, const uint4* lds, const RayGeom& q, int j0,
+                                                int S, int lane, float (&z)[4])
+{
+    using L = MlpLds<C, H, NH, false, 2>;
+    constexpr int KS1 = L::KS1;
+    const int col = lane & 31, grp = lane >> 5;
+    Frag fh[2][KS1], fl[2][KS1];
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+        const int j = min(j0 + 32 * nb + col, S - 1);
+        const Cell3 c = sample_cell<CC>(g, q, j);
+        sample_features<KIND, C, CG, GT>(g, q, c, grp, fh[nb], fl[nb]);
+    }
+    mlp_outputs<C, H, NH>(lds, reinterpret_cast<const float*>(lds + L::BIAS), lane, fh, fl, z);
 }
 
 }  // namespace lp

@@ -76,6 +76,19 @@ def test_decoder_matrix_core_with_contract_coordinates(lp, oracle, kind, hidden_
           flush=True)
 
 
+@pytest.mark.parametrize("kind", [VOXEL, TRIPLANE])
+def test_decoder_at_the_papers_size(lp, oracle, kind):
+    """32 grid channels, two 3-layer MLPs of width 64, two octaves of direction encoding (appendix,
+    "Experimental Details"): the merged MLP is 128 wide, too wide for the matrix-core kernels and
+    too large for 64 rays' activations beside it in LDS, so the generic kernels run blocks of
+    fewer rays (partial wavefronts) and accumulate the MLP gradients in their records."""
+    inp = problem(kind, channels=32, hidden_s=(64, 64), hidden_v=(64, 64), n_freq=2, n_feat=3, seed=89,
+                  n_rays=150, samples=24, n_scenes=2, res=(8, 7, 9), grid_std=0.3, bias_std=0.1)
+    grid, _, _, _ = lp.to_device(inp)
+    assert not lp.lp_dec_has_fast_path(grid, lp.decoder_to_device(inp.decoder))
+    print(check_case_dec(lp, oracle, inp, lp.LP_MATH_DEFAULT, label=f"dec paper size kind={kind}"), flush=True)
+
+
 def test_decoder_fast_path_limits(lp):
     mk = lambda **kw: problem(VOXEL, **{**dict(channels=16, hidden_s=(16,), hidden_v=(16,), n_freq=1, n_feat=3, n_rays=8), **kw})
     def fast(inp):
