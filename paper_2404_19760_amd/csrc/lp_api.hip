@@ -518,13 +518,24 @@ int32_t lp_dec_has_fast_path(const lp_grid* grid, const lp_decoder* dec)
     dummy.S = 1;
     lp::GridDev g; lp::MlpDev m; lp::RaysDev r; lp::DecLayout d;
     if (decoder_views(grid, dec, &dummy, nullptr, &g, &m, &r, &d) != LP_OK) return 0;
-    return lp::mfma_supported(g, m) ? 1 : 0;
+    return (lp::mfma_supported(g, m) || lp::dec2_supported(g, d, m.n_feat, m.feat_act)) ? 1 : 0;
 }
 
 // kernel family and number of partial-sum records for a decoder call
-lp_status decoder_path(const lp::GridDev& g, const lp::MlpDev& m, int32_t math_mode, Path* path, int* records)
+lp_status decoder_path(const lp::GridDev& g, const lp::MlpDev& m, const lp::DecLayout& d, int32_t math_mode,
+                       Path* path, int* records, bool* two_chains)
 {
-    lp_status st = choose_path(g, m, math_mode, path);
+    // two 3-layer MLPs of width 64 run as two chains on the matrix cores (the merged MLP would be
+    // 128 wide, which only the generic kernels take)
+    *two_chains = math_mode != LP_MATH_GENERIC && !lp::mfma_supported(g, m) &&
+                  lp::dec2_supported(g, d, m.n_feat, m.feat_act);
+    lp_status st = LP_OK;
+    if (*two_chains) {
+        if (math_mode != LP_MATH_DEFAULT && math_mode != LP_MATH_BF16X3) return fail(LP_ERR_INVALID_ARG, "unknown math_mode");
+        *path = Path::Mfma;
+    } else {
+        st = choose_path(g, m, math_mode, path);
+    }
     if (st != LP_OK) return st;
     std::string err;
     int n_cu = 0;
@@ -542,7 +553,8 @@ lp_status lp_dec_workspace_bytes(const lp_grid* grid, const lp_decoder* dec, con
     Path path;
     int records = 0;
     // alignment of the grid tensors decides the path too; sizes take the larger record count
-    st = decoder_path(g, m, math_mode, &path, &records);
+    bool two_chains = false;
+    st = decoder_path(g, m, d, math_mode, &path, &records, &two_chains);
     if (st != LP_OK) return st;
     const size_t params = align256(sizeof(float) * (size_t)m.param_total);
     if (fwd_bytes) *fwd_bytes = params;
@@ -573,18 +585,18 @@ lp_status lp_render_dec_fwd(const lp_grid* grid, const lp_decoder* dec, const lp
     lp::FwdOut fo;
     fo.rgb = out; fo.alpha = alpha; fo.depth = depth; fo.cache = ray_cache;
     for (int c = 0; c < LP_MAX_FEATURES; ++c) fo.bg[c] = c < dec->n_feat ? bg[c] : 0.0f;
-    if (math_mode == LP_MATH_DEFAULT && !lp::mfma_supported(g, m) && lp::dec2_supported(g, d, m.n_feat, m.feat_act)) {
-        // two 3-layer MLPs of width 64: two chains on the matrix cores, nothing to merge
+    Path path;
+    int records = 0;
+    bool two_chains = false;
+    st = decoder_path(g, m, d, math_mode, &path, &records, &two_chains);
+    if (st != LP_OK) return st;
+    if (two_chains) {   // nothing to merge
         hipError_t e2 = lp::launch_dec2_fwd(g, lp::dec2_view(d), r, fo, n_cu, s);
         if (e2 != hipSuccess) return hip_fail("two-chain decoder forward kernel launch", e2);
         return LP_OK;
     }
     hipError_t e = lp::launch_dec_pack(d, m, (float*)workspace, nullptr, s);
     if (e != hipSuccess) return hip_fail("decoder merge kernel launch", e);
-    Path path;
-    int records = 0;
-    st = decoder_path(g, m, math_mode, &path, &records);
-    if (st != LP_OK) return st;
     return run_fwd(g, m, r, fo, path, n_cu, s);
 }
 
@@ -625,6 +637,23 @@ lp_status lp_render_dec_bwd(const lp_grid* grid, const lp_decoder* dec, const lp
     const size_t params = align256(sizeof(float) * (size_t)m.param_total);
     float* packed = (float*)workspace;
     float* grads = (float*)((char*)workspace + params);
+    Path path;
+    int records = 0;
+    bool two_chains = false;
+    st = decoder_path(g, m, d, math_mode, &path, &records, &two_chains);
+    if (st != LP_OK) return st;
+    if (two_chains) {   // the two MLPs as they are: their gradients are accumulated in place
+        lp::BwdIo io2;
+        std::memset(&io2, 0, sizeof(io2));
+        io2.d_rgb = d_out; io2.d_alpha = d_alpha; io2.d_depth = d_depth; io2.cache = ray_cache;
+        for (int p = 0; p < 3; ++p) io2.d_grid[p] = p < n_planes ? d_grid[p] : nullptr;
+        for (int c = 0; c < dec->n_feat; ++c) io2.bg[c] = bg[c];
+        io2.ws = (float*)((char*)workspace + 2 * params);
+        io2.ws_stride = ws_stride(m);
+        hipError_t e2 = lp::launch_dec2_bwd(g, lp::dec2_view(d), r, io2, n_cu, s);
+        if (e2 != hipSuccess) return hip_fail("two-chain decoder backward kernel launch", e2);
+        return LP_OK;
+    }
     hipError_t e = lp::launch_dec_pack(d, m, packed, grads, s);
     if (e != hipSuccess) return hip_fail("decoder merge kernel launch", e);
 
@@ -636,10 +665,6 @@ lp_status lp_render_dec_bwd(const lp_grid* grid, const lp_decoder* dec, const lp
     for (int c = 0; c < dec->n_feat; ++c) io.bg[c] = bg[c];
     io.ws = (float*)((char*)workspace + 2 * params);
     io.ws_stride = ws_stride(m);
-    Path path;
-    int records = 0;
-    st = decoder_path(g, m, math_mode, &path, &records);
-    if (st != LP_OK) return st;
     st = run_bwd(g, m, r, io, path == Path::Mfma, records, n_cu, s);
     if (st != LP_OK) return st;
     e = lp::launch_dec_unpack(d, m, grads, s);

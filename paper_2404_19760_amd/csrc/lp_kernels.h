@@ -86,5 +86,10 @@ bool dec2_supported(const GridDev& g, const DecLayout& d, int n_feat, int feat_a
 Dec2Dev dec2_view(const DecLayout& d);
 hipError_t launch_dec2_fwd(const GridDev& g, const Dec2Dev& d, const RaysDev& rays, const FwdOut& out, int n_cu,
                            hipStream_t stream);
+// backward: ACCUMULATES into io.d_grid and into d's gradient pointers; io.ws holds
+// mfma_bwd_records(n_cu) records of io.ws_stride floats (at least either MLP's parameter count);
+// io.dW / io.db are not used
+hipError_t launch_dec2_bwd(const GridDev& g, const Dec2Dev& d, const RaysDev& rays, const BwdIo& io, int n_cu,
+                           hipStream_t stream);
 
 }  // namespace lp

@@ -220,9 +220,11 @@ __device__ __forceinline__ void sample_features(const GridDev& g, const RayGeom&
 }
 
 // MLP forward of one step from the input features a.fh / a.fl: fills the hidden activations and
-// the decoder outputs a.z.
+// the decoder outputs a.z.  bias1, if given, replaces the first layer's bias (one that holds a
+// ray's constant inputs already contracted).
 template <int C, int H, int NH, bool BWD, int NB>
-__device__ __forceinline__ void mlp_forward(const uint4* lds, int lane, StepActs<C, H, NH, NB>& a)
+__device__ __forceinline__ void mlp_forward(const uint4* lds, int lane, StepActs<C, H, NH, NB>& a,
+                                            const float* bias1 = nullptr)
 {
     using L = MlpLds<C, H, NH, BWD, NB>;
     constexpr int MB = L::MB, KS1 = L::KS1, KSH = L::KSH;
@@ -230,7 +232,7 @@ __device__ __forceinline__ void mlp_forward(const uint4* lds, int lane, StepActs
     const float* sbias = reinterpret_cast<const float*>(lds + L::BIAS);
 
     f32x16 acc[MB][NB];
-    init_bias<MB, NB>(acc, sbias, grp);
+    init_bias<MB, NB>(acc, bias1 ? bias1 : sbias, grp);
     layer_mfma<MB, KS1, NB>(acc, lds + L::A1, lane, a.fh, a.fl);
     to_operands<MB, true, NB>(acc, a.h1h, a.h1l);
     if constexpr (NH == 2) {

@@ -77,16 +77,30 @@ def test_decoder_matrix_core_with_contract_coordinates(lp, oracle, kind, hidden_
 
 
 @pytest.mark.parametrize("kind", [VOXEL, TRIPLANE])
-def test_decoder_at_the_papers_size(lp, oracle, kind):
-    """32 grid channels, two 3-layer MLPs of width 64, two octaves of direction encoding (appendix,
-    "Experimental Details"): the merged MLP is 128 wide, too wide for the matrix-core kernels and
-    too large for 64 rays' activations beside it in LDS, so the generic kernels run blocks of
-    fewer rays (partial wavefronts) and accumulate the MLP gradients in their records."""
+@pytest.mark.parametrize("channels,n_freq,contract", [(32, 2, 0.0), (16, 1, 0.0), (32, 0, 1.3)])
+def test_decoder_at_the_papers_size(lp, oracle, kind, channels, n_freq, contract):
+    """Two 3-layer MLPs of width 64 (appendix, "Experimental Details") on 16 / 32 grid channels:
+    merged they would be 128 wide; they run as two chains on the matrix cores, the backward in
+    two passes.  Ragged sample counts, several scenes, once with contract coordinates."""
+    kw = dict(origin_radius=1.5, near=(0.0, 0.3), far=(6.0, 20.0)) if contract else {}
+    inp = problem(kind, channels=channels, hidden_s=(64, 64), hidden_v=(64, 64), n_freq=n_freq, n_feat=3, seed=89,
+                  n_rays=203, samples=75, n_scenes=2, res=(12, 10, 11), grid_std=0.3, bias_std=0.1, **kw)
+    if contract:
+        inp = dataclasses.replace(inp, contract_a=contract)
+    grid, _, _, _ = lp.to_device(inp)
+    assert lp.lp_dec_has_fast_path(grid, lp.decoder_to_device(inp.decoder))
+    print(check_case_dec(lp, oracle, inp, lp.LP_MATH_BF16X3, label=f"dec two chains kind={kind} C={channels}"),
+          flush=True)
+
+
+@pytest.mark.parametrize("kind", [VOXEL, TRIPLANE])
+def test_decoder_at_the_papers_size_on_the_generic_kernels(lp, oracle, kind):
+    """The same decoder on the generic kernels: the merged MLP is too large for 64 rays'
+    activations beside it in LDS, so they run blocks of fewer rays (partial wavefronts) and
+    accumulate the MLP gradients in their records."""
     inp = problem(kind, channels=32, hidden_s=(64, 64), hidden_v=(64, 64), n_freq=2, n_feat=3, seed=89,
                   n_rays=150, samples=24, n_scenes=2, res=(8, 7, 9), grid_std=0.3, bias_std=0.1)
-    grid, _, _, _ = lp.to_device(inp)
-    assert not lp.lp_dec_has_fast_path(grid, lp.decoder_to_device(inp.decoder))
-    print(check_case_dec(lp, oracle, inp, lp.LP_MATH_DEFAULT, label=f"dec paper size kind={kind}"), flush=True)
+    print(check_case_dec(lp, oracle, inp, lp.LP_MATH_GENERIC, label=f"dec paper size generic kind={kind}"), flush=True)
 
 
 def test_decoder_fast_path_limits(lp):
