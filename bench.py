@@ -43,7 +43,7 @@ def parse():
                     help="storage type of the grid on the GPU (gradients stay f32)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
-    ap.add_argument("--also", default="batched,single_scene,contract,decoder,splat_naive,splat_mlp",
+    ap.add_argument("--also", default="batched,single_scene,contract,decoder,decoder_paper,splat_naive,splat_mlp",
                     help="further workloads reported for context under 'also' (comma-separated, '' to skip)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy kernel (reference for HBM counters)")
