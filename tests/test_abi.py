@@ -102,6 +102,20 @@ def test_fast_path_queries_are_host_logic():
     assert render(grid(0, 16), mlp(16, 64, 32, 4)) == 0      # equal hidden widths
     assert render(grid(0, 16), mlp(16, 64, 64, 64, 4)) == 0  # at most two hidden layers
 
+    def decoder(g, dims_s, dims_v, n_freq, n_feat=3, feat_act=0):
+        d = lp._Decoder()
+        d.opacity, d.feature = mlp(*dims_s), mlp(*dims_v)
+        d.n_freq, d.n_feat, d.feat_act = n_freq, n_feat, feat_act
+        return lib.lp_dec_has_fast_path(C.byref(g), C.byref(d))
+
+    assert decoder(grid(0, 16), (16, 32, 32, 1), (31, 32, 32, 3), 2) == 1     # merged into one 64-wide MLP
+    assert decoder(grid(1, 32), (32, 64, 64, 1), (47, 64, 64, 3), 2) == 1     # the paper's size: two chains
+    assert decoder(grid(0, 16, contract=1.0), (16, 64, 64, 1), (19, 64, 64, 3), 0) == 1
+    assert decoder(grid(0, 32), (32, 64, 64, 1), (53, 64, 64, 3), 3) == 0     # at most 16 direction inputs
+    assert decoder(grid(0, 32), (32, 64, 1), (47, 64, 64, 3), 2) == 0         # two chains: both 3-layer
+    assert decoder(grid(0, 32), (32, 64, 64, 1), (47, 64, 64, 4), 2, n_feat=4) == 0
+    assert decoder(grid(0, 24), (24, 64, 64, 1), (39, 64, 64, 3), 2) == 0
+
     def splat(target, n_in, n_freq=-1, prior=None, m=None):
         s = lp._Splat()
         s.n_in, s.n_freq, s.feats = n_in, n_freq, 4096
