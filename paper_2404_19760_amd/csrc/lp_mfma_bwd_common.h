@@ -47,6 +47,51 @@ __device__ __forceinline__ void relu_mask(f32x16 (&acc)[MB][kBwdNB], const Frag 
             }
 }
 
+// ---- matrix-core helpers of the backward kernels ----
+__device__ __forceinline__ f32x16 mfma1(const Frag& a, const Frag& b, f32x16 acc)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a), as_bf16x8(b), acc, 0, 0, 0);
+}
+
+__device__ __forceinline__ f32x16 zero16()
+{
+    const f32x16 z = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+    return z;
+}
+
+// Keeps a long-lived accumulator in the accumulation register file between its updates, so
+// that the vector registers stay free for the working set of a step.
+__device__ __forceinline__ void park(f32x16& acc)
+{
+    asm volatile("" : "+a"(acc));
+}
+
+// Registers of a transposed block D[sample][feature] (values exactly representable in bf16)
+// -> operand fragments over the samples: K-step ks takes registers 8 ks .. 8 ks + 7.
+__device__ __forceinline__ void pack_exact(const f32x16& d, Frag (&f)[kBwdKS])
+{
+#pragma unroll
+    for (int ks = 0; ks < kBwdKS; ++ks)
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+            f[ks].d[w] = __builtin_amdgcn_perm(__float_as_uint(d[8 * ks + 2 * w + 1]), __float_as_uint(d[8 * ks + 2 * w]),
+                                               0x07060302u);
+}
+
+// 0/1 selection operand: element e of lane (j, grp) is 1.0 iff index_of(grp, e) == j.
+template <class IndexFn>
+__device__ __forceinline__ Frag selection(int j, int grp, IndexFn index_of)
+{
+    Frag f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        const uint32_t lo = index_of(grp, 2 * w) == j ? 0x3f80u : 0u;
+        const uint32_t hi = index_of(grp, 2 * w + 1) == j ? 0x3f80u : 0u;
+        f.d[w] = lo | (hi << 16);
+    }
+    return f;
+}
+
 // ---- scatter records: what the channel lanes need to know about each sample of the step ----
 // 16 dwords per sample.  voxel: 8 corner weights, then the element offset of corner 0; the
 // weights are in corner order 4dx + 2dy + dz for 32 channels and in order 4dz + 2dx + dy for 16

@@ -16,7 +16,7 @@
 // chain's backward, so that only one chain's activations are alive at a time.
 // Each pass writes one record of partial sums per wave and is followed by the reduction kernel.
 #pragma once
-#include "lp_mfma_bwd.h"
+#include "lp_mfma_bwd_common.h"
 #include "lp_mfma_dec2.h"
 
 namespace lp {
@@ -24,6 +24,7 @@ namespace lp {
 namespace {
 
 using dec2::kH;
+using dec2::kWaves;
 
 // gradient accumulators of one chain, alive for a whole pass
 template <int C>
