@@ -200,7 +200,7 @@ lp_status lp_render_dec_bwd(const lp_grid* grid, const lp_decoder* dec, const lp
    three sigmoid features on fp32 grids: 16 grid channels with a merged hidden width (opacity +
    feature MLP, layer by layer) of 32 or 64, one or two hidden layers, at most 16 direction
    inputs; and 16 or 32 grid channels with two 3-layer MLPs of width 64 each (the paper's
-   experimental size), which run as two chains. */
+   experimental size, any n_freq), which run as two chains. */
 int32_t lp_dec_has_fast_path(const lp_grid* grid, const lp_decoder* dec);
 
 /* ---- Splatter (Section 3.3 "Splatter"; appendix "Normalization Process in Splatter") ---------

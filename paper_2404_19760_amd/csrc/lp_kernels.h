@@ -79,7 +79,7 @@ struct Dec2Dev {
     const float* Wv[3]; const float* bv[3];
     float* dWs[3]; float* dbs[3];
     float* dWv[3]; float* dbv[3];
-    int E;   // width of the direction encoding (at most 16)
+    int E;   // width of the direction encoding (at most 32)
 };
 // grids of 16 / 32 fp32 channels, both MLPs with two hidden layers of 64, three sigmoid features
 bool dec2_supported(const GridDev& g, const DecLayout& d, int n_feat, int feat_act);

@@ -21,17 +21,20 @@ namespace dec2 {
 constexpr int kWaves = 4;
 constexpr int kH = 64;
 
+constexpr int kMaxDir = 32;   // direction inputs (two K-steps); four octaves need 27
+
 // LDS layout in 16-byte units: the two chains in the single-MLP layout, the feature chain's
 // direction columns of the first layer, then per wave the ray's feature-chain bias (64 floats)
-// and its encoded direction (16 floats).
+// and its encoded direction (32 floats).
 template <int C, bool BWD, int NB>
 struct Lds {
     using Chain = MlpLds<C, kH, 2, BWD, NB>;
+    static constexpr int KSE = kMaxDir / 16;
     static constexpr int S = 0;                       // opacity chain
     static constexpr int V = Chain::END;              // feature chain
-    static constexpr int A1E = V + Chain::END;        // W1 of the feature chain, direction columns [2][1]
-    static constexpr int WAVE = A1E + 2 * 128;
-    static constexpr int W_BIAS = 0, W_X = kH / 4, W_UNITS = W_X + 4;
+    static constexpr int A1E = V + Chain::END;        // W1 of the feature chain, direction columns [2][KSE]
+    static constexpr int WAVE = A1E + 2 * KSE * 128;
+    static constexpr int W_BIAS = 0, W_X = kH / 4, W_UNITS = W_X + kMaxDir / 4;
     static constexpr int END = WAVE + kWaves * W_UNITS;
 };
 
@@ -73,11 +76,11 @@ __device__ __forceinline__ void stage_decoder(uint4* lds, const Dec2Dev& d)
     using L = Lds<C, BWD, NB>;
     stage_chain<C, BWD, NB>(lds + L::S, d.Ws[0], C, d.Ws[1], d.Ws[2], d.bs[0], d.bs[1], d.bs[2], 1, 0);
     stage_chain<C, BWD, NB>(lds + L::V, d.Wv[0], C + d.E, d.Wv[1], d.Wv[2], d.bv[0], d.bv[1], d.bv[2], 3, 1);
-    // direction columns of the feature chain's first layer: one K-step, element e of lane group g
-    // is direction input 8 g + e
+    // direction columns of the feature chain's first layer: element e of lane group g in K-step s
+    // is direction input 16 s + 8 g + e
     const int E = d.E;
-    stage_operand(lds + L::A1E, d.Wv[0], 2, 1, C + E, [](int mb, int i) { return 32 * mb + i; },
-                  [=](int, int gg, int e) { return 8 * gg + e < E ? C + 8 * gg + e : -1; });
+    stage_operand(lds + L::A1E, d.Wv[0], 2, L::KSE, C + E, [](int mb, int i) { return 32 * mb + i; },
+                  [=](int s, int gg, int e) { return 16 * s + 8 * gg + e < E ? C + 16 * s + 8 * gg + e : -1; });
 }
 
 // The ray's feature-chain bias b1 + W1[:, direction inputs] enc(d) into the wave's LDS area.
@@ -93,20 +96,21 @@ __device__ __forceinline__ void ray_direction_bias(uint4* lds, const Dec2Dev& d,
     const float x_lane = lane < d.E ? dir_encoding(dir, lane) : 0.0f;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
-    if (lane < 16) ray_x[lane] = x_lane;
+    if (lane < kMaxDir) ray_x[lane] = x_lane;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     f32x16 acc[2][1];
     init_bias<2, 1>(acc, reinterpret_cast<const float*>(lds + L::V + L::Chain::BIAS), grp);
-    Frag eh[1][1], el[1][1];
-    {
+    Frag eh[1][L::KSE], el[1][L::KSE];
+#pragma unroll
+    for (int s = 0; s < L::KSE; ++s) {
         float x[8];
-        *reinterpret_cast<f32x4*>(x) = *reinterpret_cast<const f32x4*>(ray_x + 8 * grp);
-        *reinterpret_cast<f32x4*>(x + 4) = *reinterpret_cast<const f32x4*>(ray_x + 8 * grp + 4);
-        split8(x, eh[0][0], el[0][0]);
+        *reinterpret_cast<f32x4*>(x) = *reinterpret_cast<const f32x4*>(ray_x + 16 * s + 8 * grp);
+        *reinterpret_cast<f32x4*>(x + 4) = *reinterpret_cast<const f32x4*>(ray_x + 16 * s + 8 * grp + 4);
+        split8(x, eh[0][s], el[0][s]);
     }
-    layer_mfma<2, 1, 1>(acc, lds + L::A1E, lane, eh, el);
+    layer_mfma<2, L::KSE, 1>(acc, lds + L::A1E, lane, eh, el);
     if (col == 0) {  // every column holds the same values
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)

@@ -238,7 +238,7 @@ __global__ __launch_bounds__(kWaves * 64) void dec2_bwd_kernel(GridDev g, Dec2De
 
     ChainGrads<C> G;
     G.clear();
-    f32x16 dW1e[2];   // PASS 1: [64 x direction inputs (16 of 32 columns)]
+    f32x16 dW1e[2];   // PASS 1: [64 x direction inputs]
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb) { dW1e[mb] = zero16(); park(dW1e[mb]); }
 
@@ -341,7 +341,7 @@ __global__ __launch_bounds__(kWaves * 64) void dec2_bwd_kernel(GridDev g, Dec2De
             Frag bh, bl;
             {
                 uint32_t h, l;
-                split2(col < 16 ? ray_x[col] : 0.0f, 0.0f, h, l);
+                split2(ray_x[col], 0.0f, h, l);
                 bh.d[0] = grp == 0 ? h : 0u; bl.d[0] = grp == 0 ? l : 0u;
 #pragma unroll
                 for (int w = 1; w < 4; ++w) bh.d[w] = bl.d[w] = 0u;

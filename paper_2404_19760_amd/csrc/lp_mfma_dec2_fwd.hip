@@ -108,7 +108,7 @@ bool dec2_supported(const GridDev& g, const DecLayout& d, int n_feat, int feat_a
     if (g.C != 16 && g.C != 32) return false;
     if (g.dtype != LP_F32) return false;
     if (n_feat != 3 || feat_act != 0) return false;
-    if (d.Ls != 3 || d.Lv != 3 || d.E > 16) return false;
+    if (d.Ls != 3 || d.Lv != 3 || d.E > dec2::kMaxDir) return false;
     if (d.dims_s[0] != g.C || d.dims_s[1] != kH || d.dims_s[2] != kH || d.dims_s[3] != 1) return false;
     if (d.dims_v[0] != g.C + d.E || d.dims_v[1] != kH || d.dims_v[2] != kH || d.dims_v[3] != 3) return false;
     // 32-bit byte offsets inside one scene's tensor, 16-byte aligned tensors (as the single-MLP kernels)

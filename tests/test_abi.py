@@ -111,7 +111,8 @@ def test_fast_path_queries_are_host_logic():
     assert decoder(grid(0, 16), (16, 32, 32, 1), (31, 32, 32, 3), 2) == 1     # merged into one 64-wide MLP
     assert decoder(grid(1, 32), (32, 64, 64, 1), (47, 64, 64, 3), 2) == 1     # the paper's size: two chains
     assert decoder(grid(0, 16, contract=1.0), (16, 64, 64, 1), (19, 64, 64, 3), 0) == 1
-    assert decoder(grid(0, 32), (32, 64, 64, 1), (53, 64, 64, 3), 3) == 0     # at most 16 direction inputs
+    assert decoder(grid(0, 32), (32, 64, 64, 1), (59, 64, 64, 3), 4) == 1     # any number of octaves
+    assert decoder(grid(0, 16), (16, 16, 16, 1), (37, 48, 48, 3), 3) == 0     # merged: at most 16 direction inputs
     assert decoder(grid(0, 32), (32, 64, 1), (47, 64, 64, 3), 2) == 0         # two chains: both 3-layer
     assert decoder(grid(0, 32), (32, 64, 64, 1), (47, 64, 64, 4), 2, n_feat=4) == 0
     assert decoder(grid(0, 24), (24, 64, 64, 1), (39, 64, 64, 3), 2) == 0

@@ -77,7 +77,7 @@ def test_decoder_matrix_core_with_contract_coordinates(lp, oracle, kind, hidden_
 
 
 @pytest.mark.parametrize("kind", [VOXEL, TRIPLANE])
-@pytest.mark.parametrize("channels,n_freq,contract", [(32, 2, 0.0), (16, 1, 0.0), (32, 0, 1.3)])
+@pytest.mark.parametrize("channels,n_freq,contract", [(32, 2, 0.0), (16, 1, 0.0), (32, 0, 1.3), (16, 4, 0.0)])
 def test_decoder_at_the_papers_size(lp, oracle, kind, channels, n_freq, contract):
     """Two 3-layer MLPs of width 64 (appendix, "Experimental Details") on 16 / 32 grid channels:
     merged they would be 128 wide; they run as two chains on the matrix cores, the backward in
