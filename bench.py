@@ -74,7 +74,8 @@ def cpu_baseline(inp, budget_s: float):
             f"all {inp.samples} samples each, fp64 forward + stored-forward reverse-mode backward, {t:.1f} s"}
 
 
-def measure(lp, torch, name, mode, steps, warmup, calibrate_copy=False, grid_dtype="f32", aabb=None):
+def measure(lp, torch, name, mode, steps, warmup, calibrate_copy=False, grid_dtype="f32", aabb=None,
+            measure_memory=False):
     """Times `steps` forward+backward steps of workload `name`; returns the result fields."""
     import lp_inputs
     w = lp_inputs.WORKLOADS[name]
@@ -149,8 +150,30 @@ def measure(lp, torch, name, mode, steps, warmup, calibrate_copy=False, grid_dty
     fwd_ms = float(np.mean([e0.elapsed_time(e1) for e0, e1, _, _ in events]))
     bwd_ms = float(np.mean([e2.elapsed_time(e3) for _, _, e2, e3 in events]))
     mid_ms = float(np.mean([e1.elapsed_time(e2) for _, e1, e2, _ in events]))   # loss gradient + zeroing
+    memory = None
+    if measure_memory and dec is None:
+        # Device memory a forward + backward needs beyond its inputs and the gradient buffers:
+        # outputs (20 B per ray), the cached scalar (4 B per ray), the upstream gradient and the
+        # workspace; measured as the allocator's peak over one step, at S and at 4 S samples.
+        import dataclasses
+        memory = {"state_kept_for_backward_bytes_per_ray": 4}
+        for mult in (1, 4):
+            r2 = dataclasses.replace(rays, samples=inp.samples * mult)
+            torch.cuda.synchronize()
+            torch.cuda.reset_peak_memory_stats()
+            base = torch.cuda.memory_allocated()
+            o = [torch.empty((m, 3), device=dev), torch.empty(m, device=dev), torch.empty(m, device=dev),
+                 torch.empty(m, device=dev)]
+            w2 = torch.empty(lp.lp_bwd_workspace_bytes(grid, mlp, r2, mode), dtype=torch.uint8, device=dev)
+            lp.lp_render_fwd(grid, mlp, r2, bg, o[0], o[1], o[2], o[3], mode)
+            g2 = (o[0] - target) * inv
+            lp.lp_render_bwd(grid, mlp, r2, bg, g2, None, None, o[3], d_grid, grads[0], grads[1], w2, mode)
+            torch.cuda.synchronize()
+            memory["peak_extra_bytes_at_%dS" % mult] = int(torch.cuda.max_memory_allocated() - base)
+            memory["workspace_bytes_at_%dS" % mult] = int(w2.numel())
+            del o, w2, g2
     return dict(w=w, inp=inp, fast=fast, rays=m, samples=m * inp.samples, elapsed=elapsed,
-                fwd_ms=fwd_ms, bwd_ms=bwd_ms, mid_ms=mid_ms)
+                fwd_ms=fwd_ms, bwd_ms=bwd_ms, mid_ms=mid_ms, memory=memory)
 
 
 def measure_splat(lp, torch, name, steps, warmup):
@@ -200,7 +223,8 @@ def main():
         print("bench.py: no GPU visible; the Renderer has no CPU path", file=sys.stderr)
         sys.exit(2)
     mode = {"default": lp.LP_MATH_DEFAULT, "generic": lp.LP_MATH_GENERIC, "bf16x3": lp.LP_MATH_BF16X3}[args.math]
-    r = measure(lp, torch, args.config, mode, args.steps, args.warmup, args.calibrate_copy, args.grid_dtype, args.aabb)
+    r = measure(lp, torch, args.config, mode, args.steps, args.warmup, args.calibrate_copy, args.grid_dtype, args.aabb,
+                measure_memory=not args.calibrate_copy)
     w, inp, fast, m, samples = r["w"], r["inp"], r["fast"], r["rays"], r["samples"]
     elapsed, fwd_avg, bwd_avg = r["elapsed"], r["fwd_ms"], r["bwd_ms"]
 
@@ -236,6 +260,7 @@ def main():
                               "frac_hbm_peak": (2 * g_bytes + g_write) * samples / ((fwd_avg + bwd_avg) * 1e-3) / 1e9
                               / HBM_PEAK_GBS},
         "loss_grad_and_zeroing_ms": r["mid_ms"],
+        "memory": r["memory"],
         "alu_view": {"flop_per_sample_fwd": f_fwd, "flop_per_sample_fwd_bwd": f_all,
                      "fwd_TFLOPs": f_fwd * samples / (fwd_avg * 1e-3) / 1e12,
                      "fwd_bwd_TFLOPs": f_all * samples / step_s / 1e12,
