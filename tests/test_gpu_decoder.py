@@ -93,6 +93,17 @@ def test_decoder_at_the_papers_size(lp, oracle, kind, channels, n_freq, contract
           flush=True)
 
 
+@pytest.mark.parametrize("n_rays,samples", [(1, 1), (5, 33), (3, 64), (259, 2)])
+def test_decoder_two_chains_degenerate_sizes(lp, oracle, n_rays, samples):
+    """Fewer rays than a workgroup has waves, a single sample, sample counts around the 32- and
+    64-sample steps."""
+    inp = problem(VOXEL, channels=32, hidden_s=(64, 64), hidden_v=(64, 64), n_freq=1, n_feat=3, seed=97,
+                  n_rays=n_rays, samples=samples, res=(6, 5, 7), grid_std=0.3, bias_std=0.1)
+    grid, _, _, _ = lp.to_device(inp)
+    assert lp.lp_dec_has_fast_path(grid, lp.decoder_to_device(inp.decoder))
+    print(check_case_dec(lp, oracle, inp, lp.LP_MATH_DEFAULT, label=f"dec two chains M={n_rays} S={samples}"), flush=True)
+
+
 @pytest.mark.parametrize("kind", [VOXEL, TRIPLANE])
 def test_decoder_at_the_papers_size_on_the_generic_kernels(lp, oracle, kind):
     """The same decoder on the generic kernels: the merged MLP is too large for 64 rays'

@@ -64,6 +64,17 @@ def test_splatter_mlp_on_matrix_cores(lp, oracle, kind, channels, n_in, hidden, 
     print(check_case_splat(lp, oracle, sp, label=f"splat mfma kind={kind} C={channels} n_in={n_in}"), flush=True)
 
 
+@pytest.mark.parametrize("n_rays,samples", [(1, 1), (5, 33), (3, 32)])
+def test_splatter_mlp_on_matrix_cores_degenerate_sizes(lp, oracle, n_rays, samples):
+    """Fewer rays than a workgroup has waves, a single point, point counts around the 32-point step."""
+    sp = lp_inputs.make_splat_small(TRIPLANE, channels=16, res=(6, 5, 7), n_in=9, hidden=(64, 64), n_freq=0,
+                                    prior_channels=16, prior_res=(4, 5, 3), n_rays=n_rays, samples=samples, seed=111,
+                                    bias_std=0.1)
+    target, _, splat = lp.splat_to_device(sp)
+    assert lp.lp_splat_has_fast_path(target, splat)
+    print(check_case_splat(lp, oracle, sp, label=f"splat mfma M={n_rays} S={samples}"), flush=True)
+
+
 def test_splatter_fast_path_query(lp):
     for kw, fast in [(dict(channels=32, n_in=32, hidden=(64, 64), n_freq=0, prior_channels=32), True),
                      (dict(channels=32, n_in=32, hidden=(64, 32), n_freq=0, prior_channels=32), False),
