@@ -251,8 +251,9 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
             // the next step's texel loads are issued here, before the contractions of the hidden
             // layers, and interpolated after them, so that their latency passes under that work
             // (measured: 66.1 -> 63.6 ms on the largest config; issued a stage earlier they cost more
-            // in displaced registers than they hide)
-            constexpr bool kEarly = kPrefetch && CG == C;
+            // in displaced registers than they hide).  Voxel grids only: the 12 corners of a triplane
+            // sample are half as many registers again, which the compiler does not survive.
+            constexpr bool kEarly = kPrefetch && CG == C && KIND == LP_GRID_VOXEL;
             GatherRaw<KIND, C / 2, GT> raw_next;
             Cell3 cell_next;
             if constexpr (kEarly) {
