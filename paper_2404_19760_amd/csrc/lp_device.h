@@ -101,9 +101,12 @@ struct SplatDev {
 // foreground scale a = `contract` (0.5 a x inside the unit interval,
 // 0.5 ((2 - a)(1 - 1/|x|) + a) sign(x) beyond), each axis on its own.  1/|x| from the fp32
 // reciprocal plus one Newton step in fp64 (relative error ~1e-14).
+// g = 1 - f, rounded from the fp64 index as well: formed from the rounded f it would carry an
+// absolute error of 6e-8 however small it is, which the Splatter's division by a cell's weight
+// sum turns into an unbounded relative error for cells that only receive tiny weights.
 template <bool CC = false>
 __device__ __forceinline__ void axis_cell(double x, double lo, double scale, int N, double contract, int& i,
-                                          float& f)
+                                          float& f, float& g)
 {
     if constexpr (CC) {
         const double m = fmax(fabs(x), 1.0);
@@ -117,7 +120,17 @@ __device__ __forceinline__ void axis_cell(double x, double lo, double scale, int
     int c = (int)u;  // u >= 0: truncation is floor
     c = min(c, N - 2);
     i = c;
-    f = (float)(u - (double)c);
+    const double fr = u - (double)c;
+    f = (float)fr;
+    g = (float)(1.0 - fr);
+}
+
+template <bool CC = false>
+__device__ __forceinline__ void axis_cell(double x, double lo, double scale, int N, double contract, int& i,
+                                          float& f)
+{
+    float g;
+    axis_cell<CC>(x, lo, scale, N, contract, i, f, g);
 }
 
 // Entry e of the view-direction encoding (Section 3.3: the feature MLP takes "the sampled feature

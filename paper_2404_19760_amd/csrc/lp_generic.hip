@@ -32,17 +32,18 @@ __device__ void stage_params(const MlpDev& m, float* sW)
 struct Cell {
     int i[3];
     float f[3];
+    float g[3];  // 1 - f, rounded from the fp64 index
 };
 
 __device__ __forceinline__ Cell locate(const GridDev& g, double x, double y, double z)
 {
     Cell c;
-    if (g.contract > 0.0) axis_cell<true>(x, g.amin[0], g.scale[0], g.N[0], g.contract, c.i[0], c.f[0]);
-    else axis_cell<false>(x, g.amin[0], g.scale[0], g.N[0], g.contract, c.i[0], c.f[0]);
-    if (g.contract > 0.0) axis_cell<true>(y, g.amin[1], g.scale[1], g.N[1], g.contract, c.i[1], c.f[1]);
-    else axis_cell<false>(y, g.amin[1], g.scale[1], g.N[1], g.contract, c.i[1], c.f[1]);
-    if (g.contract > 0.0) axis_cell<true>(z, g.amin[2], g.scale[2], g.N[2], g.contract, c.i[2], c.f[2]);
-    else axis_cell<false>(z, g.amin[2], g.scale[2], g.N[2], g.contract, c.i[2], c.f[2]);
+    if (g.contract > 0.0) axis_cell<true>(x, g.amin[0], g.scale[0], g.N[0], g.contract, c.i[0], c.f[0], c.g[0]);
+    else axis_cell<false>(x, g.amin[0], g.scale[0], g.N[0], g.contract, c.i[0], c.f[0], c.g[0]);
+    if (g.contract > 0.0) axis_cell<true>(y, g.amin[1], g.scale[1], g.N[1], g.contract, c.i[1], c.f[1], c.g[1]);
+    else axis_cell<false>(y, g.amin[1], g.scale[1], g.N[1], g.contract, c.i[1], c.f[1], c.g[1]);
+    if (g.contract > 0.0) axis_cell<true>(z, g.amin[2], g.scale[2], g.N[2], g.contract, c.i[2], c.f[2], c.g[2]);
+    else axis_cell<false>(z, g.amin[2], g.scale[2], g.N[2], g.contract, c.i[2], c.f[2], c.g[2]);
     return c;
 }
 
@@ -56,8 +57,8 @@ __device__ void gather_feat(const GridDev& g, int scene, const Cell& c, float* f
             float acc = 0.0f;
             for (int d = 0; d < 8; ++d) {
                 const int dx = d >> 2, dy = (d >> 1) & 1, dz = d & 1;
-                const float w = (dx ? c.f[0] : 1.0f - c.f[0]) * (dy ? c.f[1] : 1.0f - c.f[1]) *
-                                (dz ? c.f[2] : 1.0f - c.f[2]);
+                const float w = (dx ? c.f[0] : c.g[0]) * (dy ? c.f[1] : c.g[1]) *
+                                (dz ? c.f[2] : c.g[2]);
                 const size_t off =
                     (((size_t)(c.i[0] + dx) * g.N[1] + (c.i[1] + dy)) * g.N[2] + (c.i[2] + dz)) * C;
                 acc += w * grid_load(g, g.data[0], V + off + k);
@@ -73,7 +74,7 @@ __device__ void gather_feat(const GridDev& g, int scene, const Cell& c, float* f
                 const size_t P = (size_t)scene * g.N[a] * g.N[b] * C;
                 for (int d = 0; d < 4; ++d) {
                     const int da = d >> 1, db = d & 1;
-                    const float w = (da ? c.f[a] : 1.0f - c.f[a]) * (db ? c.f[b] : 1.0f - c.f[b]);
+                    const float w = (da ? c.f[a] : c.g[a]) * (db ? c.f[b] : c.g[b]);
                     acc += w * grid_load(g, g.data[p], P + ((size_t)(c.i[a] + da) * g.N[b] + (c.i[b] + db)) * C + k);
                 }
             }
@@ -91,8 +92,8 @@ __device__ void scatter_feat(const GridDev& g, float* const d_grid[3], int scene
         float* V = d_grid[0] + (size_t)scene * g.N[0] * g.N[1] * g.N[2] * C;
         for (int d = 0; d < 8; ++d) {
             const int dx = d >> 2, dy = (d >> 1) & 1, dz = d & 1;
-            const float w = (dx ? c.f[0] : 1.0f - c.f[0]) * (dy ? c.f[1] : 1.0f - c.f[1]) *
-                            (dz ? c.f[2] : 1.0f - c.f[2]);
+            const float w = (dx ? c.f[0] : c.g[0]) * (dy ? c.f[1] : c.g[1]) *
+                            (dz ? c.f[2] : c.g[2]);
             const size_t off =
                 (((size_t)(c.i[0] + dx) * g.N[1] + (c.i[1] + dy)) * g.N[2] + (c.i[2] + dz)) * C;
             for (int k = 0; k < C; ++k) atomicAdd(V + off + k, w * dfeat[k * block_lanes() + lane]);
@@ -103,7 +104,7 @@ __device__ void scatter_feat(const GridDev& g, float* const d_grid[3], int scene
             float* P = d_grid[p] + (size_t)scene * g.N[a] * g.N[b] * C;
             for (int d = 0; d < 4; ++d) {
                 const int da = d >> 1, db = d & 1;
-                const float w = (da ? c.f[a] : 1.0f - c.f[a]) * (db ? c.f[b] : 1.0f - c.f[b]);
+                const float w = (da ? c.f[a] : c.g[a]) * (db ? c.f[b] : c.g[b]);
                 const size_t off = ((size_t)(c.i[a] + da) * g.N[b] + (c.i[b] + db)) * C;
                 for (int k = 0; k < C; ++k) atomicAdd(P + off + k, w * dfeat[k * block_lanes() + lane]);
             }
@@ -228,8 +229,8 @@ __device__ void scatter_weight(const GridDev& g, float* const d_w[3], int scene,
         float* V = d_w[0] + (size_t)scene * g.N[0] * g.N[1] * g.N[2];
         for (int d = 0; d < 8; ++d) {
             const int dx = d >> 2, dy = (d >> 1) & 1, dz = d & 1;
-            const float w = (dx ? c.f[0] : 1.0f - c.f[0]) * (dy ? c.f[1] : 1.0f - c.f[1]) *
-                            (dz ? c.f[2] : 1.0f - c.f[2]);
+            const float w = (dx ? c.f[0] : c.g[0]) * (dy ? c.f[1] : c.g[1]) *
+                            (dz ? c.f[2] : c.g[2]);
             atomicAdd(V + ((size_t)(c.i[0] + dx) * g.N[1] + (c.i[1] + dy)) * g.N[2] + (c.i[2] + dz), w);
         }
     } else {
@@ -238,7 +239,7 @@ __device__ void scatter_weight(const GridDev& g, float* const d_w[3], int scene,
             float* P = d_w[p] + (size_t)scene * g.N[a] * g.N[b];
             for (int d = 0; d < 4; ++d) {
                 const int da = d >> 1, db = d & 1;
-                const float w = (da ? c.f[a] : 1.0f - c.f[a]) * (db ? c.f[b] : 1.0f - c.f[b]);
+                const float w = (da ? c.f[a] : c.g[a]) * (db ? c.f[b] : c.g[b]);
                 atomicAdd(P + (size_t)(c.i[a] + da) * g.N[b] + (c.i[b] + db), w);
             }
         }
@@ -256,8 +257,8 @@ __device__ void gather_normalised(const GridDev& g, const float* const G[3], con
         const size_t cells = (size_t)scene * g.N[0] * g.N[1] * g.N[2];
         for (int d = 0; d < 8; ++d) {
             const int dx = d >> 2, dy = (d >> 1) & 1, dz = d & 1;
-            const float w = (dx ? c.f[0] : 1.0f - c.f[0]) * (dy ? c.f[1] : 1.0f - c.f[1]) *
-                            (dz ? c.f[2] : 1.0f - c.f[2]);
+            const float w = (dx ? c.f[0] : c.g[0]) * (dy ? c.f[1] : c.g[1]) *
+                            (dz ? c.f[2] : c.g[2]);
             const size_t cell = cells + ((size_t)(c.i[0] + dx) * g.N[1] + (c.i[1] + dy)) * g.N[2] + (c.i[2] + dz);
             const float ws = Wt[0][cell];
             const float s = ws > 0.0f ? w / ws : 0.0f;
@@ -269,7 +270,7 @@ __device__ void gather_normalised(const GridDev& g, const float* const G[3], con
             const size_t cells = (size_t)scene * g.N[a] * g.N[b];
             for (int d = 0; d < 4; ++d) {
                 const int da = d >> 1, db = d & 1;
-                const float w = (da ? c.f[a] : 1.0f - c.f[a]) * (db ? c.f[b] : 1.0f - c.f[b]);
+                const float w = (da ? c.f[a] : c.g[a]) * (db ? c.f[b] : c.g[b]);
                 const size_t cell = cells + (size_t)(c.i[a] + da) * g.N[b] + (c.i[b] + db);
                 const float ws = Wt[p][cell];
                 const float s = ws > 0.0f ? w / ws : 0.0f;

@@ -218,15 +218,16 @@ __device__ __forceinline__ float fast_logistic(float z)
 struct Cell3 {
     int i[3];
     float f[3];
+    float g[3];  // 1 - f from the fp64 index (only the Splatter reads it; unused copies cost nothing)
 };
 
 template <bool CC>
 __device__ __forceinline__ Cell3 locate3(const GridDev& g, double x, double y, double z)
 {
     Cell3 c;
-    axis_cell<CC>(x, g.amin[0], g.scale[0], g.N[0], g.contract, c.i[0], c.f[0]);
-    axis_cell<CC>(y, g.amin[1], g.scale[1], g.N[1], g.contract, c.i[1], c.f[1]);
-    axis_cell<CC>(z, g.amin[2], g.scale[2], g.N[2], g.contract, c.i[2], c.f[2]);
+    axis_cell<CC>(x, g.amin[0], g.scale[0], g.N[0], g.contract, c.i[0], c.f[0], c.g[0]);
+    axis_cell<CC>(y, g.amin[1], g.scale[1], g.N[1], g.contract, c.i[1], c.f[1], c.g[1]);
+    axis_cell<CC>(z, g.amin[2], g.scale[2], g.N[2], g.contract, c.i[2], c.f[2], c.g[2]);
     return c;
 }
 

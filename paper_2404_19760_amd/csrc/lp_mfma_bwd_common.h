@@ -97,11 +97,14 @@ __device__ __forceinline__ Frag selection(int j, int grp, IndexFn index_of)
 // weights are in corner order 4dx + 2dy + dz for 32 channels and in order 4dz + 2dx + dy for 16
 // channels (where the two halves of a lane group take the corners of one dz each).
 // triplane: 12 weights (plane p, corner 2da + db at 4p + ..), then 3 plane offsets.
-template <int KIND, int C>
+// EXACT: the complements 1 - f come from the fp64 index (the Splatter, whose result divides by sums
+// of these weights); otherwise from the rounded f (the Renderer's gradient scatter).
+template <int KIND, int C, bool EXACT = false>
 __device__ __forceinline__ void write_scatter_record(float* rec, const GridDev& g, const Cell3& c)
 {
     if constexpr (KIND == LP_GRID_VOXEL) {
-        const float x1 = c.f[0], x0 = 1.0f - x1, y1 = c.f[1], y0 = 1.0f - y1, z1 = c.f[2], z0 = 1.0f - z1;
+        const float x1 = c.f[0], x0 = EXACT ? c.g[0] : 1.0f - x1, y1 = c.f[1], y0 = EXACT ? c.g[1] : 1.0f - y1,
+                    z1 = c.f[2], z0 = EXACT ? c.g[2] : 1.0f - z1;
         const float4 w0 = C == 16 ? make_float4(x0 * y0 * z0, x0 * y1 * z0, x1 * y0 * z0, x1 * y1 * z0)
                                   : make_float4(x0 * y0 * z0, x0 * y0 * z1, x0 * y1 * z0, x0 * y1 * z1);
         const float4 w1 = C == 16 ? make_float4(x0 * y0 * z1, x0 * y1 * z1, x1 * y0 * z1, x1 * y1 * z1)
@@ -116,7 +119,7 @@ __device__ __forceinline__ void write_scatter_record(float* rec, const GridDev& 
 #pragma unroll
         for (int p = 0; p < 3; ++p) {
             const int a = p, b = (p + 1) % 3;
-            const float a1 = c.f[a], a0 = 1.0f - a1, b1 = c.f[b], b0 = 1.0f - b1;
+            const float a1 = c.f[a], a0 = EXACT ? c.g[a] : 1.0f - a1, b1 = c.f[b], b0 = EXACT ? c.g[b] : 1.0f - b1;
             reinterpret_cast<float4*>(rec)[p] = make_float4(a0 * b0, a0 * b1, a1 * b0, a1 * b1);
             base[p] = ((unsigned)c.i[a] * (unsigned)g.N[b] + (unsigned)c.i[b]) * C;
         }

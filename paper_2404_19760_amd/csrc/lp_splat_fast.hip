@@ -49,7 +49,7 @@ __global__ __launch_bounds__(kWaves * 64) void splat_naive_kernel(GridDev tgt, R
             wave_lds_fence();
             if (grp == 0) {
                 float* rec = info + col * 16;
-                write_scatter_record<KIND, C>(rec, tgt, c);
+                write_scatter_record<KIND, C, true>(rec, tgt, c);
                 if (j >= S) {  // a point past the end of the ray pushes nothing
 #pragma unroll
                     for (int k = 0; k < (KIND == LP_GRID_VOXEL ? 8 : 12); ++k) rec[k] = 0.0f;

@@ -142,7 +142,7 @@ __global__ __launch_bounds__(kWaves * 64) void splat_mfma_kernel(GridDev tgt, Ml
             wave_lds_fence();
             if (grp == 0) {
                 float* rec = info + col * 16;
-                write_scatter_record<KIND, CO>(rec, tgt, ct);
+                write_scatter_record<KIND, CO, true>(rec, tgt, ct);
                 if (j >= S) {  // a point past the end of the ray pushes nothing
 #pragma unroll
                     for (int k = 0; k < (KIND == LP_GRID_VOXEL ? 8 : 12); ++k) rec[k] = 0.0f;

@@ -132,7 +132,7 @@ __device__ __forceinline__ void gather_normalised(const GridDev& tgt, const Spla
 #pragma unroll
         for (int d = 0; d < 8; ++d) {
             const int dx = d >> 2, dy = (d >> 1) & 1, dz = d & 1;
-            const float w = (dx ? c.f[0] : 1.0f - c.f[0]) * (dy ? c.f[1] : 1.0f - c.f[1]) * (dz ? c.f[2] : 1.0f - c.f[2]);
+            const float w = (dx ? c.f[0] : c.g[0]) * (dy ? c.f[1] : c.g[1]) * (dz ? c.f[2] : c.g[2]);
             const float ws = W[base + dx * sx + dy * sy + dz];
             wn[d] = (valid && ws > 0.0f) ? w * __frcp_rn(ws) : 0.0f;
         }
@@ -146,7 +146,7 @@ __device__ __forceinline__ void gather_normalised(const GridDev& tgt, const Spla
 #pragma unroll
             for (int d = 0; d < 4; ++d) {
                 const int da = d >> 1, db = d & 1;
-                const float w = (da ? c.f[a] : 1.0f - c.f[a]) * (db ? c.f[b] : 1.0f - c.f[b]);
+                const float w = (da ? c.f[a] : c.g[a]) * (db ? c.f[b] : c.g[b]);
                 const float ws = W[base + da * sa + db];
                 wn[4 * p + d] = (valid && ws > 0.0f) ? w * __frcp_rn(ws) : 0.0f;
             }

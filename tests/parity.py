@@ -29,16 +29,6 @@ def close(gpu: np.ndarray, ref: np.ndarray, rtol: float, what: str, extra=None):
     return float(err.max() / max(rms, 1e-300))
 
 
-# Interpolation fractions are fp32 numbers in [0, 1] (spacing 6e-8 near 1), so a corner weight, a
-# product of up to three factors f or 1 - f, carries an ABSOLUTE error of up to ~2e-7 however
-# small it is.  The Splatter's normalised result theta = (sum w v) / (sum w) of a cell that only a
-# few points touch with tiny weights inherits n * 2e-7 * (|v| + |theta|) / theta_w: unbounded
-# as theta_w -> 0.  n = 8 contributions are allowed for; the un-normalised sums are checked
-# at the plain tolerance.
-SPLAT_WEIGHT_ABS_ERR = 2e-7
-SPLAT_CONTRIBUTIONS = 8
-
-
 # Kink band, as a multiple of each hidden unit's rounding-error scale |b| + sum_k |W_k x_k|.
 # The kernels form sample positions and interpolation fractions in fp64, so what is left on a
 # pre-activation is the contraction error and what the layer below passes on.  For the
@@ -49,14 +39,36 @@ SPLAT_CONTRIBUTIONS = 8
 # weight and neighbouring samples are nearly equal, so the errors are far from independent.
 KINK_BAND = 2e-5
 
+# The envelope is a worst case: every banded sample adds its whole contribution to upper - lower
+# (relative L2 widths of 4e-3 ... 6e-2 on the configurations, see test_oracle_envelope.py),
+# while a kernel flips only the few units whose rounding error really crosses zero.  So the
+# whole-tensor error around the definition's gradient may use at most this much of the width.
+WIDTH_CAP = 1e-3
+# Splatter: points of a ray that are clamped to one border position of the prior structure share
+# every MLP input (pixel feature and direction are per ray), so their pre-activations coincide and
+# flip TOGETHER; there the flips do not average out and the cap is the width itself.
+WIDTH_CAP_SPLAT_BORDER = None
+# Share of a gradient tensor's elements that may miss the plain tolerance around the definition's
+# gradient (they must still lie inside the envelope).  Observed on the GPU: at most 1 %.
+MAX_STRICT_FAIL = 0.02
 
-def close_envelope(gpu, ref, lo, hi, rtol: float, what: str):
+
+class GradErr(tuple):
+    """(max distance to the envelope / rms, share of elements outside the plain tolerance,
+    relative L2 error around the definition's gradient, relative L2 width of the envelope)."""
+    env = property(lambda s: s[0])
+    strict_fail = property(lambda s: s[1])
+    l2 = property(lambda s: s[2])
+    width = property(lambda s: s[3])
+
+
+def close_envelope(gpu, ref, lo, hi, rtol: float, what: str, width_cap=WIDTH_CAP):
     """Gradient check.  Where a hidden pre-activation lies within rounding of the ReLU kink,
     either one-sided derivative is a correct answer; `lo`/`hi` are the elementwise envelope
     of the oracle's gradients over those choices (lo == hi == ref for elements no such sample
     touches).  EVERY element must lie within tolerance of the envelope; the fraction of
     elements outside the strict tolerance around `ref` itself is returned for the caller to
-    bound.  Returns (max envelope error / rms, strict failure fraction)."""
+    bound.  Returns a GradErr."""
     gpu = np.asarray(gpu, dtype=np.float64)
     assert gpu.shape == ref.shape, (what, gpu.shape, ref.shape)
     assert np.isfinite(gpu).all(), f"{what}: non-finite values from the GPU"
@@ -72,17 +84,54 @@ def close_envelope(gpu, ref, lo, hi, rtol: float, what: str):
     strict_fail = float((np.abs(gpu - ref) > bound).mean()) if ref.size else 0.0
     # whole-tensor checks.  The part of the difference that no choice at a kink explains (the
     # distance to the envelope) is bounded like an ordinary error.  Around the definition's own
-    # gradient the bound grows by the width of the envelope: kink samples are usually few and
-    # independent, so that width is far below the tolerance, but points of a ray that are clamped
-    # to the same border position of a structure share their pre-activations and flip together.
+    # gradient the bound grows by the width of the envelope, capped (see WIDTH_CAP).
     norm = max(float(np.linalg.norm(ref)), 1e-300)
     l2_env = float(np.linalg.norm(err)) / norm
     assert l2_env <= 3.0 * rtol, f"{what}: relative L2 distance to the kink envelope {l2_env:g} exceeds {3.0 * rtol:g}"
     l2 = float(np.linalg.norm(gpu - ref)) / norm
     width = float(np.linalg.norm(hi - lo)) / norm
-    assert l2 <= 3.0 * rtol + width, \
-        f"{what}: relative L2 error {l2:g} exceeds {3.0 * rtol:g} + envelope width {width:g}"
-    return float(err.max() / max(rms, 1e-300)), strict_fail
+    allowed = width if width_cap is None else min(width, width_cap)
+    assert l2 <= 3.0 * rtol + allowed, \
+        f"{what}: relative L2 error {l2:g} exceeds {3.0 * rtol:g} + {allowed:g} (envelope width {width:g})"
+    return GradErr((float(err.max() / max(rms, 1e-300)), strict_fail, l2, width))
+
+
+# Which tensors the strict share is asserted for.  Grid gradients (and the Splatter's per-pixel and
+# prior gradients): an element sums the few samples that touch it, so a flipped unit spoils few
+# elements.  Weight and bias gradients are different: a unit whose sign decision differs from the
+# fp64 one (|z| below the kernel's rounding error, probability p per unit and sample) changes a
+# whole row of dW by that sample's contribution, and because a row is a sum with random signs over
+# ALL samples, the row's relative error is about sqrt(p / P(unit active)) whatever the number of
+# samples: 2e-3 ... 4e-3 for the split-bf16 contractions (p ~ 1e-5), i.e. right at the plain
+# tolerance, for a third of the elements or none.  For those tensors the envelope (every element)
+# and the whole-tensor L2 bound are asserted, and the share is reported.
+STRICT_SHARE_TENSORS = ("d_grid", "d_prior", "d_feats")
+
+
+def assert_strict_share(worst: dict, label: str, max_strict_fail: float):
+    """Besides lying inside the envelope, all but a small share of the elements of a grid-like
+    gradient tensor must meet the plain tolerance around the definition's gradient."""
+    for k, v in worst.items():
+        if isinstance(v, GradErr) and k.startswith(STRICT_SHARE_TENSORS):
+            assert v.strict_fail <= max_strict_fail, (
+                f"{label} {k}: {v.strict_fail:.2%} of the elements miss the plain tolerance "
+                f"(allowed {max_strict_fail:.2%}; relative L2 error {v.l2:.2e}, envelope width {v.width:.2e})")
+
+
+def summary(worst: dict) -> str:
+    """One line for logs: worst forward error / rms, and over the gradient tensors the worst
+    distance to the envelope / rms, relative L2 error around the definition's gradient, and
+    share of elements outside the plain tolerance."""
+    fwd = max((v for v in worst.values() if not isinstance(v, GradErr)), default=0.0)
+    g = [v for v in worst.values() if isinstance(v, GradErr)]
+    if not g:
+        return f"forward err/rms {fwd:.1e}"
+    grid = [v for k, v in worst.items() if isinstance(v, GradErr) and k.startswith(STRICT_SHARE_TENSORS)]
+    par = [v for k, v in worst.items() if isinstance(v, GradErr) and not k.startswith(STRICT_SHARE_TENSORS)]
+    share = lambda vs: f"{max((v.strict_fail for v in vs), default=0.0):.2%}"
+    return (f"forward err/rms {fwd:.1e}; gradients: outside envelope/rms {max(v.env for v in g):.1e}, "
+            f"L2 error vs definition {max(v.l2 for v in g):.1e}, strict-miss share grid {share(grid)} / "
+            f"parameters {share(par)} (envelope width up to {max(v.width for v in g):.1e})")
 
 
 def mse_upstream(rgb64: np.ndarray, target: np.ndarray, scene=None, n_scenes: int = 1) -> np.ndarray:
@@ -113,7 +162,7 @@ def run_gpu(lp, inp, p_rgb, p_alpha=None, p_depth=None, math_mode=0, device="cud
                 d_grid=[cpu(t) for t in d_grid], dW=[cpu(t) for t in dW], db=[cpu(t) for t in db])
 
 
-def check_case(lp, oracle, inp, math_mode=0, aux_grads=True, seed=0, label="", max_strict_fail=0.5, grid_dtype=None):
+def check_case(lp, oracle, inp, math_mode=0, aux_grads=True, seed=0, label="", max_strict_fail=MAX_STRICT_FAIL, grid_dtype=None):
     """Full parity of one problem: forward outputs and every gradient tensor."""
     import lp_inputs
     prob = oracle.Problem(inp)
@@ -138,15 +187,7 @@ def check_case(lp, oracle, inp, math_mode=0, aux_grads=True, seed=0, label="", m
         worst[f"dW{l}"] = close_envelope(a, b, *env(1, l), BWD_RTOL, f"{label} dW[{l}]")
     for l, (a, b) in enumerate(zip(g["db"], o_db)):
         worst[f"db{l}"] = close_envelope(a, b, *env(2, l), BWD_RTOL, f"{label} db[{l}]")
-    # besides the envelope, all but a small fraction of the elements must meet the plain
-    # tolerance around the definition's gradient (tiny problems: one kink sample can touch a
-    # whole small tensor, hence the loose default; the configurations use 3 %)
-    # (grid tensors only: a weight-gradient element sums every sample of the problem with heavy
-    # cancellation, so its plain tolerance is bounded through the whole-tensor L2 check instead)
-    for k, v in worst.items():
-        if isinstance(v, tuple) and k.startswith("d_grid"):
-            assert v[1] <= max_strict_fail, (f"{label} {k}: {v[1]:.2%} of the elements miss the plain "
-                                             f"tolerance (allowed {max_strict_fail:.2%})")
+    assert_strict_share(worst, label, max_strict_fail)
     return worst
 
 
@@ -168,7 +209,7 @@ def run_gpu_dec(lp, inp, p_out, p_alpha=None, p_depth=None, math_mode=0, device=
                 dWv=lst(dWv), dbv=lst(dbv))
 
 
-def check_case_dec(lp, oracle, inp, math_mode=0, aux_grads=True, seed=0, label="", max_strict_fail=0.5):
+def check_case_dec(lp, oracle, inp, math_mode=0, aux_grads=True, seed=0, label="", max_strict_fail=MAX_STRICT_FAIL):
     """Full parity of one problem with the two-MLP decoder: outputs and every gradient tensor."""
     import lp_inputs
     prob = oracle.Problem(inp)
@@ -189,16 +230,13 @@ def check_case_dec(lp, oracle, inp, math_mode=0, aux_grads=True, seed=0, label="
         for j, a in enumerate(g[name]):
             worst[f"{name}{j}"] = close_envelope(a, ref[i][j], lower[i][j], upper[i][j], BWD_RTOL,
                                                  f"{label} {name}[{j}]")
-    for k, v in worst.items():
-        if isinstance(v, tuple) and k.startswith("d_grid"):
-            assert v[1] <= max_strict_fail, (f"{label} {k}: {v[1]:.2%} of the elements miss the plain "
-                                             f"tolerance (allowed {max_strict_fail:.2%})")
+    assert_strict_share(worst, label, max_strict_fail)
     return worst
 
 
 # ---- Splatter ---------------------------------------------------------------------------------
 
-def check_case_splat(lp, oracle, sp, seed=0, label=""):
+def check_case_splat(lp, oracle, sp, seed=0, label="", max_strict_fail=MAX_STRICT_FAIL, width_cap=WIDTH_CAP):
     """Splatter parity: normalised structure, weight sums and every gradient against the oracle."""
     import torch
     prob = oracle.SplatProblem(sp)
@@ -218,17 +256,16 @@ def check_case_splat(lp, oracle, sp, seed=0, label=""):
     for p in range(len(o_theta)):
         g_w, g_t = cpu(theta_w[p]), cpu(theta[p])
         worst[f"theta_w{p}"] = close(g_w, o_w[p], FWD_RTOL, f"{label} theta_w[{p}]")
-        # the sums the kernel accumulates, then the normalised result with the allowance for cells
-        # of tiny weight
+        # the sums the kernel accumulates, then the normalised result: both at the plain tolerance
+        # (the corner weights keep their relative accuracy however small they are: f and 1 - f are
+        # both rounded from the fp64 index)
         worst[f"sum{p}"] = close(g_t.astype(np.float64) * g_w[..., None], o_theta[p] * o_w[p][..., None], FWD_RTOL,
                                  f"{label} theta[{p}] * theta_w[{p}]")
-        vmax = float(np.abs(o_theta[p]).max()) if o_theta[p].size else 0.0
-        with np.errstate(divide="ignore"):
-            extra = np.where(o_w[p] > 0, SPLAT_CONTRIBUTIONS * SPLAT_WEIGHT_ABS_ERR * 2.0 * vmax / o_w[p], 0.0)
-        worst[f"theta{p}"] = close(g_t, o_theta[p], FWD_RTOL, f"{label} theta[{p}]", extra=extra[..., None])
+        worst[f"theta{p}"] = close(g_t, o_theta[p], FWD_RTOL, f"{label} theta[{p}]")
     flat = lambda r: [("d_feats", r[0])] + [(f"d_prior{i}", a) for i, a in enumerate(r[1])] \
         + [(f"dW{i}", a) for i, a in enumerate(r[2])] + [(f"db{i}", a) for i, a in enumerate(r[3])]
     gpu = [d_feats] + list(d_prior) + list(dW) + list(db)
     for (name, r), (_, lo), (_, hi), g in zip(flat(ref), flat(lower), flat(upper), gpu):
-        worst[name] = close_envelope(cpu(g), r, lo, hi, BWD_RTOL, f"{label} {name}")
+        worst[name] = close_envelope(cpu(g), r, lo, hi, BWD_RTOL, f"{label} {name}", width_cap=width_cap)
+    assert_strict_share(worst, label, max_strict_fail)
     return worst

@@ -89,8 +89,10 @@ def test_decoder_at_the_papers_size(lp, oracle, kind, channels, n_freq, contract
         inp = dataclasses.replace(inp, contract_a=contract)
     grid, _, _, _ = lp.to_device(inp)
     assert lp.lp_dec_has_fast_path(grid, lp.decoder_to_device(inp.decoder))
-    print(check_case_dec(lp, oracle, inp, lp.LP_MATH_BF16X3, label=f"dec two chains kind={kind} C={channels}"),
-          flush=True)
+    # 1 320 texels take 15 000 samples: a grid-gradient element here sums dozens of samples of many
+    # rays, so one unit whose sign decision differs reaches a larger share of this small tensor
+    print(check_case_dec(lp, oracle, inp, lp.LP_MATH_BF16X3, label=f"dec two chains kind={kind} C={channels}",
+                         max_strict_fail=0.05), flush=True)
 
 
 @pytest.mark.parametrize("n_rays,samples", [(1, 1), (5, 33), (3, 64), (259, 2)])

@@ -7,7 +7,7 @@ import pytest
 import lp_inputs
 from lp_inputs import TRIPLANE, VOXEL
 
-from parity import check_case_splat
+from parity import WIDTH_CAP_SPLAT_BORDER, check_case_splat
 
 pytestmark = pytest.mark.gpu
 
@@ -61,7 +61,11 @@ def test_splatter_mlp_on_matrix_cores(lp, oracle, kind, channels, n_in, hidden, 
                                     samples=41, seed=101 + n_in, n_scenes=2, bias_std=0.1, far=(2.2, 6.0))
     target, _, splat = lp.splat_to_device(sp)
     assert lp.lp_splat_has_fast_path(target, splat)
-    print(check_case_splat(lp, oracle, sp, label=f"splat mfma kind={kind} C={channels} n_in={n_in}"), flush=True)
+    # the rays run out of the prior's box (far up to 6): the clamped points of a ray share every
+    # MLP input and flip together, so the whole-tensor error may use the envelope's full width and a
+    # larger share of the small prior-gradient tensor misses the plain tolerance
+    print(check_case_splat(lp, oracle, sp, label=f"splat mfma kind={kind} C={channels} n_in={n_in}",
+                           width_cap=WIDTH_CAP_SPLAT_BORDER, max_strict_fail=0.06), flush=True)
 
 
 @pytest.mark.parametrize("n_rays,samples", [(1, 1), (5, 33), (3, 32)])
