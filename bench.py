@@ -7,9 +7,22 @@ One step = one pass of the whole hot path over one batch of synthetic rays: forw
 (sample, interpolate, decode, composite), MSE loss gradient, zeroing of the gradient
 buffers, backward (recompute, emission-absorption VJP, MLP backward, scatter into the
 grid and MLP gradients).  Inputs are resident in HBM before the timed region.  Prints
-ONE JSON line: ray-samples/s of forward+backward, the HBM-roofline view of the dominant
-kernel (algorithmic gather/scatter bytes over its HIP-event duration), and the CPU oracle
+ONE JSON line: ray-samples/s of forward+backward; three roofline views of the dominant kernel
+(the backward) over its HIP-event duration, with the one that binds first; and the CPU oracle
 timed on a bounded ray subset of the same workload on this machine's host cores.
+
+Roofline views (`roofline`):
+  * "mfma": the MLP contractions run on the bf16 matrix cores with fp32 operands split into
+    hi + lo, three products per multiply-add.  achieved = 3 products x 3 F FLOP per sample
+    (recompute, input gradients, weight gradients; F = the MLP's forward FLOPs) x samples /
+    duration, against the dense bf16 peak.  This is the unit the kernel is closest to, together
+    with the vector ALU work that feeds it (the kernel is bound by instruction issue, see
+    profiles/), so it is reported as THE bound;
+  * "hbm_effective": the algorithmic no-reuse bytes (every sample re-reads its corners and adds a
+    gradient of the same size) / duration against the HBM peak: an EFFECTIVE bandwidth, met
+    mostly from the caches (it can exceed the peak where the reuse is high);
+  * "hbm_counters": the HBM bytes the profiler's FETCH_SIZE / WRITE_SIZE counters saw per launch
+    (`traffic`, from profiles/) / duration.
 """
 from __future__ import annotations
 
@@ -21,6 +34,7 @@ import time
 import numpy as np
 
 HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 # HBM bytes per launch of the backward kernel from two rocprofv3 --pmc runs (FETCH_SIZE scaled
 # by 2.0, WRITE_SIZE by 1.0 against a 1 GiB copy kernel in the same run); the summary with the
@@ -43,8 +57,10 @@ def parse():
                     help="storage type of the grid on the GPU (gradients stay f32)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
-    ap.add_argument("--also", default="batched,single_scene,contract,decoder,decoder_paper,splat_naive,splat_mlp",
-                    help="further workloads reported for context under 'also' (comma-separated, '' to skip)")
+    ap.add_argument("--also", default="tiny,single_scene,voxel,batched,large:bf16,contract,decoder,decoder_paper,"
+                                      "splat_naive,splat_mlp",
+                    help="further workloads reported for context under 'also' (comma-separated, '' to skip; "
+                         "name:bf16 / name:f16 = that workload with the grid stored in reduced precision)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy kernel (reference for HBM counters)")
     return ap.parse_args()
@@ -239,6 +255,9 @@ def main():
     interp = 2 * w.corners * w.channels
     f_fwd, f_all = w.mlp_flop_per_sample + interp, 4 * w.mlp_flop_per_sample + 3 * interp
     step_s = elapsed / args.steps
+    bwd_flop = (9 if fast else 3) * w.mlp_flop_per_sample
+    bwd_tflops = bwd_flop * samples / (bwd_avg * 1e-3) / 1e12
+    traffic = MEASURED_BWD_HBM_BYTES.get(args.config) if fast and args.grid_dtype == "f32" and args.aabb is None else None
     out = {
         "metric": "ray-samples/sec fwd+bwd (Renderer hot path)",
         "value": samples / (elapsed / args.steps),
@@ -255,37 +274,57 @@ def main():
                    "aabb_half_width": inp.aabb_max[0],
                    "kernels": "mfma" if fast else "generic"},
         "fwd": {"ms": fwd_avg, "ray_samples_per_s": samples / (fwd_avg * 1e-3),
-                "algorithmic_GBs": fwd_gbs, "frac_hbm_peak": fwd_gbs / HBM_PEAK_GBS},
-        "fwd_bwd_effective": {"algorithmic_GBs": (2 * g_bytes + g_write) * samples / ((fwd_avg + bwd_avg) * 1e-3) / 1e9,
-                              "frac_hbm_peak": (2 * g_bytes + g_write) * samples / ((fwd_avg + bwd_avg) * 1e-3) / 1e9
-                              / HBM_PEAK_GBS},
+                "mfma_bf16_TFLOPs": (3 if fast else 1) * w.mlp_flop_per_sample * samples / (fwd_avg * 1e-3) / 1e12,
+                "frac_mfma_bf16_peak": ((3 * w.mlp_flop_per_sample * samples / (fwd_avg * 1e-3) / 1e12
+                                         / MFMA_BF16_PEAK_TFLOPS) if fast else None),
+                "hbm_effective_GBs": fwd_gbs, "hbm_effective_frac": fwd_gbs / HBM_PEAK_GBS},
+        "fwd_bwd_hbm_effective": {"GBs": (2 * g_bytes + g_write) * samples / ((fwd_avg + bwd_avg) * 1e-3) / 1e9,
+                                  "frac": (2 * g_bytes + g_write) * samples / ((fwd_avg + bwd_avg) * 1e-3) / 1e9
+                                  / HBM_PEAK_GBS},
         "loss_grad_and_zeroing_ms": r["mid_ms"],
         "memory": r["memory"],
-        "alu_view": {"flop_per_sample_fwd": f_fwd, "flop_per_sample_fwd_bwd": f_all,
-                     "fwd_TFLOPs": f_fwd * samples / (fwd_avg * 1e-3) / 1e12,
-                     "fwd_bwd_TFLOPs": f_all * samples / step_s / 1e12,
-                     "fwd_bwd_frac_fp32_vector_peak": f_all * samples / step_s / 1e12 / 157.3},
-        "roofline": {"kernel": "lp_render_bwd", "bound": "hbm", "achieved": bwd_gbs, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": bwd_gbs / HBM_PEAK_GBS,
-                     "traffic": MEASURED_BWD_HBM_BYTES.get(args.config) if fast and args.grid_dtype == "f32" else None,
-                     "bytes_per_sample": g_bytes + g_write, "ms": bwd_avg},
+        "fp32_equivalent": {"flop_per_sample_fwd": f_fwd, "flop_per_sample_fwd_bwd": f_all,
+                            "fwd_TFLOPs": f_fwd * samples / (fwd_avg * 1e-3) / 1e12,
+                            "fwd_bwd_TFLOPs": f_all * samples / step_s / 1e12,
+                            "note": "algorithmic fp32 FLOPs of MLP + interpolation; for comparison with plain fp32 "
+                                    "vector code (peak 157.3 TFLOP/s), not a roofline of this kernel"},
+        "roofline": {"kernel": "lp_render_bwd", "bound": "mfma" if fast else "alu",
+                     "achieved": bwd_tflops, "peak": MFMA_BF16_PEAK_TFLOPS if fast else 157.3,
+                     "unit": "TFLOP/s", "frac": bwd_tflops / (MFMA_BF16_PEAK_TFLOPS if fast else 157.3),
+                     "traffic": traffic, "ms": bwd_avg,
+                     "flop_per_sample": bwd_flop,
+                     "flop_counting": ("3 bf16 products per fp32 multiply-add x 3 F (recompute, dX, dW), F = MLP forward FLOPs"
+                                       if fast else "3 F fp32 (recompute, dX, dW), F = MLP forward FLOPs"),
+                     "hbm_effective": {"bound": "hbm-effective (no-reuse algorithmic bytes, served mostly from caches)",
+                                       "achieved": bwd_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                       "frac": bwd_gbs / HBM_PEAK_GBS, "bytes_per_sample": g_bytes + g_write},
+                     "hbm_counters": None if traffic is None else
+                     {"bound": "hbm (FETCH_SIZE + WRITE_SIZE per launch, profiles/)",
+                      "achieved": traffic / (bwd_avg * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                      "frac": traffic / (bwd_avg * 1e-3) / 1e9 / HBM_PEAK_GBS}},
     }
     # further workloads for context (short runs), e.g. the single-scene configuration and the
     # paper's experimental Renderer shape with contract coordinates
     del r
-    for name in [n for n in args.also.split(",") if n and n != args.config]:
+    for entry in [n for n in args.also.split(",") if n and n != args.config]:
         torch.cuda.empty_cache()
+        name, _, gdt = entry.partition(":")
         if name in __import__("lp_inputs").SPLAT_WORKLOADS:
             out.setdefault("also", []).append(measure_splat(lp, torch, name, max(3, args.steps // 2), 2))
             continue
         k = max(3, args.steps // 2)
-        o = measure(lp, torch, name, mode, k, 2)
+        o = measure(lp, torch, name, mode, k, 2, grid_dtype=gdt or "f32")
         ow = o["w"]
+        gw = ow.gather_bytes_per_sample
+        gr = gw if not gdt else gw // 2
+        nine_f = (9 if o["fast"] else 3) * ow.mlp_flop_per_sample
         out.setdefault("also", []).append(
-            {"workload": name, "ray_samples": o["samples"], "value": o["samples"] / (o["elapsed"] / k),
-             "unit": "ray-samples/s", "fwd_ms": o["fwd_ms"], "bwd_ms": o["bwd_ms"],
+            {"workload": entry, "ray_samples": o["samples"], "value": o["samples"] / (o["elapsed"] / k),
+             "unit": "ray-samples/s", "fwd_ms": o["fwd_ms"], "bwd_ms": o["bwd_ms"], "grid_dtype": gdt or "f32",
              "contract_a": ow.contract_a, "two_mlp_decoder": ow.dec_hidden is not None, "kernels": "mfma" if o["fast"] else "generic",
-             "fwd_bwd_frac_hbm_peak": 3 * ow.gather_bytes_per_sample * o["samples"]
+             "bwd_mfma_bf16_frac": (nine_f * o["samples"] / (o["bwd_ms"] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS
+                                    if o["fast"] and ow.dec_hidden is None else None),
+             "fwd_bwd_hbm_effective_frac": (2 * gr + gw) * o["samples"]
              / ((o["fwd_ms"] + o["bwd_ms"]) * 1e-3) / 1e9 / HBM_PEAK_GBS})
         del o
     if not args.no_cpu_baseline:
