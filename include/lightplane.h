@@ -145,6 +145,25 @@ lp_status lp_render_bwd(const lp_grid* grid, const lp_mlp* mlp, const lp_rays* r
 lp_status lp_bwd_workspace_bytes(const lp_grid* grid, const lp_mlp* mlp, const lp_rays* rays,
                                  int32_t math_mode, size_t* bytes);
 
+/*
+ * lp_render_bwd for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * results and error behaviour as lp_render_bwd without `workspace`: the per-wave partial-sum
+ * records of the MLP gradients go to a static device array of LP_STATIC_SCRATCH_BYTES that the
+ * library holds on every GPU it runs on until the process ends.  The call allocates nothing.
+ * A shape whose records need more (an MLP of more than about 8 000 parameters on the
+ * matrix-core kernels) is refused with LP_ERR_UNSUPPORTED and a message that names both sizes.
+ * All calls on one GPU share that array: calls that overlap on one GPU (different streams or
+ * threads) race; calls that are ordered on one stream do not (the records are fully rewritten
+ * by every call before they are read, nothing needs clearing).
+ */
+#define LP_STATIC_SCRATCH_BYTES (32u * 1024u * 1024u)
+lp_status lp_render_bwd_static(const lp_grid* grid, const lp_mlp* mlp, const lp_rays* rays,
+                               const float bg[3], const float* d_rgb, const float* d_alpha,
+                               const float* d_depth, const float* ray_cache, float* const d_grid[3],
+                               float* const dW[LP_MAX_LAYERS], float* const db[LP_MAX_LAYERS],
+                               int32_t math_mode, void* stream);
+
 /* 1 if the matrix-core (LP_MATH_BF16X3) kernels cover this grid kind / MLP shape, else 0. */
 int32_t lp_has_fast_path(const lp_grid* grid, const lp_mlp* mlp);
 

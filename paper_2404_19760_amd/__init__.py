@@ -82,6 +82,11 @@ def _load() -> C.CDLL:
                                   C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
                                   C.POINTER(C.c_void_p), C.c_void_p, C.c_size_t, C.c_int32,
                                   C.c_void_p]
+    lib.lp_render_bwd_static.restype = C.c_int
+    lib.lp_render_bwd_static.argtypes = [C.POINTER(_Grid), C.POINTER(_Mlp), C.POINTER(_Rays),
+                                         C.POINTER(C.c_float), C.c_void_p, C.c_void_p, C.c_void_p,
+                                         C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
+                                         C.POINTER(C.c_void_p), C.c_int32, C.c_void_p]
     lib.lp_bwd_workspace_bytes.restype = C.c_int
     lib.lp_bwd_workspace_bytes.argtypes = [C.POINTER(_Grid), C.POINTER(_Mlp), C.POINTER(_Rays),
                                            C.c_int32, C.POINTER(C.c_size_t)]
@@ -296,6 +301,18 @@ def lp_bwd_workspace_bytes(grid: Grid, mlp: Mlp, rays: Rays, math_mode: int = LP
     return int(n.value)
 
 
+LP_STATIC_SCRATCH_BYTES = 32 * 1024 * 1024
+
+
+def lp_render_bwd_static(grid: Grid, mlp: Mlp, rays: Rays, bg, d_rgb: torch.Tensor,
+                         d_alpha: Optional[torch.Tensor], d_depth: Optional[torch.Tensor],
+                         ray_cache: torch.Tensor, d_grid: List[torch.Tensor], dW: List[torch.Tensor],
+                         db: List[torch.Tensor], math_mode: int = LP_MATH_DEFAULT, stream=None) -> None:
+    """lp_render_bwd without a workspace: the library's static device scratch holds the records
+    (nothing is allocated; shapes that need more than LP_STATIC_SCRATCH_BYTES are refused)."""
+    _render_bwd(grid, mlp, rays, bg, d_rgb, d_alpha, d_depth, ray_cache, d_grid, dW, db, None, math_mode, stream)
+
+
 def lp_render_bwd(grid: Grid, mlp: Mlp, rays: Rays, bg, d_rgb: torch.Tensor,
                   d_alpha: Optional[torch.Tensor], d_depth: Optional[torch.Tensor],
                   ray_cache: torch.Tensor, d_grid: List[torch.Tensor], dW: List[torch.Tensor],
@@ -304,6 +321,12 @@ def lp_render_bwd(grid: Grid, mlp: Mlp, rays: Rays, bg, d_rgb: torch.Tensor,
     """Enqueue the backward; d_grid / dW / db are ACCUMULATED into (same shapes as the
     grid tensors, weights and biases); `workspace` is a GPU byte tensor of at least
     lp_bwd_workspace_bytes(...) bytes."""
+    if workspace is None:
+        raise ValueError("workspace must be a contiguous GPU tensor")
+    _render_bwd(grid, mlp, rays, bg, d_rgb, d_alpha, d_depth, ray_cache, d_grid, dW, db, workspace, math_mode, stream)
+
+
+def _render_bwd(grid, mlp, rays, bg, d_rgb, d_alpha, d_depth, ray_cache, d_grid, dW, db, workspace, math_mode, stream):
     m = rays.n_rays
     g, ml, r = grid.c_struct(), mlp.c_struct(), rays.c_struct()
     shapes = grid.shapes()
@@ -316,13 +339,16 @@ def lp_render_bwd(grid: Grid, mlp: Mlp, rays: Rays, bg, d_rgb: torch.Tensor,
         raise ValueError("dW / db need one tensor per layer")
     dWp = (C.c_void_p * LP_MAX_LAYERS)(*[_dev_f32(w, f"dW[{l}]", (dims[l + 1], dims[l])) for l, w in enumerate(dW)])
     dbp = (C.c_void_p * LP_MAX_LAYERS)(*[_dev_f32(b, f"db[{l}]", (dims[l + 1],)) for l, b in enumerate(db)])
+    common = (C.byref(g), C.byref(ml), C.byref(r), _bg(bg),
+              _dev_f32(d_rgb, "d_rgb", (m, 3)), _dev_f32(d_alpha, "d_alpha", (m,)),
+              _dev_f32(d_depth, "d_depth", (m,)), _dev_f32(ray_cache, "ray_cache", (m,)), dg, dWp, dbp)
+    if workspace is None:
+        _check(_lib.lp_render_bwd_static(*common, int(math_mode), _stream_ptr(stream)))
+        return
     if not (workspace.is_cuda and workspace.is_contiguous()):
         raise ValueError("workspace must be a contiguous GPU tensor")
     ws_bytes = workspace.numel() * workspace.element_size()
-    _check(_lib.lp_render_bwd(C.byref(g), C.byref(ml), C.byref(r), _bg(bg),
-                              _dev_f32(d_rgb, "d_rgb", (m, 3)), _dev_f32(d_alpha, "d_alpha", (m,)),
-                              _dev_f32(d_depth, "d_depth", (m,)), _dev_f32(ray_cache, "ray_cache", (m,)),
-                              dg, dWp, dbp, C.c_void_p(workspace.data_ptr()), C.c_size_t(ws_bytes),
+    _check(_lib.lp_render_bwd(*common, C.c_void_p(workspace.data_ptr()), C.c_size_t(ws_bytes),
                               int(math_mode), _stream_ptr(stream)))
 
 

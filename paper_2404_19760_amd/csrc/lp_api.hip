@@ -5,6 +5,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <string>
 
 #include "lightplane.h"
@@ -399,6 +400,93 @@ lp_status splat_views(const lp_grid* target, const lp_rays* rays, const lp_splat
     return LP_OK;
 }
 
+
+// ---- static scratch of lp_render_bwd_static -----------------------------------------------
+// Device memory of the library's own for callers that cannot allocate: every GPU the library
+// runs on holds its own copy of this array, at its own address, until the process ends.  In
+// host code the name `scratch` is only a handle for hipGetSymbolAddress: the address a kernel
+// may use is looked up once per device, with that device current, and kept in g_scratch_ptr.
+static __device__ __align__(256) unsigned char scratch[LP_STATIC_SCRATCH_BYTES];
+
+lp_status static_scratch_ptr(void** out)
+{
+    static void* g_scratch_ptr[kMaxDevices] = {nullptr};
+    static std::mutex g_scratch_mutex;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(LP_ERR_HIP, std::string("hipGetDevice: ") + hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return fail(LP_ERR_UNSUPPORTED, "device index beyond the library's table");
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p)
+            return fail(LP_ERR_HIP, std::string("hipGetSymbolAddress(scratch): ") + hipGetErrorString(e));
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return LP_OK;
+}
+
+// lp_render_bwd with the partial-sum records in `workspace` (the caller's, or the static scratch)
+lp_status render_bwd_with(const lp_grid* grid, const lp_mlp* mlp, const lp_rays* rays,
+                          const float bg[3], const float* d_rgb, const float* d_alpha,
+                          const float* d_depth, const float* ray_cache, float* const d_grid[3],
+                          float* const dW[LP_MAX_LAYERS], float* const db[LP_MAX_LAYERS],
+                          void* workspace, size_t workspace_bytes, bool static_scratch, int32_t math_mode,
+                          void* stream)
+{
+    lp_status st = validate(grid, mlp, rays);
+
+    if (st != LP_OK) return st;
+    if (!bg || !d_grid || !dW || !db) return fail(LP_ERR_INVALID_ARG, "bg, d_grid, dW and db must not be NULL");
+    const int n_planes = grid->kind == LP_GRID_VOXEL ? 1 : 3;
+    for (int p = 0; p < n_planes; ++p)
+        if (!d_grid[p]) return fail(LP_ERR_INVALID_ARG, "d_grid has a NULL tensor");
+    for (int l = 0; l < mlp->n_layers; ++l)
+        if (!dW[l] || !db[l]) return fail(LP_ERR_INVALID_ARG, "dW / db has a NULL layer");
+    if (rays->M > 0 && (!d_rgb || !ray_cache))
+        return fail(LP_ERR_INVALID_ARG, "d_rgb and ray_cache must not be NULL");
+    lp::GridDev g; lp::MlpDev m; lp::RaysDev r;
+    to_device_views(grid, mlp, rays, &g, &m, &r);
+    Path path;
+    st = choose_path(g, m, math_mode, &path);
+    if (st != LP_OK) return st;
+    if (rays->M == 0) return LP_OK;
+
+    std::string err;
+    int n_cu = 0;
+    if (compute_units(&n_cu, &err)) return fail(LP_ERR_HIP, err);
+    const bool fast_bwd = path == Path::Mfma && lp::mfma_bwd_records(n_cu) > 0;
+    const int max_records = fast_bwd ? lp::mfma_bwd_records(n_cu) : generic_bwd_blocks(n_cu);
+    const size_t need = sizeof(float) * (size_t)max_records * (size_t)ws_stride(m);
+    if (static_scratch) {
+        if (need > (size_t)LP_STATIC_SCRATCH_BYTES)
+            return fail(LP_ERR_UNSUPPORTED, "lp_render_bwd_static: this MLP needs " + std::to_string(need) +
+                        " bytes of partial-sum records, more than the library's static scratch of " +
+                        std::to_string((size_t)LP_STATIC_SCRATCH_BYTES) +
+                        " bytes (LP_STATIC_SCRATCH_BYTES); use lp_render_bwd with a workspace");
+        st = static_scratch_ptr(&workspace);
+        if (st != LP_OK) return st;
+        workspace_bytes = (size_t)LP_STATIC_SCRATCH_BYTES;
+    }
+    if (!workspace || workspace_bytes < need)
+        return fail(LP_ERR_WORKSPACE, "workspace is NULL or smaller than lp_bwd_workspace_bytes()");
+    if (((uintptr_t)workspace & 255u) != 0) return fail(LP_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+
+    lp::BwdIo io;
+    std::memset(&io, 0, sizeof(io));
+    io.d_rgb = d_rgb; io.d_alpha = d_alpha; io.d_depth = d_depth; io.cache = ray_cache;
+    for (int p = 0; p < 3; ++p) io.d_grid[p] = p < n_planes ? d_grid[p] : nullptr;
+    for (int l = 0; l < mlp->n_layers; ++l) { io.dW[l] = dW[l]; io.db[l] = db[l]; }
+    for (int c = 0; c < 3; ++c) io.bg[c] = bg[c];
+    io.ws = (float*)workspace;
+    io.ws_stride = ws_stride(m);
+    hipStream_t s = (hipStream_t)stream;
+
+    return run_bwd(g, m, r, io, fast_bwd, max_records, n_cu, s);
+}
+
 }  // namespace
 
 extern "C" {
@@ -471,44 +559,18 @@ lp_status lp_render_bwd(const lp_grid* grid, const lp_mlp* mlp, const lp_rays* r
                         float* const dW[LP_MAX_LAYERS], float* const db[LP_MAX_LAYERS],
                         void* workspace, size_t workspace_bytes, int32_t math_mode, void* stream)
 {
-    lp_status st = validate(grid, mlp, rays);
-    if (st != LP_OK) return st;
-    if (!bg || !d_grid || !dW || !db) return fail(LP_ERR_INVALID_ARG, "bg, d_grid, dW and db must not be NULL");
-    const int n_planes = grid->kind == LP_GRID_VOXEL ? 1 : 3;
-    for (int p = 0; p < n_planes; ++p)
-        if (!d_grid[p]) return fail(LP_ERR_INVALID_ARG, "d_grid has a NULL tensor");
-    for (int l = 0; l < mlp->n_layers; ++l)
-        if (!dW[l] || !db[l]) return fail(LP_ERR_INVALID_ARG, "dW / db has a NULL layer");
-    if (rays->M > 0 && (!d_rgb || !ray_cache))
-        return fail(LP_ERR_INVALID_ARG, "d_rgb and ray_cache must not be NULL");
-    lp::GridDev g; lp::MlpDev m; lp::RaysDev r;
-    to_device_views(grid, mlp, rays, &g, &m, &r);
-    Path path;
-    st = choose_path(g, m, math_mode, &path);
-    if (st != LP_OK) return st;
-    if (rays->M == 0) return LP_OK;
+    return render_bwd_with(grid, mlp, rays, bg, d_rgb, d_alpha, d_depth, ray_cache, d_grid, dW, db, workspace,
+                           workspace_bytes, /*static_scratch=*/false, math_mode, stream);
+}
 
-    std::string err;
-    int n_cu = 0;
-    if (compute_units(&n_cu, &err)) return fail(LP_ERR_HIP, err);
-    const bool fast_bwd = path == Path::Mfma && lp::mfma_bwd_records(n_cu) > 0;
-    const int max_records = fast_bwd ? lp::mfma_bwd_records(n_cu) : generic_bwd_blocks(n_cu);
-    const size_t need = sizeof(float) * (size_t)max_records * (size_t)ws_stride(m);
-    if (!workspace || workspace_bytes < need)
-        return fail(LP_ERR_WORKSPACE, "workspace is NULL or smaller than lp_bwd_workspace_bytes()");
-    if (((uintptr_t)workspace & 255u) != 0) return fail(LP_ERR_WORKSPACE, "workspace must be 256-byte aligned");
-
-    lp::BwdIo io;
-    std::memset(&io, 0, sizeof(io));
-    io.d_rgb = d_rgb; io.d_alpha = d_alpha; io.d_depth = d_depth; io.cache = ray_cache;
-    for (int p = 0; p < 3; ++p) io.d_grid[p] = p < n_planes ? d_grid[p] : nullptr;
-    for (int l = 0; l < mlp->n_layers; ++l) { io.dW[l] = dW[l]; io.db[l] = db[l]; }
-    for (int c = 0; c < 3; ++c) io.bg[c] = bg[c];
-    io.ws = (float*)workspace;
-    io.ws_stride = ws_stride(m);
-    hipStream_t s = (hipStream_t)stream;
-
-    return run_bwd(g, m, r, io, fast_bwd, max_records, n_cu, s);
+lp_status lp_render_bwd_static(const lp_grid* grid, const lp_mlp* mlp, const lp_rays* rays,
+                               const float bg[3], const float* d_rgb, const float* d_alpha,
+                               const float* d_depth, const float* ray_cache, float* const d_grid[3],
+                               float* const dW[LP_MAX_LAYERS], float* const db[LP_MAX_LAYERS],
+                               int32_t math_mode, void* stream)
+{
+    return render_bwd_with(grid, mlp, rays, bg, d_rgb, d_alpha, d_depth, ray_cache, d_grid, dW, db, nullptr, 0,
+                           /*static_scratch=*/true, math_mode, stream);
 }
 
 int32_t lp_dec_has_fast_path(const lp_grid* grid, const lp_decoder* dec)
