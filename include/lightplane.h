@@ -216,7 +216,7 @@ lp_status lp_render_dec_bwd(const lp_grid* grid, const lp_decoder* dec, const lp
                             void* workspace, size_t workspace_bytes, int32_t math_mode, void* stream);
 
 /* 1 if the matrix-core kernels cover this grid kind / decoder shape, else 0.  Covered, for
-   three sigmoid features on fp32 grids: 16 grid channels with a merged hidden width (opacity +
+   three sigmoid features on grids of any storage type: 16 grid channels with a merged hidden width (opacity +
    feature MLP, layer by layer) of 32 or 64, one or two hidden layers, at most 16 direction
    inputs; and 16 or 32 grid channels with two 3-layer MLPs of width 64 each (the paper's
    experimental size, any n_freq), which run as two chains. */
@@ -252,9 +252,10 @@ lp_status lp_splat_fwd(const lp_grid* target, const lp_rays* rays, const lp_spla
                        float* const theta[3], float* const theta_w[3], void* stream);
 
 /* 1 if lp_splat_fwd (and, with an MLP, lp_splat_bwd) runs this target / splat on the
-   wavefront-per-ray kernels, else 0 (generic kernels, same results).  Covered: targets of 16 or 32 channels; with an MLP also a prior of
-   the same channel count in fp32, no contraction, one or two hidden layers of width 64, and at
-   most 48 pixel-feature plus direction-encoding inputs.  Nothing behind the device pointers is read. */
+   wavefront-per-ray kernels, else 0 (generic kernels, same results).  Covered: targets of 16 or
+   32 channels, with or without contract coordinates; with an MLP also a prior of the same
+   channel count and contraction in fp32, one or two hidden layers of width 64, and at most 48
+   pixel-feature plus direction-encoding inputs.  Nothing behind the device pointers is read. */
 int32_t lp_splat_has_fast_path(const lp_grid* target, const lp_splat* splat);
 
 /* Backward for d_theta[p] = dL/d(out) (device).  The weights depend on the ray geometry only,

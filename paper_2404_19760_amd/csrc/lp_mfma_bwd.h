@@ -143,7 +143,7 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
         q_next = load_ray_geom(rays, ray_of(cur));
         if constexpr (CG != C) set_direction_inputs(m, q_next);
         if constexpr (kPrefetch) {
-            cell = sample_cell<CC>(g, q_next, min(j_last + slot_to_sample(col), S - 1));
+            cell = sample_cell_for<CC, GT>(g, q_next, min(j_last + slot_to_sample(col), S - 1));
             sample_features<KIND, C, CG, GT>(g, q_next, cell, grp, fh, fl);
         }
     }
@@ -167,7 +167,7 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
 
         for (int j0 = j_last; j0 >= 0; j0 -= kBwdStep) {
             if constexpr (!kPrefetch) {
-                cell = sample_cell<CC>(g, q, min(j0 + slot_to_sample(col), S - 1));
+                cell = sample_cell_for<CC, GT>(g, q, min(j0 + slot_to_sample(col), S - 1));
                 sample_features<KIND, C, CG, GT>(g, q, cell, grp, fh, fl);
             }
             StepActs<C, H, NH, kBwdNB> a;
@@ -259,7 +259,7 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
             if constexpr (kEarly) {
                 const bool same = j0 > 0;
                 const RayGeom& qn = same ? q : q_next;
-                cell_next = sample_cell<CC>(g, qn, min((same ? j0 - kBwdStep : j_last) + slot_to_sample(col), S - 1));
+                cell_next = sample_cell_for<CC, GT>(g, qn, min((same ? j0 - kBwdStep : j_last) + slot_to_sample(col), S - 1));
                 gather_issue<KIND, C, C / 2, GT>(g, qn.scene, cell_next, grp * (C / 2), raw_next);
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -339,7 +339,7 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
                 // cell of the next step of this ray, or of the last step of the next ray
                 const bool same = j0 > 0;
                 const RayGeom& qn = same ? q : q_next;
-                cell = sample_cell<CC>(g, qn, min((same ? j0 - kBwdStep : j_last) + slot_to_sample(col), S - 1));
+                cell = sample_cell_for<CC, GT>(g, qn, min((same ? j0 - kBwdStep : j_last) + slot_to_sample(col), S - 1));
                 __builtin_amdgcn_sched_barrier(0);
                 sample_features<KIND, C, CG, GT>(g, qn, cell, grp, fh, fl);
                 // the sampled features must be complete here (not sunk below the scatter)

@@ -11,15 +11,15 @@ hipError_t dispatch_bwd(const GridDev& g, const MlpDev& m, const RaysDev& rays, 
                          hipStream_t stream)
 {
     const int C = m.dims[0], CG = g.C, H = m.dims[1], NH = m.n_layers - 1;
-    // grids stored in bf16 / fp16: plain inputs, no contract coordinates
+    // grids stored in bf16 / fp16: plain inputs; the contraction is a run-time branch of these kernels
 #define LP_CASE(c, h, nh)                                                                                  \
-    if (C == c && CG == c && H == h && NH == nh && g.dtype != LP_F32 && !(g.contract > 0.0))               \
+    if (C == c && CG == c && H == h && NH == nh && g.dtype != LP_F32)               \
         return g.dtype == LP_BF16 ? launch_bwd<KIND, c, h, nh, false, c, LP_BF16>(g, m, rays, io, n_cu, stream) \
                                   : launch_bwd<KIND, c, h, nh, false, c, LP_F16>(g, m, rays, io, n_cu, stream);
     LP_CASE(16, 32, 1) LP_CASE(16, 64, 1) LP_CASE(32, 32, 1) LP_CASE(32, 64, 1)
     LP_CASE(16, 32, 2) LP_CASE(16, 64, 2) LP_CASE(32, 32, 2) LP_CASE(32, 64, 2)
 #undef LP_CASE
-    if (g.dtype != LP_F32) return hipErrorInvalidValue;
+    if (g.dtype != LP_F32 && CG == C) return hipErrorInvalidValue;   // (the decoder kernels read any storage type)
 #define LP_CASE(c, cg, h, nh)                                                                     \
     if (C == c && CG == cg && H == h && NH == nh)                                                 \
         return g.contract > 0.0 ? launch_bwd<KIND, c, h, nh, true, cg>(g, m, rays, io, n_cu, stream) \
@@ -33,7 +33,7 @@ hipError_t dispatch_bwd(const GridDev& g, const MlpDev& m, const RaysDev& rays, 
         return launch_bwd_mfma_b(g, m, rays, io, n_cu, stream);
 #define LP_CASE(h, nh) \
     if (C == 32 && CG == 16 && H == h && NH == nh) \
-        return launch_bwd<KIND, 32, h, nh, false, 16>(g, m, rays, io, n_cu, stream);
+        return launch_bwd<KIND, 32, h, nh, false, 16, kAnyDtype>(g, m, rays, io, n_cu, stream);
     LP_CASE(32, 1) LP_CASE(64, 1) LP_CASE(32, 2)
     if constexpr (KIND == LP_GRID_VOXEL) { LP_CASE(64, 2) }
 #undef LP_CASE

@@ -14,13 +14,13 @@ hipError_t dispatch_b(const GridDev& g, const MlpDev& m, const RaysDev& rays, co
     const int H = m.dims[1], NH = m.n_layers - 1;
     if (g.contract > 0.0) {
 #define LP_CASE(h, nh) \
-    if (H == h && NH == nh) return launch_bwd<KIND, 32, h, nh, true, 16>(g, m, rays, io, n_cu, stream);
+    if (H == h && NH == nh) return launch_bwd<KIND, 32, h, nh, true, 16, kAnyDtype>(g, m, rays, io, n_cu, stream);
         LP_CASE(32, 1) LP_CASE(64, 1) LP_CASE(32, 2) LP_CASE(64, 2)
 #undef LP_CASE
         return hipErrorInvalidValue;
     }
     if constexpr (KIND == LP_GRID_TRIPLANE) {
-        if (H == 64 && NH == 2) return launch_bwd<KIND, 32, 64, 2, false, 16>(g, m, rays, io, n_cu, stream);
+        if (H == 64 && NH == 2) return launch_bwd<KIND, 32, 64, 2, false, 16, kAnyDtype>(g, m, rays, io, n_cu, stream);
     }
     return hipErrorInvalidValue;
 }

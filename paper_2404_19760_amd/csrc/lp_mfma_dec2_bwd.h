@@ -268,7 +268,7 @@ __global__ __launch_bounds__(kWaves * 64) void dec2_bwd_kernel(GridDev g, Dec2De
             const int j = j0 + to_smp;
             const bool valid = j < S;
             a.cell[0] = sample_cell<CC>(g, q, min(j, S - 1));
-            sample_features<KIND, C, C, LP_F32>(g, q, a.cell[0], grp, a.fh[0], a.fl[0]);
+            sample_features<KIND, C, C, kAnyDtype>(g, q, a.cell[0], grp, a.fh[0], a.fl[0]);
             if constexpr (PASS == 0) {
                 wave_lds_fence();
                 if (grp == 0) write_scatter_record<KIND, C>(info + col * 16, g, a.cell[0]);

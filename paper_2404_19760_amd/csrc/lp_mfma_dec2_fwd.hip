@@ -36,7 +36,7 @@ __global__ __launch_bounds__(kWaves * 64) void dec2_fwd_kernel(GridDev g, Dec2De
 #pragma unroll
             for (int nb = 0; nb < 2; ++nb) {
                 const Cell3 c = sample_cell<CC>(g, q, min(j0 + 32 * nb + col, S - 1));
-                sample_features<KIND, C, C, LP_F32>(g, q, c, grp, fh[nb], fl[nb]);
+                sample_features<KIND, C, C, kAnyDtype>(g, q, c, grp, fh[nb], fl[nb]);
             }
             // the chains' outputs occupy different rows (opacity: 0, features: 1..3)
             float zs[4], zv[4];
@@ -106,7 +106,6 @@ hipError_t dispatch(const GridDev& g, const Dec2Dev& d, const RaysDev& rays, con
 bool dec2_supported(const GridDev& g, const DecLayout& d, int n_feat, int feat_act)
 {
     if (g.C != 16 && g.C != 32) return false;
-    if (g.dtype != LP_F32) return false;
     if (n_feat != 3 || feat_act != 0) return false;
     if (d.Ls != 3 || d.Lv != 3 || d.E > dec2::kMaxDir) return false;
     if (d.dims_s[0] != g.C || d.dims_s[1] != kH || d.dims_s[2] != kH || d.dims_s[3] != 1) return false;

@@ -101,15 +101,15 @@ hipError_t dispatch_fwd(const GridDev& g, const MlpDev& m, const RaysDev& rays, 
                         hipStream_t stream)
 {
     const int C = m.dims[0], CG = g.C, H = m.dims[1], NH = m.n_layers - 1;
-    // grids stored in bf16 / fp16: plain inputs, no contract coordinates
+    // grids stored in bf16 / fp16: plain inputs; the contraction is a run-time branch of these kernels
 #define LP_CASE(c, h, nh)                                                                                     \
-    if (C == c && CG == c && H == h && NH == nh && g.dtype != LP_F32 && !(g.contract > 0.0))                  \
+    if (C == c && CG == c && H == h && NH == nh && g.dtype != LP_F32)                  \
         return g.dtype == LP_BF16 ? launch_fwd<KIND, c, h, nh, 2, false, c, LP_BF16>(g, m, rays, out, n_cu, stream) \
                                   : launch_fwd<KIND, c, h, nh, 2, false, c, LP_F16>(g, m, rays, out, n_cu, stream);
     LP_CASE(16, 32, 1) LP_CASE(16, 64, 1) LP_CASE(32, 32, 1) LP_CASE(32, 64, 1)
     LP_CASE(16, 32, 2) LP_CASE(16, 64, 2) LP_CASE(32, 32, 2) LP_CASE(32, 64, 2)
 #undef LP_CASE
-    if (g.dtype != LP_F32) return hipErrorInvalidValue;
+    if (g.dtype != LP_F32 && CG == C) return hipErrorInvalidValue;   // (the decoder kernels read any storage type)
 #define LP_CASE(c, cg, h, nh)                                                                          \
     if (C == c && CG == cg && H == h && NH == nh)                                                      \
         return g.contract > 0.0 ? launch_fwd<KIND, c, h, nh, 2, true, cg>(g, m, rays, out, n_cu, stream) \
@@ -120,8 +120,8 @@ hipError_t dispatch_fwd(const GridDev& g, const MlpDev& m, const RaysDev& rays, 
     // 16 grid channels + direction inputs (the two-MLP decoder merged into one MLP of 32 inputs)
 #define LP_CASE(h, nh)                                                                                  \
     if (C == 32 && CG == 16 && H == h && NH == nh)                                                      \
-        return g.contract > 0.0 ? launch_fwd<KIND, 32, h, nh, 2, true, 16>(g, m, rays, out, n_cu, stream) \
-                                : launch_fwd<KIND, 32, h, nh, 2, false, 16>(g, m, rays, out, n_cu, stream);
+        return g.contract > 0.0 ? launch_fwd<KIND, 32, h, nh, 2, true, 16, kAnyDtype>(g, m, rays, out, n_cu, stream) \
+                                : launch_fwd<KIND, 32, h, nh, 2, false, 16, kAnyDtype>(g, m, rays, out, n_cu, stream);
     LP_CASE(32, 1) LP_CASE(64, 1) LP_CASE(32, 2) LP_CASE(64, 2)
 #undef LP_CASE
     return hipErrorInvalidValue;
@@ -135,8 +135,7 @@ bool mfma_supported(const GridDev& g, const MlpDev& m)
     const bool plain = m.n_enc == 0 && m.dims[0] == g.C && (g.C == 16 || g.C == 32);
     const bool with_dir = m.n_enc > 0 && g.C == 16 && m.dims[0] == 32 && m.n_enc <= 16;
     if (!plain && !with_dir) return false;
-    if (g.dtype != LP_F32 && (!plain || g.contract > 0.0)) return false;
-    if (m.n_feat != 3 || m.feat_act != 0 || m.dims[m.n_layers] != 4) return false;
+        if (m.n_feat != 3 || m.feat_act != 0 || m.dims[m.n_layers] != 4) return false;
     if (m.n_layers != 2 && m.n_layers != 3) return false;
     const int H = m.dims[1];
     if (H != 32 && H != 64) return false;

@@ -184,6 +184,26 @@ __device__ __forceinline__ Cell3 sample_cell(const GridDev& g, const RayGeom& q,
                    (double)q.oz + t * (double)q.dz);
 }
 
+// Same, with the contraction chosen at run time (a uniform branch): for kernels that are bound by
+// their scatter, where a second set of instantiations would only cost build time.
+__device__ __forceinline__ Cell3 sample_cell_any(const GridDev& g, const RayGeom& q, int j)
+{
+    return g.contract > 0.0 ? sample_cell<true>(g, q, j) : sample_cell<false>(g, q, j);
+}
+
+// Storage type "decided at run time": kernels instantiated with it read g.dtype in a uniform branch
+// around their gathers (the decoder kernels, which would otherwise triple their instantiations).
+constexpr int kAnyDtype = 3;
+
+// The kernels for grids stored in reduced precision take the contraction at run time as well (no
+// second set of instantiations); those for fp32 grids have it compiled in.
+template <bool CC, int GT>
+__device__ __forceinline__ Cell3 sample_cell_for(const GridDev& g, const RayGeom& q, int j)
+{
+    if constexpr (GT != LP_F32) return sample_cell_any(g, q, j);
+    else return sample_cell<CC>(g, q, j);
+}
+
 // Sample (within a 32-sample step) that MFMA column `slot` stands for when the step is
 // permuted so that each lane group's D registers of a [sample x channel] block hold 16
 // CONSECUTIVE samples: slot 8q + 4g + p  <->  sample 16g + 4q + p.
@@ -200,8 +220,8 @@ __host__ __device__ constexpr int sample_to_slot(int smp)
 // [grp C/2, (grp+1) C/2).  CG == C: all inputs are grid channels.  CG == C/2: lane group 0 holds
 // the CG grid channels, lane group 1 the per-ray direction inputs q.extra.
 template <int KIND, int C, int CG, int GT = LP_F32>
-__device__ __forceinline__ void sample_features(const GridDev& g, const RayGeom& q, const Cell3& c, int grp,
-                                                Frag (&fh)[C / 16], Frag (&fl)[C / 16])
+__device__ __forceinline__ void sample_features_typed(const GridDev& g, const RayGeom& q, const Cell3& c, int grp,
+                                                      Frag (&fh)[C / 16], Frag (&fl)[C / 16])
 {
     float feat[C / 2];
     if constexpr (CG == C) {
@@ -217,6 +237,20 @@ __device__ __forceinline__ void sample_features(const GridDev& g, const RayGeom&
     }
 #pragma unroll
     for (int s = 0; s < C / 16; ++s) split8(feat + 8 * s, fh[s], fl[s]);
+}
+
+// GT = kAnyDtype: the grid's storage type is taken at run time (a uniform branch around the gather).
+template <int KIND, int C, int CG, int GT = LP_F32>
+__device__ __forceinline__ void sample_features(const GridDev& g, const RayGeom& q, const Cell3& c, int grp,
+                                                Frag (&fh)[C / 16], Frag (&fl)[C / 16])
+{
+    if constexpr (GT == kAnyDtype) {
+        if (g.dtype == LP_F32) sample_features_typed<KIND, C, CG, LP_F32>(g, q, c, grp, fh, fl);
+        else if (g.dtype == LP_BF16) sample_features_typed<KIND, C, CG, LP_BF16>(g, q, c, grp, fh, fl);
+        else sample_features_typed<KIND, C, CG, LP_F16>(g, q, c, grp, fh, fl);
+    } else {
+        sample_features_typed<KIND, C, CG, GT>(g, q, c, grp, fh, fl);
+    }
 }
 
 // MLP forward of one step from the input features a.fh / a.fl: fills the hidden activations and
@@ -273,7 +307,7 @@ __device__ __forceinline__ void forward_step(const GridDev& g, const uint4* lds,
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
         const int j = min(j0 + 32 * nb + (PERM ? slot_to_sample(col) : col), S - 1);
-        const Cell3 c = sample_cell<CC>(g, q, j);
+        const Cell3 c = sample_cell_for<CC, GT>(g, q, j);
         a.cell[nb] = c;
         sample_features<KIND, C, CG, GT>(g, q, c, grp, a.fh[nb], a.fl[nb]);
     }
@@ -348,7 +382,7 @@ __device__ __forceinline__ void forward_outputs(const GridDev& g, const uint4* l
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
         const int j = min(j0 + 32 * nb + col, S - 1);
-        const Cell3 c = sample_cell<CC>(g, q, j);
+        const Cell3 c = sample_cell_for<CC, GT>(g, q, j);
         sample_features<KIND, C, CG, GT>(g, q, c, grp, fh[nb], fl[nb]);
     }
     mlp_outputs<C, H, NH>(lds, reinterpret_cast<const float*>(lds + L::BIAS), lane, fh, fl, z);

@@ -9,7 +9,8 @@
 // per point) only.  The last layer is taken
 // with the roles swapped, V = H^T Wout^T (points along M, channels along N), which leaves lane =
 // channel and registers = 16 consecutive points: the layout the run-merging scatter of the
-// Renderer's backward works on, so the push shares that code.
+// Renderer's backward works on, so the push shares that code.  Contract coordinates are a
+// run-time branch in the point placement (uniform over the launch).
 #include "lp_kernels.h"
 #include "lp_mfma.h"
 #include "lp_mfma_mlp.h"
@@ -130,7 +131,7 @@ __global__ __launch_bounds__(kWaves * 64) void splat_mfma_kernel(GridDev tgt, Ml
             const int jj = min(j, S - 1);
             Frag fh[1][KSP], fl[1][KSP];
             {
-                const Cell3 cp = sample_cell<false>(sp.prior, q, jj);
+                const Cell3 cp = sample_cell_any(sp.prior, q, jj);
 #pragma unroll
                 for (int s = 0; s < KSP; ++s) {
                     float feat[8];
@@ -138,7 +139,7 @@ __global__ __launch_bounds__(kWaves * 64) void splat_mfma_kernel(GridDev tgt, Ml
                     split8(feat, fh[0][s], fl[0][s]);
                 }
             }
-            const Cell3 ct = sample_cell<false>(tgt, q, jj);
+            const Cell3 ct = sample_cell_any(tgt, q, jj);
             wave_lds_fence();
             if (grp == 0) {
                 float* rec = info + col * 16;
@@ -224,7 +225,7 @@ bool splat_mfma_supported(const GridDev& tgt, const MlpDev& m, const SplatDev& s
     for (int l = 1; l < m.n_layers; ++l)
         if (m.dims[l] != kHidden) return false;
     if (!sp.has_prior || sp.prior.C != tgt.C || sp.prior.dtype != LP_F32) return false;
-    if (tgt.contract > 0.0 || sp.prior.contract > 0.0) return false;
+    if (tgt.contract != sp.prior.contract) return false;
     if (sp.n_in + m.n_enc > 48) return false;
     return splat_naive_supported(tgt) && splat_naive_supported(sp.prior);
 }

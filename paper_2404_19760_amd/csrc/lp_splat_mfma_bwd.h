@@ -299,7 +299,7 @@ __global__ __launch_bounds__(kWaves * 64) void splat_mfma_bwd_kernel(GridDev tgt
             const bool valid = j < S;
             const int jj = min(j, S - 1);
             Frag fh[1][KSP], fl[1][KSP];
-            const Cell3 cp = sample_cell<false>(sp.prior, q, jj);
+            const Cell3 cp = sample_cell_any(sp.prior, q, jj);
 #pragma unroll
             for (int s = 0; s < KSP; ++s) {
                 float feat[8];
@@ -309,7 +309,7 @@ __global__ __launch_bounds__(kWaves * 64) void splat_mfma_bwd_kernel(GridDev tgt
                 __builtin_amdgcn_sched_barrier(0);
             }
             Frag gv_h[1][KSP], gv_l[1][KSP];
-            gather_normalised<KIND, CP>(tgt, sp, q.scene, sample_cell<false>(tgt, q, jj), grp, valid, gv_h, gv_l);
+            gather_normalised<KIND, CP>(tgt, sp, q.scene, sample_cell_any(tgt, q, jj), grp, valid, gv_h, gv_l);
             // scatter record of this lane's point in the prior, read at the end of the step
             wave_lds_fence();
             if (grp == 0) write_scatter_record<KIND, CP>(info + col * 16, sp.prior, cp);

@@ -193,10 +193,13 @@ def check_case(lp, oracle, inp, math_mode=0, aux_grads=True, seed=0, label="", m
 
 # ---- the two-MLP, view-dependent decoder ----------------------------------------------------
 
-def run_gpu_dec(lp, inp, p_out, p_alpha=None, p_depth=None, math_mode=0, device="cuda:0"):
-    """Forward + backward with `inp.decoder` through the C ABI; everything returned as numpy."""
+def run_gpu_dec(lp, inp, p_out, p_alpha=None, p_depth=None, math_mode=0, device="cuda:0", grid_dtype=None):
+    """Forward + backward with `inp.decoder` through the C ABI; everything returned as numpy.
+    grid_dtype: torch dtype the grid is STORED in on the GPU (gradients stay float32)."""
     import torch
     grid, _, rays, bg = lp.to_device(inp, device)
+    if grid_dtype is not None:
+        grid.data = [t.to(grid_dtype) for t in grid.data]
     dec = lp.decoder_to_device(inp.decoder, device)
     out, alpha, depth, cache = lp.render_dec_fwd(grid, dec, rays, bg, math_mode)
     up = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device)
@@ -209,7 +212,8 @@ def run_gpu_dec(lp, inp, p_out, p_alpha=None, p_depth=None, math_mode=0, device=
                 dWv=lst(dWv), dbv=lst(dbv))
 
 
-def check_case_dec(lp, oracle, inp, math_mode=0, aux_grads=True, seed=0, label="", max_strict_fail=MAX_STRICT_FAIL):
+def check_case_dec(lp, oracle, inp, math_mode=0, aux_grads=True, seed=0, label="", max_strict_fail=MAX_STRICT_FAIL,
+                   grid_dtype=None):
     """Full parity of one problem with the two-MLP decoder: outputs and every gradient tensor."""
     import lp_inputs
     prob = oracle.Problem(inp)
@@ -222,7 +226,7 @@ def check_case_dec(lp, oracle, inp, math_mode=0, aux_grads=True, seed=0, label="
     ref = oracle.render2_bwd(prob, p_out, p_alpha, p_depth)
     upper = oracle.render2_bwd(prob, p_out, p_alpha, p_depth, kink_band=KINK_BAND, kink_side=+1)
     lower = oracle.render2_bwd(prob, p_out, p_alpha, p_depth, kink_band=KINK_BAND, kink_side=-1)
-    g = run_gpu_dec(lp, inp, p_out, p_alpha, p_depth, math_mode)
+    g = run_gpu_dec(lp, inp, p_out, p_alpha, p_depth, math_mode, grid_dtype=grid_dtype)
     worst = {"out": close(g["out"], o_out, FWD_RTOL, f"{label} out"),
              "alpha": close(g["alpha"], o_alpha, FWD_RTOL, f"{label} alpha"),
              "depth": close(g["depth"], o_depth, FWD_RTOL, f"{label} depth")}

@@ -72,7 +72,7 @@ def test_fast_path_queries_are_host_logic():
     import paper_2404_19760_amd as lp
     lib = lp._lib
 
-    def grid(kind, channels, res=(8, 8, 8), contract=0.0):
+    def grid(kind, channels, res=(8, 8, 8), contract=0.0, dtype=None):
         g = lp._Grid()
         g.kind, g.B, g.C = kind, 1, channels
         g.NX, g.NY, g.NZ = res
@@ -80,7 +80,7 @@ def test_fast_path_queries_are_host_logic():
             g.data[p] = 4096
             g.aabb_min[p], g.aabb_max[p] = -1.0, 1.0
         g.contract_a = contract
-        g.dtype = lp.LP_F32
+        g.dtype = lp.LP_F32 if dtype is None else dtype
         return g
 
     def mlp(*dims):
@@ -97,6 +97,8 @@ def test_fast_path_queries_are_host_logic():
     assert render(grid(0, 16), mlp(16, 64, 64, 4)) == 1
     assert render(grid(1, 32), mlp(32, 64, 4)) == 1
     assert render(grid(0, 16, contract=1.0), mlp(16, 32, 4)) == 1
+    assert render(grid(0, 16, contract=1.0, dtype=lp.LP_BF16), mlp(16, 64, 64, 4)) == 1   # reduced-precision storage too
+    assert render(grid(1, 32, dtype=lp.LP_F16), mlp(32, 64, 4)) == 1
     assert render(grid(0, 24), mlp(24, 64, 4)) == 0          # 16 or 32 channels
     assert render(grid(0, 16), mlp(16, 48, 4)) == 0          # hidden width 32 or 64
     assert render(grid(0, 16), mlp(16, 64, 32, 4)) == 0      # equal hidden widths
@@ -112,6 +114,8 @@ def test_fast_path_queries_are_host_logic():
     assert decoder(grid(1, 32), (32, 64, 64, 1), (47, 64, 64, 3), 2) == 1     # the paper's size: two chains
     assert decoder(grid(0, 16, contract=1.0), (16, 64, 64, 1), (19, 64, 64, 3), 0) == 1
     assert decoder(grid(0, 32), (32, 64, 64, 1), (59, 64, 64, 3), 4) == 1     # any number of octaves
+    assert decoder(grid(0, 16, dtype=lp.LP_BF16), (16, 32, 32, 1), (31, 32, 32, 3), 2) == 1   # grids in bf16 / fp16 too
+    assert decoder(grid(0, 32, contract=1.0, dtype=lp.LP_F16), (32, 64, 64, 1), (47, 64, 64, 3), 2) == 1
     assert decoder(grid(0, 16), (16, 16, 16, 1), (37, 48, 48, 3), 3) == 0     # merged: at most 16 direction inputs
     assert decoder(grid(0, 32), (32, 64, 1), (47, 64, 64, 3), 2) == 0         # two chains: both 3-layer
     assert decoder(grid(0, 32), (32, 64, 64, 1), (47, 64, 64, 4), 2, n_feat=4) == 0
@@ -132,7 +136,8 @@ def test_fast_path_queries_are_host_logic():
     assert splat(grid(0, 32), 32, 0, grid(0, 32), mlp(67, 64, 60, 32)) == 0              # hidden width 64 only
     assert splat(grid(0, 32), 32, 0, grid(0, 16), mlp(51, 64, 32)) == 0                  # prior and target alike
     assert splat(grid(0, 32), 46, 0, grid(0, 32), mlp(81, 64, 32)) == 0                  # at most 48 per-ray inputs
-    assert splat(grid(0, 32, contract=1.0), 32, 0, grid(0, 32, contract=1.0), mlp(67, 64, 32)) == 0
+    assert splat(grid(0, 32, contract=1.0), 32, 0, grid(0, 32, contract=1.0), mlp(67, 64, 32)) == 1
+    assert splat(grid(0, 32, contract=1.0), 32, 0, grid(0, 32), mlp(67, 64, 32)) == 0      # prior without the target's contraction
     assert splat(grid(0, 32), 32, 0, None, mlp(35, 64, 32)) == 0                         # needs a prior
     assert splat(grid(0, 32), 30, 0, grid(0, 32), mlp(67, 64, 32)) == 0                  # inconsistent widths
 

@@ -95,6 +95,30 @@ def test_decoder_at_the_papers_size(lp, oracle, kind, channels, n_freq, contract
                          max_strict_fail=0.05), flush=True)
 
 
+@pytest.mark.parametrize("kind", [VOXEL, TRIPLANE])
+@pytest.mark.parametrize("dtype", ["bfloat16", "float16"])
+def test_decoder_on_reduced_precision_grids(lp, oracle, kind, dtype):
+    """Grids stored in bf16 / fp16 under the two-MLP decoder: the merged matrix-core kernels (16 grid
+    channels + direction inputs) and the two chains at the paper's size, the latter with contract
+    coordinates.  The stored values are exactly representable, so the oracle receives them widened."""
+    import torch
+    tdt = getattr(torch, dtype)
+    cases = [dict(channels=16, hidden_s=(32, 32), hidden_v=(32, 32), n_freq=2, contract=0.0),
+             dict(channels=32, hidden_s=(64, 64), hidden_v=(64, 64), n_freq=1, contract=1.3)]
+    for c in cases:
+        kw = dict(origin_radius=1.5, near=(0.0, 0.3), far=(6.0, 20.0)) if c["contract"] else {}
+        inp = problem(kind, channels=c["channels"], hidden_s=c["hidden_s"], hidden_v=c["hidden_v"], n_freq=c["n_freq"],
+                      n_feat=3, seed=97, n_rays=203, samples=75, n_scenes=2, res=(12, 10, 11), grid_std=0.3,
+                      bias_std=0.1, **kw)
+        stored = [torch.from_numpy(g).to(tdt) for g in inp.grid]
+        inp = dataclasses.replace(inp, grid=[t.to(torch.float32).numpy() for t in stored], contract_a=c["contract"])
+        grid, _, _, _ = lp.to_device(inp)
+        grid.data = [t.to(tdt) for t in grid.data]
+        assert lp.lp_dec_has_fast_path(grid, lp.decoder_to_device(inp.decoder))
+        print(check_case_dec(lp, oracle, inp, lp.LP_MATH_BF16X3, label=f"dec {dtype} kind={kind} C={c['channels']}",
+                             max_strict_fail=0.05, grid_dtype=tdt), flush=True)
+
+
 @pytest.mark.parametrize("n_rays,samples", [(1, 1), (5, 33), (3, 64), (259, 2)])
 def test_decoder_two_chains_degenerate_sizes(lp, oracle, n_rays, samples):
     """Fewer rays than a workgroup has waves, a single sample, sample counts around the 32- and

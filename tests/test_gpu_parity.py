@@ -130,6 +130,15 @@ def test_reduced_precision_grid_storage(lp, oracle, kind, dtype):
         for mode in _modes(lp, widened):
             print(mode, check_case(lp, oracle, widened, mode, label=f"{dtype} kind={kind} C={channels} mode={mode}",
                                    grid_dtype=tdt), flush=True)
+    # with contract coordinates (rays from inside the unit cube to far beyond it)
+    inp = lp_inputs.make_small(kind, channels=32, res=(14, 12, 13), mlp_dims=(32, 64, 64, 4), n_rays=150, samples=100,
+                               seed=60, grid_std=0.3, origin_radius=1.4, near=(0.0, 0.3), far=(6.0, 30.0))
+    stored = [torch.from_numpy(g).to(tdt) for g in inp.grid]
+    widened = dataclasses.replace(inp, grid=[t.to(torch.float32).numpy() for t in stored], contract_a=1.3)
+    assert len(_modes(lp, widened)) == 2
+    for mode in _modes(lp, widened):
+        print(mode, check_case(lp, oracle, widened, mode, label=f"{dtype} contract kind={kind} mode={mode}",
+                               grid_dtype=tdt), flush=True)
 
 # ------------------------------------------------------------------ the five configurations
 

@@ -68,6 +68,23 @@ def test_splatter_mlp_on_matrix_cores(lp, oracle, kind, channels, n_in, hidden, 
                            width_cap=WIDTH_CAP_SPLAT_BORDER, max_strict_fail=0.06), flush=True)
 
 
+@pytest.mark.parametrize("kind", [VOXEL, TRIPLANE])
+@pytest.mark.parametrize("channels", [16, 32])
+def test_splatter_mlp_on_matrix_cores_with_contract_coordinates(lp, oracle, kind, channels):
+    """The paper's experimental setting uses the Splatter's MLP together with contract coordinates
+    (appendix, "Experimental Details"): rays that start inside the unit cube and run far beyond
+    it, prior and target contracted alike, matrix-core kernels forward and backward."""
+    sp = lp_inputs.make_splat_small(kind, channels=channels, res=(14, 12, 13), n_in=channels, hidden=(64, 64),
+                                    n_freq=0, prior_channels=channels, prior_res=(9, 8, 7), n_rays=150, samples=70,
+                                    seed=121, n_scenes=2, bias_std=0.1, origin_radius=0.8, near=(0.0, 0.3),
+                                    far=(6.0, 30.0))
+    sp = dataclasses.replace(sp, contract_a=1.4)
+    target, _, splat = lp.splat_to_device(sp)
+    assert lp.lp_splat_has_fast_path(target, splat)
+    print(check_case_splat(lp, oracle, sp, label=f"splat mfma contract kind={kind} C={channels}",
+                           max_strict_fail=0.06), flush=True)
+
+
 @pytest.mark.parametrize("n_rays,samples", [(1, 1), (5, 33), (3, 32)])
 def test_splatter_mlp_on_matrix_cores_degenerate_sizes(lp, oracle, n_rays, samples):
     """Fewer rays than a workgroup has waves, a single point, point counts around the 32-point step."""
