@@ -85,7 +85,7 @@ typedef struct {
 } lp_mlp;
 
 /*
- * M rays with S samples each (Section 3.3: "M rays and R+1 points per ray").  Sample j
+ * M rays with S samples each (the ray set of Section 3.3, whose R + 1 points per ray are read as S samples).  Sample j
  * (j = 1..S) sits at distance t_j = near + (j - 1/2) (far - near) / S from the origin along
  * the UNIT direction, so Delta = (far - near) / S is the world distance between samples.
  */

@@ -644,9 +644,9 @@ int lpo_num_threads(void)
 
 /* ==== The Renderer with the paper's own decoder (Section 3.3, below Eq. (1)) =================
  *
- * "feeds the feature to an MLP g_sigma to calculate the opacity"; the rendered feature
- * f_v "is calculated by another MLP g_v taking the sampled feature and view directions as
- * inputs", and the rendered quantity is a feature vector of any width ("e.g. colors, depths").
+ * Two MLPs read the feature sampled at a point: the opacity MLP g_sigma gives the density, and a
+ * second MLP g_v, which also receives the view direction, gives the feature f_v that is rendered;
+ * that feature is a vector of any width (colours and depths are the paper's examples).
  *
  *   sigma_j = softplus( g_sigma( h(x_j) )[0] )                 g_sigma : C -> ... -> 1
  *   f_j     = act( g_v( [ h(x_j) ; enc(d) ] ) )                g_v     : C + E -> ... -> F

@@ -133,8 +133,8 @@ __device__ __forceinline__ void axis_cell(double x, double lo, double scale, int
     axis_cell<CC>(x, lo, scale, N, contract, i, f, g);
 }
 
-// Entry e of the view-direction encoding (Section 3.3: the feature MLP takes "the sampled feature
-// and view directions"; the form is this library's reading): the direction itself, then per
+// Entry e of the view-direction encoding (Section 3.3: the feature MLP also receives the view
+// direction; the form of the encoding is this library's reading): the direction itself, then per
 // octave k the sines and the cosines of 2^k pi d, component by component.
 __device__ __forceinline__ float dir_encoding(const float d[3], int e)
 {

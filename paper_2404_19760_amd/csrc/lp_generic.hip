@@ -1,6 +1,6 @@
 // Generic Renderer kernels: any channel count and any MLP widths, scalar fp32.
 //
-// One lane marches one ray (the paper's "one kernel instance per ray", Section 3.4): it
+// One lane marches one ray (the granularity of the paper's own kernels, Section 3.4): it
 // samples, decodes and composites sample after sample, keeping only the running
 // transmittance and the rendered features.  A block is a single wavefront; MLP weights
 // live in LDS, activations in LDS columns indexed [feature][lane] (conflict free).
