@@ -65,7 +65,7 @@ class _Rays(C.Structure):
 
 def _load() -> C.CDLL:
     if not os.path.exists(LIB_PATH):
-        raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_2404_19760_amd.build` "
+        raise ImportError(f"{LIB_PATH} is not built; run `python paper_2404_19760_amd/build.py` "
                           "(there is no fallback implementation)")
     lib = C.CDLL(LIB_PATH)
     lib.lp_last_error.restype = C.c_char_p

@@ -1,6 +1,6 @@
 """Builds `liblightplane.so` (the C-ABI library) for gfx950 with hipcc, in-tree.
 
-    python -m paper_2404_19760_amd.build
+    python paper_2404_19760_amd/build.py
 
 Packed-FP32 instruction selection is switched off for every HIP source, and hardware
 floating-point atomics are enabled (the gradient buffers are ordinary device memory).
