@@ -19,9 +19,9 @@
 //      register = sample; a lane then walks its samples in ray order, sums the contributions
 //      of consecutive samples that fall into the same cell, and the lanes of one corner issue
 //      one atomic add per channel on consecutive addresses (whole 64-byte lines).
-// The weight-gradient accumulators are parked in the accumulation registers between their
-// updates; every other matrix-core result lands in ordinary vector registers (build flag of
-// this file), where the vector ALU post-processes it.  Each wave writes one record of partial
+// The weight-gradient accumulators live in the accumulation registers and are updated there
+// (mfma6_parked); every other matrix-core result lands in ordinary vector registers (build flag
+// of this file), where the vector ALU post-processes it.  Each wave writes one record of partial
 // sums at the end and a second kernel adds the records in a fixed order.
 //
 // This header holds the kernel and its launcher template.  lp_mfma_bwd.hip instantiates the
@@ -238,9 +238,7 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
                 for (int nb2 = 0; nb2 < MB; ++nb2) {
                     Frag bh[kBwdKS], bl[kBwdKS];
                     transpose_hidden(lh, ll, nb2, bh, bl);
-                    dWo[nb2] = mfma3(ah[0], al[0], bh[0], bl[0], dWo[nb2]);
-                    dWo[nb2] = mfma3(ah[1], al[1], bh[1], bl[1], dWo[nb2]);
-                    park(dWo[nb2]);
+                    mfma6_parked(dWo[nb2], ah, al, bh, bl);
                 }
             }
             relu_mask<MB>(acc, lh);
@@ -280,9 +278,7 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
                     transpose_hidden(a.h1h, a.h1l, nb2, bh, bl);
 #pragma unroll
                     for (int mb = 0; mb < MB; ++mb) {
-                        dW2[mb][nb2] = mfma3(ah[mb][0], al[mb][0], bh[0], bl[0], dW2[mb][nb2]);
-                        dW2[mb][nb2] = mfma3(ah[mb][1], al[mb][1], bh[1], bl[1], dW2[mb][nb2]);
-                        park(dW2[mb][nb2]);
+                        mfma6_parked(dW2[mb][nb2], ah[mb], al[mb], bh, bl);
                     }
                 }
                 relu_mask<MB>(acc, a.h1h);
@@ -311,9 +307,7 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
                     transpose_hidden(gz_h, gz_l, mb, ah, al);
 #pragma unroll
                     for (int ks = 0; ks < kBwdKS; ++ks) db1[mb] = frag_sum(al[ks], frag_sum(ah[ks], db1[mb]));
-                    dW1[mb] = mfma3(ah[0], al[0], bh[0], bl[0], dW1[mb]);
-                    dW1[mb] = mfma3(ah[1], al[1], bh[1], bl[1], dW1[mb]);
-                    park(dW1[mb]);
+                    mfma6_parked(dW1[mb], ah, al, bh, bl);
                 }
             }
             f32x16 dFt;

@@ -66,6 +66,37 @@ __device__ __forceinline__ void park(f32x16& acc)
     asm volatile("" : "+a"(acc));
 }
 
+// acc += A B over the two K-steps of a 32-sample step, each product as (a_hi + a_lo)(b_hi + b_lo)
+// without lo*lo, for an accumulator that LIVES in the accumulation registers: the six
+// instructions read and write it there, with no copies through vector registers (left to itself
+// the compiler keeps some of the long-lived accumulators in vector-register form and copies them
+// in and out of the accumulation registers at every step: 64 copies per step for two blocks).
+// The compiler does not look inside the block, so the block keeps the rules that apply itself:
+//   - a matrix instruction may read a vector register two wait states after a vector instruction
+//     wrote it at the earliest: the leading s_nop;
+//   - it may take the previous matrix instruction's result as its addend without wait states only
+//     when it follows it immediately: six in a row, nothing in between;
+//   - whatever touches the accumulator next (a copy the register allocator decides to make, the
+//     record at the end of the kernel) must find the last result landed: an 8-pass instruction's
+//     result may be read 18 wait states after its issue, the trailing s_nops.
+__device__ __forceinline__ void mfma6_parked(f32x16& acc, const Frag (&ah)[kBwdKS], const Frag (&al)[kBwdKS],
+                                             const Frag (&bh)[kBwdKS], const Frag (&bl)[kBwdKS])
+{
+    static_assert(kBwdKS == 2, "two K-steps per backward step");
+    asm volatile("s_nop 1\n\t"
+                 "v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0\n\t"
+                 "v_mfma_f32_32x32x16_bf16 %0, %3, %4, %0\n\t"
+                 "v_mfma_f32_32x32x16_bf16 %0, %3, %2, %0\n\t"
+                 "v_mfma_f32_32x32x16_bf16 %0, %5, %6, %0\n\t"
+                 "v_mfma_f32_32x32x16_bf16 %0, %7, %8, %0\n\t"
+                 "v_mfma_f32_32x32x16_bf16 %0, %7, %6, %0\n\t"
+                 "s_nop 15\n\t"
+                 "s_nop 1"
+                 : "+a"(acc)
+                 : "v"(as_bf16x8(al[0])), "v"(as_bf16x8(bh[0])), "v"(as_bf16x8(ah[0])), "v"(as_bf16x8(bl[0])),
+                   "v"(as_bf16x8(al[1])), "v"(as_bf16x8(bh[1])), "v"(as_bf16x8(ah[1])), "v"(as_bf16x8(bl[1])));
+}
+
 // Registers of a transposed block D[sample][feature] (values exactly representable in bf16)
 // -> operand fragments over the samples: K-step ks takes registers 8 ks .. 8 ks + 7.
 __device__ __forceinline__ void pack_exact(const f32x16& d, Frag (&f)[kBwdKS])
