@@ -89,9 +89,7 @@ __device__ __forceinline__ void chain_backward(const uint4* cl, int lane, const 
         for (int nb2 = 0; nb2 < MB; ++nb2) {
             Frag bh[kBwdKS], bl[kBwdKS];
             transpose_hidden(sel, a.h2h, a.h2l, nb2, bh, bl);
-            G.dWo[nb2] = mfma3(ah[0], al[0], bh[0], bl[0], G.dWo[nb2]);
-            G.dWo[nb2] = mfma3(ah[1], al[1], bh[1], bl[1], G.dWo[nb2]);
-            park(G.dWo[nb2]);
+            mfma6_parked(G.dWo[nb2], ah, al, bh, bl);
         }
     }
     relu_mask<MB>(acc, a.h2h);
@@ -115,9 +113,7 @@ __device__ __forceinline__ void chain_backward(const uint4* cl, int lane, const 
             transpose_hidden(sel, a.h1h, a.h1l, nb2, bh, bl);
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) {
-                G.dW2[mb][nb2] = mfma3(ah[mb][0], al[mb][0], bh[0], bl[0], G.dW2[mb][nb2]);
-                G.dW2[mb][nb2] = mfma3(ah[mb][1], al[mb][1], bh[1], bl[1], G.dW2[mb][nb2]);
-                park(G.dW2[mb][nb2]);
+                mfma6_parked(G.dW2[mb][nb2], ah[mb], al[mb], bh, bl);
             }
         }
     } else {
@@ -150,9 +146,7 @@ __device__ __forceinline__ void chain_backward(const uint4* cl, int lane, const 
             for (int ks = 0; ks < kBwdKS; ++ks) sum = frag_sum(al[ks], frag_sum(ah[ks], sum));
             G.db1[mb] += sum;
             if (ray_db1) ray_db1[mb] += sum;
-            G.dW1[mb] = mfma3(ah[0], al[0], bh[0], bl[0], G.dW1[mb]);
-            G.dW1[mb] = mfma3(ah[1], al[1], bh[1], bl[1], G.dW1[mb]);
-            park(G.dW1[mb]);
+            mfma6_parked(G.dW1[mb], ah, al, bh, bl);
         }
     }
     if constexpr (WANT_DF) {

@@ -340,9 +340,7 @@ __global__ __launch_bounds__(kWaves * 64) void splat_mfma_bwd_kernel(GridDev tgt
                 for (int nb2 = 0; nb2 < MB; ++nb2) {
                     Frag bh[kBwdKS], bl[kBwdKS];
                     transpose_hidden(lh, ll, nb2, bh, bl);
-                    dWo[nb2] = mfma3(ah[0], al[0], bh[0], bl[0], dWo[nb2]);
-                    dWo[nb2] = mfma3(ah[1], al[1], bh[1], bl[1], dWo[nb2]);
-                    park(dWo[nb2]);
+                    mfma6_parked(dWo[nb2], ah, al, bh, bl);
                     __builtin_amdgcn_sched_barrier(0);  // one accumulator block out of its parking place at a time
                 }
             }
@@ -367,9 +365,7 @@ __global__ __launch_bounds__(kWaves * 64) void splat_mfma_bwd_kernel(GridDev tgt
                     transpose_hidden(h1h, h1l, nb2, bh, bl);
 #pragma unroll
                     for (int mb = 0; mb < MB; ++mb) {
-                        dW2[mb][nb2] = mfma3(ah[mb][0], al[mb][0], bh[0], bl[0], dW2[mb][nb2]);
-                        dW2[mb][nb2] = mfma3(ah[mb][1], al[mb][1], bh[1], bl[1], dW2[mb][nb2]);
-                        park(dW2[mb][nb2]);
+                        mfma6_parked(dW2[mb][nb2], ah[mb], al[mb], bh, bl);
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 }
@@ -388,9 +384,7 @@ __global__ __launch_bounds__(kWaves * 64) void splat_mfma_bwd_kernel(GridDev tgt
                     transpose_hidden(gz_h, gz_l, mb, ah, al);
 #pragma unroll
                     for (int ks = 0; ks < kBwdKS; ++ks) dbr[mb] = frag_sum(al[ks], frag_sum(ah[ks], dbr[mb]));
-                    dW1p[mb] = mfma3(ah[0], al[0], bh[0], bl[0], dW1p[mb]);
-                    dW1p[mb] = mfma3(ah[1], al[1], bh[1], bl[1], dW1p[mb]);
-                    park(dW1p[mb]);
+                    mfma6_parked(dW1p[mb], ah, al, bh, bl);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
