@@ -11,9 +11,11 @@
 //   pass 1 accumulates the feature MLP's gradients and scatters nothing.  The direction inputs
 //          are constant along a ray: with s = the ray's sum of dZ1, their weight gradient is
 //          s enc(d)^T, one rank-one matrix-core update per ray.
-// A step first runs both chains forward for the decoder outputs only, evaluates the
-// emission-absorption backward (Eq. (2)), then re-runs a chain's forward right before that
-// chain's backward, so that only one chain's activations are alive at a time.
+// A step runs both chains forward, evaluates the emission-absorption backward (Eq. (2)), then
+// the backward of the chain whose weight gradients the pass accumulates, on that chain's live
+// activations.  In pass 0 the feature chain also has to pass its input gradient on; for that its
+// backward needs only the ReLU masks of its hidden layers, i.e. the high halves of their
+// activation fragments (32 registers), which are kept across the opacity chain's work.
 // Each pass writes one record of partial sums per wave and is followed by the reduction kernel.
 #pragma once
 #include "lp_mfma_bwd_common.h"
@@ -268,12 +270,27 @@ __global__ __launch_bounds__(kWaves * 64) void dec2_bwd_kernel(GridDev g, Dec2De
                 if (grp == 0) write_scatter_record<KIND, C>(info + col * 16, g, a.cell[0]);
             }
             // ---- both chains forward for the decoder outputs ----
+            // PASS 0: the feature chain first; of its activations only the high halves of the two
+            // hidden layers are kept (its backward here needs nothing but their ReLU masks), then the
+            // opacity chain, whose activations stay alive for its weight gradients.
+            // PASS 1: the opacity chain for its output only, then the feature chain, which stays alive.
             float z[4];
-            mlp_forward<C, kH, 2, true, 1>(lds_s, lane, a);
-            z[0] = a.z[0];
-            __builtin_amdgcn_sched_barrier(0);
-            mlp_forward<C, kH, 2, true, 1>(lds_v, lane, a, bias_v);
-            z[1] = a.z[1]; z[2] = a.z[2]; z[3] = a.z[3];
+            StepActs<C, kH, 2, 1> masks_v;   // PASS 0: h1h / h2h of the feature chain
+            if constexpr (PASS == 0) {
+                mlp_forward<C, kH, 2, true, 1>(lds_v, lane, a, bias_v);
+                z[1] = a.z[1]; z[2] = a.z[2]; z[3] = a.z[3];
+#pragma unroll
+                for (int s = 0; s < 4; ++s) { masks_v.h1h[0][s] = a.h1h[0][s]; masks_v.h2h[0][s] = a.h2h[0][s]; }
+                __builtin_amdgcn_sched_barrier(0);
+                mlp_forward<C, kH, 2, true, 1>(lds_s, lane, a);
+                z[0] = a.z[0];
+            } else {
+                mlp_forward<C, kH, 2, true, 1>(lds_s, lane, a);
+                z[0] = a.z[0];
+                __builtin_amdgcn_sched_barrier(0);
+                mlp_forward<C, kH, 2, true, 1>(lds_v, lane, a, bias_v);
+                z[1] = a.z[1]; z[2] = a.z[2]; z[3] = a.z[3];
+            }
             __builtin_amdgcn_sched_barrier(0);
 
             // ---- emission-absorption backward; MFMA column col stands for sample
@@ -318,11 +335,10 @@ __global__ __launch_bounds__(kWaves * 64) void dec2_bwd_kernel(GridDev g, Dec2De
 
             f32x16 dFt;
             if constexpr (PASS == 0) {
-                // the feature chain's activations are the ones alive: its input-gradient chain first
-                chain_backward<C, false, true>(lds_v, lane, sel, a, gzo_h, gzo_l, G, dFt, true, nullptr);
-                mlp_forward<C, kH, 2, true, 1>(lds_s, lane, a);
-                __builtin_amdgcn_sched_barrier(0);
-                chain_backward<C, true, true>(lds_s, lane, sel, a, gzo_h, gzo_l, G, dFt, false, nullptr);
+                // the opacity chain's activations are the ones alive: its full backward first, then the
+                // feature chain's input-gradient chain from the kept masks
+                chain_backward<C, true, true>(lds_s, lane, sel, a, gzo_h, gzo_l, G, dFt, true, nullptr);
+                chain_backward<C, false, true>(lds_v, lane, sel, masks_v, gzo_h, gzo_l, G, dFt, false, nullptr);
                 wave_lds_fence();
                 scatter_channels<KIND, C>(g, io.d_grid, q.scene, info, dFt, col, grp);
             } else {
