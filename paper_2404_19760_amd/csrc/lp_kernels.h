@@ -31,6 +31,11 @@ hipError_t launch_bwd_mfma_b(const GridDev& g, const MlpDev& m, const RaysDev& r
                              int n_cu, hipStream_t stream);
 
 
+// the shapes that run as a pair of waves per ray (lp_mfma_bwd_ws.hip)
+bool bwd_ws_supported(const GridDev& g, const MlpDev& m);
+hipError_t launch_bwd_mfma_ws(const GridDev& g, const MlpDev& m, const RaysDev& rays, const BwdIo& io,
+                              int n_cu, hipStream_t stream);
+
 // ---- naive Splatter forward, wavefront per ray (lp_splat_fast.hip): 16 or 32 channels ----
 bool splat_naive_supported(const GridDev& tgt);
 hipError_t launch_splat_naive(const GridDev& tgt, const RaysDev& rays, const SplatDev& sp, int n_cu,

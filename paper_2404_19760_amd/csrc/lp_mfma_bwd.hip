@@ -48,6 +48,7 @@ int mfma_bwd_records(int n_cu) { return ((n_cu + 7) / 8 * 8) * kWaves; }
 hipError_t launch_bwd_mfma(const GridDev& g, const MlpDev& m, const RaysDev& rays, const BwdIo& io, int n_cu,
                            hipStream_t stream)
 {
+    if (bwd_ws_supported(g, m)) return launch_bwd_mfma_ws(g, m, rays, io, n_cu, stream);
     return g.kind == LP_GRID_VOXEL ? dispatch_bwd<LP_GRID_VOXEL>(g, m, rays, io, n_cu, stream)
                                    : dispatch_bwd<LP_GRID_TRIPLANE>(g, m, rays, io, n_cu, stream);
 }

@@ -1,0 +1,24 @@
+// Matrix-core backward kernel of the Renderer with a chain wave and a weights wave per ray (see
+// lp_mfma_bwd_ws.h): shapes it covers and their instantiations.
+#include "lp_mfma_bwd_ws.h"
+
+#include <cstdlib>
+
+namespace lp {
+
+bool bwd_ws_supported(const GridDev& g, const MlpDev& m)
+{
+    static const bool off = [] { const char* e = std::getenv("LP_BWD_ONE_WAVE"); return e && e[0] == '1'; }();
+    if (off) return false;
+    return g.kind == LP_GRID_VOXEL && g.dtype == LP_F32 && g.C == 16 && m.dims[0] == 16 && m.n_layers == 3 &&
+           m.dims[1] == 64 && m.dims[2] == 64 && !(g.contract > 0.0);
+}
+
+hipError_t launch_bwd_mfma_ws(const GridDev& g, const MlpDev& m, const RaysDev& rays, const BwdIo& io, int n_cu,
+                              hipStream_t stream)
+{
+    if (!bwd_ws_supported(g, m)) return hipErrorInvalidValue;
+    return launch_bwd_ws<LP_GRID_VOXEL, 16, 64, false>(g, m, rays, io, n_cu, stream);
+}
+
+}  // namespace lp
