@@ -188,11 +188,14 @@ struct CornerAcc {
 // samples in ray order.  Contributions are summed per corner while the ray stays in a cell
 // (and on shared corners across a step into a neighbouring cell) before one atomic add per
 // corner; the lanes ch = 0..C-1 of a group address consecutive floats.
-template <int KIND, int C>
+// IN_ORDER: record s belongs to sample s of the step and dFt[r] to sample 16 grp + r (a kernel that
+// passes the feature gradient through LDS reads it back in this order without permuting the step).
+template <int KIND, int C, bool IN_ORDER = false>
 __device__ __forceinline__ void scatter_channels(const GridDev& g, float* const d_grid[3], int scene,
                                                  const float* info, const f32x16& dFt, int ch, int grp)
 {
     const bool live = ch < C;
+    auto record_of = [grp](int r) { return IN_ORDER ? 16 * grp + r : d_row(r, grp); };
     if constexpr (KIND == LP_GRID_VOXEL && C == 16) {
         // 16 channels fill half a lane group: lanes 16..31 hold the same feature gradients as lanes
         // 0..15 (the transposed first-layer weights are staged twice), and each half takes the four
@@ -217,7 +220,7 @@ __device__ __forceinline__ void scatter_channels(const GridDev& g, float* const 
         unsigned bq[kAhead];
 #pragma unroll
         for (int r = 0; r < kAhead; ++r) {
-            const float* rec = info + d_row(r, grp) * 16;
+            const float* rec = info + record_of(r) * 16;
             wq[r] = reinterpret_cast<const float4*>(rec)[dz];
             bq[r] = reinterpret_cast<const unsigned*>(rec)[8];
         }
@@ -226,7 +229,7 @@ __device__ __forceinline__ void scatter_channels(const GridDev& g, float* const 
             const float4 w4 = wq[r % kAhead];
             const unsigned base = bq[r % kAhead];
             if (r + kAhead < 16) {
-                const float* rec = info + d_row(r + kAhead, grp) * 16;
+                const float* rec = info + record_of(r + kAhead) * 16;
                 wq[r % kAhead] = reinterpret_cast<const float4*>(rec)[dz];
                 bq[r % kAhead] = reinterpret_cast<const unsigned*>(rec)[8];
             }
@@ -258,7 +261,7 @@ __device__ __forceinline__ void scatter_channels(const GridDev& g, float* const 
         };
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const float* rec = info + d_row(r, grp) * 16;
+            const float* rec = info + record_of(r) * 16;
             const float4 w0 = reinterpret_cast<const float4*>(rec)[0];
             const float4 w1 = reinterpret_cast<const float4*>(rec)[1];
             const unsigned base = reinterpret_cast<const unsigned*>(rec)[8];
@@ -302,7 +305,7 @@ __device__ __forceinline__ void scatter_channels(const GridDev& g, float* const 
             };
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const float* rec = info + d_row(r, grp) * 16;
+                const float* rec = info + record_of(r) * 16;
                 const float4 w4 = reinterpret_cast<const float4*>(rec)[pl];
                 const unsigned base = reinterpret_cast<const unsigned*>(rec)[12 + pl];
                 const float w[4] = {w4.x, w4.y, w4.z, w4.w};

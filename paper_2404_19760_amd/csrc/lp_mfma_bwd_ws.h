@@ -52,7 +52,7 @@ struct PairLds {
     static constexpr int SLOT1 = SLOT0 + SLOT;             // h2, then dZ2
     static constexpr int F = SLOT1 + SLOT;                 // input features: KS1 fragments, hi and lo
     static constexpr int ZO = F + KS1 * 128;               // output gradients of sample column c: (hi01, hi23, lo01, lo23)
-    static constexpr int DFT = ZO + 32;                    // feature gradient: [4 register quads][2 lane groups][C channels]
+    static constexpr int DFT = ZO + 32;                    // feature gradient: [8 quads of samples][C channels] x 4 samples
     static constexpr int REC = DFT + 4 * 2 * C;            // two buffers of 32 scatter records (16 dwords each)
     static constexpr int FLAGS = REC + 2 * 128;
     static constexpr int UNITS = FLAGS + 4;
@@ -186,7 +186,7 @@ __global__ __launch_bounds__(2 * kPairs * 64) void bwd_ws_kernel(GridDev g, MlpD
         Frag fh[KS1], fl[KS1];
         if (cur.live()) {
             q_next = load_ray_geom(rays, cur.ray());
-            cell = sample_cell_for<CC, GT>(g, q_next, min(j_last + slot_to_sample(col), S - 1));
+            cell = sample_cell_for<CC, GT>(g, q_next, min(j_last + col, S - 1));
             sample_features<KIND, C, C, GT>(g, q_next, cell, grp, fh, fl);
         }
         while (cur.live()) {
@@ -213,7 +213,7 @@ __global__ __launch_bounds__(2 * kPairs * 64) void bwd_ws_kernel(GridDev g, MlpD
                 GatherRaw<KIND, C / 2, GT> raw_next;
                 Cell3 cell_next = cell;
                 if (more) {
-                    cell_next = sample_cell_for<CC, GT>(g, qn, min((same ? j0 - kBwdStep : j_last) + slot_to_sample(col), S - 1));
+                    cell_next = sample_cell_for<CC, GT>(g, qn, min((same ? j0 - kBwdStep : j_last) + col, S - 1));
                     gather_issue<KIND, C, C / 2, GT>(g, qn.scene, cell_next, grp * (C / 2), raw_next);
                 }
                 __builtin_amdgcn_sched_barrier(0);
@@ -233,27 +233,23 @@ __global__ __launch_bounds__(2 * kPairs * 64) void bwd_ws_kernel(GridDev g, MlpD
                 store_frags<KSH>(mine + P::SLOT1, lane, a.h2h, a.h2l);
                 ho.post(progress(n, C_H2));
 
-                // ---- emission-absorption backward; MFMA column col stands for sample
-                //      j0 + slot_to_sample(col) (both lane groups alike), so the scans along the
-                //      ray run on values moved into sample order and their results are moved back ----
-                const int to_slot = sample_to_slot(col), to_smp = slot_to_sample(col);
-                const int j = j0 + to_smp;
+                // ---- emission-absorption backward; MFMA column col stands for sample j0 + col (both lane
+                //      groups alike): the scans along the ray run over the 32 lanes of a group ----
+                const int j = j0 + col;
                 const bool valid = j < S;
                 const float t = near + ((float)j + 0.5f) * delta;
                 const float sd = valid ? fast_softplus(a.z[0]) * delta : 0.0f;
-                const float incl_ord = group_scan_incl<kBwdStep>(__shfl(sd, to_slot, kBwdStep), col);
-                const float incl = __shfl(incl_ord, to_smp, kBwdStep);
-                const float tau_start = tau_end - __shfl(incl_ord, kBwdStep - 1, kBwdStep);
+                const float incl = group_scan_incl<kBwdStep>(sd, col);
+                const float tau_start = tau_end - __int_as_float(__builtin_amdgcn_readlane(__float_as_int(incl), kBwdStep - 1));
                 const float Tprev = __expf(-(tau_start + (incl - sd)));
                 const float w = Tprev * one_minus_exp_neg(sd);
                 const float Tq = Tprev - w;
                 const float c1 = fast_logistic(a.z[1]), c2 = fast_logistic(a.z[2]), c3 = fast_logistic(a.z[3]);
                 const float aa = p0 * c1 + p1 * c2 + p2 * c3 + p_depth * t;
                 const float wa = w * aa;
-                const float wa_ord = __shfl(wa, to_slot, kBwdStep);
-                const float pre_ord = group_scan_incl<kBwdStep>(wa_ord, col);
-                const float wa_total = __shfl(pre_ord, kBwdStep - 1, kBwdStep);
-                const float suf = __shfl(wa_total - pre_ord + wa_ord, to_smp, kBwdStep);
+                const float pre = group_scan_incl<kBwdStep>(wa, col);
+                const float wa_total = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pre), kBwdStep - 1));
+                const float suf = wa_total - pre + wa;
                 const float dsigma = delta * (Tq * aa - (suf - wa + carry) + kS);
                 carry += wa_total;
                 tau_end = tau_start;
@@ -472,12 +468,12 @@ __global__ __launch_bounds__(2 * kPairs * 64) void bwd_ws_kernel(GridDev g, MlpD
             f32x16 dFt;
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
-                const uint4 v = mine[P::DFT + (qd * 2 + grp) * C + (col & (C - 1))];
+                const uint4 v = mine[P::DFT + (4 * grp + qd) * C + (col & (C - 1))];   // samples 16 grp + 4 qd ..
                 dFt[4 * qd] = __uint_as_float(v.x); dFt[4 * qd + 1] = __uint_as_float(v.y);
                 dFt[4 * qd + 2] = __uint_as_float(v.z); dFt[4 * qd + 3] = __uint_as_float(v.w);
             }
             ho.post(progress(n, W_DFT));
-            scatter_channels<KIND, C>(g, io.d_grid, scene, reinterpret_cast<const float*>(mine + P::REC + (n & 1) * 128),
+            scatter_channels<KIND, C, true>(g, io.d_grid, scene, reinterpret_cast<const float*>(mine + P::REC + (n & 1) * 128),
                                       dFt, col, grp);
             ho.post(progress(n, W_WALK));
             __builtin_amdgcn_sched_barrier(0);
