@@ -39,7 +39,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # HBM bytes per launch of the backward kernel from two rocprofv3 --pmc runs (FETCH_SIZE scaled
 # by 2.0, WRITE_SIZE by 1.0 against a 1 GiB copy kernel in the same run); the summary with the
 # commands is profiles/large_voxel256_fwd_bwd_kernels.md.  None = not measured for that workload.
-MEASURED_BWD_HBM_BYTES = {"large": 11.08e9 + 65.42e9}
+MEASURED_BWD_HBM_BYTES = {"large": 12.06e9 + 65.42e9}
 
 
 def parse():
@@ -61,6 +61,9 @@ def parse():
                                       "splat_naive,splat_mlp",
                     help="further workloads reported for context under 'also' (comma-separated, '' to skip; "
                          "name:bf16 / name:f16 = that workload with the grid stored in reduced precision)")
+    ap.add_argument("--coexecution", action="store_true",
+                    help="instead of the benchmark: time how one SIMD overlaps matrix and vector instructions "
+                         "(one JSON line)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy kernel (reference for HBM counters)")
     return ap.parse_args()
@@ -238,6 +241,14 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the Renderer has no CPU path", file=sys.stderr)
         sys.exit(2)
+    if args.coexecution:
+        ns = lp.lp_diag_coexecution()
+        print(json.dumps({
+            "measurement": "overlap of 32x32x16 bf16 matrix products (32 cycles) with vector multiply-adds (4 cycles) on one SIMD",
+            "one_wave_ns_per_product_followed_by_K_multiply_adds": {"K=0": ns[0], "K=4": ns[1], "K=8": ns[2], "K=12": ns[3]},
+            "two_waves_w_and_w_plus_4_ns_per_iteration": {"8 products only": ns[4], "64 multiply-adds only": ns[5], "both": ns[6]},
+            "two_waves_w_and_w_plus_1_ns_per_iteration": {"8 products only": ns[7], "64 multiply-adds only": ns[8], "both": ns[9]}}))
+        return
     mode = {"default": lp.LP_MATH_DEFAULT, "generic": lp.LP_MATH_GENERIC, "bf16x3": lp.LP_MATH_BF16X3}[args.math]
     r = measure(lp, torch, args.config, mode, args.steps, args.warmup, args.calibrate_copy, args.grid_dtype, args.aabb,
                 measure_memory=not args.calibrate_copy)

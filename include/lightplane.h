@@ -272,6 +272,18 @@ lp_status lp_splat_bwd(const lp_grid* target, const lp_rays* rays, const lp_spla
 lp_status lp_splat_bwd_workspace_bytes(const lp_grid* target, const lp_rays* rays, const lp_splat* splat,
                                        size_t* bytes);
 
+/* Diagnostics, not part of the method: how one SIMD of this GPU overlaps matrix instructions
+   (32x32x16 bf16 products, 32 cycles each) with vector instructions (4 cycles each); the split of
+   the Renderer's backward into two waves per ray follows from it.  ns_per_iteration (host, 10
+   floats) receives nanoseconds per loop iteration of
+     [0..3]  one wave per SIMD issuing one product followed by 0, 4, 8, 12 independent vector
+             multiply-adds (a sum 32 + 4 K cycles means no overlap inside a wave);
+     [4..6]  two waves per SIMD, waves w and w + 4 of a workgroup paired: the first issues 8 products
+             per iteration, the second 64 multiply-adds; only the first works, only the second, both;
+     [7..9]  the same with waves w and w + 1 paired.
+   Allocates and frees a small device buffer; synchronises the stream. */
+lp_status lp_diag_coexecution(float* ns_per_iteration, void* stream);
+
 /* Message of the last failure on this thread ("" if none).  Owned by the library. */
 const char* lp_last_error(void);
 

@@ -70,6 +70,8 @@ def _load() -> C.CDLL:
     lib = C.CDLL(LIB_PATH)
     lib.lp_last_error.restype = C.c_char_p
     lib.lp_version.restype = C.c_int32
+    lib.lp_diag_coexecution.restype = C.c_int
+    lib.lp_diag_coexecution.argtypes = [C.POINTER(C.c_float), C.c_void_p]
     lib.lp_has_fast_path.restype = C.c_int32
     lib.lp_has_fast_path.argtypes = [C.POINTER(_Grid), C.POINTER(_Mlp)]
     lib.lp_render_fwd.restype = C.c_int
@@ -273,6 +275,13 @@ def _bg(bg) -> C.Array:
 
 def lp_version() -> int:
     return int(_lib.lp_version())
+
+
+def lp_diag_coexecution(stream=None):
+    """Nanoseconds per loop iteration of the ten measurements the header describes."""
+    out = (C.c_float * 10)()
+    _check(_lib.lp_diag_coexecution(out, _stream_ptr(stream)))
+    return [float(v) for v in out]
 
 
 def lp_has_fast_path(grid: Grid, mlp: Mlp) -> bool:
