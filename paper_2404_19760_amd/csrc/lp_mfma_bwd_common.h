@@ -215,7 +215,7 @@ __device__ __forceinline__ void scatter_channels(const GridDev& g, float* const 
         };
         // the records are read two samples ahead of their use, so that the LDS latency is covered by
         // the work on the samples in between
-        constexpr int kAhead = 2;
+        constexpr int kAhead = IN_ORDER ? 6 : 2;   // (the two-wave kernel's weights wave has registers to spare here)
         float4 wq[kAhead];
         unsigned bq[kAhead];
 #pragma unroll

@@ -7,29 +7,39 @@
 // 16-64-64-4 MLP are 128 registers per lane, so two waves that each do the whole backward of a
 // ray do not fit the 512 registers of a SIMD lane.  Two waves of different ROLES do:
 //
-//   chain wave    recomputes the MLP forward of a 32-sample step, evaluates Eq. (2), and runs the
-//                 input-gradient chain dX = W^T dZ down to the feature gradient: the dependent
-//                 sequence layer -> split into bf16 operands -> layer, about 700 vector and 84 matrix
-//                 instructions per step.  It holds no accumulators and touches no global memory
-//                 inside a step.
-//   weights wave  samples the hash structure (Section 3.2) for the step AFTER the current one,
-//                 transposes the activations and pre-activation gradients the chain wave hands over
+//   chain wave    samples the hash structure (Section 3.2; the texel loads of the next step are issued
+//                 at the start of a step and interpolated at its end), recomputes the MLP forward of
+//                 a 32-sample step, evaluates Eq. (2), and runs the input-gradient chain dX = W^T dZ
+//                 down to the feature gradient: the dependent sequence layer -> split into bf16
+//                 operands -> layer.  It holds no accumulators and issues no atomic adds, so its
+//                 loads never queue behind them.
+//   weights wave  transposes the activations and pre-activation gradients the chain wave hands over
 //                 (0/1 selection products), accumulates dW += dZ X^T and db, and scatters the feature
-//                 gradient into the grid gradient (run-merged atomic adds).  Its waits on global
-//                 memory and its matrix work run under the chain wave's vector work.
+//                 gradient into the grid gradient (run-merged atomic adds).  Apart from those atomic
+//                 adds it touches no global memory inside a step.
 //
 // Waves w and w + 4 of a workgroup of eight land on the same SIMD (measured: two matrix-bound waves
 // w, w + 4 take twice the time of one; w, w + 1 do not), so pair p = (wave p: chain, wave p + 4:
-// weights) marches the rays the one-wave kernel gives to wave p.
+// weights) marches the rays the one-wave kernel gives to wave p.  Steps are marched in sample order
+// (MFMA column c = sample j0 + c): the scans of Eq. (2) then run in lane order, and the order the walk
+// wants (16 consecutive samples per lane group) is produced by the way the weights wave reads the
+// feature gradient back from LDS.
 //
 // Hand-over through LDS, per pair: two 8 KiB slots for the hidden tensors as operand fragments (h1
-// then dZ2 in one, h2 then dZ1 in the other), the input features, the output gradients, the
-// feature gradient, two buffers of scatter records; nothing per sample goes to global memory.  Every
-// buffer has a `posted` and a `taken` counter holding the number of the last step written /
-// consumed; LDS operations of a wave execute in order, so data written before a counter is visible
-// to whoever reads the counter first.  Waits poll with s_sleep and give up after kSpinLimit polls:
-// the wave then stops waiting for good and the weight-gradient record is poisoned with NaN, so a
-// broken hand-over ends as a wrong (loudly wrong) result, never as a hang.
+// then dZ1 in one, h2 then dZ2 in the other), the input features, the output gradients, the feature
+// gradient, two buffers of scatter records; nothing per sample goes to global memory.  Each wave
+// publishes ONE counter in LDS that says how far it has got (see HandOver); LDS operations of a wave
+// execute in order, so data written before a counter value is visible to whoever reads that value.
+// Waits poll with s_sleep and give up after kSpinLimit polls: the wave then stops waiting for good
+// and the weight-gradient record is poisoned with NaN, so a broken hand-over ends as a wrong (loudly
+// wrong) result, never as a hang.
+//
+// Tried and dropped (largest configuration, same box; this layout: 60.5 ms, one wave per ray: 63.6 ms):
+// sampling in the weights wave (its loads queue behind its own atomic adds: 83 ms); the walk of a step
+// deferred behind the next step's transposes (more live registers than the 256 of a wave: spills that
+// also queue behind the atomic adds, 62.6 - 80 ms); the second half of the input-gradient chain in
+// the weights wave (64 ms: that wave becomes the longer one).  With the weights wave idle the chain
+// wave alone takes 53 ms, so the split as such cannot go below that.
 #pragma once
 #include "lp_kernels.h"
 #include "lp_mfma.h"
@@ -41,7 +51,7 @@ namespace lp {
 namespace {
 
 constexpr int kPairs = 4;             // (chain, weights) wave pairs per workgroup
-constexpr int kSpinLimit = 1 << 20;   // polls of one wait before the wave gives up (normal: < 100)
+constexpr int kSpinLimit = 1 << 20;   // polls of one wait before the wave gives up (normal: a handful)
 
 // LDS area of one pair in 16-byte units.
 template <int C, int H>
@@ -67,24 +77,27 @@ enum ChainStage { C_H1, C_H2, C_ZO, C_Z2, C_F, C_Z1, C_DFT };
 enum WeightsStage { W_H2, W_ZO, W_H1, W_Z2, W_F, W_Z1, W_DFT, W_WALK };
 __host__ __device__ constexpr int progress(int n, int stage) { return 8 * n + stage; }
 
+typedef __attribute__((address_space(3))) int LdsInt;   // the counters are addressed as LDS, never through flat instructions
+                                                        // (a flat access waits for the wave's global memory operations too)
+
 struct HandOver {
-    int* own;           // counter this wave publishes
-    const int* other;   // the partner's counter
-    int seen;           // last value read from the partner's counter
-    bool dead;          // a wait ran into the spin limit: never wait again
+    LdsInt* own;           // counter this wave publishes
+    const LdsInt* other;   // the partner's counter
+    int seen;              // last value read from the partner's counter
+    bool dead;             // a wait ran into the spin limit: never wait again
 
     // everything this wave wrote to LDS before is visible to whoever reads the new value
     __device__ __forceinline__ void post(int value)
     {
         wave_lds_fence();
-        *reinterpret_cast<volatile int*>(own) = value;
+        *const_cast<volatile LdsInt*>(own) = value;
     }
     __device__ __forceinline__ void await(int need)
     {
         if (seen < need && !dead) {
             int spins = 0;
-            while ((seen = __builtin_amdgcn_readfirstlane(*reinterpret_cast<const volatile int*>(other))) < need) {
-                __builtin_amdgcn_s_sleep(1);
+            while ((seen = __builtin_amdgcn_readfirstlane(*const_cast<const volatile LdsInt*>(other))) < need) {
+                __builtin_amdgcn_s_sleep(10);   // 640 cycles: polling faster than this only takes issue slots from the partner wave
                 if (++spins > kSpinLimit) { dead = true; break; }
             }
         }
@@ -161,7 +174,7 @@ __global__ __launch_bounds__(2 * kPairs * 64) void bwd_ws_kernel(GridDev g, MlpD
     const bool chain = wave < kPairs;
     uint4* mine = lds + L::END + pair * P::UNITS;
     // the two counters sit in different 32-byte halves of the flag area
-    int* flags = reinterpret_cast<int*>(mine + P::FLAGS);
+    LdsInt* flags = (LdsInt*)reinterpret_cast<int*>(mine + P::FLAGS);
     HandOver ho;
     ho.own = flags + (chain ? 0 : 8);
     ho.other = flags + (chain ? 8 : 0);

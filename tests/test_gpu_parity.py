@@ -81,6 +81,20 @@ def test_config_shapes_ragged(lp, oracle, kind, channels, dims, samples):
               flush=True)
 
 
+def test_one_wave_backward_of_the_two_wave_shape():
+    """The shape whose backward runs as a pair of waves per ray (voxel grid, 16 fp32 channels, MLP
+    16-64-64-4) also has the one-wave kernel; LP_BWD_ONE_WAVE=1 selects it when the library is loaded,
+    hence the child process.  Same parity bar."""
+    import os, subprocess, sys
+    env = dict(os.environ, LP_BWD_ONE_WAVE="1")
+    test = os.path.abspath(__file__) + "::test_config_shapes_ragged[150-0-16-dims0]"
+    res = subprocess.run([sys.executable, "-m", "pytest", test, "-m", "gpu", "-x", "-q", "--timeout", "200",
+                          "--timeout-method", "thread", "-p", "no:cacheprovider"],
+                         env=env, capture_output=True, text=True, timeout=400)
+    assert res.returncode == 0, res.stdout[-2000:] + res.stderr[-2000:]
+    assert "1 passed" in res.stdout
+
+
 # ------------------------------------------------------------------ contract coordinates
 
 @pytest.mark.parametrize("kind", [VOXEL, TRIPLANE])
