@@ -10,15 +10,19 @@ bool bwd_ws_supported(const GridDev& g, const MlpDev& m)
 {
     static const bool off = [] { const char* e = std::getenv("LP_BWD_ONE_WAVE"); return e && e[0] == '1'; }();
     if (off) return false;
-    return g.kind == LP_GRID_VOXEL && g.dtype == LP_F32 && g.C == 16 && m.dims[0] == 16 && m.n_layers == 3 &&
-           m.dims[1] == 64 && m.dims[2] == 64 && !(g.contract > 0.0);
+    return g.kind == LP_GRID_VOXEL && g.C == 16 && m.dims[0] == 16 && m.n_layers == 3 && m.dims[1] == 64 &&
+           m.dims[2] == 64 && (g.dtype == LP_F32 || g.dtype == LP_BF16 || g.dtype == LP_F16);
 }
 
 hipError_t launch_bwd_mfma_ws(const GridDev& g, const MlpDev& m, const RaysDev& rays, const BwdIo& io, int n_cu,
                               hipStream_t stream)
 {
     if (!bwd_ws_supported(g, m)) return hipErrorInvalidValue;
-    return launch_bwd_ws<LP_GRID_VOXEL, 16, 64, false>(g, m, rays, io, n_cu, stream);
+    // grids stored in bf16 / fp16 take the contraction as a run-time branch (as in the one-wave kernels)
+    if (g.dtype == LP_BF16) return launch_bwd_ws<LP_GRID_VOXEL, 16, 64, false, LP_BF16>(g, m, rays, io, n_cu, stream);
+    if (g.dtype == LP_F16) return launch_bwd_ws<LP_GRID_VOXEL, 16, 64, false, LP_F16>(g, m, rays, io, n_cu, stream);
+    return g.contract > 0.0 ? launch_bwd_ws<LP_GRID_VOXEL, 16, 64, true>(g, m, rays, io, n_cu, stream)
+                            : launch_bwd_ws<LP_GRID_VOXEL, 16, 64, false>(g, m, rays, io, n_cu, stream);
 }
 
 }  // namespace lp
