@@ -216,7 +216,7 @@ lp_status lp_render_dec_bwd(const lp_grid* grid, const lp_decoder* dec, const lp
                             void* workspace, size_t workspace_bytes, int32_t math_mode, void* stream);
 
 /* 1 if the matrix-core kernels cover this grid kind / decoder shape, else 0.  Covered, for
-   three sigmoid features on grids of any storage type: 16 grid channels with a merged hidden width (opacity +
+   three features (sigmoid or identity) on grids of any storage type: 16 grid channels with a merged hidden width (opacity +
    feature MLP, layer by layer) of 32 or 64, one or two hidden layers, at most 16 direction
    inputs; and 16 or 32 grid channels with two 3-layer MLPs of width 64 each (the paper's
    experimental size, any n_freq), which run as two chains. */

@@ -653,7 +653,7 @@ lp_status lp_render_dec_fwd(const lp_grid* grid, const lp_decoder* dec, const lp
     st = decoder_path(g, m, d, math_mode, &path, &records, &two_chains);
     if (st != LP_OK) return st;
     if (two_chains) {   // nothing to merge
-        hipError_t e2 = lp::launch_dec2_fwd(g, lp::dec2_view(d), r, fo, n_cu, s);
+        hipError_t e2 = lp::launch_dec2_fwd(g, lp::dec2_view(d, m.feat_act), r, fo, n_cu, s);
         if (e2 != hipSuccess) return hip_fail("two-chain decoder forward kernel launch", e2);
         return LP_OK;
     }
@@ -712,7 +712,7 @@ lp_status lp_render_dec_bwd(const lp_grid* grid, const lp_decoder* dec, const lp
         for (int c = 0; c < dec->n_feat; ++c) io2.bg[c] = bg[c];
         io2.ws = (float*)((char*)workspace + 2 * params);
         io2.ws_stride = ws_stride(m);
-        hipError_t e2 = lp::launch_dec2_bwd(g, lp::dec2_view(d), r, io2, n_cu, s);
+        hipError_t e2 = lp::launch_dec2_bwd(g, lp::dec2_view(d, m.feat_act), r, io2, n_cu, s);
         if (e2 != hipSuccess) return hip_fail("two-chain decoder backward kernel launch", e2);
         return LP_OK;
     }

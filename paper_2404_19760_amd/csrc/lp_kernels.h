@@ -85,10 +85,11 @@ struct Dec2Dev {
     float* dWs[3]; float* dbs[3];
     float* dWv[3]; float* dbv[3];
     int E;   // width of the direction encoding (at most 32)
+    int feat_act;   // 0: sigmoid features, 1: identity
 };
-// grids of 16 / 32 fp32 channels, both MLPs with two hidden layers of 64, three sigmoid features
+// grids of 16 / 32 channels, both MLPs with two hidden layers of 64, three features (sigmoid or identity)
 bool dec2_supported(const GridDev& g, const DecLayout& d, int n_feat, int feat_act);
-Dec2Dev dec2_view(const DecLayout& d);
+Dec2Dev dec2_view(const DecLayout& d, int feat_act);
 hipError_t launch_dec2_fwd(const GridDev& g, const Dec2Dev& d, const RaysDev& rays, const FwdOut& out, int n_cu,
                            hipStream_t stream);
 // backward: ACCUMULATES into io.d_grid and into d's gradient pointers; io.ws holds

@@ -213,6 +213,11 @@ __device__ __forceinline__ float fast_logistic(float z)
     return __frcp_rn(1.0f + __expf(-z));
 }
 
+// Rendered feature from its decoder output: logistic sigmoid, or the output itself (`identity`, a
+// uniform run-time flag), and the derivative of that head given its value.
+__device__ __forceinline__ float feature_head(float z, bool identity) { return identity ? z : fast_logistic(z); }
+__device__ __forceinline__ float feature_head_slope(float c, bool identity) { return identity ? 1.0f : c * (1.0f - c); }
+
 // ---- sampling of the hash structure (Section 3.2) for one lane's half of the channels ----
 
 struct Cell3 {

@@ -51,6 +51,7 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
     stage_mlp<C, H, NH, true, kBwdNB, CG>(lds, m);
     __syncthreads();
 
+    const bool identity = m.feat_act != 0;   // rendered features without the sigmoid (two-MLP decoder only)
     const int lane = threadIdx.x & 63;
     const int col = lane & 31, grp = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -190,7 +191,7 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
             const float Tprev = __expf(-(tau_start + (incl - sd)));
             const float w = Tprev * one_minus_exp_neg(sd);
             const float Tq = Tprev - w;
-            const float c1 = fast_logistic(a.z[1]), c2 = fast_logistic(a.z[2]), c3 = fast_logistic(a.z[3]);
+            const float c1 = feature_head(a.z[1], identity), c2 = feature_head(a.z[2], identity), c3 = feature_head(a.z[3], identity);
             const float aa = p0 * c1 + p1 * c2 + p2 * c3 + p_depth * t;
             const float wa = w * aa;
             const float wa_ord = __shfl(wa, to_slot, kBwdStep);
@@ -202,9 +203,9 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
             tau_end = tau_start;
             float dz[4];
             dz[0] = valid ? dsigma * fast_logistic(a.z[0]) : 0.0f;
-            dz[1] = valid ? w * p0 * c1 * (1.0f - c1) : 0.0f;
-            dz[2] = valid ? w * p1 * c2 * (1.0f - c2) : 0.0f;
-            dz[3] = valid ? w * p2 * c3 * (1.0f - c3) : 0.0f;
+            dz[1] = valid ? w * p0 * feature_head_slope(c1, identity) : 0.0f;
+            dz[2] = valid ? w * p1 * feature_head_slope(c2, identity) : 0.0f;
+            dz[3] = valid ? w * p2 * feature_head_slope(c3, identity) : 0.0f;
 #pragma unroll
             for (int k = 0; k < 4; ++k) dbo[k] += grp == 0 ? dz[k] : 0.0f;
 

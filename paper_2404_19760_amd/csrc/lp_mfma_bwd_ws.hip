@@ -10,7 +10,7 @@ bool bwd_ws_supported(const GridDev& g, const MlpDev& m)
 {
     static const bool off = [] { const char* e = std::getenv("LP_BWD_ONE_WAVE"); return e && e[0] == '1'; }();
     if (off) return false;
-    return g.kind == LP_GRID_VOXEL && g.C == 16 && m.dims[0] == 16 && m.n_layers == 3 && m.dims[1] == 64 &&
+    return g.kind == LP_GRID_VOXEL && g.C == 16 && m.dims[0] == 16 && m.n_feat == 3 && m.feat_act == 0 && m.n_layers == 3 && m.dims[1] == 64 &&
            m.dims[2] == 64 && (g.dtype == LP_F32 || g.dtype == LP_BF16 || g.dtype == LP_F16);
 }
 

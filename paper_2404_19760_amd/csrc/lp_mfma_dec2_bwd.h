@@ -303,7 +303,8 @@ __global__ __launch_bounds__(kWaves * 64) void dec2_bwd_kernel(GridDev g, Dec2De
             const float Tprev = __expf(-(tau_start + (incl - sd)));
             const float w = Tprev * one_minus_exp_neg(sd);
             const float Tq = Tprev - w;
-            const float c1 = fast_logistic(z[1]), c2 = fast_logistic(z[2]), c3 = fast_logistic(z[3]);
+            const bool identity = d.feat_act != 0;
+            const float c1 = feature_head(z[1], identity), c2 = feature_head(z[2], identity), c3 = feature_head(z[3], identity);
             const float aa = p0 * c1 + p1 * c2 + p2 * c3 + p_depth * t;
             const float wa = w * aa;
             const float wa_ord = __shfl(wa, to_slot, kBwdStep);
@@ -315,9 +316,9 @@ __global__ __launch_bounds__(kWaves * 64) void dec2_bwd_kernel(GridDev g, Dec2De
             tau_end = tau_start;
             float dz[4];
             dz[0] = valid ? dsigma * fast_logistic(z[0]) : 0.0f;
-            dz[1] = valid ? w * p0 * c1 * (1.0f - c1) : 0.0f;
-            dz[2] = valid ? w * p1 * c2 * (1.0f - c2) : 0.0f;
-            dz[3] = valid ? w * p2 * c3 * (1.0f - c3) : 0.0f;
+            dz[1] = valid ? w * p0 * feature_head_slope(c1, identity) : 0.0f;
+            dz[2] = valid ? w * p1 * feature_head_slope(c2, identity) : 0.0f;
+            dz[3] = valid ? w * p2 * feature_head_slope(c3, identity) : 0.0f;
 #pragma unroll
             for (int k = 0; k < 4; ++k) G.dbo[k] += grp == 0 ? dz[k] : 0.0f;
             Frag gzo_h[1][1], gzo_l[1][1];

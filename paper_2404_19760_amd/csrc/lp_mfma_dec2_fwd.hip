@@ -51,9 +51,9 @@ __global__ __launch_bounds__(kWaves * 64) void dec2_fwd_kernel(GridDev g, Dec2De
             const float incl = group_scan_incl<kStep>(sd, lane);
             const float Tprev = __expf(-(tau + (incl - sd)));
             const float w = Tprev * one_minus_exp_neg(sd);
-            acc_r += w * fast_logistic(zv[1]);
-            acc_g += w * fast_logistic(zv[2]);
-            acc_b += w * fast_logistic(zv[3]);
+            acc_r += w * feature_head(zv[1], d.feat_act != 0);
+            acc_g += w * feature_head(zv[2], d.feat_act != 0);
+            acc_b += w * feature_head(zv[3], d.feat_act != 0);
             acc_d += w * t;
             tau += __shfl(incl, kStep - 1, kStep);
         }
@@ -106,7 +106,7 @@ hipError_t dispatch(const GridDev& g, const Dec2Dev& d, const RaysDev& rays, con
 bool dec2_supported(const GridDev& g, const DecLayout& d, int n_feat, int feat_act)
 {
     if (g.C != 16 && g.C != 32) return false;
-    if (n_feat != 3 || feat_act != 0) return false;
+    if (n_feat != 3 || (feat_act != 0 && feat_act != 1)) return false;
     if (d.Ls != 3 || d.Lv != 3 || d.E > dec2::kMaxDir) return false;
     if (d.dims_s[0] != g.C || d.dims_s[1] != kH || d.dims_s[2] != kH || d.dims_s[3] != 1) return false;
     if (d.dims_v[0] != g.C + d.E || d.dims_v[1] != kH || d.dims_v[2] != kH || d.dims_v[3] != 3) return false;
@@ -122,7 +122,7 @@ bool dec2_supported(const GridDev& g, const DecLayout& d, int n_feat, int feat_a
     return true;
 }
 
-Dec2Dev dec2_view(const DecLayout& d)
+Dec2Dev dec2_view(const DecLayout& d, int feat_act)
 {
     Dec2Dev v;
     for (int l = 0; l < 3; ++l) {
@@ -132,6 +132,7 @@ Dec2Dev dec2_view(const DecLayout& d)
         v.dWv[l] = d.dWv[l]; v.dbv[l] = d.dbv[l];
     }
     v.E = d.E;
+    v.feat_act = feat_act;
     return v;
 }
 

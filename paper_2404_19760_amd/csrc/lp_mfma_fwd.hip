@@ -30,6 +30,7 @@ __global__ __launch_bounds__(kWaves * 64) void fwd_mfma_kernel(GridDev g, MlpDev
     const int lane = threadIdx.x & 63;
     const RaySchedule sched = ray_schedule(rays.M, kWaves);
     const int S = rays.S;
+    const bool identity = m.feat_act != 0;   // rendered features without the sigmoid (two-MLP decoder only)
 
     for (long long ray = sched.first; ray < sched.end; ray += sched.stride) {
         RayGeom q = load_ray_geom(rays, ray);
@@ -56,9 +57,9 @@ __global__ __launch_bounds__(kWaves * 64) void fwd_mfma_kernel(GridDev g, MlpDev
             const float incl = group_scan_incl<kStep>(sd, pos);
             const float Tprev = __expf(-(tau + (incl - sd)));
             const float w = (NB == 2 || lane < 32) ? Tprev * one_minus_exp_neg(sd) : 0.0f;
-            acc_r += w * fast_logistic(a.z[1]);
-            acc_g += w * fast_logistic(a.z[2]);
-            acc_b += w * fast_logistic(a.z[3]);
+            acc_r += w * feature_head(a.z[1], identity);
+            acc_g += w * feature_head(a.z[2], identity);
+            acc_b += w * feature_head(a.z[3], identity);
             acc_d += w * t;
             tau += __shfl(incl, kStep - 1, kStep);
         }
@@ -135,7 +136,7 @@ bool mfma_supported(const GridDev& g, const MlpDev& m)
     const bool plain = m.n_enc == 0 && m.dims[0] == g.C && (g.C == 16 || g.C == 32);
     const bool with_dir = m.n_enc > 0 && g.C == 16 && m.dims[0] == 32 && m.n_enc <= 16;
     if (!plain && !with_dir) return false;
-        if (m.n_feat != 3 || m.feat_act != 0 || m.dims[m.n_layers] != 4) return false;
+        if (m.n_feat != 3 || m.dims[m.n_layers] != 4) return false;
     if (m.n_layers != 2 && m.n_layers != 3) return false;
     const int H = m.dims[1];
     if (H != 32 && H != 64) return false;

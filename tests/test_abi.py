@@ -116,6 +116,8 @@ def test_fast_path_queries_are_host_logic():
     assert decoder(grid(0, 32), (32, 64, 64, 1), (59, 64, 64, 3), 4) == 1     # any number of octaves
     assert decoder(grid(0, 16, dtype=lp.LP_BF16), (16, 32, 32, 1), (31, 32, 32, 3), 2) == 1   # grids in bf16 / fp16 too
     assert decoder(grid(0, 32, contract=1.0, dtype=lp.LP_F16), (32, 64, 64, 1), (47, 64, 64, 3), 2) == 1
+    assert decoder(grid(0, 32), (32, 64, 64, 1), (47, 64, 64, 3), 2, feat_act=1) == 1   # identity features too
+    assert decoder(grid(0, 16), (16, 32, 32, 1), (31, 32, 32, 3), 2, feat_act=1) == 1
     assert decoder(grid(0, 16), (16, 16, 16, 1), (37, 48, 48, 3), 3) == 0     # merged: at most 16 direction inputs
     assert decoder(grid(0, 32), (32, 64, 1), (47, 64, 64, 3), 2) == 0         # two chains: both 3-layer
     assert decoder(grid(0, 32), (32, 64, 64, 1), (47, 64, 64, 4), 2, n_feat=4) == 0

@@ -119,6 +119,26 @@ def test_decoder_on_reduced_precision_grids(lp, oracle, kind, dtype):
                              max_strict_fail=0.05, grid_dtype=tdt), flush=True)
 
 
+@pytest.mark.parametrize("kind", [VOXEL, TRIPLANE])
+def test_decoder_identity_features_on_the_matrix_cores(lp, oracle, kind):
+    """Rendered features without the sigmoid (feat_act = identity), three of them: the merged
+    matrix-core kernels and the two chains at the paper's size, the latter with contract coordinates."""
+    cases = [dict(channels=16, hidden_s=(32, 32), hidden_v=(32, 32), n_freq=2, contract=0.0),
+             dict(channels=16, hidden_s=(24,), hidden_v=(40,), n_freq=1, contract=1.3),
+             dict(channels=32, hidden_s=(64, 64), hidden_v=(64, 64), n_freq=1, contract=1.3),
+             dict(channels=16, hidden_s=(64, 64), hidden_v=(64, 64), n_freq=2, contract=0.0)]
+    for c in cases:
+        kw = dict(origin_radius=1.5, near=(0.0, 0.3), far=(6.0, 20.0)) if c["contract"] else {}
+        inp = problem(kind, channels=c["channels"], hidden_s=c["hidden_s"], hidden_v=c["hidden_v"], n_freq=c["n_freq"],
+                      n_feat=3, feat_act=1, seed=101, n_rays=203, samples=75, n_scenes=2, res=(12, 10, 11), grid_std=0.3,
+                      bias_std=0.1, **kw)
+        inp = dataclasses.replace(inp, contract_a=c["contract"])
+        grid, _, _, _ = lp.to_device(inp)
+        assert lp.lp_dec_has_fast_path(grid, lp.decoder_to_device(inp.decoder))
+        print(check_case_dec(lp, oracle, inp, lp.LP_MATH_BF16X3, label=f"dec identity kind={kind} C={c['channels']} {c['hidden_v']}",
+                             max_strict_fail=0.05), flush=True)
+
+
 @pytest.mark.parametrize("n_rays,samples", [(1, 1), (5, 33), (3, 64), (259, 2)])
 def test_decoder_two_chains_degenerate_sizes(lp, oracle, n_rays, samples):
     """Fewer rays than a workgroup has waves, a single sample, sample counts around the 32- and
@@ -147,11 +167,11 @@ def test_decoder_fast_path_limits(lp):
         return lp.lp_dec_has_fast_path(grid, lp.decoder_to_device(inp.decoder))
     assert fast(mk())
     assert not fast(mk(n_feat=4))                      # three features only
-    assert not fast(mk(feat_act=1))                    # sigmoid only
+    assert fast(mk(feat_act=1))                        # sigmoid or identity
     assert not fast(mk(hidden_s=(16,), hidden_v=(20,)))  # merged width must be 32 or 64
     assert not fast(mk(channels=32, hidden_s=(16,), hidden_v=(16,)))
     assert fast(dataclasses.replace(mk(), contract_a=1.0))
-    inp = mk(feat_act=1)
+    inp = mk(n_feat=4)
     grid, _, rays, bg = lp.to_device(inp)
     with pytest.raises(lp.LightplaneError) as e:
         lp.render_dec_fwd(grid, lp.decoder_to_device(inp.decoder), rays, bg, lp.LP_MATH_BF16X3)
