@@ -10,13 +10,15 @@
 //   chain wave    samples the hash structure (Section 3.2; the texel loads of the next step are issued
 //                 at the start of a step and interpolated at its end), recomputes the MLP forward of
 //                 a 32-sample step, evaluates Eq. (2), and runs the input-gradient chain dX = W^T dZ
-//                 down to the feature gradient: the dependent sequence layer -> split into bf16
-//                 operands -> layer.  It holds no accumulators and issues no atomic adds, so its
-//                 loads never queue behind them.
+//                 down to the first layer's pre-activation gradient dZ1: the dependent sequence
+//                 layer -> split into bf16 operands -> layer.  It holds no accumulators and issues no
+//                 atomic adds, so its loads never queue behind them.
 //   weights wave  transposes the activations and pre-activation gradients the chain wave hands over
-//                 (0/1 selection products), accumulates dW += dZ X^T and db, and scatters the feature
-//                 gradient into the grid gradient (run-merged atomic adds).  Apart from those atomic
-//                 adds it touches no global memory inside a step.
+//                 (0/1 selection products, their operands kept in LDS), accumulates dW += dZ X^T and
+//                 db, takes the chain's last link (feature gradient dF = W1^T dZ1: matrix
+//                 instructions only, and this wave's matrix work is hidden under the chain wave's
+//                 vector work) and scatters it into the grid gradient (run-merged atomic adds).
+//                 Apart from those atomic adds it touches no global memory inside a step.
 //
 // Waves w and w + 4 of a workgroup of eight land on the same SIMD (measured: two matrix-bound waves
 // w, w + 4 take twice the time of one; w, w + 1 do not), so pair p = (wave p: chain, wave p + 4:
@@ -26,15 +28,16 @@
 // feature gradient back from LDS.
 //
 // Hand-over through LDS, per pair: two 8 KiB slots for the hidden tensors as operand fragments (h1
-// then dZ1 in one, h2 then dZ2 in the other), the input features, the output gradients, the feature
-// gradient, two buffers of scatter records; nothing per sample goes to global memory.  Each wave
+// then dZ1 in one, h2 then dZ2 in the other), the input features, the output gradients, two buffers
+// of scatter records (and the weights wave's own area for re-ordering the feature gradient); nothing
+// per sample goes to global memory.  Each wave
 // publishes ONE counter in LDS that says how far it has got (see HandOver); LDS operations of a wave
 // execute in order, so data written before a counter value is visible to whoever reads that value.
 // Waits poll with s_sleep and give up after kSpinLimit polls: the wave then stops waiting for good
 // and the weight-gradient record is poisoned with NaN, so a broken hand-over ends as a wrong (loudly
 // wrong) result, never as a hang.
 //
-// Tried and dropped (largest configuration, same box; this layout: 60.5 ms, one wave per ray: 63.6 ms):
+// Tried and dropped (largest configuration, same box; this layout: 60 ms, one wave per ray: 63.6 ms):
 // sampling in the weights wave (its loads queue behind its own atomic adds: 83 ms); the walk of a step
 // deferred behind the next step's transposes (more live registers than the 256 of a wave: spills that
 // also queue behind the atomic adds, 62.6 - 80 ms); the second half of the input-gradient chain in
@@ -62,7 +65,7 @@ struct PairLds {
     static constexpr int SLOT1 = SLOT0 + SLOT;             // h2, then dZ2
     static constexpr int F = SLOT1 + SLOT;                 // input features: KS1 fragments, hi and lo
     static constexpr int ZO = F + KS1 * 128;               // output gradients of sample column c: (hi01, hi23, lo01, lo23)
-    static constexpr int DFT = ZO + 32;                    // feature gradient: [8 quads of samples][C channels] x 4 samples
+    static constexpr int DFT = ZO + 32;                    // (weights wave only) feature gradient: [8 quads of samples][C channels] x 4 samples
     static constexpr int REC = DFT + 4 * 2 * C;            // two buffers of 32 scatter records (16 dwords each)
     static constexpr int FLAGS = REC + 2 * 128;
     static constexpr int UNITS = FLAGS + 4;
@@ -73,8 +76,8 @@ struct PairLds {
 // program order; for the weights wave the buffers it has finished READING (plus the end of its walk).
 // A wave that needs the partner to have passed (n, stage) compares with the last value it has seen and
 // reads the counter again only if that is not enough, so most checks cost nothing.
-enum ChainStage { C_H1, C_H2, C_ZO, C_Z2, C_F, C_Z1, C_DFT };
-enum WeightsStage { W_H2, W_ZO, W_H1, W_Z2, W_F, W_Z1, W_DFT, W_WALK };
+enum ChainStage { C_H1, C_H2, C_ZO, C_Z2, C_F, C_Z1 };
+enum WeightsStage { W_H2, W_ZO, W_H1, W_Z2, W_F, W_Z1, W_WALK };
 __host__ __device__ constexpr int progress(int n, int stage) { return 8 * n + stage; }
 
 typedef __attribute__((address_space(3))) int LdsInt;   // the counters are addressed as LDS, never through flat instructions
@@ -161,6 +164,18 @@ __global__ __launch_bounds__(2 * kPairs * 64) void bwd_ws_kernel(GridDev g, MlpD
     constexpr int MB = L::MB, KS1 = L::KS1, KSH = L::KSH;
     extern __shared__ uint4 lds[];
     stage_mlp<C, H, NH, true, kBwdNB, C>(lds, m);
+    // the 0/1 selection operands of the transposes, one 16-byte entry per lane each: hidden tensors
+    // (two K-steps per 32-feature block), output gradients, input features
+    constexpr int kSel = L::END + kPairs * P::UNITS, kSelH0 = 0, kSelH1 = 1, kSelO = 2, kSelF = 3;
+    if (threadIdx.x < 64) {
+        const int c = threadIdx.x & 31, gq = threadIdx.x >> 5;
+        auto put = [&](int k, const Frag& f) { lds[kSel + k * 64 + threadIdx.x] = make_uint4(f.d[0], f.d[1], f.d[2], f.d[3]); };
+        put(kSelH0, selection(c, gq, [](int gg, int e) { return k_hidden(0, gg, e); }));
+        put(kSelH1, selection(c, gq, [](int gg, int e) { return k_hidden(1, gg, e); }));
+        put(kSelO, selection(c, gq, [](int gg, int e) { return (gg == 0 && e < 4) ? e : -1; }));
+#pragma unroll
+        for (int s = 0; s < KS1; ++s) put(kSelF + s, selection(c, gq, [s](int gg, int e) { return k_input<C>(s, gg, e); }));
+    }
     if (threadIdx.x < kPairs * 16) {
         const int p = threadIdx.x / 16, i = threadIdx.x % 16;
         reinterpret_cast<int*>(lds + L::END + p * P::UNITS + P::FLAGS)[i] = i == 8 ? progress(0, W_WALK) : 0;
@@ -289,8 +304,8 @@ __global__ __launch_bounds__(2 * kPairs * 64) void bwd_ws_kernel(GridDev g, MlpD
                     gzo_l[0][0].d[2] = 0u; gzo_l[0][0].d[3] = 0u;
                 }
 
-                // ---- input-gradient chain: dZ2 = relu'(.) * (Wout^T dZo), dZ1 = relu'(.) * (W2^T dZ2),
-                //      feature gradient transposed: dF^T[sample][channel] = dZ1^T W1 ----
+                // ---- input-gradient chain: dZ2 = relu'(.) * (Wout^T dZo), dZ1 = relu'(.) * (W2^T dZ2); the
+                //      last link (the feature gradient) is left to the weights wave, which holds dZ1 anyway ----
                 f32x16 acc[MB][kBwdNB];
                 Frag gz_h[kBwdNB][KSH], gz_l[kBwdNB][KSH];
                 layer_mfma<MB, 1, kBwdNB, true>(acc, lds + L::T3, lane, gzo_h, gzo_l);
@@ -308,22 +323,6 @@ __global__ __launch_bounds__(2 * kPairs * 64) void bwd_ws_kernel(GridDev g, MlpD
                 ho.await(progress(n, W_H1));
                 store_frags<KSH>(mine + P::SLOT0, lane, gz_h, gz_l);
                 ho.post(progress(n, C_Z1));
-                f32x16 dFt;
-#pragma unroll
-                for (int s = 0; s < KSH; ++s) {
-                    Frag th, tl;
-                    load_operand(lds + L::T1 + s * 128, lane, th, tl);
-                    dFt = s == 0 ? mfma3_first(gz_h[0][s], gz_l[0][s], th, tl) : mfma3(gz_h[0][s], gz_l[0][s], th, tl, dFt);
-                }
-                ho.await(progress(n - 1, W_DFT));
-                if (col < C) {
-#pragma unroll
-                    for (int q = 0; q < 4; ++q)
-                        mine[P::DFT + (q * 2 + grp) * C + col] =
-                            make_uint4(__float_as_uint(dFt[4 * q]), __float_as_uint(dFt[4 * q + 1]),
-                                       __float_as_uint(dFt[4 * q + 2]), __float_as_uint(dFt[4 * q + 3]));
-                }
-                ho.post(progress(n, C_DFT));
                 if (more) {
                     float feat[C / 2];
                     gather_finish<KIND, C / 2, GT>(cell_next, raw_next, feat);
@@ -342,44 +341,44 @@ __global__ __launch_bounds__(2 * kPairs * 64) void bwd_ws_kernel(GridDev g, MlpD
     }
 
     // ================= weights wave =================
-    const Frag sel_h0 = selection(col, grp, [](int gg, int e) { return k_hidden(0, gg, e); });
-    const Frag sel_h1 = selection(col, grp, [](int gg, int e) { return k_hidden(1, gg, e); });
-    const Frag sel_o = selection(col, grp, [](int gg, int e) { return (gg == 0 && e < 4) ? e : -1; });
-    Frag sel_f[KS1];
-#pragma unroll
-    for (int s = 0; s < KS1; ++s)
-        sel_f[s] = selection(col, grp, [s](int gg, int e) { return k_input<C>(s, gg, e); });
+    // (read from LDS where they are used: sixteen registers less that live through the whole loop)
+    auto sel = [&](int k) {
+        const uint4 v = lds[kSel + k * 64 + lane];
+        Frag f;
+        f.d[0] = v.x; f.d[1] = v.y; f.d[2] = v.z; f.d[3] = v.w;
+        return f;
+    };
     // block nb2 (features 32 nb2 .. +31) of the hidden tensor in `slot`, transposed; the hi and the lo
-    // parts one after the other, so that one 16-register product is alive at a time
+    // parts one after the other (issuing the four products back to back measured no faster)
     auto transpose_block = [&](const uint4* slot, int nb2, Frag (&th)[kBwdKS], Frag (&tl)[kBwdKS]) {
         Frag x0h, x0l, x1h, x1l;
         load_operand(slot + (2 * nb2) * 128, lane, x0h, x0l);
         load_operand(slot + (2 * nb2 + 1) * 128, lane, x1h, x1l);
         {
-            f32x16 d = mfma1(x0h, sel_h0, zero16());
-            d = mfma1(x1h, sel_h1, d);
+            f32x16 d = mfma1(x0h, sel(kSelH0), zero16());
+            d = mfma1(x1h, sel(kSelH1), d);
             pack_exact(d, th);
         }
         __builtin_amdgcn_sched_barrier(0);
         {
-            f32x16 d = mfma1(x0l, sel_h0, zero16());
-            d = mfma1(x1l, sel_h1, d);
+            f32x16 d = mfma1(x0l, sel(kSelH0), zero16());
+            d = mfma1(x1l, sel(kSelH1), d);
             pack_exact(d, tl);
         }
         __builtin_amdgcn_sched_barrier(0);
     };
     auto transpose_features = [&](const Frag (&xh)[KS1], const Frag (&xl)[KS1], Frag (&th)[kBwdKS], Frag (&tl)[kBwdKS]) {
         {
-            f32x16 d = mfma1(xh[0], sel_f[0], zero16());
+            f32x16 d = mfma1(xh[0], sel(kSelF), zero16());
 #pragma unroll
-            for (int s = 1; s < KS1; ++s) d = mfma1(xh[s], sel_f[s], d);
+            for (int s = 1; s < KS1; ++s) d = mfma1(xh[s], sel(kSelF + s), d);
             pack_exact(d, th);
         }
         __builtin_amdgcn_sched_barrier(0);
         {
-            f32x16 d = mfma1(xl[0], sel_f[0], zero16());
+            f32x16 d = mfma1(xl[0], sel(kSelF), zero16());
 #pragma unroll
-            for (int s = 1; s < KS1; ++s) d = mfma1(xl[s], sel_f[s], d);
+            for (int s = 1; s < KS1; ++s) d = mfma1(xl[s], sel(kSelF + s), d);
             pack_exact(d, tl);
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -421,9 +420,9 @@ __global__ __launch_bounds__(2 * kPairs * 64) void bwd_ws_kernel(GridDev g, MlpD
                 gh.d[0] = grp == 0 ? zo.x : 0u; gh.d[1] = grp == 0 ? zo.y : 0u; gh.d[2] = 0u; gh.d[3] = 0u;
                 gl.d[0] = grp == 0 ? zo.z : 0u; gl.d[1] = grp == 0 ? zo.w : 0u; gl.d[2] = 0u; gl.d[3] = 0u;
                 Frag ah[kBwdKS], al[kBwdKS];
-                pack_exact(mfma1(gh, sel_o, zero16()), ah);
+                pack_exact(mfma1(gh, sel(kSelO), zero16()), ah);
                 __builtin_amdgcn_sched_barrier(0);
-                pack_exact(mfma1(gl, sel_o, zero16()), al);
+                pack_exact(mfma1(gl, sel(kSelO), zero16()), al);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int nb2 = 0; nb2 < MB; ++nb2) accumulate(dWo[nb2], ah, al, t2h[nb2], t2l[nb2]);
@@ -452,7 +451,7 @@ __global__ __launch_bounds__(2 * kPairs * 64) void bwd_ws_kernel(GridDev g, MlpD
             }
             __builtin_amdgcn_sched_barrier(0);
 
-            // ---- dW1 += dZ1 F^T ; db1 += sum dZ1 ----
+            // ---- dW1 += dZ1 F^T ; db1 += sum dZ1 ; feature gradient ----
             {
                 Frag bf_h[kBwdKS], bf_l[kBwdKS];
                 {
@@ -463,6 +462,27 @@ __global__ __launch_bounds__(2 * kPairs * 64) void bwd_ws_kernel(GridDev g, MlpD
                     transpose_features(f_h[0], f_l[0], bf_h, bf_l);
                 }
                 ho.await(progress(n, C_Z1));
+                // feature gradient, transposed: dF^T[sample][channel] = dZ1^T W1 (operands swapped: lane =
+                // channel, registers = samples 8q + 4 grp ..), K-steps in order; parked in this wave's LDS
+                // area at once, from where the walk reads it in its own order
+                {
+                    f32x16 dFt;
+#pragma unroll
+                    for (int s = 0; s < KSH; ++s) {
+                        Frag xh, xl, th, tl;
+                        load_operand(mine + P::SLOT0 + s * 128, lane, xh, xl);
+                        load_operand(lds + L::T1 + s * 128, lane, th, tl);
+                        dFt = s == 0 ? mfma3_first(xh, xl, th, tl) : mfma3(xh, xl, th, tl, dFt);
+                    }
+                    if (col < C) {
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+                            mine[P::DFT + (q * 2 + grp) * C + col] =
+                                make_uint4(__float_as_uint(dFt[4 * q]), __float_as_uint(dFt[4 * q + 1]),
+                                           __float_as_uint(dFt[4 * q + 2]), __float_as_uint(dFt[4 * q + 3]));
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb) {
                     Frag ah[kBwdKS], al[kBwdKS];
@@ -476,8 +496,8 @@ __global__ __launch_bounds__(2 * kPairs * 64) void bwd_ws_kernel(GridDev g, MlpD
             }
             __builtin_amdgcn_sched_barrier(0);
 
-            // ---- scatter of the feature gradient (lane = channel, register = sample) ----
-            ho.await(progress(n, C_DFT));
+            // ---- scatter of the feature gradient (lane = channel, register = 16 consecutive samples) ----
+            wave_lds_fence();
             f32x16 dFt;
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
@@ -485,7 +505,6 @@ __global__ __launch_bounds__(2 * kPairs * 64) void bwd_ws_kernel(GridDev g, MlpD
                 dFt[4 * qd] = __uint_as_float(v.x); dFt[4 * qd + 1] = __uint_as_float(v.y);
                 dFt[4 * qd + 2] = __uint_as_float(v.z); dFt[4 * qd + 3] = __uint_as_float(v.w);
             }
-            ho.post(progress(n, W_DFT));
             scatter_channels<KIND, C, true>(g, io.d_grid, scene, reinterpret_cast<const float*>(mine + P::REC + (n & 1) * 128),
                                       dFt, col, grp);
             ho.post(progress(n, W_WALK));
@@ -522,7 +541,7 @@ template <int KIND, int C, int H, bool CC, int GT = LP_F32>
 hipError_t launch_bwd_ws(const GridDev& g, const MlpDev& m, const RaysDev& rays, const BwdIo& io, int n_cu,
                          hipStream_t stream)
 {
-    constexpr int kLdsBytes = (MlpLds<C, H, 2, true, kBwdNB>::END + kPairs * PairLds<C, H>::UNITS) * 16;
+    constexpr int kLdsBytes = (MlpLds<C, H, 2, true, kBwdNB>::END + kPairs * PairLds<C, H>::UNITS + (3 + C / 16) * 64) * 16;
     static_assert(kLdsBytes <= 160 * 1024, "LDS budget of a gfx950 compute unit");
     auto kernel = bwd_ws_kernel<KIND, C, H, CC, GT>;
     hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);

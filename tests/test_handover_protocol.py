@@ -48,7 +48,17 @@ def _parse():
     init = re.search(r"i == 8 \? progress\(0, (\w+)\) : 0", text).group(1)
     # only the loop over the steps: from the first await of a role on
     chain = _role_ops(lines[a0:b0])
-    weights = _role_ops(lines[b0:b1])
+    shared = {o[1] for o in chain if o[0] == "touch"}
+    weights = []
+    since_post = set()   # several accesses of one buffer before the next counter update read the same item
+    for o in _role_ops(lines[b0:b1]):
+        if o[0] == "post":
+            since_post = set()
+        if o[0] == "touch":
+            if o[1] not in shared or o[1] in since_post:
+                continue
+            since_post.add(o[1])
+        weights.append(o)
     first = lambda ops: next(i for i, o in enumerate(ops) if o[0] == "await")
     return chain[first(chain):], weights[first(weights):], chain_stages, weights_stages, init
 
@@ -89,10 +99,11 @@ def test_source_declares_the_expected_protocol():
         posted = [o[1] for o in ops if o[0] == "post"]
         assert posted == stages
     # the chain wave only writes the shared buffers, the weights wave only reads them, and every item
-    # written in a step is read in that step
+    # written in a step is read in that step (a buffer the chain wave never touches is the weights
+    # wave's own)
     written = [o[1] for o in chain if o[0] == "touch"]
-    read = [o[1] for o in weights if o[0] == "touch"]
-    assert sorted(written) == sorted(read) and set(written) == set(BUFFERS)
+    read = [o[1] for o in weights if o[0] == "touch" and o[1] in set(written)]
+    assert sorted(written) == sorted(read) and {"SLOT0", "SLOT1", "F", "ZO", "REC"} <= set(written)
     assert init == ws[-1]
 
 
