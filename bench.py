@@ -39,7 +39,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # HBM bytes per launch of the backward kernel from two rocprofv3 --pmc runs (FETCH_SIZE scaled
 # by 2.0, WRITE_SIZE by 1.0 against a 1 GiB copy kernel in the same run); the summary with the
 # commands is profiles/large_voxel256_fwd_bwd_kernels.md.  None = not measured for that workload.
-MEASURED_BWD_HBM_BYTES = {"large": 12.06e9 + 65.42e9}
+MEASURED_BWD_HBM_BYTES = {"large": 19.51e9 + 65.42e9}
 
 
 def parse():
