@@ -64,6 +64,10 @@ def parse():
     ap.add_argument("--coexecution", action="store_true",
                     help="instead of the benchmark: time how one SIMD overlaps matrix and vector instructions "
                          "(one JSON line)")
+    ap.add_argument("--ws-phases", action="store_true",
+                    help="with a measurement build of the library (LP_EXTRA_HIPCC_FLAGS=-DLP_WS_PHASES python "
+                         "paper_2404_19760_amd/build.py): after the run, print where the two roles of the two-wave "
+                         "backward spend their cycles (a second JSON line)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy kernel (reference for HBM counters)")
     return ap.parse_args()
@@ -341,6 +345,26 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(inp, args.cpu_seconds)
     print(json.dumps(out))
+    if args.ws_phases:
+        try:
+            cyc = lp.lp_diag_ws_phases()
+        except lp.LightplaneError:
+            print("bench.py: --ws-phases needs a measurement build: LP_EXTRA_HIPCC_FLAGS=-DLP_WS_PHASES python "
+                  "paper_2404_19760_amd/build.py", file=sys.stderr)
+            sys.exit(2)
+        chain = ["step start", "sampling issue", "forward", "hand-over h1 h2", "Eq. (2)", "hand-over output gradients",
+                 "chain link 1 (dZ2)", "hand-over dZ2", "chain link 2 (dZ1)", "hand-over features, records, dZ1",
+                 "interpolation of the next features"]
+        weights = ["step start", "h2 taken + transposed", "wait for output gradients", "dWo", "h1 transposed", "wait for dZ2",
+                   "dW2", "features taken + transposed", "wait for dZ1", "feature gradient + dW1", "walk"]
+        def shares(names, vals):
+            tot = max(sum(vals), 1)
+            return {n: round(c / tot, 4) for n, c in zip(names, vals)}
+        print(json.dumps({"two_wave_backward_phase_shares": {"chain_wave": shares(chain, cyc[:11]),
+                                                              "weights_wave": shares(weights, cyc[16:27])},
+                          "note": "shares of the cycles between marks, summed over all waves and all launches of this "
+                                  "run; waits for the partner are inside the hand-over / wait phases"}))
+
 
 
 if __name__ == "__main__":

@@ -284,6 +284,17 @@ lp_status lp_splat_bwd_workspace_bytes(const lp_grid* target, const lp_rays* ray
    Allocates and frees a small device buffer; synchronises the stream. */
 lp_status lp_diag_coexecution(float* ns_per_iteration, void* stream);
 
+/* Diagnostics of a MEASUREMENT build (the library compiled with -DLP_WS_PHASES; an ordinary build
+   returns LP_ERR_UNSUPPORTED): cycles the two roles of the two-wave backward have spent in the
+   phases of their steps since the last call, summed over all waves.  cycles (host, 32 values):
+   [0..10] chain wave (step start, sampling issue, forward, hand-over of h1 and h2, Eq. (2), hand-over
+   of the output gradients, first link of the input-gradient chain, hand-over of dZ2, second link,
+   hand-over of the features, records and dZ1, interpolation of the next step's features),
+   [16..26] weights wave (step start, h2 taken and transposed, wait for the output gradients, dWo, h1
+   transposed, wait for dZ2, dW2, features taken and transposed, wait for dZ1, feature gradient and
+   dW1, walk).  The sums are cleared by the call. */
+lp_status lp_diag_ws_phases(unsigned long long* cycles);
+
 /* Message of the last failure on this thread ("" if none).  Owned by the library. */
 const char* lp_last_error(void);
 

@@ -72,6 +72,8 @@ def _load() -> C.CDLL:
     lib.lp_version.restype = C.c_int32
     lib.lp_diag_coexecution.restype = C.c_int
     lib.lp_diag_coexecution.argtypes = [C.POINTER(C.c_float), C.c_void_p]
+    lib.lp_diag_ws_phases.restype = C.c_int
+    lib.lp_diag_ws_phases.argtypes = [C.POINTER(C.c_ulonglong)]
     lib.lp_has_fast_path.restype = C.c_int32
     lib.lp_has_fast_path.argtypes = [C.POINTER(_Grid), C.POINTER(_Mlp)]
     lib.lp_render_fwd.restype = C.c_int
@@ -282,6 +284,13 @@ def lp_diag_coexecution(stream=None):
     out = (C.c_float * 10)()
     _check(_lib.lp_diag_coexecution(out, _stream_ptr(stream)))
     return [float(v) for v in out]
+
+
+def lp_diag_ws_phases():
+    """Cycle sums per phase of the two-wave backward (measurement builds only; see the header)."""
+    out = (C.c_ulonglong * 32)()
+    _check(_lib.lp_diag_ws_phases(out))
+    return [int(v) for v in out]
 
 
 def lp_has_fast_path(grid: Grid, mlp: Mlp) -> bool:

@@ -54,6 +54,31 @@ namespace lp {
 namespace {
 
 constexpr int kPairs = 4;             // (chain, weights) wave pairs per workgroup
+
+// Measurement build (-DLP_WS_PHASES): both roles add up the cycles they spend between the marks
+// LP_PHASE(k) of a step (s_memtime; each mark is also a scheduling barrier, so such a build is a
+// few per cent slower), lp_diag_ws_phases() reads the sums.  Off by default: the marks are empty.
+#ifdef LP_WS_PHASES
+__device__ unsigned long long g_ws_phase_cycles[2][16];
+#define LP_PHASE_STATE long long ph[16] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}; long long ph_prev = clock64();
+#define LP_PHASE(k)                                             \
+    do {                                                        \
+        __builtin_amdgcn_sched_barrier(0);                      \
+        const long long ph_now = clock64();                     \
+        ph[k] += ph_now - ph_prev;                              \
+        ph_prev = ph_now;                                       \
+        __builtin_amdgcn_sched_barrier(0);                      \
+    } while (0)
+#define LP_PHASE_FLUSH(role)                                                                            \
+    do {                                                                                                \
+        if (lane == 0)                                                                                  \
+            for (int k = 0; k < 16; ++k) atomicAdd(&g_ws_phase_cycles[role][k], (unsigned long long)ph[k]); \
+    } while (0)
+#else
+#define LP_PHASE_STATE
+#define LP_PHASE(k)
+#define LP_PHASE_FLUSH(role)
+#endif
 constexpr int kSpinLimit = 1 << 20;   // polls of one wait before the wave gives up (normal: a handful)
 
 // LDS area of one pair in 16-byte units.
@@ -203,6 +228,7 @@ __global__ __launch_bounds__(2 * kPairs * 64) void bwd_ws_kernel(GridDev g, MlpD
     cur.init(rays.M, pair, group_mul, group_step);
     int n = 0;  // number of the current step of this pair
 
+    LP_PHASE_STATE
     if (chain) {
         // ================= chain wave =================
         float dbo[4] = {0.0f, 0.0f, 0.0f, 0.0f};
@@ -234,6 +260,7 @@ __global__ __launch_bounds__(2 * kPairs * 64) void bwd_ws_kernel(GridDev g, MlpD
 
             for (int j0 = j_last; j0 >= 0; j0 -= kBwdStep) {
                 ++n;
+                LP_PHASE(0);
                 // the next step's cell and texel loads
                 const bool same = j0 > 0;
                 const bool more = same || cur.live();
@@ -250,10 +277,12 @@ __global__ __launch_bounds__(2 * kPairs * 64) void bwd_ws_kernel(GridDev g, MlpD
                 if (grp == 0)
                     write_scatter_record<KIND, C>(reinterpret_cast<float*>(mine + P::REC + (n & 1) * 128) + col * 16, g, cell);
 
+                LP_PHASE(1);
                 StepActs<C, H, NH, kBwdNB> a;
 #pragma unroll
                 for (int s = 0; s < KS1; ++s) { a.fh[0][s] = fh[s]; a.fl[0][s] = fl[s]; }
                 mlp_forward<C, H, NH, true, kBwdNB>(lds, lane, a);
+                LP_PHASE(2);
                 ho.await(progress(n - 1, W_Z1));
                 store_frags<KSH>(mine + P::SLOT0, lane, a.h1h, a.h1l);
                 ho.post(progress(n, C_H1));
@@ -261,6 +290,7 @@ __global__ __launch_bounds__(2 * kPairs * 64) void bwd_ws_kernel(GridDev g, MlpD
                 store_frags<KSH>(mine + P::SLOT1, lane, a.h2h, a.h2l);
                 ho.post(progress(n, C_H2));
 
+                LP_PHASE(3);
                 // ---- emission-absorption backward; MFMA column col stands for sample j0 + col (both lane
                 //      groups alike): the scans along the ray run over the 32 lanes of a group ----
                 const int j = j0 + col;
@@ -289,6 +319,7 @@ __global__ __launch_bounds__(2 * kPairs * 64) void bwd_ws_kernel(GridDev g, MlpD
 #pragma unroll
                 for (int k = 0; k < 4; ++k) dbo[k] += grp == 0 ? dz[k] : 0.0f;
 
+                LP_PHASE(4);
                 uint32_t zh0, zl0, zh1, zl1;
                 split2(dz[0], dz[1], zh0, zl0);
                 split2(dz[2], dz[3], zh1, zl1);
@@ -304,6 +335,7 @@ __global__ __launch_bounds__(2 * kPairs * 64) void bwd_ws_kernel(GridDev g, MlpD
                     gzo_l[0][0].d[2] = 0u; gzo_l[0][0].d[3] = 0u;
                 }
 
+                LP_PHASE(5);
                 // ---- input-gradient chain: dZ2 = relu'(.) * (Wout^T dZo), dZ1 = relu'(.) * (W2^T dZ2); the
                 //      last link (the feature gradient) is left to the weights wave, which holds dZ1 anyway ----
                 f32x16 acc[MB][kBwdNB];
@@ -311,18 +343,22 @@ __global__ __launch_bounds__(2 * kPairs * 64) void bwd_ws_kernel(GridDev g, MlpD
                 layer_mfma<MB, 1, kBwdNB, true>(acc, lds + L::T3, lane, gzo_h, gzo_l);
                 relu_mask<MB>(acc, a.h2h);
                 to_operands<MB, false, kBwdNB>(acc, gz_h, gz_l);
+                LP_PHASE(6);
                 ho.await(progress(n, W_H2));
                 store_frags<KSH>(mine + P::SLOT1, lane, gz_h, gz_l);
                 ho.post(progress(n, C_Z2));
+                LP_PHASE(7);
                 layer_mfma<MB, KSH, kBwdNB, true>(acc, lds + L::T2, lane, gz_h, gz_l);
                 relu_mask<MB>(acc, a.h1h);
                 to_operands<MB, false, kBwdNB>(acc, gz_h, gz_l);
+                LP_PHASE(8);
                 ho.await(progress(n - 1, W_F));
                 store_frags<KS1>(mine + P::F, lane, a.fh, a.fl);
                 ho.post(progress(n, C_F));
                 ho.await(progress(n, W_H1));
                 store_frags<KSH>(mine + P::SLOT0, lane, gz_h, gz_l);
                 ho.post(progress(n, C_Z1));
+                LP_PHASE(9);
                 if (more) {
                     float feat[C / 2];
                     gather_finish<KIND, C / 2, GT>(cell_next, raw_next, feat);
@@ -330,6 +366,7 @@ __global__ __launch_bounds__(2 * kPairs * 64) void bwd_ws_kernel(GridDev g, MlpD
                     for (int s = 0; s < KS1; ++s) split8(feat + 8 * s, fh[s], fl[s]);
                     cell = cell_next;
                 }
+                LP_PHASE(10);
             }
         }
 #pragma unroll
@@ -337,6 +374,7 @@ __global__ __launch_bounds__(2 * kPairs * 64) void bwd_ws_kernel(GridDev g, MlpD
             const float s = wave_sum(dbo[k]);
             if (lane == 0) rec[m.b_off[NH] + k] = s;
         }
+        LP_PHASE_FLUSH(0);
         return;
     }
 
@@ -406,14 +444,17 @@ __global__ __launch_bounds__(2 * kPairs * 64) void bwd_ws_kernel(GridDev g, MlpD
         cur.advance();
         for (int j0 = j_last; j0 >= 0; j0 -= kBwdStep) {
             ++n;
+            LP_PHASE(0);
             // ---- dWo += dZo H2^T ----
             {
                 Frag t2h[MB][kBwdKS], t2l[MB][kBwdKS];
                 ho.await(progress(n, C_H2));
 #pragma unroll
                 for (int nb2 = 0; nb2 < MB; ++nb2) transpose_block(mine + P::SLOT1, nb2, t2h[nb2], t2l[nb2]);
+            LP_PHASE(1);
                 ho.post(progress(n, W_H2));
                 ho.await(progress(n, C_ZO));
+            LP_PHASE(2);
                 const uint4 zo = mine[P::ZO + col];
                 ho.post(progress(n, W_ZO));
                 Frag gh, gl;
@@ -429,14 +470,17 @@ __global__ __launch_bounds__(2 * kPairs * 64) void bwd_ws_kernel(GridDev g, MlpD
             }
             __builtin_amdgcn_sched_barrier(0);
 
+            LP_PHASE(3);
             // ---- dW2 += dZ2 H1^T ; db2 += sum dZ2 ----
             {
                 Frag t1h[MB][kBwdKS], t1l[MB][kBwdKS];
                 ho.await(progress(n, C_H1));
 #pragma unroll
                 for (int nb2 = 0; nb2 < MB; ++nb2) transpose_block(mine + P::SLOT0, nb2, t1h[nb2], t1l[nb2]);
+            LP_PHASE(4);
                 ho.post(progress(n, W_H1));
                 ho.await(progress(n, C_Z2));
+            LP_PHASE(5);
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb) {
                     Frag ah[kBwdKS], al[kBwdKS];
@@ -451,6 +495,7 @@ __global__ __launch_bounds__(2 * kPairs * 64) void bwd_ws_kernel(GridDev g, MlpD
             }
             __builtin_amdgcn_sched_barrier(0);
 
+            LP_PHASE(6);
             // ---- dW1 += dZ1 F^T ; db1 += sum dZ1 ; feature gradient ----
             {
                 Frag bf_h[kBwdKS], bf_l[kBwdKS];
@@ -461,7 +506,9 @@ __global__ __launch_bounds__(2 * kPairs * 64) void bwd_ws_kernel(GridDev g, MlpD
                     ho.post(progress(n, W_F));
                     transpose_features(f_h[0], f_l[0], bf_h, bf_l);
                 }
+            LP_PHASE(7);
                 ho.await(progress(n, C_Z1));
+            LP_PHASE(8);
                 // feature gradient, transposed: dF^T[sample][channel] = dZ1^T W1 (operands swapped: lane =
                 // channel, registers = samples 8q + 4 grp ..), K-steps in order; parked in this wave's LDS
                 // area at once, from where the walk reads it in its own order
@@ -496,6 +543,7 @@ __global__ __launch_bounds__(2 * kPairs * 64) void bwd_ws_kernel(GridDev g, MlpD
             }
             __builtin_amdgcn_sched_barrier(0);
 
+            LP_PHASE(9);
             // ---- scatter of the feature gradient (lane = channel, register = 16 consecutive samples) ----
             wave_lds_fence();
             f32x16 dFt;
@@ -508,10 +556,12 @@ __global__ __launch_bounds__(2 * kPairs * 64) void bwd_ws_kernel(GridDev g, MlpD
             scatter_channels<KIND, C, true>(g, io.d_grid, scene, reinterpret_cast<const float*>(mine + P::REC + (n & 1) * 128),
                                       dFt, col, grp);
             ho.post(progress(n, W_WALK));
+            LP_PHASE(10);
             __builtin_amdgcn_sched_barrier(0);
         }
     }
 
+    LP_PHASE_FLUSH(1);
     // ---- this pair's record of partial sums (the chain wave adds the output layer's bias gradient) ----
     const float poison = ho.dead ? __builtin_nanf("") : 0.0f;
 #pragma unroll

@@ -26,3 +26,17 @@ hipError_t launch_bwd_mfma_ws(const GridDev& g, const MlpDev& m, const RaysDev& 
 }
 
 }  // namespace lp
+
+extern "C" lp_status lp_diag_ws_phases(unsigned long long* cycles)
+{
+    if (!cycles) return LP_ERR_INVALID_ARG;
+#ifdef LP_WS_PHASES
+    if (hipMemcpyFromSymbol(cycles, HIP_SYMBOL(lp::g_ws_phase_cycles), sizeof(unsigned long long) * 32) != hipSuccess)
+        return LP_ERR_HIP;
+    static const unsigned long long zeros[32] = {};
+    if (hipMemcpyToSymbol(HIP_SYMBOL(lp::g_ws_phase_cycles), zeros, sizeof(zeros)) != hipSuccess) return LP_ERR_HIP;
+    return LP_OK;
+#else
+    return LP_ERR_UNSUPPORTED;
+#endif
+}
