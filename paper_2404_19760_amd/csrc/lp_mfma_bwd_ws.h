@@ -14,7 +14,7 @@
 //                 layer -> split into bf16 operands -> layer.  It holds no accumulators and issues no
 //                 atomic adds, so its loads never queue behind them.
 //   weights wave  transposes the activations and pre-activation gradients the chain wave hands over
-//                 (0/1 selection products, their operands kept in LDS), accumulates dW += dZ X^T and
+//                 (0/1 selection products), accumulates dW += dZ X^T and
 //                 db, takes the chain's last link (feature gradient dF = W1^T dZ1: matrix
 //                 instructions only, and this wave's matrix work is hidden under the chain wave's
 //                 vector work) and scatters it into the grid gradient (run-merged atomic adds).
@@ -92,7 +92,7 @@ struct PairLds {
     static constexpr int ZO = F + KS1 * 128;               // output gradients of sample column c: (hi01, hi23, lo01, lo23)
     static constexpr int DFT = ZO + 32;                    // (weights wave only) feature gradient: [8 quads of samples][C channels] x 4 samples
     static constexpr int REC = DFT + 4 * 2 * C;            // two buffers of 32 scatter records (16 dwords each)
-    static constexpr int FLAGS = REC + 2 * 128;
+    static constexpr int FLAGS = REC + 2 * 128;            // the two progress counters, 32 bytes apart
     static constexpr int UNITS = FLAGS + 4;
 };
 
@@ -273,7 +273,7 @@ __global__ __launch_bounds__(2 * kPairs * 64) void bwd_ws_kernel(GridDev g, MlpD
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 // scatter records of this step's samples, for the walk of the weights wave
-                ho.await(progress(n - 2, W_WALK));
+                ho.await(progress(n - 2, W_WALK));   // (implied by the slots' waits today; kept so that the record buffers do not rest on that)
                 if (grp == 0)
                     write_scatter_record<KIND, C>(reinterpret_cast<float*>(mine + P::REC + (n & 1) * 128) + col * 16, g, cell);
 
