@@ -81,6 +81,31 @@ def test_triplane_16_channels_with_many_rays(lp, oracle, dims):
     print(summary(worst), flush=True)
 
 
+@pytest.mark.parametrize("dtype", ["float32", "bfloat16"])
+def test_two_wave_backward_with_contract_coordinates_and_many_rays(lp, oracle, dtype):
+    """The two-wave backward's other instantiations (contract coordinates compiled in for fp32 grids, a
+    run-time branch for grids stored in bf16) with several rays per pair of waves: a 16-channel voxel
+    grid, MLP 16-64-64-4, a block of 6 400 neighbouring rays that start inside the unit cube."""
+    import dataclasses
+    import torch
+    w = lp_inputs.WORKLOADS["single_scene"]
+    rays = lp_inputs.make_inputs("single_scene", with_grid=False)
+    small = lp_inputs.make_small(VOXEL, channels=16, res=(48, 40, 44), mlp_dims=(16, 64, 64, 4), n_rays=8, samples=96,
+                                 seed=137, grid_std=0.3)
+    idx = _pixel_block(w.image, 24, 104)
+    inp = dataclasses.replace(small, origins=np.ascontiguousarray(rays.origins[idx] * 0.3),
+                              dirs=np.ascontiguousarray(rays.dirs[idx]), near=np.ascontiguousarray(rays.near[idx] * 0.0),
+                              far=np.ascontiguousarray(rays.far[idx] * 3.0), scene=None,
+                              target=np.ascontiguousarray(rays.target[idx]), contract_a=1.3)
+    tdt = getattr(torch, dtype)
+    if dtype != "float32":
+        stored = [torch.from_numpy(g).to(tdt) for g in inp.grid]
+        inp = dataclasses.replace(inp, grid=[t.to(torch.float32).numpy() for t in stored])
+    worst = check_case(lp, oracle, inp, lp.LP_MATH_BF16X3, label=f"two-wave contract {dtype}",
+                       grid_dtype=None if dtype == "float32" else tdt)
+    print(summary(worst), flush=True)
+
+
 def test_contract_workload_with_many_rays(lp, oracle):
     """The paper's experimental Renderer shape with contract coordinates: every second ray of the
     256^2 image (32 768 rays x 384 samples, 160^3 x 32 voxels)."""
