@@ -39,7 +39,7 @@ typedef enum {
     LP_ERR_WORKSPACE = 4    /* workspace missing or smaller than lp_bwd_workspace_bytes     */
 } lp_status;
 
-typedef enum { LP_GRID_VOXEL = 0, LP_GRID_TRIPLANE = 1 } lp_grid_kind;
+typedef enum { LP_GRID_VOXEL = 0, LP_GRID_TRIPLANE = 1, LP_GRID_HASH = 2 } lp_grid_kind;
 
 /* Storage type of the values of a hash structure that is READ (Section 3.2 notes that the
    hashing scheme is where precision and layout can be traded).  Gradients and the Splatter's
@@ -52,6 +52,14 @@ typedef enum { LP_F32 = 0, LP_BF16 = 1, LP_F16 = 2 } lp_dtype;
  *   triplane: data[0] = [B][NX][NY][C], data[1] = [B][NY][NZ][C], data[2] = [B][NZ][NX][C];
  *             a point (x,y,z) reads plane 0 at (x,y), plane 1 at (y,z), plane 2 at (z,x)
  *             bilinearly and SUMS the three feature vectors.
+ *   hash    : data[0] = [B][hash_size][C], a hash table (Section 3.2 names hash tables among the
+ *             structures; the paper defines none, this one is the single-resolution spatial hash
+ *             of Teschner et al. 2003 that Instant-NGP uses): the point is interpolated
+ *             trilinearly in a virtual NX x NY x NZ lattice as in a voxel grid, but lattice corner
+ *             (ix, iy, iz) is stored in entry ((ix * 1) xor (iy * 2654435761) xor (iz * 805459861))
+ *             mod hash_size (products and xor in 32-bit unsigned arithmetic); corners that collide
+ *             share the entry and their gradients add.  Renderer only (the Splatter refuses it);
+ *             served by the generic kernels.
  * World coordinate aabb_min[a] maps to index 0 and aabb_max[a] to index N_a - 1 along axis
  * a; positions outside the box are clamped onto it.  B scenes share the MLP.
  * contract_a: 0 = off.  In (0, 2]: contract coordinates (appendix, "Experimental Details",
@@ -69,6 +77,7 @@ typedef struct {
     float aabb_min[3], aabb_max[3];
     float contract_a;
     int32_t dtype; /* lp_dtype; LP_BF16 / LP_F16 halve the bytes a sample reads */
+    int64_t hash_size; /* LP_GRID_HASH: entries of one scene's table, in [1, 2^31); else ignored */
 } lp_grid;
 
 /*

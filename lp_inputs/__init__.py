@@ -21,6 +21,7 @@ import numpy as np
 
 VOXEL = 0
 TRIPLANE = 1
+HASH = 2        # hash table: one [B][T][C] tensor; res is the virtual lattice whose corners are hashed into it
 
 
 @dataclasses.dataclass(frozen=True)
@@ -179,7 +180,7 @@ class Inputs:
     n_scenes: int
     channels: int
     res: Tuple[int, int, int]
-    grid: List[np.ndarray]            # 1 (voxel) or 3 (triplane) float32 arrays
+    grid: List[np.ndarray]            # 1 (voxel, hash table) or 3 (triplane) float32 arrays
     aabb_min: Tuple[float, float, float]
     aabb_max: Tuple[float, float, float]
     mlp_dims: Tuple[int, ...]
@@ -200,6 +201,11 @@ class Inputs:
     def n_rays(self) -> int:
         return int(self.origins.shape[0])
 
+    @property
+    def hash_size(self) -> int:
+        """Entries per scene of a hash table (kind HASH), else 0."""
+        return int(self.grid[0].shape[1]) if self.kind == HASH else 0
+
     def subset(self, idx: np.ndarray) -> "Inputs":
         """The same scene with only rays `idx` (rays are independent units)."""
         idx = np.asarray(idx)
@@ -214,17 +220,20 @@ class Inputs:
         )
 
 
-def grid_shapes(kind: int, n_scenes: int, res, channels: int):
+def grid_shapes(kind: int, n_scenes: int, res, channels: int, hash_size: Optional[int] = None):
     nx, ny, nz = res
     if kind == VOXEL:
         return [(n_scenes, nx, ny, nz, channels)]
+    if kind == HASH:
+        assert hash_size is not None and hash_size >= 1
+        return [(n_scenes, int(hash_size), channels)]
     return [(n_scenes, nx, ny, channels), (n_scenes, ny, nz, channels),
             (n_scenes, nz, nx, channels)]
 
 
-def make_grid(kind, n_scenes, res, channels, std, seed) -> List[np.ndarray]:
+def make_grid(kind, n_scenes, res, channels, std, seed, hash_size=None) -> List[np.ndarray]:
     out = []
-    shapes = grid_shapes(kind, n_scenes, res, channels)
+    shapes = grid_shapes(kind, n_scenes, res, channels, hash_size)
     per_scene = [np.empty(s, dtype=np.float32) for s in shapes]
     for b in range(n_scenes):
         rng = np.random.default_rng(seed + 10 * b)
@@ -297,12 +306,12 @@ def make_small(kind: int, *, n_scenes=1, channels=4, res=(5, 4, 6), mlp_dims=(4,
                n_rays=6, samples=7, seed=0, grid_std=0.5, bias_std=0.3,
                aabb_min=(-1.0, -1.0, -1.0), aabb_max=(1.0, 1.0, 1.0),
                near=(0.3, 0.9), far=(2.2, 3.7), origin_radius=2.0,
-               bg=(0.9, 0.5, 0.2)) -> Inputs:
+               bg=(0.9, 0.5, 0.2), hash_size=None) -> Inputs:
     """A small random problem for pins and edge cases: rays from random points on a
     sphere towards random points near the origin, per-ray near/far, non-cubic grid,
     non-zero biases, coloured background."""
     rng = np.random.default_rng(seed)
-    grid = make_grid(kind, n_scenes, res, channels, grid_std, seed + 1)
+    grid = make_grid(kind, n_scenes, res, channels, grid_std, seed + 1, hash_size)
     ws, bs = make_mlp(mlp_dims, seed + 2, bias_std=bias_std)
     p = rng.standard_normal((n_rays, 3))
     p /= np.linalg.norm(p, axis=1, keepdims=True)

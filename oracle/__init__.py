@@ -37,7 +37,7 @@ class _Grid(C.Structure):
                 ("NX", C.c_int32), ("NY", C.c_int32), ("NZ", C.c_int32),
                 ("data", C.c_void_p * 3),
                 ("aabb_min", C.c_double * 3), ("aabb_max", C.c_double * 3),
-                ("contract_a", C.c_double)]
+                ("contract_a", C.c_double), ("hash_size", C.c_int64)]
 
 
 class _Mlp(C.Structure):
@@ -68,6 +68,13 @@ def _load():
         _lib.lpo_render2_bwd.restype = C.c_int
         _lib.lpo_dir_encode.restype = C.c_int
     return _lib
+
+
+def hash_slot(ix: int, iy: int, iz: int, hash_size: int) -> int:
+    """Entry of lattice corner (ix, iy, iz) in a hash table of `hash_size` entries."""
+    lib = _load()
+    lib.lpo_hash_slot.restype = C.c_int64
+    return int(lib.lpo_hash_slot(C.c_int32(ix), C.c_int32(iy), C.c_int32(iz), C.c_int64(hash_size)))
 
 
 def num_threads() -> int:
@@ -104,6 +111,7 @@ class Problem:
             g.aabb_max[a] = float(inp.aabb_max[a])
         # the library takes the scale as float32; widen that value exactly
         g.contract_a = float(np.float32(getattr(inp, "contract_a", 0.0)))
+        g.hash_size = int(self.grid[0].shape[1]) if inp.kind == 2 else 0   # hash table [B][T][C]
         self.c_grid = g
 
         m = _Mlp()

@@ -41,6 +41,7 @@
 
 #define LPO_VOXEL 0
 #define LPO_TRIPLANE 1
+#define LPO_HASH 2
 #define LPO_MAX_LAYERS 8
 
 typedef struct {
@@ -48,6 +49,7 @@ typedef struct {
     const double* data[3];
     double aabb_min[3], aabb_max[3];
     double contract_a; /* 0: no contraction; else the foreground scale a of CC */
+    int64_t hash_size; /* LPO_HASH: entries T of the table of one scene, data[0] = [B][T][C] */
 } lpo_grid;
 
 typedef struct {
@@ -124,6 +126,17 @@ static void plane_scatter(double* P, int NB, int C, int ia, int ib, double fa, d
         }
 }
 
+/* Hash-table structure (Section 3.2 names hash tables among the structures h; the paper gives no
+   definition, this is the single-resolution spatial hash of Teschner et al. 2003 as Instant-NGP
+   uses it): lattice corner (ix, iy, iz) of the virtual NX x NY x NZ grid lives in entry
+   ((ix * 1) xor (iy * 2654435761) xor (iz * 805459861)) mod T, products and xor in 32-bit unsigned
+   arithmetic; corners that collide share the entry. */
+int64_t lpo_hash_slot(int32_t ix, int32_t iy, int32_t iz, int64_t T)
+{
+    const uint32_t h = ((uint32_t)ix * 1u) ^ ((uint32_t)iy * 2654435761u) ^ ((uint32_t)iz * 805459861u);
+    return (int64_t)((uint64_t)h % (uint64_t)T);
+}
+
 /* h(x): feature of world point x in scene b */
 static void grid_gather(const lpo_grid* g, int b, const double x[3], double* feat)
 {
@@ -143,6 +156,17 @@ static void grid_gather(const lpo_grid* g, int b, const double x[3], double* fea
                                (dz ? f[2] : 1.0 - f[2]);
                     const double* v =
                         V + (((int64_t)(i[0] + dx) * g->NY + (i[1] + dy)) * g->NZ + (i[2] + dz)) * C;
+                    for (int k = 0; k < C; ++k) feat[k] += w * v[k];
+                }
+    } else if (g->kind == LPO_HASH) {
+        /* trilinear over the 8 lattice corners of the cell, each read from its table entry */
+        const double* V = g->data[0] + (int64_t)b * g->hash_size * C;
+        for (int dx = 0; dx < 2; ++dx)
+            for (int dy = 0; dy < 2; ++dy)
+                for (int dz = 0; dz < 2; ++dz) {
+                    double w = (dx ? f[0] : 1.0 - f[0]) * (dy ? f[1] : 1.0 - f[1]) *
+                               (dz ? f[2] : 1.0 - f[2]);
+                    const double* v = V + lpo_hash_slot(i[0] + dx, i[1] + dy, i[2] + dz, g->hash_size) * C;
                     for (int k = 0; k < C; ++k) feat[k] += w * v[k];
                 }
     } else {
@@ -172,6 +196,20 @@ static void grid_scatter(const lpo_grid* g, double* const d_grid[3], int b, cons
                                (dz ? f[2] : 1.0 - f[2]);
                     double* v =
                         V + (((int64_t)(i[0] + dx) * g->NY + (i[1] + dy)) * g->NZ + (i[2] + dz)) * C;
+                    for (int k = 0; k < C; ++k) {
+                        double add = w * dfeat[k];
+#pragma omp atomic
+                        v[k] += add;
+                    }
+                }
+    } else if (g->kind == LPO_HASH) {
+        double* V = d_grid[0] + (int64_t)b * g->hash_size * C;
+        for (int dx = 0; dx < 2; ++dx)
+            for (int dy = 0; dy < 2; ++dy)
+                for (int dz = 0; dz < 2; ++dz) {
+                    double w = (dx ? f[0] : 1.0 - f[0]) * (dy ? f[1] : 1.0 - f[1]) *
+                               (dz ? f[2] : 1.0 - f[2]);
+                    double* v = V + lpo_hash_slot(i[0] + dx, i[1] + dy, i[2] + dz, g->hash_size) * C;
                     for (int k = 0; k < C; ++k) {
                         double add = w * dfeat[k];
 #pragma omp atomic
@@ -604,6 +642,7 @@ int lpo_ray_trace(const lpo_grid* g, const lpo_mlp* m, const lpo_rays* rays, con
         /* throw-away gradient buffers */
         int64_t gsz[3] = {0, 0, 0};
         if (g->kind == LPO_VOXEL) gsz[0] = (int64_t)g->B * g->NX * g->NY * g->NZ * C;
+        else if (g->kind == LPO_HASH) gsz[0] = (int64_t)g->B * g->hash_size * C;
         else {
             gsz[0] = (int64_t)g->B * g->NX * g->NY * C;
             gsz[1] = (int64_t)g->B * g->NY * g->NZ * C;
@@ -1043,6 +1082,7 @@ typedef struct {
 static int64_t grid_elems(const lpo_grid* g, int p)
 {
     if (g->kind == LPO_VOXEL) return p == 0 ? (int64_t)g->B * g->NX * g->NY * g->NZ : 0;
+    if (g->kind == LPO_HASH) return p == 0 ? (int64_t)g->B * g->hash_size : 0;
     const int64_t n[3] = {(int64_t)g->NX * g->NY, (int64_t)g->NY * g->NZ, (int64_t)g->NZ * g->NX};
     return (int64_t)g->B * n[p];
 }
@@ -1054,6 +1094,7 @@ static int splat_check(const lpo_grid* tgt, const lpo_rays* rays, const lpo_spla
     if (rays->M < 0 || rays->S < 1 || sp->n_in < 1 || sp->n_freq < -1) return 1;
     const int E = sp->n_freq < 0 ? 0 : 3 + 6 * sp->n_freq;
     const int Cp = sp->prior ? sp->prior->C : 0;
+    if (tgt->kind == LPO_HASH) return 1; /* the Splatter writes voxel grids and triplanes */
     if (sp->prior && (sp->prior->kind != tgt->kind || sp->prior->B != tgt->B)) return 1;
     if (!sp->mlp) return (sp->n_in != tgt->C || sp->prior || E) ? 1 : 0;
     if (sp->mlp->n_layers < 1 || sp->mlp->n_layers > LPO_MAX_LAYERS) return 1;

@@ -22,7 +22,7 @@ LIB_PATH = os.environ.get("LP_LIB_PATH", os.path.join(_HERE, "liblightplane.so")
 
 LP_MAX_LAYERS = 8
 LP_OK, LP_ERR_INVALID_ARG, LP_ERR_UNSUPPORTED, LP_ERR_HIP, LP_ERR_WORKSPACE = range(5)
-LP_GRID_VOXEL, LP_GRID_TRIPLANE = 0, 1
+LP_GRID_VOXEL, LP_GRID_TRIPLANE, LP_GRID_HASH = 0, 1, 2
 LP_MATH_DEFAULT, LP_MATH_GENERIC, LP_MATH_BF16X3 = 0, 1, 2
 LP_FEAT_SIGMOID, LP_FEAT_IDENTITY = 0, 1
 LP_F32, LP_BF16, LP_F16 = 0, 1, 2
@@ -39,7 +39,7 @@ class _Grid(C.Structure):
                 ("NX", C.c_int32), ("NY", C.c_int32), ("NZ", C.c_int32),
                 ("data", C.c_void_p * 3),
                 ("aabb_min", C.c_float * 3), ("aabb_max", C.c_float * 3), ("contract_a", C.c_float),
-                ("dtype", C.c_int32)]
+                ("dtype", C.c_int32), ("hash_size", C.c_int64)]
 
 
 class _Mlp(C.Structure):
@@ -147,9 +147,9 @@ _GRID_DTYPES = {torch.float32: LP_F32, torch.bfloat16: LP_BF16, torch.float16: L
 
 @dataclasses.dataclass
 class Grid:
-    """Voxel grid [B][NX][NY][NZ][C] (one tensor) or triplane (three tensors
-    [B][NX][NY][C], [B][NY][NZ][C], [B][NZ][NX][C]); float32, bfloat16 or float16 (all tensors
-    alike), on the GPU."""
+    """Voxel grid [B][NX][NY][NZ][C] (one tensor), triplane (three tensors [B][NX][NY][C],
+    [B][NY][NZ][C], [B][NZ][NX][C]) or hash table [B][T][C] (one tensor; res = the virtual lattice
+    whose corners are hashed into it); float32, bfloat16 or float16 (all tensors alike), on the GPU."""
     kind: int
     data: List[torch.Tensor]
     res: Sequence[int]
@@ -170,12 +170,15 @@ class Grid:
         nx, ny, nz = self.res
         if self.kind == LP_GRID_VOXEL:
             return [(b, nx, ny, nz, c)]
+        if self.kind == LP_GRID_HASH:
+            return [(b, int(self.data[0].shape[1]), c)]
         return [(b, nx, ny, c), (b, ny, nz, c), (b, nz, nx, c)]
 
     def c_struct(self) -> _Grid:
         g = _Grid()
         g.kind, g.B, g.C = self.kind, self.n_scenes, self.channels
         g.NX, g.NY, g.NZ = [int(v) for v in self.res]
+        g.hash_size = int(self.data[0].shape[1]) if self.kind == LP_GRID_HASH else 0
         shapes = self.shapes()
         if len(self.data) != len(shapes):
             raise ValueError("wrong number of grid tensors for this kind")

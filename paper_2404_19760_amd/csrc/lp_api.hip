@@ -46,12 +46,14 @@ int compute_units(int* out_n_cu, std::string* err)
 lp_status validate(const lp_grid* grid, const lp_mlp* mlp, const lp_rays* rays)
 {
     if (!grid || !mlp || !rays) return fail(LP_ERR_INVALID_ARG, "grid, mlp and rays must not be NULL");
-    if (grid->kind != LP_GRID_VOXEL && grid->kind != LP_GRID_TRIPLANE)
-        return fail(LP_ERR_INVALID_ARG, "grid->kind must be LP_GRID_VOXEL or LP_GRID_TRIPLANE");
+    if (grid->kind != LP_GRID_VOXEL && grid->kind != LP_GRID_TRIPLANE && grid->kind != LP_GRID_HASH)
+        return fail(LP_ERR_INVALID_ARG, "grid->kind must be LP_GRID_VOXEL, LP_GRID_TRIPLANE or LP_GRID_HASH");
+    if (grid->kind == LP_GRID_HASH && (grid->hash_size < 1 || grid->hash_size >= (1ll << 31)))
+        return fail(LP_ERR_INVALID_ARG, "grid->hash_size must be in [1, 2^31) for a hash table");
     if (grid->B < 1 || grid->C < 1) return fail(LP_ERR_INVALID_ARG, "grid->B and grid->C must be >= 1");
     if (grid->NX < 2 || grid->NY < 2 || grid->NZ < 2)
         return fail(LP_ERR_INVALID_ARG, "every grid resolution must be >= 2");
-    const int n_planes = grid->kind == LP_GRID_VOXEL ? 1 : 3;
+    const int n_planes = grid->kind == LP_GRID_TRIPLANE ? 3 : 1;
     for (int p = 0; p < n_planes; ++p)
         if (!grid->data[p]) return fail(LP_ERR_INVALID_ARG, "grid->data has a NULL tensor");
     for (int a = 0; a < 3; ++a) {
@@ -92,6 +94,7 @@ void to_device_views(const lp_grid* grid, const lp_mlp* mlp, const lp_rays* rays
     }
     g->contract = (double)grid->contract_a;
     g->dtype = grid->dtype;
+    g->hash_size = grid->kind == LP_GRID_HASH ? (unsigned)grid->hash_size : 0u;
     std::memset(m, 0, sizeof(*m));
     m->n_layers = mlp->n_layers;
     int off = 0, maxw = 0, act = 0;
@@ -335,6 +338,8 @@ lp_status splat_views(const lp_grid* target, const lp_rays* rays, const lp_splat
     }
     lp_status st = validate(target ? &tgt_checked : nullptr, &stand_in, rays);
     if (st != LP_OK) return st;
+    if (target->kind == LP_GRID_HASH)
+        return fail(LP_ERR_UNSUPPORTED, "the Splatter writes voxel grids and triplanes, not hash tables");
     if (sp->n_in < 1) return fail(LP_ERR_INVALID_ARG, "splat->n_in must be >= 1");
     if (rays->M > 0 && !sp->feats) return fail(LP_ERR_INVALID_ARG, "splat->feats must not be NULL");
     if (sp->n_freq < -1 || sp->n_freq > 4) return fail(LP_ERR_INVALID_ARG, "splat->n_freq must be in [-1, 4]");
@@ -440,7 +445,7 @@ lp_status render_bwd_with(const lp_grid* grid, const lp_mlp* mlp, const lp_rays*
 
     if (st != LP_OK) return st;
     if (!bg || !d_grid || !dW || !db) return fail(LP_ERR_INVALID_ARG, "bg, d_grid, dW and db must not be NULL");
-    const int n_planes = grid->kind == LP_GRID_VOXEL ? 1 : 3;
+    const int n_planes = grid->kind == LP_GRID_TRIPLANE ? 3 : 1;
     for (int p = 0; p < n_planes; ++p)
         if (!d_grid[p]) return fail(LP_ERR_INVALID_ARG, "d_grid has a NULL tensor");
     for (int l = 0; l < mlp->n_layers; ++l)
@@ -674,7 +679,7 @@ lp_status lp_render_dec_bwd(const lp_grid* grid, const lp_decoder* dec, const lp
     if (st != LP_OK) return st;
     if (!bg || !d_grid || !dW_opacity || !db_opacity || !dW_feature || !db_feature)
         return fail(LP_ERR_INVALID_ARG, "bg, d_grid and the four gradient lists must not be NULL");
-    const int n_planes = grid->kind == LP_GRID_VOXEL ? 1 : 3;
+    const int n_planes = grid->kind == LP_GRID_TRIPLANE ? 3 : 1;
     for (int p = 0; p < n_planes; ++p)
         if (!d_grid[p]) return fail(LP_ERR_INVALID_ARG, "d_grid has a NULL tensor");
     for (int l = 0; l < dec->opacity.n_layers; ++l)

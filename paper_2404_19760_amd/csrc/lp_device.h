@@ -18,6 +18,7 @@ struct GridDev {
     double amin[3];
     double scale[3];  // (N-1)/(max-min): world -> continuous index
     double contract;  // foreground scale a of the contract coordinates, 0 = off
+    unsigned hash_size;  // LP_GRID_HASH: entries of one scene's table
 };
 
 struct MlpDev {
@@ -77,6 +78,13 @@ __device__ __forceinline__ float grid_load(const GridDev& g, const void* base, s
     const unsigned short h = reinterpret_cast<const unsigned short*>(base)[idx];
     if (g.dtype == LP_BF16) return __uint_as_float((unsigned)h << 16);
     return __half2float(__ushort_as_half(h));
+}
+
+// Table entry of lattice corner (ix, iy, iz) in a hash-table structure: the spatial hash of Teschner et
+// al. 2003 (the one Instant-NGP uses), in 32-bit unsigned arithmetic.
+__device__ __forceinline__ unsigned hash_slot(int ix, int iy, int iz, unsigned hash_size)
+{
+    return (((unsigned)ix * 1u) ^ ((unsigned)iy * 2654435761u) ^ ((unsigned)iz * 805459861u)) % hash_size;
 }
 
 // Splatter arguments (Section 3.3 "Splatter"): pixel features, optional prior structure, the

@@ -65,6 +65,20 @@ __device__ void gather_feat(const GridDev& g, int scene, const Cell& c, float* f
             }
             feat[k * block_lanes() + lane] = acc;
         }
+    } else if (g.kind == LP_GRID_HASH) {
+        // trilinear over the 8 lattice corners, each read from its table entry
+        const size_t V = (size_t)scene * g.hash_size * C;
+        for (int k = 0; k < C; ++k) {
+            float acc = 0.0f;
+            for (int d = 0; d < 8; ++d) {
+                const int dx = d >> 2, dy = (d >> 1) & 1, dz = d & 1;
+                const float w = (dx ? c.f[0] : c.g[0]) * (dy ? c.f[1] : c.g[1]) *
+                                (dz ? c.f[2] : c.g[2]);
+                const size_t off = (size_t)hash_slot(c.i[0] + dx, c.i[1] + dy, c.i[2] + dz, g.hash_size) * C;
+                acc += w * grid_load(g, g.data[0], V + off + k);
+            }
+            feat[k * block_lanes() + lane] = acc;
+        }
     } else {
         // plane p spans axes (a, b) = (0,1), (1,2), (2,0)
         for (int k = 0; k < C; ++k) {
@@ -96,6 +110,15 @@ __device__ void scatter_feat(const GridDev& g, float* const d_grid[3], int scene
                             (dz ? c.f[2] : c.g[2]);
             const size_t off =
                 (((size_t)(c.i[0] + dx) * g.N[1] + (c.i[1] + dy)) * g.N[2] + (c.i[2] + dz)) * C;
+            for (int k = 0; k < C; ++k) atomicAdd(V + off + k, w * dfeat[k * block_lanes() + lane]);
+        }
+    } else if (g.kind == LP_GRID_HASH) {
+        float* V = d_grid[0] + (size_t)scene * g.hash_size * C;
+        for (int d = 0; d < 8; ++d) {
+            const int dx = d >> 2, dy = (d >> 1) & 1, dz = d & 1;
+            const float w = (dx ? c.f[0] : c.g[0]) * (dy ? c.f[1] : c.g[1]) *
+                            (dz ? c.f[2] : c.g[2]);
+            const size_t off = (size_t)hash_slot(c.i[0] + dx, c.i[1] + dy, c.i[2] + dz, g.hash_size) * C;
             for (int k = 0; k < C; ++k) atomicAdd(V + off + k, w * dfeat[k * block_lanes() + lane]);
         }
     } else {

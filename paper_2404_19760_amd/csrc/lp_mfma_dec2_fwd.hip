@@ -105,6 +105,7 @@ hipError_t dispatch(const GridDev& g, const Dec2Dev& d, const RaysDev& rays, con
 
 bool dec2_supported(const GridDev& g, const DecLayout& d, int n_feat, int feat_act)
 {
+    if (g.kind != LP_GRID_VOXEL && g.kind != LP_GRID_TRIPLANE) return false;
     if (g.C != 16 && g.C != 32) return false;
     if (n_feat != 3 || (feat_act != 0 && feat_act != 1)) return false;
     if (d.Ls != 3 || d.Lv != 3 || d.E > dec2::kMaxDir) return false;

@@ -132,6 +132,7 @@ hipError_t dispatch_fwd(const GridDev& g, const MlpDev& m, const RaysDev& rays, 
 
 bool mfma_supported(const GridDev& g, const MlpDev& m)
 {
+    if (g.kind != LP_GRID_VOXEL && g.kind != LP_GRID_TRIPLANE) return false;   // hash tables: generic kernels
     // inputs: all of them grid channels (16 or 32), or 16 grid channels + 16 direction inputs
     const bool plain = m.n_enc == 0 && m.dims[0] == g.C && (g.C == 16 || g.C == 32);
     const bool with_dir = m.n_enc > 0 && g.C == 16 && m.dims[0] == 32 && m.n_enc <= 16;
