@@ -58,8 +58,9 @@ typedef enum { LP_F32 = 0, LP_BF16 = 1, LP_F16 = 2 } lp_dtype;
  *             trilinearly in a virtual NX x NY x NZ lattice as in a voxel grid, but lattice corner
  *             (ix, iy, iz) is stored in entry ((ix * 1) xor (iy * 2654435761) xor (iz * 805459861))
  *             mod hash_size (products and xor in 32-bit unsigned arithmetic); corners that collide
- *             share the entry and their gradients add.  Renderer only (the Splatter refuses it);
- *             served by the generic kernels.
+ *             share the entry and their gradients add.  Renderer only (the Splatter refuses it).
+ *             The matrix-core kernels take tables whose hash_size is a power of two (16 or 32
+ *             channels, no direction inputs); every other table runs on the generic kernels.
  * World coordinate aabb_min[a] maps to index 0 and aabb_max[a] to index N_a - 1 along axis
  * a; positions outside the box are clamped onto it.  B scenes share the MLP.
  * contract_a: 0 = off.  In (0, 2]: contract coordinates (appendix, "Experimental Details",

@@ -44,6 +44,7 @@ class Workload:
     contract_a: float = 0.0   # > 0: contract coordinates with this foreground scale (grid spans [-1, 1]^3)
     dec_hidden: Optional[Tuple[Tuple[int, ...], Tuple[int, ...]]] = None  # two-MLP decoder: hidden widths (opacity, feature)
     dec_freq: int = 0         # octaves of its view-direction encoding
+    hash_size: int = 0        # kind HASH: entries of the table per scene
 
     @property
     def rays(self) -> int:
@@ -55,7 +56,7 @@ class Workload:
 
     @property
     def corners(self) -> int:
-        return 8 if self.kind == VOXEL else 12
+        return 12 if self.kind == TRIPLANE else 8
 
     @property
     def gather_bytes_per_sample(self) -> int:
@@ -95,6 +96,10 @@ WORKLOADS = {
     "decoder_paper": Workload("decoder_paper", VOXEL, 1, 32, (160, 160, 160), 0.1, (32, 64, 64, 4),
                               256, 1, 384, near=0.5, far=12.0, aabb=1.0, cfg_id=10, contract_a=1.0,
                               dec_hidden=((64, 64), (64, 64)), dec_freq=2),
+    # A hash table (one level of Instant-NGP's spatial hash, 2^19 entries of 16 channels over a 128^3
+    # lattice) under the largest configuration's MLP; served by the generic kernels.
+    "hash": Workload("hash", HASH, 1, 16, (128, 128, 128), 0.1, (16, 64, 64, 4), 128, 1, 128, cfg_id=11,
+                     hash_size=1 << 19),
 }
 WORKLOAD_ORDER = ["tiny", "single_scene", "voxel", "batched", "large"]
 
@@ -279,7 +284,7 @@ def make_inputs(name: str, aabb: Optional[float] = None, with_grid: bool = True)
     """All host buffers of workload `name` (see WORKLOADS)."""
     w = WORKLOADS[name]
     a = w.aabb if aabb is None else aabb
-    grid = (make_grid(w.kind, w.n_scenes, w.res, w.channels, w.grid_std, _seed(w.cfg_id, 0))
+    grid = (make_grid(w.kind, w.n_scenes, w.res, w.channels, w.grid_std, _seed(w.cfg_id, 0), w.hash_size or None)
             if with_grid else [])
     ws, bs = make_mlp(w.mlp_dims, _seed(w.cfg_id, 1))
     origins, dirs, near, far, scene = make_rays(w)

@@ -29,7 +29,9 @@ hipError_t launch_bwd_mfma(const GridDev& g, const MlpDev& m, const RaysDev& ray
 // coordinates or with two 64-wide hidden layers on a triplane)
 hipError_t launch_bwd_mfma_b(const GridDev& g, const MlpDev& m, const RaysDev& rays, const BwdIo& io,
                              int n_cu, hipStream_t stream);
-
+// its instantiations for hash tables (lp_mfma_bwd_hash.hip)
+hipError_t launch_bwd_mfma_hash(const GridDev& g, const MlpDev& m, const RaysDev& rays, const BwdIo& io,
+                                int n_cu, hipStream_t stream);
 
 // the shapes that run as a pair of waves per ray (lp_mfma_bwd_ws.hip)
 bool bwd_ws_supported(const GridDev& g, const MlpDev& m);

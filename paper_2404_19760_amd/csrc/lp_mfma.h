@@ -236,13 +236,29 @@ __device__ __forceinline__ Cell3 locate3(const GridDev& g, double x, double y, d
     return c;
 }
 
+// Table entries of the 8 lattice corners of cell c in a hash table whose size is a power of two (the
+// matrix-core kernels take only those): corner 4dx + 2dy + dz.  The spatial hash of Teschner et al.
+// 2003 with Instant-NGP's primes, in 32-bit unsigned arithmetic; `mod size` is a mask here.
+__device__ __forceinline__ void hash_corner_slots(const Cell3& c, unsigned hash_size, unsigned (&slot)[8])
+{
+    const unsigned mask = hash_size - 1u;
+    const unsigned hx = (unsigned)c.i[0], hy = (unsigned)c.i[1] * 2654435761u, hz = (unsigned)c.i[2] * 805459861u;
+#pragma unroll
+    for (int d = 0; d < 8; ++d) {
+        const unsigned x = hx + (unsigned)(d >> 2);
+        const unsigned y = hy + (((d >> 1) & 1) ? 2654435761u : 0u);
+        const unsigned z = hz + ((d & 1) ? 805459861u : 0u);
+        slot[d] = (x ^ y ^ z) & mask;
+    }
+}
+
 // The texels one lane reads for a sample: NCH consecutive channels of every corner (voxel: corner
 // 4dx + 2dy + dz; triplane: plane p, corner 2da + db at 4p + ..), as 16-byte loads of the grid's
 // storage type GT (lp_dtype: 4 fp32 or 8 bf16 / fp16 values each).  Loading and interpolating
 // are separate steps so that a kernel can issue the loads early and do other work meanwhile.
 template <int KIND, int NCH, int GT>
 struct GatherRaw {
-    static constexpr int kCorners = KIND == LP_GRID_VOXEL ? 8 : 12;
+    static constexpr int kCorners = KIND == LP_GRID_TRIPLANE ? 12 : 8;
     static constexpr int kPerVec = GT == LP_F32 ? 4 : 8;
     static constexpr int kVecs = NCH / kPerVec;
     uint4 v[kCorners][kVecs];
@@ -262,6 +278,16 @@ __device__ __forceinline__ void gather_issue(const GridDev& g, int scene, const 
         for (int d = 0; d < 8; ++d) {
             const int dx = d >> 2, dy = (d >> 1) & 1, dz = d & 1;
             const uint4* p = reinterpret_cast<const uint4*>(V + (size_t)(base + dx * sx + dy * sy + dz * sz) * kElem);
+#pragma unroll
+            for (int i = 0; i < kVecs; ++i) raw.v[d][i] = p[i];
+        }
+    } else if constexpr (KIND == LP_GRID_HASH) {
+        const char* V = reinterpret_cast<const char*>(g.data[0]) + (size_t)scene * g.hash_size * C * kElem;
+        unsigned slot[8];
+        hash_corner_slots(c, g.hash_size, slot);
+#pragma unroll
+        for (int d = 0; d < 8; ++d) {
+            const uint4* p = reinterpret_cast<const uint4*>(V + ((size_t)slot[d] * C + ch0) * kElem);
 #pragma unroll
             for (int i = 0; i < kVecs; ++i) raw.v[d][i] = p[i];
         }
@@ -316,7 +342,7 @@ __device__ __forceinline__ void gather_finish(const Cell3& c, const GatherRaw<KI
 #pragma unroll
     for (int d = 0; d < R::kCorners; ++d) {
         float w;
-        if constexpr (KIND == LP_GRID_VOXEL) {
+        if constexpr (KIND != LP_GRID_TRIPLANE) {
             const int dx = d >> 2, dy = (d >> 1) & 1, dz = d & 1;
             w = (dx ? c.f[0] : 1.0f - c.f[0]) * (dy ? c.f[1] : 1.0f - c.f[1]) * (dz ? c.f[2] : 1.0f - c.f[2]);
         } else {

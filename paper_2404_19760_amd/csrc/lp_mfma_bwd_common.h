@@ -128,6 +128,8 @@ __device__ __forceinline__ Frag selection(int j, int grp, IndexFn index_of)
 // weights are in corner order 4dx + 2dy + dz for 32 channels and in order 4dz + 2dx + dy for 16
 // channels (where the two halves of a lane group take the corners of one dz each).
 // triplane: 12 weights (plane p, corner 2da + db at 4p + ..), then 3 plane offsets.
+// hash table: the 8 corner weights in the voxel's order for this channel count, then the element
+// offsets (entry x channels) of the 8 corners in the same order.
 // EXACT: the complements 1 - f come from the fp64 index (the Splatter, whose result divides by sums
 // of these weights); otherwise from the rounded f (the Renderer's gradient scatter).
 template <int KIND, int C, bool EXACT = false>
@@ -145,6 +147,21 @@ __device__ __forceinline__ void write_scatter_record(float* rec, const GridDev& 
         reinterpret_cast<float4*>(rec)[0] = w0;
         reinterpret_cast<float4*>(rec)[1] = w1;
         reinterpret_cast<unsigned*>(rec)[8] = base;
+    } else if constexpr (KIND == LP_GRID_HASH) {
+        const float x1 = c.f[0], x0 = 1.0f - x1, y1 = c.f[1], y0 = 1.0f - y1, z1 = c.f[2], z0 = 1.0f - z1;
+        unsigned s[8];   // corner 4dx + 2dy + dz
+        hash_corner_slots(c, g.hash_size, s);
+        if constexpr (C == 16) {   // order 4dz + 2dx + dy: the two halves of a lane group take one dz each
+            reinterpret_cast<float4*>(rec)[0] = make_float4(x0 * y0 * z0, x0 * y1 * z0, x1 * y0 * z0, x1 * y1 * z0);
+            reinterpret_cast<float4*>(rec)[1] = make_float4(x0 * y0 * z1, x0 * y1 * z1, x1 * y0 * z1, x1 * y1 * z1);
+            reinterpret_cast<uint4*>(rec)[2] = make_uint4(s[0] * C, s[2] * C, s[4] * C, s[6] * C);
+            reinterpret_cast<uint4*>(rec)[3] = make_uint4(s[1] * C, s[3] * C, s[5] * C, s[7] * C);
+        } else {                   // order 4dx + 2dy + dz
+            reinterpret_cast<float4*>(rec)[0] = make_float4(x0 * y0 * z0, x0 * y0 * z1, x0 * y1 * z0, x0 * y1 * z1);
+            reinterpret_cast<float4*>(rec)[1] = make_float4(x1 * y0 * z0, x1 * y0 * z1, x1 * y1 * z0, x1 * y1 * z1);
+            reinterpret_cast<uint4*>(rec)[2] = make_uint4(s[0] * C, s[1] * C, s[2] * C, s[3] * C);
+            reinterpret_cast<uint4*>(rec)[3] = make_uint4(s[4] * C, s[5] * C, s[6] * C, s[7] * C);
+        }
     } else {
         unsigned base[3];
 #pragma unroll
@@ -196,7 +213,51 @@ __device__ __forceinline__ void scatter_channels(const GridDev& g, float* const 
 {
     const bool live = ch < C;
     auto record_of = [grp](int r) { return IN_ORDER ? 16 * grp + r : d_row(r, grp); };
-    if constexpr (KIND == LP_GRID_VOXEL && C == 16) {
+    if constexpr (KIND == LP_GRID_HASH) {
+        // Hash table: a lane (channel; with 16 channels the two halves of a lane group take the four
+        // corners of one dz each, as for voxels) sums the contributions of consecutive samples whose
+        // corners are the SAME table entries and adds them when any entry changes; equal entries are
+        // the merge criterion, so colliding corners of different cells merge as well.
+        constexpr int N = C == 16 ? 4 : 8;          // corners per lane
+        const int c16 = ch & (C - 1), half = C == 16 ? ch >> 4 : 0;
+        float* V = d_grid[0] + (size_t)scene * g.hash_size * C;
+        float acc[N];
+        unsigned prev[N] = {};
+        auto flush = [&]() {
+            if (live || C == 16) {
+#pragma unroll
+                for (int k = 0; k < N; ++k) atomicAdd(V + prev[k] + c16, acc[k]);
+            }
+        };
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const float* rec = info + record_of(r) * 16;
+            float w[N];
+            unsigned o[N];
+            if constexpr (C == 16) {
+                const float4 w4 = reinterpret_cast<const float4*>(rec)[half];
+                const uint4 o4 = reinterpret_cast<const uint4*>(rec)[2 + half];
+                w[0] = w4.x; w[1] = w4.y; w[2] = w4.z; w[3] = w4.w;
+                o[0] = o4.x; o[1] = o4.y; o[2] = o4.z; o[3] = o4.w;
+            } else {
+                const float4 wa = reinterpret_cast<const float4*>(rec)[0], wb = reinterpret_cast<const float4*>(rec)[1];
+                const uint4 oa = reinterpret_cast<const uint4*>(rec)[2], ob = reinterpret_cast<const uint4*>(rec)[3];
+                w[0] = wa.x; w[1] = wa.y; w[2] = wa.z; w[3] = wa.w; w[4] = wb.x; w[5] = wb.y; w[6] = wb.z; w[7] = wb.w;
+                o[0] = oa.x; o[1] = oa.y; o[2] = oa.z; o[3] = oa.w; o[4] = ob.x; o[5] = ob.y; o[6] = ob.z; o[7] = ob.w;
+            }
+            const float v = dFt[r];
+            bool moved = false;
+#pragma unroll
+            for (int k = 0; k < N; ++k) moved = moved || (o[k] != prev[k]);
+            if (r > 0 && moved) flush();
+#pragma unroll
+            for (int k = 0; k < N; ++k) {
+                acc[k] = (r == 0 || moved) ? w[k] * v : acc[k] + w[k] * v;
+                prev[k] = o[k];
+            }
+        }
+        flush();
+    } else if constexpr (KIND == LP_GRID_VOXEL && C == 16) {
         // 16 channels fill half a lane group: lanes 16..31 hold the same feature gradients as lanes
         // 0..15 (the transposed first-layer weights are staged twice), and each half takes the four
         // corners of one dz, so that a flush is four instructions on two full 64-byte lines each

@@ -106,6 +106,20 @@ def test_two_wave_backward_with_contract_coordinates_and_many_rays(lp, oracle, d
     print(summary(worst), flush=True)
 
 
+@pytest.mark.parametrize("pick", ["every_2nd_ray", "block_of_96x96_pixels"])
+def test_hash_workload_with_many_rays(lp, oracle, pick):
+    """The hash-table workload (2^19 entries x 16 channels over a 128^3 lattice, MLP 16-64-64-4, 128
+    samples per ray) on the matrix-core kernels with about eight rays per wavefront: neighbouring
+    rays add into the same table entries within one launch, colliding corners included."""
+    inp = lp_inputs.make_inputs("hash")
+    idx = np.arange(0, inp.n_rays, 2) if pick == "every_2nd_ray" else _pixel_block(128, 16, 112)
+    sub = inp.subset(idx)
+    grid, mlp, _, _ = lp.to_device(sub)
+    assert lp.lp_has_fast_path(grid, mlp)
+    worst = check_case(lp, oracle, sub, lp.LP_MATH_BF16X3, label=f"hash {pick}")
+    print(summary(worst), flush=True)
+
+
 def test_contract_workload_with_many_rays(lp, oracle):
     """The paper's experimental Renderer shape with contract coordinates: every second ray of the
     256^2 image (32 768 rays x 384 samples, 160^3 x 32 voxels)."""
