@@ -40,6 +40,10 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # by 2.0, WRITE_SIZE by 1.0 against a 1 GiB copy kernel in the same run); the summary with the
 # commands is profiles/large_voxel256_fwd_bwd_kernels.md.  None = not measured for that workload.
 MEASURED_BWD_HBM_BYTES = {"large": 19.51e9 + 65.42e9}
+# 64-byte lines of atomic adds per launch of the backward kernel: its WRITE_SIZE (each atomic line
+# request is written through as 64 bytes; TCC_ATOMIC counts the same requests), same summaries
+# (large_voxel256_..., batched_triplane256_fwd_bwd_kernels.md).
+MEASURED_BWD_ATOMIC_LINES = {"large": 65.42e9 / 64, "batched": 257.0e9 / 64}
 
 
 def parse():
@@ -64,6 +68,9 @@ def parse():
     ap.add_argument("--coexecution", action="store_true",
                     help="instead of the benchmark: time how one SIMD overlaps matrix and vector instructions "
                          "(one JSON line)")
+    ap.add_argument("--atomic-rate", action="store_true",
+                    help="instead of the benchmark: time how many 64-byte lines of fp32 atomic adds the GPU retires "
+                         "per second (one JSON line)")
     ap.add_argument("--ws-phases", action="store_true",
                     help="with a measurement build of the library (LP_EXTRA_HIPCC_FLAGS=-DLP_WS_PHASES python "
                          "paper_2404_19760_amd/build.py): after the run, print where the two roles of the two-wave "
@@ -253,6 +260,14 @@ def main():
             "two_waves_w_and_w_plus_4_ns_per_iteration": {"8 products only": ns[4], "64 multiply-adds only": ns[5], "both": ns[6]},
             "two_waves_w_and_w_plus_1_ns_per_iteration": {"8 products only": ns[7], "64 multiply-adds only": ns[8], "both": ns[9]}}))
         return
+    if args.atomic_rate:
+        r = lp.lp_diag_atomic_rate()
+        print(json.dumps({
+            "measurement": "64-byte lines of fp32 atomic adds retired per second (2048 workgroups of 4 waves, 16 lanes per line)",
+            "random_lines_in_256MiB": {"4 lines per instruction": r[0], "2 lines per instruction": r[1], "1 line per instruction": r[2]},
+            "random_lines_in_256KiB_4_per_instruction": r[3],
+            "neighbouring_lines_4_per_instruction": {"256MiB": r[4], "256KiB": r[5]}}))
+        return
     mode = {"default": lp.LP_MATH_DEFAULT, "generic": lp.LP_MATH_GENERIC, "bf16x3": lp.LP_MATH_BF16X3}[args.math]
     r = measure(lp, torch, args.config, mode, args.steps, args.warmup, args.calibrate_copy, args.grid_dtype, args.aabb,
                 measure_memory=not args.calibrate_copy)
@@ -273,6 +288,8 @@ def main():
     bwd_flop = (9 if fast else 3) * w.mlp_flop_per_sample
     bwd_tflops = bwd_flop * samples / (bwd_avg * 1e-3) / 1e12
     traffic = MEASURED_BWD_HBM_BYTES.get(args.config) if fast and args.grid_dtype == "f32" and args.aabb is None else None
+    lines = MEASURED_BWD_ATOMIC_LINES.get(args.config) if fast and args.grid_dtype == "f32" and args.aabb is None else None
+    atomic_peak = lp.lp_diag_atomic_rate()[0]     # measured now, on this GPU
     out = {
         "metric": "ray-samples/sec fwd+bwd (Renderer hot path)",
         "value": samples / (elapsed / args.steps),
@@ -316,7 +333,12 @@ def main():
                      "hbm_counters": None if traffic is None else
                      {"bound": "hbm (FETCH_SIZE + WRITE_SIZE per launch, profiles/)",
                       "achieved": traffic / (bwd_avg * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                      "frac": traffic / (bwd_avg * 1e-3) / 1e9 / HBM_PEAK_GBS}},
+                      "frac": traffic / (bwd_avg * 1e-3) / 1e9 / HBM_PEAK_GBS},
+                     "atomic_lines": None if lines is None else
+                     {"bound": "atomic adds of whole 64-byte lines (lines per launch from the counters in profiles/; "
+                               "peak measured in this run by lp_diag_atomic_rate, random lines in 256 MiB)",
+                      "achieved": lines / (bwd_avg * 1e-3), "peak": atomic_peak, "unit": "lines/s",
+                      "frac": lines / (bwd_avg * 1e-3) / atomic_peak}},
     }
     # further workloads for context (short runs), e.g. the single-scene configuration and the
     # paper's experimental Renderer shape with contract coordinates
@@ -340,7 +362,9 @@ def main():
              "bwd_mfma_bf16_frac": (nine_f * o["samples"] / (o["bwd_ms"] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS
                                     if o["fast"] and ow.dec_hidden is None else None),
              "fwd_bwd_hbm_effective_frac": (2 * gr + gw) * o["samples"]
-             / ((o["fwd_ms"] + o["bwd_ms"]) * 1e-3) / 1e9 / HBM_PEAK_GBS})
+             / ((o["fwd_ms"] + o["bwd_ms"]) * 1e-3) / 1e9 / HBM_PEAK_GBS,
+             "bwd_atomic_lines_frac": (MEASURED_BWD_ATOMIC_LINES[name] / (o["bwd_ms"] * 1e-3) / atomic_peak
+                                       if name in MEASURED_BWD_ATOMIC_LINES and o["fast"] and not gdt else None)})
         del o
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(inp, args.cpu_seconds)

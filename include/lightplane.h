@@ -294,6 +294,15 @@ lp_status lp_splat_bwd_workspace_bytes(const lp_grid* target, const lp_rays* ray
    Allocates and frees a small device buffer; synchronises the stream. */
 lp_status lp_diag_coexecution(float* ns_per_iteration, void* stream);
 
+/* Diagnostics, not part of the method: the rate at which this GPU retires fp32 atomic adds that cover
+   whole 64-byte lines (16 lanes per line), the unit the gradient scatter of the backward works in
+   (Section 3.4: the backward adds every sample's feature gradient into the structure).
+   lines_per_second (host, 6 floats): lines drawn at random from 256 MiB with 4, 2, 1 lines per
+   instruction [0..2]; from 256 KiB with 4 lines per instruction [3]; neighbouring lines (a walk) in
+   256 MiB and in 256 KiB [4..5].  Allocates and frees 256 MiB of device memory; synchronises the
+   stream. */
+lp_status lp_diag_atomic_rate(float* lines_per_second, void* stream);
+
 /* Diagnostics of a MEASUREMENT build (the library compiled with -DLP_WS_PHASES; an ordinary build
    returns LP_ERR_UNSUPPORTED): cycles the two roles of the two-wave backward have spent in the
    phases of their steps since the last call, summed over all waves.  cycles (host, 32 values):

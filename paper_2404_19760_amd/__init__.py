@@ -72,6 +72,8 @@ def _load() -> C.CDLL:
     lib.lp_version.restype = C.c_int32
     lib.lp_diag_coexecution.restype = C.c_int
     lib.lp_diag_coexecution.argtypes = [C.POINTER(C.c_float), C.c_void_p]
+    lib.lp_diag_atomic_rate.restype = C.c_int
+    lib.lp_diag_atomic_rate.argtypes = [C.POINTER(C.c_float), C.c_void_p]
     lib.lp_diag_ws_phases.restype = C.c_int
     lib.lp_diag_ws_phases.argtypes = [C.POINTER(C.c_ulonglong)]
     lib.lp_has_fast_path.restype = C.c_int32
@@ -286,6 +288,13 @@ def lp_diag_coexecution(stream=None):
     """Nanoseconds per loop iteration of the ten measurements the header describes."""
     out = (C.c_float * 10)()
     _check(_lib.lp_diag_coexecution(out, _stream_ptr(stream)))
+    return [float(v) for v in out]
+
+
+def lp_diag_atomic_rate(stream=None):
+    """64-byte lines of fp32 atomic adds per second in the six settings the header describes."""
+    out = (C.c_float * 6)()
+    _check(_lib.lp_diag_atomic_rate(out, _stream_ptr(stream)))
     return [float(v) for v in out]
 
 
