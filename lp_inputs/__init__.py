@@ -22,6 +22,7 @@ import numpy as np
 VOXEL = 0
 TRIPLANE = 1
 HASH = 2        # hash table: one [B][T][C] tensor; res is the virtual lattice whose corners are hashed into it
+HEXPLANE = 3    # three spatial planes as a triplane's + three space-time planes [B][N_c][NT][C]
 
 
 @dataclasses.dataclass(frozen=True)
@@ -185,7 +186,7 @@ class Inputs:
     n_scenes: int
     channels: int
     res: Tuple[int, int, int]
-    grid: List[np.ndarray]            # 1 (voxel, hash table) or 3 (triplane) float32 arrays
+    grid: List[np.ndarray]            # 1 (voxel, hash table), 3 (triplane) or 6 (HexPlane) float32 arrays
     aabb_min: Tuple[float, float, float]
     aabb_max: Tuple[float, float, float]
     mlp_dims: Tuple[int, ...]
@@ -201,6 +202,13 @@ class Inputs:
     target: Optional[np.ndarray] = None  # [M][3] float32 (for the MSE loss)
     contract_a: float = 0.0           # > 0: contract coordinates with this foreground scale
     decoder: Optional[Decoder] = None  # set: the two-MLP decoder is used (bg / target have n_feat channels)
+    time: Optional[np.ndarray] = None  # [M] float32: the time of every ray (read by a HexPlane only)
+    t_range: Tuple[float, float] = (0.0, 1.0)   # times that map to the first and last index of the time axis
+
+    @property
+    def n_time(self) -> int:
+        """Resolution of the time axis of a HexPlane, else 0."""
+        return int(self.grid[3].shape[2]) if self.kind == HEXPLANE else 0
 
     @property
     def n_rays(self) -> int:
@@ -222,29 +230,40 @@ class Inputs:
             far=np.ascontiguousarray(self.far[idx]),
             scene=None if self.scene is None else np.ascontiguousarray(self.scene[idx]),
             target=None if self.target is None else np.ascontiguousarray(self.target[idx]),
+            time=None if self.time is None else np.ascontiguousarray(self.time[idx]),
         )
 
 
-def grid_shapes(kind: int, n_scenes: int, res, channels: int, hash_size: Optional[int] = None):
+def grid_shapes(kind: int, n_scenes: int, res, channels: int, hash_size: Optional[int] = None,
+                n_time: Optional[int] = None):
     nx, ny, nz = res
     if kind == VOXEL:
         return [(n_scenes, nx, ny, nz, channels)]
     if kind == HASH:
         assert hash_size is not None and hash_size >= 1
         return [(n_scenes, int(hash_size), channels)]
-    return [(n_scenes, nx, ny, channels), (n_scenes, ny, nz, channels),
-            (n_scenes, nz, nx, channels)]
+    planes = [(n_scenes, nx, ny, channels), (n_scenes, ny, nz, channels), (n_scenes, nz, nx, channels)]
+    if kind == HEXPLANE:
+        # the space-time plane of pair p spans (the spatial axis plane p leaves out, time)
+        assert n_time is not None and n_time >= 2
+        planes += [(n_scenes, nz, int(n_time), channels), (n_scenes, nx, int(n_time), channels),
+                   (n_scenes, ny, int(n_time), channels)]
+    return planes
 
 
-def make_grid(kind, n_scenes, res, channels, std, seed, hash_size=None) -> List[np.ndarray]:
+def make_grid(kind, n_scenes, res, channels, std, seed, hash_size=None, n_time=None) -> List[np.ndarray]:
+    """Entries N(0, std); the space-time planes of a HexPlane N(1, std), so that the products of a
+    pair keep the scale of the spatial planes."""
     out = []
-    shapes = grid_shapes(kind, n_scenes, res, channels, hash_size)
+    shapes = grid_shapes(kind, n_scenes, res, channels, hash_size, n_time)
     per_scene = [np.empty(s, dtype=np.float32) for s in shapes]
     for b in range(n_scenes):
         rng = np.random.default_rng(seed + 10 * b)
         for p, s in enumerate(shapes):
             blk = rng.standard_normal(s[1:], dtype=np.float32)
             blk *= np.float32(std)
+            if kind == HEXPLANE and p >= 3:
+                blk += np.float32(1.0)
             per_scene[p][b] = blk
     out.extend(per_scene)
     return out
@@ -311,12 +330,12 @@ def make_small(kind: int, *, n_scenes=1, channels=4, res=(5, 4, 6), mlp_dims=(4,
                n_rays=6, samples=7, seed=0, grid_std=0.5, bias_std=0.3,
                aabb_min=(-1.0, -1.0, -1.0), aabb_max=(1.0, 1.0, 1.0),
                near=(0.3, 0.9), far=(2.2, 3.7), origin_radius=2.0,
-               bg=(0.9, 0.5, 0.2), hash_size=None) -> Inputs:
+               bg=(0.9, 0.5, 0.2), hash_size=None, n_time=None, t_range=(0.0, 1.0)) -> Inputs:
     """A small random problem for pins and edge cases: rays from random points on a
     sphere towards random points near the origin, per-ray near/far, non-cubic grid,
     non-zero biases, coloured background."""
     rng = np.random.default_rng(seed)
-    grid = make_grid(kind, n_scenes, res, channels, grid_std, seed + 1, hash_size)
+    grid = make_grid(kind, n_scenes, res, channels, grid_std, seed + 1, hash_size, n_time)
     ws, bs = make_mlp(mlp_dims, seed + 2, bias_std=bias_std)
     p = rng.standard_normal((n_rays, 3))
     p /= np.linalg.norm(p, axis=1, keepdims=True)
@@ -332,7 +351,12 @@ def make_small(kind: int, *, n_scenes=1, channels=4, res=(5, 4, 6), mlp_dims=(4,
     if n_scenes > 1:
         scene = rng.integers(0, n_scenes, size=n_rays).astype(np.int32)
     target = rng.random((n_rays, 3), dtype=np.float32)
-    return Inputs(kind=kind, n_scenes=n_scenes, channels=channels, res=tuple(res), grid=grid,
+    time = None
+    if kind == HEXPLANE:
+        # times over a little more than the range, so that some rays clamp onto its ends
+        span = t_range[1] - t_range[0]
+        time = rng.uniform(t_range[0] - 0.1 * span, t_range[1] + 0.1 * span, size=n_rays).astype(np.float32)
+    return Inputs(time=time, t_range=tuple(t_range), kind=kind, n_scenes=n_scenes, channels=channels, res=tuple(res), grid=grid,
                   aabb_min=tuple(aabb_min), aabb_max=tuple(aabb_max), mlp_dims=tuple(mlp_dims),
                   weights=ws, biases=bs, origins=np.ascontiguousarray(origins),
                   dirs=np.ascontiguousarray(d), near=nr, far=fr, scene=scene, samples=samples,

@@ -37,7 +37,8 @@ class _Grid(C.Structure):
                 ("NX", C.c_int32), ("NY", C.c_int32), ("NZ", C.c_int32),
                 ("data", C.c_void_p * 3),
                 ("aabb_min", C.c_double * 3), ("aabb_max", C.c_double * 3),
-                ("contract_a", C.c_double), ("hash_size", C.c_int64)]
+                ("contract_a", C.c_double), ("hash_size", C.c_int64),
+                ("data_t", C.c_void_p * 3), ("NT", C.c_int32), ("t_min", C.c_double), ("t_max", C.c_double)]
 
 
 class _Mlp(C.Structure):
@@ -53,7 +54,7 @@ class _Decoder(C.Structure):
 class _Rays(C.Structure):
     _fields_ = [("M", C.c_int64), ("S", C.c_int32),
                 ("origins", C.c_void_p), ("dirs", C.c_void_p),
-                ("near", C.c_void_p), ("far", C.c_void_p), ("scene", C.c_void_p)]
+                ("near", C.c_void_p), ("far", C.c_void_p), ("scene", C.c_void_p), ("time", C.c_void_p)]
 
 
 def _load():
@@ -98,6 +99,7 @@ class Problem:
         self.near = _f64(inp.near)
         self.far = _f64(inp.far)
         self.scene = None if inp.scene is None else np.ascontiguousarray(inp.scene, dtype=np.int32)
+        self.time = None if getattr(inp, "time", None) is None else _f64(inp.time)
         # the library takes bg as float32; widen that value exactly
         self.bg = (C.c_double * len(inp.bg))(*[float(np.float32(v)) for v in inp.bg])
 
@@ -105,7 +107,13 @@ class Problem:
         g.kind, g.B, g.C = inp.kind, inp.n_scenes, inp.channels
         g.NX, g.NY, g.NZ = inp.res
         for p, arr in enumerate(self.grid):
-            g.data[p] = arr.ctypes.data
+            if p < 3:
+                g.data[p] = arr.ctypes.data
+            else:
+                g.data_t[p - 3] = arr.ctypes.data          # HexPlane: the space-time planes
+        if inp.kind == 3:
+            g.NT = int(self.grid[3].shape[2])
+            g.t_min, g.t_max = float(np.float32(inp.t_range[0])), float(np.float32(inp.t_range[1]))
         for a in range(3):
             g.aabb_min[a] = float(inp.aabb_min[a])
             g.aabb_max[a] = float(inp.aabb_max[a])
@@ -150,6 +158,7 @@ class Problem:
         r.origins, r.dirs = self.origins.ctypes.data, self.dirs.ctypes.data
         r.near, r.far = self.near.ctypes.data, self.far.ctypes.data
         r.scene = None if self.scene is None else self.scene.ctypes.data
+        r.time = None if self.time is None else self.time.ctypes.data
         self.c_rays = r
 
     @property
@@ -184,7 +193,7 @@ def render_bwd(inp, p_rgb, p_alpha=None, p_depth=None, kink_band: float = 0.0, k
     d_grid = [np.zeros_like(g) for g in p.grid]
     dW = [np.zeros_like(w) for w in p.W]
     db = [np.zeros_like(b) for b in p.b]
-    dg_arr = (C.c_void_p * 3)(*[d_grid[i].ctypes.data if i < len(d_grid) else None for i in range(3)])
+    dg_arr = (C.c_void_p * 6)(*[d_grid[i].ctypes.data if i < len(d_grid) else None for i in range(6)])
     dW_arr = (C.c_void_p * _MAX_LAYERS)(*[w.ctypes.data for w in dW])
     db_arr = (C.c_void_p * _MAX_LAYERS)(*[b.ctypes.data for b in db])
     rc = _load().lpo_render_bwd(C.byref(p.c_grid), C.byref(p.c_mlp), C.byref(p.c_rays), p.bg,
@@ -263,7 +272,7 @@ def render2_bwd(inp, p_out, p_alpha=None, p_depth=None, kink_band: float = 0.0, 
     dWs = [np.zeros_like(w) for w in p.Ws]; dbs = [np.zeros_like(b) for b in p.bs]
     dWv = [np.zeros_like(w) for w in p.Wv]; dbv = [np.zeros_like(b) for b in p.bv]
     arr = lambda lst: (C.c_void_p * _MAX_LAYERS)(*[a.ctypes.data for a in lst])
-    dg_arr = (C.c_void_p * 3)(*[d_grid[i].ctypes.data if i < len(d_grid) else None for i in range(3)])
+    dg_arr = (C.c_void_p * 6)(*[d_grid[i].ctypes.data if i < len(d_grid) else None for i in range(6)])
     rc = _load().lpo_render2_bwd(C.byref(p.c_grid), C.byref(p.c_decoder), C.byref(p.c_rays), p.bg,
                                  C.c_void_p(p_out.ctypes.data),
                                  None if pa is None else C.c_void_p(pa.ctypes.data),

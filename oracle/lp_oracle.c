@@ -42,6 +42,7 @@
 #define LPO_VOXEL 0
 #define LPO_TRIPLANE 1
 #define LPO_HASH 2
+#define LPO_HEXPLANE 3
 #define LPO_MAX_LAYERS 8
 
 typedef struct {
@@ -50,6 +51,12 @@ typedef struct {
     double aabb_min[3], aabb_max[3];
     double contract_a; /* 0: no contraction; else the foreground scale a of CC */
     int64_t hash_size; /* LPO_HASH: entries T of the table of one scene, data[0] = [B][T][C] */
+    /* LPO_HEXPLANE: data[p] as the triplane's planes; data_t[p] = [B][N_c][NT][C] is the space-time
+       plane over (c, t), c the spatial axis that plane p leaves out (z, x, y for p = 0, 1, 2); time
+       t_min maps to index 0 and t_max to index NT - 1 */
+    const double* data_t[3];
+    int32_t NT;
+    double t_min, t_max;
 } lpo_grid;
 
 typedef struct {
@@ -67,7 +74,13 @@ typedef struct {
     const double* near;    /* [M] */
     const double* far;     /* [M] */
     const int32_t* scene;  /* [M] or NULL */
+    const double* time;    /* [M] or NULL (every ray at the grid's t_min); read by LPO_HEXPLANE only */
 } lpo_rays;
+
+static double ray_time(const lpo_grid* g, const lpo_rays* rays, int64_t i)
+{
+    return rays->time ? rays->time[i] : g->t_min;
+}
 
 /* ---- Section 3.2: the hashing scheme h (bi/tri-linear interpolation) ---------- */
 
@@ -137,8 +150,27 @@ int64_t lpo_hash_slot(int32_t ix, int32_t iy, int32_t iz, int64_t T)
     return (int64_t)((uint64_t)h % (uint64_t)T);
 }
 
-/* h(x): feature of world point x in scene b */
-static void grid_gather(const lpo_grid* g, int b, const double x[3], double* feat)
+/* HexPlane (Section 3.2 names it among the structures h; the definition is Cao & Johnson 2023's):
+   six planes in three complementary pairs, (x,y) with (z,t), (y,z) with (x,t), (z,x) with (y,t).
+   Both planes of a pair are read bilinearly, the two feature vectors are multiplied channel by
+   channel, and the three products are added (the fusion that keeps C channels, as the triplane's sum
+   does).  s[p], u[p]: the reads of the spatial and of the space-time plane of pair p. */
+static void hexplane_reads(const lpo_grid* g, int b, const int i[3], const double f[3], double t,
+                           double* s /* [3][C] */, double* u /* [3][C] */, int* it, double* ft)
+{
+    const int N[3] = {g->NX, g->NY, g->NZ};
+    const int C = g->C;
+    axis_cell(t, g->t_min, g->t_max, g->NT, it, ft);
+    for (int k = 0; k < 3 * C; ++k) s[k] = u[k] = 0.0;
+    for (int p = 0; p < 3; ++p) {
+        const int a = p, bb = (p + 1) % 3, c = (p + 2) % 3;
+        plane_gather(g->data[p] + (int64_t)b * N[a] * N[bb] * C, N[bb], C, i[a], i[bb], f[a], f[bb], s + p * C);
+        plane_gather(g->data_t[p] + (int64_t)b * N[c] * g->NT * C, g->NT, C, i[c], *it, f[c], *ft, u + p * C);
+    }
+}
+
+/* h(x): feature of world point x (at time t, which only a HexPlane reads) in scene b */
+static void grid_gather(const lpo_grid* g, int b, const double x[3], double t, double* feat)
 {
     int i[3];
     double f[3], y[3];
@@ -169,6 +201,15 @@ static void grid_gather(const lpo_grid* g, int b, const double x[3], double* fea
                     const double* v = V + lpo_hash_slot(i[0] + dx, i[1] + dy, i[2] + dz, g->hash_size) * C;
                     for (int k = 0; k < C; ++k) feat[k] += w * v[k];
                 }
+    } else if (g->kind == LPO_HEXPLANE) {
+        int it;
+        double ft;
+        double* s = (double*)malloc(sizeof(double) * 6 * (size_t)C);
+        double* u = s + 3 * C;
+        hexplane_reads(g, b, i, f, t, s, u, &it, &ft);
+        for (int p = 0; p < 3; ++p)
+            for (int k = 0; k < C; ++k) feat[k] += s[p * C + k] * u[p * C + k];
+        free(s);
     } else {
         /* planes sampled at (x,y), (y,z), (z,x) and summed */
         plane_gather(g->data[0] + (int64_t)b * g->NX * g->NY * C, g->NY, C, i[0], i[1], f[0], f[1], feat);
@@ -178,7 +219,8 @@ static void grid_gather(const lpo_grid* g, int b, const double x[3], double* fea
 }
 
 /* transpose of grid_gather: d_grid[corner] += weight * dfeat, same corners and weights */
-static void grid_scatter(const lpo_grid* g, double* const d_grid[3], int b, const double x[3],
+/* (a HexPlane has six gradient tensors: d_grid[p] for data[p], d_grid[3 + p] for data_t[p]) */
+static void grid_scatter(const lpo_grid* g, double* const d_grid[], int b, const double x[3], double t,
                          const double* dfeat)
 {
     int i[3];
@@ -216,6 +258,23 @@ static void grid_scatter(const lpo_grid* g, double* const d_grid[3], int b, cons
                         v[k] += add;
                     }
                 }
+    } else if (g->kind == LPO_HEXPLANE) {
+        /* product rule: the spatial plane of a pair receives dfeat times the space-time plane's read,
+           and the other way round */
+        int it;
+        double ft;
+        double* s = (double*)malloc(sizeof(double) * 7 * (size_t)C);
+        double* u = s + 3 * C;
+        double* tmp = s + 6 * C;
+        hexplane_reads(g, b, i, f, t, s, u, &it, &ft);
+        for (int p = 0; p < 3; ++p) {
+            const int a = p, bb = (p + 1) % 3, c = (p + 2) % 3;
+            for (int k = 0; k < C; ++k) tmp[k] = dfeat[k] * u[p * C + k];
+            plane_scatter(d_grid[p] + (int64_t)b * N[a] * N[bb] * C, N[bb], C, i[a], i[bb], f[a], f[bb], tmp);
+            for (int k = 0; k < C; ++k) tmp[k] = dfeat[k] * s[p * C + k];
+            plane_scatter(d_grid[3 + p] + (int64_t)b * N[c] * g->NT * C, g->NT, C, i[c], it, f[c], ft, tmp);
+        }
+        free(s);
     } else {
         plane_scatter(d_grid[0] + (int64_t)b * g->NX * g->NY * C, g->NY, C, i[0], i[1], f[0], f[1], dfeat);
         plane_scatter(d_grid[1] + (int64_t)b * g->NY * g->NZ * C, g->NZ, C, i[1], i[2], f[1], f[2], dfeat);
@@ -313,7 +372,7 @@ static void ray_forward(const lpo_grid* g, const lpo_mlp* m, const lpo_rays* ray
         r->t[j] = t;
         for (int a = 0; a < 3; ++a) r->x[3 * j + a] = o[a] + t * d[a];
         double* act = r->act + (size_t)j * nact;
-        grid_gather(g, b, r->x + 3 * j, act);
+        grid_gather(g, b, r->x + 3 * j, ray_time(g, rays, i), act);
         mlp_forward(m, act, r->pre + (size_t)j * (nact - C));
         const double* out = act + out_off;
         r->sigma[j] = softplus(out[0]);
@@ -332,6 +391,7 @@ static int check_args(const lpo_grid* g, const lpo_mlp* m, const lpo_rays* rays)
 {
     if (!g || !m || !rays) return 1;
     if (g->B < 1 || g->C < 1 || g->NX < 2 || g->NY < 2 || g->NZ < 2) return 1;
+    if (g->kind == LPO_HEXPLANE && (g->NT < 2 || !(g->t_max > g->t_min))) return 1;
     if (m->n_layers < 1 || m->n_layers > LPO_MAX_LAYERS) return 1;
     if (m->dims[0] != g->C || m->dims[m->n_layers] != 4) return 1;
     if (rays->M < 0 || rays->S < 1) return 1;
@@ -443,7 +503,7 @@ typedef struct {
    elementwise maximum / minimum over all on/off choices for those units. */
 static void ray_backward(const lpo_grid* g, const lpo_mlp* m, const lpo_rays* rays, int64_t i,
                          const double bg[3], const ray_tape* r, const double p_rgb[3],
-                         double p_alpha, double p_depth, double* const d_grid[3],
+                         double p_alpha, double p_depth, double* const d_grid[],
                          double* const dW[], double* const db[], double* scratch,
                          double* dsig_out, double* dcol_out, double band, int side, kink_tmp* kt)
 {
@@ -524,7 +584,7 @@ static void ray_backward(const lpo_grid* g, const lpo_mlp* m, const lpo_rays* ra
             for (int c = 0; c < 4; ++c) dact[out_off + c] = dout[c];
             sample_mlp_backward(m, act, pre, C, nact, dact, dW, db, 0, NULL, NULL, 0u);
         }
-        grid_scatter(g, d_grid, b, r->x + 3 * j, dact);
+        grid_scatter(g, d_grid, b, r->x + 3 * j, ray_time(g, rays, i), dact);
     }
 }
 
@@ -562,7 +622,7 @@ static void kink_free(kink_tmp* kt)
    add.  The forward is never affected. */
 int lpo_render_bwd(const lpo_grid* g, const lpo_mlp* m, const lpo_rays* rays, const double bg[3],
                    const double* p_rgb, const double* p_alpha, const double* p_depth,
-                   double* const d_grid[3], double* const dW[], double* const db[], double band,
+                   double* const d_grid[], double* const dW[], double* const db[], double band,
                    int side)
 {
     if (check_args(g, m, rays)) return 1;
@@ -640,20 +700,25 @@ int lpo_ray_trace(const lpo_grid* g, const lpo_mlp* m, const lpo_rays* rays, con
     int rc = 0;
     if (p_rgb && (dsigma || dcol)) {
         /* throw-away gradient buffers */
-        int64_t gsz[3] = {0, 0, 0};
+        int64_t gsz[6] = {0, 0, 0, 0, 0, 0};
         if (g->kind == LPO_VOXEL) gsz[0] = (int64_t)g->B * g->NX * g->NY * g->NZ * C;
         else if (g->kind == LPO_HASH) gsz[0] = (int64_t)g->B * g->hash_size * C;
         else {
             gsz[0] = (int64_t)g->B * g->NX * g->NY * C;
             gsz[1] = (int64_t)g->B * g->NY * g->NZ * C;
             gsz[2] = (int64_t)g->B * g->NZ * g->NX * C;
+            if (g->kind == LPO_HEXPLANE) {
+                gsz[3] = (int64_t)g->B * g->NZ * g->NT * C;
+                gsz[4] = (int64_t)g->B * g->NX * g->NT * C;
+                gsz[5] = (int64_t)g->B * g->NY * g->NT * C;
+            }
         }
-        double* dg[3] = {NULL, NULL, NULL};
+        double* dg[6] = {NULL, NULL, NULL, NULL, NULL, NULL};
         double* tW[LPO_MAX_LAYERS] = {NULL};
         double* tb[LPO_MAX_LAYERS] = {NULL};
         double* scratch = (double*)malloc(sizeof(double) * (size_t)(S + 1 + nact));
         int ok = scratch != NULL;
-        for (int p = 0; p < 3; ++p)
+        for (int p = 0; p < 6; ++p)
             if (gsz[p]) { dg[p] = (double*)calloc((size_t)gsz[p], sizeof(double)); ok = ok && dg[p]; }
         for (int l = 0; l < nl; ++l) {
             tW[l] = (double*)calloc((size_t)m->dims[l] * m->dims[l + 1], sizeof(double));
@@ -664,7 +729,7 @@ int lpo_ray_trace(const lpo_grid* g, const lpo_mlp* m, const lpo_rays* rays, con
             ray_backward(g, m, rays, ray, bg, &r, p_rgb, p_alpha, p_depth, dg, tW, tb, scratch,
                          dsigma, dcol, 0.0, 0, NULL);
         else rc = 2;
-        for (int p = 0; p < 3; ++p) free(dg[p]);
+        for (int p = 0; p < 6; ++p) free(dg[p]);
         for (int l = 0; l < nl; ++l) { free(tW[l]); free(tb[l]); }
         free(scratch);
     }
@@ -760,6 +825,7 @@ static int dec_check(const lpo_grid* g, const lpo_decoder* dc, const lpo_rays* r
 {
     if (!g || !dc || !rays) return 1;
     if (g->B < 1 || g->C < 1 || g->NX < 2 || g->NY < 2 || g->NZ < 2) return 1;
+    if (g->kind == LPO_HEXPLANE && (g->NT < 2 || !(g->t_max > g->t_min))) return 1;
     const lpo_mlp* ms = &dc->opacity;
     const lpo_mlp* mv = &dc->color;
     if (ms->n_layers < 1 || ms->n_layers > LPO_MAX_LAYERS) return 1;
@@ -791,7 +857,7 @@ static void dec_ray_forward(const lpo_grid* g, const lpo_decoder* dc, const lpo_
         for (int a = 0; a < 3; ++a) r->x[3 * j + a] = o[a] + t * d[a];
         double* as = r->act_s + (size_t)j * r->na_s;
         double* av = r->act_v + (size_t)j * r->na_v;
-        grid_gather(g, b, r->x + 3 * j, as);
+        grid_gather(g, b, r->x + 3 * j, ray_time(g, rays, i), as);
         for (int k = 0; k < C; ++k) av[k] = as[k];
         dir_encode(d, dc->n_freq, av + C);
         mlp_forward(&dc->opacity, as, r->pre_s + (size_t)j * r->na_s);
@@ -926,7 +992,7 @@ static void mlp_backward_choice(const lpo_mlp* m, const double* act, const doubl
    gradients, so the envelope of the sum is the sum of the envelopes. */
 static void dec_ray_backward(const lpo_grid* g, const lpo_decoder* dc, const lpo_rays* rays, int64_t i,
                              const double* bg, const dec_tape* r, const double* p_out, double p_alpha,
-                             double p_depth, double* const d_grid[3], double* const dWs[],
+                             double p_depth, double* const d_grid[], double* const dWs[],
                              double* const dbs[], double* const dWv[], double* const dbv[],
                              double* scratch, double band, int side, kink_tmp* kts, kink_tmp* ktv)
 {
@@ -964,14 +1030,14 @@ static void dec_ray_backward(const lpo_grid* g, const lpo_decoder* dc, const lpo
         mlp_backward_choice(&dc->color, av, r->pre_v + (size_t)j * r->na_v, r->na_v, dout_v, band, side,
                             ktv, dWv, dbv, dact_v, din_v);
         for (int k = 0; k < C; ++k) din_s[k] += din_v[k];
-        grid_scatter(g, d_grid, b, r->x + 3 * j, din_s);
+        grid_scatter(g, d_grid, b, r->x + 3 * j, ray_time(g, rays, i), din_s);
     }
 }
 
 /* d_grid and the four gradient lists are ACCUMULATED into.  band / side as in lpo_render_bwd. */
 int lpo_render2_bwd(const lpo_grid* g, const lpo_decoder* dc, const lpo_rays* rays, const double* bg,
                     const double* p_out, const double* p_alpha, const double* p_depth,
-                    double* const d_grid[3], double* const dWs[], double* const dbs[],
+                    double* const d_grid[], double* const dWs[], double* const dbs[],
                     double* const dWv[], double* const dbv[], double band, int side)
 {
     if (dec_check(g, dc, rays)) return 1;
@@ -1094,7 +1160,7 @@ static int splat_check(const lpo_grid* tgt, const lpo_rays* rays, const lpo_spla
     if (rays->M < 0 || rays->S < 1 || sp->n_in < 1 || sp->n_freq < -1) return 1;
     const int E = sp->n_freq < 0 ? 0 : 3 + 6 * sp->n_freq;
     const int Cp = sp->prior ? sp->prior->C : 0;
-    if (tgt->kind == LPO_HASH) return 1; /* the Splatter writes voxel grids and triplanes */
+    if (tgt->kind == LPO_HASH || tgt->kind == LPO_HEXPLANE) return 1; /* the Splatter writes voxel grids and triplanes */
     if (sp->prior && (sp->prior->kind != tgt->kind || sp->prior->B != tgt->B)) return 1;
     if (!sp->mlp) return (sp->n_in != tgt->C || sp->prior || E) ? 1 : 0;
     if (sp->mlp->n_layers < 1 || sp->mlp->n_layers > LPO_MAX_LAYERS) return 1;
@@ -1109,7 +1175,7 @@ static void splat_inputs(const lpo_rays* rays, const lpo_splat* sp, int64_t i, i
     int n = 0;
     for (int k = 0; k < sp->n_in; ++k) in[n++] = sp->feats[(size_t)i * sp->n_in + k];
     if (sp->prior) {
-        grid_gather(sp->prior, b, x, in + n);
+        grid_gather(sp->prior, b, x, 0.0, in + n);
         n += sp->prior->C;
     }
     if (sp->n_freq >= 0) dir_encode(rays->dirs + 3 * i, sp->n_freq, in + n);
@@ -1156,8 +1222,8 @@ int lpo_splat_fwd(const lpo_grid* tgt, const lpo_rays* rays, const lpo_splat* sp
                         mlp_forward(sp->mlp, act, pre);
                         vt = act + nact - C;
                     }
-                    grid_scatter(tgt, theta, b, x, vt);
-                    grid_scatter(&wgrid, theta_w, b, x, &one);
+                    grid_scatter(tgt, theta, b, x, 0.0, vt);
+                    grid_scatter(&wgrid, theta_w, b, x, 0.0, &one);
                 }
             }
         }
@@ -1237,7 +1303,7 @@ int lpo_splat_bwd(const lpo_grid* tgt, const lpo_rays* rays, const lpo_splat* sp
                 for (int j = 0; j < S; ++j) {
                     const double t = nr + ((double)j + 0.5) * delta;
                     const double x[3] = {o[0] + t * d[0], o[1] + t * d[1], o[2] + t * d[2]};
-                    grid_gather(&ggrid, b, x, dvt); /* dL/d(vt_ij) */
+                    grid_gather(&ggrid, b, x, 0.0, dvt); /* dL/d(vt_ij) */
                     if (!m) {
                         for (int k = 0; k < n_in; ++k) d_feats[(size_t)i * n_in + k] += dvt[k];
                         continue;
@@ -1246,7 +1312,7 @@ int lpo_splat_bwd(const lpo_grid* tgt, const lpo_rays* rays, const lpo_splat* sp
                     mlp_forward(m, act, pre);
                     mlp_backward_choice(m, act, pre, nact, dvt, band, side, &kt, tW, tb, dact, din);
                     for (int k = 0; k < n_in; ++k) d_feats[(size_t)i * n_in + k] += din[k];
-                    if (sp->prior) grid_scatter(sp->prior, d_prior, b, x, din + n_in);
+                    if (sp->prior) grid_scatter(sp->prior, d_prior, b, x, 0.0, din + n_in);
                 }
             }
             if (m) {
