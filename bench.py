@@ -62,7 +62,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
     ap.add_argument("--also", default="tiny,single_scene,voxel,batched,large:bf16,contract,decoder,decoder_paper,"
-                                      "hash,splat_naive,splat_mlp",
+                                      "hash,hexplane,splat_naive,splat_mlp",
                     help="further workloads reported for context under 'also' (comma-separated, '' to skip; "
                          "name:bf16 / name:f16 = that workload with the grid stored in reduced precision)")
     ap.add_argument("--coexecution", action="store_true",

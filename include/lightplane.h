@@ -39,7 +39,7 @@ typedef enum {
     LP_ERR_WORKSPACE = 4    /* workspace missing or smaller than lp_bwd_workspace_bytes     */
 } lp_status;
 
-typedef enum { LP_GRID_VOXEL = 0, LP_GRID_TRIPLANE = 1, LP_GRID_HASH = 2 } lp_grid_kind;
+typedef enum { LP_GRID_VOXEL = 0, LP_GRID_TRIPLANE = 1, LP_GRID_HASH = 2, LP_GRID_HEXPLANE = 3 } lp_grid_kind;
 
 /* Storage type of the values of a hash structure that is READ (Section 3.2 notes that the
    hashing scheme is where precision and layout can be traded).  Gradients and the Splatter's
@@ -61,6 +61,15 @@ typedef enum { LP_F32 = 0, LP_BF16 = 1, LP_F16 = 2 } lp_dtype;
  *             share the entry and their gradients add.  Renderer only (the Splatter refuses it).
  *             The matrix-core kernels take tables whose hash_size is a power of two (16 or 32
  *             channels, no direction inputs); every other table runs on the generic kernels.
+ *   hexplane: a structure over space AND time (Section 3.2 names HexPlane among the structures;
+ *             the definition is Cao & Johnson 2023's): data[0..2] as the triplane's planes, and
+ *             data_t[p] = [B][N_c][NT][C] the space-time plane over (c, t), c being the spatial
+ *             axis that plane p leaves out (z, x, y for p = 0, 1, 2).  A point (x,y,z) of a ray
+ *             with time t reads both planes of a pair bilinearly, multiplies the two feature
+ *             vectors channel by channel, and SUMS the three products.  Time t_min maps to index 0
+ *             and t_max to index NT - 1 of the time axis, times outside are clamped; contract
+ *             coordinates act on the spatial axes only.  The gradient has six tensors (d_grid[p]
+ *             for data[p], d_grid[3 + p] for data_t[p]).  Renderer only, generic kernels.
  * World coordinate aabb_min[a] maps to index 0 and aabb_max[a] to index N_a - 1 along axis
  * a; positions outside the box are clamped onto it.  B scenes share the MLP.
  * contract_a: 0 = off.  In (0, 2]: contract coordinates (appendix, "Experimental Details",
@@ -79,6 +88,9 @@ typedef struct {
     float contract_a;
     int32_t dtype; /* lp_dtype; LP_BF16 / LP_F16 halve the bytes a sample reads */
     int64_t hash_size; /* LP_GRID_HASH: entries of one scene's table, in [1, 2^31); else ignored */
+    const void* data_t[3]; /* LP_GRID_HEXPLANE: device, the space-time planes; else ignored */
+    int32_t NT;            /* LP_GRID_HEXPLANE: resolution of the time axis, >= 2 */
+    float t_min, t_max;    /* LP_GRID_HEXPLANE: times of the first and last index, t_max > t_min */
 } lp_grid;
 
 /*
@@ -107,6 +119,8 @@ typedef struct {
     const float* near;    /* device [M] */
     const float* far;     /* device [M] */
     const int32_t* scene; /* device [M] scene index in [0,B), or NULL (all rays use scene 0) */
+    const float* time;    /* device [M] time of every ray, or NULL (all rays at the grid's t_min);
+                             read for LP_GRID_HEXPLANE only */
 } lp_rays;
 
 /* How the MLP contractions are evaluated by the matrix-core kernels. */
@@ -136,7 +150,8 @@ lp_status lp_render_fwd(const lp_grid* grid, const lp_mlp* mlp, const lp_rays* r
  * all device.  Marches each ray in reverse, recomputes sampling and MLP, rebuilds the
  * transmittance from ray_cache (as written by lp_render_fwd for the SAME inputs), and
  * ACCUMULATES into (the caller zeroes or pre-loads them):
- *     d_grid[p] — same shape as grid->data[p] (device; triplane: all three required),
+ *     d_grid[p] — same shape as grid->data[p] (device; triplane: all three required; HexPlane: six,
+ *                 d_grid[3 + p] with the shape of grid->data_t[p]),
  *     dW[l], db[l] — same shapes as mlp->W[l], mlp->b[l] (device).
  * No gradient is produced for rays, near, far or bg.  `workspace` is device memory of at
  * least lp_bwd_workspace_bytes(...) bytes, 256-byte aligned, contents ignored on entry and
@@ -145,7 +160,7 @@ lp_status lp_render_fwd(const lp_grid* grid, const lp_mlp* mlp, const lp_rays* r
  */
 lp_status lp_render_bwd(const lp_grid* grid, const lp_mlp* mlp, const lp_rays* rays,
                         const float bg[3], const float* d_rgb, const float* d_alpha,
-                        const float* d_depth, const float* ray_cache, float* const d_grid[3],
+                        const float* d_depth, const float* ray_cache, float* const d_grid[],
                         float* const dW[LP_MAX_LAYERS], float* const db[LP_MAX_LAYERS],
                         void* workspace, size_t workspace_bytes, int32_t math_mode,
                         void* stream);
@@ -170,7 +185,7 @@ lp_status lp_bwd_workspace_bytes(const lp_grid* grid, const lp_mlp* mlp, const l
 #define LP_STATIC_SCRATCH_BYTES (32u * 1024u * 1024u)
 lp_status lp_render_bwd_static(const lp_grid* grid, const lp_mlp* mlp, const lp_rays* rays,
                                const float bg[3], const float* d_rgb, const float* d_alpha,
-                               const float* d_depth, const float* ray_cache, float* const d_grid[3],
+                               const float* d_depth, const float* ray_cache, float* const d_grid[],
                                float* const dW[LP_MAX_LAYERS], float* const db[LP_MAX_LAYERS],
                                int32_t math_mode, void* stream);
 
@@ -220,7 +235,7 @@ lp_status lp_render_dec_fwd(const lp_grid* grid, const lp_decoder* dec, const lp
    workspace: at least the bwd_bytes of lp_dec_workspace_bytes. */
 lp_status lp_render_dec_bwd(const lp_grid* grid, const lp_decoder* dec, const lp_rays* rays,
                             const float* bg, const float* d_out, const float* d_alpha,
-                            const float* d_depth, const float* ray_cache, float* const d_grid[3],
+                            const float* d_depth, const float* ray_cache, float* const d_grid[],
                             float* const dW_opacity[LP_MAX_LAYERS], float* const db_opacity[LP_MAX_LAYERS],
                             float* const dW_feature[LP_MAX_LAYERS], float* const db_feature[LP_MAX_LAYERS],
                             void* workspace, size_t workspace_bytes, int32_t math_mode, void* stream);

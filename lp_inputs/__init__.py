@@ -46,6 +46,7 @@ class Workload:
     dec_hidden: Optional[Tuple[Tuple[int, ...], Tuple[int, ...]]] = None  # two-MLP decoder: hidden widths (opacity, feature)
     dec_freq: int = 0         # octaves of its view-direction encoding
     hash_size: int = 0        # kind HASH: entries of the table per scene
+    n_time: int = 0           # kind HEXPLANE: resolution of the time axis (times run over [0, 1])
 
     @property
     def rays(self) -> int:
@@ -57,7 +58,7 @@ class Workload:
 
     @property
     def corners(self) -> int:
-        return 12 if self.kind == TRIPLANE else 8
+        return {TRIPLANE: 12, HEXPLANE: 24}.get(self.kind, 8)
 
     @property
     def gather_bytes_per_sample(self) -> int:
@@ -98,9 +99,13 @@ WORKLOADS = {
                               256, 1, 384, near=0.5, far=12.0, aabb=1.0, cfg_id=10, contract_a=1.0,
                               dec_hidden=((64, 64), (64, 64)), dec_freq=2),
     # A hash table (one level of Instant-NGP's spatial hash, 2^19 entries of 16 channels over a 128^3
-    # lattice) under the largest configuration's MLP; served by the generic kernels.
+    # lattice) under the largest configuration's MLP.
     "hash": Workload("hash", HASH, 1, 16, (128, 128, 128), 0.1, (16, 64, 64, 4), 128, 1, 128, cfg_id=11,
                      hash_size=1 << 19),
+    # A HexPlane (three 128^2 spatial planes and three 128 x 16 space-time planes of 16 channels), rays
+    # of one view with a frame time each; served by the generic kernels.
+    "hexplane": Workload("hexplane", HEXPLANE, 1, 16, (128, 128, 128), 0.1, (16, 64, 64, 4), 128, 1, 128, cfg_id=12,
+                         n_time=16),
 }
 WORKLOAD_ORDER = ["tiny", "single_scene", "voxel", "batched", "large"]
 
@@ -303,7 +308,8 @@ def make_inputs(name: str, aabb: Optional[float] = None, with_grid: bool = True)
     """All host buffers of workload `name` (see WORKLOADS)."""
     w = WORKLOADS[name]
     a = w.aabb if aabb is None else aabb
-    grid = (make_grid(w.kind, w.n_scenes, w.res, w.channels, w.grid_std, _seed(w.cfg_id, 0), w.hash_size or None)
+    grid = (make_grid(w.kind, w.n_scenes, w.res, w.channels, w.grid_std, _seed(w.cfg_id, 0), w.hash_size or None,
+                      w.n_time or None)
             if with_grid else [])
     ws, bs = make_mlp(w.mlp_dims, _seed(w.cfg_id, 1))
     origins, dirs, near, far, scene = make_rays(w)
@@ -312,7 +318,10 @@ def make_inputs(name: str, aabb: Optional[float] = None, with_grid: bool = True)
     decoder = None
     if w.dec_hidden is not None:
         decoder = make_decoder(w.channels, w.dec_hidden[0], w.dec_hidden[1], w.dec_freq, 3, _seed(w.cfg_id, 3))
-    return Inputs(kind=w.kind, n_scenes=w.n_scenes, channels=w.channels, res=w.res, grid=grid, decoder=decoder,
+    time = None
+    if w.kind == HEXPLANE:   # a training batch of a dynamic scene: every ray from a frame drawn at random
+        time = np.random.default_rng(_seed(w.cfg_id, 4)).random(origins.shape[0], dtype=np.float32)
+    return Inputs(time=time, kind=w.kind, n_scenes=w.n_scenes, channels=w.channels, res=w.res, grid=grid, decoder=decoder,
                   aabb_min=(-a, -a, -a), aabb_max=(a, a, a), mlp_dims=w.mlp_dims,
                   weights=ws, biases=bs, origins=origins, dirs=dirs, near=near, far=far,
                   scene=scene, samples=w.samples, bg=(1.0, 1.0, 1.0), target=target,

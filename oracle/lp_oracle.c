@@ -219,9 +219,12 @@ static void grid_gather(const lpo_grid* g, int b, const double x[3], double t, d
 }
 
 /* transpose of grid_gather: d_grid[corner] += weight * dfeat, same corners and weights */
-/* (a HexPlane has six gradient tensors: d_grid[p] for data[p], d_grid[3 + p] for data_t[p]) */
+/* (a HexPlane has six gradient tensors: d_grid[p] for data[p], d_grid[3 + p] for data_t[p]).
+   dfeat_neg: NULL, or -- when dfeat is one side of the kink envelope of the feature gradient -- the
+   other side, which a HexPlane uses wherever the feature gradient is multiplied by a NEGATIVE plane
+   read (the upper bound of a product with a negative factor comes from the lower bound). */
 static void grid_scatter(const lpo_grid* g, double* const d_grid[], int b, const double x[3], double t,
-                         const double* dfeat)
+                         const double* dfeat, const double* dfeat_neg)
 {
     int i[3];
     double f[3], y[3];
@@ -269,9 +272,9 @@ static void grid_scatter(const lpo_grid* g, double* const d_grid[], int b, const
         hexplane_reads(g, b, i, f, t, s, u, &it, &ft);
         for (int p = 0; p < 3; ++p) {
             const int a = p, bb = (p + 1) % 3, c = (p + 2) % 3;
-            for (int k = 0; k < C; ++k) tmp[k] = dfeat[k] * u[p * C + k];
+            for (int k = 0; k < C; ++k) tmp[k] = ((u[p * C + k] < 0.0 && dfeat_neg) ? dfeat_neg[k] : dfeat[k]) * u[p * C + k];
             plane_scatter(d_grid[p] + (int64_t)b * N[a] * N[bb] * C, N[bb], C, i[a], i[bb], f[a], f[bb], tmp);
-            for (int k = 0; k < C; ++k) tmp[k] = dfeat[k] * s[p * C + k];
+            for (int k = 0; k < C; ++k) tmp[k] = ((s[p * C + k] < 0.0 && dfeat_neg) ? dfeat_neg[k] : dfeat[k]) * s[p * C + k];
             plane_scatter(d_grid[3 + p] + (int64_t)b * N[c] * g->NT * C, g->NT, C, i[c], it, f[c], ft, tmp);
         }
         free(s);
@@ -544,6 +547,7 @@ static void ray_backward(const lpo_grid* g, const lpo_mlp* m, const lpo_rays* ra
         }
         int kl[LPO_MAX_KINKS], ko[LPO_MAX_KINKS];
         const int nk = (side != 0 && kt) ? sample_kinks(m, act, pre, C, band, kl, ko) : 0;
+        const double* dact_neg = NULL;
         if (nk > 0) {
             for (unsigned mask = 0; mask < (1u << nk); ++mask) {
                 for (int l = 0; l < nl; ++l) {
@@ -578,13 +582,15 @@ static void ray_backward(const lpo_grid* g, const lpo_mlp* m, const lpo_rays* ra
                 for (int k = 0; k < m->dims[l + 1]; ++k) db[l][k] += kt->b[pick][l][k];
             }
             /* interpolation weights are non-negative, so the envelope of weight * dfeat is the
-               weight times the envelope of dfeat */
+               weight times the envelope of dfeat (a HexPlane also multiplies by signed plane reads
+               and takes the other side there, see grid_scatter) */
             for (int k = 0; k < C; ++k) dact[k] = kt->dact[pick][k];
+            dact_neg = kt->dact[1 - pick];
         } else {
             for (int c = 0; c < 4; ++c) dact[out_off + c] = dout[c];
             sample_mlp_backward(m, act, pre, C, nact, dact, dW, db, 0, NULL, NULL, 0u);
         }
-        grid_scatter(g, d_grid, b, r->x + 3 * j, ray_time(g, rays, i), dact);
+        grid_scatter(g, d_grid, b, r->x + 3 * j, ray_time(g, rays, i), dact, dact_neg);
     }
 }
 
@@ -941,7 +947,8 @@ static void mlp_backward_sample(const lpo_mlp* m, const double* act, const doubl
    the n_out output gradients.  Adds to dW, db; writes dL/d(input) to din[0 .. dims[0]). */
 static void mlp_backward_choice(const lpo_mlp* m, const double* act, const double* pre, int nact,
                                 const double* dout, double band, int side, kink_tmp* kt,
-                                double* const dW[], double* const db[], double* dact, double* din)
+                                double* const dW[], double* const db[], double* dact, double* din,
+                                double* din_other /* the other side of the envelope of din (= din for side 0) */)
 {
     const int nl = m->n_layers, n_in = m->dims[0], n_out = m->dims[nl];
     int kl[LPO_MAX_KINKS], ko[LPO_MAX_KINKS];
@@ -949,7 +956,7 @@ static void mlp_backward_choice(const lpo_mlp* m, const double* act, const doubl
     if (nk == 0) {
         for (int c = 0; c < n_out; ++c) dact[nact - n_out + c] = dout[c];
         mlp_backward_sample(m, act, pre, nact, dact, dW, db, 0, NULL, NULL, 0u);
-        for (int k = 0; k < n_in; ++k) din[k] = dact[k];
+        for (int k = 0; k < n_in; ++k) din[k] = din_other[k] = dact[k];
         return;
     }
     for (unsigned mask = 0; mask < (1u << nk); ++mask) {
@@ -984,7 +991,7 @@ static void mlp_backward_choice(const lpo_mlp* m, const double* act, const doubl
         for (int64_t k = 0; k < n; ++k) dW[l][k] += kt->W[pick][l][k];
         for (int k = 0; k < m->dims[l + 1]; ++k) db[l][k] += kt->b[pick][l][k];
     }
-    for (int k = 0; k < n_in; ++k) din[k] = kt->dact[pick][k];
+    for (int k = 0; k < n_in; ++k) { din[k] = kt->dact[pick][k]; din_other[k] = kt->dact[1 - pick][k]; }
 }
 
 /* Reverse of dec_ray_forward, operation by operation.  The two MLPs of a sample choose their
@@ -1004,6 +1011,8 @@ static void dec_ray_backward(const lpo_grid* g, const lpo_decoder* dc, const lpo
     double* din_s = dact_v + r->na_v;        /* [C]     */
     double* din_v = din_s + C;               /* [C + E] */
     double* dout_v = din_v + (C + r->E);     /* [F]     */
+    double* oth_s = dout_v + F;              /* [C]     the other side of the envelope of din_s */
+    double* oth_v = oth_s + C;               /* [C + E] ... of din_v */
     for (int j = 0; j <= S; ++j) dT[j] = 0.0;
     dT[S] += -p_alpha;
     for (int k = 0; k < F; ++k) dT[S] += p_out[k] * bg[k];
@@ -1026,11 +1035,11 @@ static void dec_ray_backward(const lpo_grid* g, const lpo_decoder* dc, const lpo
             dout_v[k] = dc->feat_act == 0 ? df * f * (1.0 - f) : df;
         }
         mlp_backward_choice(&dc->opacity, as, r->pre_s + (size_t)j * r->na_s, r->na_s, &dout_s, band, side,
-                            kts, dWs, dbs, dact_s, din_s);
+                            kts, dWs, dbs, dact_s, din_s, oth_s);
         mlp_backward_choice(&dc->color, av, r->pre_v + (size_t)j * r->na_v, r->na_v, dout_v, band, side,
-                            ktv, dWv, dbv, dact_v, din_v);
-        for (int k = 0; k < C; ++k) din_s[k] += din_v[k];
-        grid_scatter(g, d_grid, b, r->x + 3 * j, ray_time(g, rays, i), din_s);
+                            ktv, dWv, dbv, dact_v, din_v, oth_v);
+        for (int k = 0; k < C; ++k) { din_s[k] += din_v[k]; oth_s[k] += oth_v[k]; }
+        grid_scatter(g, d_grid, b, r->x + 3 * j, ray_time(g, rays, i), din_s, side != 0 ? oth_s : NULL);
     }
 }
 
@@ -1051,7 +1060,7 @@ int lpo_render2_bwd(const lpo_grid* g, const lpo_decoder* dc, const lpo_rays* ra
     {
         dec_tape r;
         kink_tmp kts, ktv;
-        double* scratch = (double*)malloc(sizeof(double) * (size_t)(rays->S + 1 + na_s + na_v + 2 * C + E + F));
+        double* scratch = (double*)malloc(sizeof(double) * (size_t)(rays->S + 1 + na_s + na_v + 4 * C + 2 * E + F));
         double* tWs[LPO_MAX_LAYERS] = {NULL};
         double* tbs[LPO_MAX_LAYERS] = {NULL};
         double* tWv[LPO_MAX_LAYERS] = {NULL};
@@ -1222,8 +1231,8 @@ int lpo_splat_fwd(const lpo_grid* tgt, const lpo_rays* rays, const lpo_splat* sp
                         mlp_forward(sp->mlp, act, pre);
                         vt = act + nact - C;
                     }
-                    grid_scatter(tgt, theta, b, x, 0.0, vt);
-                    grid_scatter(&wgrid, theta_w, b, x, 0.0, &one);
+                    grid_scatter(tgt, theta, b, x, 0.0, vt, NULL);
+                    grid_scatter(&wgrid, theta_w, b, x, 0.0, &one, NULL);
                 }
             }
         }
@@ -1276,6 +1285,7 @@ int lpo_splat_bwd(const lpo_grid* tgt, const lpo_rays* rays, const lpo_splat* sp
         double* pre = (double*)malloc(sizeof(double) * (size_t)(nact + 1));
         double* dact = (double*)malloc(sizeof(double) * (size_t)(nact + 1));
         double* din = (double*)malloc(sizeof(double) * (size_t)(nact + 1));
+        double* din_other = (double*)malloc(sizeof(double) * (size_t)(nact + 1)); /* unused: no HexPlane here */
         double* dvt = (double*)malloc(sizeof(double) * (size_t)C);
         double* tW[LPO_MAX_LAYERS] = {NULL};
         double* tb[LPO_MAX_LAYERS] = {NULL};
@@ -1310,9 +1320,9 @@ int lpo_splat_bwd(const lpo_grid* tgt, const lpo_rays* rays, const lpo_splat* sp
                     }
                     splat_inputs(rays, sp, i, b, x, act);
                     mlp_forward(m, act, pre);
-                    mlp_backward_choice(m, act, pre, nact, dvt, band, side, &kt, tW, tb, dact, din);
+                    mlp_backward_choice(m, act, pre, nact, dvt, band, side, &kt, tW, tb, dact, din, din_other);
                     for (int k = 0; k < n_in; ++k) d_feats[(size_t)i * n_in + k] += din[k];
-                    if (sp->prior) grid_scatter(sp->prior, d_prior, b, x, 0.0, din + n_in);
+                    if (sp->prior) grid_scatter(sp->prior, d_prior, b, x, 0.0, din + n_in, NULL);
                 }
             }
             if (m) {
@@ -1325,7 +1335,7 @@ int lpo_splat_bwd(const lpo_grid* tgt, const lpo_rays* rays, const lpo_splat* sp
             }
         }
         for (int l = 0; l < LPO_MAX_LAYERS; ++l) { free(tW[l]); free(tb[l]); }
-        free(act); free(pre); free(dact); free(din); free(dvt);
+        free(act); free(pre); free(dact); free(din); free(din_other); free(dvt);
         if (m) kink_free(&kt);
     }
     for (int p = 0; p < 3; ++p) free(gbuf[p]);

@@ -22,7 +22,7 @@ LIB_PATH = os.environ.get("LP_LIB_PATH", os.path.join(_HERE, "liblightplane.so")
 
 LP_MAX_LAYERS = 8
 LP_OK, LP_ERR_INVALID_ARG, LP_ERR_UNSUPPORTED, LP_ERR_HIP, LP_ERR_WORKSPACE = range(5)
-LP_GRID_VOXEL, LP_GRID_TRIPLANE, LP_GRID_HASH = 0, 1, 2
+LP_GRID_VOXEL, LP_GRID_TRIPLANE, LP_GRID_HASH, LP_GRID_HEXPLANE = 0, 1, 2, 3
 LP_MATH_DEFAULT, LP_MATH_GENERIC, LP_MATH_BF16X3 = 0, 1, 2
 LP_FEAT_SIGMOID, LP_FEAT_IDENTITY = 0, 1
 LP_F32, LP_BF16, LP_F16 = 0, 1, 2
@@ -39,7 +39,8 @@ class _Grid(C.Structure):
                 ("NX", C.c_int32), ("NY", C.c_int32), ("NZ", C.c_int32),
                 ("data", C.c_void_p * 3),
                 ("aabb_min", C.c_float * 3), ("aabb_max", C.c_float * 3), ("contract_a", C.c_float),
-                ("dtype", C.c_int32), ("hash_size", C.c_int64)]
+                ("dtype", C.c_int32), ("hash_size", C.c_int64),
+                ("data_t", C.c_void_p * 3), ("NT", C.c_int32), ("t_min", C.c_float), ("t_max", C.c_float)]
 
 
 class _Mlp(C.Structure):
@@ -60,7 +61,7 @@ class _Splat(C.Structure):
 class _Rays(C.Structure):
     _fields_ = [("M", C.c_int64), ("S", C.c_int32),
                 ("origins", C.c_void_p), ("dirs", C.c_void_p),
-                ("near", C.c_void_p), ("far", C.c_void_p), ("scene", C.c_void_p)]
+                ("near", C.c_void_p), ("far", C.c_void_p), ("scene", C.c_void_p), ("time", C.c_void_p)]
 
 
 def _load() -> C.CDLL:
@@ -151,13 +152,16 @@ _GRID_DTYPES = {torch.float32: LP_F32, torch.bfloat16: LP_BF16, torch.float16: L
 class Grid:
     """Voxel grid [B][NX][NY][NZ][C] (one tensor), triplane (three tensors [B][NX][NY][C],
     [B][NY][NZ][C], [B][NZ][NX][C]) or hash table [B][T][C] (one tensor; res = the virtual lattice
-    whose corners are hashed into it); float32, bfloat16 or float16 (all tensors alike), on the GPU."""
+    whose corners are hashed into it) or HexPlane (six tensors: the triplane's three, then the
+    space-time planes [B][NZ][NT][C], [B][NX][NT][C], [B][NY][NT][C]; t_range = the times of the first
+    and last index of the time axis); float32, bfloat16 or float16 (all tensors alike), on the GPU."""
     kind: int
     data: List[torch.Tensor]
     res: Sequence[int]
     aabb_min: Sequence[float] = (-1.0, -1.0, -1.0)
     aabb_max: Sequence[float] = (1.0, 1.0, 1.0)
     contract_a: float = 0.0
+    t_range: Sequence[float] = (0.0, 1.0)
 
     @property
     def n_scenes(self) -> int:
@@ -174,7 +178,13 @@ class Grid:
             return [(b, nx, ny, nz, c)]
         if self.kind == LP_GRID_HASH:
             return [(b, int(self.data[0].shape[1]), c)]
-        return [(b, nx, ny, c), (b, ny, nz, c), (b, nz, nx, c)]
+        planes = [(b, nx, ny, c), (b, ny, nz, c), (b, nz, nx, c)]
+        if self.kind == LP_GRID_HEXPLANE:
+            if len(self.data) != 6:
+                raise ValueError("a HexPlane has six tensors")
+            nt = int(self.data[3].shape[2])
+            planes += [(b, nz, nt, c), (b, nx, nt, c), (b, ny, nt, c)]
+        return planes
 
     def c_struct(self) -> _Grid:
         g = _Grid()
@@ -192,7 +202,13 @@ class Grid:
             if not (t.is_cuda and t.dtype == dt and t.is_contiguous() and tuple(t.shape) == tuple(s)):
                 raise ValueError(f"grid.data[{p}] must be a contiguous GPU tensor of shape {tuple(s)} and the "
                                  "dtype of grid.data[0]")
-            g.data[p] = t.data_ptr()
+            if p < 3:
+                g.data[p] = t.data_ptr()
+            else:
+                g.data_t[p - 3] = t.data_ptr()
+        if self.kind == LP_GRID_HEXPLANE:
+            g.NT = int(self.data[3].shape[2])
+            g.t_min, g.t_max = float(self.t_range[0]), float(self.t_range[1])
         for a in range(3):
             g.aabb_min[a] = float(self.aabb_min[a])
             g.aabb_max[a] = float(self.aabb_max[a])
@@ -249,6 +265,7 @@ class Rays:
     far: torch.Tensor              # [M]
     samples: int                   # S
     scene: Optional[torch.Tensor] = None  # [M] int32
+    time: Optional[torch.Tensor] = None   # [M] float32, the time of every ray (read by a HexPlane only)
 
     @property
     def n_rays(self) -> int:
@@ -267,6 +284,8 @@ class Rays:
             if not (s.is_cuda and s.dtype == torch.int32 and s.is_contiguous() and tuple(s.shape) == (m,)):
                 raise ValueError("scene must be a contiguous int32 GPU tensor of shape [M]")
             r.scene = s.data_ptr()
+        if self.time is not None:
+            r.time = _dev_f32(self.time, "time", (m,))
         return r
 
 
@@ -362,8 +381,8 @@ def _render_bwd(grid, mlp, rays, bg, d_rgb, d_alpha, d_depth, ray_cache, d_grid,
     shapes = grid.shapes()
     if len(d_grid) != len(shapes):
         raise ValueError("d_grid needs one tensor per grid tensor")
-    dg = (C.c_void_p * 3)(*[_dev_f32(d_grid[p], f"d_grid[{p}]", shapes[p]) if p < len(shapes) else None
-                            for p in range(3)])
+    dg = (C.c_void_p * 6)(*[_dev_f32(d_grid[p], f"d_grid[{p}]", shapes[p]) if p < len(shapes) else None
+                            for p in range(6)])
     dims = mlp.dims
     if len(dW) != len(mlp.weights) or len(db) != len(mlp.weights):
         raise ValueError("dW / db need one tensor per layer")
@@ -427,8 +446,8 @@ def lp_render_dec_bwd(grid: Grid, dec: Decoder, rays: Rays, bg, d_out: torch.Ten
     shapes = grid.shapes()
     if len(d_grid) != len(shapes):
         raise ValueError("d_grid needs one tensor per grid tensor")
-    dg = (C.c_void_p * 3)(*[_dev_f32(d_grid[p], f"d_grid[{p}]", shapes[p]) if p < len(shapes) else None
-                            for p in range(3)])
+    dg = (C.c_void_p * 6)(*[_dev_f32(d_grid[p], f"d_grid[{p}]", shapes[p]) if p < len(shapes) else None
+                            for p in range(6)])
 
     def lists(mlp, dW, db, name):
         dims = mlp.dims
@@ -564,10 +583,11 @@ def to_device(inp, device="cuda:0"):
     up = lambda a: torch.from_numpy(a).to(dev)
     grid = Grid(kind=int(inp.kind), data=[up(g) for g in inp.grid], res=tuple(inp.res),
                 aabb_min=tuple(inp.aabb_min), aabb_max=tuple(inp.aabb_max),
-                contract_a=float(getattr(inp, "contract_a", 0.0)))
+                contract_a=float(getattr(inp, "contract_a", 0.0)), t_range=tuple(getattr(inp, "t_range", (0.0, 1.0))))
     mlp = Mlp(weights=[up(w) for w in inp.weights], biases=[up(b) for b in inp.biases])
     rays = Rays(origins=up(inp.origins), dirs=up(inp.dirs), near=up(inp.near), far=up(inp.far),
-                samples=int(inp.samples), scene=None if inp.scene is None else up(inp.scene))
+                samples=int(inp.samples), scene=None if inp.scene is None else up(inp.scene),
+                time=None if getattr(inp, "time", None) is None else up(inp.time))
     return grid, mlp, rays, tuple(float(v) for v in inp.bg)
 
 

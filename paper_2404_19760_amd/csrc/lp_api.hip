@@ -46,14 +46,23 @@ int compute_units(int* out_n_cu, std::string* err)
 lp_status validate(const lp_grid* grid, const lp_mlp* mlp, const lp_rays* rays)
 {
     if (!grid || !mlp || !rays) return fail(LP_ERR_INVALID_ARG, "grid, mlp and rays must not be NULL");
-    if (grid->kind != LP_GRID_VOXEL && grid->kind != LP_GRID_TRIPLANE && grid->kind != LP_GRID_HASH)
-        return fail(LP_ERR_INVALID_ARG, "grid->kind must be LP_GRID_VOXEL, LP_GRID_TRIPLANE or LP_GRID_HASH");
+    if (grid->kind != LP_GRID_VOXEL && grid->kind != LP_GRID_TRIPLANE && grid->kind != LP_GRID_HASH &&
+        grid->kind != LP_GRID_HEXPLANE)
+        return fail(LP_ERR_INVALID_ARG,
+                    "grid->kind must be LP_GRID_VOXEL, LP_GRID_TRIPLANE, LP_GRID_HASH or LP_GRID_HEXPLANE");
+    if (grid->kind == LP_GRID_HEXPLANE) {
+        if (grid->NT < 2) return fail(LP_ERR_INVALID_ARG, "grid->NT must be >= 2 for a HexPlane");
+        if (!std::isfinite(grid->t_min) || !std::isfinite(grid->t_max) || !(grid->t_max > grid->t_min))
+            return fail(LP_ERR_INVALID_ARG, "grid->t_max must exceed grid->t_min (finite values)");
+        for (int p = 0; p < 3; ++p)
+            if (!grid->data_t[p]) return fail(LP_ERR_INVALID_ARG, "grid->data_t has a NULL tensor");
+    }
     if (grid->kind == LP_GRID_HASH && (grid->hash_size < 1 || grid->hash_size >= (1ll << 31)))
         return fail(LP_ERR_INVALID_ARG, "grid->hash_size must be in [1, 2^31) for a hash table");
     if (grid->B < 1 || grid->C < 1) return fail(LP_ERR_INVALID_ARG, "grid->B and grid->C must be >= 1");
     if (grid->NX < 2 || grid->NY < 2 || grid->NZ < 2)
         return fail(LP_ERR_INVALID_ARG, "every grid resolution must be >= 2");
-    const int n_planes = grid->kind == LP_GRID_TRIPLANE ? 3 : 1;
+    const int n_planes = (grid->kind == LP_GRID_TRIPLANE || grid->kind == LP_GRID_HEXPLANE) ? 3 : 1;
     for (int p = 0; p < n_planes; ++p)
         if (!grid->data[p]) return fail(LP_ERR_INVALID_ARG, "grid->data has a NULL tensor");
     for (int a = 0; a < 3; ++a) {
@@ -95,6 +104,12 @@ void to_device_views(const lp_grid* grid, const lp_mlp* mlp, const lp_rays* rays
     g->contract = (double)grid->contract_a;
     g->dtype = grid->dtype;
     g->hash_size = grid->kind == LP_GRID_HASH ? (unsigned)grid->hash_size : 0u;
+    if (grid->kind == LP_GRID_HEXPLANE) {
+        for (int p = 0; p < 3; ++p) g->data_t[p] = grid->data_t[p];
+        g->NT = grid->NT;
+        g->tmin = (double)grid->t_min;
+        g->tscale = (double)(grid->NT - 1) / ((double)grid->t_max - (double)grid->t_min);
+    }
     std::memset(m, 0, sizeof(*m));
     m->n_layers = mlp->n_layers;
     int off = 0, maxw = 0, act = 0;
@@ -116,6 +131,7 @@ void to_device_views(const lp_grid* grid, const lp_mlp* mlp, const lp_rays* rays
     r->M = rays->M; r->S = rays->S;
     r->origins = rays->origins; r->dirs = rays->dirs; r->near = rays->near; r->far = rays->far;
     r->scene = rays->scene;
+    r->time = rays->time;
 }
 
 enum class Path { Generic, Mfma };
@@ -338,8 +354,8 @@ lp_status splat_views(const lp_grid* target, const lp_rays* rays, const lp_splat
     }
     lp_status st = validate(target ? &tgt_checked : nullptr, &stand_in, rays);
     if (st != LP_OK) return st;
-    if (target->kind == LP_GRID_HASH)
-        return fail(LP_ERR_UNSUPPORTED, "the Splatter writes voxel grids and triplanes, not hash tables");
+    if (target->kind == LP_GRID_HASH || target->kind == LP_GRID_HEXPLANE)
+        return fail(LP_ERR_UNSUPPORTED, "the Splatter writes voxel grids and triplanes, not hash tables or HexPlanes");
     if (sp->n_in < 1) return fail(LP_ERR_INVALID_ARG, "splat->n_in must be >= 1");
     if (rays->M > 0 && !sp->feats) return fail(LP_ERR_INVALID_ARG, "splat->feats must not be NULL");
     if (sp->n_freq < -1 || sp->n_freq > 4) return fail(LP_ERR_INVALID_ARG, "splat->n_freq must be in [-1, 4]");
@@ -436,7 +452,7 @@ lp_status static_scratch_ptr(void** out)
 // lp_render_bwd with the partial-sum records in `workspace` (the caller's, or the static scratch)
 lp_status render_bwd_with(const lp_grid* grid, const lp_mlp* mlp, const lp_rays* rays,
                           const float bg[3], const float* d_rgb, const float* d_alpha,
-                          const float* d_depth, const float* ray_cache, float* const d_grid[3],
+                          const float* d_depth, const float* ray_cache, float* const d_grid[],
                           float* const dW[LP_MAX_LAYERS], float* const db[LP_MAX_LAYERS],
                           void* workspace, size_t workspace_bytes, bool static_scratch, int32_t math_mode,
                           void* stream)
@@ -445,8 +461,9 @@ lp_status render_bwd_with(const lp_grid* grid, const lp_mlp* mlp, const lp_rays*
 
     if (st != LP_OK) return st;
     if (!bg || !d_grid || !dW || !db) return fail(LP_ERR_INVALID_ARG, "bg, d_grid, dW and db must not be NULL");
-    const int n_planes = grid->kind == LP_GRID_TRIPLANE ? 3 : 1;
-    for (int p = 0; p < n_planes; ++p)
+    const bool hexplane = grid->kind == LP_GRID_HEXPLANE;   // six gradient tensors: d_grid[3 + p] for data_t[p]
+    const int n_planes = (grid->kind == LP_GRID_TRIPLANE || hexplane) ? 3 : 1;
+    for (int p = 0; p < (hexplane ? 6 : n_planes); ++p)
         if (!d_grid[p]) return fail(LP_ERR_INVALID_ARG, "d_grid has a NULL tensor");
     for (int l = 0; l < mlp->n_layers; ++l)
         if (!dW[l] || !db[l]) return fail(LP_ERR_INVALID_ARG, "dW / db has a NULL layer");
@@ -483,6 +500,7 @@ lp_status render_bwd_with(const lp_grid* grid, const lp_mlp* mlp, const lp_rays*
     std::memset(&io, 0, sizeof(io));
     io.d_rgb = d_rgb; io.d_alpha = d_alpha; io.d_depth = d_depth; io.cache = ray_cache;
     for (int p = 0; p < 3; ++p) io.d_grid[p] = p < n_planes ? d_grid[p] : nullptr;
+    for (int p = 0; p < 3; ++p) io.d_grid_t[p] = hexplane ? d_grid[3 + p] : nullptr;
     for (int l = 0; l < mlp->n_layers; ++l) { io.dW[l] = dW[l]; io.db[l] = db[l]; }
     for (int c = 0; c < 3; ++c) io.bg[c] = bg[c];
     io.ws = (float*)workspace;
@@ -560,7 +578,7 @@ lp_status lp_bwd_workspace_bytes(const lp_grid* grid, const lp_mlp* mlp, const l
 
 lp_status lp_render_bwd(const lp_grid* grid, const lp_mlp* mlp, const lp_rays* rays,
                         const float bg[3], const float* d_rgb, const float* d_alpha,
-                        const float* d_depth, const float* ray_cache, float* const d_grid[3],
+                        const float* d_depth, const float* ray_cache, float* const d_grid[],
                         float* const dW[LP_MAX_LAYERS], float* const db[LP_MAX_LAYERS],
                         void* workspace, size_t workspace_bytes, int32_t math_mode, void* stream)
 {
@@ -570,7 +588,7 @@ lp_status lp_render_bwd(const lp_grid* grid, const lp_mlp* mlp, const lp_rays* r
 
 lp_status lp_render_bwd_static(const lp_grid* grid, const lp_mlp* mlp, const lp_rays* rays,
                                const float bg[3], const float* d_rgb, const float* d_alpha,
-                               const float* d_depth, const float* ray_cache, float* const d_grid[3],
+                               const float* d_depth, const float* ray_cache, float* const d_grid[],
                                float* const dW[LP_MAX_LAYERS], float* const db[LP_MAX_LAYERS],
                                int32_t math_mode, void* stream)
 {
@@ -669,7 +687,7 @@ lp_status lp_render_dec_fwd(const lp_grid* grid, const lp_decoder* dec, const lp
 
 lp_status lp_render_dec_bwd(const lp_grid* grid, const lp_decoder* dec, const lp_rays* rays,
                             const float* bg, const float* d_out, const float* d_alpha,
-                            const float* d_depth, const float* ray_cache, float* const d_grid[3],
+                            const float* d_depth, const float* ray_cache, float* const d_grid[],
                             float* const dW_opacity[LP_MAX_LAYERS], float* const db_opacity[LP_MAX_LAYERS],
                             float* const dW_feature[LP_MAX_LAYERS], float* const db_feature[LP_MAX_LAYERS],
                             void* workspace, size_t workspace_bytes, int32_t math_mode, void* stream)
@@ -679,8 +697,9 @@ lp_status lp_render_dec_bwd(const lp_grid* grid, const lp_decoder* dec, const lp
     if (st != LP_OK) return st;
     if (!bg || !d_grid || !dW_opacity || !db_opacity || !dW_feature || !db_feature)
         return fail(LP_ERR_INVALID_ARG, "bg, d_grid and the four gradient lists must not be NULL");
-    const int n_planes = grid->kind == LP_GRID_TRIPLANE ? 3 : 1;
-    for (int p = 0; p < n_planes; ++p)
+    const bool hexplane = grid->kind == LP_GRID_HEXPLANE;   // six gradient tensors: d_grid[3 + p] for data_t[p]
+    const int n_planes = (grid->kind == LP_GRID_TRIPLANE || hexplane) ? 3 : 1;
+    for (int p = 0; p < (hexplane ? 6 : n_planes); ++p)
         if (!d_grid[p]) return fail(LP_ERR_INVALID_ARG, "d_grid has a NULL tensor");
     for (int l = 0; l < dec->opacity.n_layers; ++l)
         if (!dW_opacity[l] || !db_opacity[l]) return fail(LP_ERR_INVALID_ARG, "dW_opacity / db_opacity has a NULL layer");
@@ -728,6 +747,7 @@ lp_status lp_render_dec_bwd(const lp_grid* grid, const lp_decoder* dec, const lp
     std::memset(&io, 0, sizeof(io));
     io.d_rgb = d_out; io.d_alpha = d_alpha; io.d_depth = d_depth; io.cache = ray_cache;
     for (int p = 0; p < 3; ++p) io.d_grid[p] = p < n_planes ? d_grid[p] : nullptr;
+    for (int p = 0; p < 3; ++p) io.d_grid_t[p] = hexplane ? d_grid[3 + p] : nullptr;
     for (int l = 0; l < m.n_layers; ++l) { io.dW[l] = grads + m.w_off[l]; io.db[l] = grads + m.b_off[l]; }
     for (int c = 0; c < dec->n_feat; ++c) io.bg[c] = bg[c];
     io.ws = (float*)((char*)workspace + 2 * params);

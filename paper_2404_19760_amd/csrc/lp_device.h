@@ -19,6 +19,10 @@ struct GridDev {
     double scale[3];  // (N-1)/(max-min): world -> continuous index
     double contract;  // foreground scale a of the contract coordinates, 0 = off
     unsigned hash_size;  // LP_GRID_HASH: entries of one scene's table
+    // LP_GRID_HEXPLANE: the space-time planes (pair p: plane data[p] with data_t[p] over (axis p + 2, time))
+    const void* data_t[3];
+    int NT;
+    double tmin, tscale;  // (NT-1)/(t_max-t_min)
 };
 
 struct MlpDev {
@@ -47,6 +51,7 @@ struct RaysDev {
     const float* near;
     const float* far;
     const int* scene;
+    const float* time;  // per ray, or null (LP_GRID_HEXPLANE)
 };
 
 struct FwdOut {
@@ -63,6 +68,7 @@ struct BwdIo {
     const float* d_depth;
     const float* cache;
     float* d_grid[3];
+    float* d_grid_t[3];  // LP_GRID_HEXPLANE: gradients of the space-time planes
     float* dW[LP_MAX_LAYERS];
     float* db[LP_MAX_LAYERS];
     float bg[LP_MAX_FEATURES];

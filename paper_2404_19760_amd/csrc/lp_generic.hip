@@ -33,6 +33,9 @@ struct Cell {
     int i[3];
     float f[3];
     float g[3];  // 1 - f, rounded from the fp64 index
+    // the ray's time on the time axis of a HexPlane (unset for the other structures)
+    int it;
+    float ft, gt;
 };
 
 __device__ __forceinline__ Cell locate(const GridDev& g, double x, double y, double z)
@@ -79,6 +82,26 @@ __device__ void gather_feat(const GridDev& g, int scene, const Cell& c, float* f
             }
             feat[k * block_lanes() + lane] = acc;
         }
+    } else if (g.kind == LP_GRID_HEXPLANE) {
+        // pair p: the spatial plane over axes (a, b) = (0,1), (1,2), (2,0) times the space-time plane
+        // over (c, time), c the third axis; the three products are added
+        for (int k = 0; k < C; ++k) {
+            float acc = 0.0f;
+            for (int p = 0; p < 3; ++p) {
+                const int a = p, b = (p + 1) % 3, cc = (p + 2) % 3;
+                const size_t P = (size_t)scene * g.N[a] * g.N[b] * C, Q = (size_t)scene * g.N[cc] * g.NT * C;
+                float s = 0.0f, u = 0.0f;
+                for (int d = 0; d < 4; ++d) {
+                    const int da = d >> 1, db = d & 1;
+                    s += (da ? c.f[a] : c.g[a]) * (db ? c.f[b] : c.g[b]) *
+                         grid_load(g, g.data[p], P + ((size_t)(c.i[a] + da) * g.N[b] + (c.i[b] + db)) * C + k);
+                    u += (da ? c.f[cc] : c.g[cc]) * (db ? c.ft : c.gt) *
+                         grid_load(g, g.data_t[p], Q + ((size_t)(c.i[cc] + da) * g.NT + (c.it + db)) * C + k);
+                }
+                acc += s * u;
+            }
+            feat[k * block_lanes() + lane] = acc;
+        }
     } else {
         // plane p spans axes (a, b) = (0,1), (1,2), (2,0)
         for (int k = 0; k < C; ++k) {
@@ -98,8 +121,10 @@ __device__ void gather_feat(const GridDev& g, int scene, const Cell& c, float* f
 }
 
 // d_grid[corner] += weight * dfeat  — the transpose of gather_feat, same corners and weights.
+// (HexPlane: d_grid_t holds the gradients of the space-time planes; by the product rule each plane
+// of a pair receives dfeat times the other plane's read, which is formed again here)
 __device__ void scatter_feat(const GridDev& g, float* const d_grid[3], int scene, const Cell& c,
-                             const float* dfeat, int lane)
+                             const float* dfeat, int lane, float* const d_grid_t[3] = nullptr)
 {
     const int C = g.C;
     if (g.kind == LP_GRID_VOXEL) {
@@ -120,6 +145,31 @@ __device__ void scatter_feat(const GridDev& g, float* const d_grid[3], int scene
                             (dz ? c.f[2] : c.g[2]);
             const size_t off = (size_t)hash_slot(c.i[0] + dx, c.i[1] + dy, c.i[2] + dz, g.hash_size) * C;
             for (int k = 0; k < C; ++k) atomicAdd(V + off + k, w * dfeat[k * block_lanes() + lane]);
+        }
+    } else if (g.kind == LP_GRID_HEXPLANE) {
+        for (int p = 0; p < 3; ++p) {
+            const int a = p, b = (p + 1) % 3, cc = (p + 2) % 3;
+            const size_t Ps = (size_t)scene * g.N[a] * g.N[b] * C, Qs = (size_t)scene * g.N[cc] * g.NT * C;
+            float* P = d_grid[p] + Ps;
+            float* Q = d_grid_t[p] + Qs;
+            for (int k = 0; k < C; ++k) {
+                float s = 0.0f, u = 0.0f;
+                for (int d = 0; d < 4; ++d) {
+                    const int da = d >> 1, db = d & 1;
+                    s += (da ? c.f[a] : c.g[a]) * (db ? c.f[b] : c.g[b]) *
+                         grid_load(g, g.data[p], Ps + ((size_t)(c.i[a] + da) * g.N[b] + (c.i[b] + db)) * C + k);
+                    u += (da ? c.f[cc] : c.g[cc]) * (db ? c.ft : c.gt) *
+                         grid_load(g, g.data_t[p], Qs + ((size_t)(c.i[cc] + da) * g.NT + (c.it + db)) * C + k);
+                }
+                const float df = dfeat[k * block_lanes() + lane];
+                for (int d = 0; d < 4; ++d) {
+                    const int da = d >> 1, db = d & 1;
+                    atomicAdd(P + ((size_t)(c.i[a] + da) * g.N[b] + (c.i[b] + db)) * C + k,
+                              (da ? c.f[a] : c.g[a]) * (db ? c.f[b] : c.g[b]) * (df * u));
+                    atomicAdd(Q + ((size_t)(c.i[cc] + da) * g.NT + (c.it + db)) * C + k,
+                              (da ? c.f[cc] : c.g[cc]) * (db ? c.ft : c.gt) * (df * s));
+                }
+            }
         }
     } else {
         for (int p = 0; p < 3; ++p) {
@@ -159,14 +209,18 @@ struct RayRegs {
     float o[3], d[3], near, delta;
     double delta64;
     int scene;
+    float time;  // read by a HexPlane only
 };
 
 // cell of sample j: position in fp64 from the fp32 ray
 __device__ __forceinline__ Cell sample_cell(const GridDev& g, const RayRegs& q, int j)
 {
     const double t = (double)q.near + ((double)j + 0.5) * q.delta64;
-    return locate(g, (double)q.o[0] + t * (double)q.d[0], (double)q.o[1] + t * (double)q.d[1],
-                  (double)q.o[2] + t * (double)q.d[2]);
+    Cell c = locate(g, (double)q.o[0] + t * (double)q.d[0], (double)q.o[1] + t * (double)q.d[1],
+                    (double)q.o[2] + t * (double)q.d[2]);
+    // the time axis is not contracted
+    if (g.kind == LP_GRID_HEXPLANE) axis_cell<false>((double)q.time, g.tmin, g.tscale, g.NT, 0.0, c.it, c.ft, c.gt);
+    return c;
 }
 
 __device__ __forceinline__ RayRegs load_ray(const RaysDev& r, long long ray)
@@ -180,6 +234,7 @@ __device__ __forceinline__ RayRegs load_ray(const RaysDev& r, long long ray)
     q.delta64 = ((double)r.far[ray] - (double)q.near) / (double)r.S;
     q.delta = (float)q.delta64;
     q.scene = r.scene ? r.scene[ray] : 0;
+    q.time = r.time ? r.time[ray] : -INFINITY;  // no times given: clamps onto the first index, the grid's t_min
     return q;
 }
 
@@ -541,7 +596,7 @@ __global__ __launch_bounds__(kMaxLanes) void bwd_generic_kernel(GridDev g, MlpDe
             }
 
             dz = mlp_backward(m, sW, sdW, acts, dz, dz_next, lane);
-            if (live) scatter_feat(g, io.d_grid, q.scene, c, dz, lane);
+            if (live) scatter_feat(g, io.d_grid, q.scene, c, dz, lane, io.d_grid_t);
         }
     }
     __syncthreads();

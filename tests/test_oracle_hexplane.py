@@ -157,3 +157,32 @@ def test_time_is_clamped_and_defaults_to_the_first_time(oracle):
     np.testing.assert_array_equal(b, c)
     np.testing.assert_array_equal(oracle.render_fwd(late)[0], oracle.render_fwd(last)[0])
     assert np.abs(oracle.render_fwd(last)[0] - b).max() > 1e-3      # time matters
+
+
+@pytest.mark.parametrize("decoder", [False, True])
+def test_kink_envelope_brackets_the_definition(oracle, decoder):
+    """The feature gradient's envelope reaches the planes through products with signed plane reads: the
+    upper side must still lie above the definition, the lower side below it, on all six planes (a
+    wide band, so that many units fall inside it), and a vanishing band must collapse onto it."""
+    inp = _problem(seed=47, n_scenes=2)
+    assert min(float(g.min()) for g in inp.grid[:3]) < 0        # negative reads occur
+    rng = np.random.default_rng(8)
+    if decoder:
+        dec = lp_inputs.make_decoder(3, (5,), (6, 4), 1, 3, 48, 0.2, 0)
+        inp = dataclasses.replace(inp, decoder=dec)
+        p = rng.standard_normal((inp.n_rays, 3))
+        run = lambda band, side: oracle.render2_bwd(inp, p, kink_band=band, kink_side=side)[0]
+    else:
+        p = rng.standard_normal((inp.n_rays, 3))
+        run = lambda band, side: oracle.render_bwd(inp, p, kink_band=band, kink_side=side)[0]
+    base, lo, hi = run(0.0, 0), run(5e-2, -1), run(5e-2, +1)
+    wide = 0
+    for q in range(6):
+        tol = 1e-12 * np.abs(base[q]).max()
+        assert (lo[q] <= base[q] + tol).all() and (base[q] <= hi[q] + tol).all(), q
+        wide += int(((hi[q] - lo[q]) > 1e-6 * np.abs(base[q]).max()).sum())
+    assert wide > 0
+    for q, (a, b) in enumerate(zip(run(1e-15, +1), run(1e-15, -1))):
+        # (the scatter adds with atomics from several threads: equal up to the order of the sums)
+        np.testing.assert_allclose(a, base[q], rtol=1e-12, atol=1e-15)
+        np.testing.assert_allclose(b, base[q], rtol=1e-12, atol=1e-15)
