@@ -40,10 +40,11 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # by 2.0, WRITE_SIZE by 1.0 against a 1 GiB copy kernel in the same run); the summary with the
 # commands is profiles/large_voxel256_fwd_bwd_kernels.md.  None = not measured for that workload.
 MEASURED_BWD_HBM_BYTES = {"large": 19.51e9 + 65.42e9}
-# 64-byte lines of atomic adds per launch of the backward kernel: its WRITE_SIZE (each atomic line
-# request is written through as 64 bytes; TCC_ATOMIC counts the same requests), same summaries
-# (large_voxel256_..., batched_triplane256_fwd_bwd_kernels.md).
-MEASURED_BWD_ATOMIC_LINES = {"large": 65.42e9 / 64, "batched": 257.0e9 / 64}
+# 64-byte lines of atomic adds per launch of the backward kernel: TCC_ATOMIC (each request is one line,
+# written through as 64 bytes: WRITE_SIZE / 64 gives the same number); profiles/atomic_line_rate.md.
+MEASURED_BWD_ATOMIC_LINES = {"large": 65.42e9 / 64, "batched": 257.0e9 / 64, "voxel": 171758784.0,
+                             "contract": 140152160.0, "single_scene": 15266496.0, "decoder": 52144736.0,
+                             "hash": 10885988.0}
 
 
 def parse():
