@@ -223,7 +223,7 @@ lp_status run_bwd(const lp::GridDev& g, const lp::MlpDev& m, const lp::RaysDev& 
         return LP_OK;
     }
     GenericShape shape;
-    if (!generic_shape(m, (size_t)m.act_total + 2 * (size_t)m.max_width + m.n_feat, true, &shape))
+    if (!generic_shape(m, (size_t)m.act_total + 2 * (size_t)m.max_width + m.n_feat + lp::kGenericCellColumns, true, &shape))
         return fail(LP_ERR_UNSUPPORTED, "MLP too large for the generic backward kernel's LDS budget");
     lp::BwdIo io = io_in;
     io.acc_in_record = shape.acc_in_record;

@@ -120,11 +120,11 @@ __device__ void gather_feat(const GridDev& g, int scene, const Cell& c, float* f
     }
 }
 
-// d_grid[corner] += weight * dfeat  — the transpose of gather_feat, same corners and weights.
-// (HexPlane: d_grid_t holds the gradients of the space-time planes; by the product rule each plane
-// of a pair receives dfeat times the other plane's read, which is formed again here)
-__device__ void scatter_feat(const GridDev& g, float* const d_grid[3], int scene, const Cell& c,
-                             const float* dfeat, int lane, float* const d_grid_t[3] = nullptr)
+// d_grid[corner][k] += weight * df for ONE channel k: the transpose of gather_feat, same corners and
+// weights.  (HexPlane: d_grid_t holds the gradients of the space-time planes; by the product rule each
+// plane of a pair receives df times the other plane's read, which is formed again here.)
+__device__ void scatter_channel(const GridDev& g, float* const d_grid[3], float* const d_grid_t[3], int scene,
+                                const Cell& c, int k, float df)
 {
     const int C = g.C;
     if (g.kind == LP_GRID_VOXEL) {
@@ -135,7 +135,7 @@ __device__ void scatter_feat(const GridDev& g, float* const d_grid[3], int scene
                             (dz ? c.f[2] : c.g[2]);
             const size_t off =
                 (((size_t)(c.i[0] + dx) * g.N[1] + (c.i[1] + dy)) * g.N[2] + (c.i[2] + dz)) * C;
-            for (int k = 0; k < C; ++k) atomicAdd(V + off + k, w * dfeat[k * block_lanes() + lane]);
+            atomicAdd(V + off + k, w * df);
         }
     } else if (g.kind == LP_GRID_HASH) {
         float* V = d_grid[0] + (size_t)scene * g.hash_size * C;
@@ -144,7 +144,7 @@ __device__ void scatter_feat(const GridDev& g, float* const d_grid[3], int scene
             const float w = (dx ? c.f[0] : c.g[0]) * (dy ? c.f[1] : c.g[1]) *
                             (dz ? c.f[2] : c.g[2]);
             const size_t off = (size_t)hash_slot(c.i[0] + dx, c.i[1] + dy, c.i[2] + dz, g.hash_size) * C;
-            for (int k = 0; k < C; ++k) atomicAdd(V + off + k, w * dfeat[k * block_lanes() + lane]);
+            atomicAdd(V + off + k, w * df);
         }
     } else if (g.kind == LP_GRID_HEXPLANE) {
         for (int p = 0; p < 3; ++p) {
@@ -152,23 +152,20 @@ __device__ void scatter_feat(const GridDev& g, float* const d_grid[3], int scene
             const size_t Ps = (size_t)scene * g.N[a] * g.N[b] * C, Qs = (size_t)scene * g.N[cc] * g.NT * C;
             float* P = d_grid[p] + Ps;
             float* Q = d_grid_t[p] + Qs;
-            for (int k = 0; k < C; ++k) {
-                float s = 0.0f, u = 0.0f;
-                for (int d = 0; d < 4; ++d) {
-                    const int da = d >> 1, db = d & 1;
-                    s += (da ? c.f[a] : c.g[a]) * (db ? c.f[b] : c.g[b]) *
-                         grid_load(g, g.data[p], Ps + ((size_t)(c.i[a] + da) * g.N[b] + (c.i[b] + db)) * C + k);
-                    u += (da ? c.f[cc] : c.g[cc]) * (db ? c.ft : c.gt) *
-                         grid_load(g, g.data_t[p], Qs + ((size_t)(c.i[cc] + da) * g.NT + (c.it + db)) * C + k);
-                }
-                const float df = dfeat[k * block_lanes() + lane];
-                for (int d = 0; d < 4; ++d) {
-                    const int da = d >> 1, db = d & 1;
-                    atomicAdd(P + ((size_t)(c.i[a] + da) * g.N[b] + (c.i[b] + db)) * C + k,
-                              (da ? c.f[a] : c.g[a]) * (db ? c.f[b] : c.g[b]) * (df * u));
-                    atomicAdd(Q + ((size_t)(c.i[cc] + da) * g.NT + (c.it + db)) * C + k,
-                              (da ? c.f[cc] : c.g[cc]) * (db ? c.ft : c.gt) * (df * s));
-                }
+            float s = 0.0f, u = 0.0f;
+            for (int d = 0; d < 4; ++d) {
+                const int da = d >> 1, db = d & 1;
+                s += (da ? c.f[a] : c.g[a]) * (db ? c.f[b] : c.g[b]) *
+                     grid_load(g, g.data[p], Ps + ((size_t)(c.i[a] + da) * g.N[b] + (c.i[b] + db)) * C + k);
+                u += (da ? c.f[cc] : c.g[cc]) * (db ? c.ft : c.gt) *
+                     grid_load(g, g.data_t[p], Qs + ((size_t)(c.i[cc] + da) * g.NT + (c.it + db)) * C + k);
+            }
+            for (int d = 0; d < 4; ++d) {
+                const int da = d >> 1, db = d & 1;
+                atomicAdd(P + ((size_t)(c.i[a] + da) * g.N[b] + (c.i[b] + db)) * C + k,
+                          (da ? c.f[a] : c.g[a]) * (db ? c.f[b] : c.g[b]) * (df * u));
+                atomicAdd(Q + ((size_t)(c.i[cc] + da) * g.NT + (c.it + db)) * C + k,
+                          (da ? c.f[cc] : c.g[cc]) * (db ? c.ft : c.gt) * (df * s));
             }
         }
     } else {
@@ -179,9 +176,63 @@ __device__ void scatter_feat(const GridDev& g, float* const d_grid[3], int scene
                 const int da = d >> 1, db = d & 1;
                 const float w = (da ? c.f[a] : c.g[a]) * (db ? c.f[b] : c.g[b]);
                 const size_t off = ((size_t)(c.i[a] + da) * g.N[b] + (c.i[b] + db)) * C;
-                for (int k = 0; k < C; ++k) atomicAdd(P + off + k, w * dfeat[k * block_lanes() + lane]);
+                atomicAdd(P + off + k, w * df);
             }
         }
+    }
+}
+
+// the lane's own sample: every channel of dfeat[k * lanes + lane]
+__device__ void scatter_feat(const GridDev& g, float* const d_grid[3], int scene, const Cell& c,
+                             const float* dfeat, int lane, float* const d_grid_t[3] = nullptr)
+{
+    for (int k = 0; k < g.C; ++k) scatter_channel(g, d_grid, d_grid_t, scene, c, k, dfeat[k * block_lanes() + lane]);
+}
+
+// The samples of a whole tile, channel by channel ACROSS lanes: consecutive lanes add consecutive
+// channels of one sample's corner, so that an atomic instruction covers whole lines of a few samples
+// instead of one float of 64 samples' lines.  `cells` holds kCellColumns columns [field][lane] with every
+// lane's cell (see publish_cell); dz the feature gradients [channel][lane].  All lanes call it.
+static_assert(kGenericCellColumns >= 14, "a cell has 14 fields");
+
+__device__ __forceinline__ void publish_cell(float* cells, int lane, const Cell& c, int scene, bool live)
+{
+    const int L = block_lanes();
+    int* ci = reinterpret_cast<int*>(cells);
+    for (int a = 0; a < 3; ++a) {
+        ci[a * L + lane] = c.i[a];
+        cells[(4 + a) * L + lane] = c.f[a];
+        cells[(8 + a) * L + lane] = c.g[a];
+    }
+    ci[3 * L + lane] = c.it;
+    cells[7 * L + lane] = c.ft;
+    cells[11 * L + lane] = c.gt;
+    ci[12 * L + lane] = scene;
+    ci[13 * L + lane] = live ? 1 : 0;
+}
+
+__device__ void scatter_tile(const GridDev& g, float* const d_grid[3], float* const d_grid_t[3], const float* cells,
+                             const float* dz, int lane)
+{
+    const int L = block_lanes(), C = g.C;
+    const int* ci = reinterpret_cast<const int*>(cells);
+    const int per_pass = C <= L ? L / C : 1;   // samples served by one pass over the lanes
+    const int sub = C <= L ? lane / C : 0;
+    for (int rb = 0; rb < L; rb += per_pass) {
+        const int r = rb + sub;
+        if (sub >= per_pass || r >= L || ci[13 * L + r] == 0) continue;
+        Cell c;
+        for (int a = 0; a < 3; ++a) {
+            c.i[a] = ci[a * L + r];
+            c.f[a] = cells[(4 + a) * L + r];
+            c.g[a] = cells[(8 + a) * L + r];
+        }
+        c.it = ci[3 * L + r];
+        c.ft = cells[7 * L + r];
+        c.gt = cells[11 * L + r];
+        const int scene = ci[12 * L + r];
+        for (int k = C <= L ? lane - sub * C : lane; k < C; k += L)   // (C <= L: the one channel of this lane)
+            scatter_channel(g, d_grid, d_grid_t, scene, c, k, dz[k * L + r]);
     }
 }
 
@@ -195,10 +246,40 @@ __device__ void mlp_forward(const MlpDev& m, const float* sW, float* acts, int l
         const float* W = sW + m.w_off[l];
         const float* B = sW + m.b_off[l];
         const bool hidden = l + 1 < m.n_layers;
-        for (int o = 0; o < nout; ++o) {
-            float z = B[o];
-            for (int k = 0; k < nin; ++k) z += W[o * nin + k] * acts[(off_in + k) * block_lanes() + lane];
-            acts[(off_out + o) * block_lanes() + lane] = hidden ? fmaxf(z, 0.0f) : z;
+        if ((nin & 3) == 0 && (m.w_off[l] & 3) == 0) {
+            // eight outputs at a time, four inputs per step: the lane's four activations are read once
+            // for eight rows of weights, and a row's four weights come as one 16-byte broadcast read
+            // (three LDS reads per eight multiply-adds instead of sixteen)
+            for (int o0 = 0; o0 < nout; o0 += 8) {
+                float z[8];
+                const float* row[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const int o = min(o0 + i, nout - 1);   // rows beyond the layer repeat its last row; not stored
+                    z[i] = B[o];
+                    row[i] = W + o * nin;
+                }
+                for (int k = 0; k < nin; k += 4) {
+                    const float a0 = acts[(off_in + k + 0) * block_lanes() + lane];
+                    const float a1 = acts[(off_in + k + 1) * block_lanes() + lane];
+                    const float a2 = acts[(off_in + k + 2) * block_lanes() + lane];
+                    const float a3 = acts[(off_in + k + 3) * block_lanes() + lane];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        const float4 w = *reinterpret_cast<const float4*>(row[i] + k);
+                        z[i] += w.x * a0 + w.y * a1 + w.z * a2 + w.w * a3;
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    if (o0 + i < nout) acts[(off_out + o0 + i) * block_lanes() + lane] = hidden ? fmaxf(z[i], 0.0f) : z[i];
+            }
+        } else {
+            for (int o = 0; o < nout; ++o) {
+                float z = B[o];
+                for (int k = 0; k < nin; ++k) z += W[o * nin + k] * acts[(off_in + k) * block_lanes() + lane];
+                acts[(off_out + o) * block_lanes() + lane] = hidden ? fmaxf(z, 0.0f) : z;
+            }
         }
         off_in = off_out;
         off_out += nout;
@@ -253,23 +334,87 @@ __device__ float* mlp_backward(const MlpDev& m, const float* sW, float* sdW, con
         __syncthreads();
         // weight and bias gradients: each lane owns a strided set of weights and sums
         // the outer product over the 64 rays of the tile
-        for (int idx = lane; idx < nin * nout; idx += block_lanes()) {
-            const int o = idx / nin, k = idx - o * nin;
-            float s = 0.0f;
-            for (int r = 0; r < block_lanes(); ++r) s += dz[o * block_lanes() + r] * acts[(off_in + k) * block_lanes() + r];
-            sdW[m.w_off[l] + idx] += s;
+        // (every lane walks the rays of the tile starting at its own lane number: the lanes read
+        // different rows at the same moment, and rows are a multiple of the LDS banks apart, so a
+        // common starting ray would put all of them on one bank)
+        const int L = block_lanes();
+        if ((nin & 3) == 0 && (nout & 3) == 0 && (L & 3) == 0 && (((uintptr_t)acts | (uintptr_t)dz) & 15u) == 0) {
+            // a lane owns 4 x 4 blocks of the weight matrix and reads four rays of a row at a time:
+            // eight 16-byte reads per 64 multiply-adds
+            const int tiles_k = nin >> 2, n_tiles = (nout >> 2) * tiles_k;
+            for (int tile = lane; tile < n_tiles; tile += L) {
+                const int o0 = (tile / tiles_k) << 2, k0 = (tile % tiles_k) << 2;
+                float acc[4][4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) acc[i][j] = 0.0f;
+                const int r0 = (4 * lane) % L;
+                for (int t = 0; t < L; t += 4) {
+                    int r = r0 + t;
+                    if (r >= L) r -= L;
+                    float4 d[4], a[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        d[i] = *reinterpret_cast<const float4*>(dz + (o0 + i) * L + r);
+                        a[i] = *reinterpret_cast<const float4*>(acts + (off_in + k0 + i) * L + r);
+                    }
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            acc[i][j] += d[i].x * a[j].x + d[i].y * a[j].y + d[i].z * a[j].z + d[i].w * a[j].w;
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) sdW[m.w_off[l] + (o0 + i) * nin + k0 + j] += acc[i][j];
+            }
+        } else {
+            for (int idx = lane; idx < nin * nout; idx += L) {
+                const int o = idx / nin, k = idx - o * nin;
+                float s = 0.0f;
+                for (int t = 0; t < L; ++t) {
+                    int r = lane + t;
+                    if (r >= L) r -= L;
+                    s += dz[o * L + r] * acts[(off_in + k) * L + r];
+                }
+                sdW[m.w_off[l] + idx] += s;
+            }
         }
         for (int o = lane; o < nout; o += block_lanes()) {
             float s = 0.0f;
-            for (int r = 0; r < block_lanes(); ++r) s += dz[o * block_lanes() + r];
+            for (int t = 0; t < block_lanes(); ++t) {
+                int r = lane + t;
+                if (r >= block_lanes()) r -= block_lanes();
+                s += dz[o * block_lanes() + r];
+            }
             sdW[m.b_off[l] + o] += s;
         }
         // input gradient of the lane's own column, through the ReLU of the layer below
-        for (int k = 0; k < nin; ++k) {
-            float s = 0.0f;
-            for (int o = 0; o < nout; ++o) s += W[o * nin + k] * dz[o * block_lanes() + lane];
-            if (l > 0 && !(acts[(off_in + k) * block_lanes() + lane] > 0.0f)) s = 0.0f;
-            dz_next[k * block_lanes() + lane] = s;
+        if ((nin & 3) == 0 && (m.w_off[l] & 3) == 0) {
+            // four inputs at a time: one 16-byte broadcast read of a weight row's four entries per output
+            for (int k = 0; k < nin; k += 4) {
+                float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
+                for (int o = 0; o < nout; ++o) {
+                    const float d = dz[o * block_lanes() + lane];
+                    const float4 w = *reinterpret_cast<const float4*>(W + o * nin + k);
+                    s0 += w.x * d; s1 += w.y * d; s2 += w.z * d; s3 += w.w * d;
+                }
+                const float sk[4] = {s0, s1, s2, s3};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const bool off = l > 0 && !(acts[(off_in + k + i) * block_lanes() + lane] > 0.0f);
+                    dz_next[(k + i) * block_lanes() + lane] = off ? 0.0f : sk[i];
+                }
+            }
+        } else {
+            for (int k = 0; k < nin; ++k) {
+                float s = 0.0f;
+                for (int o = 0; o < nout; ++o) s += W[o * nin + k] * dz[o * block_lanes() + lane];
+                if (l > 0 && !(acts[(off_in + k) * block_lanes() + lane] > 0.0f)) s = 0.0f;
+                dz_next[k * block_lanes() + lane] = s;
+            }
         }
         __syncthreads();
         float* tmp = dz; dz = dz_next; dz_next = tmp;
@@ -372,7 +517,7 @@ __device__ void set_splat_ray_inputs(const SplatDev& sp, const MlpDev& m, const 
 
 __global__ __launch_bounds__(kMaxLanes) void splat_fwd_generic_kernel(GridDev tgt, MlpDev m, RaysDev rays, SplatDev sp)
 {
-    extern __shared__ float smem[];
+    extern __shared__ __align__(16) float smem[];
     float* sW = smem;
     float* acts = smem + m.param_total;
     stage_params(m, sW);
@@ -417,7 +562,7 @@ __global__ void fill_zero_kernel(float* p, long long n)
 __global__ __launch_bounds__(kMaxLanes) void splat_bwd_generic_kernel(GridDev tgt, MlpDev m, RaysDev rays, SplatDev sp,
                                                                    BwdIo io, int tiles_per_block)
 {
-    extern __shared__ float smem[];
+    extern __shared__ __align__(16) float smem[];
     float* sW = smem;
     // gradient accumulators of the block: in LDS, or (MLPs whose two copies do not fit) directly in
     // the block's record in the workspace; every element has one owner lane either way
@@ -476,7 +621,7 @@ namespace {
 __global__ __launch_bounds__(kMaxLanes) void fwd_generic_kernel(GridDev g, MlpDev m, RaysDev rays,
                                                              FwdOut out)
 {
-    extern __shared__ float smem[];
+    extern __shared__ __align__(16) float smem[];
     float* sW = smem;
     float* acts = smem + m.param_total;
     stage_params(m, sW);
@@ -521,11 +666,11 @@ __global__ __launch_bounds__(kMaxLanes) void fwd_generic_kernel(GridDev g, MlpDe
 // T_{q-1} = T_q exp(Delta sigma_q), kept in the log domain so that it survives T_S
 // underflowing), then Eq. (2) with the running suffix sum of w_j a_j.
 // LDS: params | dparams accumulators | acts (act_total columns) | dz (2 * max_width columns) |
-// upstream feature gradients (n_feat columns).
+// upstream feature gradients (n_feat columns) | the lanes' cells (kGenericCellColumns columns).
 __global__ __launch_bounds__(kMaxLanes) void bwd_generic_kernel(GridDev g, MlpDev m, RaysDev rays,
                                                              BwdIo io, int tiles_per_block)
 {
-    extern __shared__ float smem[];
+    extern __shared__ __align__(16) float smem[];
     float* sW = smem;
     // gradient accumulators of the block: in LDS, or (MLPs whose two copies do not fit) directly in
     // the block's record in the workspace; every element has one owner lane either way
@@ -535,6 +680,7 @@ __global__ __launch_bounds__(kMaxLanes) void bwd_generic_kernel(GridDev g, MlpDe
     float* dz0 = acts + m.act_total * block_lanes();
     float* dz1 = dz0 + m.max_width * block_lanes();
     float* pcol = dz1 + m.max_width * block_lanes();
+    float* cells = pcol + m.n_feat * block_lanes();   // kCellColumns columns
     stage_params(m, sW);
     for (int i = threadIdx.x; i < m.param_total; i += blockDim.x) sdW[i] = 0.0f;
     __syncthreads();
@@ -596,7 +742,10 @@ __global__ __launch_bounds__(kMaxLanes) void bwd_generic_kernel(GridDev g, MlpDe
             }
 
             dz = mlp_backward(m, sW, sdW, acts, dz, dz_next, lane);
-            if (live) scatter_feat(g, io.d_grid, q.scene, c, dz, lane, io.d_grid_t);
+            publish_cell(cells, lane, c, q.scene, live);
+            __syncthreads();
+            scatter_tile(g, io.d_grid, io.d_grid_t, cells, dz, lane);
+            __syncthreads();   // the next sample overwrites cells and dz
         }
     }
     __syncthreads();

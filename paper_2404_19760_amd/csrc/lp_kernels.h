@@ -7,6 +7,7 @@ namespace lp {
 // ---- generic scalar kernels (lp_generic.hip) ---------------------------------------
 __global__ void fwd_generic_kernel(GridDev g, MlpDev m, RaysDev rays, FwdOut out);
 __global__ void bwd_generic_kernel(GridDev g, MlpDev m, RaysDev rays, BwdIo io, int tiles_per_block);
+constexpr int kGenericCellColumns = 16;  // LDS columns of the generic backward kernel that hold the lanes' cells
 constexpr int kReduceThreads = 1024;  // block size of reduce_params_kernel; one block per 64 parameters
 __global__ void reduce_params_kernel(MlpDev m, BwdIo io, int n_records);
 __global__ void splat_fwd_generic_kernel(GridDev tgt, MlpDev m, RaysDev rays, SplatDev sp);
