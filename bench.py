@@ -344,6 +344,8 @@ def main():
     # further workloads for context (short runs), e.g. the single-scene configuration and the
     # paper's experimental Renderer shape with contract coordinates
     del r
+    import gc
+    gc.collect()   # the main workload's host buffers go back before the short context runs are timed
     for entry in [n for n in args.also.split(",") if n and n != args.config]:
         torch.cuda.empty_cache()
         name, _, gdt = entry.partition(":")
@@ -351,7 +353,7 @@ def main():
             out.setdefault("also", []).append(measure_splat(lp, torch, name, max(3, args.steps // 2), 2))
             continue
         k = max(3, args.steps // 2)
-        o = measure(lp, torch, name, mode, k, 2, grid_dtype=gdt or "f32")
+        o = measure(lp, torch, name, mode, k, 5, grid_dtype=gdt or "f32")
         ow = o["w"]
         gw = ow.gather_bytes_per_sample
         gr = gw if not gdt else gw // 2
