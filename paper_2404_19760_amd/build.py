@@ -19,7 +19,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.environ.get("LP_LIB_OUT", os.path.join(HERE, "liblightplane.so"))
 
 SOURCES = ["lp_api.hip", "lp_diag.hip", "lp_decoder.hip", "lp_generic.hip", "lp_mfma_fwd.hip", "lp_mfma_bwd.hip", "lp_mfma_bwd_b.hip", "lp_mfma_bwd_ws.hip",
-           "lp_mfma_bwd_hash.hip",
+           "lp_mfma_bwd_hash.hip", "lp_mfma_bwd_hexplane.hip",
            "lp_mfma_dec2_fwd.hip", "lp_mfma_dec2_bwd.hip", "lp_splat_fast.hip",
            "lp_splat_mfma.hip", "lp_splat_mfma_bwd.hip", "lp_splat_mfma_bwd_t32.hip"]
 
@@ -47,6 +47,7 @@ PER_SOURCE_FLAGS = {"lp_mfma_fwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
                     "lp_mfma_bwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
                     "lp_mfma_bwd_ws.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
                     "lp_mfma_bwd_hash.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+                    "lp_mfma_bwd_hexplane.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
                     "lp_diag.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
                     "lp_mfma_dec2_fwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
                     "lp_mfma_dec2_bwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],

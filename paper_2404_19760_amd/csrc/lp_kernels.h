@@ -34,6 +34,10 @@ hipError_t launch_bwd_mfma_b(const GridDev& g, const MlpDev& m, const RaysDev& r
 hipError_t launch_bwd_mfma_hash(const GridDev& g, const MlpDev& m, const RaysDev& rays, const BwdIo& io,
                                 int n_cu, hipStream_t stream);
 
+// its instantiations for HexPlanes (lp_mfma_bwd_hexplane.hip)
+hipError_t launch_bwd_mfma_hexplane(const GridDev& g, const MlpDev& m, const RaysDev& rays, const BwdIo& io,
+                                    int n_cu, hipStream_t stream);
+
 // the shapes that run as a pair of waves per ray (lp_mfma_bwd_ws.hip)
 bool bwd_ws_supported(const GridDev& g, const MlpDev& m);
 hipError_t launch_bwd_mfma_ws(const GridDev& g, const MlpDev& m, const RaysDev& rays, const BwdIo& io,

@@ -368,6 +368,69 @@ __device__ __forceinline__ void gather_half(const GridDev& g, int scene, const C
     gather_finish<KIND, NCH, GT>(c, raw, feat);
 }
 
+// HexPlane (Section 3.2 names it among the structures; Cao & Johnson 2023): the cell of the ray's time on
+// the time axis (not contracted, clamped at both ends).
+__device__ __forceinline__ void time_cell(const GridDev& g, float time, int& it, float& ft)
+{
+    float gt;
+    axis_cell<false>((double)time, g.tmin, g.tscale, g.NT, 0.0, it, ft, gt);
+}
+
+// feat[0..NCH) = channels [ch0, ch0 + NCH) of a HexPlane at cell c and time `time`: for each of the three
+// pairs, the bilinear read of the spatial plane over axes (a, b) = (0,1), (1,2), (2,0) times the bilinear
+// read of the space-time plane over (c, t), c the third axis; the three products added.
+template <int C, int NCH, int GT>
+__device__ __forceinline__ void gather_half_hexplane(const GridDev& g, int scene, const Cell3& c, float time,
+                                                     int ch0, float* feat)
+{
+    constexpr int kPerVec = GT == LP_F32 ? 4 : 8, kVecs = NCH / kPerVec;
+    constexpr unsigned kElem = GT == LP_F32 ? 4u : 2u;
+    int it;
+    float ft;
+    time_cell(g, time, it, ft);
+#pragma unroll
+    for (int k = 0; k < NCH; ++k) feat[k] = 0.0f;
+#pragma unroll
+    for (int p = 0; p < 3; ++p) {
+        const int a = p, b = (p + 1) % 3, cc = (p + 2) % 3;
+        const char* P = reinterpret_cast<const char*>(g.data[p]) + (size_t)scene * g.N[a] * g.N[b] * C * kElem;
+        const char* Q = reinterpret_cast<const char*>(g.data_t[p]) + (size_t)scene * g.N[cc] * g.NT * C * kElem;
+        const unsigned bs = ((unsigned)c.i[a] * (unsigned)g.N[b] + (unsigned)c.i[b]) * C + ch0;
+        const unsigned bu = ((unsigned)c.i[cc] * (unsigned)g.NT + (unsigned)it) * C + ch0;
+        uint4 rs[4][kVecs], ru[4][kVecs];
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const int da = d >> 1, db = d & 1;
+            const uint4* ps = reinterpret_cast<const uint4*>(P + (size_t)(bs + (da * (unsigned)g.N[b] + db) * C) * kElem);
+            const uint4* pu = reinterpret_cast<const uint4*>(Q + (size_t)(bu + (da * (unsigned)g.NT + db) * C) * kElem);
+#pragma unroll
+            for (int i = 0; i < kVecs; ++i) { rs[d][i] = ps[i]; ru[d][i] = pu[i]; }
+        }
+        float s[NCH], u[NCH];
+#pragma unroll
+        for (int k = 0; k < NCH; ++k) s[k] = u[k] = 0.0f;
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const int da = d >> 1, db = d & 1;
+            const float ws = (da ? c.f[a] : 1.0f - c.f[a]) * (db ? c.f[b] : 1.0f - c.f[b]);
+            const float wu = (da ? c.f[cc] : 1.0f - c.f[cc]) * (db ? ft : 1.0f - ft);
+#pragma unroll
+            for (int i = 0; i < kVecs; ++i) {
+                float vs[kPerVec], vu[kPerVec];
+                unpack_values<GT>(rs[d][i], vs);
+                unpack_values<GT>(ru[d][i], vu);
+#pragma unroll
+                for (int e = 0; e < kPerVec; ++e) {
+                    s[kPerVec * i + e] += ws * vs[e];
+                    u[kPerVec * i + e] += wu * vu[e];
+                }
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < NCH; ++k) feat[k] += s[k] * u[k];
+    }
+}
+
 // Ranges of rays per XCD: workgroup b runs on XCD b % 8, so giving XCD x the contiguous ray
 // range x keeps neighbouring rays (which read neighbouring texels) behind one L2.
 struct RaySchedule {

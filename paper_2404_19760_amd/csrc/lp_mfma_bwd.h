@@ -55,7 +55,7 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
     const int lane = threadIdx.x & 63;
     const int col = lane & 31, grp = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    float* info = reinterpret_cast<float*>(lds + L::END + wave * L::INFO_UNITS);
+    float* info = reinterpret_cast<float*>(lds + L::END + wave * L::INFO_UNITS * (kRecordDwords<KIND> / 16));
 
     // selection operands: hidden tensors (two K-steps per 32-feature block), output gradients,
     // input features
@@ -222,7 +222,7 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
             }
             // scatter record of this lane's sample, read at the end of the step
             wave_lds_fence();
-            if (grp == 0) write_scatter_record<KIND, CG>(info + col * 16, g, a.cell[0]);
+            if (grp == 0) write_scatter_record<KIND, CG>(info + col * kRecordDwords<KIND>, g, a.cell[0], q.time);
 
             const Frag (&lh)[kBwdNB][KSH] = NH == 2 ? a.h2h : a.h1h;  // last hidden layer's activations
             const Frag (&ll)[kBwdNB][KSH] = NH == 2 ? a.h2l : a.h1l;
@@ -345,7 +345,7 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_mfma_kernel(GridDev g, MlpDev
             }
             __builtin_amdgcn_sched_barrier(0);
             wave_lds_fence();
-            scatter_channels<KIND, CG>(g, io.d_grid, q.scene, info, dFt, col, grp);
+            scatter_channels<KIND, CG>(g, io.d_grid, q.scene, info, dFt, col, grp, io.d_grid_t);
         }
     }
 
@@ -387,7 +387,8 @@ template <int KIND, int C, int H, int NH, bool CC, int CG, int GT = LP_F32>
 hipError_t launch_bwd(const GridDev& g, const MlpDev& m, const RaysDev& rays, const BwdIo& io, int n_cu,
                        hipStream_t stream)
 {
-    constexpr int kLdsBytes = MlpLds<C, H, NH, true, kBwdNB>::bytes(kWaves);
+    using L = MlpLds<C, H, NH, true, kBwdNB>;
+    constexpr int kLdsBytes = L::bytes(kWaves) + kWaves * L::INFO_UNITS * (kRecordDwords<KIND> / 16 - 1) * 16;
     static_assert(kLdsBytes <= 160 * 1024, "LDS budget of a gfx950 compute unit");
     auto kernel = bwd_mfma_kernel<KIND, C, H, NH, CC, CG, GT>;
     hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);

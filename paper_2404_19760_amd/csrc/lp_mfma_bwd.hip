@@ -50,6 +50,7 @@ hipError_t launch_bwd_mfma(const GridDev& g, const MlpDev& m, const RaysDev& ray
 {
     if (bwd_ws_supported(g, m)) return launch_bwd_mfma_ws(g, m, rays, io, n_cu, stream);
     if (g.kind == LP_GRID_HASH) return launch_bwd_mfma_hash(g, m, rays, io, n_cu, stream);
+    if (g.kind == LP_GRID_HEXPLANE) return launch_bwd_mfma_hexplane(g, m, rays, io, n_cu, stream);
     return g.kind == LP_GRID_VOXEL ? dispatch_bwd<LP_GRID_VOXEL>(g, m, rays, io, n_cu, stream)
                                    : dispatch_bwd<LP_GRID_TRIPLANE>(g, m, rays, io, n_cu, stream);
 }

@@ -130,11 +130,35 @@ __device__ __forceinline__ Frag selection(int j, int grp, IndexFn index_of)
 // triplane: 12 weights (plane p, corner 2da + db at 4p + ..), then 3 plane offsets.
 // hash table: the 8 corner weights in the voxel's order for this channel count, then the element
 // offsets (entry x channels) of the 8 corners in the same order.
+// HexPlane: 32 dwords per sample: 12 weights of the spatial planes as for a triplane, 12 weights of the
+// space-time planes (pair p, corner 2dc + dt at 12 + 4p + ..), then the 3 + 3 plane offsets.
 // EXACT: the complements 1 - f come from the fp64 index (the Splatter, whose result divides by sums
 // of these weights); otherwise from the rounded f (the Renderer's gradient scatter).
+template <int KIND>
+constexpr int kRecordDwords = KIND == LP_GRID_HEXPLANE ? 32 : 16;
+
 template <int KIND, int C, bool EXACT = false>
-__device__ __forceinline__ void write_scatter_record(float* rec, const GridDev& g, const Cell3& c)
+__device__ __forceinline__ void write_scatter_record(float* rec, const GridDev& g, const Cell3& c, float time = 0.0f)
 {
+    if constexpr (KIND == LP_GRID_HEXPLANE) {
+        int it;
+        float ft;
+        time_cell(g, time, it, ft);
+        unsigned offs[6];
+#pragma unroll
+        for (int p = 0; p < 3; ++p) {
+            const int a = p, b = (p + 1) % 3, cc = (p + 2) % 3;
+            const float a1 = c.f[a], a0 = 1.0f - a1, b1 = c.f[b], b0 = 1.0f - b1;
+            const float c1 = c.f[cc], c0 = 1.0f - c1, t1 = ft, t0 = 1.0f - ft;
+            reinterpret_cast<float4*>(rec)[p] = make_float4(a0 * b0, a0 * b1, a1 * b0, a1 * b1);
+            reinterpret_cast<float4*>(rec)[3 + p] = make_float4(c0 * t0, c0 * t1, c1 * t0, c1 * t1);
+            offs[p] = ((unsigned)c.i[a] * (unsigned)g.N[b] + (unsigned)c.i[b]) * C;
+            offs[3 + p] = ((unsigned)c.i[cc] * (unsigned)g.NT + (unsigned)it) * C;
+        }
+        reinterpret_cast<uint4*>(rec)[6] = make_uint4(offs[0], offs[1], offs[2], offs[3]);
+        reinterpret_cast<uint4*>(rec)[7] = make_uint4(offs[4], offs[5], 0u, 0u);
+        return;
+    }
     if constexpr (KIND == LP_GRID_VOXEL) {
         const float x1 = c.f[0], x0 = EXACT ? c.g[0] : 1.0f - x1, y1 = c.f[1], y0 = EXACT ? c.g[1] : 1.0f - y1,
                     z1 = c.f[2], z0 = EXACT ? c.g[2] : 1.0f - z1;
@@ -209,10 +233,57 @@ struct CornerAcc {
 // passes the feature gradient through LDS reads it back in this order without permuting the step).
 template <int KIND, int C, bool IN_ORDER = false>
 __device__ __forceinline__ void scatter_channels(const GridDev& g, float* const d_grid[3], int scene,
-                                                 const float* info, const f32x16& dFt, int ch, int grp)
+                                                 const float* info, const f32x16& dFt, int ch, int grp,
+                                                 float* const d_grid_t[3] = nullptr)
 {
     const bool live = ch < C;
     auto record_of = [grp](int r) { return IN_ORDER ? 16 * grp + r : d_row(r, grp); };
+    if constexpr (KIND == LP_GRID_HEXPLANE) {
+        // HexPlane: by the product rule each plane of a pair receives the feature gradient times the
+        // OTHER plane's read, which this channel's lane forms again from four loads.  With 32 channels a
+        // lane serves both planes of every pair; with 16 channels the first half of a lane group serves
+        // the spatial planes and the second half the space-time planes.  One atomic add per corner and
+        // sample (no merging over samples).
+        const int c16 = ch & (C - 1);
+        const bool do_s = C == 32 || ch < 16, do_u = C == 32 || ch >= 16;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const float* rec = info + record_of(r) * 32;
+            const float v = dFt[r];
+            const uint4 o0 = reinterpret_cast<const uint4*>(rec)[6], o1 = reinterpret_cast<const uint4*>(rec)[7];
+            const unsigned off[6] = {o0.x, o0.y, o0.z, o0.w, o1.x, o1.y};
+#pragma unroll
+            for (int p = 0; p < 3; ++p) {
+                const int a = p, b = (p + 1) % 3, cc = (p + 2) % 3;
+                const float4 ws4 = reinterpret_cast<const float4*>(rec)[p], wu4 = reinterpret_cast<const float4*>(rec)[3 + p];
+                const float ws[4] = {ws4.x, ws4.y, ws4.z, ws4.w}, wu[4] = {wu4.x, wu4.y, wu4.z, wu4.w};
+                const size_t Sb = (size_t)scene * g.N[a] * g.N[b] * C, Ub = (size_t)scene * g.N[cc] * g.NT * C;
+                unsigned es[4], eu[4];   // element offsets of the four corners of either plane
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    es[d] = off[p] + ((d >> 1) * (unsigned)g.N[b] + (d & 1)) * C + c16;
+                    eu[d] = off[3 + p] + ((d >> 1) * (unsigned)g.NT + (d & 1)) * C + c16;
+                }
+                if (do_s) {   // spatial plane += weights * (gradient * read of the space-time plane)
+                    float u = 0.0f;
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) u += wu[d] * grid_load(g, g.data_t[p], Ub + eu[d]);
+                    const float vu = v * u;
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) atomicAdd(d_grid[p] + Sb + es[d], ws[d] * vu);
+                }
+                if (do_u) {   // space-time plane += weights * (gradient * read of the spatial plane)
+                    float s = 0.0f;
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) s += ws[d] * grid_load(g, g.data[p], Sb + es[d]);
+                    const float vs = v * s;
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) atomicAdd(d_grid_t[p] + Ub + eu[d], wu[d] * vs);
+                }
+            }
+        }
+        return;
+    }
     if constexpr (KIND == LP_GRID_HASH) {
         // Hash table: a lane (channel; with 16 channels the two halves of a lane group take the four
         // corners of one dz each, as for voxels) sums the contributions of consecutive samples whose

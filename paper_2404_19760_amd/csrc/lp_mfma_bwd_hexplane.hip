@@ -1,0 +1,21 @@
+// Matrix-core backward kernel of the Renderer over a HexPlane (Section 3.2 names HexPlane among the
+// structures h): the instantiations of lp_mfma_bwd.h for it.  The storage type and the contraction
+// are run-time branches, so that one set of kernels serves every HexPlane.
+#include "lp_mfma_bwd.h"
+
+namespace lp {
+
+hipError_t launch_bwd_mfma_hexplane(const GridDev& g, const MlpDev& m, const RaysDev& rays, const BwdIo& io, int n_cu,
+                                    hipStream_t stream)
+{
+    const int C = m.dims[0], H = m.dims[1], NH = m.n_layers - 1;
+#define LP_CASE(c, h, nh)                         \
+    if (C == c && g.C == c && H == h && NH == nh) \
+        return launch_bwd<LP_GRID_HEXPLANE, c, h, nh, false, c, kAnyDtype>(g, m, rays, io, n_cu, stream);
+    LP_CASE(16, 32, 1) LP_CASE(16, 64, 1) LP_CASE(32, 32, 1) LP_CASE(32, 64, 1)
+    LP_CASE(16, 32, 2) LP_CASE(16, 64, 2) LP_CASE(32, 32, 2) LP_CASE(32, 64, 2)
+#undef LP_CASE
+    return hipErrorInvalidValue;
+}
+
+}  // namespace lp

@@ -142,11 +142,26 @@ hipError_t dispatch_fwd_hash(const GridDev& g, const MlpDev& m, const RaysDev& r
     return hipErrorInvalidValue;
 }
 
+// HexPlanes: likewise one set of kernels
+hipError_t dispatch_fwd_hexplane(const GridDev& g, const MlpDev& m, const RaysDev& rays, const FwdOut& out, int n_cu,
+                                 hipStream_t stream)
+{
+    const int C = m.dims[0], H = m.dims[1], NH = m.n_layers - 1;
+#define LP_CASE(c, h, nh)                         \
+    if (C == c && g.C == c && H == h && NH == nh) \
+        return launch_fwd<LP_GRID_HEXPLANE, c, h, nh, 2, false, c, kAnyDtype>(g, m, rays, out, n_cu, stream);
+    LP_CASE(16, 32, 1) LP_CASE(16, 64, 1) LP_CASE(32, 32, 1) LP_CASE(32, 64, 1)
+    LP_CASE(16, 32, 2) LP_CASE(16, 64, 2) LP_CASE(32, 32, 2) LP_CASE(32, 64, 2)
+#undef LP_CASE
+    return hipErrorInvalidValue;
+}
+
 }  // namespace
 
 bool mfma_supported(const GridDev& g, const MlpDev& m)
 {
-    if (g.kind != LP_GRID_VOXEL && g.kind != LP_GRID_TRIPLANE && g.kind != LP_GRID_HASH) return false;
+    if (g.kind != LP_GRID_VOXEL && g.kind != LP_GRID_TRIPLANE && g.kind != LP_GRID_HASH && g.kind != LP_GRID_HEXPLANE)
+        return false;
     // inputs: all of them grid channels (16 or 32), or 16 grid channels + 16 direction inputs
     const bool plain = m.n_enc == 0 && m.dims[0] == g.C && (g.C == 16 || g.C == 32);
     const bool with_dir = m.n_enc > 0 && g.C == 16 && m.dims[0] == 32 && m.n_enc <= 16;
@@ -171,6 +186,13 @@ bool mfma_supported(const GridDev& g, const MlpDev& m)
         if (n0 * n1 * g.C >= (1ull << 30) || n1 * n2 * g.C >= (1ull << 30) || n2 * n0 * g.C >= (1ull << 30)) return false;
         for (int p = 0; p < 3; ++p)
             if ((uintptr_t)g.data[p] & 15u) return false;
+        if (g.kind == LP_GRID_HEXPLANE) {   // no direction inputs; the space-time planes under the same limits
+            const unsigned long long nt = (unsigned long long)g.NT;
+            if (!plain || n0 * nt * g.C >= (1ull << 30) || n1 * nt * g.C >= (1ull << 30) || n2 * nt * g.C >= (1ull << 30))
+                return false;
+            for (int p = 0; p < 3; ++p)
+                if ((uintptr_t)g.data_t[p] & 15u) return false;
+        }
     }
     return true;
 }
@@ -179,6 +201,7 @@ hipError_t launch_fwd_mfma(const GridDev& g, const MlpDev& m, const RaysDev& ray
                            hipStream_t stream)
 {
     if (g.kind == LP_GRID_HASH) return dispatch_fwd_hash(g, m, rays, out, n_cu, stream);
+    if (g.kind == LP_GRID_HEXPLANE) return dispatch_fwd_hexplane(g, m, rays, out, n_cu, stream);
     return g.kind == LP_GRID_VOXEL ? dispatch_fwd<LP_GRID_VOXEL>(g, m, rays, out, n_cu, stream)
                                    : dispatch_fwd<LP_GRID_TRIPLANE>(g, m, rays, out, n_cu, stream);
 }

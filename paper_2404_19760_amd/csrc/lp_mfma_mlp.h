@@ -152,6 +152,7 @@ struct RayGeom {
     float ox, oy, oz, dx, dy, dz, near, delta;
     double delta64;
     int scene;
+    float time;       // the ray's time (read for a HexPlane only; -inf = none given: clamps onto the first index)
     float extra[16];  // direction inputs of the MLP (only when the MLP has more inputs than the grid has channels)
 };
 
@@ -172,6 +173,7 @@ __device__ __forceinline__ RayGeom load_ray_geom(const RaysDev& rays, long long 
     q.delta64 = ((double)rays.far[ray] - (double)q.near) / (double)rays.S;
     q.delta = (float)q.delta64;
     q.scene = rays.scene ? rays.scene[ray] : 0;
+    q.time = rays.time ? rays.time[ray] : -INFINITY;
     return q;
 }
 
@@ -224,7 +226,9 @@ __device__ __forceinline__ void sample_features_typed(const GridDev& g, const Ra
                                                       Frag (&fh)[C / 16], Frag (&fl)[C / 16])
 {
     float feat[C / 2];
-    if constexpr (CG == C) {
+    if constexpr (CG == C && KIND == LP_GRID_HEXPLANE) {
+        gather_half_hexplane<C, C / 2, GT>(g, q.scene, c, q.time, grp * (C / 2), feat);
+    } else if constexpr (CG == C) {
         gather_half<KIND, C, C / 2, GT>(g, q.scene, c, grp * (C / 2), feat);
     } else {
         static_assert(2 * CG == C && CG == 16, "direction inputs take the second half of 32 inputs");
