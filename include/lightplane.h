@@ -69,7 +69,9 @@ typedef enum { LP_F32 = 0, LP_BF16 = 1, LP_F16 = 2 } lp_dtype;
  *             vectors channel by channel, and SUMS the three products.  Time t_min maps to index 0
  *             and t_max to index NT - 1 of the time axis, times outside are clamped; contract
  *             coordinates act on the spatial axes only.  The gradient has six tensors (d_grid[p]
- *             for data[p], d_grid[3 + p] for data_t[p]).  Renderer only, generic kernels.
+ *             for data[p], d_grid[3 + p] for data_t[p]).  Renderer only (the Splatter refuses it).
+ *             The matrix-core kernels take 16 or 32 channels without direction inputs; every
+ *             other shape runs on the generic kernels.
  * World coordinate aabb_min[a] maps to index 0 and aabb_max[a] to index N_a - 1 along axis
  * a; positions outside the box are clamped onto it.  B scenes share the MLP.
  * contract_a: 0 = off.  In (0, 2]: contract coordinates (appendix, "Experimental Details",

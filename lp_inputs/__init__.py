@@ -103,7 +103,7 @@ WORKLOADS = {
     "hash": Workload("hash", HASH, 1, 16, (128, 128, 128), 0.1, (16, 64, 64, 4), 128, 1, 128, cfg_id=11,
                      hash_size=1 << 19),
     # A HexPlane (three 128^2 spatial planes and three 128 x 16 space-time planes of 16 channels), rays
-    # of one view with a frame time each; served by the generic kernels.
+    # of one view with a frame time each.
     "hexplane": Workload("hexplane", HEXPLANE, 1, 16, (128, 128, 128), 0.1, (16, 64, 64, 4), 128, 1, 128, cfg_id=12,
                          n_time=16),
 }

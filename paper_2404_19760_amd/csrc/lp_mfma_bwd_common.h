@@ -242,44 +242,100 @@ __device__ __forceinline__ void scatter_channels(const GridDev& g, float* const 
         // HexPlane: by the product rule each plane of a pair receives the feature gradient times the
         // OTHER plane's read, which this channel's lane forms again from four loads.  With 32 channels a
         // lane serves both planes of every pair; with 16 channels the first half of a lane group serves
-        // the spatial planes and the second half the space-time planes.  One atomic add per corner and
-        // sample (no merging over samples).
+        // the spatial planes and the second half the space-time planes.  Per plane, the contributions of
+        // consecutive samples that fall into the same texel cell are summed before one atomic add per
+        // corner (the time of a ray is fixed, so a space-time plane changes cell only along one axis).
         const int c16 = ch & (C - 1);
         const bool do_s = C == 32 || ch < 16, do_u = C == 32 || ch >= 16;
+        float acc_s[3][4], acc_u[3][4];
+        unsigned prev_s[3] = {0u, 0u, 0u}, prev_u[3] = {0u, 0u, 0u};
+        size_t Sb[3], Ub[3];
+#pragma unroll
+        for (int p = 0; p < 3; ++p) {
+            const int a = p, b = (p + 1) % 3, cc = (p + 2) % 3;
+            Sb[p] = (size_t)scene * g.N[a] * g.N[b] * C + c16;
+            Ub[p] = (size_t)scene * g.N[cc] * g.NT * C + c16;
+        }
+        // the other plane's reads of sample r + 1 are loaded before the adds of sample r are issued, so
+        // that their latency passes behind those adds
+        auto other_reads = [&](int r, float (&u)[3], float (&sv)[3]) {
+            const float* rec = info + record_of(r) * 32;
+            const uint4 o0 = reinterpret_cast<const uint4*>(rec)[6], o1 = reinterpret_cast<const uint4*>(rec)[7];
+            const unsigned off[6] = {o0.x, o0.y, o0.z, o0.w, o1.x, o1.y};
+#pragma unroll
+            for (int p = 0; p < 3; ++p) {
+                const int b = (p + 1) % 3;
+                const unsigned sa = (unsigned)g.N[b] * C, ua = (unsigned)g.NT * C;
+                u[p] = sv[p] = 0.0f;
+                if (do_s) {
+                    const float4 w4 = reinterpret_cast<const float4*>(rec)[3 + p];
+                    const float w[4] = {w4.x, w4.y, w4.z, w4.w};
+#pragma unroll
+                    for (int d = 0; d < 4; ++d)
+                        u[p] += w[d] * grid_load(g, g.data_t[p], Ub[p] + off[3 + p] + (d >> 1) * ua + (d & 1) * C);
+                }
+                if (do_u) {
+                    const float4 w4 = reinterpret_cast<const float4*>(rec)[p];
+                    const float w[4] = {w4.x, w4.y, w4.z, w4.w};
+#pragma unroll
+                    for (int d = 0; d < 4; ++d)
+                        sv[p] += w[d] * grid_load(g, g.data[p], Sb[p] + off[p] + (d >> 1) * sa + (d & 1) * C);
+                }
+            }
+        };
+        float cur_u[3], cur_s[3];
+        other_reads(0, cur_u, cur_s);
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const float* rec = info + record_of(r) * 32;
             const float v = dFt[r];
             const uint4 o0 = reinterpret_cast<const uint4*>(rec)[6], o1 = reinterpret_cast<const uint4*>(rec)[7];
             const unsigned off[6] = {o0.x, o0.y, o0.z, o0.w, o1.x, o1.y};
+            float nxt_u[3] = {0.0f, 0.0f, 0.0f}, nxt_s[3] = {0.0f, 0.0f, 0.0f};
+            if (r + 1 < 16) other_reads(r + 1, nxt_u, nxt_s);
 #pragma unroll
             for (int p = 0; p < 3; ++p) {
-                const int a = p, b = (p + 1) % 3, cc = (p + 2) % 3;
+                const int b = (p + 1) % 3;
                 const float4 ws4 = reinterpret_cast<const float4*>(rec)[p], wu4 = reinterpret_cast<const float4*>(rec)[3 + p];
                 const float ws[4] = {ws4.x, ws4.y, ws4.z, ws4.w}, wu[4] = {wu4.x, wu4.y, wu4.z, wu4.w};
-                const size_t Sb = (size_t)scene * g.N[a] * g.N[b] * C, Ub = (size_t)scene * g.N[cc] * g.NT * C;
-                unsigned es[4], eu[4];   // element offsets of the four corners of either plane
-#pragma unroll
-                for (int d = 0; d < 4; ++d) {
-                    es[d] = off[p] + ((d >> 1) * (unsigned)g.N[b] + (d & 1)) * C + c16;
-                    eu[d] = off[3 + p] + ((d >> 1) * (unsigned)g.NT + (d & 1)) * C + c16;
-                }
+                const unsigned sa = (unsigned)g.N[b] * C, ua = (unsigned)g.NT * C;   // step to the next row of either plane
                 if (do_s) {   // spatial plane += weights * (gradient * read of the space-time plane)
-                    float u = 0.0f;
+                    const float vu = v * cur_u[p];
+                    const bool moved = off[p] != prev_s[p];
+                    if (r > 0 && moved) {
 #pragma unroll
-                    for (int d = 0; d < 4; ++d) u += wu[d] * grid_load(g, g.data_t[p], Ub + eu[d]);
-                    const float vu = v * u;
+                        for (int d = 0; d < 4; ++d) atomicAdd(d_grid[p] + Sb[p] + prev_s[p] + (d >> 1) * sa + (d & 1) * C, acc_s[p][d]);
+                    }
 #pragma unroll
-                    for (int d = 0; d < 4; ++d) atomicAdd(d_grid[p] + Sb + es[d], ws[d] * vu);
+                    for (int d = 0; d < 4; ++d) acc_s[p][d] = (r == 0 || moved) ? ws[d] * vu : acc_s[p][d] + ws[d] * vu;
+                    prev_s[p] = off[p];
                 }
                 if (do_u) {   // space-time plane += weights * (gradient * read of the spatial plane)
-                    float s = 0.0f;
+                    const float vs = v * cur_s[p];
+                    const bool moved = off[3 + p] != prev_u[p];
+                    if (r > 0 && moved) {
 #pragma unroll
-                    for (int d = 0; d < 4; ++d) s += ws[d] * grid_load(g, g.data[p], Sb + es[d]);
-                    const float vs = v * s;
+                        for (int d = 0; d < 4; ++d) atomicAdd(d_grid_t[p] + Ub[p] + prev_u[p] + (d >> 1) * ua + (d & 1) * C, acc_u[p][d]);
+                    }
 #pragma unroll
-                    for (int d = 0; d < 4; ++d) atomicAdd(d_grid_t[p] + Ub + eu[d], wu[d] * vs);
+                    for (int d = 0; d < 4; ++d) acc_u[p][d] = (r == 0 || moved) ? wu[d] * vs : acc_u[p][d] + wu[d] * vs;
+                    prev_u[p] = off[3 + p];
                 }
+            }
+#pragma unroll
+            for (int p = 0; p < 3; ++p) { cur_u[p] = nxt_u[p]; cur_s[p] = nxt_s[p]; }
+        }
+#pragma unroll
+        for (int p = 0; p < 3; ++p) {
+            const int b = (p + 1) % 3;
+            const unsigned sa = (unsigned)g.N[b] * C, ua = (unsigned)g.NT * C;
+            if (do_s) {
+#pragma unroll
+                for (int d = 0; d < 4; ++d) atomicAdd(d_grid[p] + Sb[p] + prev_s[p] + (d >> 1) * sa + (d & 1) * C, acc_s[p][d]);
+            }
+            if (do_u) {
+#pragma unroll
+                for (int d = 0; d < 4; ++d) atomicAdd(d_grid_t[p] + Ub[p] + prev_u[p] + (d >> 1) * ua + (d & 1) * C, acc_u[p][d]);
             }
         }
         return;

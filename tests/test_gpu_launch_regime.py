@@ -120,6 +120,20 @@ def test_hash_workload_with_many_rays(lp, oracle, pick):
     print(summary(worst), flush=True)
 
 
+def test_hexplane_workload_with_many_rays(lp, oracle):
+    """The HexPlane workload (three 128^2 spatial and three 128 x 16 space-time planes of 16 channels,
+    MLP 16-64-64-4, 128 samples per ray, a frame time per ray) on the matrix-core kernels: a 96 x 96
+    pixel block, about nine rays per wavefront, neighbouring rays adding into the same texels."""
+    inp = lp_inputs.make_inputs("hexplane")
+    sub = inp.subset(_pixel_block(128, 16, 112))
+    grid, mlp, _, _ = lp.to_device(sub)
+    assert lp.lp_has_fast_path(grid, mlp)
+    # (an entry of the small space-time planes sums some hundred thousand sample contributions, so a
+    # larger share of their entries contains at least one ReLU decision inside the kink band: seen 3.8 %)
+    worst = check_case(lp, oracle, sub, lp.LP_MATH_BF16X3, label="hexplane block", max_strict_fail=0.08)
+    print(summary(worst), flush=True)
+
+
 def test_contract_workload_with_many_rays(lp, oracle):
     """The paper's experimental Renderer shape with contract coordinates: every second ray of the
     256^2 image (32 768 rays x 384 samples, 160^3 x 32 voxels)."""
