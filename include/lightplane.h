@@ -60,7 +60,8 @@ typedef enum { LP_F32 = 0, LP_BF16 = 1, LP_F16 = 2 } lp_dtype;
  *             mod hash_size (products and xor in 32-bit unsigned arithmetic); corners that collide
  *             share the entry and their gradients add.  Renderer only (the Splatter refuses it).
  *             The matrix-core kernels take tables whose hash_size is a power of two (16 or 32
- *             channels, no direction inputs); every other table runs on the generic kernels.
+ *             channels, or 16 channels under the merged two-MLP decoder); every other table runs
+ *             on the generic kernels.
  *   hexplane: a structure over space AND time (Section 3.2 names HexPlane among the structures;
  *             the definition is Cao & Johnson 2023's): data[0..2] as the triplane's planes, and
  *             data_t[p] = [B][N_c][NT][C] the space-time plane over (c, t), c being the spatial
@@ -70,8 +71,8 @@ typedef enum { LP_F32 = 0, LP_BF16 = 1, LP_F16 = 2 } lp_dtype;
  *             and t_max to index NT - 1 of the time axis, times outside are clamped; contract
  *             coordinates act on the spatial axes only.  The gradient has six tensors (d_grid[p]
  *             for data[p], d_grid[3 + p] for data_t[p]).  Renderer only (the Splatter refuses it).
- *             The matrix-core kernels take 16 or 32 channels without direction inputs; every
- *             other shape runs on the generic kernels.
+ *             The matrix-core kernels take 16 or 32 channels (or 16 channels under the merged
+ *             two-MLP decoder); every other shape runs on the generic kernels.
  * World coordinate aabb_min[a] maps to index 0 and aabb_max[a] to index N_a - 1 along axis
  * a; positions outside the box are clamped onto it.  B scenes share the MLP.
  * contract_a: 0 = off.  In (0, 2]: contract coordinates (appendix, "Experimental Details",

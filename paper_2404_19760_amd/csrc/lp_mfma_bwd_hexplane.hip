@@ -15,6 +15,12 @@ hipError_t launch_bwd_mfma_hexplane(const GridDev& g, const MlpDev& m, const Ray
     LP_CASE(16, 32, 1) LP_CASE(16, 64, 1) LP_CASE(32, 32, 1) LP_CASE(32, 64, 1)
     LP_CASE(16, 32, 2) LP_CASE(16, 64, 2) LP_CASE(32, 32, 2) LP_CASE(32, 64, 2)
 #undef LP_CASE
+    // 16 grid channels + direction inputs (the two-MLP decoder merged into one MLP of 32 inputs)
+#define LP_CASE(h, nh)                             \
+    if (C == 32 && g.C == 16 && H == h && NH == nh) \
+        return launch_bwd<LP_GRID_HEXPLANE, 32, h, nh, false, 16, kAnyDtype>(g, m, rays, io, n_cu, stream);
+    LP_CASE(32, 1) LP_CASE(64, 1) LP_CASE(32, 2) LP_CASE(64, 2)
+#undef LP_CASE
     return hipErrorInvalidValue;
 }
 

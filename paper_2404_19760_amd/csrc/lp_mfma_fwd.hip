@@ -139,6 +139,12 @@ hipError_t dispatch_fwd_hash(const GridDev& g, const MlpDev& m, const RaysDev& r
     LP_CASE(16, 32, 1) LP_CASE(16, 64, 1) LP_CASE(32, 32, 1) LP_CASE(32, 64, 1)
     LP_CASE(16, 32, 2) LP_CASE(16, 64, 2) LP_CASE(32, 32, 2) LP_CASE(32, 64, 2)
 #undef LP_CASE
+    // 16 table channels + direction inputs (the two-MLP decoder merged into one MLP of 32 inputs)
+#define LP_CASE(h, nh)                             \
+    if (C == 32 && g.C == 16 && H == h && NH == nh) \
+        return launch_fwd<LP_GRID_HASH, 32, h, nh, 2, false, 16, kAnyDtype>(g, m, rays, out, n_cu, stream);
+    LP_CASE(32, 1) LP_CASE(64, 1) LP_CASE(32, 2) LP_CASE(64, 2)
+#undef LP_CASE
     return hipErrorInvalidValue;
 }
 
@@ -152,6 +158,12 @@ hipError_t dispatch_fwd_hexplane(const GridDev& g, const MlpDev& m, const RaysDe
         return launch_fwd<LP_GRID_HEXPLANE, c, h, nh, 2, false, c, kAnyDtype>(g, m, rays, out, n_cu, stream);
     LP_CASE(16, 32, 1) LP_CASE(16, 64, 1) LP_CASE(32, 32, 1) LP_CASE(32, 64, 1)
     LP_CASE(16, 32, 2) LP_CASE(16, 64, 2) LP_CASE(32, 32, 2) LP_CASE(32, 64, 2)
+#undef LP_CASE
+    // 16 plane channels + direction inputs (the two-MLP decoder merged into one MLP of 32 inputs)
+#define LP_CASE(h, nh)                             \
+    if (C == 32 && g.C == 16 && H == h && NH == nh) \
+        return launch_fwd<LP_GRID_HEXPLANE, 32, h, nh, 2, false, 16, kAnyDtype>(g, m, rays, out, n_cu, stream);
+    LP_CASE(32, 1) LP_CASE(64, 1) LP_CASE(32, 2) LP_CASE(64, 2)
 #undef LP_CASE
     return hipErrorInvalidValue;
 }
@@ -178,17 +190,17 @@ bool mfma_supported(const GridDev& g, const MlpDev& m)
         if (per_scene >= (1ull << 30)) return false;
         if ((uintptr_t)g.data[0] & 15u) return false;
     } else if (g.kind == LP_GRID_HASH) {
-        // a table whose size is a power of two (`mod size` is a mask in these kernels), no direction inputs
+        // a table whose size is a power of two (`mod size` is a mask in these kernels)
         const unsigned long long T = (unsigned long long)g.hash_size;
-        if (!plain || T == 0 || (T & (T - 1)) != 0 || T * g.C >= (1ull << 30)) return false;
+        if (T == 0 || (T & (T - 1)) != 0 || T * g.C >= (1ull << 30)) return false;
         if ((uintptr_t)g.data[0] & 15u) return false;
     } else {
         if (n0 * n1 * g.C >= (1ull << 30) || n1 * n2 * g.C >= (1ull << 30) || n2 * n0 * g.C >= (1ull << 30)) return false;
         for (int p = 0; p < 3; ++p)
             if ((uintptr_t)g.data[p] & 15u) return false;
-        if (g.kind == LP_GRID_HEXPLANE) {   // no direction inputs; the space-time planes under the same limits
+        if (g.kind == LP_GRID_HEXPLANE) {   // the space-time planes under the same limits
             const unsigned long long nt = (unsigned long long)g.NT;
-            if (!plain || n0 * nt * g.C >= (1ull << 30) || n1 * nt * g.C >= (1ull << 30) || n2 * nt * g.C >= (1ull << 30))
+            if (n0 * nt * g.C >= (1ull << 30) || n1 * nt * g.C >= (1ull << 30) || n2 * nt * g.C >= (1ull << 30))
                 return false;
             for (int p = 0; p < 3; ++p)
                 if ((uintptr_t)g.data_t[p] & 15u) return false;

@@ -233,7 +233,8 @@ __device__ __forceinline__ void sample_features_typed(const GridDev& g, const Ra
     } else {
         static_assert(2 * CG == C && CG == 16, "direction inputs take the second half of 32 inputs");
         if (grp == 0) {
-            gather_half<KIND, CG, CG, GT>(g, q.scene, c, 0, feat);
+            if constexpr (KIND == LP_GRID_HEXPLANE) gather_half_hexplane<CG, CG, GT>(g, q.scene, c, q.time, 0, feat);
+            else gather_half<KIND, CG, CG, GT>(g, q.scene, c, 0, feat);
         } else {
 #pragma unroll
             for (int e = 0; e < CG; ++e) feat[e] = q.extra[e];

@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 
 import lp_inputs
-from lp_inputs import TRIPLANE, VOXEL
+from lp_inputs import HASH, HEXPLANE, TRIPLANE, VOXEL
 
 from parity import check_case_dec
 
@@ -59,6 +59,33 @@ def test_decoder_matrix_core(lp, oracle, kind, hidden_s, hidden_v, n_freq, sampl
     for mode in (lp.LP_MATH_GENERIC, lp.LP_MATH_BF16X3):
         print(mode, check_case_dec(lp, oracle, inp, mode, label=f"dec mfma kind={kind} {hidden_s}/{hidden_v} mode={mode}"),
               flush=True)
+
+
+@pytest.mark.parametrize("kind,extra", [(HASH, dict(hash_size=4096)), (HEXPLANE, dict(n_time=4, t_range=(-0.5, 1.5)))])
+@pytest.mark.parametrize("hidden_s,hidden_v,n_freq,contract,stored", [
+    ((16,), (16,), 0, 0.0, None),
+    ((32, 32), (32, 32), 2, 1.3, None),      # width 64, two hidden layers, 15 direction inputs, contraction
+    ((24,), (40,), 1, 0.0, "bfloat16"),
+    ((16, 16), (16, 16), 1, 0.0, None),
+])
+def test_decoder_matrix_core_on_hash_tables_and_hexplanes(lp, oracle, kind, extra, hidden_s, hidden_v, n_freq, contract, stored):
+    """The merged two-MLP decoder (16 channels + direction inputs) over a hash table of a power-of-two
+    size and over a HexPlane with a time per ray, on the matrix-core kernels, both arithmetic modes."""
+    import torch
+    kw = dict(origin_radius=1.5, near=(0.0, 0.3), far=(6.0, 20.0)) if contract else {}
+    inp = problem(kind, channels=16, hidden_s=hidden_s, hidden_v=hidden_v, n_freq=n_freq, n_feat=3, seed=89,
+                  n_rays=150, samples=70, n_scenes=2, res=(12, 10, 11), grid_std=0.3, **extra, **kw)
+    inp = dataclasses.replace(inp, contract_a=contract)
+    dtype = None
+    if stored:
+        dtype = getattr(torch, stored)
+        kept = [torch.from_numpy(g).to(dtype) for g in inp.grid]
+        inp = dataclasses.replace(inp, grid=[t.to(torch.float32).numpy() for t in kept])
+    grid, _, _, _ = lp.to_device(inp)
+    assert lp.lp_dec_has_fast_path(grid, lp.decoder_to_device(inp.decoder))
+    for mode in (lp.LP_MATH_GENERIC, lp.LP_MATH_BF16X3):
+        print(mode, check_case_dec(lp, oracle, inp, mode, label=f"dec mfma kind={kind} {hidden_s}/{hidden_v} mode={mode}",
+                                   max_strict_fail=0.05, grid_dtype=dtype), flush=True)
 
 
 @pytest.mark.parametrize("kind", [VOXEL, TRIPLANE])
