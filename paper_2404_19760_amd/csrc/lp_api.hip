@@ -223,7 +223,8 @@ lp_status run_bwd(const lp::GridDev& g, const lp::MlpDev& m, const lp::RaysDev& 
         return LP_OK;
     }
     GenericShape shape;
-    if (!generic_shape(m, (size_t)m.act_total + 2 * (size_t)m.max_width + m.n_feat + lp::kGenericCellColumns, true, &shape))
+    const size_t cell_columns = m.max_width >= lp::kGenericCellColumns ? 0 : lp::kGenericCellColumns;
+    if (!generic_shape(m, (size_t)m.act_total + 2 * (size_t)m.max_width + m.n_feat + cell_columns, true, &shape))
         return fail(LP_ERR_UNSUPPORTED, "MLP too large for the generic backward kernel's LDS budget");
     lp::BwdIo io = io_in;
     io.acc_in_record = shape.acc_in_record;

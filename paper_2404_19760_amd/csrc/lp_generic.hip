@@ -666,7 +666,8 @@ __global__ __launch_bounds__(kMaxLanes) void fwd_generic_kernel(GridDev g, MlpDe
 // T_{q-1} = T_q exp(Delta sigma_q), kept in the log domain so that it survives T_S
 // underflowing), then Eq. (2) with the running suffix sum of w_j a_j.
 // LDS: params | dparams accumulators | acts (act_total columns) | dz (2 * max_width columns) |
-// upstream feature gradients (n_feat columns) | the lanes' cells (kGenericCellColumns columns).
+// upstream feature gradients (n_feat columns) | the lanes' cells (kGenericCellColumns columns; only for
+// MLPs narrower than that: otherwise the cells go into the dz buffer that the MLP backward leaves free).
 __global__ __launch_bounds__(kMaxLanes) void bwd_generic_kernel(GridDev g, MlpDev m, RaysDev rays,
                                                              BwdIo io, int tiles_per_block)
 {
@@ -680,7 +681,7 @@ __global__ __launch_bounds__(kMaxLanes) void bwd_generic_kernel(GridDev g, MlpDe
     float* dz0 = acts + m.act_total * block_lanes();
     float* dz1 = dz0 + m.max_width * block_lanes();
     float* pcol = dz1 + m.max_width * block_lanes();
-    float* cells = pcol + m.n_feat * block_lanes();   // kCellColumns columns
+    float* cells_extra = pcol + m.n_feat * block_lanes();   // present when max_width < kGenericCellColumns
     stage_params(m, sW);
     for (int i = threadIdx.x; i < m.param_total; i += blockDim.x) sdW[i] = 0.0f;
     __syncthreads();
@@ -742,6 +743,8 @@ __global__ __launch_bounds__(kMaxLanes) void bwd_generic_kernel(GridDev g, MlpDe
             }
 
             dz = mlp_backward(m, sW, sdW, acts, dz, dz_next, lane);
+            // (the MLP backward alternates between dz0 and dz1; the one it did not return is free now)
+            float* cells = m.max_width >= kGenericCellColumns ? (dz == dz0 ? dz1 : dz0) : cells_extra;
             publish_cell(cells, lane, c, q.scene, live);
             __syncthreads();
             scatter_tile(g, io.d_grid, io.d_grid_t, cells, dz, lane);
