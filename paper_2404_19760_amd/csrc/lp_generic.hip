@@ -50,10 +50,76 @@ __device__ __forceinline__ Cell locate(const GridDev& g, double x, double y, dou
     return c;
 }
 
+// Channels [k, k + 4) of h(x), for fp32 structures whose channel count is a multiple of four and whose
+// tensors are 16-byte aligned: one 16-byte load per corner instead of four loads.
+__device__ __forceinline__ void fma4(float4& acc, float w, const float4& v)
+{
+    acc.x += w * v.x; acc.y += w * v.y; acc.z += w * v.z; acc.w += w * v.w;
+}
+
+__device__ float4 gather_channels4(const GridDev& g, int scene, const Cell& c, int k)
+{
+    const int C = g.C;
+    float4 acc = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    auto at = [](const void* base, size_t idx) { return *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(base) + idx); };
+    if (g.kind == LP_GRID_VOXEL || g.kind == LP_GRID_HASH) {
+        const size_t V = (size_t)scene * (g.kind == LP_GRID_VOXEL ? (size_t)g.N[0] * g.N[1] * g.N[2] : (size_t)g.hash_size) * C;
+        for (int d = 0; d < 8; ++d) {
+            const int dx = d >> 2, dy = (d >> 1) & 1, dz = d & 1;
+            const float w = (dx ? c.f[0] : c.g[0]) * (dy ? c.f[1] : c.g[1]) *
+                            (dz ? c.f[2] : c.g[2]);
+            const size_t off = g.kind == LP_GRID_VOXEL
+                ? (((size_t)(c.i[0] + dx) * g.N[1] + (c.i[1] + dy)) * g.N[2] + (c.i[2] + dz)) * C
+                : (size_t)hash_slot(c.i[0] + dx, c.i[1] + dy, c.i[2] + dz, g.hash_size) * C;
+            fma4(acc, w, at(g.data[0], V + off + k));
+        }
+    } else {
+        for (int p = 0; p < 3; ++p) {
+            const int a = p, b = (p + 1) % 3, cc = (p + 2) % 3;
+            const size_t P = (size_t)scene * g.N[a] * g.N[b] * C;
+            float4 s = make_float4(0.0f, 0.0f, 0.0f, 0.0f), u = s;
+            for (int d = 0; d < 4; ++d) {
+                const int da = d >> 1, db = d & 1;
+                fma4(s, (da ? c.f[a] : c.g[a]) * (db ? c.f[b] : c.g[b]),
+                     at(g.data[p], P + ((size_t)(c.i[a] + da) * g.N[b] + (c.i[b] + db)) * C + k));
+            }
+            if (g.kind == LP_GRID_HEXPLANE) {
+                const size_t Q = (size_t)scene * g.N[cc] * g.NT * C;
+                for (int d = 0; d < 4; ++d) {
+                    const int da = d >> 1, db = d & 1;
+                    fma4(u, (da ? c.f[cc] : c.g[cc]) * (db ? c.ft : c.gt),
+                         at(g.data_t[p], Q + ((size_t)(c.i[cc] + da) * g.NT + (c.it + db)) * C + k));
+                }
+                acc.x += s.x * u.x; acc.y += s.y * u.y; acc.z += s.z * u.z; acc.w += s.w * u.w;
+            } else {
+                acc.x += s.x; acc.y += s.y; acc.z += s.z; acc.w += s.w;
+            }
+        }
+    }
+    return acc;
+}
+
 // feat[k*lanes + lane] = h(x)[k], k < C  (Section 3.2)
 __device__ void gather_feat(const GridDev& g, int scene, const Cell& c, float* feat, int lane)
 {
     const int C = g.C;
+    {
+        uintptr_t bits = 0;
+        const int n_planes = g.kind == LP_GRID_VOXEL || g.kind == LP_GRID_HASH ? 1 : 3;
+        for (int p = 0; p < n_planes; ++p) bits |= (uintptr_t)g.data[p];
+        if (g.kind == LP_GRID_HEXPLANE)
+            for (int p = 0; p < 3; ++p) bits |= (uintptr_t)g.data_t[p];
+        if (g.dtype == LP_F32 && (C & 3) == 0 && (bits & 15u) == 0) {
+            for (int k = 0; k < C; k += 4) {
+                const float4 v = gather_channels4(g, scene, c, k);
+                feat[(k + 0) * block_lanes() + lane] = v.x;
+                feat[(k + 1) * block_lanes() + lane] = v.y;
+                feat[(k + 2) * block_lanes() + lane] = v.z;
+                feat[(k + 3) * block_lanes() + lane] = v.w;
+            }
+            return;
+        }
+    }
     if (g.kind == LP_GRID_VOXEL) {
         const size_t V = (size_t)scene * g.N[0] * g.N[1] * g.N[2] * C;  // first element of the scene
         for (int k = 0; k < C; ++k) {
