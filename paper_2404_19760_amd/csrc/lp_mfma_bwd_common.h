@@ -231,6 +231,8 @@ struct CornerAcc {
 // corner; the lanes ch = 0..C-1 of a group address consecutive floats.
 // IN_ORDER: record s belongs to sample s of the step and dFt[r] to sample 16 grp + r (a kernel that
 // passes the feature gradient through LDS reads it back in this order without permuting the step).
+constexpr int kWalkAhead = 2;   // samples whose scatter records are read ahead in the 32-channel and triplane walks
+
 template <int KIND, int C, bool IN_ORDER = false>
 __device__ __forceinline__ void scatter_channels(const GridDev& g, float* const d_grid[3], int scene,
                                                  const float* info, const f32x16& dFt, int ch, int grp,
@@ -447,12 +449,27 @@ __device__ __forceinline__ void scatter_channels(const GridDev& g, float* const 
         auto add = [&](int d, float v) {
             if (live) atomicAdd(reinterpret_cast<float*>(Vd[d] + 4u * (prev + ch)), v);
         };
+        // the records are read kWalkAhead samples ahead of their use (the adds to global memory in between
+        // keep the compiler from moving the LDS reads up by itself)
+        float4 w0q[kWalkAhead], w1q[kWalkAhead];
+        unsigned bq[kWalkAhead];
+#pragma unroll
+        for (int r = 0; r < kWalkAhead; ++r) {
+            const float* rec = info + record_of(r) * 16;
+            w0q[r] = reinterpret_cast<const float4*>(rec)[0];
+            w1q[r] = reinterpret_cast<const float4*>(rec)[1];
+            bq[r] = reinterpret_cast<const unsigned*>(rec)[8];
+        }
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const float* rec = info + record_of(r) * 16;
-            const float4 w0 = reinterpret_cast<const float4*>(rec)[0];
-            const float4 w1 = reinterpret_cast<const float4*>(rec)[1];
-            const unsigned base = reinterpret_cast<const unsigned*>(rec)[8];
+            const float4 w0 = w0q[r % kWalkAhead], w1 = w1q[r % kWalkAhead];
+            const unsigned base = bq[r % kWalkAhead];
+            if (r + kWalkAhead < 16) {
+                const float* rec = info + record_of(r + kWalkAhead) * 16;
+                w0q[r % kWalkAhead] = reinterpret_cast<const float4*>(rec)[0];
+                w1q[r % kWalkAhead] = reinterpret_cast<const float4*>(rec)[1];
+                bq[r % kWalkAhead] = reinterpret_cast<const unsigned*>(rec)[8];
+            }
             const float w[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
             const float v = dFt[r];
             if (r > 0 && base != prev) {
@@ -491,11 +508,23 @@ __device__ __forceinline__ void scatter_channels(const GridDev& g, float* const 
             auto add = [&](int d, float v) {
                 if (live) atomicAdd(reinterpret_cast<float*>(Pd[d] + 4u * (prev + ch)), v);
             };
+            float4 wq[kWalkAhead];
+            unsigned bq[kWalkAhead];
+#pragma unroll
+            for (int r = 0; r < kWalkAhead; ++r) {
+                const float* rec = info + record_of(r) * 16;
+                wq[r] = reinterpret_cast<const float4*>(rec)[pl];
+                bq[r] = reinterpret_cast<const unsigned*>(rec)[12 + pl];
+            }
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const float* rec = info + record_of(r) * 16;
-                const float4 w4 = reinterpret_cast<const float4*>(rec)[pl];
-                const unsigned base = reinterpret_cast<const unsigned*>(rec)[12 + pl];
+                const float4 w4 = wq[r % kWalkAhead];
+                const unsigned base = bq[r % kWalkAhead];
+                if (r + kWalkAhead < 16) {
+                    const float* rec = info + record_of(r + kWalkAhead) * 16;
+                    wq[r % kWalkAhead] = reinterpret_cast<const float4*>(rec)[pl];
+                    bq[r % kWalkAhead] = reinterpret_cast<const unsigned*>(rec)[12 + pl];
+                }
                 const float w[4] = {w4.x, w4.y, w4.z, w4.w};
                 const float v = dFt[r];
                 if (r > 0 && base != prev) {
