@@ -72,15 +72,18 @@ def test_fast_path_queries_are_host_logic():
     import paper_2404_19760_amd as lp
     lib = lp._lib
 
-    def grid(kind, channels, res=(8, 8, 8), contract=0.0, dtype=None):
+    def grid(kind, channels, res=(8, 8, 8), contract=0.0, dtype=None, hash_size=0, n_time=0):
         g = lp._Grid()
         g.kind, g.B, g.C = kind, 1, channels
         g.NX, g.NY, g.NZ = res
         for p in range(3):
             g.data[p] = 4096
+            g.data_t[p] = 4096 if n_time else None
             g.aabb_min[p], g.aabb_max[p] = -1.0, 1.0
         g.contract_a = contract
         g.dtype = lp.LP_F32 if dtype is None else dtype
+        g.hash_size = hash_size
+        g.NT, g.t_min, g.t_max = n_time, 0.0, 1.0
         return g
 
     def mlp(*dims):
@@ -103,6 +106,17 @@ def test_fast_path_queries_are_host_logic():
     assert render(grid(0, 16), mlp(16, 48, 4)) == 0          # hidden width 32 or 64
     assert render(grid(0, 16), mlp(16, 64, 32, 4)) == 0      # equal hidden widths
     assert render(grid(0, 16), mlp(16, 64, 64, 64, 4)) == 0  # at most two hidden layers
+    # hash tables: a size that is a power of two; HexPlanes: 16 or 32 channels
+    assert render(grid(lp.LP_GRID_HASH, 16, hash_size=1 << 14), mlp(16, 64, 64, 4)) == 1
+    assert render(grid(lp.LP_GRID_HASH, 32, hash_size=4096, contract=1.0, dtype=lp.LP_BF16), mlp(32, 32, 4)) == 1
+    assert render(grid(lp.LP_GRID_HASH, 16, hash_size=1), mlp(16, 32, 4)) == 1
+    assert render(grid(lp.LP_GRID_HASH, 16, hash_size=12289), mlp(16, 64, 64, 4)) == 0
+    assert render(grid(lp.LP_GRID_HASH, 8, hash_size=4096), mlp(8, 64, 4)) == 0
+    assert render(grid(lp.LP_GRID_HASH, 16, hash_size=0), mlp(16, 64, 4)) == 0       # invalid: no fast path either
+    assert render(grid(lp.LP_GRID_HEXPLANE, 16, n_time=5), mlp(16, 64, 64, 4)) == 1
+    assert render(grid(lp.LP_GRID_HEXPLANE, 32, n_time=2, contract=1.0, dtype=lp.LP_F16), mlp(32, 32, 4)) == 1
+    assert render(grid(lp.LP_GRID_HEXPLANE, 8, n_time=5), mlp(8, 64, 4)) == 0
+    assert render(grid(lp.LP_GRID_HEXPLANE, 16, n_time=1), mlp(16, 64, 4)) == 0      # invalid: a time axis has two entries at least
 
     def decoder(g, dims_s, dims_v, n_freq, n_feat=3, feat_act=0):
         d = lp._Decoder()
@@ -122,6 +136,11 @@ def test_fast_path_queries_are_host_logic():
     assert decoder(grid(0, 32), (32, 64, 1), (47, 64, 64, 3), 2) == 0         # two chains: both 3-layer
     assert decoder(grid(0, 32), (32, 64, 64, 1), (47, 64, 64, 4), 2, n_feat=4) == 0
     assert decoder(grid(0, 24), (24, 64, 64, 1), (39, 64, 64, 3), 2) == 0
+    # hash tables and HexPlanes: the merged decoder (16 channels + direction inputs), not the two chains
+    assert decoder(grid(lp.LP_GRID_HASH, 16, hash_size=4096), (16, 32, 32, 1), (31, 32, 32, 3), 2) == 1
+    assert decoder(grid(lp.LP_GRID_HEXPLANE, 16, n_time=4), (16, 32, 32, 1), (31, 32, 32, 3), 2) == 1
+    assert decoder(grid(lp.LP_GRID_HASH, 32, hash_size=4096), (32, 64, 64, 1), (47, 64, 64, 3), 2) == 0
+    assert decoder(grid(lp.LP_GRID_HEXPLANE, 32, n_time=4), (32, 64, 64, 1), (47, 64, 64, 3), 2) == 0
 
     def splat(target, n_in, n_freq=-1, prior=None, m=None):
         s = lp._Splat()
@@ -133,6 +152,8 @@ def test_fast_path_queries_are_host_logic():
     assert splat(grid(0, 32), 32) == 1                                                   # naive, 32 channels
     assert splat(grid(1, 16), 16) == 1
     assert splat(grid(0, 8), 8) == 0
+    assert splat(grid(lp.LP_GRID_HASH, 32, hash_size=4096), 32) == 0                     # voxel grids and triplanes only
+    assert splat(grid(lp.LP_GRID_HEXPLANE, 32, n_time=4), 32) == 0
     assert splat(grid(0, 32), 32, 0, grid(0, 32, (5, 6, 7)), mlp(67, 64, 64, 32)) == 1   # the paper's MLP
     assert splat(grid(1, 16), 20, 1, grid(1, 16), mlp(45, 64, 16)) == 1
     assert splat(grid(0, 32), 32, 0, grid(0, 32), mlp(67, 64, 60, 32)) == 0              # hidden width 64 only
