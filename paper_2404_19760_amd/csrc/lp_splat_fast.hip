@@ -89,6 +89,7 @@ hipError_t dispatch(const GridDev& tgt, const RaysDev& rays, const SplatDev& sp,
 
 bool splat_naive_supported(const GridDev& tgt)
 {
+    if (tgt.kind != LP_GRID_VOXEL && tgt.kind != LP_GRID_TRIPLANE) return false;   // (the API refuses other targets already)
     if (tgt.C != 16 && tgt.C != 32) return false;
     const unsigned long long n0 = (unsigned long long)tgt.N[0], n1 = (unsigned long long)tgt.N[1], n2 = (unsigned long long)tgt.N[2];
     if (tgt.kind == LP_GRID_VOXEL) return n0 * n1 * n2 * tgt.C < (1ull << 30);   // 32-bit byte offsets in a scene
