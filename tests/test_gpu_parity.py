@@ -49,6 +49,11 @@ def test_wide_mlp_on_the_generic_kernels(lp, oracle):
     inp = lp_inputs.make_small(VOXEL, channels=24, res=(6, 5, 7), mlp_dims=(24, 96, 96, 4), n_rays=90, samples=21,
                                seed=45, grid_std=0.3)
     print(check_case(lp, oracle, inp, lp.LP_MATH_GENERIC, label="wide generic"), flush=True)
+    # wider still: the activation columns only fit for a partial wavefront of 8 rays, fewer lanes than the
+    # grid has channels (the gradient scatter across lanes then takes several channels per lane)
+    inp = lp_inputs.make_small(VOXEL, channels=24, res=(6, 5, 7), mlp_dims=(24, 160, 160, 4), n_rays=43, samples=11,
+                               seed=46, grid_std=0.3)
+    print(check_case(lp, oracle, inp, lp.LP_MATH_GENERIC, label="wider generic"), flush=True)
     huge = lp_inputs.make_small(VOXEL, channels=8, mlp_dims=(8, 256, 256, 4), n_rays=8)
     grid, mlp, rays, bg = lp.to_device(huge)
     with pytest.raises(lp.LightplaneError) as e:
