@@ -27,6 +27,12 @@
  *     scale a is positive, every axis of a sample position goes through CC on its own (the
  *     text says the axes are converted independently, so ||x|| and x/||x|| are |x| and
  *     sign(x)) before the box mapping; sample spacing Delta stays the world distance.
+ *   - further structures h that Section 3.2 names without defining them: a hash table (one level
+ *     of the spatial hash of Teschner et al. 2003 with Instant-NGP's primes, trilinear over a
+ *     virtual lattice) and a HexPlane (Cao & Johnson 2023: three pairs of a spatial and a
+ *     space-time plane, the reads of a pair multiplied, the three products added; one time per
+ *     ray).  Both are pinned like the other structures (tests/test_oracle_hash.py,
+ *     tests/test_oracle_hexplane.py); no function of this file is parity-unpinned.
  *
  * All arithmetic is double.  Parallel over rays only (OpenMP); grid gradients are
  * added with atomic updates, weight gradients in per-thread buffers summed at the end.
