@@ -407,6 +407,8 @@ class SplatInputs:
     weights: Optional[List[np.ndarray]] = None
     biases: Optional[List[np.ndarray]] = None
     contract_a: float = 0.0
+    hash_size: int = 0                # kind HASH: entries per scene of the target table
+    prior_hash_size: int = 0          # kind HASH: entries per scene of the prior table
 
     @property
     def n_rays(self) -> int:
@@ -423,17 +425,17 @@ class SplatInputs:
 
 def make_splat_small(kind: int, *, n_scenes=1, channels=4, res=(5, 4, 6), n_in=None, hidden=None,
                      n_freq=-1, prior_channels=0, prior_res=(4, 5, 3), n_rays=6, samples=7, seed=0,
-                     bias_std=0.3, **ray_kw) -> SplatInputs:
+                     bias_std=0.3, hash_size=0, prior_hash_size=0, **ray_kw) -> SplatInputs:
     """A small random Splatter problem: the rays of `make_small`, random pixel features,
     optionally a random prior structure and a He-normal MLP with hidden widths `hidden`."""
     base = make_small(kind, n_scenes=n_scenes, channels=channels, res=res, mlp_dims=(channels, 4),
-                      n_rays=n_rays, samples=samples, seed=seed, **ray_kw)
+                      n_rays=n_rays, samples=samples, seed=seed, hash_size=hash_size or None, **ray_kw)
     rng = np.random.default_rng(seed + 50)
     n_in = channels if n_in is None else n_in
     feats = rng.standard_normal((n_rays, n_in)).astype(np.float32)
     prior = None
     if prior_channels:
-        prior = make_grid(kind, n_scenes, prior_res, prior_channels, 0.5, seed + 51)
+        prior = make_grid(kind, n_scenes, prior_res, prior_channels, 0.5, seed + 51, prior_hash_size or None)
     dims = ws = bs = None
     if hidden is not None:
         n_enc = 0 if n_freq < 0 else 3 + 6 * n_freq
@@ -444,7 +446,8 @@ def make_splat_small(kind: int, *, n_scenes=1, channels=4, res=(5, 4, 6), n_in=N
                        near=base.near, far=base.far, scene=base.scene, samples=samples, feats=feats,
                        n_freq=n_freq if hidden is not None else -1, prior=prior,
                        prior_res=tuple(prior_res) if prior_channels else None, prior_channels=prior_channels,
-                       mlp_dims=dims, weights=ws, biases=bs)
+                       mlp_dims=dims, weights=ws, biases=bs, hash_size=int(hash_size),
+                       prior_hash_size=int(prior_hash_size) if prior_channels else 0)
 
 
 @dataclasses.dataclass(frozen=True)

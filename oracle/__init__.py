@@ -301,10 +301,11 @@ class SplatProblem:
         self.scene = None if sp.scene is None else np.ascontiguousarray(sp.scene, dtype=np.int32)
         self.feats = _f64(sp.feats)
 
-        def grid_struct(res, channels, arrays):
+        def grid_struct(res, channels, arrays, hash_size):
             g = _Grid()
             g.kind, g.B, g.C = sp.kind, sp.n_scenes, channels
             g.NX, g.NY, g.NZ = res
+            g.hash_size = int(hash_size) if sp.kind == 2 else 0
             for p, arr in enumerate(arrays or []):
                 g.data[p] = arr.ctypes.data
             for a in range(3):
@@ -312,9 +313,10 @@ class SplatProblem:
                 g.aabb_max[a] = float(sp.aabb_max[a])
             g.contract_a = float(np.float32(sp.contract_a))
             return g
-        self.c_target = grid_struct(sp.res, sp.channels, None)
+        self.c_target = grid_struct(sp.res, sp.channels, None, getattr(sp, "hash_size", 0))
         self.prior = None if sp.prior is None else [_f64(g) for g in sp.prior]
-        self.c_prior = None if sp.prior is None else grid_struct(sp.prior_res, sp.prior_channels, self.prior)
+        self.c_prior = None if sp.prior is None else grid_struct(sp.prior_res, sp.prior_channels, self.prior,
+                                                                 getattr(sp, "prior_hash_size", 0))
         self.W = self.b = None
         self.c_mlp = None
         if sp.mlp_dims is not None:
@@ -346,6 +348,8 @@ class SplatProblem:
         b, (nx, ny, nz) = sp.n_scenes, sp.res
         if sp.kind == 0:
             return [(b, nx, ny, nz, channels)]
+        if sp.kind == 2:
+            return [(b, int(sp.hash_size), channels)]
         return [(b, nx, ny, channels), (b, ny, nz, channels), (b, nz, nx, channels)]
 
 

@@ -1175,7 +1175,8 @@ static int splat_check(const lpo_grid* tgt, const lpo_rays* rays, const lpo_spla
     if (rays->M < 0 || rays->S < 1 || sp->n_in < 1 || sp->n_freq < -1) return 1;
     const int E = sp->n_freq < 0 ? 0 : 3 + 6 * sp->n_freq;
     const int Cp = sp->prior ? sp->prior->C : 0;
-    if (tgt->kind == LPO_HASH || tgt->kind == LPO_HEXPLANE) return 1; /* the Splatter writes voxel grids and triplanes */
+    if (tgt->kind == LPO_HEXPLANE) return 1; /* the Splatter writes voxel grids, triplanes and hash tables */
+    if (tgt->kind == LPO_HASH && tgt->hash_size < 1) return 1;
     if (sp->prior && (sp->prior->kind != tgt->kind || sp->prior->B != tgt->B)) return 1;
     if (!sp->mlp) return (sp->n_in != tgt->C || sp->prior || E) ? 1 : 0;
     if (sp->mlp->n_layers < 1 || sp->mlp->n_layers > LPO_MAX_LAYERS) return 1;
@@ -1202,7 +1203,7 @@ int lpo_splat_fwd(const lpo_grid* tgt, const lpo_rays* rays, const lpo_splat* sp
                   double* const theta_w[3])
 {
     if (splat_check(tgt, rays, sp)) return 1;
-    const int C = tgt->C, S = rays->S, np = tgt->kind == LPO_VOXEL ? 1 : 3;
+    const int C = tgt->C, S = rays->S, np = tgt->kind == LPO_TRIPLANE ? 3 : 1;
     lpo_grid wgrid = *tgt;
     wgrid.C = 1;
     for (int p = 0; p < np; ++p) {
@@ -1264,7 +1265,7 @@ int lpo_splat_bwd(const lpo_grid* tgt, const lpo_rays* rays, const lpo_splat* sp
 {
     if (splat_check(tgt, rays, sp)) return 1;
     if (side != 0 && !(band > 0.0)) return 1;
-    const int C = tgt->C, S = rays->S, np = tgt->kind == LPO_VOXEL ? 1 : 3;
+    const int C = tgt->C, S = rays->S, np = tgt->kind == LPO_TRIPLANE ? 3 : 1;
     /* dL/dtheta = G / theta_w as a grid that is then read by interpolation */
     lpo_grid ggrid = *tgt;
     double* gbuf[3] = {NULL, NULL, NULL};

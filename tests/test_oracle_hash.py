@@ -121,3 +121,66 @@ def test_table_gradient_by_central_differences(oracle):
         step = float(up[0][0, t, c]) - float(dn[0][0, t, c])
         fd = (loss(dataclasses.replace(inp, grid=up)) - loss(dataclasses.replace(inp, grid=dn))) / step
         assert abs(fd - g[0, t, c]) <= 1e-5 * max(1.0, abs(fd)), (t, c, fd, g[0, t, c])
+
+
+# ---- the Splatter into a hash table (Section 3.3: the Splatter writes the hash structure; colliding
+# corners share an entry, whose feature is the weighted mean over everything pushed into it)
+
+def _splat(T, seed, hidden=None, prior_T=0, n_freq=-1):
+    return lp_inputs.make_splat_small(HASH, n_scenes=2, channels=3, res=(5, 4, 6), n_rays=40, samples=11, seed=seed,
+                                      hash_size=T, hidden=hidden, n_freq=n_freq, n_in=3 if hidden is None else 4,
+                                      prior_channels=2 if prior_T else 0, prior_res=(4, 5, 3), prior_hash_size=prior_T)
+
+
+@pytest.mark.parametrize("T", [1, 7, 64, 1000003])
+def test_splat_into_a_table_pools_the_voxel_splat_over_colliding_corners(oracle, T):
+    sp = _splat(T, seed=61 + T % 5)
+    as_voxel = dataclasses.replace(sp, kind=VOXEL, hash_size=0)
+    th, tw = oracle.splat_fwd(sp)
+    tv, wv = oracle.splat_fwd(as_voxel)
+    slots = _slots(oracle, sp.res, T).reshape(-1)
+    for b in range(sp.n_scenes):
+        w = np.zeros(T)
+        s = np.zeros((T, sp.channels))
+        np.add.at(w, slots, wv[0][b].reshape(-1))
+        np.add.at(s, slots, (tv[0][b] * wv[0][b][..., None]).reshape(-1, sp.channels))   # un-normalised sums
+        np.testing.assert_allclose(tw[0][b], w, rtol=1e-12, atol=1e-15)
+        want = np.divide(s, w[:, None], out=np.zeros_like(s), where=w[:, None] > 0)
+        np.testing.assert_allclose(th[0][b], want, rtol=1e-11, atol=1e-14)
+    assert np.isclose(tw[0].sum(), sp.n_rays * sp.samples)         # the weights of a point sum to one
+
+
+def test_splat_into_a_table_gradients_by_central_differences(oracle):
+    """Naive Splatter: pixel features; with MLP and a prior table: features, prior entries, weights."""
+    rng = np.random.default_rng(9)
+    for sp in (_splat(13, seed=67), _splat(29, seed=71, hidden=(6,), prior_T=11, n_freq=0)):
+        th, tw = oracle.splat_fwd(sp)
+        G = [rng.standard_normal(t.shape) for t in th]
+        d_feats, d_prior, dW, db = oracle.splat_bwd(sp, tw, G)
+        loss = lambda s: float(sum((a * g).sum() for a, g in zip(oracle.splat_fwd(s)[0], G)))
+        h = 1e-4
+
+        def fd(field, idx, which=None):
+            up, dn = [np.array(a, copy=True) for a in (getattr(sp, field) if which is None else getattr(sp, field)[which],) * 2]
+            up[idx] += np.float32(h); dn[idx] -= np.float32(h)
+            step = float(up[idx]) - float(dn[idx])
+            def put(a):
+                if which is None:
+                    return dataclasses.replace(sp, **{field: a})
+                lst = list(getattr(sp, field)); lst[which] = a
+                return dataclasses.replace(sp, **{field: lst})
+            return (loss(put(up)) - loss(put(dn))) / step
+
+        for idx in [(0, 0), (17, 2), (39, 1)]:
+            v = fd("feats", idx)
+            assert abs(v - d_feats[idx]) <= 2e-5 * max(1.0, abs(v)), ("feats", idx, v, d_feats[idx])
+        if sp.mlp_dims is not None:
+            flat = np.argsort(-np.abs(d_prior[0]).reshape(-1))[:3]
+            for f in flat:
+                idx = np.unravel_index(int(f), d_prior[0].shape)
+                v = fd("prior", idx, 0)
+                assert abs(v - d_prior[0][idx]) <= 2e-5 * max(1.0, abs(v)), ("prior", idx, v, d_prior[0][idx])
+            for l in range(len(dW)):
+                idx = np.unravel_index(int(np.argmax(np.abs(dW[l]))), dW[l].shape)
+                v = fd("weights", idx, l)
+                assert abs(v - dW[l][idx]) <= 2e-5 * max(1.0, abs(v)), ("W", l, idx, v, dW[l][idx])
