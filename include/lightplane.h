@@ -58,7 +58,8 @@ typedef enum { LP_F32 = 0, LP_BF16 = 1, LP_F16 = 2 } lp_dtype;
  *             trilinearly in a virtual NX x NY x NZ lattice as in a voxel grid, but lattice corner
  *             (ix, iy, iz) is stored in entry ((ix * 1) xor (iy * 2654435761) xor (iz * 805459861))
  *             mod hash_size (products and xor in 32-bit unsigned arithmetic); corners that collide
- *             share the entry and their gradients add.  Renderer only (the Splatter refuses it).
+ *             share the entry and their gradients add.  The Splatter writes such tables too
+ *             (colliding corners pool what is pushed into them; generic kernels).
  *             The matrix-core kernels take tables whose hash_size is a power of two (16 or 32
  *             channels, or 16 channels under the merged two-MLP decoder); every other table runs
  *             on the generic kernels.
@@ -262,7 +263,9 @@ int32_t lp_dec_has_fast_path(const lp_grid* grid, const lp_decoder* dec);
  * structure read at the point (prior == NULL: none) and enc the direction encoding of the
  * two-MLP decoder above (n_freq = -1: none); ReLU hidden layers, linear output;
  * mlp->dims[0] == n_in + prior->C + (3 + 6 n_freq), mlp->dims[last] == target->C.
- * The prior has the target's kind, scene count, box and contraction; its own resolution.
+ * The prior has the target's kind, scene count, box and contraction; its own resolution (and,
+ * for hash tables, its own hash_size).  Targets: voxel grids, triplanes and hash tables (a
+ * HexPlane target is refused with LP_ERR_UNSUPPORTED).
  */
 typedef struct {
     int32_t n_in;         /* channels of the pixel features */
@@ -280,8 +283,8 @@ lp_status lp_splat_fwd(const lp_grid* target, const lp_rays* rays, const lp_spla
                        float* const theta[3], float* const theta_w[3], void* stream);
 
 /* 1 if lp_splat_fwd (and, with an MLP, lp_splat_bwd) runs this target / splat on the
-   wavefront-per-ray kernels, else 0 (generic kernels, same results).  Covered: targets of 16 or
-   32 channels, with or without contract coordinates; with an MLP also a prior of the same
+   wavefront-per-ray kernels, else 0 (generic kernels, same results).  Covered: voxel-grid and
+   triplane targets of 16 or 32 channels, with or without contract coordinates; with an MLP also a prior of the same
    channel count and contraction in fp32, one or two hidden layers of width 64, and at most 48
    pixel-feature plus direction-encoding inputs.  Nothing behind the device pointers is read. */
 int32_t lp_splat_has_fast_path(const lp_grid* target, const lp_splat* splat);

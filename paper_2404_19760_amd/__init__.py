@@ -494,9 +494,11 @@ class Splat:
 
 
 def target_struct(kind: int, n_scenes: int, channels: int, res, aabb_min=(-1.0, -1.0, -1.0),
-                  aabb_max=(1.0, 1.0, 1.0), contract_a: float = 0.0) -> _Grid:
-    """lp_grid describing the structure a Splatter call builds (no data pointers)."""
+                  aabb_max=(1.0, 1.0, 1.0), contract_a: float = 0.0, hash_size: int = 0) -> _Grid:
+    """lp_grid describing the structure a Splatter call builds (no data pointers; hash_size: the
+    entries per scene of a hash-table target)."""
     g = _Grid()
+    g.hash_size = int(hash_size) if int(kind) == LP_GRID_HASH else 0
     g.kind, g.B, g.C = int(kind), int(n_scenes), int(channels)
     g.NX, g.NY, g.NZ = [int(v) for v in res]
     for a in range(3):
@@ -511,6 +513,8 @@ def _target_shapes(t: _Grid, channels: Optional[int]):
     c = () if channels is None else (channels,)
     if t.kind == LP_GRID_VOXEL:
         return [(b, nx, ny, nz) + c]
+    if t.kind == LP_GRID_HASH:
+        return [(b, int(t.hash_size)) + c]
     return [(b, nx, ny) + c, (b, ny, nz) + c, (b, nz, nx) + c]
 
 
@@ -657,7 +661,8 @@ def splat_to_device(sp, device="cuda:0"):
     """Upload host buffers with the fields of `lp_inputs.SplatInputs`.  Returns (target, Rays, Splat)."""
     dev = torch.device(device)
     up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
-    target = target_struct(sp.kind, sp.n_scenes, sp.channels, sp.res, sp.aabb_min, sp.aabb_max, sp.contract_a)
+    target = target_struct(sp.kind, sp.n_scenes, sp.channels, sp.res, sp.aabb_min, sp.aabb_max, sp.contract_a,
+                           getattr(sp, "hash_size", 0))
     rays = Rays(origins=up(sp.origins), dirs=up(sp.dirs), near=up(sp.near), far=up(sp.far),
                 samples=int(sp.samples), scene=None if sp.scene is None else up(sp.scene))
     prior = None

@@ -332,6 +332,7 @@ size_t align256(size_t n) { return (n + 255) / 256 * 256; }
 long long plane_cells(const lp_grid* g, int p)
 {
     if (g->kind == LP_GRID_VOXEL) return (long long)g->B * g->NX * g->NY * g->NZ;
+    if (g->kind == LP_GRID_HASH) return (long long)g->B * g->hash_size;
     const long long n[3] = {(long long)g->NX * g->NY, (long long)g->NY * g->NZ, (long long)g->NZ * g->NX};
     return (long long)g->B * n[p];
 }
@@ -355,8 +356,8 @@ lp_status splat_views(const lp_grid* target, const lp_rays* rays, const lp_splat
     }
     lp_status st = validate(target ? &tgt_checked : nullptr, &stand_in, rays);
     if (st != LP_OK) return st;
-    if (target->kind == LP_GRID_HASH || target->kind == LP_GRID_HEXPLANE)
-        return fail(LP_ERR_UNSUPPORTED, "the Splatter writes voxel grids and triplanes, not hash tables or HexPlanes");
+    if (target->kind == LP_GRID_HEXPLANE)
+        return fail(LP_ERR_UNSUPPORTED, "the Splatter writes voxel grids, triplanes and hash tables, not HexPlanes");
     if (sp->n_in < 1) return fail(LP_ERR_INVALID_ARG, "splat->n_in must be >= 1");
     if (rays->M > 0 && !sp->feats) return fail(LP_ERR_INVALID_ARG, "splat->feats must not be NULL");
     if (sp->n_freq < -1 || sp->n_freq > 4) return fail(LP_ERR_INVALID_ARG, "splat->n_freq must be in [-1, 4]");
@@ -767,7 +768,7 @@ lp_status lp_splat_fwd(const lp_grid* target, const lp_rays* rays, const lp_spla
     lp_status st = splat_views(target, rays, splat, &g, &m, &r, &sd);
     if (st != LP_OK) return st;
     if (!theta || !theta_w) return fail(LP_ERR_INVALID_ARG, "theta and theta_w must not be NULL");
-    const int n_planes = target->kind == LP_GRID_VOXEL ? 1 : 3;
+    const int n_planes = target->kind == LP_GRID_TRIPLANE ? 3 : 1;
     for (int p = 0; p < n_planes; ++p) {
         if (!theta[p] || !theta_w[p]) return fail(LP_ERR_INVALID_ARG, "theta / theta_w has a NULL tensor");
         sd.theta[p] = theta[p];
@@ -863,7 +864,7 @@ lp_status lp_splat_bwd(const lp_grid* target, const lp_rays* rays, const lp_spla
     if (st != LP_OK) return st;
     if (!theta_w || !d_theta) return fail(LP_ERR_INVALID_ARG, "theta_w and d_theta must not be NULL");
     if (rays->M > 0 && !d_feats) return fail(LP_ERR_INVALID_ARG, "d_feats must not be NULL");
-    const int n_planes = target->kind == LP_GRID_VOXEL ? 1 : 3;
+    const int n_planes = target->kind == LP_GRID_TRIPLANE ? 3 : 1;
     lp::BwdIo io;
     std::memset(&io, 0, sizeof(io));
     for (int p = 0; p < n_planes; ++p) {

@@ -514,7 +514,15 @@ __device__ __forceinline__ float feature_act(const MlpDev& m, float z)
 // d_w[corner] += weight   (one channel, same cells and weights as scatter_feat)
 __device__ void scatter_weight(const GridDev& g, float* const d_w[3], int scene, const Cell& c)
 {
-    if (g.kind == LP_GRID_VOXEL) {
+    if (g.kind == LP_GRID_HASH) {
+        float* V = d_w[0] + (size_t)scene * g.hash_size;
+        for (int d = 0; d < 8; ++d) {
+            const int dx = d >> 2, dy = (d >> 1) & 1, dz = d & 1;
+            const float w = (dx ? c.f[0] : c.g[0]) * (dy ? c.f[1] : c.g[1]) *
+                            (dz ? c.f[2] : c.g[2]);
+            atomicAdd(V + hash_slot(c.i[0] + dx, c.i[1] + dy, c.i[2] + dz, g.hash_size), w);
+        }
+    } else if (g.kind == LP_GRID_VOXEL) {
         float* V = d_w[0] + (size_t)scene * g.N[0] * g.N[1] * g.N[2];
         for (int d = 0; d < 8; ++d) {
             const int dx = d >> 2, dy = (d >> 1) & 1, dz = d & 1;
@@ -542,7 +550,18 @@ __device__ void gather_normalised(const GridDev& g, const float* const G[3], con
 {
     const int C = g.C;
     for (int k = 0; k < C; ++k) feat[k * block_lanes() + lane] = 0.0f;
-    if (g.kind == LP_GRID_VOXEL) {
+    if (g.kind == LP_GRID_HASH) {
+        const size_t cells = (size_t)scene * g.hash_size;
+        for (int d = 0; d < 8; ++d) {
+            const int dx = d >> 2, dy = (d >> 1) & 1, dz = d & 1;
+            const float w = (dx ? c.f[0] : c.g[0]) * (dy ? c.f[1] : c.g[1]) *
+                            (dz ? c.f[2] : c.g[2]);
+            const size_t cell = cells + hash_slot(c.i[0] + dx, c.i[1] + dy, c.i[2] + dz, g.hash_size);
+            const float ws = Wt[0][cell];
+            const float s = ws > 0.0f ? w / ws : 0.0f;
+            for (int k = 0; k < C; ++k) feat[k * block_lanes() + lane] += s * G[0][cell * C + k];
+        }
+    } else if (g.kind == LP_GRID_VOXEL) {
         const size_t cells = (size_t)scene * g.N[0] * g.N[1] * g.N[2];
         for (int d = 0; d < 8; ++d) {
             const int dx = d >> 2, dy = (d >> 1) & 1, dz = d & 1;

@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 
 import lp_inputs
-from lp_inputs import TRIPLANE, VOXEL
+from lp_inputs import HASH, TRIPLANE, VOXEL
 
 from parity import WIDTH_CAP_SPLAT_BORDER, check_case_splat
 
@@ -23,6 +23,23 @@ def test_naive_splatter(lp, oracle, kind):
     """No MLP: every point pushes its pixel's feature vector."""
     sp = lp_inputs.make_splat_small(kind, channels=5, res=(9, 8, 10), n_rays=131, samples=37, seed=91, n_scenes=3)
     print(check_case_splat(lp, oracle, sp, label=f"naive splat kind={kind}"), flush=True)
+
+
+@pytest.mark.parametrize("hash_size", [1, 97, 4096])
+@pytest.mark.parametrize("channels,hidden,prior_channels,contract", [(5, None, 0, 0.0), (16, None, 0, 1.3),
+                                                                     (6, (8, 7), 3, 0.0), (32, (64,), 32, 0.0)])
+def test_splatter_into_a_hash_table(lp, oracle, hash_size, channels, hidden, prior_channels, contract):
+    """Hash-table targets (and priors): colliding lattice corners pool what is pushed into them.  Generic
+    kernels, also for the channel counts and MLPs that voxel grids and triplanes run on the fast ones."""
+    kw = dict(far=(2.2, 6.0)) if contract else {}
+    sp = lp_inputs.make_splat_small(HASH, channels=channels, res=(9, 8, 10), n_in=None if hidden is None else 4,
+                                    hidden=hidden, n_freq=-1 if hidden is None else 1, prior_channels=prior_channels,
+                                    prior_res=(7, 6, 5), n_rays=131, samples=37, seed=95 + hash_size % 7, n_scenes=2,
+                                    hash_size=hash_size, prior_hash_size=211 if prior_channels else 0, **kw)
+    sp = dataclasses.replace(sp, contract_a=contract)
+    target, _, splat = lp.splat_to_device(sp)
+    assert not lp.lp_splat_has_fast_path(target, splat)
+    print(check_case_splat(lp, oracle, sp, label=f"splat hash T={hash_size} C={channels} hidden={hidden}"), flush=True)
 
 
 @pytest.mark.parametrize("kind", [VOXEL, TRIPLANE])
