@@ -59,7 +59,7 @@ typedef enum { LP_F32 = 0, LP_BF16 = 1, LP_F16 = 2 } lp_dtype;
  *             (ix, iy, iz) is stored in entry ((ix * 1) xor (iy * 2654435761) xor (iz * 805459861))
  *             mod hash_size (products and xor in 32-bit unsigned arithmetic); corners that collide
  *             share the entry and their gradients add.  The Splatter writes such tables too
- *             (colliding corners pool what is pushed into them; generic kernels).
+ *             (colliding corners pool what is pushed into them).
  *             The matrix-core kernels take tables whose hash_size is a power of two (16 or 32
  *             channels, or 16 channels under the merged two-MLP decoder); every other table runs
  *             on the generic kernels.
@@ -283,8 +283,9 @@ lp_status lp_splat_fwd(const lp_grid* target, const lp_rays* rays, const lp_spla
                        float* const theta[3], float* const theta_w[3], void* stream);
 
 /* 1 if lp_splat_fwd (and, with an MLP, lp_splat_bwd) runs this target / splat on the
-   wavefront-per-ray kernels, else 0 (generic kernels, same results).  Covered: voxel-grid and
-   triplane targets of 16 or 32 channels, with or without contract coordinates; with an MLP also a prior of the same
+   wavefront-per-ray kernels, else 0 (generic kernels, same results).  Covered: targets of 16 or
+   32 channels, with or without contract coordinates (voxel grids, triplanes and, for the naive
+   Splatter, hash tables whose size is a power of two); for voxel grids and triplanes with an MLP also a prior of the same
    channel count and contraction in fp32, one or two hidden layers of width 64, and at most 48
    pixel-feature plus direction-encoding inputs.  Nothing behind the device pointers is read. */
 int32_t lp_splat_has_fast_path(const lp_grid* target, const lp_splat* splat);

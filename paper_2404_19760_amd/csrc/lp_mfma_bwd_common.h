@@ -172,7 +172,8 @@ __device__ __forceinline__ void write_scatter_record(float* rec, const GridDev& 
         reinterpret_cast<float4*>(rec)[1] = w1;
         reinterpret_cast<unsigned*>(rec)[8] = base;
     } else if constexpr (KIND == LP_GRID_HASH) {
-        const float x1 = c.f[0], x0 = 1.0f - x1, y1 = c.f[1], y0 = 1.0f - y1, z1 = c.f[2], z0 = 1.0f - z1;
+        const float x1 = c.f[0], x0 = EXACT ? c.g[0] : 1.0f - x1, y1 = c.f[1], y0 = EXACT ? c.g[1] : 1.0f - y1,
+                    z1 = c.f[2], z0 = EXACT ? c.g[2] : 1.0f - z1;
         unsigned s[8];   // corner 4dx + 2dy + dz
         hash_corner_slots(c, g.hash_size, s);
         if constexpr (C == 16) {   // order 4dz + 2dx + dy: the two halves of a lane group take one dz each

@@ -5,18 +5,24 @@
 
 namespace lp {
 
-// Weight sums: lane `corner` (< 8 voxel, < 12 triplane) of each lane group walks the group's 16
-// points and adds the summed weight of every run into theta_w.
+// Weight sums: lane `corner` (< 8 voxel and hash table, < 12 triplane) of each lane group walks the
+// group's 16 points and adds the summed weight of every run into theta_w (hash table: a run = the
+// points whose corner `corner` falls into the same entry).
 template <int KIND, int C>
 __device__ __forceinline__ void scatter_weights(const GridDev& g, float* const theta_w[3], int scene,
                                                 const float* info, int corner, int grp)
 {
-    constexpr int NC = KIND == LP_GRID_VOXEL ? 8 : 12;
+    constexpr int NC = KIND == LP_GRID_TRIPLANE ? 12 : 8;
     const bool live = corner < NC;
     const int cid = live ? corner : 0;
     float* dst;
     int widx, bidx;
-    if constexpr (KIND == LP_GRID_VOXEL) {
+    if constexpr (KIND == LP_GRID_HASH) {
+        // the record holds the entry offset (entry x channels) of every corner beside its weight
+        dst = theta_w[0] + (size_t)scene * g.hash_size;
+        widx = cid;
+        bidx = 8 + cid;
+    } else if constexpr (KIND == LP_GRID_VOXEL) {
         // record order of the 8 weights: 4dx + 2dy + dz (32 channels), 4dz + 2dx + dy (16 channels)
         const int dx = C == 16 ? (cid >> 1) & 1 : cid >> 2;
         const int dy = C == 16 ? cid & 1 : (cid >> 1) & 1;

@@ -52,7 +52,7 @@ __global__ __launch_bounds__(kWaves * 64) void splat_naive_kernel(GridDev tgt, R
                 write_scatter_record<KIND, C, true>(rec, tgt, c);
                 if (j >= S) {  // a point past the end of the ray pushes nothing
 #pragma unroll
-                    for (int k = 0; k < (KIND == LP_GRID_VOXEL ? 8 : 12); ++k) rec[k] = 0.0f;
+                    for (int k = 0; k < (KIND == LP_GRID_TRIPLANE ? 12 : 8); ++k) rec[k] = 0.0f;
                 }
             }
             wave_lds_fence();
@@ -89,8 +89,12 @@ hipError_t dispatch(const GridDev& tgt, const RaysDev& rays, const SplatDev& sp,
 
 bool splat_naive_supported(const GridDev& tgt)
 {
-    if (tgt.kind != LP_GRID_VOXEL && tgt.kind != LP_GRID_TRIPLANE) return false;   // (the API refuses other targets already)
+    if (tgt.kind != LP_GRID_VOXEL && tgt.kind != LP_GRID_TRIPLANE && tgt.kind != LP_GRID_HASH) return false;
     if (tgt.C != 16 && tgt.C != 32) return false;
+    if (tgt.kind == LP_GRID_HASH) {   // a table whose size is a power of two (`mod size` is a mask in this kernel)
+        const unsigned long long T = tgt.hash_size;
+        return T != 0 && (T & (T - 1)) == 0 && T * tgt.C < (1ull << 30);
+    }
     const unsigned long long n0 = (unsigned long long)tgt.N[0], n1 = (unsigned long long)tgt.N[1], n2 = (unsigned long long)tgt.N[2];
     if (tgt.kind == LP_GRID_VOXEL) return n0 * n1 * n2 * tgt.C < (1ull << 30);   // 32-bit byte offsets in a scene
     return n0 * n1 * tgt.C < (1ull << 30) && n1 * n2 * tgt.C < (1ull << 30) && n2 * n0 * tgt.C < (1ull << 30);
@@ -99,6 +103,7 @@ bool splat_naive_supported(const GridDev& tgt)
 hipError_t launch_splat_naive(const GridDev& tgt, const RaysDev& rays, const SplatDev& sp, int n_cu,
                               hipStream_t stream)
 {
+    if (tgt.kind == LP_GRID_HASH) return dispatch<LP_GRID_HASH>(tgt, rays, sp, n_cu, stream);
     return tgt.kind == LP_GRID_VOXEL ? dispatch<LP_GRID_VOXEL>(tgt, rays, sp, n_cu, stream)
                                      : dispatch<LP_GRID_TRIPLANE>(tgt, rays, sp, n_cu, stream);
 }

@@ -221,6 +221,7 @@ hipError_t by_channels(const GridDev& tgt, const MlpDev& m, const RaysDev& rays,
 
 bool splat_mfma_supported(const GridDev& tgt, const MlpDev& m, const SplatDev& sp)
 {
+    if (tgt.kind != LP_GRID_VOXEL && tgt.kind != LP_GRID_TRIPLANE) return false;   // (hash tables: generic kernels)
     if (m.n_layers != 2 && m.n_layers != 3) return false;
     for (int l = 1; l < m.n_layers; ++l)
         if (m.dims[l] != kHidden) return false;

@@ -152,7 +152,9 @@ def test_fast_path_queries_are_host_logic():
     assert splat(grid(0, 32), 32) == 1                                                   # naive, 32 channels
     assert splat(grid(1, 16), 16) == 1
     assert splat(grid(0, 8), 8) == 0
-    assert splat(grid(lp.LP_GRID_HASH, 32, hash_size=4096), 32) == 0                     # voxel grids and triplanes only
+    assert splat(grid(lp.LP_GRID_HASH, 32, hash_size=4096), 32) == 1                     # naive, a table of a power-of-two size
+    assert splat(grid(lp.LP_GRID_HASH, 32, hash_size=4097), 32) == 0
+    assert splat(grid(lp.LP_GRID_HASH, 32, hash_size=4096), 32, 0, grid(lp.LP_GRID_HASH, 32, hash_size=4096), mlp(67, 64, 64, 32)) == 0   # with an MLP: generic
     assert splat(grid(lp.LP_GRID_HEXPLANE, 32, n_time=4), 32) == 0
     assert splat(grid(0, 32), 32, 0, grid(0, 32, (5, 6, 7)), mlp(67, 64, 64, 32)) == 1   # the paper's MLP
     assert splat(grid(1, 16), 20, 1, grid(1, 16), mlp(45, 64, 16)) == 1

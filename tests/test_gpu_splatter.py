@@ -26,11 +26,12 @@ def test_naive_splatter(lp, oracle, kind):
 
 
 @pytest.mark.parametrize("hash_size", [1, 97, 4096])
-@pytest.mark.parametrize("channels,hidden,prior_channels,contract", [(5, None, 0, 0.0), (16, None, 0, 1.3),
+@pytest.mark.parametrize("channels,hidden,prior_channels,contract", [(5, None, 0, 0.0), (16, None, 0, 1.3), (32, None, 0, 0.0),
                                                                      (6, (8, 7), 3, 0.0), (32, (64,), 32, 0.0)])
 def test_splatter_into_a_hash_table(lp, oracle, hash_size, channels, hidden, prior_channels, contract):
-    """Hash-table targets (and priors): colliding lattice corners pool what is pushed into them.  Generic
-    kernels, also for the channel counts and MLPs that voxel grids and triplanes run on the fast ones."""
+    """Hash-table targets (and priors): colliding lattice corners pool what is pushed into them.  The naive
+    Splatter runs on the wavefront-per-ray kernel for 16 or 32 channels and a table size that is a power
+    of two; everything else, and every MLP, on the generic kernels."""
     kw = dict(far=(2.2, 6.0)) if contract else {}
     sp = lp_inputs.make_splat_small(HASH, channels=channels, res=(9, 8, 10), n_in=None if hidden is None else 4,
                                     hidden=hidden, n_freq=-1 if hidden is None else 1, prior_channels=prior_channels,
@@ -38,7 +39,8 @@ def test_splatter_into_a_hash_table(lp, oracle, hash_size, channels, hidden, pri
                                     hash_size=hash_size, prior_hash_size=211 if prior_channels else 0, **kw)
     sp = dataclasses.replace(sp, contract_a=contract)
     target, _, splat = lp.splat_to_device(sp)
-    assert not lp.lp_splat_has_fast_path(target, splat)
+    fast = hidden is None and channels in (16, 32) and hash_size & (hash_size - 1) == 0
+    assert lp.lp_splat_has_fast_path(target, splat) == fast
     print(check_case_splat(lp, oracle, sp, label=f"splat hash T={hash_size} C={channels} hidden={hidden}"), flush=True)
 
 
