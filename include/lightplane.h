@@ -285,9 +285,10 @@ lp_status lp_splat_fwd(const lp_grid* target, const lp_rays* rays, const lp_spla
 /* 1 if lp_splat_fwd (and, with an MLP, lp_splat_bwd) runs this target / splat on the
    wavefront-per-ray kernels, else 0 (generic kernels, same results).  Covered: targets of 16 or
    32 channels, with or without contract coordinates (voxel grids, triplanes and, for the naive
-   Splatter, hash tables whose size is a power of two); for voxel grids and triplanes with an MLP also a prior of the same
-   channel count and contraction in fp32, one or two hidden layers of width 64, and at most 48
-   pixel-feature plus direction-encoding inputs.  Nothing behind the device pointers is read. */
+   Splatter, hash tables whose size is a power of two); with an MLP, voxel grids and triplanes
+   with a prior of the same channel count and contraction in fp32, one or two hidden layers of
+   width 64, and at most 48 pixel-feature plus direction-encoding inputs.  Nothing behind the
+   device pointers is read. */
 int32_t lp_splat_has_fast_path(const lp_grid* target, const lp_splat* splat);
 
 /* Backward for d_theta[p] = dL/d(out) (device).  The weights depend on the ray geometry only,
