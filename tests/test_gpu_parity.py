@@ -367,3 +367,43 @@ def test_large_full_size_gradient_properties(lp, large_full):
     fd = (loss(+eps) - loss(-eps)) / (2 * eps)
     predicted = float((full[2][-1].double() * direction.double()).sum())
     assert predicted == pytest.approx(fd, rel=2e-3), (predicted, fd)
+
+
+@pytest.mark.parametrize("name", ["voxel", "batched"])
+def test_full_size_forward_and_gradient_properties_of_the_other_large_configs(lp, oracle, name):
+    """The voxel (64^3 x 32, 262 144 rays x 256 samples) and batched (8 triplanes 256^2 x 32, 2 097 152 rays
+    x 192 samples) configurations at full size, as bench.py launches them: the forward of 500 sampled
+    rays (plus the first and last ray of every XCD's range) against the oracle ray by ray, and the
+    gradient of the full launch against the sum over two parts of the rays."""
+    import torch
+    inp = lp_inputs.make_inputs(name)
+    grid, mlp, rays, bg = lp.to_device(inp)
+    rgb, alpha, depth, cache = lp.render_fwd(grid, mlp, rays, bg)
+    torch.cuda.synchronize()
+    m = inp.n_rays
+    per_xcd = (m + 7) // 8
+    edges = [x for k in range(8) for x in (k * per_xcd, min(m, (k + 1) * per_xcd) - 1)]
+    idx = np.unique(np.concatenate([lp_inputs.strided_ray_subset(m, 480, offset=5), np.array(edges + [0, m - 1])]))
+    o_rgb, o_alpha, o_depth = oracle.render_fwd(inp.subset(idx))
+    close(rgb.cpu().numpy()[idx], o_rgb, FWD_RTOL, f"{name} full rgb")
+    close(alpha.cpu().numpy()[idx], o_alpha, FWD_RTOL, f"{name} full alpha")
+    close(depth.cpu().numpy()[idx], o_depth, FWD_RTOL, f"{name} full depth")
+
+    target = torch.from_numpy(inp.target).to("cuda:0")
+    d_rgb = (2.0 * (rgb - target) / (3.0 * m)).contiguous()
+    full = lp.render_bwd(grid, mlp, rays, bg, d_rgb, cache)
+    cut = m // 2 + 41
+
+    def part(lo, hi):
+        r = lp.Rays(origins=rays.origins[lo:hi].contiguous(), dirs=rays.dirs[lo:hi].contiguous(),
+                    near=rays.near[lo:hi].contiguous(), far=rays.far[lo:hi].contiguous(), samples=rays.samples,
+                    scene=None if rays.scene is None else rays.scene[lo:hi].contiguous())
+        return lp.render_bwd(grid, mlp, r, bg, d_rgb[lo:hi].contiguous(), cache[lo:hi].contiguous())
+
+    a, b = part(0, cut), part(cut, m)
+    torch.cuda.synchronize()
+    for grp in range(3):
+        for f, x, y in zip(full[grp], a[grp], b[grp]):
+            f64 = f.double()
+            l2 = float((f64 - (x.double() + y.double())).norm() / f64.norm())
+            assert l2 < 1e-4, (name, grp, l2)
